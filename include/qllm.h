@@ -1,0 +1,217 @@
+/*
+ * libqllm: the reassembled low-bit linear layer of QLLM (arXiv 2310.08041) for AMD MI355X (gfx950).
+ *
+ *   norm -> channel disassembly -> channel assembly -> per-token b-bit quantization
+ *        -> integer GEMM against per-output-channel quantized weights -> dequantising epilogue
+ *
+ * C ABI.  All sizes are int64_t, all status returns int32_t (qllm_status, 0 = ok).  Unless a
+ * parameter says "host", every pointer is a DEVICE pointer owned by the caller; the library
+ * allocates no device memory and keeps no state.  Device work is enqueued on the HIP stream the
+ * caller passes (a hipStream_t cast to void*, NULL = the default stream) and the call returns
+ * without synchronising.  Outputs are overwritten, never accumulated into.  Arguments that can be
+ * checked on the host (sizes, enums, null pointers, alignment) are checked before anything is
+ * launched; nothing is launched when a check fails.  The contents of device arrays (the map, the
+ * codes) are trusted: pass maps made by qllm_build_map_host or checked by qllm_check_map_host.
+ *
+ * Notation: N tokens, C_in channels entering the layer, C_out = K reassembled channels, O output
+ * features, b bits, qmax = 2^b - 1.
+ *
+ * Fixed arithmetic.  The paper leaves precision open; this library computes
+ *   - row statistics (sums for mean / variance / mean square) in fp64, rounded once to fp32;
+ *   - every element-wise step in fp32, one rounding per operation, no fused multiply-add;
+ *   - Eq. (2) as alpha = (max-min)/qmax (fp32), inv = 1/alpha (fp32),
+ *     code = clamp(rne(x*inv) + beta, 0, qmax), beta = -rne(min*inv), where rne() rounds the
+ *     EXACT product to the nearest integer, ties to even; a constant row takes alpha = 1;
+ *   - integer accumulators exactly (int32), the epilogue bracket exactly (int64).
+ */
+#ifndef QLLM_H
+#define QLLM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QLLM_OK = 0,
+    QLLM_ERR_NULL = -1,      /* a required pointer is NULL */
+    QLLM_ERR_SHAPE = -2,     /* a size is negative, zero where it may not be, inconsistent or above a limit */
+    QLLM_ERR_BITS = -3,      /* bit width outside {4, 6, 8}, or an unsupported pair of widths */
+    QLLM_ERR_DTYPE = -4,     /* unknown qllm_dtype / qllm_norm value */
+    QLLM_ERR_MAP = -5,       /* malformed reassembly map or merge list */
+    QLLM_ERR_ALIGN = -6,     /* a buffer or stride misses the required alignment */
+    QLLM_ERR_WORKSPACE = -7, /* workspace missing or smaller than qllm_workspace_bytes says */
+    QLLM_ERR_HIP = -8        /* the HIP runtime reported an error (launch, attribute, device) */
+} qllm_status;
+
+typedef enum { QLLM_F32 = 0, QLLM_BF16 = 1 } qllm_dtype;
+typedef enum { QLLM_NORM_NONE = 0, QLLM_NORM_LAYER = 1, QLLM_NORM_RMS = 2 } qllm_norm;
+
+/* Largest channel counts the fused kernel accepts (one token row is staged on chip in fp32). */
+#define QLLM_MAX_CHANNELS 32768
+/* Rows of packed codes are padded with zero codes to a multiple of this many codes. */
+#define QLLM_K_PAD 256
+/* Output channels are described to the fused kernel in groups of this many. */
+#define QLLM_MAP_GROUP 8
+
+/*
+ * Reassembly map: channel disassembly (Sec. 4.1.1, Eq. 3) followed by channel assembly
+ * (Sec. 4.1.2, Eq. 4), composed into one sparse matrix in CSR form over the OUTPUT channels:
+ *     x^[n, ch] = sum_{e = row_ptr[ch]}^{row_ptr[ch+1]-1} scale[e] * y[n, src[e]]
+ * evaluated left to right in fp32.  A sub-channel of a channel split T ways has one entry with
+ * scale 1/T; a channel merged from a group of g has g entries with scale 1/g; every other channel
+ * has one entry with scale 1.  theta does not appear: it is consumed when the map is built.
+ */
+typedef struct {
+    int64_t C_in;           /* channels of y */
+    int64_t C_out;          /* reassembled channels, 1 .. QLLM_MAX_CHANNELS */
+    int64_t nnz;            /* entries, >= C_out */
+    const int32_t *row_ptr; /* [C_out+1] increasing, row_ptr[0] = 0, row_ptr[C_out] = nnz, no empty row */
+    const int32_t *src;     /* [nnz] 0 <= src < C_in */
+    const float *scale;     /* [nnz] */
+    const int32_t *group_desc; /* optional [ceil(C_out/QLLM_MAP_GROUP)], from qllm_build_map_host or
+                                  qllm_describe_map_host: entry g >= 0 says that the 8 channels of group g
+                                  are single-entry, scale exactly 1, with sources g_desc, g_desc+1, ...;
+                                  -1 says "walk the CSR".  NULL: every group walks the CSR (slower). */
+} qllm_map;
+
+/*
+ * Packed codes (activations and weights use the same format).  A row holds K codes followed by
+ * zero codes up to a multiple of QLLM_K_PAD; qllm_packed_row_bytes(K, bits) is the row stride.
+ *   8 bit: one byte per code.
+ *   4 bit: code 2j in bits 0..3, code 2j+1 in bits 4..7 of byte j.
+ *   6 bit: codes 4j..4j+3 in the 24 bits of bytes 3j..3j+2, little endian, code 4j lowest.
+ * Code buffers must be 16-byte aligned.
+ */
+
+/* Per-output-channel quantized weights, built offline (qllm_quantize_weight_host): Eq. (2) applied
+ * to each output channel of the reassembled weight (Sec. 5, "Quantization settings"). */
+typedef struct {
+    int64_t O;              /* output features */
+    int64_t K;              /* reassembled input channels; must equal map.C_out */
+    int32_t bits;           /* 4, 6 or 8 */
+    const uint8_t *codes;   /* [O, qllm_packed_row_bytes(K, bits)] */
+    const float *scale;     /* [O] alpha_w */
+    const int32_t *zero;    /* [O] beta_w */
+    const int32_t *colsum;  /* [O] sum_k codes[o, k] */
+} qllm_weight;
+
+/* Per-token quantized activations: output of the fused kernel, input of the GEMM. */
+typedef struct {
+    uint8_t *codes;         /* [N, qllm_packed_row_bytes(K, bits)] */
+    float *scale;           /* [N] alpha_x */
+    int32_t *zero;          /* [N] beta_x (not clamped to [0, qmax]) */
+    int32_t *rowsum;        /* [N] sum_k codes[n, k] */
+} qllm_qact;
+
+/* ------------------------------------------------------------------------------------------
+ * Steps a1..a4 in one kernel: norm (the layer that precedes the runtime reassembly, Sec. 4.3),
+ * channel disassembly (Eq. 3), channel assembly (Eq. 4), per-token asymmetric quantization (Eq. 2).
+ *
+ *   x        [N, ldx] row-major, x_dtype (QLLM_BF16 = raw bfloat16 bits); ldx >= C in elements.
+ *   norm     LAYER: y = ((x-mu)*rstd)*gamma + beta, biased variance, beta may be NULL (no shift)
+ *            RMS  : y = (x*rstd)*gamma        NONE: y = x (gamma, beta ignored)
+ *   gamma, beta  [C] fp32.      eps is added to the variance / mean square under the root.
+ *   map      map->C_in must equal C.
+ *   bits     4, 6 or 8.
+ *   out      caller-allocated; fully overwritten, padding codes included.
+ * Errors: NULL / SHAPE / BITS / DTYPE / ALIGN / HIP as described above.  N == 0 is a no-op.
+ * Rows whose values are not finite give unspecified codes.
+ */
+int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
+                                   int32_t norm, const float *gamma, const float *beta, float eps,
+                                   const qllm_map *map, int32_t bits, const qllm_qact *out,
+                                   void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Steps a5..a6: Eq. (1) on the codes, acc[n,o] = sum_k a[n,k]*w[o,k] on the int8 matrix cores,
+ * and the epilogue that undoes Eq. (2) on both operands,
+ *   Y[n,o] = ((float)(acc - beta_x[n]*colsum_w[o] - beta_w[o]*rowsum_x[n] + K*beta_x[n]*beta_w[o])
+ *             * alpha_x[n]) * alpha_w[o]                               (= quant(X^) quant(W^), Sec. 4.1.3)
+ *
+ *   a, a_bits   quantized activations [N, K]; a_bits must equal w->bits, or be 8 with w->bits 4.
+ *   y           [N, ldy] y_dtype (fp32, or bf16 rounded to nearest even); ldy >= O in elements.
+ *   acc_dump    NULL, or [N, O] int32 that receives the raw accumulators.
+ *   workspace   scratch of at least qllm_gemm_workspace_bytes(N, w->K, w->O, a_bits) bytes (may be
+ *               NULL when that is 0); contents undefined afterwards.
+ */
+int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
+                      int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
+                      int64_t workspace_bytes, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * The whole layer a1..a6: qllm_norm_reassemble_quant into workspace, then qllm_int_gemm, on one
+ * stream.  workspace must hold qllm_workspace_bytes(N, map->C_out, w->O, a_bits) bytes, 256-byte
+ * aligned.  Arguments as in the two calls above.
+ */
+int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
+                                int32_t norm, const float *gamma, const float *beta, float eps,
+                                const qllm_map *map, int32_t a_bits, const qllm_weight *w, void *y,
+                                int32_t y_dtype, int64_t ldy, void *workspace, int64_t workspace_bytes,
+                                void *hip_stream);
+
+/* Sizes.  Negative return = qllm_status. */
+int64_t qllm_packed_row_bytes(int64_t K, int32_t bits);
+int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
+int64_t qllm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
+
+const char *qllm_status_string(int32_t status);
+
+/* ------------------------------------------------------------------------------------------
+ * Offline helpers.  HOST pointers throughout; plain CPU code; no GPU needed.
+ */
+
+/* Builds the map from the calibration statistics, in the paper's own terms:
+ *   T_c = max(1, ceil(chan_absmax[c] / theta))                      (Sec. 4.1.1)
+ *   the disassembled axis (sum_c T_c positions) is split into set A (even positions) and set B
+ *   (odd positions); pair k merges A-member src_idx[k] into B-member dst_idx[k] (Sec. 4.1.2,
+ *   Appendix A, and the indexing of the runtime pseudo-code figure); several A-members may share
+ *   a B-member; sub-channels of a split channel may not take part (QLLM_ERR_MAP).
+ * Outputs (caller-sized: row_ptr C + extra + 1, src/scale C + extra entries, group_desc
+ * ceil((C + extra)/8), where extra = sum(T_c - 1) can be obtained by a first call with
+ * row_ptr == NULL): the CSR arrays, C_out = C + extra - r, nnz = C + extra, the T vector.
+ * Entry order inside a merged row: destination first, then sources by ascending position.
+ * num_split_out and group_desc may be NULL.
+ */
+int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx,
+                            const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
+                            float *scale, int32_t *group_desc, int64_t *C_out, int64_t *nnz,
+                            int32_t *num_split_out);
+
+/* Fills group_desc [ceil(C_out/8)] for an existing CSR map (see qllm_map.group_desc). */
+int32_t qllm_describe_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
+                               int64_t C_out, int32_t *group_desc);
+
+/* Verifies a host copy of a map: monotone row_ptr without empty rows, sources in range, finite scales. */
+int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
+                            int64_t C_in, int64_t C_out, int64_t nnz);
+
+/* Reassembles and quantizes the weights of one layer (offline half of Sec. 4.1.1 / 4.1.2):
+ *   W^[ch, :] = sum of W[src[e], :] over the entries e of map row ch (rows duplicated for
+ *   sub-channels as in Eq. (3), summed for merged channels as in Eq. (4)), then Eq. (2) per output
+ *   channel over ch.  W is [C_in, O] row-major fp32 (input channels x output features, the layout
+ *   of Eq. (1)).  Outputs: codes [O, qllm_packed_row_bytes(C_out, bits)] packed, scale/zero/colsum [O].
+ */
+int32_t qllm_quantize_weight_host(const float *W, int64_t C_in, int64_t O, const int32_t *row_ptr,
+                                  const int32_t *src, int64_t C_out, int32_t bits, uint8_t *codes,
+                                  float *scale, int32_t *zero, int32_t *colsum);
+
+/* Packs / unpacks rows of one-byte codes into the storage format above (R rows of K codes). */
+int32_t qllm_pack_codes_host(const uint8_t *codes, int64_t R, int64_t K, int32_t bits, uint8_t *packed);
+int32_t qllm_unpack_codes_host(const uint8_t *packed, int64_t R, int64_t K, int32_t bits, uint8_t *codes);
+
+/* ------------------------------------------------------------------------------------------
+ * Calibration statistic on the device: the norm of each row as in qllm_norm_reassemble_quant,
+ * then absmax[c] = max(absmax[c], max_n |y[n,c]|) (Sec. 4.1.1 "max(|x_M|)"; vector m of Algorithm 1).
+ * absmax [C] fp32 must be initialised by the caller (zeros for a fresh statistic).  y_dump, if not
+ * NULL, receives the first n_dump rows of y as [n_dump, C] fp32.
+ */
+int32_t qllm_norm_channel_absmax(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
+                                 int32_t norm, const float *gamma, const float *beta, float eps,
+                                 float *absmax, float *y_dump, int64_t n_dump, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QLLM_H */

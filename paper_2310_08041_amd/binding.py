@@ -1,0 +1,279 @@
+"""ctypes binding of libqllm.so: the same entry points as include/qllm.h, taking torch tensors.
+
+Argument marshalling only.  torch supplies device memory and the current HIP stream; every step of
+the layer runs inside the library's kernels.  Importing this module fails loudly if the library has
+not been built (run `python __graft_entry__.py` or `paper_2310_08041_amd/_build.py`).
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqllm.so")
+
+F32, BF16 = 0, 1
+NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
+MAX_CHANNELS, K_PAD, MAP_GROUP = 32768, 256, 8
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python __graft_entry__.py)")
+_lib = C.CDLL(LIB_PATH)
+
+
+class QllmError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class _Map(C.Structure):
+    _fields_ = [("C_in", C.c_int64), ("C_out", C.c_int64), ("nnz", C.c_int64), ("row_ptr", C.c_void_p),
+                ("src", C.c_void_p), ("scale", C.c_void_p), ("group_desc", C.c_void_p)]
+
+
+class _Weight(C.Structure):
+    _fields_ = [("O", C.c_int64), ("K", C.c_int64), ("bits", C.c_int32), ("codes", C.c_void_p),
+                ("scale", C.c_void_p), ("zero", C.c_void_p), ("colsum", C.c_void_p)]
+
+
+class _QAct(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scale", C.c_void_p), ("zero", C.c_void_p), ("rowsum", C.c_void_p)]
+
+
+_i64, _i32, _vp, _f = C.c_int64, C.c_int32, C.c_void_p, C.c_float
+_sigs = {
+    "qllm_norm_reassemble_quant": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, C.POINTER(_Map), _i32,
+                                          C.POINTER(_QAct), _vp]),
+    "qllm_int_gemm": (_i32, [C.POINTER(_QAct), _i32, _i64, C.POINTER(_Weight), _vp, _i32, _i64, _vp, _vp, _i64, _vp]),
+    "qllm_reassembled_linear": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, C.POINTER(_Map), _i32,
+                                       C.POINTER(_Weight), _vp, _i32, _i64, _vp, _i64, _vp]),
+    "qllm_packed_row_bytes": (_i64, [_i64, _i32]),
+    "qllm_gemm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
+    "qllm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
+    "qllm_status_string": (C.c_char_p, [_i32]),
+    "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, _vp, C.POINTER(_i64),
+                                   C.POINTER(_i64), _vp]),
+    "qllm_describe_map_host": (_i32, [_vp, _vp, _vp, _i64, _vp]),
+    "qllm_check_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64]),
+    "qllm_quantize_weight_host": (_i32, [_vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp]),
+    "qllm_pack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
+    "qllm_unpack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
+    "qllm_norm_channel_absmax": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, _vp, _vp, _i64, _vp]),
+}
+EXPORTS = tuple(_sigs)
+for _name, (_res, _args) in _sigs.items():
+    _fn = getattr(_lib, _name)           # AttributeError here = the library misses a declared symbol
+    _fn.restype, _fn.argtypes = _res, _args
+
+
+def status_string(status):
+    return _lib.qllm_status_string(int(status)).decode()
+
+
+qllm_status_string = status_string
+
+
+def _chk(rc, where):
+    if rc != 0:
+        raise QllmError(rc, where)
+
+
+def _np(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a):
+    return None if a is None else a.ctypes.data
+
+
+def qllm_packed_row_bytes(K, bits):
+    v = _lib.qllm_packed_row_bytes(int(K), int(bits))
+    _chk(v if v < 0 else 0, "qllm_packed_row_bytes")
+    return v
+
+
+def qllm_workspace_bytes(N, K, O, a_bits):
+    v = _lib.qllm_workspace_bytes(int(N), int(K), int(O), int(a_bits))
+    _chk(v if v < 0 else 0, "qllm_workspace_bytes")
+    return v
+
+
+def qllm_gemm_workspace_bytes(N, K, O, a_bits):
+    v = _lib.qllm_gemm_workspace_bytes(int(N), int(K), int(O), int(a_bits))
+    _chk(v if v < 0 else 0, "qllm_gemm_workspace_bytes")
+    return v
+
+
+# ---------------------------------------------------------------- host helpers (numpy in, numpy out)
+
+def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx):
+    """Returns dict(row_ptr, src, scale, group_desc, num_split, C_in, C_out, nnz) of numpy arrays."""
+    m = _np(chan_absmax, np.float32)
+    si, di = _np(src_idx, np.int32), _np(dst_idx, np.int32)
+    Cc, r = m.size, si.size
+    c_out, nnz = _i64(0), _i64(0)
+    T = np.empty(Cc, np.int32)
+    _chk(_lib.qllm_build_map_host(_hp(m), Cc, theta, _hp(si), _hp(di), r, None, None, None, None, C.byref(c_out),
+                                  C.byref(nnz), _hp(T)), "qllm_build_map_host(size)")
+    row_ptr = np.empty(c_out.value + 1, np.int32)
+    src = np.empty(nnz.value, np.int32)
+    scale = np.empty(nnz.value, np.float32)
+    desc = np.empty((c_out.value + MAP_GROUP - 1) // MAP_GROUP, np.int32)
+    _chk(_lib.qllm_build_map_host(_hp(m), Cc, theta, _hp(si), _hp(di), r, _hp(row_ptr), _hp(src), _hp(scale),
+                                  _hp(desc), C.byref(c_out), C.byref(nnz), _hp(T)), "qllm_build_map_host")
+    return dict(row_ptr=row_ptr, src=src, scale=scale, group_desc=desc, num_split=T, C_in=Cc, C_out=c_out.value,
+                nnz=nnz.value)
+
+
+def qllm_describe_map_host(row_ptr, src, scale):
+    row_ptr, src, scale = _np(row_ptr, np.int32), _np(src, np.int32), _np(scale, np.float32)
+    c_out = row_ptr.size - 1
+    desc = np.empty((c_out + MAP_GROUP - 1) // MAP_GROUP, np.int32)
+    _chk(_lib.qllm_describe_map_host(_hp(row_ptr), _hp(src), _hp(scale), c_out, _hp(desc)), "qllm_describe_map_host")
+    return desc
+
+
+def qllm_check_map_host(row_ptr, src, scale, C_in):
+    row_ptr, src, scale = _np(row_ptr, np.int32), _np(src, np.int32), _np(scale, np.float32)
+    return _lib.qllm_check_map_host(_hp(row_ptr), _hp(src), _hp(scale), int(C_in), row_ptr.size - 1, src.size)
+
+
+def qllm_quantize_weight_host(W, row_ptr, src, bits):
+    """W [C_in, O] float32 -> dict(codes [O, row_bytes] u8 packed, scale, zero, colsum, O, K, bits)."""
+    W = _np(W, np.float32)
+    row_ptr, src = _np(row_ptr, np.int32), _np(src, np.int32)
+    c_in, O = W.shape
+    K = row_ptr.size - 1
+    rb = qllm_packed_row_bytes(K, bits)
+    codes = np.empty((O, rb), np.uint8)
+    scale = np.empty(O, np.float32)
+    zero = np.empty(O, np.int32)
+    colsum = np.empty(O, np.int32)
+    _chk(_lib.qllm_quantize_weight_host(_hp(W), c_in, O, _hp(row_ptr), _hp(src), K, int(bits), _hp(codes),
+                                        _hp(scale), _hp(zero), _hp(colsum)), "qllm_quantize_weight_host")
+    return dict(codes=codes, scale=scale, zero=zero, colsum=colsum, O=O, K=K, bits=int(bits))
+
+
+def qllm_pack_codes_host(codes, bits):
+    codes = _np(codes, np.uint8)
+    R, K = codes.shape
+    out = np.empty((R, qllm_packed_row_bytes(K, bits)), np.uint8)
+    _chk(_lib.qllm_pack_codes_host(_hp(codes), R, K, int(bits), _hp(out)), "qllm_pack_codes_host")
+    return out
+
+
+def qllm_unpack_codes_host(packed, K, bits):
+    packed = _np(packed, np.uint8)
+    R = packed.shape[0]
+    assert packed.shape[1] == qllm_packed_row_bytes(K, bits)
+    out = np.empty((R, K), np.uint8)
+    _chk(_lib.qllm_unpack_codes_host(_hp(packed), R, int(K), int(bits), _hp(out)), "qllm_unpack_codes_host")
+    return out
+
+
+# ---------------------------------------------------------------- device side (torch tensors)
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dp(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _x_dtype(x):
+    torch = _torch()
+    if x.dtype == torch.bfloat16:
+        return BF16
+    if x.dtype == torch.float32:
+        return F32
+    raise TypeError(f"activations must be float32 or bfloat16, got {x.dtype}")
+
+
+class DeviceMap:
+    """Device copy of a reassembly map (keeps the tensors alive next to the C struct)."""
+
+    def __init__(self, row_ptr, src, scale, C_in, group_desc=None, device="cuda"):
+        torch = _torch()
+        self.row_ptr = torch.as_tensor(np.ascontiguousarray(row_ptr, np.int32)).to(device)
+        self.src = torch.as_tensor(np.ascontiguousarray(src, np.int32)).to(device)
+        self.scale = torch.as_tensor(np.ascontiguousarray(scale, np.float32)).to(device)
+        self.group_desc = None if group_desc is None else torch.as_tensor(
+            np.ascontiguousarray(group_desc, np.int32)).to(device)
+        self.C_in, self.C_out, self.nnz = int(C_in), int(self.row_ptr.numel() - 1), int(self.src.numel())
+        self.c = _Map(self.C_in, self.C_out, self.nnz, _dp(self.row_ptr), _dp(self.src), _dp(self.scale),
+                      _dp(self.group_desc))
+
+
+class DeviceWeight:
+    """Device copy of packed per-output-channel quantized weights."""
+
+    def __init__(self, codes, scale, zero, colsum, K, bits, device="cuda"):
+        torch = _torch()
+        self.codes = torch.as_tensor(np.ascontiguousarray(codes, np.uint8)).to(device)
+        self.scale = torch.as_tensor(np.ascontiguousarray(scale, np.float32)).to(device)
+        self.zero = torch.as_tensor(np.ascontiguousarray(zero, np.int32)).to(device)
+        self.colsum = torch.as_tensor(np.ascontiguousarray(colsum, np.int32)).to(device)
+        self.O, self.K, self.bits = int(self.codes.shape[0]), int(K), int(bits)
+        assert self.codes.shape[1] == qllm_packed_row_bytes(K, bits)
+        self.c = _Weight(self.O, self.K, self.bits, _dp(self.codes), _dp(self.scale), _dp(self.zero),
+                         _dp(self.colsum))
+
+
+class DeviceQAct:
+    """Caller-owned buffers for the quantized activations of N tokens."""
+
+    def __init__(self, N, K, bits, device="cuda"):
+        torch = _torch()
+        self.N, self.K, self.bits = int(N), int(K), int(bits)
+        self.codes = torch.empty((N, qllm_packed_row_bytes(K, bits)), dtype=torch.uint8, device=device)
+        self.scale = torch.empty(N, dtype=torch.float32, device=device)
+        self.zero = torch.empty(N, dtype=torch.int32, device=device)
+        self.rowsum = torch.empty(N, dtype=torch.int32, device=device)
+        self.c = _QAct(_dp(self.codes), _dp(self.scale), _dp(self.zero), _dp(self.rowsum))
+
+
+def qllm_norm_reassemble_quant(x, norm, gamma, beta, eps, dmap, bits, out, stream=None):
+    N, Cc = x.shape
+    _chk(_lib.qllm_norm_reassemble_quant(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
+                                         float(eps), C.byref(dmap.c), int(bits), C.byref(out.c), _stream(stream)),
+         "qllm_norm_reassemble_quant")
+    return out
+
+
+def qllm_int_gemm(a, weight, y, acc_dump=None, workspace=None, stream=None):
+    _chk(_lib.qllm_int_gemm(C.byref(a.c), a.bits, a.N, C.byref(weight.c), _dp(y), _x_dtype(y), y.stride(0),
+                            _dp(acc_dump), _dp(workspace), 0 if workspace is None else workspace.numel(),
+                            _stream(stream)), "qllm_int_gemm")
+    return y
+
+
+def qllm_reassembled_linear(x, norm, gamma, beta, eps, dmap, a_bits, weight, y, workspace, stream=None):
+    N, Cc = x.shape
+    _chk(_lib.qllm_reassembled_linear(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
+                                      float(eps), C.byref(dmap.c), int(a_bits), C.byref(weight.c), _dp(y),
+                                      _x_dtype(y), y.stride(0), _dp(workspace), workspace.numel(), _stream(stream)),
+         "qllm_reassembled_linear")
+    return y
+
+
+def qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y_dump=None, stream=None):
+    N, Cc = x.shape
+    n_dump = 0 if y_dump is None else y_dump.shape[0]
+    _chk(_lib.qllm_norm_channel_absmax(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
+                                       float(eps), _dp(absmax), _dp(y_dump), n_dump, _stream(stream)),
+         "qllm_norm_channel_absmax")
+    return absmax
+
+
+def raw():
+    """The ctypes library handle, for tests that pass deliberately bad arguments."""
+    return _lib

@@ -1,0 +1,319 @@
+// Offline, host-side half of libqllm: building the reassembly map from calibration statistics and
+// reassembling + quantizing the weights.  Plain C++, no GPU calls.
+//
+// Paper: channel disassembly Sec. 4.1.1 (Eq. 3), channel assembly Sec. 4.1.2 (Eq. 4) with the
+// bipartite A/B split of Appendix A, uniform quantizer Eq. (2), per-output-channel weights
+// (Sec. 5 "Quantization settings"), weight-side rewrites of Appendix B.
+#include "qllm.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <thread>
+#include <vector>
+
+namespace {
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+inline bool bits_supported(int32_t bits) { return bits == 4 || bits == 6 || bits == 8; }
+
+// What every disassembled position is, and what happens to it in assembly.
+struct Position {
+    int32_t channel;   // source channel of y
+    int32_t splits;    // T of that channel
+    int32_t target;    // B-position this A-position is merged into, or -1
+    int32_t members;   // 1 + number of A-positions merged into this position
+};
+
+template <class F>
+void parallel_blocks(int64_t n_blocks, F &&body)
+{
+    unsigned hw = std::thread::hardware_concurrency();
+    int64_t n_thr = std::max<int64_t>(1, std::min<int64_t>({(int64_t)(hw ? hw : 1), 16, n_blocks}));
+    if (n_thr == 1) {
+        for (int64_t b = 0; b < n_blocks; ++b) body(b);
+        return;
+    }
+    std::vector<std::thread> pool;
+    for (int64_t t = 0; t < n_thr; ++t)
+        pool.emplace_back([&, t] {
+            for (int64_t b = t; b < n_blocks; b += n_thr) body(b);
+        });
+    for (auto &th : pool) th.join();
+}
+
+// Eq. (2) for one vector held with a stride; rne() acts on the exact product (fp32 x fp32 fits fp64).
+struct QuantParams {
+    float alpha, inv;
+    int64_t beta;
+};
+
+inline int64_t rne_product(float a, float b) { return (int64_t)std::nearbyint((double)a * (double)b); }
+
+inline QuantParams quant_params(float mn, float mx, int qmax)
+{
+    QuantParams p;
+    const float range = mx - mn;
+    p.alpha = range > 0.0f ? range / (float)qmax : 1.0f;
+    p.inv = 1.0f / p.alpha;
+    p.beta = -rne_product(mn, p.inv);
+    const int64_t lim = std::numeric_limits<int32_t>::max();
+    p.beta = std::min(lim, std::max(-lim, p.beta));
+    return p;
+}
+
+inline uint32_t quant_code(float v, const QuantParams &p, int qmax)
+{
+    int64_t q = rne_product(v, p.inv) + p.beta;
+    return (uint32_t)std::min<int64_t>(qmax, std::max<int64_t>(0, q));
+}
+
+inline void put_code(uint8_t *row, int64_t k, int32_t bits, uint32_t code)
+{
+    if (bits == 8) {
+        row[k] = (uint8_t)code;
+    } else if (bits == 4) {
+        row[k >> 1] |= (uint8_t)(code << ((k & 1) * 4));
+    } else { // 6 bit: four codes per three bytes
+        const int64_t bit = k * 6;
+        const int sh = (int)(bit & 7);
+        row[bit >> 3] |= (uint8_t)(code << sh);
+        if (sh > 2) row[(bit >> 3) + 1] |= (uint8_t)(code >> (8 - sh));
+    }
+}
+
+inline uint32_t get_code(const uint8_t *row, int64_t k, int32_t bits)
+{
+    if (bits == 8) return row[k];
+    if (bits == 4) return (row[k >> 1] >> ((k & 1) * 4)) & 15u;
+    const int64_t bit = k * 6;
+    const int sh = (int)(bit & 7);
+    uint32_t w = row[bit >> 3];
+    if (sh > 2) w |= (uint32_t)row[(bit >> 3) + 1] << 8;
+    return (w >> sh) & 63u;
+}
+
+} // namespace
+
+extern "C" {
+
+int64_t qllm_packed_row_bytes(int64_t K, int32_t bits)
+{
+    if (!bits_supported(bits)) return QLLM_ERR_BITS;
+    if (K <= 0) return QLLM_ERR_SHAPE;
+    return round_up(K, QLLM_K_PAD) * bits / 8;
+}
+
+const char *qllm_status_string(int32_t status)
+{
+    switch (status) {
+    case QLLM_OK: return "ok";
+    case QLLM_ERR_NULL: return "a required pointer is NULL";
+    case QLLM_ERR_SHAPE: return "bad size or leading dimension";
+    case QLLM_ERR_BITS: return "unsupported bit width";
+    case QLLM_ERR_DTYPE: return "unknown dtype or norm kind";
+    case QLLM_ERR_MAP: return "malformed reassembly map";
+    case QLLM_ERR_ALIGN: return "buffer or stride not aligned";
+    case QLLM_ERR_WORKSPACE: return "workspace missing or too small";
+    case QLLM_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int32_t qllm_describe_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
+                               int64_t C_out, int32_t *group_desc)
+{
+    if (!row_ptr || !src || !scale || !group_desc) return QLLM_ERR_NULL;
+    if (C_out <= 0) return QLLM_ERR_SHAPE;
+    const int64_t n_groups = (C_out + QLLM_MAP_GROUP - 1) / QLLM_MAP_GROUP;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        const int64_t c0 = g * QLLM_MAP_GROUP;
+        int32_t desc = -1;
+        if (c0 + QLLM_MAP_GROUP <= C_out) {
+            const int32_t e0 = row_ptr[c0];
+            bool plain = row_ptr[c0 + QLLM_MAP_GROUP] - e0 == QLLM_MAP_GROUP;
+            for (int j = 0; plain && j < QLLM_MAP_GROUP; ++j)
+                plain = row_ptr[c0 + j] == e0 + j && src[e0 + j] == src[e0] + j && scale[e0 + j] == 1.0f;
+            if (plain) desc = src[e0];
+        }
+        group_desc[g] = desc;
+    }
+    return QLLM_OK;
+}
+
+int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
+                            int64_t C_in, int64_t C_out, int64_t nnz)
+{
+    if (!row_ptr || !src || !scale) return QLLM_ERR_NULL;
+    if (C_in <= 0 || C_out <= 0 || nnz < C_out) return QLLM_ERR_SHAPE;
+    if (row_ptr[0] != 0 || row_ptr[C_out] != nnz) return QLLM_ERR_MAP;
+    for (int64_t c = 0; c < C_out; ++c)
+        if (row_ptr[c + 1] <= row_ptr[c]) return QLLM_ERR_MAP;
+    for (int64_t e = 0; e < nnz; ++e)
+        if (src[e] < 0 || src[e] >= C_in || !std::isfinite(scale[e])) return QLLM_ERR_MAP;
+    return QLLM_OK;
+}
+
+int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx,
+                            const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
+                            float *scale, int32_t *group_desc, int64_t *C_out, int64_t *nnz,
+                            int32_t *num_split_out)
+{
+    if (!chan_absmax || !C_out || !nnz) return QLLM_ERR_NULL;
+    if (r > 0 && (!src_idx || !dst_idx)) return QLLM_ERR_NULL;
+    if (C <= 0 || r < 0 || !(theta > 0.0f)) return QLLM_ERR_SHAPE;
+
+    // T = ceil(max|x| / theta), never below 1 (Sec. 4.1.1)
+    std::vector<int32_t> T((size_t)C);
+    int64_t total = 0;
+    for (int64_t c = 0; c < C; ++c) {
+        const double q = std::ceil((double)chan_absmax[c] / (double)theta);
+        if (!(q <= 1e9)) return QLLM_ERR_SHAPE; // also catches NaN
+        T[c] = q >= 1.0 ? (int32_t)q : 1;
+        total += T[c];
+    }
+    if (total > std::numeric_limits<int32_t>::max() || r > total) return QLLM_ERR_SHAPE;
+    *C_out = total - r;
+    *nnz = total;
+    if (num_split_out) std::copy(T.begin(), T.end(), num_split_out);
+    if (!row_ptr) return QLLM_OK; // sizing call
+    if (!src || !scale) return QLLM_ERR_NULL;
+    if (*C_out <= 0) return QLLM_ERR_SHAPE;
+
+    std::vector<Position> pos((size_t)total);
+    {
+        int64_t p = 0;
+        for (int64_t c = 0; c < C; ++c)
+            for (int32_t t = 0; t < T[c]; ++t) pos[p++] = Position{(int32_t)c, T[c], -1, 1};
+    }
+    const int64_t n_a = (total + 1) / 2, n_b = total / 2;
+    for (int64_t k = 0; k < r; ++k) {
+        if (src_idx[k] < 0 || src_idx[k] >= n_a || dst_idx[k] < 0 || dst_idx[k] >= n_b) return QLLM_ERR_MAP;
+        Position &a = pos[2 * (size_t)src_idx[k]];
+        Position &b = pos[2 * (size_t)dst_idx[k] + 1];
+        if (a.target != -1) return QLLM_ERR_MAP;                 // an A-member can be merged once
+        if (a.splits != 1 || b.splits != 1) return QLLM_ERR_MAP; // sub-channels stay out of assembly
+        a.target = 2 * dst_idx[k] + 1;
+        b.members += 1;
+    }
+    // sources of every destination, ascending: bucket the A-positions by target
+    std::vector<int32_t> first((size_t)total + 1, 0);
+    for (int64_t p = 0; p < total; p += 2)
+        if (pos[p].target != -1) first[(size_t)pos[p].target + 1] += 1;
+    for (int64_t p = 0; p < total; ++p) first[p + 1] += first[p];
+    std::vector<int32_t> merged_src((size_t)std::max<int64_t>(r, 1));
+    {
+        std::vector<int32_t> fill(first.begin(), first.end() - 1);
+        for (int64_t p = 0; p < total; p += 2)
+            if (pos[p].target != -1) merged_src[fill[pos[p].target]++] = (int32_t)p;
+    }
+    int64_t ch = 0, e = 0;
+    for (int64_t p = 0; p < total; ++p) {
+        const Position &q = pos[p];
+        if (q.target != -1) continue; // merged away
+        row_ptr[ch++] = (int32_t)e;
+        if (q.members == 1) {
+            src[e] = q.channel;
+            scale[e++] = (float)(1.0 / (double)q.splits);
+        } else {
+            const float s = (float)(1.0 / (double)q.members);
+            src[e] = q.channel;
+            scale[e++] = s;
+            for (int32_t i = first[p]; i < first[p + 1]; ++i) {
+                src[e] = pos[merged_src[i]].channel;
+                scale[e++] = s;
+            }
+        }
+    }
+    row_ptr[ch] = (int32_t)e;
+    if (ch != *C_out || e != *nnz) return QLLM_ERR_MAP;
+    if (group_desc) return qllm_describe_map_host(row_ptr, src, scale, *C_out, group_desc);
+    return QLLM_OK;
+}
+
+int32_t qllm_pack_codes_host(const uint8_t *codes, int64_t R, int64_t K, int32_t bits, uint8_t *packed)
+{
+    if (!codes || !packed) return QLLM_ERR_NULL;
+    if (!bits_supported(bits)) return QLLM_ERR_BITS;
+    if (R < 0 || K <= 0) return QLLM_ERR_SHAPE;
+    const int64_t rb = qllm_packed_row_bytes(K, bits);
+    for (int64_t i = 0; i < R; ++i) {
+        uint8_t *row = packed + i * rb;
+        std::memset(row, 0, (size_t)rb);
+        for (int64_t k = 0; k < K; ++k) {
+            if (codes[i * K + k] >> bits) return QLLM_ERR_BITS;
+            put_code(row, k, bits, codes[i * K + k]);
+        }
+    }
+    return QLLM_OK;
+}
+
+int32_t qllm_unpack_codes_host(const uint8_t *packed, int64_t R, int64_t K, int32_t bits, uint8_t *codes)
+{
+    if (!codes || !packed) return QLLM_ERR_NULL;
+    if (!bits_supported(bits)) return QLLM_ERR_BITS;
+    if (R < 0 || K <= 0) return QLLM_ERR_SHAPE;
+    const int64_t rb = qllm_packed_row_bytes(K, bits);
+    for (int64_t i = 0; i < R; ++i)
+        for (int64_t k = 0; k < K; ++k) codes[i * K + k] = (uint8_t)get_code(packed + i * rb, k, bits);
+    return QLLM_OK;
+}
+
+int32_t qllm_quantize_weight_host(const float *W, int64_t C_in, int64_t O, const int32_t *row_ptr,
+                                  const int32_t *src, int64_t C_out, int32_t bits, uint8_t *codes,
+                                  float *scale, int32_t *zero, int32_t *colsum)
+{
+    if (!W || !row_ptr || !src || !codes || !scale || !zero || !colsum) return QLLM_ERR_NULL;
+    if (!bits_supported(bits)) return QLLM_ERR_BITS;
+    if (C_in <= 0 || O <= 0 || C_out <= 0) return QLLM_ERR_SHAPE;
+    if (row_ptr[0] != 0) return QLLM_ERR_MAP;
+    for (int64_t c = 0; c < C_out; ++c) {
+        if (row_ptr[c + 1] <= row_ptr[c]) return QLLM_ERR_MAP;
+        for (int32_t e = row_ptr[c]; e < row_ptr[c + 1]; ++e)
+            if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
+    }
+    const int qmax = (1 << bits) - 1;
+    const int64_t rb = qllm_packed_row_bytes(C_out, bits);
+    constexpr int64_t BLK = 64; // output channels handled together: one cache line of every weight row
+    const int64_t n_blocks = (O + BLK - 1) / BLK;
+
+    parallel_blocks(n_blocks, [&](int64_t b) {
+        const int64_t o0 = b * BLK, nb = std::min(BLK, O - o0);
+        std::vector<float> what((size_t)(C_out * nb)); // reassembled weight, this block of columns
+        std::vector<float> mn((size_t)nb, std::numeric_limits<float>::infinity());
+        std::vector<float> mx((size_t)nb, -std::numeric_limits<float>::infinity());
+        for (int64_t c = 0; c < C_out; ++c) {
+            float *dst = &what[(size_t)(c * nb)];
+            int32_t e = row_ptr[c];
+            const float *w0 = W + (int64_t)src[e] * O + o0;
+            for (int64_t j = 0; j < nb; ++j) dst[j] = w0[j];
+            for (++e; e < row_ptr[c + 1]; ++e) { // merged channel: rows add up (Eq. 4)
+                const float *w1 = W + (int64_t)src[e] * O + o0;
+                for (int64_t j = 0; j < nb; ++j) dst[j] = dst[j] + w1[j];
+            }
+            for (int64_t j = 0; j < nb; ++j) {
+                mn[j] = std::min(mn[j], dst[j]);
+                mx[j] = std::max(mx[j], dst[j]);
+            }
+        }
+        for (int64_t j = 0; j < nb; ++j) {
+            const QuantParams p = quant_params(mn[j], mx[j], qmax);
+            uint8_t *row = codes + (o0 + j) * rb;
+            std::memset(row, 0, (size_t)rb);
+            int64_t sum = 0;
+            for (int64_t c = 0; c < C_out; ++c) {
+                const uint32_t q = quant_code(what[(size_t)(c * nb + j)], p, qmax);
+                put_code(row, c, bits, q);
+                sum += q;
+            }
+            scale[o0 + j] = p.alpha;
+            zero[o0 + j] = (int32_t)p.beta;
+            colsum[o0 + j] = (int32_t)sum;
+        }
+    });
+    return QLLM_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,347 @@
+// Integer GEMM on the gfx950 int8 matrix cores with a dequantising epilogue.
+//
+//   acc[n, o] = sum_k a[n, k] * w[o, k]          (Eq. 1 on the codes of Eq. 2; exact int32)
+//   Y[n, o]   = ((float)(acc - bx[n]*cs[o] - bw[o]*rs[n] + K*bx[n]*bw[o]) * ax[n]) * aw[o]
+//
+// Both operands arrive as packed 4/6/8-bit codes, K contiguous.  A workgroup of 256 lanes (4 waves,
+// 2 x 2) owns a 128 x 128 tile of Y.  Per K-tile of 256 codes every lane fetches 64-code units of
+// the packed rows from HBM into registers (16-byte loads), expands them to one byte per code and
+// stores them into LDS (16-byte chunks, XOR-swizzled by row so that the matrix-core operand reads
+// are bank-conflict free); the loads of the next K-tile are in flight while the current one is
+// multiplied.  Each wave multiplies 64 x 64 with v_mfma_i32_16x16x64_i8 (16 accumulator tiles).
+//
+// 8-bit codes do not fit a signed byte: they are stored as code-128 and the accumulator is corrected
+// with the row / column sums the epilogue already has.
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+
+#include "qllm.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int BM = 128, BN = 128, KT = 256; // block tile; KT codes per LDS stage
+constexpr int THREADS = 256;
+constexpr int UNIT = 64;                    // codes per fetch unit = K of one MFMA
+constexpr int ROW_LDS = KT;                 // bytes per tile row in LDS (one byte per code)
+
+struct GemmArgs {
+    const uint8_t *a_codes, *w_codes;
+    int64_t a_row_bytes, w_row_bytes;
+    const float *ax, *aw;
+    const int32_t *bx, *bw, *rs, *cs;
+    int32_t N, O, K, Kpad;
+    void *y;
+    int64_t ldy;
+    int32_t *acc_dump;
+};
+
+template <int BITS>
+struct Unit {
+    uint4 r[BITS / 2]; // 64 codes: 32 / 48 / 64 bytes
+};
+
+template <int BITS>
+__device__ __forceinline__ void load_unit(Unit<BITS> &u, const uint8_t *row, int kt, int ku)
+{
+    const uint4 *p = reinterpret_cast<const uint4 *>(row + ((int64_t)kt * KT + ku * UNIT) * BITS / 8);
+#pragma unroll
+    for (int i = 0; i < BITS / 2; ++i) u.r[i] = p[i];
+}
+
+// 8 nibbles of w -> 8 bytes in channel order
+__device__ __forceinline__ void expand4(uint32_t w, uint32_t &d0, uint32_t &d1)
+{
+    const uint32_t lo = w & 0x0f0f0f0fu;        // codes 0 2 4 6
+    const uint32_t hi = (w >> 4) & 0x0f0f0f0fu; // codes 1 3 5 7
+    d0 = __builtin_amdgcn_perm(hi, lo, 0x05010400u); // lo.b0 hi.b0 lo.b1 hi.b1
+    d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u); // lo.b2 hi.b2 lo.b3 hi.b3
+}
+
+// four 6-bit codes in the low 24 bits of t -> four bytes
+__device__ __forceinline__ uint32_t expand6(uint32_t t)
+{
+    return (t & 0x3fu) | ((t << 2) & 0x3f00u) | ((t << 4) & 0x3f0000u) | ((t << 6) & 0x3f000000u);
+}
+
+// Expands one unit to 64 bytes and stores it as four 16-byte chunks of LDS row `row`.
+template <int BITS>
+__device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, int row, int ku)
+{
+    uint32_t d[16];
+    if constexpr (BITS == 4) {
+        const uint32_t w[8] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y, u.r[1].z, u.r[1].w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) expand4(w[i], d[2 * i], d[2 * i + 1]);
+    } else if constexpr (BITS == 6) {
+        const uint32_t w[12] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y,
+                                u.r[1].z, u.r[1].w, u.r[2].x, u.r[2].y, u.r[2].z, u.r[2].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { // 3 dwords = 4 groups of 24 bits
+            const uint32_t w0 = w[3 * i], w1 = w[3 * i + 1], w2 = w[3 * i + 2];
+            d[4 * i + 0] = expand6(w0);
+            d[4 * i + 1] = expand6((w0 >> 24) | (w1 << 8));
+            d[4 * i + 2] = expand6((w1 >> 16) | (w2 << 16));
+            d[4 * i + 3] = expand6(w2 >> 8);
+        }
+    } else {
+        const uint32_t w[16] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y, u.r[1].z, u.r[1].w,
+                                u.r[2].x, u.r[2].y, u.r[2].z, u.r[2].w, u.r[3].x, u.r[3].y, u.r[3].z, u.r[3].w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) d[i] = w[i] ^ 0x80808080u; // code - 128 as a signed byte
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int chunk = (ku * 4 + c) ^ (row & 7);
+        *reinterpret_cast<uint4 *>(tile + row * ROW_LDS + chunk * 16) =
+            make_uint4(d[4 * c], d[4 * c + 1], d[4 * c + 2], d[4 * c + 3]);
+    }
+}
+
+__device__ __forceinline__ v4i load_frag(const uint8_t *tile, int row, int chunk)
+{
+    return *reinterpret_cast<const v4i *>(tile + row * ROW_LDS + ((chunk ^ (row & 7)) * 16));
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <int ABITS, int WBITS, typename YT>
+__global__ __launch_bounds__(THREADS) void int_gemm_kernel(const GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds_a[BM * ROW_LDS];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_w[BN * ROW_LDS];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1; // wave position in the 2 x 2 arrangement
+    const int n0 = blockIdx.y * BM, o0 = blockIdx.x * BN;
+
+    // fetch assignment: units tid and tid + 256 of each operand tile (unit = row * 4 + ku)
+    const int f_row = tid >> 2, f_ku = tid & 3;
+    const uint8_t *a_row[2], *w_row[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int rn = min(n0 + f_row + 64 * h, g.N - 1); // rows past the edge re-read the last row
+        const int ro = min(o0 + f_row + 64 * h, g.O - 1);
+        a_row[h] = g.a_codes + (int64_t)rn * g.a_row_bytes;
+        w_row[h] = g.w_codes + (int64_t)ro * g.w_row_bytes;
+    }
+
+    v4i acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+    Unit<ABITS> ua[2];
+    Unit<WBITS> uw[2];
+    const int n_kt = g.Kpad / KT;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        load_unit<ABITS>(ua[h], a_row[h], 0, f_ku);
+        load_unit<WBITS>(uw[h], w_row[h], 0, f_ku);
+    }
+
+    for (int kt = 0; kt < n_kt; ++kt) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            store_unit<ABITS>(ua[h], lds_a, f_row + 64 * h, f_ku);
+            store_unit<WBITS>(uw[h], lds_w, f_row + 64 * h, f_ku);
+        }
+        __syncthreads();
+        if (kt + 1 < n_kt) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                load_unit<ABITS>(ua[h], a_row[h], kt + 1, f_ku);
+                load_unit<WBITS>(uw[h], w_row[h], kt + 1, f_ku);
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < KT / UNIT; ++ks) {
+            const int chunk = ks * 4 + (lane >> 4);
+            v4i fa[4], fw[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fa[i] = load_frag(lds_a, wm * 64 + i * 16 + (lane & 15), chunk);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fw[j] = load_frag(lds_w, wn * 64 + j * 16 + (lane & 15), chunk);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    // operand order (w, a): the lane then holds 4 consecutive OUTPUT features of one
+                    // token, so the stores below write 16 bytes per lane
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue.  acc[i][j][r]: token n0 + wm*64 + i*16 + (lane & 15),
+    //                               feature o0 + wn*64 + j*16 + 4*(lane >> 4) + r
+    constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = n0 + wm * 64 + i * 16 + (lane & 15);
+        if (n >= g.N) continue;
+        const int64_t bx = g.bx[n], rs = g.rs[n];
+        const float ax = g.ax[n];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int ob = o0 + wn * 64 + j * 16 + 4 * (lane >> 4);
+            float out[4];
+            int32_t raw[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int o = min(ob + r, g.O - 1);
+                const int64_t cs = g.cs[o], bw = g.bw[o];
+                int64_t a = (int64_t)acc[i][j][r];
+                a += 128 * SW * rs + 128 * SA * cs - (int64_t)(16384 * SA * SW) * g.Kpad;
+                raw[r] = (int32_t)a;
+                const int64_t bracket = a - bx * cs - bw * rs + (int64_t)g.K * bx * bw;
+                float v = (float)bracket;
+                v = v * ax;
+                v = v * g.aw[o];
+                out[r] = v;
+            }
+            if (ob + 3 < g.O) {
+                if constexpr (sizeof(YT) == 4) {
+                    float *yp = reinterpret_cast<float *>(g.y) + (int64_t)n * g.ldy + ob;
+                    if ((reinterpret_cast<uintptr_t>(yp) & 15u) == 0) {
+                        *reinterpret_cast<float4 *>(yp) = make_float4(out[0], out[1], out[2], out[3]);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) yp[r] = out[r];
+                    }
+                } else {
+                    uint16_t *yp = reinterpret_cast<uint16_t *>(g.y) + (int64_t)n * g.ldy + ob;
+                    const uint32_t p0 = f32_to_bf16_rne(out[0]) | ((uint32_t)f32_to_bf16_rne(out[1]) << 16);
+                    const uint32_t p1 = f32_to_bf16_rne(out[2]) | ((uint32_t)f32_to_bf16_rne(out[3]) << 16);
+                    if ((reinterpret_cast<uintptr_t>(yp) & 7u) == 0) {
+                        *reinterpret_cast<uint2 *>(yp) = make_uint2(p0, p1);
+                    } else {
+                        yp[0] = (uint16_t)p0; yp[1] = (uint16_t)(p0 >> 16);
+                        yp[2] = (uint16_t)p1; yp[3] = (uint16_t)(p1 >> 16);
+                    }
+                }
+                if (g.acc_dump) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (ob + r < g.O) {
+                        if constexpr (sizeof(YT) == 4)
+                            reinterpret_cast<float *>(g.y)[(int64_t)n * g.ldy + ob + r] = out[r];
+                        else
+                            reinterpret_cast<uint16_t *>(g.y)[(int64_t)n * g.ldy + ob + r] = f32_to_bf16_rne(out[r]);
+                        if (g.acc_dump) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
+                    }
+            }
+        }
+    }
+}
+
+template <int ABITS, int WBITS>
+int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
+    if (y_dtype == QLLM_F32)
+        hipLaunchKernelGGL((int_gemm_kernel<ABITS, WBITS, float>), grid, dim3(THREADS), 0, stream, g);
+    else
+        hipLaunchKernelGGL((int_gemm_kernel<ABITS, WBITS, uint16_t>), grid, dim3(THREADS), 0, stream, g);
+    return hipGetLastError() == hipSuccess ? QLLM_OK : QLLM_ERR_HIP;
+}
+
+} // namespace
+
+extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    if (a_bits != 4 && a_bits != 6 && a_bits != 8) return QLLM_ERR_BITS;
+    if (N < 0 || K <= 0 || O <= 0) return QLLM_ERR_SHAPE;
+    return 0;
+}
+
+extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
+                                 int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
+                                 int64_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    if (!a || !w || !y) return QLLM_ERR_NULL;
+    if (!a->codes || !a->scale || !a->zero || !a->rowsum) return QLLM_ERR_NULL;
+    if (!w->codes || !w->scale || !w->zero || !w->colsum) return QLLM_ERR_NULL;
+    if (y_dtype != QLLM_F32 && y_dtype != QLLM_BF16) return QLLM_ERR_DTYPE;
+    const int32_t wb = w->bits;
+    const bool pair_ok = (a_bits == wb && (wb == 4 || wb == 6 || wb == 8)) || (a_bits == 8 && wb == 4);
+    if (!pair_ok) return QLLM_ERR_BITS;
+    if (N < 0 || N > INT32_MAX || w->O <= 0 || w->O > INT32_MAX || w->K <= 0 || w->K > (1 << 24) || ldy < w->O)
+        return QLLM_ERR_SHAPE;
+    // the largest possible sum of products must stay inside int32
+    const int64_t qa = (1 << a_bits) - 1, qw = (1 << wb) - 1;
+    if (qa * qw * w->K > INT32_MAX) return QLLM_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(a->codes) & 15u) || (reinterpret_cast<uintptr_t>(w->codes) & 15u))
+        return QLLM_ERR_ALIGN;
+    if (workspace_bytes < qllm_gemm_workspace_bytes(N, w->K, w->O, a_bits)) return QLLM_ERR_WORKSPACE;
+    if (N == 0) return QLLM_OK;
+
+    GemmArgs g{};
+    g.a_codes = a->codes;
+    g.w_codes = w->codes;
+    g.a_row_bytes = qllm_packed_row_bytes(w->K, a_bits);
+    g.w_row_bytes = qllm_packed_row_bytes(w->K, wb);
+    g.ax = a->scale; g.bx = a->zero; g.rs = a->rowsum;
+    g.aw = w->scale; g.bw = w->zero; g.cs = w->colsum;
+    g.N = (int32_t)N; g.O = (int32_t)w->O; g.K = (int32_t)w->K;
+    g.Kpad = (int32_t)((w->K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD);
+    g.y = y; g.ldy = ldy; g.acc_dump = acc_dump;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (a_bits == 4) return launch<4, 4>(g, y_dtype, stream);
+    if (a_bits == 6) return launch<6, 6>(g, y_dtype, stream);
+    if (wb == 8) return launch<8, 8>(g, y_dtype, stream);
+    return launch<8, 4>(g, y_dtype, stream);
+}
+
+extern "C" int64_t qllm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    const int64_t gw = qllm_gemm_workspace_bytes(N, K, O, a_bits);
+    if (gw < 0) return gw;
+    const int64_t rb = qllm_packed_row_bytes(K, a_bits);
+    auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
+    return up(N * rb) + 3 * up(N * 4) + up(gw);
+}
+
+extern "C" int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
+                                           int32_t norm, const float *gamma, const float *beta, float eps,
+                                           const qllm_map *map, int32_t a_bits, const qllm_weight *w, void *y,
+                                           int32_t y_dtype, int64_t ldy, void *workspace, int64_t workspace_bytes,
+                                           void *hip_stream)
+{
+    if (!map || !w) return QLLM_ERR_NULL;
+    if (w->K != map->C_out) return QLLM_ERR_SHAPE;
+    if (N < 0) return QLLM_ERR_SHAPE;
+    const int64_t need = qllm_workspace_bytes(N, map->C_out, w->O, a_bits);
+    if (need < 0) return (int32_t)need;
+    if (N > 0 && (!workspace || workspace_bytes < need)) return QLLM_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QLLM_ERR_ALIGN;
+    auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
+    uint8_t *p = static_cast<uint8_t *>(workspace);
+    qllm_qact q;
+    q.codes = p;
+    p += up(N * qllm_packed_row_bytes(map->C_out, a_bits));
+    q.scale = reinterpret_cast<float *>(p);
+    p += up(N * 4);
+    q.zero = reinterpret_cast<int32_t *>(p);
+    p += up(N * 4);
+    q.rowsum = reinterpret_cast<int32_t *>(p);
+    p += up(N * 4);
+    int32_t rc = qllm_norm_reassemble_quant(x, x_dtype, N, C, ldx, norm, gamma, beta, eps, map, a_bits, &q, hip_stream);
+    if (rc != QLLM_OK) return rc;
+    return qllm_int_gemm(&q, a_bits, N, w, y, y_dtype, ldy, nullptr, p, workspace_bytes - (p - static_cast<uint8_t *>(workspace)),
+                         hip_stream);
+}

@@ -1,0 +1,202 @@
+"""The C-ABI library without a GPU: exported symbols, argument validation (every check happens
+before a launch), and the host helpers against the oracle."""
+import ctypes as C
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+from helpers import make_case
+from paper_2310_08041_amd import binding as b
+from paper_2310_08041_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "qllm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qllm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 14
+    lib = C.CDLL(b.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(b.EXPORTS) == names      # the binding wraps exactly what the header declares
+
+
+def test_status_strings():
+    assert b.status_string(0) == "ok"
+    seen = {b.status_string(s) for s in range(-8, 1)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert b.status_string(-99) == "unknown status"
+
+
+def test_packed_row_bytes_and_workspace():
+    assert b.qllm_packed_row_bytes(28672, 4) == 14336
+    assert b.qllm_packed_row_bytes(1, 4) == 128 and b.qllm_packed_row_bytes(257, 6) == 384
+    assert b.qllm_packed_row_bytes(256, 8) == 256
+    with pytest.raises(b.QllmError):
+        b.qllm_packed_row_bytes(16, 5)
+    with pytest.raises(b.QllmError):
+        b.qllm_packed_row_bytes(0, 4)
+    ws = b.qllm_workspace_bytes(2048, 28672, 8192, 4)
+    assert ws >= 2048 * 14336 + 3 * 2048 * 4 and ws % 256 == 0
+
+
+def _structs():
+    m = b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, None)
+    q = b._QAct(0x1000, 0x1000, 0x1000, 0x1000)
+    w = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000)
+    return m, q, w
+
+
+def test_fused_entry_point_rejects_bad_arguments_before_launching():
+    lib = b.raw()
+    m, q, w = _structs()
+    f = lib.qllm_norm_reassemble_quant
+    X, G = 0x1000, 0x2000     # never dereferenced: every call below fails validation first
+    ok = dict(x=X, dt=b.BF16, N=4, C=64, ldx=64, norm=b.NORM_RMS, gamma=G, beta=None, eps=1e-5, bits=4)
+
+    def call(mp=m, qa=q, **kw):
+        a = dict(ok, **kw)
+        return f(a["x"], a["dt"], a["N"], a["C"], a["ldx"], a["norm"], a["gamma"], a["beta"], a["eps"],
+                 C.byref(mp) if mp is not None else None, a["bits"], C.byref(qa) if qa is not None else None, None)
+
+    assert call(x=None) == -1
+    assert call(gamma=None) == -1
+    assert call(mp=None) == -1 and call(qa=None) == -1
+    assert call(dt=7) == -4 and call(norm=3) == -4
+    assert call(C=0) == -2 and call(C=b.MAX_CHANNELS + 1, ldx=b.MAX_CHANNELS + 1) == -2
+    assert call(ldx=63) == -2 and call(N=-1) == -2
+    assert call(bits=5) == -3 and call(bits=2) == -3
+    assert call(gamma=G + 4) == -6
+    bad_map = b._Map(65, 64, 64, 0x1000, 0x1000, 0x1000, None)      # C_in differs from C
+    assert call(mp=bad_map) == -2
+    assert call(mp=b._Map(64, 64, 64, None, 0x1000, 0x1000, None)) == -1
+    assert call(mp=b._Map(64, 64, 10, 0x1000, 0x1000, 0x1000, None)) == -2
+    assert call(qa=b._QAct(0x1008, 0x1000, 0x1000, 0x1000)) == -6
+    assert call(qa=b._QAct(0x1000, None, 0x1000, 0x1000)) == -1
+    assert call(N=0) == 0                                             # empty batch: nothing to do
+
+
+def test_gemm_entry_point_rejects_bad_arguments_before_launching():
+    lib = b.raw()
+    m, q, w = _structs()
+    f = lib.qllm_int_gemm
+    Y = 0x3000
+
+    def call(qa=q, a_bits=4, N=4, wt=w, y=Y, ydt=b.F32, ldy=32, ws_bytes=0):
+        return f(C.byref(qa) if qa is not None else None, a_bits, N, C.byref(wt) if wt is not None else None, y,
+                 ydt, ldy, None, None, ws_bytes, None)
+
+    assert call(qa=None) == -1 and call(wt=None) == -1 and call(y=None) == -1
+    assert call(ydt=5) == -4
+    assert call(a_bits=6) == -3                                      # 6-bit activations, 4-bit weights
+    assert call(a_bits=4, wt=b._Weight(32, 64, 8, 0x1000, 0x1000, 0x1000, 0x1000)) == -3
+    assert call(a_bits=3) == -3
+    assert call(ldy=31) == -2 and call(N=-2) == -2
+    assert call(wt=b._Weight(0, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000)) == -2
+    assert call(a_bits=8, wt=b._Weight(32, 40000, 8, 0x1000, 0x1000, 0x1000, 0x1000)) == -2   # could overflow int32
+    assert call(wt=b._Weight(32, 64, 4, 0x1004, 0x1000, 0x1000, 0x1000)) == -6
+    assert call(qa=b._QAct(0x1000, 0x1000, None, 0x1000)) == -1
+    assert call(N=0) == 0
+
+
+def test_linear_entry_point_rejects_bad_arguments_before_launching():
+    lib = b.raw()
+    m, q, w = _structs()
+    f = lib.qllm_reassembled_linear
+
+    def call(mp=m, wt=w, N=4, ws=0x4000, ws_bytes=1 << 20):
+        return f(0x1000, b.BF16, N, 64, 64, b.NORM_RMS, 0x2000, None, 1e-5, C.byref(mp), 4, C.byref(wt), 0x3000,
+                 b.F32, 32, ws, ws_bytes, None)
+
+    assert call(wt=b._Weight(32, 65, 4, 0x1000, 0x1000, 0x1000, 0x1000)) == -2     # K != C_out
+    assert call(ws=None) == -7 and call(ws_bytes=16) == -7
+    assert call(ws=0x4010) == -6
+    assert call(N=0) == 0
+
+
+# ---------------------------------------------------------------- host helpers against the oracle
+
+def test_build_map_matches_hand_worked_example():
+    G = json.load(open(os.path.join(ROOT, "tests", "golden", "hand_worked_example.json")))
+    r = b.qllm_build_map_host(np.abs(np.array(G["y"], np.float32)), G["theta"], G["src_idx"], G["dst_idx"])
+    assert r["num_split"].tolist() == G["T"]
+    assert r["row_ptr"].tolist() == G["map_row_ptr"] and r["src"].tolist() == G["map_src"]
+    assert r["scale"].tolist() == [float(np.float32(n / d)) for n, d in G["map_scale_num_den"]]
+    assert (r["C_out"], r["nnz"]) == (6, 7)
+
+
+@pytest.mark.parametrize("name,N,C,O", [("tiny", 64, 512, 96), ("llama7b_qkv", 48, 1000, 40),
+                                        ("llama70b_down", 32, 2050, 24), ("llama70b_q_decode", 16, 777, 33)])
+def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
+    w = wl.WORKLOADS[name]
+    c = make_case(oracle, w, N=N, C=C, O=O)
+    r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
+    assert np.array_equal(r["num_split"], c.T)
+    assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
+    assert np.array_equal(r["scale"], c.scale)
+    assert b.qllm_check_map_host(r["row_ptr"], r["src"], r["scale"], C) == 0
+    # group descriptors: a non-negative entry promises 8 plain channels with consecutive sources
+    desc = r["group_desc"]
+    assert np.array_equal(desc, b.qllm_describe_map_host(c.row_ptr, c.src, c.scale))
+    assert (desc >= 0).sum() > 0.25 * desc.size
+    for g in np.nonzero(desc >= 0)[0]:
+        rows = slice(8 * g, 8 * g + 8)
+        e = c.row_ptr[rows]
+        assert np.all(np.diff(c.row_ptr[8 * g:8 * g + 9]) == 1)
+        assert np.array_equal(c.src[e], desc[g] + np.arange(8)) and np.all(c.scale[e] == 1.0)
+    for g in np.nonzero(desc < 0)[0]:
+        lo, hi = 8 * g, min(8 * g + 8, c.K)
+        e = c.row_ptr[lo:hi]
+        plain = (hi - lo == 8 and np.all(np.diff(c.row_ptr[lo:hi + 1]) == 1) and np.all(c.scale[e] == 1.0)
+                 and np.array_equal(c.src[e], c.src[e[0]] + np.arange(8)))
+        assert not plain
+    # weights: reassembled, quantized per output channel and packed by the library == the oracle's
+    q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, w.w_bits)
+    assert np.array_equal(q["scale"], c.aw) and np.array_equal(q["zero"], c.bw) and np.array_equal(q["colsum"], c.cs)
+    assert q["codes"].shape[1] == b.qllm_packed_row_bytes(c.K, w.w_bits)
+    assert np.array_equal(q["codes"], oracle.pack_codes(c.wcodes, w.w_bits, q["codes"].shape[1]))
+    assert np.array_equal(b.qllm_unpack_codes_host(q["codes"], c.K, w.w_bits), c.wcodes)
+
+
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_pack_helpers_match_the_oracle(oracle, bits):
+    rng = np.random.default_rng(bits)
+    codes = rng.integers(0, 2 ** bits, (7, 300), dtype=np.uint8)
+    p = b.qllm_pack_codes_host(codes, bits)
+    assert np.array_equal(p, oracle.pack_codes(codes, bits, p.shape[1]))
+    assert np.array_equal(b.qllm_unpack_codes_host(p, 300, bits), codes)
+    with pytest.raises(b.QllmError):
+        b.qllm_pack_codes_host(np.full((1, 4), 2 ** bits if bits < 8 else 0, np.uint8) if bits < 8
+                               else np.zeros((1, 0), np.uint8), bits)
+
+
+def test_build_map_rejects_malformed_merge_lists():
+    m = np.array([1, 1, 9, 1, 1, 1], np.float32)        # theta 4: channel 2 splits in 3 -> positions 2,3,4
+    with pytest.raises(b.QllmError) as e:
+        b.qllm_build_map_host(m, 4.0, [1], [0])         # A member 1 = position 2: a sub-channel
+    assert e.value.status == -5
+    with pytest.raises(b.QllmError):
+        b.qllm_build_map_host(m, 4.0, [0], [1])         # B member 1 = position 3: a sub-channel
+    with pytest.raises(b.QllmError):
+        b.qllm_build_map_host(m, 4.0, [0, 0], [0, 3])   # A member merged twice
+    with pytest.raises(b.QllmError):
+        b.qllm_build_map_host(m, 4.0, [4], [0])         # outside set A (8 positions -> 4 members)
+    with pytest.raises(b.QllmError):
+        b.qllm_build_map_host(m, 0.0, [], [])           # theta must be positive
+    ok = b.qllm_build_map_host(m, 4.0, [0, 3], [0, 0])  # positions 0 and 6 both join position 1: group of 3
+    assert ok["C_out"] == 6 and np.diff(ok["row_ptr"]).max() == 3
+    bad_rp = ok["row_ptr"].copy()
+    bad_rp[2] = bad_rp[1]
+    assert b.qllm_check_map_host(bad_rp, ok["src"], ok["scale"], 6) == -5
+    bad_src = ok["src"].copy()
+    bad_src[0] = 6
+    assert b.qllm_check_map_host(ok["row_ptr"], bad_src, ok["scale"], 6) == -5

@@ -1,0 +1,274 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element.
+
+Bars: packed activation codes, zero-points, row sums and int32 accumulators bit-exact; per-token
+scales bit-exact (same fp32 operations on both sides); dequantised outputs within 1e-3 relative
+(fp32) / 2e-2 (bf16) -- in practice they are bit-exact too, which is reported but not required.
+"""
+import numpy as np
+import pytest
+
+from helpers import expected_qact, make_case, rel_err, to_torch_x
+from paper_2310_08041_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-3, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def b():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2310_08041_amd import binding
+    return binding
+
+
+def device_map(b, c, use_desc=True):
+    r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
+    assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
+    assert np.array_equal(r["scale"], c.scale)
+    return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C, r["group_desc"] if use_desc else None)
+
+
+def device_weight(b, c, bits=None):
+    bits = c.w.w_bits if bits is None else bits
+    return b.DeviceWeight(b.qllm_pack_codes_host(c.wcodes, bits), c.aw, c.bw, c.cs, c.K, bits)
+
+
+def run_fused(b, c, bits, use_desc=True, x=None):
+    import torch
+    dm = device_map(b, c, use_desc)
+    xt = to_torch_x(c.x) if x is None else x
+    g = None if c.gamma is None else torch.from_numpy(c.gamma).cuda()
+    be = None if c.beta is None else torch.from_numpy(c.beta).cuda()
+    out = b.DeviceQAct(xt.shape[0], c.K, bits)
+    out.codes.fill_(0xAB)           # poison: the kernel must overwrite everything, padding included
+    out.rowsum.fill_(-7)
+    b.qllm_norm_reassemble_quant(xt, c.norm, g, be, c.eps, dm, bits, out)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_fused(oracle, c, out, bits):
+    exp = expected_qact(oracle, c, bits)
+    rb = out.codes.shape[1]
+    exp_packed = oracle.pack_codes(exp["codes"], bits, rb)
+    got = out.codes.cpu().numpy()
+    bad_rows = np.nonzero((got != exp_packed).any(1))[0]
+    assert bad_rows.size == 0, f"{bad_rows.size} rows differ, first {bad_rows[:5]}"
+    assert np.array_equal(out.scale.cpu().numpy().view(np.uint32), exp["alpha"].view(np.uint32))
+    assert np.array_equal(out.zero.cpu().numpy(), exp["beta"])
+    assert np.array_equal(out.rowsum.cpu().numpy(), exp["rowsum"])
+    return exp
+
+
+# ---------------------------------------------------------------- fused kernel (steps a1..a4)
+
+@pytest.mark.parametrize("use_desc", [True, False])
+def test_fused_tiny_config(oracle, b, use_desc):
+    c = make_case(oracle, wl.WORKLOADS["tiny"], real_weights=False)
+    assert c.K == 512 and c.T.max() > 1
+    check_fused(oracle, c, run_fused(b, c, 4, use_desc), 4)
+
+
+SHAPES = [("tiny", 1, 8, 4), ("tiny", 3, 7, 4), ("tiny", 5, 100, 6), ("llama7b_qkv", 7, 1000, 4),
+          ("llama7b_qkv", 2, 2049, 8), ("llama13b_upgate", 3, 8200, 4), ("llama70b_down", 2, 16392, 6),
+          ("llama70b_down", 3, 32768, 4), ("llama70b_q_decode", 16, 515, 6), ("llama70b_q_decode", 4, 4104, 8)]
+
+
+@pytest.mark.parametrize("name,N,C,bits", SHAPES)
+@pytest.mark.parametrize("merge", [True, False])
+def test_fused_odd_shapes(oracle, b, name, N, C, bits, merge):
+    w = wl.WORKLOADS[name]
+    rule = ("expand", 0.03) if C >= 64 else ("fixed", 1.0)
+    if C * 1.03 > 32768 and not merge:
+        pytest.skip("disassembly alone would exceed the channel limit")
+    c = make_case(oracle, w, N=N, C=C, O=8, merge=merge, real_weights=False, theta_rule=rule)
+    if not merge and C >= 64:
+        assert c.K > C                                  # disassembly only: more channels than it started with
+    check_fused(oracle, c, run_fused(b, c, bits), bits)
+
+
+@pytest.mark.parametrize("norm", ["none", "layer", "rms"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fused_norm_kinds_and_strided_input(oracle, b, norm, dtype):
+    import dataclasses
+    import torch
+    w = dataclasses.replace(wl.WORKLOADS["llama7b_qkv"], norm=norm, in_dtype=dtype)
+    c = make_case(oracle, w, N=9, C=1096, O=8, real_weights=False, theta_rule=("expand", 0.02))
+    if norm == "layer":
+        c.beta = np.random.default_rng(0).standard_normal(c.C).astype(np.float32)
+        c2 = c
+        y = oracle.norm(c2.x, c2.norm, c2.gamma, c2.beta, c2.eps)       # recalibrate with the shift
+        from oracle import calibrate
+        cal = calibrate.calibrate(y, ("expand", 0.02))
+        c.absmax, c.theta, c.T, c.src_idx, c.dst_idx = (cal[k] for k in ("absmax", "theta", "T", "src_idx", "dst_idx"))
+        c.row_ptr, c.src, c.scale = oracle.build_map(c.T, c.src_idx, c.dst_idx)
+        c.K = c.row_ptr.size - 1
+    check_fused(oracle, c, run_fused(b, c, 4), 4)
+    # the same rows inside a wider, misaligned buffer: ldx > C and a base that is not 16-byte aligned
+    xt = to_torch_x(c.x)
+    wide = torch.zeros((c.N, c.C + 13), dtype=xt.dtype, device="cuda")
+    wide[:, 3:3 + c.C] = xt
+    check_fused(oracle, c, run_fused(b, c, 4, x=wide[:, 3:3 + c.C]), 4)
+
+
+def test_fused_degenerate_rows(oracle, b):
+    """Constant rows, a zero row, one-sided rows, a row whose quotients leave the fast rounding path."""
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["tiny"], norm="none")
+    c = make_case(oracle, w, N=8, C=264, O=8, real_weights=False, theta_rule=("fixed", 1e9))
+    assert np.all(c.T == 1)
+    x = c.x
+    x[0] = 3.25
+    x[1] = 0.0
+    x[2] = np.abs(x[2]) + 100.0
+    x[3] = -np.abs(x[3]) - 100.0
+    x[4] = 1.0e6 + np.arange(264, dtype=np.float32) * 0.125     # |x / alpha| ~ 2^25: slow path
+    x[5] = np.where(np.arange(264) % 2 == 0, -6.0, 9.0)          # alpha = 1 exactly (4 bit)
+    x[6] = np.arange(264, dtype=np.float32) * 0.5 - 60.0         # exact .5 ties after scaling
+    for bits in (4, 6, 8):
+        exp = check_fused(oracle, c, run_fused(b, c, bits), bits)
+        assert exp["alpha"][0] == 1.0 and exp["beta"][0] == -3 and exp["beta"][2] < 0 and exp["beta"][3] > 2 ** bits
+        assert abs(int(exp["beta"][4])) > 2 ** 22
+
+
+FULL = ["llama7b_qkv", "llama13b_upgate", "llama70b_down", "llama70b_q_decode"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_fused_full_configs(oracle, b, name):
+    w = wl.WORKLOADS[name]
+    c = make_case(oracle, w, real_weights=False)
+    assert c.K == w.C                                   # merged back to the original channel count
+    check_fused(oracle, c, run_fused(b, c, w.a_bits), w.a_bits)
+
+
+def test_channel_absmax_kernel(oracle, b):
+    import torch
+    for name, N, C in [("tiny", 64, 512), ("llama7b_qkv", 100, 4096), ("llama70b_down", 40, 28672), ("tiny", 5, 77)]:
+        w = wl.WORKLOADS[name]
+        c = make_case(oracle, w, N=N, C=C, O=8, real_weights=False, theta_rule=("fixed", 1e9))
+        y = oracle.norm(c.x, c.norm, c.gamma, c.beta, c.eps)
+        absmax = torch.zeros(C, dtype=torch.float32, device="cuda")
+        dump = torch.empty((min(N, 7), C), dtype=torch.float32, device="cuda")
+        g = torch.from_numpy(c.gamma).cuda()
+        be = None if c.beta is None else torch.from_numpy(c.beta).cuda()
+        b.qllm_norm_channel_absmax(to_torch_x(c.x), c.norm, g, be, c.eps, absmax, dump)
+        torch.cuda.synchronize()
+        assert np.array_equal(absmax.cpu().numpy(), oracle.channel_absmax(y))
+        assert np.array_equal(dump.cpu().numpy(), y[:dump.shape[0]])
+
+
+# ---------------------------------------------------------------- GEMM + epilogue (steps a5, a6)
+
+def random_gemm_case(rng, N, K, O, a_bits, w_bits):
+    a = rng.integers(0, 2 ** a_bits, (N, K), dtype=np.uint8)
+    w = rng.integers(0, 2 ** w_bits, (O, K), dtype=np.uint8)
+    ax = rng.uniform(0.01, 0.5, N).astype(np.float32)
+    aw = rng.uniform(0.001, 0.05, O).astype(np.float32)
+    bx = rng.integers(-5, 2 ** a_bits + 5, N).astype(np.int32)
+    bw = rng.integers(0, 2 ** w_bits, O).astype(np.int32)
+    return a, w, ax, aw, bx, bw
+
+
+def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True):
+    import torch
+    N, K = a.shape
+    O = w.shape[0]
+    qa = b.DeviceQAct(N, K, a_bits)
+    qa.codes.copy_(torch.from_numpy(b.qllm_pack_codes_host(a, a_bits)))
+    qa.scale.copy_(torch.from_numpy(ax))
+    qa.zero.copy_(torch.from_numpy(bx))
+    qa.rowsum.copy_(torch.from_numpy(a.astype(np.int64).sum(1).astype(np.int32)))
+    dw = b.DeviceWeight(b.qllm_pack_codes_host(w, w_bits), aw, bw, w.astype(np.int64).sum(1).astype(np.int32), K, w_bits)
+    y = torch.full((N, O), float("nan"), dtype=torch.float32 if y_dtype == "f32" else torch.bfloat16, device="cuda")
+    acc = torch.full((N, O), -1, dtype=torch.int32, device="cuda") if dump else None
+    b.qllm_int_gemm(qa, dw, y, acc)
+    torch.cuda.synchronize()
+    return y, acc
+
+
+def check_y(oracle, y, ref_f32, y_dtype):
+    if y_dtype == "bf16":
+        got = oracle.widen_bf16(y.view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+        ref = oracle.widen_bf16(oracle.round_to_bf16(ref_f32))
+    else:
+        got, ref = y.cpu().numpy(), ref_f32
+    err = rel_err(got, ref_f32).max()
+    assert err <= TOL[y_dtype], err
+    return bool(np.array_equal(got, ref))
+
+
+@pytest.mark.parametrize("a_bits,w_bits", [(4, 4), (6, 6), (8, 8), (8, 4)])
+@pytest.mark.parametrize("N,K,O", [(1, 1, 1), (16, 64, 16), (130, 300, 200), (257, 1030, 129), (64, 2048, 384)])
+@pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
+def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
+    rng = np.random.default_rng(N * 1000 + K + O + a_bits)
+    a, w, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, a_bits, w_bits)
+    y, acc = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype)
+    ref_acc = oracle.int_gemm(a, w)
+    assert np.array_equal(acc.cpu().numpy(), ref_acc)
+    ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
+    check_y(oracle, y, ref_y, y_dtype)
+
+
+def test_gemm_extreme_codes(oracle, b):
+    """All codes at their maximum: the largest accumulators the shapes allow."""
+    for bits, K in [(4, 28672), (6, 8192), (8, 28672)]:
+        a = np.full((17, K), 2 ** bits - 1, np.uint8)
+        w = np.full((33, K), 2 ** bits - 1, np.uint8)
+        ax, aw = np.ones(17, np.float32), np.ones(33, np.float32)
+        bx, bw = np.zeros(17, np.int32), np.zeros(33, np.int32)
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, bits, bits, "f32")
+        assert np.all(acc.cpu().numpy() == (2 ** bits - 1) ** 2 * K)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_gemm_full_configs_sampled(oracle, b, name):
+    """Full benchmark shapes; the oracle checks all tokens x 48 sampled output features and
+    24 sampled tokens x all output features."""
+    w = wl.WORKLOADS[name]
+    rng = np.random.default_rng(w.seed)
+    a, wc, ax, aw, bx, bw = random_gemm_case(rng, w.N, w.C, w.O, w.a_bits, w.w_bits)
+    y, acc = run_gemm(b, a, wc, ax, aw, bx, bw, w.a_bits, w.w_bits, "bf16")
+    acc = acc.cpu().numpy()
+    cols = np.sort(rng.choice(w.O, 48, replace=False))
+    rows = np.sort(rng.choice(w.N, min(24, w.N), replace=False))
+    assert np.array_equal(acc[:, cols], oracle.int_gemm(a, wc[cols]))
+    assert np.array_equal(acc[rows], oracle.int_gemm(a[rows], wc))
+    # a property that holds at any size: sums over the output axis, against numpy int64
+    assert np.array_equal(acc.astype(np.int64).sum(1), a.astype(np.int64) @ wc.astype(np.int64).sum(0))
+    rs, cs = a.astype(np.int64).sum(1), wc.astype(np.int64).sum(1)
+    ref_rows = oracle.epilogue(acc[rows], w.C, ax[rows], bx[rows], rs[rows], aw, bw, cs)
+    got_rows = oracle.widen_bf16(y[__import__("torch").from_numpy(rows).cuda()].view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+    assert rel_err(got_rows, ref_rows).max() <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------- the whole layer (a1..a6)
+
+@pytest.mark.parametrize("name,N,C,O,y_dtype", [("tiny", None, None, None, "f32"), ("tiny", 33, 200, 50, "bf16"),
+                                               ("llama7b_qkv", 300, 4096, 640, "bf16"),
+                                               ("llama70b_q_decode", 16, 8192, 256, "f32")])
+def test_reassembled_linear_end_to_end(oracle, b, name, N, C, O, y_dtype):
+    import torch
+    w = wl.WORKLOADS[name]
+    c = make_case(oracle, w, N=N, C=C, O=O)
+    exp = oracle.reassembled_linear(c.x, c.norm, c.gamma, c.beta, c.eps, c.T, c.src_idx, c.dst_idx, w.a_bits,
+                                    (c.wcodes, c.aw, c.bw, c.cs))
+    dm = device_map(b, c)
+    q = b.qllm_quantize_weight_host(c.W, dm.row_ptr.cpu().numpy(), dm.src.cpu().numpy(), w.w_bits)
+    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], c.K, w.w_bits)
+    y = torch.full((c.N, c.O), float("nan"), dtype=torch.float32 if y_dtype == "f32" else torch.bfloat16, device="cuda")
+    ws = torch.empty(b.qllm_workspace_bytes(c.N, c.K, c.O, w.a_bits), dtype=torch.uint8, device="cuda")
+    g = torch.from_numpy(c.gamma).cuda()
+    be = None if c.beta is None else torch.from_numpy(c.beta).cuda()
+    b.qllm_reassembled_linear(to_torch_x(c.x), c.norm, g, be, c.eps, dm, w.a_bits, dw, y, ws)
+    torch.cuda.synchronize()
+    exact = check_y(oracle, y, exp["y"], y_dtype)
+    print(f"{name}: dequantised output bit-exact = {exact}")
+    # and the layer does its job: close to the full-precision norm -> linear
+    yn = oracle.norm(c.x, c.norm, c.gamma, c.beta, c.eps).astype(np.float64)
+    full = yn @ c.W.astype(np.float64)
+    got = exp["y"].astype(np.float64)
+    assert np.sqrt(((got - full) ** 2).mean()) < 0.6 * np.sqrt((full ** 2).mean())
