@@ -158,6 +158,10 @@ int64_t qllm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
 
 const char *qllm_status_string(int32_t status);
 
+/* After a call on this thread returned QLLM_ERR_HIP: the HIP runtime's own name for what went wrong
+ * and the library step that met it (a static or thread-local string; "" if there was none). */
+const char *qllm_last_hip_error(void);
+
 /* ------------------------------------------------------------------------------------------
  * Offline helpers.  HOST pointers throughout; plain CPU code; no GPU needed.
  */

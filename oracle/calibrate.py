@@ -57,7 +57,8 @@ def nearest_pairs(y, T, r, n_match_tokens=256, chunk=2048):
     pos_a = pos_a[eligible[pos_a]]
     pos_b = pos_b[eligible[pos_b]]
     if pos_a.size == 0 or pos_b.size == 0:
-        raise ValueError("no channel is eligible for merging")
+        return np.zeros(0, np.int32), np.zeros(0, np.int32)
+    r = min(r, pos_a.size)                              # tiny layers: merge what can be merged
     ys = np.asarray(y[:n_match_tokens], np.float64)
     cols_a = ys[:, chan_of[pos_a]]                      # [n, |A|]
     cols_b = ys[:, chan_of[pos_b]]                      # [n, |B|]
@@ -70,8 +71,6 @@ def nearest_pairs(y, T, r, n_match_tokens=256, chunk=2048):
         j = d2.argmin(1)
         best_j[s:s + chunk] = j
         best_d[s:s + chunk] = d2[np.arange(j.size), j]
-    if r > pos_a.size:
-        raise ValueError("more merges requested than set A has eligible members")
     pick = np.argsort(best_d, kind="stable")[:r]
     pick.sort()
     src_idx = (pos_a[pick] // 2).astype(np.int32)
@@ -81,7 +80,8 @@ def nearest_pairs(y, T, r, n_match_tokens=256, chunk=2048):
 
 def calibrate(y, theta_rule, merge=True, n_match_tokens=256):
     """y: norm output [N, C] float32 (from the oracle).  Returns a dict with absmax, theta, T,
-    src_idx, dst_idx.  With merge=True exactly sum(T-1) pairs are merged, so C^ == C."""
+    src_idx, dst_idx.  With merge=True sum(T-1) pairs are merged, so C^ == C (fewer only if set A
+    has fewer eligible members than that)."""
     absmax = api.channel_absmax(y)
     theta = theta_from_rule(absmax, theta_rule)
     T = api.num_split(absmax, theta)

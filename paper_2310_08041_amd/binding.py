@@ -8,6 +8,8 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- first: libqllm.so must bind to the HIP runtime torch has already loaded;
+#                              two HIP runtimes in one process leave the second without a device
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqllm.so")
@@ -24,7 +26,8 @@ _lib = C.CDLL(LIB_PATH)
 class QllmError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        detail = f" [{qllm_last_hip_error()}]" if status == -8 else ""
+        super().__init__(f"{where}: {status_string(status)} (status {status}){detail}")
 
 
 class _Map(C.Structure):
@@ -52,6 +55,7 @@ _sigs = {
     "qllm_gemm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_status_string": (C.c_char_p, [_i32]),
+    "qllm_last_hip_error": (C.c_char_p, []),
     "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, _vp, C.POINTER(_i64),
                                    C.POINTER(_i64), _vp]),
     "qllm_describe_map_host": (_i32, [_vp, _vp, _vp, _i64, _vp]),
@@ -72,6 +76,10 @@ def status_string(status):
 
 
 qllm_status_string = status_string
+
+
+def qllm_last_hip_error():
+    return _lib.qllm_last_hip_error().decode()
 
 
 def _chk(rc, where):
@@ -175,7 +183,6 @@ def qllm_unpack_codes_host(packed, K, bits):
 # ---------------------------------------------------------------- device side (torch tensors)
 
 def _torch():
-    import torch
     return torch
 
 

@@ -20,6 +20,8 @@
 
 #include "qllm.h"
 
+extern "C" void qllm_note_hip_error(const char *step, const char *name);
+
 namespace {
 
 constexpr int GROUP = QLLM_MAP_GROUP; // 8 channels per lane and step
@@ -408,14 +410,21 @@ template <typename K>
 int32_t launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, const FusedArgs &args)
 {
     if (lds_bytes > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds_bytes) != hipSuccess) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) {
             (void)hipGetLastError();
+            qllm_note_hip_error("fused kernel: raising the LDS limit", hipGetErrorName(e));
             return QLLM_ERR_HIP;
         }
     }
+    (void)hipGetLastError(); // drop any stale error of the calling thread: only this launch is judged
     hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args);
-    if (hipGetLastError() != hipSuccess) return QLLM_ERR_HIP;
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        qllm_note_hip_error("fused kernel: launch", hipGetErrorName(e));
+        return QLLM_ERR_HIP;
+    }
     return QLLM_OK;
 }
 

@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <limits>
 #include <thread>
@@ -97,7 +98,17 @@ inline uint32_t get_code(const uint8_t *row, int64_t k, int32_t bits)
 
 } // namespace
 
+// Text of the last HIP failure seen by this thread (written by the launch sites).
+thread_local char g_hip_error[160] = "";
+
+extern "C" void qllm_note_hip_error(const char *step, const char *name)
+{
+    std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", step, name);
+}
+
 extern "C" {
+
+const char *qllm_last_hip_error(void) { return g_hip_error; }
 
 int64_t qllm_packed_row_bytes(int64_t K, int32_t bits)
 {

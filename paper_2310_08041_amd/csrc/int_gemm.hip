@@ -18,6 +18,8 @@
 
 #include "qllm.h"
 
+extern "C" void qllm_note_hip_error(const char *step, const char *name);
+
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -252,11 +254,17 @@ template <int ABITS, int WBITS>
 int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
+    (void)hipGetLastError(); // drop any stale error of the calling thread: only this launch is judged
     if (y_dtype == QLLM_F32)
         hipLaunchKernelGGL((int_gemm_kernel<ABITS, WBITS, float>), grid, dim3(THREADS), 0, stream, g);
     else
         hipLaunchKernelGGL((int_gemm_kernel<ABITS, WBITS, uint16_t>), grid, dim3(THREADS), 0, stream, g);
-    return hipGetLastError() == hipSuccess ? QLLM_OK : QLLM_ERR_HIP;
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        qllm_note_hip_error("int gemm: launch", hipGetErrorName(e));
+        return QLLM_ERR_HIP;
+    }
+    return QLLM_OK;
 }
 
 } // namespace

@@ -124,7 +124,7 @@ def test_fused_degenerate_rows(oracle, b):
     x[1] = 0.0
     x[2] = np.abs(x[2]) + 100.0
     x[3] = -np.abs(x[3]) - 100.0
-    x[4] = 1.0e6 + np.arange(264, dtype=np.float32) * 0.125     # |x / alpha| ~ 2^25: slow path
+    x[4] = 1.0e6 + (np.arange(264) % 4).astype(np.float32) * 0.0625   # |x / alpha| > 2^26: slow path
     x[5] = np.where(np.arange(264) % 2 == 0, -6.0, 9.0)          # alpha = 1 exactly (4 bit)
     x[6] = np.arange(264, dtype=np.float32) * 0.5 - 60.0         # exact .5 ties after scaling
     for bits in (4, 6, 8):
