@@ -1,0 +1,89 @@
+"""Offline calibration that manufactures a reassembly map for a batch of activations.
+
+This is NOT the hot path: it runs once per layer, before inference (Sec. 4.3: the channel indices are
+pre-computed from calibration data).  The per-channel statistic comes from the library's own kernel
+(qllm_norm_channel_absmax); T and the CSR map come from qllm_build_map_host.  The pair selection in
+between (Appendix A: one edge from every member of set A to its nearest member of set B, keep the r
+shortest) uses torch matrix products on the device as a library primitive.  The edge length is the
+plain L2 distance between activation columns over the first `n_match` tokens -- the benchmark's
+policy for synthetic data -- not the paper's Eq. (5).
+"""
+import numpy as np
+import torch
+
+from . import binding as b
+
+
+def _extra_channels(absmax, theta):
+    return b.qllm_build_map_host(absmax, theta, [], [])["nnz"] - absmax.size
+
+
+def choose_theta(absmax, rule):
+    """("fixed", theta) | ("tmax", T_max): theta = max(m)/T_max | ("expand", ratio): the largest theta
+    whose disassembly adds at least ratio*C channels (Sec. 5.2 fixes theta through the expansion ratio)."""
+    kind, val = rule
+    m = np.asarray(absmax, np.float32)
+    if kind == "fixed":
+        return float(np.float32(val))
+    if kind == "tmax":
+        return float(np.float32(m.max()) / np.float32(val))
+    if kind == "expand":
+        target = max(1, int(round(val * m.size)))
+        hi = float(m.max())
+        lo = hi / 1e6
+        for _ in range(200):
+            mid = 0.5 * (lo + hi)
+            if _extra_channels(m, float(np.float32(mid))) >= target:
+                lo = mid
+            else:
+                hi = mid
+            if hi - lo <= 1e-7 * hi:
+                break
+        return float(np.float32(lo))
+    raise ValueError(kind)
+
+
+def match_pairs(y, num_split, r, chunk=4096):
+    """y: [n, C] fp32 device tensor of norm outputs.  Returns (src_idx, dst_idx) int32 numpy arrays."""
+    T = torch.as_tensor(num_split, device=y.device, dtype=torch.int64)
+    chan_of = torch.repeat_interleave(torch.arange(T.numel(), device=y.device), T)
+    eligible = T[chan_of] == 1
+    pos = torch.arange(chan_of.numel(), device=y.device)
+    pos_a = pos[(pos % 2 == 0) & eligible]
+    pos_b = pos[(pos % 2 == 1) & eligible]
+    r = min(r, pos_a.numel())
+    if r == 0 or pos_b.numel() == 0:
+        return np.zeros(0, np.int32), np.zeros(0, np.int32)
+    yd = y.double()
+    cols_b = yd[:, chan_of[pos_b]]
+    nb2 = (cols_b * cols_b).sum(0)
+    best_d, best_j = [], []
+    for s in range(0, pos_a.numel(), chunk):
+        a = yd[:, chan_of[pos_a[s:s + chunk]]]
+        d2 = (a * a).sum(0)[:, None] + nb2[None, :] - 2.0 * (a.T @ cols_b)
+        d, j = d2.min(1)
+        best_d.append(d)
+        best_j.append(j)
+    best_d, best_j = torch.cat(best_d), torch.cat(best_j)
+    pick = torch.argsort(best_d, stable=True)[:r].sort().values
+    src_idx = (pos_a[pick] // 2).to(torch.int32).cpu().numpy()
+    dst_idx = ((pos_b[best_j[pick]] - 1) // 2).to(torch.int32).cpu().numpy()
+    return src_idx, dst_idx
+
+
+def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256):
+    """x: [N, C] device tensor (fp32 / bf16).  Returns the dict of qllm_build_map_host plus theta,
+    absmax, src_idx, dst_idx."""
+    N, C = x.shape
+    absmax = torch.zeros(C, dtype=torch.float32, device=x.device)
+    y = torch.empty((min(N, n_match), C), dtype=torch.float32, device=x.device)
+    b.qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y)
+    m = absmax.cpu().numpy()
+    theta = choose_theta(m, theta_rule)
+    sizing = b.qllm_build_map_host(m, theta, [], [])
+    T = sizing["num_split"]
+    r = int(sizing["nnz"] - C) if merge else 0
+    src_idx, dst_idx = match_pairs(y, T, r)
+    out = b.qllm_build_map_host(m, theta, src_idx, dst_idx)
+    out.update(theta=theta, absmax=m, src_idx=src_idx, dst_idx=dst_idx)
+    return out
