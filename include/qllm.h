@@ -52,7 +52,7 @@ typedef enum { QLLM_NORM_NONE = 0, QLLM_NORM_LAYER = 1, QLLM_NORM_RMS = 2 } qllm
 #define QLLM_MAX_CHANNELS 32768
 /* Rows of packed codes are padded with zero codes to a multiple of this many codes. */
 #define QLLM_K_PAD 256
-/* Output channels are described to the fused kernel in groups of this many. */
+/* The fused kernel handles channels in groups of this many. */
 #define QLLM_MAP_GROUP 8
 
 /*
@@ -70,10 +70,12 @@ typedef struct {
     const int32_t *row_ptr; /* [C_out+1] increasing, row_ptr[0] = 0, row_ptr[C_out] = nnz, no empty row */
     const int32_t *src;     /* [nnz] 0 <= src < C_in */
     const float *scale;     /* [nnz] */
-    const int32_t *group_desc; /* optional [ceil(C_out/QLLM_MAP_GROUP)], from qllm_build_map_host or
-                                  qllm_describe_map_host: entry g >= 0 says that the 8 channels of group g
-                                  are single-entry, scale exactly 1, with sources g_desc, g_desc+1, ...;
-                                  -1 says "walk the CSR".  NULL: every group walks the CSR (slower). */
+    const int32_t *plan;    /* optional: device copy of the array qllm_plan_map_host makes from this very
+                               map (an index of it for the fused kernel: which groups of 8 output channels
+                               are plain shifted copies, the entries of all others, which inputs pass
+                               unscaled).  NULL: the kernel walks the CSR for every channel (much slower). */
+    int64_t plan_general;   /* the n_general value qllm_plan_map_host returned with that plan (0 with NULL) */
+    int64_t plan_len;       /* words in plan (0 with NULL) */
 } qllm_map;
 
 /*
@@ -172,20 +174,30 @@ const char *qllm_last_hip_error(void);
  *   (odd positions); pair k merges A-member src_idx[k] into B-member dst_idx[k] (Sec. 4.1.2,
  *   Appendix A, and the indexing of the runtime pseudo-code figure); several A-members may share
  *   a B-member; sub-channels of a split channel may not take part (QLLM_ERR_MAP).
- * Outputs (caller-sized: row_ptr C + extra + 1, src/scale C + extra entries, group_desc
- * ceil((C + extra)/8), where extra = sum(T_c - 1) can be obtained by a first call with
- * row_ptr == NULL): the CSR arrays, C_out = C + extra - r, nnz = C + extra, the T vector.
+ * Outputs (caller-sized: row_ptr C + extra + 1, src/scale C + extra entries, where
+ * extra = sum(T_c - 1) can be obtained by a first call with row_ptr == NULL): the CSR arrays,
+ * C_out = C + extra - r, nnz = C + extra, the T vector (num_split_out may be NULL).
  * Entry order inside a merged row: destination first, then sources by ascending position.
- * num_split_out and group_desc may be NULL.
  */
 int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx,
                             const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
-                            float *scale, int32_t *group_desc, int64_t *C_out, int64_t *nnz,
-                            int32_t *num_split_out);
+                            float *scale, int64_t *C_out, int64_t *nnz, int32_t *num_split_out);
 
-/* Fills group_desc [ceil(C_out/8)] for an existing CSR map (see qllm_map.group_desc). */
-int32_t qllm_describe_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
-                               int64_t C_out, int32_t *group_desc);
+/* Indexes a CSR map for the fused kernel (see qllm_map.plan).  Call once with plan == NULL to get
+ * *plan_len (int32 words) and *n_general, then with plan pointing at that many words.  The plan
+ * depends only on the map; upload it next to the CSR arrays.  Layout (int32 words):
+ *   [0..7]   header: magic, version, C_in, C_out, n_groups = ceil(C_out/8), n_general, n_chunks = ceil(C_in/8), n_long
+ *   desc     [n_groups]: d >= 0: the 8 channels of the group are single-entry with scale exactly 1 and
+ *            sources d, d+1, ..., d+7; d < 0: general group number -(d+1)
+ *   items    (starting at the next multiple of 4 words) [n_general * 8][2]: for channel k of a general
+ *            group {src0 | src1 << 16, scale}: one entry (src1 = 0xffff) or two entries of equal scale;
+ *            {-1, 0}: padding past C_out; {-2, first | count << 24}: any other row (at most 255
+ *            entries), its entries are longs[first .. first + count)
+ *   passes   [n_chunks]: bit j set: input channel 8*chunk + j is a source of some plain group
+ *   longs    [n_long][2]: {src, scale} entries of the rows that are neither of the two short forms
+ */
+int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,
+                           int64_t C_out, int32_t *plan, int64_t *plan_len, int64_t *n_general);
 
 /* Verifies a host copy of a map: monotone row_ptr without empty rows, sources in range, finite scales. */
 int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,

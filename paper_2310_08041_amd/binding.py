@@ -32,7 +32,7 @@ class QllmError(RuntimeError):
 
 class _Map(C.Structure):
     _fields_ = [("C_in", C.c_int64), ("C_out", C.c_int64), ("nnz", C.c_int64), ("row_ptr", C.c_void_p),
-                ("src", C.c_void_p), ("scale", C.c_void_p), ("group_desc", C.c_void_p)]
+                ("src", C.c_void_p), ("scale", C.c_void_p), ("plan", C.c_void_p), ("plan_general", C.c_int64), ("plan_len", C.c_int64)]
 
 
 class _Weight(C.Structure):
@@ -56,9 +56,9 @@ _sigs = {
     "qllm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_status_string": (C.c_char_p, [_i32]),
     "qllm_last_hip_error": (C.c_char_p, []),
-    "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, _vp, C.POINTER(_i64),
-                                   C.POINTER(_i64), _vp]),
-    "qllm_describe_map_host": (_i32, [_vp, _vp, _vp, _i64, _vp]),
+    "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64),
+                                   _vp]),
+    "qllm_plan_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, C.POINTER(_i64), C.POINTER(_i64)]),
     "qllm_check_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64]),
     "qllm_quantize_weight_host": (_i32, [_vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp]),
     "qllm_pack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
@@ -115,31 +115,37 @@ def qllm_gemm_workspace_bytes(N, K, O, a_bits):
 
 # ---------------------------------------------------------------- host helpers (numpy in, numpy out)
 
-def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx):
-    """Returns dict(row_ptr, src, scale, group_desc, num_split, C_in, C_out, nnz) of numpy arrays."""
+def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx, with_plan=True):
+    """Returns dict(row_ptr, src, scale, num_split, C_in, C_out, nnz[, plan, plan_general]) of numpy arrays."""
     m = _np(chan_absmax, np.float32)
     si, di = _np(src_idx, np.int32), _np(dst_idx, np.int32)
     Cc, r = m.size, si.size
     c_out, nnz = _i64(0), _i64(0)
     T = np.empty(Cc, np.int32)
-    _chk(_lib.qllm_build_map_host(_hp(m), Cc, theta, _hp(si), _hp(di), r, None, None, None, None, C.byref(c_out),
+    _chk(_lib.qllm_build_map_host(_hp(m), Cc, theta, _hp(si), _hp(di), r, None, None, None, C.byref(c_out),
                                   C.byref(nnz), _hp(T)), "qllm_build_map_host(size)")
     row_ptr = np.empty(c_out.value + 1, np.int32)
     src = np.empty(nnz.value, np.int32)
     scale = np.empty(nnz.value, np.float32)
-    desc = np.empty((c_out.value + MAP_GROUP - 1) // MAP_GROUP, np.int32)
     _chk(_lib.qllm_build_map_host(_hp(m), Cc, theta, _hp(si), _hp(di), r, _hp(row_ptr), _hp(src), _hp(scale),
-                                  _hp(desc), C.byref(c_out), C.byref(nnz), _hp(T)), "qllm_build_map_host")
-    return dict(row_ptr=row_ptr, src=src, scale=scale, group_desc=desc, num_split=T, C_in=Cc, C_out=c_out.value,
-                nnz=nnz.value)
+                                  C.byref(c_out), C.byref(nnz), _hp(T)), "qllm_build_map_host")
+    out = dict(row_ptr=row_ptr, src=src, scale=scale, num_split=T, C_in=Cc, C_out=c_out.value, nnz=nnz.value)
+    if with_plan:
+        out["plan"], out["plan_general"] = qllm_plan_map_host(row_ptr, src, scale, Cc)
+    return out
 
 
-def qllm_describe_map_host(row_ptr, src, scale):
+def qllm_plan_map_host(row_ptr, src, scale, C_in):
+    """Returns (plan int32 array, n_general) for a CSR map."""
     row_ptr, src, scale = _np(row_ptr, np.int32), _np(src, np.int32), _np(scale, np.float32)
     c_out = row_ptr.size - 1
-    desc = np.empty((c_out + MAP_GROUP - 1) // MAP_GROUP, np.int32)
-    _chk(_lib.qllm_describe_map_host(_hp(row_ptr), _hp(src), _hp(scale), c_out, _hp(desc)), "qllm_describe_map_host")
-    return desc
+    n, g = _i64(0), _i64(0)
+    _chk(_lib.qllm_plan_map_host(_hp(row_ptr), _hp(src), _hp(scale), int(C_in), c_out, None, C.byref(n), C.byref(g)),
+         "qllm_plan_map_host(size)")
+    plan = np.empty(n.value, np.int32)
+    _chk(_lib.qllm_plan_map_host(_hp(row_ptr), _hp(src), _hp(scale), int(C_in), c_out, _hp(plan), C.byref(n),
+                                 C.byref(g)), "qllm_plan_map_host")
+    return plan, g.value
 
 
 def qllm_check_map_host(row_ptr, src, scale, C_in):
@@ -208,16 +214,16 @@ def _x_dtype(x):
 class DeviceMap:
     """Device copy of a reassembly map (keeps the tensors alive next to the C struct)."""
 
-    def __init__(self, row_ptr, src, scale, C_in, group_desc=None, device="cuda"):
+    def __init__(self, row_ptr, src, scale, C_in, plan=None, plan_general=0, device="cuda"):
         torch = _torch()
         self.row_ptr = torch.as_tensor(np.ascontiguousarray(row_ptr, np.int32)).to(device)
         self.src = torch.as_tensor(np.ascontiguousarray(src, np.int32)).to(device)
         self.scale = torch.as_tensor(np.ascontiguousarray(scale, np.float32)).to(device)
-        self.group_desc = None if group_desc is None else torch.as_tensor(
-            np.ascontiguousarray(group_desc, np.int32)).to(device)
+        self.plan = None if plan is None else torch.as_tensor(np.ascontiguousarray(plan, np.int32)).to(device)
+        self.plan_general = int(plan_general) if plan is not None else 0
         self.C_in, self.C_out, self.nnz = int(C_in), int(self.row_ptr.numel() - 1), int(self.src.numel())
         self.c = _Map(self.C_in, self.C_out, self.nnz, _dp(self.row_ptr), _dp(self.src), _dp(self.scale),
-                      _dp(self.group_desc))
+                      _dp(self.plan), self.plan_general, 0 if self.plan is None else int(self.plan.numel()))
 
 
 class DeviceWeight:

@@ -15,7 +15,7 @@ from . import binding as b
 
 
 def _extra_channels(absmax, theta):
-    return b.qllm_build_map_host(absmax, theta, [], [])["nnz"] - absmax.size
+    return b.qllm_build_map_host(absmax, theta, [], [], with_plan=False)["nnz"] - absmax.size
 
 
 def choose_theta(absmax, rule):
@@ -80,7 +80,7 @@ def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256):
     b.qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y)
     m = absmax.cpu().numpy()
     theta = choose_theta(m, theta_rule)
-    sizing = b.qllm_build_map_host(m, theta, [], [])
+    sizing = b.qllm_build_map_host(m, theta, [], [], with_plan=False)
     T = sizing["num_split"]
     r = int(sizing["nnz"] - C) if merge else 0
     src_idx, dst_idx = match_pairs(y, T, r)

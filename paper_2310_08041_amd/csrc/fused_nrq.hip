@@ -12,6 +12,12 @@
 // LDS rows, the dword next to its neighbour lane's: reads and writes are bank-conflict free also
 // when the map shifts the source channels by an amount that is not a multiple of 8.
 //
+// Two kernels.  fused_planned_kernel is the fast one: persistent workgroups (each keeps its share of
+// gamma and of the map's plan in registers across the rows it processes), the next row's loads in
+// flight while the current row is worked on, no global reads of the map per row.  It needs the plan
+// of qllm_plan_map_host.  fused_nrq_kernel is the plain one that walks the CSR; it serves maps
+// without a plan, or whose general groups do not fit in LDS next to the row.
+//
 // Compiled with -ffp-contract=off: every fp32 product and sum is rounded on its own; the only fused
 // multiply-adds are the explicit ones of the quantizer, whose single rounding is the definition.
 #include <hip/hip_runtime.h>
@@ -19,35 +25,11 @@
 #include <stdint.h>
 
 #include "qllm.h"
+#include "fused_common.h"
 
-extern "C" void qllm_note_hip_error(const char *step, const char *name);
+using namespace qllm_detail;
 
 namespace {
-
-constexpr int GROUP = QLLM_MAP_GROUP; // 8 channels per lane and step
-constexpr float MAGIC = 12582912.0f;  // 1.5 * 2^23: x + MAGIC rounds x to an integer, ties to even
-constexpr int32_t MAGIC_BITS = 0x4B400000;
-constexpr float FAST_LIMIT = 2097152.0f; // 2^21: below it the MAGIC trick is exact
-
-struct FusedArgs {
-    const void *x;
-    int64_t ldx;
-    int32_t N, C, norm, vec_ok;
-    const float *gamma, *beta;
-    float eps;
-    const int32_t *row_ptr, *src, *desc;
-    const float *scale;
-    int32_t C_out, n_groups, n_groups_pad, S;
-    uint8_t *codes;
-    int64_t row_bytes;
-    float *alpha;
-    int32_t *zero, *rowsum;
-    // calibration variant
-    float *absmax, *y_dump;
-    int32_t n_dump;
-};
-
-__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
 // ---- block-wide reductions: shuffles inside a wavefront, then a fixed-order sum over the waves
 template <int THREADS>
@@ -221,36 +203,6 @@ __device__ __forceinline__ void load_norm_stage(const FusedArgs &a, int64_t row,
             }
         }
     }
-}
-
-// ---- Eq. (2) for one value; the row's parameters are uniform over the workgroup
-struct RowQuant {
-    float inv;
-    int32_t beta;
-    int32_t fast; // all |x*inv| < 2^21: the MAGIC trick is exact
-};
-
-// rne(x*inv) on the exact product.  Fast form: one fused multiply-add against MAGIC, whose single
-// rounding lands on the integer grid.  Slow form (huge quotients): the product is exact in fp64.
-__device__ __forceinline__ int32_t rne_product_fast(float x, float inv)
-{
-    return __float_as_int(__builtin_fmaf(x, inv, MAGIC)) - MAGIC_BITS;
-}
-
-__device__ __forceinline__ double rne_product_slow(float x, float inv)
-{
-    return rint((double)x * (double)inv);
-}
-
-template <int QMAX>
-__device__ __forceinline__ int32_t quant_code(float x, float inv, int32_t beta, int32_t fast)
-{
-    if (fast) {
-        const int32_t q = rne_product_fast(x, inv) + beta; // both below 2^22 in magnitude
-        return q < 0 ? 0 : (q > QMAX ? QMAX : q);
-    }
-    const double q = rne_product_slow(x, inv) + (double)beta;
-    return (int32_t)fmin(fmax(q, 0.0), (double)QMAX);
 }
 
 template <typename XT, int BITS, int THREADS, int ITERS>
@@ -498,7 +450,17 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     a.row_ptr = map->row_ptr;
     a.src = map->src;
     a.scale = map->scale;
-    a.desc = map->group_desc;
+    if (map->plan) { // header (8 words), then desc, items, passes: see qllm_plan_map_host
+        if (map->plan_general < 0 || (reinterpret_cast<uintptr_t>(map->plan) & 15u)) return QLLM_ERR_ALIGN;
+        a.n_general = (int32_t)map->plan_general;
+        a.desc = map->plan + 8;
+        a.items = map->plan + (8 + (map->C_out + GROUP - 1) / GROUP + 3) / 4 * 4;
+        a.passes = a.items + (int64_t)a.n_general * GROUP * 2;
+        a.longs = a.passes + (C + GROUP - 1) / GROUP;
+        const int64_t n_long = (map->plan_len - (a.longs - map->plan)) / 2;
+        if (n_long < 0 || n_long > 0xffffff) return QLLM_ERR_SHAPE;
+        a.n_long = (int32_t)n_long;
+    }
     a.C_out = (int32_t)map->C_out;
     a.n_groups = (int32_t)((map->C_out + GROUP - 1) / GROUP);
     a.row_bytes = qllm_packed_row_bytes(map->C_out, bits);
@@ -509,6 +471,10 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     a.rowsum = out->rowsum;
     const int max_units = a.S > a.n_groups_pad ? a.S : a.n_groups_pad;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (map->plan) {
+        rc = qllm_launch_fused_planned(a, x_dtype, bits, stream);
+        if (rc != QLLM_ERR_WORKSPACE) return rc; // does not fit on chip: the plain kernel below handles it
+    }
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, max_units, stream);
     return dispatch_bits<float>(a, bits, max_units, stream);
 }

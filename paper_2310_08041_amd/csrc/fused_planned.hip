@@ -1,0 +1,613 @@
+// The fast fused kernel: norm + channel disassembly + channel assembly + per-token quantization
+// (steps a1..a4; Sec. 4.3, Eq. 3, Eq. 4, Eq. 2) for maps that come with a plan.
+//
+// Shape of the computation
+//   * Persistent workgroups: grid = (CUs x resident workgroups), each workgroup walks rows
+//     blockIdx, blockIdx + grid, ...  What depends only on the map and on gamma -- the lane's share of
+//     gamma, of the plan's group descriptors, pass bits and general-group entries -- is loaded once
+//     into registers and reused for every row.
+//   * HBM: a row is read exactly once, 16 bytes per lane, consecutive lanes on consecutive addresses;
+//     the loads of the workgroup's next row are issued before the current row is processed, so they
+//     are in flight during its arithmetic.  Codes leave as one coalesced store per lane and group.
+//   * LDS: y (fp32) is staged "transposed by 8": channel c at float (c & 7) * S + (c >> 3).  A lane
+//     that owns channels 8i..8i+7 writes 8 dwords next to its neighbours' (no bank conflicts), and a
+//     lane that needs 8 consecutive channels starting anywhere reads 8 dwords next to its neighbours'.
+//     S is a compile-time constant, so all 16 addresses are one register plus an immediate.
+//   * min/max of the reassembled row without materialising it: every reassembled channel is either
+//     an unscaled copy of an input channel (those inputs carry a pass bit and enter min/max when y is
+//     produced) or a channel of a "general" group (sub-channels, merged channels and their
+//     neighbours), whose values are computed from LDS by whichever lane the item falls to, kept in a
+//     small second LDS area, and enter min/max there.  min and max do not depend on order.
+//   * Codes: one fused multiply-add against 1.5 * 2^23 rounds x * inv to the nearest-even integer in
+//     the low mantissa bits; a signed median clamps; shift-and-add packs.  Plain groups whose source
+//     offset is not a multiple of 8 are read rotated and the packed word is rotated back.
+//
+// Compiled with -ffp-contract=off (see fused_nrq.hip).
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+
+#include "qllm.h"
+#include "fused_common.h"
+
+using namespace qllm_detail;
+
+namespace {
+
+constexpr int32_t DESC_PAD = INT32_MIN; // group past C_out that exists only as zero padding
+constexpr int32_t DESC_NONE = INT32_MIN + 1;
+
+template <typename XT>
+struct Raw; // 8 input elements as they sit in memory
+template <>
+struct Raw<uint16_t> {
+    uint4 q;
+};
+template <>
+struct Raw<float> {
+    float4 lo, hi;
+};
+
+// The planned kernel is only launched for rows that are 16-byte aligned and whole chunks long
+// (C % 8 == 0); everything else goes to the plain kernel.
+__device__ __forceinline__ void load_raw(Raw<uint16_t> &r, const uint16_t *xr, int c0)
+{
+    r.q = *reinterpret_cast<const uint4 *>(xr + c0);
+}
+
+__device__ __forceinline__ void load_raw(Raw<float> &r, const float *xr, int c0)
+{
+    r.lo = *reinterpret_cast<const float4 *>(xr + c0);
+    r.hi = *reinterpret_cast<const float4 *>(xr + c0 + 4);
+}
+
+__device__ __forceinline__ void widen(const Raw<uint16_t> &r, float *v)
+{
+    const uint32_t w[4] = {r.q.x, r.q.y, r.q.z, r.q.w};
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        v[2 * p] = __uint_as_float(w[p] << 16);
+        v[2 * p + 1] = __uint_as_float(w[p] & 0xffff0000u);
+    }
+}
+
+__device__ __forceinline__ void widen(const Raw<float> &r, float *v)
+{
+    v[0] = r.lo.x; v[1] = r.lo.y; v[2] = r.lo.z; v[3] = r.lo.w;
+    v[4] = r.hi.x; v[5] = r.hi.y; v[6] = r.hi.z; v[7] = r.hi.w;
+}
+
+// Hides the register contents from the optimiser, so that widening a chunk a second time really is
+// redone (two shifts per pair) instead of keeping 8 widened floats per chunk alive across the
+// statistics reduction.
+__device__ __forceinline__ void forget(Raw<uint16_t> &r)
+{
+    asm volatile("" : "+v"(r.q.x), "+v"(r.q.y), "+v"(r.q.z), "+v"(r.q.w));
+}
+__device__ __forceinline__ void forget(Raw<float> &) {}
+
+// (float)(1 / sqrt(t)) for t > 0: the hardware's reciprocal-square-root estimate refined by two Newton
+// steps in fp64 (relative error of a few 1e-16), then rounded to fp32.  It equals the fp32 rounding of
+// the exact value unless that lies within ~1e-16 (relative) of a rounding boundary of fp32.
+__device__ __forceinline__ float rsqrt_to_f32(double t)
+{
+    double r = __builtin_amdgcn_rsq(t);
+    const double h = 0.5 * t;
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        const double e = __builtin_fma(-(h * r), r, 0.5);
+        r = __builtin_fma(r, e, r);
+    }
+    return (float)r;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Sum over the workgroup: shuffles, one LDS slot per wave, one barrier, then every lane adds the slots
+// in the same order.  The slot array is not reused before another barrier has passed.
+__device__ __forceinline__ double block_sum(double v, double *slots, int wave, int lane, int nwaves)
+{
+    v = wave_sum(v);
+    if (lane == 0) slots[wave] = v;
+    __syncthreads();
+    double s = slots[0];
+    for (int w = 1; w < nwaves; ++w) s += slots[w];
+    return s;
+}
+
+// gamma of one 8-channel chunk (held in registers for the lifetime of the workgroup).  NORM_NONE runs
+// as "rstd = 1, gamma = 1": both multiplications are exact, so y == x bit for bit.
+__device__ __forceinline__ void load_gamma(float *g, const float *gamma, int c0, int C, bool use)
+{
+#pragma unroll
+    for (int j = 0; j < GROUP; ++j) g[j] = 1.0f;
+    if (!use || c0 >= C) return;
+    const float4 g0 = *reinterpret_cast<const float4 *>(gamma + c0);
+    const float4 g1 = *reinterpret_cast<const float4 *>(gamma + c0 + 4);
+    g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w;
+    g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
+}
+
+// 8 values of a plain group whose first source channel is 8*u + V, V known at compile time:
+// channel 8u + V + j sits in LDS row (V + j) & 7, column u + ((V + j) >> 3); slot k = LDS row k.
+template <int S_T, int V>
+__device__ __forceinline__ void read_plain(const float *ycol, float *val)
+{
+#pragma unroll
+    for (int k = 0; k < GROUP; ++k) val[k] = ycol[k * S_T + (k < V ? 1 : 0)];
+}
+
+// Eq. (2) for a row whose quotients are too large for the fused-multiply-add trick.
+__device__ __noinline__ uint32_t slow_code(float x, float inv, int32_t beta, int32_t qmax)
+{
+    const double q = rne_product_slow(x, inv) + (double)beta;
+    return (uint32_t)fmin(fmax(q, 0.0), (double)qmax);
+}
+
+// Quantizes the 8 slots of one group (Eq. 2), packs them, rotates slot order back into channel order
+// and stores.  Returns the sum of the codes.
+//
+// Fast form: b = bits(fma(x, inv, MAGIC)) is MAGIC_BITS + rne(x*inv); clamping b to [lo, lo + qmax]
+// with lo = MAGIC_BITS - beta leaves lo + code.  The 8 (or 4) values are packed with shift-and-add
+// in wrapping 32-bit arithmetic and the common offset lo * (1 + 2^BITS + 2^(2 BITS) + ...) is taken
+// off once.
+template <int BITS>
+__device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, int rot, int32_t fast, float inv,
+                                              int32_t beta, uint8_t *out_row, int g)
+{
+    constexpr int QMAX = (1 << BITS) - 1;
+    uint32_t c[GROUP], bias = 0;
+    if (fast) {
+        const int32_t lo = MAGIC_BITS - beta, hi = lo + QMAX; // |beta| < 2^22: no wrap
+        bias = (uint32_t)lo;
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k)
+            c[k] = (uint32_t)min(max(__float_as_int(__builtin_fmaf(val[k], inv, MAGIC)), lo), hi);
+    } else {
+#pragma unroll 1
+        for (int k = 0; k < GROUP; ++k) c[k] = slow_code(val[k], inv, beta, QMAX); // rare; kept out of line
+    }
+    if (live != 0xffu) {
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) c[k] = (live >> k & 1u) ? c[k] : bias;
+    }
+    if constexpr (BITS == 4) {
+        uint32_t p = 0;
+#pragma unroll
+        for (int k = GROUP - 1; k >= 0; --k) p = (p << 4) + c[k];
+        p -= bias * 0x11111111u;
+        reinterpret_cast<uint32_t *>(out_row)[g] = __builtin_amdgcn_alignbit(p, p, rot * 4); // rotate right
+        return (int32_t)__builtin_amdgcn_udot8(p, 0x11111111u, 0u, false);
+    } else if constexpr (BITS == 8) {
+        uint32_t p0 = 0, p1 = 0;
+#pragma unroll
+        for (int k = 3; k >= 0; --k) {
+            p0 = (p0 << 8) + c[k];
+            p1 = (p1 << 8) + c[k + 4];
+        }
+        p0 -= bias * 0x01010101u;
+        p1 -= bias * 0x01010101u;
+        const uint64_t p = (uint64_t)p0 | ((uint64_t)p1 << 32);
+        const int sh = rot * 8;
+        reinterpret_cast<uint64_t *>(out_row)[g] = (p >> sh) | (p << ((64 - sh) & 63));
+        return (int32_t)__builtin_amdgcn_udot4(p0, 0x01010101u, __builtin_amdgcn_udot4(p1, 0x01010101u, 0u, false), false);
+    } else {
+        uint32_t h0 = 0, h1 = 0; // four 6-bit codes each
+#pragma unroll
+        for (int k = 3; k >= 0; --k) {
+            h0 = (h0 << 6) + c[k];
+            h1 = (h1 << 6) + c[k + 4];
+        }
+        h0 = (h0 - bias * 0x41041u) & 0xffffffu;
+        h1 = (h1 - bias * 0x41041u) & 0xffffffu;
+        uint64_t p = (uint64_t)h0 | ((uint64_t)h1 << 24);
+        const int sh = rot * 6;
+        p = ((p >> sh) | (p << (48 - sh))) & 0xffffffffffffull;
+        uint16_t *o16 = reinterpret_cast<uint16_t *>(out_row + (int64_t)g * 6);
+        o16[0] = (uint16_t)p;
+        o16[1] = (uint16_t)(p >> 16);
+        o16[2] = (uint16_t)(p >> 32);
+        const uint32_t f = (h0 & 0x3f03fu) + ((h0 >> 6) & 0x3f03fu) + (h1 & 0x3f03fu) + ((h1 >> 6) & 0x3f03fu);
+        return (int32_t)((f & 0xfffu) + (f >> 12));
+    }
+}
+
+// GAM_REG: the lane's share of gamma stays in registers for the lifetime of the workgroup; otherwise it
+// is re-read (from L2) for every row, which frees 8 registers per chunk.
+template <typename XT, int BITS, int S_T, int ITERS, int NT_MAX, bool GAM_REG>
+__global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
+{
+    extern __shared__ float lds[];
+    float *ylds = lds;              // [8 * S_T]        y, transposed by 8
+    float *exc = lds + GROUP * S_T; // [8 * n_general]  reassembled channels of the general groups
+    int2 *longs = reinterpret_cast<int2 *>(exc + GROUP * a.n_general); // [n_long] {src, scale} of long rows
+    __shared__ double red_d[2][16];
+    __shared__ float red_f[32];
+    __shared__ int32_t red_i[16];
+    // bf16 rows are prefetched one row ahead; fp32 rows would need twice the registers and are not
+    constexpr bool PREFETCH = sizeof(XT) == 2;
+    constexpr int ITEMS_REG = ITERS + 1; // general-group entries a lane keeps in registers
+
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nwaves = nt >> 6;
+    const int n_chunks = (a.C + GROUP - 1) / GROUP;
+    const int n_items = a.n_general * GROUP;
+    const float inf = __builtin_inff();
+    const bool layer = a.norm == QLLM_NORM_LAYER;
+
+    // ---- per-lane state that outlives the rows
+    float gam[GAM_REG ? ITERS : 1][GROUP];
+    uint32_t pass[ITERS];
+    int32_t desc[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int i = tid + it * nt;
+        pass[it] = i < n_chunks ? (uint32_t)a.passes[i] : 0u;
+        desc[it] = i < a.n_groups ? a.desc[i] : (i < a.n_groups_pad ? DESC_PAD : DESC_NONE);
+        if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
+    }
+    for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int2 *>(a.longs)[j];
+    int2 item[ITEMS_REG]; // {src0 | src1 << 16, scale}
+#pragma unroll
+    for (int m = 0; m < ITEMS_REG; ++m) {
+        const int j = tid + m * nt;
+        item[m] = j < n_items ? reinterpret_cast<const int2 *>(a.items)[j] : make_int2(-1, 0);
+    }
+
+    // value of one general-group channel from the staged row
+    auto item_value = [&](const int2 &e) -> float {
+        if (e.x != -2) {
+            const uint32_t s0 = (uint32_t)e.x & 0xffffu, s1 = (uint32_t)e.x >> 16;
+            const float sc = __int_as_float(e.y);
+            float acc = sc * ylds[(s0 & 7) * S_T + (s0 >> 3)];
+            if (s1 != 0xffffu) acc = acc + sc * ylds[(s1 & 7) * S_T + (s1 >> 3)];
+            return acc;
+        }
+        // any other row (more than two entries, or unequal scales): e.y = first | count << 24 into longs
+        const int first = e.y & 0xffffff, count = (uint32_t)e.y >> 24;
+        int2 le = longs[first];
+        float acc = __int_as_float(le.y) * ylds[(le.x & 7) * S_T + (le.x >> 3)];
+        for (int p = 1; p < count; ++p) {
+            le = longs[first + p];
+            acc = acc + __int_as_float(le.y) * ylds[(le.x & 7) * S_T + (le.x >> 3)];
+        }
+        return acc;
+    };
+
+    const XT *xbase = reinterpret_cast<const XT *>(a.x);
+    Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
+    int64_t row = blockIdx.x;
+    if (PREFETCH && row < a.N) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int i = tid + it * nt;
+            if (i < n_chunks) load_raw(ahead[PREFETCH ? it : 0], xbase + row * a.ldx, i * GROUP);
+        }
+    }
+
+    for (; row < a.N; row += gridDim.x) {
+        // Everything derived from the plan (LDS addresses, masks, shifts) costs a handful of
+        // instructions per row to recompute, but a register each to keep: make the optimiser
+        // recompute it by hiding that the plan registers do not change from row to row.
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) asm volatile("" : "+v"(desc[it]), "+v"(pass[it]));
+#pragma unroll
+        for (int m = 0; m < ITEMS_REG; ++m) asm volatile("" : "+v"(item[m].x), "+v"(item[m].y));
+
+        // ---- step a1.  Take this row (already on its way); put the next row's loads in flight.
+        if constexpr (PREFETCH) {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) raw[it] = ahead[it];
+            const int64_t next = row + gridDim.x;
+            if (next < a.N) {
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    const int i = tid + it * nt;
+                    if (i < n_chunks) load_raw(ahead[it], xbase + next * a.ldx, i * GROUP);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int i = tid + it * nt;
+                if (i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
+            }
+        }
+
+        // row statistics in fp64 (chunks past C hold zeros: load_raw pads)
+        float mu = 0.0f, rstd = 1.0f;
+        if (a.norm == QLLM_NORM_RMS) {
+            double q = 0.0;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                if (tid + it * nt < n_chunks) {
+                    float v[GROUP];
+                    widen(raw[it], v);
+#pragma unroll
+                    for (int j = 0; j < GROUP; ++j) {
+                        const double d = (double)v[j];
+                        q = __builtin_fma(d, d, q);
+                    }
+                }
+            }
+            q = block_sum(q, red_d[0], wave, lane, nwaves);
+            rstd = rsqrt_to_f32(q / (double)a.C + (double)a.eps);
+        } else if (layer) {
+            double s = 0.0;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                if (tid + it * nt < n_chunks) {
+                    float v[GROUP];
+                    widen(raw[it], v);
+#pragma unroll
+                    for (int j = 0; j < GROUP; ++j) s += (double)v[j];
+                }
+            }
+            s = block_sum(s, red_d[0], wave, lane, nwaves);
+            const double mu64 = s / (double)a.C;
+            double q = 0.0;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int c0 = (tid + it * nt) * GROUP;
+                if (c0 < a.C) {
+                    float v[GROUP];
+                    widen(raw[it], v);
+#pragma unroll
+                    for (int j = 0; j < GROUP; ++j) {
+                        const double d = (double)v[j] - mu64;
+                        q = __builtin_fma(d, d, q);
+                    }
+                }
+            }
+            q = block_sum(q, red_d[1], wave, lane, nwaves);
+            mu = (float)mu64;
+            rstd = rsqrt_to_f32(q / (double)a.C + (double)a.eps);
+        }
+
+        // ---- y into LDS; min/max over the channels that pass unscaled
+        float mn = inf, mx = -inf;
+        const bool shift = layer && a.beta != nullptr;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int i = tid + it * nt;
+            float gjit[GROUP];
+            if constexpr (!GAM_REG) load_gamma(gjit, a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
+            const float *g8 = GAM_REG ? gam[GAM_REG ? it : 0] : gjit;
+            if (i < n_chunks) {
+                float y[GROUP];
+                forget(raw[it]);
+                widen(raw[it], y);
+#pragma unroll
+                for (int j = 0; j < GROUP; ++j) {
+                    float t = y[j];
+                    if (layer) t = t - mu;
+                    t = t * rstd;
+                    t = t * g8[j];
+                    if (shift) t = t + a.beta[i * GROUP + j];
+                    y[j] = t;
+                    ylds[j * S_T + i] = t;
+                }
+                if (pass[it] == 0xffu) {
+#pragma unroll
+                    for (int j = 0; j < GROUP; ++j) {
+                        mn = fminf(mn, y[j]);
+                        mx = fmaxf(mx, y[j]);
+                    }
+                } else if (pass[it] != 0u) {
+#pragma unroll
+                    for (int j = 0; j < GROUP; ++j)
+                        if (pass[it] >> j & 1u) {
+                            mn = fminf(mn, y[j]);
+                            mx = fmaxf(mx, y[j]);
+                        }
+                }
+            }
+        }
+        __syncthreads(); // y complete
+
+        // ---- steps a2 + a3 for the general groups: sub-channels (scale 1/T), merged channels
+        //      (scale 1/g each) and the plain channels that share a group of 8 with them
+#pragma unroll
+        for (int m = 0; m < ITEMS_REG; ++m) {
+            const int j = tid + m * nt;
+            if (j < n_items) {
+                float xv = 0.0f;
+                if (item[m].x != -1) {
+                    xv = item_value(item[m]);
+                    mn = fminf(mn, xv);
+                    mx = fmaxf(mx, xv);
+                }
+                exc[j] = xv;
+            }
+        }
+        for (int j = tid + ITEMS_REG * nt; j < n_items; j += nt) {
+            const int2 e = reinterpret_cast<const int2 *>(a.items)[j];
+            float xv = 0.0f;
+            if (e.x != -1) {
+                xv = item_value(e);
+                mn = fminf(mn, xv);
+                mx = fmaxf(mx, xv);
+            }
+            exc[j] = xv;
+        }
+
+        // ---- per-token range (Eq. 2)
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            mn = fminf(mn, __shfl_xor(mn, o, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        }
+        if (lane == 0) {
+            red_f[wave] = mn;
+            red_f[16 + wave] = mx;
+        }
+        __syncthreads(); // also: exc complete
+        mn = red_f[0];
+        mx = red_f[16];
+        for (int w = 1; w < nwaves; ++w) {
+            mn = fminf(mn, red_f[w]);
+            mx = fmaxf(mx, red_f[16 + w]);
+        }
+        constexpr int QMAX = (1 << BITS) - 1;
+        const float range = mx - mn;
+        const float alpha = range > 0.0f ? range / (float)QMAX : 1.0f;
+        const float inv = 1.0f / alpha;
+        const int32_t fast = fabsf(mn * inv) < FAST_LIMIT && fabsf(mx * inv) < FAST_LIMIT;
+        int32_t beta;
+        if (fast) beta = -rne_product_fast(mn, inv);
+        else beta = (int32_t)fmin(fmax(-rne_product_slow(mn, inv), -2147483647.0), 2147483647.0);
+
+        // ---- step a4: codes
+        int32_t sum = 0;
+        uint8_t *out_row = a.codes + row * a.row_bytes;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int g = tid + it * nt;
+            const int32_t d = desc[it];
+            if (d != DESC_NONE) {
+                float val[GROUP];
+                uint32_t live = 0xffu;
+                const int vv = d & 7;
+                int rot = vv;
+                const int v0 = __builtin_amdgcn_readfirstlane(vv);
+                if (__all(d >= 0 && vv == v0)) {
+                    // the whole wave reads plain groups with the same misalignment: every address is
+                    // one register plus an immediate
+                    const float *ycol = ylds + (d >> 3);
+                    switch (v0) {
+                    case 0: read_plain<S_T, 0>(ycol, val); break;
+                    case 1: read_plain<S_T, 1>(ycol, val); break;
+                    case 2: read_plain<S_T, 2>(ycol, val); break;
+                    case 3: read_plain<S_T, 3>(ycol, val); break;
+                    case 4: read_plain<S_T, 4>(ycol, val); break;
+                    case 5: read_plain<S_T, 5>(ycol, val); break;
+                    case 6: read_plain<S_T, 6>(ycol, val); break;
+                    default: read_plain<S_T, 7>(ycol, val); break;
+                    }
+                } else if (d >= 0) {
+                    const int u = d >> 3;
+#pragma unroll
+                    for (int k = 0; k < GROUP; ++k) val[k] = ylds[k * S_T + u + (k < vv ? 1 : 0)];
+                } else if (d != DESC_PAD) {
+                    const float4 e0 = *reinterpret_cast<const float4 *>(exc + (-(d + 1)) * GROUP);
+                    const float4 e1 = *reinterpret_cast<const float4 *>(exc + (-(d + 1)) * GROUP + 4);
+                    val[0] = e0.x; val[1] = e0.y; val[2] = e0.z; val[3] = e0.w;
+                    val[4] = e1.x; val[5] = e1.y; val[6] = e1.z; val[7] = e1.w;
+                    rot = 0;
+                    const int left = a.C_out - g * GROUP;
+                    if (left < GROUP) live = (1u << left) - 1u;
+                } else {
+                    rot = 0;
+                    live = 0u;
+#pragma unroll
+                    for (int k = 0; k < GROUP; ++k) val[k] = 0.0f;
+                }
+                sum += pack_store<BITS>(val, live, rot, fast, inv, beta, out_row, g);
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if (lane == 0) red_i[wave] = sum;
+        __syncthreads(); // row done: LDS may be overwritten, red_i is complete
+        if (tid == 0) {
+            int32_t s = red_i[0];
+            for (int w = 1; w < nwaves; ++w) s += red_i[w];
+            a.alpha[row] = alpha;
+            a.zero[row] = beta;
+            a.rowsum[row] = s;
+        }
+    }
+}
+
+struct Shape {
+    int s_t, iters, nt;
+};
+
+// Smallest compiled (S, ITERS) that holds `units` 8-channel groups, and the workgroup size for it.
+Shape pick_shape(int units)
+{
+    Shape s;
+    if (units <= 256) s = {256, 1, 0};
+    else if (units <= 1024) s = {1024, 2, 0};
+    else if (units <= 2048) s = {2048, 2, 0};
+    else s = {4096, 4, 0};
+    s.nt = ((units + s.iters - 1) / s.iters + 63) / 64 * 64;
+    return s;
+}
+
+int cu_count()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    cached = n;
+    return n;
+}
+
+template <typename K>
+int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+{
+    if (lds > 48 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            qllm_note_hip_error("planned fused kernel: raising the LDS limit", hipGetErrorName(e));
+            return QLLM_ERR_HIP;
+        }
+    }
+    // resident workgroups per CU: bounded by LDS (160 KB) and by 2048 lanes
+    int per_cu = (int)((160 * 1024) / (lds + 1024));
+    per_cu = per_cu < 2048 / sh.nt ? per_cu : 2048 / sh.nt;
+    if (per_cu < 1) per_cu = 1;
+    int64_t grid = (int64_t)cu_count() * per_cu;
+    if (grid > a.N) grid = a.N;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3((unsigned)sh.nt), lds, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        qllm_note_hip_error("planned fused kernel: launch", hipGetErrorName(e));
+        return QLLM_ERR_HIP;
+    }
+    return QLLM_OK;
+}
+
+template <typename XT, int BITS>
+int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+{
+    if (sh.s_t == 256) return launch(fused_planned_kernel<XT, BITS, 256, 1, 256, true>, a, sh, lds, stream);
+    if (sh.s_t == 1024) return launch(fused_planned_kernel<XT, BITS, 1024, 2, 512, true>, a, sh, lds, stream);
+    if (sh.s_t == 2048) return launch(fused_planned_kernel<XT, BITS, 2048, 2, 1024, true>, a, sh, lds, stream);
+    return launch(fused_planned_kernel<XT, BITS, 4096, 4, 1024, false>, a, sh, lds, stream);
+}
+
+template <typename XT>
+int32_t dispatch_bits(const FusedArgs &a, int bits, const Shape &sh, size_t lds, hipStream_t stream)
+{
+    if (bits == 4) return dispatch<XT, 4>(a, sh, lds, stream);
+    if (bits == 6) return dispatch<XT, 6>(a, sh, lds, stream);
+    return dispatch<XT, 8>(a, sh, lds, stream);
+}
+
+} // namespace
+
+int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t bits, hipStream_t stream)
+{
+    const int n_chunks = (a.C + GROUP - 1) / GROUP;
+    const int units = n_chunks > a.n_groups_pad ? n_chunks : a.n_groups_pad;
+    if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
+    const Shape sh = pick_shape(units);
+    const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + (size_t)a.n_long * 8;
+    if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
+    if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);
+    return dispatch_bits<float>(a, bits, sh, lds, stream);
+}

@@ -133,23 +133,83 @@ const char *qllm_status_string(int32_t status)
     }
 }
 
-int32_t qllm_describe_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
-                               int64_t C_out, int32_t *group_desc)
+int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,
+                           int64_t C_out, int32_t *plan, int64_t *plan_len, int64_t *n_general)
 {
-    if (!row_ptr || !src || !scale || !group_desc) return QLLM_ERR_NULL;
-    if (C_out <= 0) return QLLM_ERR_SHAPE;
-    const int64_t n_groups = (C_out + QLLM_MAP_GROUP - 1) / QLLM_MAP_GROUP;
+    if (!row_ptr || !src || !scale || !plan_len || !n_general) return QLLM_ERR_NULL;
+    if (C_in <= 0 || C_out <= 0 || C_in > QLLM_MAX_CHANNELS || C_out > QLLM_MAX_CHANNELS) return QLLM_ERR_SHAPE;
+    const int64_t G = QLLM_MAP_GROUP;
+    const int64_t n_groups = (C_out + G - 1) / G, n_chunks = (C_in + G - 1) / G;
+    auto plain_source = [&](int64_t g) -> int32_t { // first source of a plain group, or -1
+        const int64_t c0 = g * G;
+        if (c0 + G > C_out) return -1;
+        const int32_t e0 = row_ptr[c0];
+        if (row_ptr[c0 + G] - e0 != G) return -1;
+        for (int j = 0; j < G; ++j)
+            if (row_ptr[c0 + j] != e0 + j || src[e0 + j] != src[e0] + j || scale[e0 + j] != 1.0f) return -1;
+        return src[e0] + G <= C_in && src[e0] >= 0 ? src[e0] : -1;
+    };
+    auto compact = [&](int64_t ch) { // one entry, or two entries of equal scale
+        const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
+        return n == 1 || (n == 2 && std::memcmp(&scale[e0], &scale[e0 + 1], 4) == 0);
+    };
+    int64_t general = 0, n_long = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
-        const int64_t c0 = g * QLLM_MAP_GROUP;
-        int32_t desc = -1;
-        if (c0 + QLLM_MAP_GROUP <= C_out) {
-            const int32_t e0 = row_ptr[c0];
-            bool plain = row_ptr[c0 + QLLM_MAP_GROUP] - e0 == QLLM_MAP_GROUP;
-            for (int j = 0; plain && j < QLLM_MAP_GROUP; ++j)
-                plain = row_ptr[c0 + j] == e0 + j && src[e0 + j] == src[e0] + j && scale[e0 + j] == 1.0f;
-            if (plain) desc = src[e0];
+        if (plain_source(g) >= 0) continue;
+        ++general;
+        for (int64_t ch = g * G; ch < std::min(C_out, (g + 1) * G); ++ch) {
+            if (row_ptr[ch + 1] <= row_ptr[ch]) return QLLM_ERR_MAP;
+            if (!compact(ch)) {
+                if (row_ptr[ch + 1] - row_ptr[ch] > 255) return QLLM_ERR_MAP; // the plan indexes at most 255 entries per row
+                n_long += row_ptr[ch + 1] - row_ptr[ch];
+            }
         }
-        group_desc[g] = desc;
+    }
+    if (n_long > 0xffffff) return QLLM_ERR_MAP;
+    *n_general = general;
+    const int64_t items_off = (8 + n_groups + 3) / 4 * 4; // items are read 8 bytes at a time
+    *plan_len = items_off + general * G * 2 + n_chunks + 2 * n_long;
+    if (!plan) return QLLM_OK;
+
+    int32_t *desc = plan + 8, *items = plan + items_off, *passes = items + general * G * 2;
+    std::fill(plan, plan + *plan_len, 0);
+    plan[0] = 0x514c4d50; plan[1] = 1; plan[2] = (int32_t)C_in; plan[3] = (int32_t)C_out;
+    plan[4] = (int32_t)n_groups; plan[5] = (int32_t)general; plan[6] = (int32_t)n_chunks; plan[7] = (int32_t)n_long;
+    std::fill(passes, passes + n_chunks, 0);
+    int32_t *longs = passes + n_chunks;
+    int64_t slot = 0, long_at = 0;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        const int32_t d = plain_source(g);
+        if (d >= 0) {
+            desc[g] = d;
+            for (int j = 0; j < G; ++j) passes[(d + j) / G] |= 1 << ((d + j) % G);
+            continue;
+        }
+        desc[g] = (int32_t)(-(slot + 1));
+        for (int k = 0; k < G; ++k) {
+            int32_t *it = items + (slot * G + k) * 2;
+            const int64_t ch = g * G + k;
+            it[0] = -1; // padding past C_out
+            it[1] = 0;
+            if (ch >= C_out) continue;
+            const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
+            if (n < 1) return QLLM_ERR_MAP;
+            for (int32_t e = e0; e < e0 + n; ++e)
+                if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
+            if (!compact(ch)) { // entries go to the table of long rows
+                it[0] = -2;
+                it[1] = (int32_t)((uint32_t)long_at | ((uint32_t)n << 24));
+                for (int32_t e = e0; e < e0 + n; ++e, ++long_at) {
+                    longs[2 * long_at] = src[e];
+                    std::memcpy(&longs[2 * long_at + 1], &scale[e], 4);
+                }
+                continue;
+            }
+            const uint32_t second = n == 2 ? (uint32_t)src[e0 + 1] : 0xffffu;
+            it[0] = (int32_t)((uint32_t)src[e0] | (second << 16));
+            std::memcpy(&it[1], &scale[e0], 4);
+        }
+        ++slot;
     }
     return QLLM_OK;
 }
@@ -169,8 +229,7 @@ int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const fl
 
 int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx,
                             const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
-                            float *scale, int32_t *group_desc, int64_t *C_out, int64_t *nnz,
-                            int32_t *num_split_out)
+                            float *scale, int64_t *C_out, int64_t *nnz, int32_t *num_split_out)
 {
     if (!chan_absmax || !C_out || !nnz) return QLLM_ERR_NULL;
     if (r > 0 && (!src_idx || !dst_idx)) return QLLM_ERR_NULL;
@@ -240,7 +299,6 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
     }
     row_ptr[ch] = (int32_t)e;
     if (ch != *C_out || e != *nnz) return QLLM_ERR_MAP;
-    if (group_desc) return qllm_describe_map_host(row_ptr, src, scale, *C_out, group_desc);
     return QLLM_OK;
 }
 

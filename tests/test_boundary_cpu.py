@@ -50,7 +50,7 @@ def test_packed_row_bytes_and_workspace():
 
 
 def _structs():
-    m = b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, None)
+    m = b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, None, 0, 0)
     q = b._QAct(0x1000, 0x1000, 0x1000, 0x1000)
     w = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000)
     return m, q, w
@@ -76,10 +76,10 @@ def test_fused_entry_point_rejects_bad_arguments_before_launching():
     assert call(ldx=63) == -2 and call(N=-1) == -2
     assert call(bits=5) == -3 and call(bits=2) == -3
     assert call(gamma=G + 4) == -6
-    bad_map = b._Map(65, 64, 64, 0x1000, 0x1000, 0x1000, None)      # C_in differs from C
+    bad_map = b._Map(65, 64, 64, 0x1000, 0x1000, 0x1000, None, 0, 0)      # C_in differs from C
     assert call(mp=bad_map) == -2
-    assert call(mp=b._Map(64, 64, 64, None, 0x1000, 0x1000, None)) == -1
-    assert call(mp=b._Map(64, 64, 10, 0x1000, 0x1000, 0x1000, None)) == -2
+    assert call(mp=b._Map(64, 64, 64, None, 0x1000, 0x1000, None, 0, 0)) == -1
+    assert call(mp=b._Map(64, 64, 10, 0x1000, 0x1000, 0x1000, None, 0, 0)) == -2
     assert call(qa=b._QAct(0x1008, 0x1000, 0x1000, 0x1000)) == -6
     assert call(qa=b._QAct(0x1000, None, 0x1000, 0x1000)) == -1
     assert call(N=0) == 0                                             # empty batch: nothing to do
@@ -144,21 +144,49 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
     assert np.array_equal(r["scale"], c.scale)
     assert b.qllm_check_map_host(r["row_ptr"], r["src"], r["scale"], C) == 0
-    # group descriptors: a non-negative entry promises 8 plain channels with consecutive sources
-    desc = r["group_desc"]
-    assert np.array_equal(desc, b.qllm_describe_map_host(c.row_ptr, c.src, c.scale))
-    assert (desc >= 0).sum() > 0.25 * desc.size
-    for g in np.nonzero(desc >= 0)[0]:
-        rows = slice(8 * g, 8 * g + 8)
-        e = c.row_ptr[rows]
+    # the plan: header, group descriptors, general-group entries, pass bits
+    plan, n_general = r["plan"], r["plan_general"]
+    n_groups, n_chunks = (c.K + 7) // 8, (C + 7) // 8
+    assert plan[:7].tolist() == [0x514C4D50, 1, C, c.K, n_groups, n_general, n_chunks]
+    desc = plan[8:8 + n_groups]
+    items_off = (8 + n_groups + 3) // 4 * 4
+    items = plan[items_off:items_off + 16 * n_general].reshape(n_general * 8, 2)
+    passes = plan[items_off + 16 * n_general:items_off + 16 * n_general + n_chunks]
+    longs = plan[items_off + 16 * n_general + n_chunks:].reshape(-1, 2)
+    assert longs.shape[0] == plan[7]
+    assert passes.size == n_chunks and (desc >= 0).sum() > 0.25 * desc.size and (desc < 0).sum() == n_general
+    expect_pass = np.zeros(n_chunks * 8, bool)
+    for g in np.nonzero(desc >= 0)[0]:       # a plain group: 8 single entries, scale 1, consecutive sources
+        e = c.row_ptr[8 * g:8 * g + 8]
         assert np.all(np.diff(c.row_ptr[8 * g:8 * g + 9]) == 1)
         assert np.array_equal(c.src[e], desc[g] + np.arange(8)) and np.all(c.scale[e] == 1.0)
-    for g in np.nonzero(desc < 0)[0]:
+        expect_pass[desc[g]:desc[g] + 8] = True
+    assert np.array_equal(np.unpackbits(passes.astype(np.uint8), bitorder="little"), expect_pass.astype(np.uint8))
+    assert sorted((-desc[desc < 0] - 1).tolist()) == list(range(n_general))
+    for g in np.nonzero(desc < 0)[0]:        # a general group: its entries, channel by channel
         lo, hi = 8 * g, min(8 * g + 8, c.K)
         e = c.row_ptr[lo:hi]
         plain = (hi - lo == 8 and np.all(np.diff(c.row_ptr[lo:hi + 1]) == 1) and np.all(c.scale[e] == 1.0)
                  and np.array_equal(c.src[e], c.src[e[0]] + np.arange(8)))
         assert not plain
+        for k in range(8):
+            it = items[(-desc[g] - 1) * 8 + k]
+            ch = lo + k
+            if ch >= c.K:
+                assert it[0] == -1
+                continue
+            e0, n = c.row_ptr[ch], c.row_ptr[ch + 1] - c.row_ptr[ch]
+            if n > 2:
+                first = int(it[1]) & 0xFFFFFF
+                assert it[0] == -2 and (int(it[1]) >> 24) & 0xFF == n
+                assert np.array_equal(longs[first:first + n, 0], c.src[e0:e0 + n])
+                assert np.array_equal(longs[first:first + n, 1].view(np.float32), c.scale[e0:e0 + n])
+                continue
+            second = c.src[e0 + 1] if n == 2 else 0xFFFF
+            assert int(it[0]) & 0xFFFFFFFF == int(c.src[e0]) | (int(second) << 16)
+            assert it[1:2].view(np.float32)[0] == c.scale[e0]
+            if n == 2:
+                assert c.scale[e0 + 1] == c.scale[e0]
     # weights: reassembled, quantized per output channel and packed by the library == the oracle's
     q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, w.w_bits)
     assert np.array_equal(q["scale"], c.aw) and np.array_equal(q["zero"], c.bw) and np.array_equal(q["colsum"], c.cs)

@@ -23,11 +23,13 @@ def b():
     return binding
 
 
-def device_map(b, c, use_desc=True):
+def device_map(b, c, use_plan=True):
     r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
     assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
     assert np.array_equal(r["scale"], c.scale)
-    return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C, r["group_desc"] if use_desc else None)
+    if use_plan:
+        return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C, r["plan"], r["plan_general"])
+    return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C)
 
 
 def device_weight(b, c, bits=None):
@@ -35,9 +37,9 @@ def device_weight(b, c, bits=None):
     return b.DeviceWeight(b.qllm_pack_codes_host(c.wcodes, bits), c.aw, c.bw, c.cs, c.K, bits)
 
 
-def run_fused(b, c, bits, use_desc=True, x=None):
+def run_fused(b, c, bits, use_plan=True, x=None):
     import torch
-    dm = device_map(b, c, use_desc)
+    dm = device_map(b, c, use_plan)
     xt = to_torch_x(c.x) if x is None else x
     g = None if c.gamma is None else torch.from_numpy(c.gamma).cuda()
     be = None if c.beta is None else torch.from_numpy(c.beta).cuda()
@@ -64,11 +66,11 @@ def check_fused(oracle, c, out, bits):
 
 # ---------------------------------------------------------------- fused kernel (steps a1..a4)
 
-@pytest.mark.parametrize("use_desc", [True, False])
-def test_fused_tiny_config(oracle, b, use_desc):
+@pytest.mark.parametrize("use_plan", [True, False])
+def test_fused_tiny_config(oracle, b, use_plan):
     c = make_case(oracle, wl.WORKLOADS["tiny"], real_weights=False)
     assert c.K == 512 and c.T.max() > 1
-    check_fused(oracle, c, run_fused(b, c, 4, use_desc), 4)
+    check_fused(oracle, c, run_fused(b, c, 4, use_plan), 4)
 
 
 SHAPES = [("tiny", 1, 8, 4), ("tiny", 3, 7, 4), ("tiny", 5, 100, 6), ("llama7b_qkv", 7, 1000, 4),
@@ -78,7 +80,8 @@ SHAPES = [("tiny", 1, 8, 4), ("tiny", 3, 7, 4), ("tiny", 5, 100, 6), ("llama7b_q
 
 @pytest.mark.parametrize("name,N,C,bits", SHAPES)
 @pytest.mark.parametrize("merge", [True, False])
-def test_fused_odd_shapes(oracle, b, name, N, C, bits, merge):
+@pytest.mark.parametrize("use_plan", [True, False])
+def test_fused_odd_shapes(oracle, b, name, N, C, bits, merge, use_plan):
     w = wl.WORKLOADS[name]
     rule = ("expand", 0.03) if C >= 64 else ("fixed", 1.0)
     if C * 1.03 > 32768 and not merge:
@@ -86,7 +89,7 @@ def test_fused_odd_shapes(oracle, b, name, N, C, bits, merge):
     c = make_case(oracle, w, N=N, C=C, O=8, merge=merge, real_weights=False, theta_rule=rule)
     if not merge and C >= 64:
         assert c.K > C                                  # disassembly only: more channels than it started with
-    check_fused(oracle, c, run_fused(b, c, bits), bits)
+    check_fused(oracle, c, run_fused(b, c, bits, use_plan), bits)
 
 
 @pytest.mark.parametrize("norm", ["none", "layer", "rms"])
