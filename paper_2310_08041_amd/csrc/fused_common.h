@@ -23,6 +23,7 @@ struct FusedArgs {
     int32_t N, C, norm, vec_ok;
     const float *gamma, *beta;
     float eps;
+    double inv_C; // 1 / C
     const int32_t *row_ptr, *src, *desc;
     const float *scale;
     const int32_t *items, *passes, *longs; // plan: entries of the general groups; per input chunk, which

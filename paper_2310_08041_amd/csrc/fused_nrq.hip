@@ -424,6 +424,7 @@ void fill_input(FusedArgs &a, const void *x, int32_t x_dtype, int64_t N, int64_t
     a.gamma = gamma;
     a.beta = beta;
     a.eps = eps;
+    a.inv_C = 1.0 / (double)C;
     a.S = (int32_t)((C + GROUP - 1) / GROUP);
 }
 

@@ -101,22 +101,79 @@ __device__ __forceinline__ float rsqrt_to_f32(double t)
     return (float)r;
 }
 
-__device__ __forceinline__ double wave_sum(double v)
+// ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips).
+// Four butterfly steps inside each row of 16 lanes, then the four row results are combined from
+// lanes 0, 16, 32, 48.  The order of the additions is fixed, so the result is reproducible.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    const uint64_t u = __double_as_longlong(v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, false);
+    return __longlong_as_double((long long)((uint64_t)lo | ((uint64_t)hi << 32)));
+}
+constexpr int DPP_XOR1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141; // lane i <-> 7 - i inside each half row
+constexpr int DPP_MIRROR = 0x140;      // lane i <-> 15 - i inside each row
+
+__device__ __forceinline__ float lane_f32(float v, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ double lane_f64(double v, int l)
+{
+    const uint64_t u = __double_as_longlong(v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), l);
+    return __longlong_as_double((long long)((uint64_t)lo | ((uint64_t)hi << 32)));
 }
 
-// Sum over the workgroup: shuffles, one LDS slot per wave, one barrier, then every lane adds the slots
-// in the same order.  The slot array is not reused before another barrier has passed.
-__device__ __forceinline__ double block_sum(double v, double *slots, int wave, int lane, int nwaves)
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v += dpp_f64<DPP_XOR1>(v);
+    v += dpp_f64<DPP_XOR2>(v);
+    v += dpp_f64<DPP_HALF_MIRROR>(v);
+    v += dpp_f64<DPP_MIRROR>(v);
+    return (lane_f64(v, 0) + lane_f64(v, 16)) + (lane_f64(v, 32) + lane_f64(v, 48));
+}
+__device__ __forceinline__ void wave_minmax(float &mn, float &mx)
+{
+    mn = fminf(mn, dpp_f32<DPP_XOR1>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR1>(mx));
+    mn = fminf(mn, dpp_f32<DPP_XOR2>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR2>(mx));
+    mn = fminf(mn, dpp_f32<DPP_HALF_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_HALF_MIRROR>(mx));
+    mn = fminf(mn, dpp_f32<DPP_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_MIRROR>(mx));
+    mn = fminf(fminf(lane_f32(mn, 0), lane_f32(mn, 16)), fminf(lane_f32(mn, 32), lane_f32(mn, 48)));
+    mx = fmaxf(fmaxf(lane_f32(mx, 0), lane_f32(mx, 16)), fmaxf(lane_f32(mx, 32), lane_f32(mx, 48)));
+}
+__device__ __forceinline__ int32_t wave_sum_i32(int32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, DPP_XOR1, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, DPP_XOR2, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, DPP_HALF_MIRROR, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, DPP_MIRROR, 0xf, 0xf, false);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+
+// Sum over the workgroup: one LDS slot per wave, one barrier, then lane w of every wave fetches slot w
+// (one LDS access instead of a dependent chain of them) and the wave adds the slots in slot order.
+// The slot array holds 16 entries, zero where there is no wave, and is not reused before another
+// barrier has passed.
+__device__ __forceinline__ double block_sum(double v, double *slots, int wave, int lane)
 {
     v = wave_sum(v);
     if (lane == 0) slots[wave] = v;
     __syncthreads();
-    double s = slots[0];
-    for (int w = 1; w < nwaves; ++w) s += slots[w];
+    const double mine = slots[lane & 15];
+    double s = lane_f64(mine, 0);
+#pragma unroll
+    for (int w = 1; w < 16; ++w) s += lane_f64(mine, w);
     return s;
 }
 
@@ -153,7 +210,7 @@ __device__ __noinline__ uint32_t slow_code(float x, float inv, int32_t beta, int
 // and stores.  Returns the sum of the codes.
 //
 // Fast form: b = bits(fma(x, inv, MAGIC)) is MAGIC_BITS + rne(x*inv); clamping b to [lo, lo + qmax]
-// with lo = MAGIC_BITS - beta leaves lo + code.  The 8 (or 4) values are packed with shift-and-add
+// with lo = MAGIC_BITS - beta (one median-of-three) leaves lo + code.  The 8 (or 4) values are packed with shift-and-add
 // in wrapping 32-bit arithmetic and the common offset lo * (1 + 2^BITS + 2^(2 BITS) + ...) is taken
 // off once.
 template <int BITS>
@@ -163,11 +220,12 @@ __device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, i
     constexpr int QMAX = (1 << BITS) - 1;
     uint32_t c[GROUP], bias = 0;
     if (fast) {
-        const int32_t lo = MAGIC_BITS - beta, hi = lo + QMAX; // |beta| < 2^22: no wrap
-        bias = (uint32_t)lo;
+        // floats in [2^23, 2^24) are integers and order like their bit patterns: clamp them as floats
+        const float lo = __int_as_float(MAGIC_BITS - beta), hi = __int_as_float(MAGIC_BITS - beta + QMAX);
+        bias = (uint32_t)(MAGIC_BITS - beta);
 #pragma unroll
         for (int k = 0; k < GROUP; ++k)
-            c[k] = (uint32_t)min(max(__float_as_int(__builtin_fmaf(val[k], inv, MAGIC)), lo), hi);
+            c[k] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(val[k], inv, MAGIC), lo, hi));
     } else {
 #pragma unroll 1
         for (int k = 0; k < GROUP; ++k) c[k] = slow_code(val[k], inv, beta, QMAX); // rare; kept out of line
@@ -219,7 +277,7 @@ __device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, i
 
 // GAM_REG: the lane's share of gamma stays in registers for the lifetime of the workgroup; otherwise it
 // is re-read (from L2) for every row, which frees 8 registers per chunk.
-template <typename XT, int BITS, int S_T, int ITERS, int NT_MAX, bool GAM_REG>
+template <typename XT, int BITS, int S_T, int ITERS, int NT_MAX, bool GAM_REG, bool LAYER>
 __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
 {
     extern __shared__ float lds[];
@@ -231,13 +289,13 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     __shared__ int32_t red_i[16];
     // bf16 rows are prefetched one row ahead; fp32 rows would need twice the registers and are not
     constexpr bool PREFETCH = sizeof(XT) == 2;
-    constexpr int ITEMS_REG = ITERS + 1; // general-group entries a lane keeps in registers
+    constexpr int ITEMS_REG = ITERS >= 4 ? ITERS : ITERS + 1; // general-group entries a lane keeps in registers
 
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nwaves = nt >> 6;
     const int n_chunks = (a.C + GROUP - 1) / GROUP;
     const int n_items = a.n_general * GROUP;
     const float inf = __builtin_inff();
-    const bool layer = a.norm == QLLM_NORM_LAYER;
+    constexpr bool layer = LAYER;
 
     // ---- per-lane state that outlives the rows
     float gam[GAM_REG ? ITERS : 1][GROUP];
@@ -251,24 +309,25 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
     }
     for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int2 *>(a.longs)[j];
+    if (tid < 16) { // reduction slots of waves that do not exist hold the identity
+        red_d[0][tid] = 0.0;
+        red_d[1][tid] = 0.0;
+        red_f[tid] = inf;
+        red_f[16 + tid] = -inf;
+        red_i[tid] = 0;
+    }
+    __syncthreads();
     int2 item[ITEMS_REG]; // {src0 | src1 << 16, scale}
 #pragma unroll
     for (int m = 0; m < ITEMS_REG; ++m) {
         const int j = tid + m * nt;
-        item[m] = j < n_items ? reinterpret_cast<const int2 *>(a.items)[j] : make_int2(-1, 0);
+        item[m] = j < n_items ? reinterpret_cast<const int2 *>(a.items)[j] : make_int2(-1, 0); // -1: nothing
     }
 
-    // value of one general-group channel from the staged row
-    auto item_value = [&](const int2 &e) -> float {
-        if (e.x != -2) {
-            const uint32_t s0 = (uint32_t)e.x & 0xffffu, s1 = (uint32_t)e.x >> 16;
-            const float sc = __int_as_float(e.y);
-            float acc = sc * ylds[(s0 & 7) * S_T + (s0 >> 3)];
-            if (s1 != 0xffffu) acc = acc + sc * ylds[(s1 & 7) * S_T + (s1 >> 3)];
-            return acc;
-        }
-        // any other row (more than two entries, or unequal scales): e.y = first | count << 24 into longs
-        const int first = e.y & 0xffffff, count = (uint32_t)e.y >> 24;
+    // value of a general-group channel whose row is neither of the two short forms:
+    // first | count << 24 into the table of long rows
+    auto long_value = [&](int32_t ref) -> float {
+        const int first = ref & 0xffffff, count = (uint32_t)ref >> 24;
         int2 le = longs[first];
         float acc = __int_as_float(le.y) * ylds[(le.x & 7) * S_T + (le.x >> 3)];
         for (int p = 1; p < count; ++p) {
@@ -320,7 +379,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
 
         // row statistics in fp64 (chunks past C hold zeros: load_raw pads)
         float mu = 0.0f, rstd = 1.0f;
-        if (a.norm == QLLM_NORM_RMS) {
+        if (!LAYER && a.norm == QLLM_NORM_RMS) {
             double q = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
@@ -334,9 +393,9 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                     }
                 }
             }
-            q = block_sum(q, red_d[0], wave, lane, nwaves);
-            rstd = rsqrt_to_f32(q / (double)a.C + (double)a.eps);
-        } else if (layer) {
+            q = block_sum(q, red_d[0], wave, lane);
+            rstd = rsqrt_to_f32(q * a.inv_C + (double)a.eps);
+        } else if constexpr (LAYER) {
             double s = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
@@ -347,8 +406,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                     for (int j = 0; j < GROUP; ++j) s += (double)v[j];
                 }
             }
-            s = block_sum(s, red_d[0], wave, lane, nwaves);
-            const double mu64 = s / (double)a.C;
+            s = block_sum(s, red_d[0], wave, lane);
+            const double mu64 = s * a.inv_C;
             double q = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
@@ -363,14 +422,14 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                     }
                 }
             }
-            q = block_sum(q, red_d[1], wave, lane, nwaves);
+            q = block_sum(q, red_d[1], wave, lane);
             mu = (float)mu64;
-            rstd = rsqrt_to_f32(q / (double)a.C + (double)a.eps);
+            rstd = rsqrt_to_f32(q * a.inv_C + (double)a.eps);
         }
 
         // ---- y into LDS; min/max over the channels that pass unscaled
         float mn = inf, mx = -inf;
-        const bool shift = layer && a.beta != nullptr;
+        const bool shift = LAYER && a.beta != nullptr;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int i = tid + it * nt;
@@ -384,10 +443,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
 #pragma unroll
                 for (int j = 0; j < GROUP; ++j) {
                     float t = y[j];
-                    if (layer) t = t - mu;
+                    if constexpr (LAYER) t = t - mu;
                     t = t * rstd;
                     t = t * g8[j];
-                    if (shift) t = t + a.beta[i * GROUP + j];
+                    if constexpr (LAYER) {
+                        if (shift) t = t + a.beta[i * GROUP + j];
+                    }
                     y[j] = t;
                     ylds[j * S_T + i] = t;
                 }
@@ -410,48 +471,49 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         __syncthreads(); // y complete
 
         // ---- steps a2 + a3 for the general groups: sub-channels (scale 1/T), merged channels
-        //      (scale 1/g each) and the plain channels that share a group of 8 with them
+        //      (scale 1/g each) and the plain channels that share a group of 8 with them.
+        //      All LDS reads are issued before any of them is used.
+        {
+            float y0[ITEMS_REG], y1[ITEMS_REG];
 #pragma unroll
-        for (int m = 0; m < ITEMS_REG; ++m) {
-            const int j = tid + m * nt;
-            if (j < n_items) {
-                float xv = 0.0f;
-                if (item[m].x != -1) {
-                    xv = item_value(item[m]);
-                    mn = fminf(mn, xv);
-                    mx = fmaxf(mx, xv);
-                }
-                exc[j] = xv;
+            for (int m = 0; m < ITEMS_REG; ++m) {
+                const bool marker = item[m].x == -1 || item[m].x == -2; // no source of its own: read channel 0
+                const uint32_t s0 = marker ? 0u : ((uint32_t)item[m].x & 0xffffu);
+                const uint32_t hi = (uint32_t)item[m].x >> 16;
+                const uint32_t s1 = (marker || hi == 0xffffu) ? s0 : hi;
+                y0[m] = ylds[(s0 & 7) * S_T + (s0 >> 3)];
+                y1[m] = ylds[(s1 & 7) * S_T + (s1 >> 3)];
             }
-        }
-        for (int j = tid + ITEMS_REG * nt; j < n_items; j += nt) {
-            const int2 e = reinterpret_cast<const int2 *>(a.items)[j];
-            float xv = 0.0f;
-            if (e.x != -1) {
-                xv = item_value(e);
-                mn = fminf(mn, xv);
-                mx = fmaxf(mx, xv);
+#pragma unroll
+            for (int m = 0; m < ITEMS_REG; ++m) {
+                const int j = tid + m * nt;
+                const float sc = __int_as_float(item[m].y);
+                float xv = sc * y0[m];
+                const float two = xv + sc * y1[m];
+                xv = ((uint32_t)item[m].x >> 16) != 0xffffu ? two : xv;
+                if (item[m].x == -2) xv = long_value(item[m].y);
+                const bool real = item[m].x != -1;
+                mn = fminf(mn, real ? xv : inf);
+                mx = fmaxf(mx, real ? xv : -inf);
+                if (j < n_items) exc[j] = real ? xv : 0.0f;
             }
-            exc[j] = xv;
         }
 
         // ---- per-token range (Eq. 2)
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            mn = fminf(mn, __shfl_xor(mn, o, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-        }
+        wave_minmax(mn, mx);
         if (lane == 0) {
             red_f[wave] = mn;
             red_f[16 + wave] = mx;
         }
         __syncthreads(); // also: exc complete
-        mn = red_f[0];
-        mx = red_f[16];
-        for (int w = 1; w < nwaves; ++w) {
-            mn = fminf(mn, red_f[w]);
-            mx = fmaxf(mx, red_f[16 + w]);
-        }
+        mn = red_f[lane & 15];
+        mx = red_f[16 + (lane & 15)];
+        mn = fminf(mn, dpp_f32<DPP_XOR1>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR1>(mx));
+        mn = fminf(mn, dpp_f32<DPP_XOR2>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR2>(mx));
+        mn = fminf(mn, dpp_f32<DPP_HALF_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_HALF_MIRROR>(mx));
+        mn = fminf(mn, dpp_f32<DPP_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_MIRROR>(mx));
+        mn = lane_f32(mn, 0);
+        mx = lane_f32(mx, 0);
         constexpr int QMAX = (1 << BITS) - 1;
         const float range = mx - mn;
         const float alpha = range > 0.0f ? range / (float)QMAX : 1.0f;
@@ -509,16 +571,20 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 sum += pack_store<BITS>(val, live, rot, fast, inv, beta, out_row, g);
             }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        sum = wave_sum_i32(sum);
         if (lane == 0) red_i[wave] = sum;
         __syncthreads(); // row done: LDS may be overwritten, red_i is complete
-        if (tid == 0) {
-            int32_t s = red_i[0];
-            for (int w = 1; w < nwaves; ++w) s += red_i[w];
+        if (wave == 0) {
+            int32_t s = red_i[lane & 15];
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR1, 0xf, 0xf, false);
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR2, 0xf, 0xf, false);
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_HALF_MIRROR, 0xf, 0xf, false);
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_MIRROR, 0xf, 0xf, false);
+            if (lane == 0) {
             a.alpha[row] = alpha;
             a.zero[row] = beta;
             a.rowsum[row] = s;
+            }
         }
     }
 }
@@ -581,21 +647,26 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
     return QLLM_OK;
 }
 
-template <typename XT, int BITS>
+template <typename XT, int BITS, bool LAYER>
 int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (sh.s_t == 256) return launch(fused_planned_kernel<XT, BITS, 256, 1, 256, true>, a, sh, lds, stream);
-    if (sh.s_t == 1024) return launch(fused_planned_kernel<XT, BITS, 1024, 2, 512, true>, a, sh, lds, stream);
-    if (sh.s_t == 2048) return launch(fused_planned_kernel<XT, BITS, 2048, 2, 1024, true>, a, sh, lds, stream);
-    return launch(fused_planned_kernel<XT, BITS, 4096, 4, 1024, false>, a, sh, lds, stream);
+    if (sh.s_t == 256) return launch(fused_planned_kernel<XT, BITS, 256, 1, 256, true, LAYER>, a, sh, lds, stream);
+    if (sh.s_t == 1024) return launch(fused_planned_kernel<XT, BITS, 1024, 2, 512, true, LAYER>, a, sh, lds, stream);
+    if (sh.s_t == 2048) return launch(fused_planned_kernel<XT, BITS, 2048, 2, 1024, true, LAYER>, a, sh, lds, stream);
+    return launch(fused_planned_kernel<XT, BITS, 4096, 4, 1024, true, LAYER>, a, sh, lds, stream);
 }
 
 template <typename XT>
 int32_t dispatch_bits(const FusedArgs &a, int bits, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (bits == 4) return dispatch<XT, 4>(a, sh, lds, stream);
-    if (bits == 6) return dispatch<XT, 6>(a, sh, lds, stream);
-    return dispatch<XT, 8>(a, sh, lds, stream);
+    if (a.norm == QLLM_NORM_LAYER) {
+        if (bits == 4) return dispatch<XT, 4, true>(a, sh, lds, stream);
+        if (bits == 6) return dispatch<XT, 6, true>(a, sh, lds, stream);
+        return dispatch<XT, 8, true>(a, sh, lds, stream);
+    }
+    if (bits == 4) return dispatch<XT, 4, false>(a, sh, lds, stream);
+    if (bits == 6) return dispatch<XT, 6, false>(a, sh, lds, stream);
+    return dispatch<XT, 8, false>(a, sh, lds, stream);
 }
 
 } // namespace
@@ -608,6 +679,8 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     const Shape sh = pick_shape(units);
     const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + (size_t)a.n_long * 8;
     if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
+    const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
+    if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // general-group entries live in registers
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);
     return dispatch_bits<float>(a, bits, sh, lds, stream);
 }
