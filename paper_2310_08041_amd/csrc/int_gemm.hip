@@ -45,10 +45,11 @@ struct Unit {
     uint4 r[BITS / 2]; // 64 codes: 32 / 48 / 64 bytes
 };
 
+// unit number `unit` (64 codes each) of a packed row
 template <int BITS>
-__device__ __forceinline__ void load_unit(Unit<BITS> &u, const uint8_t *row, int kt, int ku)
+__device__ __forceinline__ void load_unit(Unit<BITS> &u, const uint8_t *row, int unit)
 {
-    const uint4 *p = reinterpret_cast<const uint4 *>(row + ((int64_t)kt * KT + ku * UNIT) * BITS / 8);
+    const uint4 *p = reinterpret_cast<const uint4 *>(row + (int64_t)unit * (UNIT * BITS / 8));
 #pragma unroll
     for (int i = 0; i < BITS / 2; ++i) u.r[i] = p[i];
 }
@@ -68,15 +69,25 @@ __device__ __forceinline__ uint32_t expand6(uint32_t t)
     return (t & 0x3fu) | ((t << 2) & 0x3f00u) | ((t << 4) & 0x3f0000u) | ((t << 6) & 0x3f000000u);
 }
 
-// Expands one unit to 64 bytes and stores it as four 16-byte chunks of LDS row `row`.
-template <int BITS>
+// Expands one unit to 64 bytes and stores it as four 16-byte chunks of LDS row `row` (ROWB bytes per
+// row, chunks XOR-swizzled by row).  PERM: both operands are 4-bit, so the order of the codes inside a
+// unit is free as long as both sides use the same one; even codes then odd codes of each dword is
+// the cheapest (two masks and a shift instead of two more byte permutes).
+template <int BITS, int ROWB, bool PERM>
 __device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, int row, int ku)
 {
     uint32_t d[16];
     if constexpr (BITS == 4) {
         const uint32_t w[8] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y, u.r[1].z, u.r[1].w};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) expand4(w[i], d[2 * i], d[2 * i + 1]);
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (PERM) {
+                d[2 * i] = w[i] & 0x0f0f0f0fu;
+                d[2 * i + 1] = (w[i] >> 4) & 0x0f0f0f0fu;
+            } else {
+                expand4(w[i], d[2 * i], d[2 * i + 1]);
+            }
+        }
     } else if constexpr (BITS == 6) {
         const uint32_t w[12] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y,
                                 u.r[1].z, u.r[1].w, u.r[2].x, u.r[2].y, u.r[2].z, u.r[2].w};
@@ -97,14 +108,15 @@ __device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, i
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         const int chunk = (ku * 4 + c) ^ (row & 7);
-        *reinterpret_cast<uint4 *>(tile + row * ROW_LDS + chunk * 16) =
+        *reinterpret_cast<uint4 *>(tile + row * ROWB + chunk * 16) =
             make_uint4(d[4 * c], d[4 * c + 1], d[4 * c + 2], d[4 * c + 3]);
     }
 }
 
+template <int ROWB>
 __device__ __forceinline__ v4i load_frag(const uint8_t *tile, int row, int chunk)
 {
-    return *reinterpret_cast<const v4i *>(tile + row * ROW_LDS + ((chunk ^ (row & 7)) * 16));
+    return *reinterpret_cast<const v4i *>(tile + row * ROWB + ((chunk ^ (row & 7)) * 16));
 }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -113,6 +125,70 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+struct RowTerms {
+    int64_t bx, rs;
+    float ax;
+};
+
+// Dequantising epilogue for the 4 consecutive output features ob..ob+3 of token n that one lane holds
+// after a 16x16 matrix-core tile: corrects the 8-bit offset, forms the exact int64 bracket, scales,
+// rounds and stores (16 bytes per lane for fp32, 8 for bf16).
+template <int ABITS, int WBITS, typename YT>
+__device__ __forceinline__ void finish_tile(const GemmArgs &g, const v4i &acc, const RowTerms &rt, int n, int ob)
+{
+    constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
+    float out[4];
+    int32_t raw[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int o = min(ob + r, g.O - 1);
+        const int64_t cs = g.cs[o], bw = g.bw[o];
+        int64_t a = (int64_t)acc[r];
+        a += 128 * SW * rt.rs + 128 * SA * cs - (int64_t)(16384 * SA * SW) * g.Kpad;
+        raw[r] = (int32_t)a;
+        const int64_t bracket = a - rt.bx * cs - bw * rt.rs + (int64_t)g.K * rt.bx * bw;
+        float v = (float)bracket;
+        v = v * rt.ax;
+        v = v * g.aw[o];
+        out[r] = v;
+    }
+    if (ob + 3 < g.O) {
+        if constexpr (sizeof(YT) == 4) {
+            float *yp = reinterpret_cast<float *>(g.y) + (int64_t)n * g.ldy + ob;
+            if ((reinterpret_cast<uintptr_t>(yp) & 15u) == 0) {
+                *reinterpret_cast<float4 *>(yp) = make_float4(out[0], out[1], out[2], out[3]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) yp[r] = out[r];
+            }
+        } else {
+            uint16_t *yp = reinterpret_cast<uint16_t *>(g.y) + (int64_t)n * g.ldy + ob;
+            const uint32_t p0 = f32_to_bf16_rne(out[0]) | ((uint32_t)f32_to_bf16_rne(out[1]) << 16);
+            const uint32_t p1 = f32_to_bf16_rne(out[2]) | ((uint32_t)f32_to_bf16_rne(out[3]) << 16);
+            if ((reinterpret_cast<uintptr_t>(yp) & 7u) == 0) {
+                *reinterpret_cast<uint2 *>(yp) = make_uint2(p0, p1);
+            } else {
+                yp[0] = (uint16_t)p0; yp[1] = (uint16_t)(p0 >> 16);
+                yp[2] = (uint16_t)p1; yp[3] = (uint16_t)(p1 >> 16);
+            }
+        }
+        if (g.acc_dump) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (ob + r < g.O) {
+                if constexpr (sizeof(YT) == 4)
+                    reinterpret_cast<float *>(g.y)[(int64_t)n * g.ldy + ob + r] = out[r];
+                else
+                    reinterpret_cast<uint16_t *>(g.y)[(int64_t)n * g.ldy + ob + r] = f32_to_bf16_rne(out[r]);
+                if (g.acc_dump) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
+            }
+    }
 }
 
 template <int ABITS, int WBITS, typename YT>
@@ -147,22 +223,22 @@ __global__ __launch_bounds__(THREADS) void int_gemm_kernel(const GemmArgs g)
     const int n_kt = g.Kpad / KT;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        load_unit<ABITS>(ua[h], a_row[h], 0, f_ku);
-        load_unit<WBITS>(uw[h], w_row[h], 0, f_ku);
+        load_unit<ABITS>(ua[h], a_row[h], f_ku);
+        load_unit<WBITS>(uw[h], w_row[h], f_ku);
     }
 
     for (int kt = 0; kt < n_kt; ++kt) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            store_unit<ABITS>(ua[h], lds_a, f_row + 64 * h, f_ku);
-            store_unit<WBITS>(uw[h], lds_w, f_row + 64 * h, f_ku);
+            store_unit<ABITS, ROW_LDS, ABITS == 4 && WBITS == 4>(ua[h], lds_a, f_row + 64 * h, f_ku);
+            store_unit<WBITS, ROW_LDS, ABITS == 4 && WBITS == 4>(uw[h], lds_w, f_row + 64 * h, f_ku);
         }
         __syncthreads();
         if (kt + 1 < n_kt) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                load_unit<ABITS>(ua[h], a_row[h], kt + 1, f_ku);
-                load_unit<WBITS>(uw[h], w_row[h], kt + 1, f_ku);
+                load_unit<ABITS>(ua[h], a_row[h], (kt + 1) * (KT / UNIT) + f_ku);
+                load_unit<WBITS>(uw[h], w_row[h], (kt + 1) * (KT / UNIT) + f_ku);
             }
         }
 #pragma unroll
@@ -170,9 +246,9 @@ __global__ __launch_bounds__(THREADS) void int_gemm_kernel(const GemmArgs g)
             const int chunk = ks * 4 + (lane >> 4);
             v4i fa[4], fw[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) fa[i] = load_frag(lds_a, wm * 64 + i * 16 + (lane & 15), chunk);
+            for (int i = 0; i < 4; ++i) fa[i] = load_frag<ROW_LDS>(lds_a, wm * 64 + i * 16 + (lane & 15), chunk);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) fw[j] = load_frag(lds_w, wn * 64 + j * 16 + (lane & 15), chunk);
+            for (int j = 0; j < 4; ++j) fw[j] = load_frag<ROW_LDS>(lds_w, wn * 64 + j * 16 + (lane & 15), chunk);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -186,85 +262,130 @@ __global__ __launch_bounds__(THREADS) void int_gemm_kernel(const GemmArgs g)
 
     // ---- epilogue.  acc[i][j][r]: token n0 + wm*64 + i*16 + (lane & 15),
     //                               feature o0 + wn*64 + j*16 + 4*(lane >> 4) + r
-    constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int n = n0 + wm * 64 + i * 16 + (lane & 15);
         if (n >= g.N) continue;
-        const int64_t bx = g.bx[n], rs = g.rs[n];
-        const float ax = g.ax[n];
+        const RowTerms rt{g.bx[n], g.rs[n], g.ax[n]};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int ob = o0 + wn * 64 + j * 16 + 4 * (lane >> 4);
-            float out[4];
-            int32_t raw[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int o = min(ob + r, g.O - 1);
-                const int64_t cs = g.cs[o], bw = g.bw[o];
-                int64_t a = (int64_t)acc[i][j][r];
-                a += 128 * SW * rs + 128 * SA * cs - (int64_t)(16384 * SA * SW) * g.Kpad;
-                raw[r] = (int32_t)a;
-                const int64_t bracket = a - bx * cs - bw * rs + (int64_t)g.K * bx * bw;
-                float v = (float)bracket;
-                v = v * ax;
-                v = v * g.aw[o];
-                out[r] = v;
-            }
-            if (ob + 3 < g.O) {
-                if constexpr (sizeof(YT) == 4) {
-                    float *yp = reinterpret_cast<float *>(g.y) + (int64_t)n * g.ldy + ob;
-                    if ((reinterpret_cast<uintptr_t>(yp) & 15u) == 0) {
-                        *reinterpret_cast<float4 *>(yp) = make_float4(out[0], out[1], out[2], out[3]);
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) yp[r] = out[r];
-                    }
-                } else {
-                    uint16_t *yp = reinterpret_cast<uint16_t *>(g.y) + (int64_t)n * g.ldy + ob;
-                    const uint32_t p0 = f32_to_bf16_rne(out[0]) | ((uint32_t)f32_to_bf16_rne(out[1]) << 16);
-                    const uint32_t p1 = f32_to_bf16_rne(out[2]) | ((uint32_t)f32_to_bf16_rne(out[3]) << 16);
-                    if ((reinterpret_cast<uintptr_t>(yp) & 7u) == 0) {
-                        *reinterpret_cast<uint2 *>(yp) = make_uint2(p0, p1);
-                    } else {
-                        yp[0] = (uint16_t)p0; yp[1] = (uint16_t)(p0 >> 16);
-                        yp[2] = (uint16_t)p1; yp[3] = (uint16_t)(p1 >> 16);
-                    }
-                }
-                if (g.acc_dump) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (ob + r < g.O) {
-                        if constexpr (sizeof(YT) == 4)
-                            reinterpret_cast<float *>(g.y)[(int64_t)n * g.ldy + ob + r] = out[r];
-                        else
-                            reinterpret_cast<uint16_t *>(g.y)[(int64_t)n * g.ldy + ob + r] = f32_to_bf16_rne(out[r]);
-                        if (g.acc_dump) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
-                    }
-            }
-        }
+        for (int j = 0; j < 4; ++j)
+            finish_tile<ABITS, WBITS, YT>(g, acc[i][j], rt, n, o0 + wn * 64 + j * 16 + 4 * (lane >> 4));
     }
 }
 
-template <int ABITS, int WBITS>
-int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
+// ---- the large-tile kernel: 512 lanes (8 waves, 2 x 4), a 256 x 256 tile of Y, K-tiles of 128 codes,
+// two LDS buffers.  While the matrix cores work through buffer `cur`, the lanes expand the next
+// K-tile (fetched one iteration earlier) into the other buffer and fetch the one after it: one
+// barrier per K-tile, and the expansion overlaps the multiplication of the other wave on the SIMD.
+constexpr int LBM = 256, LBN = 256, LKT = 128, LTHREADS = 512, LROWB = LKT; // one byte per code in LDS
+constexpr int LBUF = (LBM + LBN) * LROWB;                                   // 64 KB per buffer
+
+template <int ABITS, int WBITS, typename YT>
+__global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g)
 {
-    const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr bool PERM = ABITS == 4 && WBITS == 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3; // wave tile: 128 tokens x 64 features
+    const int n0 = blockIdx.y * LBM, o0 = blockIdx.x * LBN;
+
+    // fetch assignment: one unit of each operand per lane and K-tile (unit = row * 2 + ku)
+    const int f_row = tid >> 1, f_ku = tid & 1;
+    const uint8_t *a_row = g.a_codes + (int64_t)min(n0 + f_row, g.N - 1) * g.a_row_bytes; // past the edge:
+    const uint8_t *w_row = g.w_codes + (int64_t)min(o0 + f_row, g.O - 1) * g.w_row_bytes; // re-read the last row
+
+    v4i acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+    Unit<ABITS> ua;
+    Unit<WBITS> uw;
+    const int n_kt = g.Kpad / LKT;
+    load_unit<ABITS>(ua, a_row, f_ku);
+    load_unit<WBITS>(uw, w_row, f_ku);
+    store_unit<ABITS, LROWB, PERM>(ua, lds, f_row, f_ku);
+    store_unit<WBITS, LROWB, PERM>(uw, lds + LBM * LROWB, f_row, f_ku);
+    if (n_kt > 1) {
+        load_unit<ABITS>(ua, a_row, 2 + f_ku);
+        load_unit<WBITS>(uw, w_row, 2 + f_ku);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < n_kt; ++kt) {
+        uint8_t *cur = lds + (kt & 1) * LBUF, *nxt = lds + ((kt + 1) & 1) * LBUF;
+        if (kt + 1 < n_kt) { // nobody reads `nxt` any more: the barrier that ended iteration kt-1 saw to that
+            store_unit<ABITS, LROWB, PERM>(ua, nxt, f_row, f_ku);
+            store_unit<WBITS, LROWB, PERM>(uw, nxt + LBM * LROWB, f_row, f_ku);
+        }
+        if (kt + 2 < n_kt) {
+            load_unit<ABITS>(ua, a_row, (kt + 2) * 2 + f_ku);
+            load_unit<WBITS>(uw, w_row, (kt + 2) * 2 + f_ku);
+        }
+        const uint8_t *ta = cur, *tw = cur + LBM * LROWB;
+#pragma unroll
+        for (int ks = 0; ks < LKT / UNIT; ++ks) {
+            const int chunk = ks * 4 + (lane >> 4);
+            v4i fa[8], fw[4];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) fa[i] = load_frag<LROWB>(ta, wm * 128 + i * 16 + (lane & 15), chunk);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fw[j] = load_frag<LROWB>(tw, wn * 64 + j * 16 + (lane & 15), chunk);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int n = n0 + wm * 128 + i * 16 + (lane & 15);
+        if (n >= g.N) continue;
+        const RowTerms rt{g.bx[n], g.rs[n], g.ax[n]};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            finish_tile<ABITS, WBITS, YT>(g, acc[i][j], rt, n, o0 + wn * 64 + j * 16 + 4 * (lane >> 4));
+    }
+}
+
+template <typename K>
+int32_t launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const GemmArgs &g, hipStream_t stream)
+{
+    if (lds > 48 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            qllm_note_hip_error("int gemm: raising the LDS limit", hipGetErrorName(e));
+            return QLLM_ERR_HIP;
+        }
+    }
     (void)hipGetLastError(); // drop any stale error of the calling thread: only this launch is judged
-    if (y_dtype == QLLM_F32)
-        hipLaunchKernelGGL((int_gemm_kernel<ABITS, WBITS, float>), grid, dim3(THREADS), 0, stream, g);
-    else
-        hipLaunchKernelGGL((int_gemm_kernel<ABITS, WBITS, uint16_t>), grid, dim3(THREADS), 0, stream, g);
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         qllm_note_hip_error("int gemm: launch", hipGetErrorName(e));
         return QLLM_ERR_HIP;
     }
     return QLLM_OK;
+}
+
+template <int ABITS, int WBITS>
+int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
+{
+    if (g.N > 128) { // enough tokens to fill 256-row tiles
+        const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
+        if (y_dtype == QLLM_F32)
+            return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
+        return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, uint16_t>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
+    }
+    const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
+    if (y_dtype == QLLM_F32) return launch_kernel(int_gemm_kernel<ABITS, WBITS, float>, grid, dim3(THREADS), 0, g, stream);
+    return launch_kernel(int_gemm_kernel<ABITS, WBITS, uint16_t>, grid, dim3(THREADS), 0, g, stream);
 }
 
 } // namespace
