@@ -35,6 +35,7 @@ struct GemmArgs {
     const float *ax, *aw;
     const int32_t *bx, *bw, *rs, *cs;
     int32_t N, O, K, Kpad;
+    int32_t small_zero; // zero-points below this (in magnitude) keep every epilogue term inside 24 / 32 bits; 0: never
     void *y;
     int64_t ldy;
     int32_t *acc_dump;
@@ -127,33 +128,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-struct RowTerms {
-    int64_t bx, rs;
-    float ax;
-};
-
-// Dequantising epilogue for the 4 consecutive output features ob..ob+3 of token n that one lane holds
-// after a 16x16 matrix-core tile: corrects the 8-bit offset, forms the exact int64 bracket, scales,
-// rounds and stores (16 bytes per lane for fp32, 8 for bf16).
-template <int ABITS, int WBITS, typename YT>
-__device__ __forceinline__ void finish_tile(const GemmArgs &g, const v4i &acc, const RowTerms &rt, int n, int ob)
+// Stores 4 consecutive output features of one token (16 bytes per lane for fp32, 8 for bf16) and,
+// if asked for, the raw accumulators.
+template <typename YT>
+__device__ __forceinline__ void store4(const GemmArgs &g, const float *out, const int32_t *raw, int n, int ob)
 {
-    constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
-    float out[4];
-    int32_t raw[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int o = min(ob + r, g.O - 1);
-        const int64_t cs = g.cs[o], bw = g.bw[o];
-        int64_t a = (int64_t)acc[r];
-        a += 128 * SW * rt.rs + 128 * SA * cs - (int64_t)(16384 * SA * SW) * g.Kpad;
-        raw[r] = (int32_t)a;
-        const int64_t bracket = a - rt.bx * cs - bw * rt.rs + (int64_t)g.K * rt.bx * bw;
-        float v = (float)bracket;
-        v = v * rt.ax;
-        v = v * g.aw[o];
-        out[r] = v;
-    }
     if (ob + 3 < g.O) {
         if constexpr (sizeof(YT) == 4) {
             float *yp = reinterpret_cast<float *>(g.y) + (int64_t)n * g.ldy + ob;
@@ -188,6 +167,68 @@ __device__ __forceinline__ void finish_tile(const GemmArgs &g, const v4i &acc, c
                     reinterpret_cast<uint16_t *>(g.y)[(int64_t)n * g.ldy + ob + r] = f32_to_bf16_rne(out[r]);
                 if (g.acc_dump) g.acc_dump[(int64_t)n * g.O + ob + r] = raw[r];
             }
+    }
+}
+
+// Dequantising epilogue of one wave tile: NI x NJ matrix-core tiles of 16 x 16; the lane holds, for
+// tile (i, j), token n_base + 16 i + (lane & 15) and features o_base + 16 j + 4 (lane >> 4) + 0..3.
+//   bracket = acc - bx*cs - bw*rs + K*bx*bw       (exact integer)
+//   Y       = ((float)bracket * ax) * aw
+// When both zero-points are small (the usual case: |beta| < g.small_zero, a bound the launcher derives
+// from K and the bit widths) every factor fits 24 bits and every sum 32 bits, and the bracket costs
+// three full-rate multiply-adds; otherwise it is formed in 64-bit arithmetic.
+template <int ABITS, int WBITS, typename YT, int NI, int NJ>
+__device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const v4i (&acc)[NI][NJ], int n_base, int o_base,
+                                                 int lane)
+{
+    constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
+    int32_t cs[NJ][4], bw[NJ][4];
+    float aw[NJ][4];
+    bool cols_small = true;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int o = min(o_base + j * 16 + 4 * (lane >> 4) + r, g.O - 1);
+            cs[j][r] = g.cs[o];
+            bw[j][r] = g.bw[o];
+            aw[j][r] = g.aw[o];
+            cols_small = cols_small && abs(bw[j][r]) < g.small_zero;
+        }
+    const int32_t k_off = 16384 * SA * SW * g.Kpad;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int n = n_base + i * 16 + (lane & 15);
+        if (n >= g.N) continue;
+        const int32_t bx = g.bx[n], rs = g.rs[n];
+        const float ax = g.ax[n];
+        const bool small = cols_small && abs(bx) < g.small_zero;
+        const int32_t kbx = g.K * bx; // only used when small
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            float out[4];
+            int32_t raw[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // the true accumulator fits int32 (checked by the launcher), so wrapping sums are exact
+                raw[r] = acc[i][j][r] + 128 * SW * rs + 128 * SA * cs[j][r] - k_off;
+                float v;
+                if (small) {
+                    int32_t t = raw[r] - __mul24(bx, cs[j][r]);
+                    t -= __mul24(bw[j][r], rs);
+                    t += __mul24(kbx, bw[j][r]);
+                    v = (float)t;
+                } else {
+                    const int64_t t = (int64_t)raw[r] - (int64_t)bx * cs[j][r] - (int64_t)bw[j][r] * rs +
+                                      (int64_t)g.K * bx * bw[j][r];
+                    v = (float)t;
+                }
+                v = v * ax;
+                v = v * aw[j][r];
+                out[r] = v;
+            }
+            store4<YT>(g, out, raw, n, o_base + j * 16 + 4 * (lane >> 4));
+        }
     }
 }
 
@@ -262,15 +303,7 @@ __global__ __launch_bounds__(THREADS) void int_gemm_kernel(const GemmArgs g)
 
     // ---- epilogue.  acc[i][j][r]: token n0 + wm*64 + i*16 + (lane & 15),
     //                               feature o0 + wn*64 + j*16 + 4*(lane >> 4) + r
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int n = n0 + wm * 64 + i * 16 + (lane & 15);
-        if (n >= g.N) continue;
-        const RowTerms rt{g.bx[n], g.rs[n], g.ax[n]};
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            finish_tile<ABITS, WBITS, YT>(g, acc[i][j], rt, n, o0 + wn * 64 + j * 16 + 4 * (lane >> 4));
-    }
+    finish_wave_tile<ABITS, WBITS, YT, 4, 4>(g, acc, n0 + wm * 64, o0 + wn * 64, lane);
 }
 
 // ---- the large-tile kernel: 512 lanes (8 waves, 2 x 4), a 256 x 256 tile of Y, K-tiles of 128 codes,
@@ -341,15 +374,7 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
         __syncthreads();
     }
 
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int n = n0 + wm * 128 + i * 16 + (lane & 15);
-        if (n >= g.N) continue;
-        const RowTerms rt{g.bx[n], g.rs[n], g.ax[n]};
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            finish_tile<ABITS, WBITS, YT>(g, acc[i][j], rt, n, o0 + wn * 64 + j * 16 + 4 * (lane >> 4));
-    }
+    finish_wave_tile<ABITS, WBITS, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
 }
 
 template <typename K>
@@ -386,6 +411,18 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
     const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
     if (y_dtype == QLLM_F32) return launch_kernel(int_gemm_kernel<ABITS, WBITS, float>, grid, dim3(THREADS), 0, g, stream);
     return launch_kernel(int_gemm_kernel<ABITS, WBITS, uint16_t>, grid, dim3(THREADS), 0, g, stream);
+}
+
+// Largest L such that |beta_x| < L and |beta_w| < L keep the epilogue inside narrow integers:
+// row and column sums below 2^23, K*beta_x below 2^23, and each of the three products below 2^29,
+// so that their sum with the accumulator stays below 2^31.
+int32_t small_zero_bound(int64_t K, int32_t a_bits, int32_t w_bits)
+{
+    const int64_t qa = (1 << a_bits) - 1, qw = (1 << w_bits) - 1, qm = qa > qw ? qa : qw;
+    if (qm * K >= (1 << 23)) return 0;
+    int64_t L = (1ll << 29) / (qm * K);
+    while (L > 0 && (K * L >= (1 << 23) || K * L * L >= (1ll << 29))) L /= 2;
+    return (int32_t)(L > (1 << 20) ? (1 << 20) : L);
 }
 
 } // namespace
@@ -429,6 +466,7 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     g.N = (int32_t)N; g.O = (int32_t)w->O; g.K = (int32_t)w->K;
     g.Kpad = (int32_t)((w->K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD);
     g.y = y; g.ldy = ldy; g.acc_dump = acc_dump;
+    g.small_zero = small_zero_bound(w->K, a_bits, wb);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (a_bits == 4) return launch<4, 4>(g, y_dtype, stream);
     if (a_bits == 6) return launch<6, 6>(g, y_dtype, stream);
