@@ -186,13 +186,15 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
 /* Indexes a CSR map for the fused kernel (see qllm_map.plan).  Call once with plan == NULL to get
  * *plan_len (int32 words) and *n_general, then with plan pointing at that many words.  The plan
  * depends only on the map; upload it next to the CSR arrays.  Layout (int32 words):
- *   [0..7]   header: magic, version, C_in, C_out, n_groups = ceil(C_out/8), n_general, n_chunks = ceil(C_in/8), n_long
- *   desc     [n_groups]: d >= 0: the 8 channels of the group are single-entry with scale exactly 1 and
- *            sources d, d+1, ..., d+7; d < 0: general group number -(d+1)
+ *   [0..7]   header: magic, version, C_in, C_out, n_work = groups of 8 output channels including the zero
+ *            padding to 256 codes, n_general, n_chunks = ceil(C_in/8), n_long
+ *   work     [n_work]: kind << 28 | group << 15 | d.  kind 0: the 8 channels of the group are single-entry
+ *            with scale exactly 1 and sources d, d+1, ..., d+7; kind 1: general group number d; kind 2:
+ *            padding.  Sorted by kind, plain groups by d & 7, then by group
  *   items    (starting at the next multiple of 4 words) [n_general * 8][2]: for channel k of a general
  *            group {src0 | src1 << 16, scale}: one entry (src1 = 0xffff) or two entries of equal scale;
- *            {-1, 0}: padding past C_out; {-2, first | count << 24}: any other row (at most 255
- *            entries), its entries are longs[first .. first + count)
+ *            {-2, first | count << 24}: any other row (at most 255 entries), its entries are
+ *            longs[first .. first + count); channels past C_out repeat the group's first channel
  *   passes   [n_chunks]: bit j set: input channel 8*chunk + j is a source of some plain group
  *   longs    [n_long][2]: {src, scale} entries of the rows that are neither of the two short forms
  */

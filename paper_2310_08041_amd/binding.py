@@ -12,7 +12,7 @@ import torch  # noqa: F401  -- first: libqllm.so must bind to the HIP runtime to
 #                              two HIP runtimes in one process leave the second without a device
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqllm.so")
+LIB_PATH = os.environ.get("QLLM_LIB", os.path.join(_HERE, "libqllm.so"))  # override: a library built elsewhere
 
 F32, BF16 = 0, 1
 NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2

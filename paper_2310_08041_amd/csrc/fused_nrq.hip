@@ -455,7 +455,7 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
         if (map->plan_general < 0 || (reinterpret_cast<uintptr_t>(map->plan) & 15u)) return QLLM_ERR_ALIGN;
         a.n_general = (int32_t)map->plan_general;
         a.desc = map->plan + 8;
-        a.items = map->plan + (8 + (map->C_out + GROUP - 1) / GROUP + 3) / 4 * 4;
+        a.items = map->plan + (8 + (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP + 3) / 4 * 4;
         a.passes = a.items + (int64_t)a.n_general * GROUP * 2;
         a.longs = a.passes + (C + GROUP - 1) / GROUP;
         const int64_t n_long = (map->plan_len - (a.longs - map->plan)) / 2;
@@ -475,6 +475,7 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     if (map->plan) {
         rc = qllm_launch_fused_planned(a, x_dtype, bits, stream);
         if (rc != QLLM_ERR_WORKSPACE) return rc; // does not fit on chip: the plain kernel below handles it
+        a.desc = nullptr;                        // ... by walking the CSR (the plan's work list is not for it)
     }
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, max_units, stream);
     return dispatch_bits<float>(a, bits, max_units, stream);

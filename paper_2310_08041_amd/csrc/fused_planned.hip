@@ -34,8 +34,10 @@ using namespace qllm_detail;
 
 namespace {
 
-constexpr int32_t DESC_PAD = INT32_MIN; // group past C_out that exists only as zero padding
-constexpr int32_t DESC_NONE = INT32_MIN + 1;
+// work-list entries (see qllm_plan_map_host): kind << 28 | group << 15 | d
+constexpr int KIND_PLAIN = 0, KIND_GENERAL = 1, KIND_PAD = 2, KIND_NONE = 3;
+constexpr int32_t WORK_NONE = KIND_NONE << 28;
+constexpr int32_t ITEM_LONG = -2; // first word of a plan item whose entries are in the table of long rows
 
 template <typename XT>
 struct Raw; // 8 input elements as they sit in memory
@@ -283,7 +285,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     extern __shared__ float lds[];
     float *ylds = lds;              // [8 * S_T]        y, transposed by 8
     float *exc = lds + GROUP * S_T; // [8 * n_general]  reassembled channels of the general groups
-    int2 *longs = reinterpret_cast<int2 *>(exc + GROUP * a.n_general); // [n_long] {src, scale} of long rows
+    float *zero = exc + GROUP * a.n_general; // [2] a zero: the "second source" of single-entry items
+    int2 *longs = reinterpret_cast<int2 *>(zero + 2); // [n_long] {src, scale} of long rows
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
@@ -305,10 +308,11 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     for (int it = 0; it < ITERS; ++it) {
         const int i = tid + it * nt;
         pass[it] = i < n_chunks ? (uint32_t)a.passes[i] : 0u;
-        desc[it] = i < a.n_groups ? a.desc[i] : (i < a.n_groups_pad ? DESC_PAD : DESC_NONE);
+        desc[it] = i < a.n_groups_pad ? a.desc[i] : WORK_NONE; // work-list entry of this lane and step
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
     }
     for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int2 *>(a.longs)[j];
+    if (tid < 2) zero[tid] = 0.0f;
     if (tid < 16) { // reduction slots of waves that do not exist hold the identity
         red_d[0][tid] = 0.0;
         red_d[1][tid] = 0.0;
@@ -317,11 +321,27 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         red_i[tid] = 0;
     }
     __syncthreads();
-    int2 item[ITEMS_REG]; // {src0 | src1 << 16, scale}
+    // general-group entries of this lane: {LDS index of source 0 | LDS index of source 1 << 16, scale}
+    // (the second index of a single-entry item points at the zero); for a long row (bit m of long_mask)
+    // the second word is first | count << 24 into the table of long rows
+    int2 item[ITEMS_REG];
+    uint32_t long_mask = 0;
 #pragma unroll
     for (int m = 0; m < ITEMS_REG; ++m) {
         const int j = tid + m * nt;
-        item[m] = j < n_items ? reinterpret_cast<const int2 *>(a.items)[j] : make_int2(-1, 0); // -1: nothing
+        item[m] = make_int2(0, 0);
+        if (j < n_items) {
+            const int2 e = reinterpret_cast<const int2 *>(a.items)[j];
+            item[m].y = e.y;
+            if (e.x == ITEM_LONG) {
+                long_mask |= 1u << m;
+            } else {
+                const uint32_t s0 = (uint32_t)e.x & 0xffffu, s1 = (uint32_t)e.x >> 16;
+                const uint32_t i0 = (s0 & 7) * S_T + (s0 >> 3);
+                const uint32_t i1 = s1 == 0xffffu ? (uint32_t)(zero - lds) : (s1 & 7) * S_T + (s1 >> 3);
+                item[m].x = (int32_t)(i0 | (i1 << 16)); // float indices into lds, both below 65536
+            }
+        }
     }
 
     // value of a general-group channel whose row is neither of the two short forms:
@@ -458,13 +478,31 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                         mn = fminf(mn, y[j]);
                         mx = fmaxf(mx, y[j]);
                     }
-                } else if (pass[it] != 0u) {
+                }
+            }
+        }
+        // Chunks in which some channel does not pass (an outlier that is split, a merged source) are
+        // few, but nearly every wave has a lane with one: handled here, one per lane and turn, so a
+        // wave spends as many turns as its busiest lane has such chunks (one or two), not ITERS.
+        // A lane re-reads its own LDS writes: in order, no barrier needed.
+        {
+            uint32_t todo = 0;
 #pragma unroll
-                    for (int j = 0; j < GROUP; ++j)
-                        if (pass[it] >> j & 1u) {
-                            mn = fminf(mn, y[j]);
-                            mx = fmaxf(mx, y[j]);
-                        }
+            for (int it = 0; it < ITERS; ++it)
+                if (pass[it] != 0xffu && pass[it] != 0u) todo |= 1u << it;
+            while (todo) {
+                const int it = __builtin_ctz(todo);
+                todo &= todo - 1;
+                uint32_t m = pass[0];
+#pragma unroll
+                for (int q = 1; q < ITERS; ++q) m = it == q ? pass[q] : m;
+                const float *col = ylds + tid + it * nt;
+#pragma unroll
+                for (int j = 0; j < GROUP; ++j) {
+                    const float yv = col[j * S_T];
+                    const bool in = m >> j & 1u;
+                    mn = fminf(mn, in ? yv : inf);
+                    mx = fmaxf(mx, in ? yv : -inf);
                 }
             }
         }
@@ -476,26 +514,34 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         {
             float y0[ITEMS_REG], y1[ITEMS_REG];
 #pragma unroll
-            for (int m = 0; m < ITEMS_REG; ++m) {
-                const bool marker = item[m].x == -1 || item[m].x == -2; // no source of its own: read channel 0
-                const uint32_t s0 = marker ? 0u : ((uint32_t)item[m].x & 0xffffu);
-                const uint32_t hi = (uint32_t)item[m].x >> 16;
-                const uint32_t s1 = (marker || hi == 0xffffu) ? s0 : hi;
-                y0[m] = ylds[(s0 & 7) * S_T + (s0 >> 3)];
-                y1[m] = ylds[(s1 & 7) * S_T + (s1 >> 3)];
+            for (int m = 0; m < ITEMS_REG; ++m) { // long rows and unused slots read index 0, harmlessly
+                const uint32_t p = (uint32_t)item[m].x;
+                y0[m] = lds[p & 0xffffu];
+                y1[m] = lds[p >> 16];
             }
 #pragma unroll
             for (int m = 0; m < ITEMS_REG; ++m) {
                 const int j = tid + m * nt;
                 const float sc = __int_as_float(item[m].y);
                 float xv = sc * y0[m];
-                const float two = xv + sc * y1[m];
-                xv = ((uint32_t)item[m].x >> 16) != 0xffffu ? two : xv;
-                if (item[m].x == -2) xv = long_value(item[m].y);
-                const bool real = item[m].x != -1;
+                xv = xv + sc * y1[m];
+                const bool real = j < n_items && !(long_mask >> m & 1u);
                 mn = fminf(mn, real ? xv : inf);
                 mx = fmaxf(mx, real ? xv : -inf);
-                if (j < n_items) exc[j] = real ? xv : 0.0f;
+                if (real) exc[j] = xv;
+            }
+            // long rows: one per lane and turn (see above)
+            uint32_t todo = long_mask;
+            while (todo) {
+                const int m = __builtin_ctz(todo);
+                todo &= todo - 1;
+                int32_t ref = item[0].y;
+#pragma unroll
+                for (int q = 1; q < ITEMS_REG; ++q) ref = m == q ? item[q].y : ref;
+                const float xv = long_value(ref);
+                mn = fminf(mn, xv);
+                mx = fmaxf(mx, xv);
+                exc[tid + m * nt] = xv;
             }
         }
 
@@ -528,17 +574,18 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         uint8_t *out_row = a.codes + row * a.row_bytes;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int g = tid + it * nt;
-            const int32_t d = desc[it];
-            if (d != DESC_NONE) {
+            const int32_t e = desc[it];
+            const int kind = (uint32_t)e >> 28;
+            if (kind != KIND_NONE) {
+                const int g = (e >> 15) & 0x1fff, d = e & 0x7fff;
                 float val[GROUP];
                 uint32_t live = 0xffu;
                 const int vv = d & 7;
                 int rot = vv;
                 const int v0 = __builtin_amdgcn_readfirstlane(vv);
-                if (__all(d >= 0 && vv == v0)) {
-                    // the whole wave reads plain groups with the same misalignment: every address is
-                    // one register plus an immediate
+                if (__all(kind == KIND_PLAIN && vv == v0)) {
+                    // the usual case (the work list is sorted for it): the whole wave reads plain groups
+                    // with the same misalignment, every address is one register plus an immediate
                     const float *ycol = ylds + (d >> 3);
                     switch (v0) {
                     case 0: read_plain<S_T, 0>(ycol, val); break;
@@ -550,13 +597,13 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                     case 6: read_plain<S_T, 6>(ycol, val); break;
                     default: read_plain<S_T, 7>(ycol, val); break;
                     }
-                } else if (d >= 0) {
+                } else if (kind == KIND_PLAIN) {
                     const int u = d >> 3;
 #pragma unroll
                     for (int k = 0; k < GROUP; ++k) val[k] = ylds[k * S_T + u + (k < vv ? 1 : 0)];
-                } else if (d != DESC_PAD) {
-                    const float4 e0 = *reinterpret_cast<const float4 *>(exc + (-(d + 1)) * GROUP);
-                    const float4 e1 = *reinterpret_cast<const float4 *>(exc + (-(d + 1)) * GROUP + 4);
+                } else if (kind == KIND_GENERAL) {
+                    const float4 e0 = *reinterpret_cast<const float4 *>(exc + d * GROUP);
+                    const float4 e1 = *reinterpret_cast<const float4 *>(exc + d * GROUP + 4);
                     val[0] = e0.x; val[1] = e0.y; val[2] = e0.z; val[3] = e0.w;
                     val[4] = e1.x; val[5] = e1.y; val[6] = e1.z; val[7] = e1.w;
                     rot = 0;
@@ -677,7 +724,7 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     const int units = n_chunks > a.n_groups_pad ? n_chunks : a.n_groups_pad;
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
     const Shape sh = pick_shape(units);
-    const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + (size_t)a.n_long * 8;
+    const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + 8 + (size_t)a.n_long * 8;
     if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
     const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
     if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // general-group entries live in registers

@@ -167,14 +167,16 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     }
     if (n_long > 0xffffff) return QLLM_ERR_MAP;
     *n_general = general;
-    const int64_t items_off = (8 + n_groups + 3) / 4 * 4; // items are read 8 bytes at a time
+    const int64_t n_work = (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G; // groups incl. zero padding
+    const int64_t items_off = (8 + n_work + 3) / 4 * 4; // items are read 8 bytes at a time
     *plan_len = items_off + general * G * 2 + n_chunks + 2 * n_long;
     if (!plan) return QLLM_OK;
 
-    int32_t *desc = plan + 8, *items = plan + items_off, *passes = items + general * G * 2;
+    int32_t *work = plan + 8, *items = plan + items_off, *passes = items + general * G * 2;
+    std::vector<int32_t> desc((size_t)n_groups);
     std::fill(plan, plan + *plan_len, 0);
-    plan[0] = 0x514c4d50; plan[1] = 1; plan[2] = (int32_t)C_in; plan[3] = (int32_t)C_out;
-    plan[4] = (int32_t)n_groups; plan[5] = (int32_t)general; plan[6] = (int32_t)n_chunks; plan[7] = (int32_t)n_long;
+    plan[0] = 0x514c4d50; plan[1] = 2; plan[2] = (int32_t)C_in; plan[3] = (int32_t)C_out;
+    plan[4] = (int32_t)n_work; plan[5] = (int32_t)general; plan[6] = (int32_t)n_chunks; plan[7] = (int32_t)n_long;
     std::fill(passes, passes + n_chunks, 0);
     int32_t *longs = passes + n_chunks;
     int64_t slot = 0, long_at = 0;
@@ -189,9 +191,11 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         for (int k = 0; k < G; ++k) {
             int32_t *it = items + (slot * G + k) * 2;
             const int64_t ch = g * G + k;
-            it[0] = -1; // padding past C_out
-            it[1] = 0;
-            if (ch >= C_out) continue;
+            if (ch >= C_out) { // padding past C_out: repeats the group's first channel (its code is forced to 0)
+                it[0] = items[slot * G * 2];
+                it[1] = items[slot * G * 2 + 1];
+                continue;
+            }
             const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
             if (n < 1) return QLLM_ERR_MAP;
             for (int32_t e = e0; e < e0 + n; ++e)
@@ -211,6 +215,19 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         }
         ++slot;
     }
+    // work list of the code-producing step, one entry per group of 8 output channels (zero padding
+    // included): kind << 28 | group << 15 | d.  Plain groups first, ordered by the misalignment d & 7 of
+    // their source so that the lanes of a wavefront mostly share it, then general groups (d = their
+    // number), then padding groups.
+    std::vector<int32_t> order;
+    order.reserve((size_t)n_work);
+    for (int v = 0; v < G; ++v)
+        for (int64_t g = 0; g < n_groups; ++g)
+            if (desc[g] >= 0 && (desc[g] & 7) == v) order.push_back((int32_t)(((uint32_t)g << 15) | (uint32_t)desc[g]));
+    for (int64_t g = 0; g < n_groups; ++g)
+        if (desc[g] < 0) order.push_back((int32_t)((1u << 28) | ((uint32_t)g << 15) | (uint32_t)(-(desc[g] + 1))));
+    for (int64_t g = n_groups; g < n_work; ++g) order.push_back((int32_t)((2u << 28) | ((uint32_t)g << 15)));
+    std::copy(order.begin(), order.end(), work);
     return QLLM_OK;
 }
 

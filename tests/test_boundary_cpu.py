@@ -144,12 +144,22 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
     assert np.array_equal(r["scale"], c.scale)
     assert b.qllm_check_map_host(r["row_ptr"], r["src"], r["scale"], C) == 0
-    # the plan: header, group descriptors, general-group entries, pass bits
+    # the plan: header, work list, general-group entries, pass bits, long rows
     plan, n_general = r["plan"], r["plan_general"]
-    n_groups, n_chunks = (c.K + 7) // 8, (C + 7) // 8
-    assert plan[:7].tolist() == [0x514C4D50, 1, C, c.K, n_groups, n_general, n_chunks]
-    desc = plan[8:8 + n_groups]
-    items_off = (8 + n_groups + 3) // 4 * 4
+    n_groups, n_chunks, n_work = (c.K + 7) // 8, (C + 7) // 8, (c.K + 255) // 256 * 32
+    assert plan[:7].tolist() == [0x514C4D50, 2, C, c.K, n_work, n_general, n_chunks]
+    work = plan[8:8 + n_work].astype(np.int64) & 0xFFFFFFFF
+    kind, grp, dd = work >> 28, (work >> 15) & 0x1FFF, work & 0x7FFF
+    assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
+    assert np.all(np.diff(kind) >= 0) and np.all(kind[grp >= n_groups] == 2) and np.all(kind[grp < n_groups] < 2)
+    plain = kind == 0
+    key = (dd[plain] & 7) * 8192 + grp[plain]                     # plain groups: by misalignment, then by group
+    assert np.all(np.diff(key) > 0)
+    desc = np.full(n_groups, -1, np.int64)
+    desc[grp[plain]] = dd[plain]
+    gen = kind == 1
+    desc[grp[gen]] = -(dd[gen] + 1)
+    items_off = (8 + n_work + 3) // 4 * 4
     items = plan[items_off:items_off + 16 * n_general].reshape(n_general * 8, 2)
     passes = plan[items_off + 16 * n_general:items_off + 16 * n_general + n_chunks]
     longs = plan[items_off + 16 * n_general + n_chunks:].reshape(-1, 2)
@@ -173,7 +183,7 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
             it = items[(-desc[g] - 1) * 8 + k]
             ch = lo + k
             if ch >= c.K:
-                assert it[0] == -1
+                assert np.array_equal(it, items[(-desc[g] - 1) * 8])      # padding repeats the first channel
                 continue
             e0, n = c.row_ptr[ch], c.row_ptr[ch + 1] - c.row_ptr[ch]
             if n > 2:
