@@ -193,10 +193,14 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  *            padding.  Sorted by kind, plain groups by d & 7, then by group
  *   items    (starting at the next multiple of 4 words) [n_general * 8][2]: for channel k of a general
  *            group {src0 | src1 << 16, scale}: one entry (src1 = 0xffff) or two entries of equal scale;
- *            {-2, first | count << 24}: any other row (at most 255 entries), its entries are
+ *            {-2, first | count << 24}: any other row (at most 64 entries), its entries are
  *            longs[first .. first + count); channels past C_out repeat the group's first channel
  *   passes   [n_chunks]: bit j set: input channel 8*chunk + j is a source of some plain group
- *   longs    [n_long][2]: {src, scale} entries of the rows that are neither of the two short forms
+ *   longs    (starting at the next multiple of 4 words) [n_long][4]: {src, dest, scale, pos}: entry pos
+ *            (0, 1, ...) of a row that is neither of the two short forms; dest = 8 * (general group
+ *            number) + k on the row's last entry, -1 elsewhere.  The kernel gives entry e to lane e % 64
+ *            of a wavefront and adds a row up lane by lane, so the table holds padding entries
+ *            {0, -1, 0.0f, 0} wherever a row would otherwise straddle a multiple of 64; n_long counts them
  */
 int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,
                            int64_t C_out, int32_t *plan, int64_t *plan_len, int64_t *n_general);

@@ -17,6 +17,7 @@ LIB_PATH = os.environ.get("QLLM_LIB", os.path.join(_HERE, "libqllm.so"))  # over
 F32, BF16 = 0, 1
 NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
 MAX_CHANNELS, K_PAD, MAP_GROUP = 32768, 256, 8
+QLLM_ERR_MAP = -5
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it first (python __graft_entry__.py)")
@@ -131,7 +132,13 @@ def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx, with_plan=True):
                                   C.byref(c_out), C.byref(nnz), _hp(T)), "qllm_build_map_host")
     out = dict(row_ptr=row_ptr, src=src, scale=scale, num_split=T, C_in=Cc, C_out=c_out.value, nnz=nnz.value)
     if with_plan:
-        out["plan"], out["plan_general"] = qllm_plan_map_host(row_ptr, src, scale, Cc)
+        try:
+            out["plan"], out["plan_general"] = qllm_plan_map_host(row_ptr, src, scale, Cc)
+        except QllmError as e:
+            if e.status != QLLM_ERR_MAP:
+                raise
+            # a channel merged from more than 64: no plan, the fused kernel walks the CSR instead
+            out["plan"], out["plan_general"] = None, 0
     return out
 
 

@@ -457,9 +457,10 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
         a.desc = map->plan + 8;
         a.items = map->plan + (8 + (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP + 3) / 4 * 4;
         a.passes = a.items + (int64_t)a.n_general * GROUP * 2;
-        a.longs = a.passes + (C + GROUP - 1) / GROUP;
-        const int64_t n_long = (map->plan_len - (a.longs - map->plan)) / 2;
-        if (n_long < 0 || n_long > 0xffffff) return QLLM_ERR_SHAPE;
+        const int64_t longs_off = ((a.passes - map->plan) + (C + GROUP - 1) / GROUP + 3) / 4 * 4;
+        a.longs = map->plan + longs_off;
+        const int64_t n_long = (map->plan_len - longs_off) / 4;
+        if (map->plan_len < longs_off || n_long > 0xffffff) return QLLM_ERR_SHAPE;
         a.n_long = (int32_t)n_long;
     }
     a.C_out = (int32_t)map->C_out;

@@ -123,6 +123,7 @@ constexpr int DPP_XOR1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int DPP_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int DPP_HALF_MIRROR = 0x141; // lane i <-> 7 - i inside each half row
 constexpr int DPP_MIRROR = 0x140;      // lane i <-> 15 - i inside each row
+constexpr int DPP_WAVE_SHR1 = 0x138;   // lane i <- lane i - 1 across the whole wavefront (lane 0 keeps `old`)
 
 __device__ __forceinline__ float lane_f32(float v, int l)
 {
@@ -285,8 +286,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     extern __shared__ float lds[];
     float *ylds = lds;              // [8 * S_T]        y, transposed by 8
     float *exc = lds + GROUP * S_T; // [8 * n_general]  reassembled channels of the general groups
-    float *zero = exc + GROUP * a.n_general; // [2] a zero: the "second source" of single-entry items
-    int2 *longs = reinterpret_cast<int2 *>(zero + 2); // [n_long] {src, scale} of long rows
+    float *zero = exc + GROUP * a.n_general; // [4] a zero: the "second source" of single-entry items
+    int4 *longs = reinterpret_cast<int4 *>(zero + 4); // [n_long] {LDS index of src, dest, scale, pos} of long rows
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
@@ -311,8 +312,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         desc[it] = i < a.n_groups_pad ? a.desc[i] : WORK_NONE; // work-list entry of this lane and step
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
     }
-    for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int2 *>(a.longs)[j];
-    if (tid < 2) zero[tid] = 0.0f;
+    for (int j = tid; j < a.n_long; j += nt) {
+        int4 le = reinterpret_cast<const int4 *>(a.longs)[j];
+        le.x = (le.x & 7) * S_T + (le.x >> 3);
+        longs[j] = le;
+    }
+    if (tid < 4) zero[tid] = 0.0f;
     if (tid < 16) { // reduction slots of waves that do not exist hold the identity
         red_d[0][tid] = 0.0;
         red_d[1][tid] = 0.0;
@@ -343,19 +348,6 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
         }
     }
-
-    // value of a general-group channel whose row is neither of the two short forms:
-    // first | count << 24 into the table of long rows
-    auto long_value = [&](int32_t ref) -> float {
-        const int first = ref & 0xffffff, count = (uint32_t)ref >> 24;
-        int2 le = longs[first];
-        float acc = __int_as_float(le.y) * ylds[(le.x & 7) * S_T + (le.x >> 3)];
-        for (int p = 1; p < count; ++p) {
-            le = longs[first + p];
-            acc = acc + __int_as_float(le.y) * ylds[(le.x & 7) * S_T + (le.x >> 3)];
-        }
-        return acc;
-    };
 
     const XT *xbase = reinterpret_cast<const XT *>(a.x);
     Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
@@ -530,18 +522,27 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 mx = fmaxf(mx, real ? xv : -inf);
                 if (real) exc[j] = xv;
             }
-            // long rows: one per lane and turn (see above)
-            uint32_t todo = long_mask;
-            while (todo) {
-                const int m = __builtin_ctz(todo);
-                todo &= todo - 1;
-                int32_t ref = item[0].y;
-#pragma unroll
-                for (int q = 1; q < ITEMS_REG; ++q) ref = m == q ? item[q].y : ref;
-                const float xv = long_value(ref);
-                mn = fminf(mn, xv);
-                mx = fmaxf(mx, xv);
-                exc[tid + m * nt] = xv;
+            // Long rows (a channel merged from three or more, Eq. 4).  The sum runs left to right in
+            // fp32, so its order is fixed; its latency need not be.  Entry e of the table belongs to lane
+            // e % 64 and a row sits in consecutive lanes of one wavefront: every lane forms its product,
+            // then "value of the lane below + own product" is repeated; the lane of entry number pos is
+            // final after pos repeats (repeating it again changes nothing) and the row's last lane
+            // ends up with the row's value.
+            for (int base = 0; base < a.n_long; base += nt) {
+                const int e = base + tid;
+                int4 le = make_int4(0, -1, 0, 0);
+                if (e < a.n_long) le = longs[e];
+                const float p = __int_as_float(le.z) * lds[le.x];
+                float acc = p;
+                for (int t = 1; __builtin_amdgcn_ballot_w64(le.w >= t) != 0; ++t) {
+                    const float below = dpp_f32<DPP_WAVE_SHR1>(acc);
+                    acc = le.w > 0 ? below + p : p;
+                }
+                if (le.y >= 0) {
+                    exc[le.y] = acc;
+                    mn = fminf(mn, acc);
+                    mx = fmaxf(mx, acc);
+                }
             }
         }
 
@@ -724,7 +725,7 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     const int units = n_chunks > a.n_groups_pad ? n_chunks : a.n_groups_pad;
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
     const Shape sh = pick_shape(units);
-    const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + 8 + (size_t)a.n_long * 8;
+    const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16;
     if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
     const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
     if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // general-group entries live in registers

@@ -153,6 +153,11 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
         return n == 1 || (n == 2 && std::memcmp(&scale[e0], &scale[e0 + 1], 4) == 0);
     };
+    // Rows that are neither short form go to the table of long rows, one entry per lane of the fused
+    // kernel: a row occupies consecutive lanes of ONE wavefront, so the table is padded wherever a row
+    // would straddle a multiple of 64.
+    constexpr int64_t WAVE = 64;
+    auto place_long = [&](int64_t at, int64_t n) { return at % WAVE + n > WAVE ? (at + WAVE - 1) / WAVE * WAVE : at; };
     int64_t general = 0, n_long = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
         if (plain_source(g) >= 0) continue;
@@ -160,8 +165,9 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         for (int64_t ch = g * G; ch < std::min(C_out, (g + 1) * G); ++ch) {
             if (row_ptr[ch + 1] <= row_ptr[ch]) return QLLM_ERR_MAP;
             if (!compact(ch)) {
-                if (row_ptr[ch + 1] - row_ptr[ch] > 255) return QLLM_ERR_MAP; // the plan indexes at most 255 entries per row
-                n_long += row_ptr[ch + 1] - row_ptr[ch];
+                const int64_t n = row_ptr[ch + 1] - row_ptr[ch];
+                if (n > WAVE) return QLLM_ERR_MAP; // a long row is summed inside one wavefront
+                n_long = place_long(n_long, n) + n;
             }
         }
     }
@@ -169,16 +175,18 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     *n_general = general;
     const int64_t n_work = (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G; // groups incl. zero padding
     const int64_t items_off = (8 + n_work + 3) / 4 * 4; // items are read 8 bytes at a time
-    *plan_len = items_off + general * G * 2 + n_chunks + 2 * n_long;
+    const int64_t longs_off = (items_off + general * G * 2 + n_chunks + 3) / 4 * 4; // read 16 bytes at a time
+    *plan_len = longs_off + 4 * n_long;
     if (!plan) return QLLM_OK;
 
     int32_t *work = plan + 8, *items = plan + items_off, *passes = items + general * G * 2;
     std::vector<int32_t> desc((size_t)n_groups);
     std::fill(plan, plan + *plan_len, 0);
-    plan[0] = 0x514c4d50; plan[1] = 2; plan[2] = (int32_t)C_in; plan[3] = (int32_t)C_out;
+    plan[0] = 0x514c4d50; plan[1] = 3; plan[2] = (int32_t)C_in; plan[3] = (int32_t)C_out;
     plan[4] = (int32_t)n_work; plan[5] = (int32_t)general; plan[6] = (int32_t)n_chunks; plan[7] = (int32_t)n_long;
     std::fill(passes, passes + n_chunks, 0);
-    int32_t *longs = passes + n_chunks;
+    int32_t *longs = plan + longs_off; // zero-filled: padding entries are {0, 0 (below: -1), 0.0f, 0}
+    for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1;
     int64_t slot = 0, long_at = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
         const int32_t d = plain_source(g);
@@ -200,12 +208,15 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
             if (n < 1) return QLLM_ERR_MAP;
             for (int32_t e = e0; e < e0 + n; ++e)
                 if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
-            if (!compact(ch)) { // entries go to the table of long rows
+            if (!compact(ch)) { // entries go to the table of long rows: {src, destination or -1, scale, position}
+                long_at = place_long(long_at, n);
                 it[0] = -2;
                 it[1] = (int32_t)((uint32_t)long_at | ((uint32_t)n << 24));
                 for (int32_t e = e0; e < e0 + n; ++e, ++long_at) {
-                    longs[2 * long_at] = src[e];
-                    std::memcpy(&longs[2 * long_at + 1], &scale[e], 4);
+                    longs[4 * long_at] = src[e];
+                    longs[4 * long_at + 1] = e == e0 + n - 1 ? (int32_t)(slot * G + k) : -1;
+                    std::memcpy(&longs[4 * long_at + 2], &scale[e], 4);
+                    longs[4 * long_at + 3] = e - e0;
                 }
                 continue;
             }

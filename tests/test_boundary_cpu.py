@@ -147,7 +147,7 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     # the plan: header, work list, general-group entries, pass bits, long rows
     plan, n_general = r["plan"], r["plan_general"]
     n_groups, n_chunks, n_work = (c.K + 7) // 8, (C + 7) // 8, (c.K + 255) // 256 * 32
-    assert plan[:7].tolist() == [0x514C4D50, 2, C, c.K, n_work, n_general, n_chunks]
+    assert plan[:7].tolist() == [0x514C4D50, 3, C, c.K, n_work, n_general, n_chunks]
     work = plan[8:8 + n_work].astype(np.int64) & 0xFFFFFFFF
     kind, grp, dd = work >> 28, (work >> 15) & 0x1FFF, work & 0x7FFF
     assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
@@ -162,8 +162,10 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     items_off = (8 + n_work + 3) // 4 * 4
     items = plan[items_off:items_off + 16 * n_general].reshape(n_general * 8, 2)
     passes = plan[items_off + 16 * n_general:items_off + 16 * n_general + n_chunks]
-    longs = plan[items_off + 16 * n_general + n_chunks:].reshape(-1, 2)
+    longs_off = (items_off + 16 * n_general + n_chunks + 3) // 4 * 4
+    longs = plan[longs_off:].reshape(-1, 4)
     assert longs.shape[0] == plan[7]
+    used = np.zeros(longs.shape[0], bool)
     assert passes.size == n_chunks and (desc >= 0).sum() > 0.25 * desc.size and (desc < 0).sum() == n_general
     expect_pass = np.zeros(n_chunks * 8, bool)
     for g in np.nonzero(desc >= 0)[0]:       # a plain group: 8 single entries, scale 1, consecutive sources
@@ -189,14 +191,21 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
             if n > 2:
                 first = int(it[1]) & 0xFFFFFF
                 assert it[0] == -2 and (int(it[1]) >> 24) & 0xFF == n
+                assert first // 64 == (first + n - 1) // 64             # inside one wavefront's 64 entries
                 assert np.array_equal(longs[first:first + n, 0], c.src[e0:e0 + n])
-                assert np.array_equal(longs[first:first + n, 1].view(np.float32), c.scale[e0:e0 + n])
+                assert np.array_equal(longs[first:first + n, 2].view(np.float32), c.scale[e0:e0 + n])
+                assert np.array_equal(longs[first:first + n, 3], np.arange(n))
+                assert np.all(longs[first:first + n - 1, 1] == -1)
+                assert longs[first + n - 1, 1] == (-desc[g] - 1) * 8 + k
+                assert not used[first:first + n].any()
+                used[first:first + n] = True
                 continue
             second = c.src[e0 + 1] if n == 2 else 0xFFFF
             assert int(it[0]) & 0xFFFFFFFF == int(c.src[e0]) | (int(second) << 16)
             assert it[1:2].view(np.float32)[0] == c.scale[e0]
             if n == 2:
                 assert c.scale[e0 + 1] == c.scale[e0]
+    assert np.all(longs[~used] == np.array([0, -1, 0, 0]))            # padding entries between rows
     # weights: reassembled, quantized per output channel and packed by the library == the oracle's
     q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, w.w_bits)
     assert np.array_equal(q["scale"], c.aw) and np.array_equal(q["zero"], c.bw) and np.array_equal(q["colsum"], c.cs)

@@ -92,6 +92,31 @@ def test_fused_odd_shapes(oracle, b, name, N, C, bits, merge, use_plan):
     check_fused(oracle, c, run_fused(b, c, bits, use_plan), bits)
 
 
+def many_to_one_case(oracle, counts, N, C, name="llama7b_qkv"):
+    """No split channel; B-member j (position 2j + 1) takes counts[j] A-members: rows of counts[j] + 1 entries."""
+    c = make_case(oracle, wl.WORKLOADS[name], N=N, C=C, O=8, merge=False, real_weights=False, theta_rule=("fixed", 1.0))
+    c.theta = float(np.float32(c.absmax.max()) * np.float32(2.0))
+    c.T = np.ones(C, np.int32)
+    rng = np.random.default_rng(sum(counts) + C)
+    a_members = rng.permutation(C // 2)[:sum(counts)]
+    c.src_idx = a_members.astype(np.int32)
+    c.dst_idx = np.repeat(rng.permutation(C // 2)[:len(counts)], counts).astype(np.int32)
+    c.row_ptr, c.src, c.scale = oracle.build_map(c.T, c.src_idx, c.dst_idx)
+    c.K = c.row_ptr.size - 1
+    assert sorted(np.diff(c.row_ptr).tolist())[-len(counts):] == sorted(n + 1 for n in counts)
+    return c
+
+
+@pytest.mark.parametrize("counts,planned", [([63, 40, 30, 2, 2, 17, 63, 5], True), ([3] * 150, True), ([70, 2], False)])
+@pytest.mark.parametrize("C,bits", [(16392, 4), (8200, 6)])
+def test_fused_channels_merged_from_many(oracle, b, counts, planned, C, bits):
+    # a long row is summed lane by lane inside one wavefront; more than 64 entries: no plan, CSR walk
+    c = many_to_one_case(oracle, counts, N=9, C=C)
+    r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
+    assert (r["plan"] is not None) == planned
+    check_fused(oracle, c, run_fused(b, c, bits), bits)
+
+
 @pytest.mark.parametrize("norm", ["none", "layer", "rms"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_fused_norm_kinds_and_strided_input(oracle, b, norm, dtype):
