@@ -67,7 +67,7 @@ def main():
 
     # ---- offline: calibration -> map; weight reassembly + quantization (library host helpers)
     cal = calibrate.calibrate(x0, norm, gamma, beta, w.eps, w.theta_rule)
-    dmap = b.DeviceMap(cal["row_ptr"], cal["src"], cal["scale"], w.C, cal["plan"], cal["plan_general"])
+    dmap = b.DeviceMap(cal["row_ptr"], cal["src"], cal["scale"], w.C, cal["plan"])
     K = dmap.C_out
     W = wl.draw_weight(w)
     q = b.qllm_quantize_weight_host(W, cal["row_ptr"], cal["src"], w.w_bits)

@@ -54,6 +54,7 @@ typedef enum { QLLM_NORM_NONE = 0, QLLM_NORM_LAYER = 1, QLLM_NORM_RMS = 2 } qllm
 #define QLLM_K_PAD 256
 /* The fused kernel handles channels in groups of this many. */
 #define QLLM_MAP_GROUP 8
+#define QLLM_PLAN_HEAD 16      /* int32 words of header at the start of a plan (qllm_plan_map_host) */
 
 /*
  * Reassembly map: channel disassembly (Sec. 4.1.1, Eq. 3) followed by channel assembly
@@ -74,8 +75,7 @@ typedef struct {
                                map (an index of it for the fused kernel: which groups of 8 output channels
                                are plain shifted copies, the entries of all others, which inputs pass
                                unscaled).  NULL: the kernel walks the CSR for every channel (much slower). */
-    int64_t plan_general;   /* the n_general value qllm_plan_map_host returned with that plan (0 with NULL) */
-    int64_t plan_len;       /* words in plan (0 with NULL) */
+    int32_t plan_head[QLLM_PLAN_HEAD]; /* host copy of the plan's first QLLM_PLAN_HEAD words (ignored with NULL) */
 } qllm_map;
 
 /*
@@ -185,22 +185,28 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
 
 /* Indexes a CSR map for the fused kernel (see qllm_map.plan).  Call once with plan == NULL to get
  * *plan_len (int32 words) and *n_general, then with plan pointing at that many words.  The plan
- * depends only on the map; upload it next to the CSR arrays.  Layout (int32 words):
- *   [0..7]   header: magic, version, C_in, C_out, n_work = groups of 8 output channels including the zero
- *            padding to 256 codes, n_general, n_chunks = ceil(C_in/8), n_long
- *   work     [n_work]: kind << 28 | group << 15 | d.  kind 0: the 8 channels of the group are single-entry
- *            with scale exactly 1 and sources d, d+1, ..., d+7; kind 1: general group number d; kind 2:
- *            padding.  Sorted by kind, plain groups by d & 7, then by group
- *   items    (starting at the next multiple of 4 words) [n_general * 8][2]: for channel k of a general
- *            group {src0 | src1 << 16, scale}: one entry (src1 = 0xffff) or two entries of equal scale;
- *            {-2, first | count << 24}: any other row (at most 64 entries), its entries are
+ * depends only on the map; upload it next to the CSR arrays and keep its first QLLM_PLAN_HEAD words
+ * in qllm_map.plan_head.  Layout (int32 words; every part starts at a multiple of 4 words):
+ *   [0..15]  header: magic, version, C_in, C_out, n_work = groups of 8 output channels including the zero
+ *            padding to 256 codes, n_general, n_chunks = ceil(C_in/8), n_long, n_pub, then the offsets of
+ *            work, chunks, items, longs, then plan_len, 0, 0
+ *   work     [n_work]: kind << 28 | group << 15 | d.  kind 0 ("plain"): the 8 channels of the group are
+ *            single-entry with scale exactly 1 and sources d, d+1, ..., d+7; kind 1: general group number d;
+ *            kind 2: padding.  Sorted by kind, then by group
+ *   chunks   [n_chunks]: bits 0..7: bit j set = input channel 8*chunk + j is a source of some plain group;
+ *            bits 8..31: p if some general group reads a channel of this chunk (the kernel then stages
+ *            the chunk's y at floats 8p .. 8p+7 of its on-chip table; p = 0 .. n_pub-1 in chunk order),
+ *            0xffffff otherwise.  Float 8*n_pub of that table is a zero
+ *   items    [n_general * 8][2]: for channel k of a general group {s0 | s1 << 16, scale}: one entry
+ *            (s1 = 8*n_pub, the zero) or two entries of equal scale, s = staged position of the source
+ *            channel; {-2, first | count << 24}: any other row (at most 64 entries), its entries are
  *            longs[first .. first + count); channels past C_out repeat the group's first channel
- *   passes   [n_chunks]: bit j set: input channel 8*chunk + j is a source of some plain group
- *   longs    (starting at the next multiple of 4 words) [n_long][4]: {src, dest, scale, pos}: entry pos
- *            (0, 1, ...) of a row that is neither of the two short forms; dest = 8 * (general group
- *            number) + k on the row's last entry, -1 elsewhere.  The kernel gives entry e to lane e % 64
- *            of a wavefront and adds a row up lane by lane, so the table holds padding entries
- *            {0, -1, 0.0f, 0} wherever a row would otherwise straddle a multiple of 64; n_long counts them
+ *   longs    [n_long][4]: {s, dest, scale, pos}: entry pos (0, 1, ...) of a row that is neither of the
+ *            two short forms; dest = 8 * (general group number) + k on the row's last entry, -1 elsewhere.
+ *            The kernel gives entry e to lane e % 64 of a wavefront and adds a row up lane by lane, so
+ *            the table holds padding entries {0, -1, 0.0f, 0} wherever a row would otherwise straddle a
+ *            multiple of 64; n_long counts them
+ * QLLM_ERR_MAP: malformed map, or a row of more than 64 entries (such a map runs without a plan).
  */
 int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,
                            int64_t C_out, int32_t *plan, int64_t *plan_len, int64_t *n_general);

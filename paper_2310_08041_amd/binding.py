@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("QLLM_LIB", os.path.join(_HERE, "libqllm.so"))  # over
 
 F32, BF16 = 0, 1
 NORM_NONE, NORM_LAYER, NORM_RMS = 0, 1, 2
-MAX_CHANNELS, K_PAD, MAP_GROUP = 32768, 256, 8
+MAX_CHANNELS, K_PAD, MAP_GROUP, PLAN_HEAD = 32768, 256, 8, 16
 QLLM_ERR_MAP = -5
 
 if not os.path.exists(LIB_PATH):
@@ -33,7 +33,7 @@ class QllmError(RuntimeError):
 
 class _Map(C.Structure):
     _fields_ = [("C_in", C.c_int64), ("C_out", C.c_int64), ("nnz", C.c_int64), ("row_ptr", C.c_void_p),
-                ("src", C.c_void_p), ("scale", C.c_void_p), ("plan", C.c_void_p), ("plan_general", C.c_int64), ("plan_len", C.c_int64)]
+                ("src", C.c_void_p), ("scale", C.c_void_p), ("plan", C.c_void_p), ("plan_head", C.c_int32 * PLAN_HEAD)]
 
 
 class _Weight(C.Structure):
@@ -117,7 +117,8 @@ def qllm_gemm_workspace_bytes(N, K, O, a_bits):
 # ---------------------------------------------------------------- host helpers (numpy in, numpy out)
 
 def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx, with_plan=True):
-    """Returns dict(row_ptr, src, scale, num_split, C_in, C_out, nnz[, plan, plan_general]) of numpy arrays."""
+    """Returns dict(row_ptr, src, scale, num_split, C_in, C_out, nnz[, plan]) of numpy arrays (plan None
+    if the map cannot have one)."""
     m = _np(chan_absmax, np.float32)
     si, di = _np(src_idx, np.int32), _np(dst_idx, np.int32)
     Cc, r = m.size, si.size
@@ -133,12 +134,12 @@ def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx, with_plan=True):
     out = dict(row_ptr=row_ptr, src=src, scale=scale, num_split=T, C_in=Cc, C_out=c_out.value, nnz=nnz.value)
     if with_plan:
         try:
-            out["plan"], out["plan_general"] = qllm_plan_map_host(row_ptr, src, scale, Cc)
+            out["plan"] = qllm_plan_map_host(row_ptr, src, scale, Cc)[0]
         except QllmError as e:
             if e.status != QLLM_ERR_MAP:
                 raise
             # a channel merged from more than 64: no plan, the fused kernel walks the CSR instead
-            out["plan"], out["plan_general"] = None, 0
+            out["plan"] = None
     return out
 
 
@@ -221,16 +222,18 @@ def _x_dtype(x):
 class DeviceMap:
     """Device copy of a reassembly map (keeps the tensors alive next to the C struct)."""
 
-    def __init__(self, row_ptr, src, scale, C_in, plan=None, plan_general=0, device="cuda"):
+    def __init__(self, row_ptr, src, scale, C_in, plan=None, device="cuda"):
         torch = _torch()
         self.row_ptr = torch.as_tensor(np.ascontiguousarray(row_ptr, np.int32)).to(device)
         self.src = torch.as_tensor(np.ascontiguousarray(src, np.int32)).to(device)
         self.scale = torch.as_tensor(np.ascontiguousarray(scale, np.float32)).to(device)
         self.plan = None if plan is None else torch.as_tensor(np.ascontiguousarray(plan, np.int32)).to(device)
-        self.plan_general = int(plan_general) if plan is not None else 0
+        head = (C.c_int32 * PLAN_HEAD)()
+        if plan is not None:
+            head[:] = [int(v) for v in np.asarray(plan).ravel()[:PLAN_HEAD]]
         self.C_in, self.C_out, self.nnz = int(C_in), int(self.row_ptr.numel() - 1), int(self.src.numel())
         self.c = _Map(self.C_in, self.C_out, self.nnz, _dp(self.row_ptr), _dp(self.src), _dp(self.scale),
-                      _dp(self.plan), self.plan_general, 0 if self.plan is None else int(self.plan.numel()))
+                      _dp(self.plan), head)
 
 
 class DeviceWeight:

@@ -26,9 +26,8 @@ struct FusedArgs {
     double inv_C; // 1 / C
     const int32_t *row_ptr, *src, *desc;
     const float *scale;
-    const int32_t *items, *passes, *longs; // plan: entries of the general groups; per input chunk, which
-                                           // channels pass unscaled; entries of the long rows
-    int32_t n_general, n_long;
+    const int32_t *work, *chunks, *items, *longs; // the parts of the plan (see qllm_plan_map_host)
+    int32_t n_general, n_long, n_pub, n_work, n_chunks;
     int32_t C_out, n_groups, n_groups_pad, S;
     uint8_t *codes;
     int64_t row_bytes;
@@ -67,8 +66,8 @@ __device__ __forceinline__ int32_t quant_code(float x, float inv, int32_t beta, 
 
 } // namespace qllm_detail
 
-// Launches the planned kernel (fused_planned.hip).  Returns QLLM_ERR_WORKSPACE if the row plus the
-// general groups do not fit in LDS: the caller then takes the plain kernel.
+// Launches the planned kernel (fused_planned.hip).  Returns QLLM_ERR_WORKSPACE if the shape or the
+// general groups are more than it holds on chip: the caller then takes the plain kernel.
 int32_t qllm_launch_fused_planned(const qllm_detail::FusedArgs &a, int32_t x_dtype, int32_t bits, hipStream_t stream);
 
 #endif

@@ -451,17 +451,24 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     a.row_ptr = map->row_ptr;
     a.src = map->src;
     a.scale = map->scale;
-    if (map->plan) { // header (8 words), then desc, items, passes: see qllm_plan_map_host
-        if (map->plan_general < 0 || (reinterpret_cast<uintptr_t>(map->plan) & 15u)) return QLLM_ERR_ALIGN;
-        a.n_general = (int32_t)map->plan_general;
-        a.desc = map->plan + 8;
-        a.items = map->plan + (8 + (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP + 3) / 4 * 4;
-        a.passes = a.items + (int64_t)a.n_general * GROUP * 2;
-        const int64_t longs_off = ((a.passes - map->plan) + (C + GROUP - 1) / GROUP + 3) / 4 * 4;
-        a.longs = map->plan + longs_off;
-        const int64_t n_long = (map->plan_len - longs_off) / 4;
-        if (map->plan_len < longs_off || n_long > 0xffffff) return QLLM_ERR_SHAPE;
-        a.n_long = (int32_t)n_long;
+    if (map->plan) { // the host copy of the header says where the parts are: see qllm_plan_map_host
+        const int32_t *h = map->plan_head;
+        if (reinterpret_cast<uintptr_t>(map->plan) & 15u) return QLLM_ERR_ALIGN;
+        if (h[0] != 0x514c4d50 || h[1] != 4 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
+        const int64_t n_chunks = (C + GROUP - 1) / GROUP, n_work = (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP;
+        if (h[4] != n_work || h[6] != n_chunks || h[5] < 0 || h[5] > n_work || h[7] < 0 || h[8] < 0 || h[8] > n_chunks ||
+            h[9] != QLLM_PLAN_HEAD || h[10] < h[9] + n_work || h[11] < h[10] + n_chunks ||
+            h[12] < h[11] + 2 * GROUP * (int64_t)h[5] || h[13] != h[12] + 4 * (int64_t)h[7] || ((h[10] | h[11] | h[12]) & 3))
+            return QLLM_ERR_MAP;
+        a.work = map->plan + h[9];
+        a.chunks = map->plan + h[10];
+        a.items = map->plan + h[11];
+        a.longs = map->plan + h[12];
+        a.n_work = h[4];
+        a.n_general = h[5];
+        a.n_chunks = h[6];
+        a.n_long = h[7];
+        a.n_pub = h[8];
     }
     a.C_out = (int32_t)map->C_out;
     a.n_groups = (int32_t)((map->C_out + GROUP - 1) / GROUP);
@@ -476,7 +483,6 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     if (map->plan) {
         rc = qllm_launch_fused_planned(a, x_dtype, bits, stream);
         if (rc != QLLM_ERR_WORKSPACE) return rc; // does not fit on chip: the plain kernel below handles it
-        a.desc = nullptr;                        // ... by walking the CSR (the plan's work list is not for it)
     }
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, max_units, stream);
     return dispatch_bits<float>(a, bits, max_units, stream);

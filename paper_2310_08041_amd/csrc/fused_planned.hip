@@ -4,23 +4,28 @@
 // Shape of the computation
 //   * Persistent workgroups: grid = (CUs x resident workgroups), each workgroup walks rows
 //     blockIdx, blockIdx + grid, ...  What depends only on the map and on gamma -- the lane's share of
-//     gamma, of the plan's group descriptors, pass bits and general-group entries -- is loaded once
-//     into registers and reused for every row.
+//     gamma and of the plan -- is loaded once into registers and reused for every row.
 //   * HBM: a row is read exactly once, 16 bytes per lane, consecutive lanes on consecutive addresses;
 //     the loads of the workgroup's next row are issued before the current row is processed, so they
 //     are in flight during its arithmetic.  Codes leave as one coalesced store per lane and group.
-//   * LDS: y (fp32) is staged "transposed by 8": channel c at float (c & 7) * S + (c >> 3).  A lane
-//     that owns channels 8i..8i+7 writes 8 dwords next to its neighbours' (no bank conflicts), and a
-//     lane that needs 8 consecutive channels starting anywhere reads 8 dwords next to its neighbours'.
-//     S is a compile-time constant, so all 16 addresses are one register plus an immediate.
+//   * y stays in the registers of the lane that loaded its chunk of 8 channels, from the norm until
+//     that same lane quantizes it.  A code does not depend on where its channel ends up, so chunks are
+//     quantized and packed in INPUT order and only the packed words (4 to 8 bytes per chunk) go through
+//     LDS.  Nearly all groups of 8 output channels are "plain": 8 consecutive input channels, unscaled,
+//     starting anywhere; such a group is two neighbouring packed words funnel-shifted by its
+//     misalignment: two LDS reads and one shift per group, whatever the misalignment.
+//   * The other ("general") groups hold sub-channels (Eq. 3, scale 1/T), merged channels (Eq. 4) and
+//     the unscaled channels that share a group of 8 with them.  The plan lists the input chunks they
+//     read; only those chunks' y (fp32) is staged in LDS.  Their values are computed by whichever lane
+//     the entry falls to, kept in a second small LDS area, and quantized by the lane that stores the
+//     group.
 //   * min/max of the reassembled row without materialising it: every reassembled channel is either
 //     an unscaled copy of an input channel (those inputs carry a pass bit and enter min/max when y is
-//     produced) or a channel of a "general" group (sub-channels, merged channels and their
-//     neighbours), whose values are computed from LDS by whichever lane the item falls to, kept in a
-//     small second LDS area, and enter min/max there.  min and max do not depend on order.
+//     produced) or a channel of a general group (enters where it is computed).
 //   * Codes: one fused multiply-add against 1.5 * 2^23 rounds x * inv to the nearest-even integer in
-//     the low mantissa bits; a signed median clamps; shift-and-add packs.  Plain groups whose source
-//     offset is not a multiple of 8 are read rotated and the packed word is rotated back.
+//     the low mantissa bits; a median-of-three clamps; shift-and-add packs.
+//   * Four barriers per row (five with LayerNorm): statistics, staged y complete, range, packed
+//     words complete.  The first also separates a row's last LDS reads from the next row's writes.
 //
 // Compiled with -ffp-contract=off (see fused_nrq.hip).
 #include <hip/hip_runtime.h>
@@ -164,20 +169,17 @@ __device__ __forceinline__ int32_t wave_sum_i32(int32_t v)
            __builtin_amdgcn_readlane(v, 48);
 }
 
-// Sum over the workgroup: one LDS slot per wave, one barrier, then lane w of every wave fetches slot w
-// (one LDS access instead of a dependent chain of them) and the wave adds the slots in slot order.
-// The slot array holds 16 entries, zero where there is no wave, and is not reused before another
-// barrier has passed.
-__device__ __forceinline__ double block_sum(double v, double *slots, int wave, int lane)
+// Sum of the 16 per-wave slots (zero where there is no wave): lane w of every row of 16 lanes fetches
+// slot w and a butterfly adds them, so every lane ends with the same total without a dependent chain
+// of LDS reads.  The slots are not reused before another barrier has passed.
+__device__ __forceinline__ double total16(const double *slots, int lane)
 {
-    v = wave_sum(v);
-    if (lane == 0) slots[wave] = v;
-    __syncthreads();
-    const double mine = slots[lane & 15];
-    double s = lane_f64(mine, 0);
-#pragma unroll
-    for (int w = 1; w < 16; ++w) s += lane_f64(mine, w);
-    return s;
+    double v = slots[lane & 15];
+    v += dpp_f64<DPP_XOR1>(v);
+    v += dpp_f64<DPP_XOR2>(v);
+    v += dpp_f64<DPP_HALF_MIRROR>(v);
+    v += dpp_f64<DPP_MIRROR>(v);
+    return v;
 }
 
 // gamma of one 8-channel chunk (held in registers for the lifetime of the workgroup).  NORM_NONE runs
@@ -193,15 +195,6 @@ __device__ __forceinline__ void load_gamma(float *g, const float *gamma, int c0,
     g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
 }
 
-// 8 values of a plain group whose first source channel is 8*u + V, V known at compile time:
-// channel 8u + V + j sits in LDS row (V + j) & 7, column u + ((V + j) >> 3); slot k = LDS row k.
-template <int S_T, int V>
-__device__ __forceinline__ void read_plain(const float *ycol, float *val)
-{
-#pragma unroll
-    for (int k = 0; k < GROUP; ++k) val[k] = ycol[k * S_T + (k < V ? 1 : 0)];
-}
-
 // Eq. (2) for a row whose quotients are too large for the fused-multiply-add trick.
 __device__ __noinline__ uint32_t slow_code(float x, float inv, int32_t beta, int32_t qmax)
 {
@@ -209,16 +202,19 @@ __device__ __noinline__ uint32_t slow_code(float x, float inv, int32_t beta, int
     return (uint32_t)fmin(fmax(q, 0.0), (double)qmax);
 }
 
-// Quantizes the 8 slots of one group (Eq. 2), packs them, rotates slot order back into channel order
-// and stores.  Returns the sum of the codes.
+// dwords of LDS per packed chunk of 8 codes (6-bit chunks take 48 of the 64 bits)
+template <int BITS>
+constexpr int PKW = BITS == 4 ? 1 : 2;
+
+// Quantizes 8 values (Eq. 2) and packs their codes, first value lowest.
 //
 // Fast form: b = bits(fma(x, inv, MAGIC)) is MAGIC_BITS + rne(x*inv); clamping b to [lo, lo + qmax]
-// with lo = MAGIC_BITS - beta (one median-of-three) leaves lo + code.  The 8 (or 4) values are packed with shift-and-add
-// in wrapping 32-bit arithmetic and the common offset lo * (1 + 2^BITS + 2^(2 BITS) + ...) is taken
-// off once.
+// with lo = MAGIC_BITS - beta (one median-of-three) leaves lo + code.  The values are packed with
+// shift-and-add in wrapping 32-bit arithmetic and the common offset lo * (1 + 2^BITS + 2^(2 BITS) + ...)
+// is taken off once.  `live`: bit k clear forces code k to 0 (channels past the end of the row).
 template <int BITS>
-__device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, int rot, int32_t fast, float inv,
-                                              int32_t beta, uint8_t *out_row, int g)
+__device__ __forceinline__ void quant_pack(const float *val, uint32_t live, int32_t fast, float inv, int32_t beta,
+                                           uint32_t &w0, uint32_t &w1)
 {
     constexpr int QMAX = (1 << BITS) - 1;
     uint32_t c[GROUP], bias = 0;
@@ -230,7 +226,7 @@ __device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, i
         for (int k = 0; k < GROUP; ++k)
             c[k] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(val[k], inv, MAGIC), lo, hi));
     } else {
-#pragma unroll 1
+#pragma unroll
         for (int k = 0; k < GROUP; ++k) c[k] = slow_code(val[k], inv, beta, QMAX); // rare; kept out of line
     }
     if (live != 0xffu) {
@@ -241,9 +237,8 @@ __device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, i
         uint32_t p = 0;
 #pragma unroll
         for (int k = GROUP - 1; k >= 0; --k) p = (p << 4) + c[k];
-        p -= bias * 0x11111111u;
-        reinterpret_cast<uint32_t *>(out_row)[g] = __builtin_amdgcn_alignbit(p, p, rot * 4); // rotate right
-        return (int32_t)__builtin_amdgcn_udot8(p, 0x11111111u, 0u, false);
+        w0 = p - bias * 0x11111111u;
+        w1 = 0;
     } else if constexpr (BITS == 8) {
         uint32_t p0 = 0, p1 = 0;
 #pragma unroll
@@ -251,12 +246,8 @@ __device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, i
             p0 = (p0 << 8) + c[k];
             p1 = (p1 << 8) + c[k + 4];
         }
-        p0 -= bias * 0x01010101u;
-        p1 -= bias * 0x01010101u;
-        const uint64_t p = (uint64_t)p0 | ((uint64_t)p1 << 32);
-        const int sh = rot * 8;
-        reinterpret_cast<uint64_t *>(out_row)[g] = (p >> sh) | (p << ((64 - sh) & 63));
-        return (int32_t)__builtin_amdgcn_udot4(p0, 0x01010101u, __builtin_amdgcn_udot4(p1, 0x01010101u, 0u, false), false);
+        w0 = p0 - bias * 0x01010101u;
+        w1 = p1 - bias * 0x01010101u;
     } else {
         uint32_t h0 = 0, h1 = 0; // four 6-bit codes each
 #pragma unroll
@@ -266,58 +257,105 @@ __device__ __forceinline__ int32_t pack_store(const float *val, uint32_t live, i
         }
         h0 = (h0 - bias * 0x41041u) & 0xffffffu;
         h1 = (h1 - bias * 0x41041u) & 0xffffffu;
-        uint64_t p = (uint64_t)h0 | ((uint64_t)h1 << 24);
-        const int sh = rot * 6;
-        p = ((p >> sh) | (p << (48 - sh))) & 0xffffffffffffull;
-        uint16_t *o16 = reinterpret_cast<uint16_t *>(out_row + (int64_t)g * 6);
-        o16[0] = (uint16_t)p;
-        o16[1] = (uint16_t)(p >> 16);
-        o16[2] = (uint16_t)(p >> 32);
+        w0 = h0 | (h1 << 24);
+        w1 = h1 >> 8;
+    }
+}
+
+// Sum of the 8 codes of a packed group.
+template <int BITS>
+__device__ __forceinline__ int32_t code_sum(uint32_t w0, uint32_t w1)
+{
+    if constexpr (BITS == 4) {
+        return (int32_t)__builtin_amdgcn_udot8(w0, 0x11111111u, 0u, false);
+    } else if constexpr (BITS == 8) {
+        return (int32_t)__builtin_amdgcn_udot4(w0, 0x01010101u, __builtin_amdgcn_udot4(w1, 0x01010101u, 0u, false), false);
+    } else {
+        const uint32_t h0 = w0 & 0xffffffu, h1 = (w0 >> 24) | (w1 << 8);
         const uint32_t f = (h0 & 0x3f03fu) + ((h0 >> 6) & 0x3f03fu) + (h1 & 0x3f03fu) + ((h1 >> 6) & 0x3f03fu);
         return (int32_t)((f & 0xfffu) + (f >> 12));
     }
 }
 
+// Packed codes of output group g into the row.
+template <int BITS>
+__device__ __forceinline__ void store_group(uint8_t *out_row, int g, uint32_t w0, uint32_t w1)
+{
+    if constexpr (BITS == 4) {
+        reinterpret_cast<uint32_t *>(out_row)[g] = w0;
+    } else if constexpr (BITS == 8) {
+        reinterpret_cast<uint2 *>(out_row)[g] = make_uint2(w0, w1);
+    } else { // 6 bytes, 2-byte aligned
+        uint16_t *o16 = reinterpret_cast<uint16_t *>(out_row + (int64_t)g * 6);
+        o16[0] = (uint16_t)w0;
+        o16[1] = (uint16_t)(w0 >> 16);
+        o16[2] = (uint16_t)w1;
+    }
+}
+
+// The 8 codes that start v codes into packed chunk u (0 <= v < 8): chunks u and u + 1 funnel-shifted.
+// The word after the last chunk exists (and is only ever shifted out).
+template <int BITS>
+__device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_t &w0, uint32_t &w1)
+{
+    if constexpr (BITS == 4) {
+        const uint32_t lo = pk[u], hi = pk[u + 1];
+        w0 = __builtin_amdgcn_alignbit(hi, lo, 4 * v); // ({hi, lo} >> 4v), low 32 bits
+        w1 = 0;
+    } else {
+        const uint2 a = reinterpret_cast<const uint2 *>(pk)[u], b = reinterpret_cast<const uint2 *>(pk)[u + 1];
+        const uint64_t A = (uint64_t)a.x | ((uint64_t)a.y << 32), B = (uint64_t)b.x | ((uint64_t)b.y << 32);
+        uint64_t r;
+        if constexpr (BITS == 6) {
+            r = ((A >> (6 * v)) | (B << (48 - 6 * v))) & 0xffffffffffffull;
+        } else {
+            const uint64_t up = B << ((64 - 8 * v) & 63);
+            r = (A >> (8 * v)) | (v ? up : 0ull);
+        }
+        w0 = (uint32_t)r;
+        w1 = (uint32_t)(r >> 32);
+    }
+}
+
 // GAM_REG: the lane's share of gamma stays in registers for the lifetime of the workgroup; otherwise it
 // is re-read (from L2) for every row, which frees 8 registers per chunk.
-template <typename XT, int BITS, int S_T, int ITERS, int NT_MAX, bool GAM_REG, bool LAYER>
+template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, bool LAYER>
 __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
 {
     extern __shared__ float lds[];
-    float *ylds = lds;              // [8 * S_T]        y, transposed by 8
-    float *exc = lds + GROUP * S_T; // [8 * n_general]  reassembled channels of the general groups
-    float *zero = exc + GROUP * a.n_general; // [4] a zero: the "second source" of single-entry items
-    int4 *longs = reinterpret_cast<int4 *>(zero + 4); // [n_long] {LDS index of src, dest, scale, pos} of long rows
+    float *pub = lds;                         // [8 * n_pub]      y of the chunks that general groups read
+    float *zero = pub + GROUP * a.n_pub;      // [4] a zero: the "second source" of single-entry items
+    float *exc = zero + 4;                    // [8 * n_general]  reassembled channels of the general groups
+    int4 *longs = reinterpret_cast<int4 *>(exc + GROUP * a.n_general); // [n_long] entries of the long rows
+    uint32_t *pk = reinterpret_cast<uint32_t *>(longs + a.n_long);     // [(n_chunks + 1) * PKW] packed codes, input order
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
     // bf16 rows are prefetched one row ahead; fp32 rows would need twice the registers and are not
     constexpr bool PREFETCH = sizeof(XT) == 2;
     constexpr int ITEMS_REG = ITERS >= 4 ? ITERS : ITERS + 1; // general-group entries a lane keeps in registers
+    constexpr int W = PKW<BITS>;
+    constexpr uint32_t NOT_PUBLISHED = 0xffffffu;
 
-    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nwaves = nt >> 6;
-    const int n_chunks = (a.C + GROUP - 1) / GROUP;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
+    const int n_chunks = a.n_chunks;
     const int n_items = a.n_general * GROUP;
     const float inf = __builtin_inff();
-    constexpr bool layer = LAYER;
 
     // ---- per-lane state that outlives the rows
     float gam[GAM_REG ? ITERS : 1][GROUP];
-    uint32_t pass[ITERS];
-    int32_t desc[ITERS];
+    uint32_t chunkw[ITERS]; // pass bits | staging slot << 8 of the lane's input chunks
+    int32_t work[ITERS];    // work-list entries of the lane's output groups
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int i = tid + it * nt;
-        pass[it] = i < n_chunks ? (uint32_t)a.passes[i] : 0u;
-        desc[it] = i < a.n_groups_pad ? a.desc[i] : WORK_NONE; // work-list entry of this lane and step
+        chunkw[it] = i < n_chunks ? (uint32_t)a.chunks[i] : NOT_PUBLISHED << 8;
+        work[it] = i < a.n_work ? a.work[i] : WORK_NONE;
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
     }
-    for (int j = tid; j < a.n_long; j += nt) {
-        int4 le = reinterpret_cast<const int4 *>(a.longs)[j];
-        le.x = (le.x & 7) * S_T + (le.x >> 3);
-        longs[j] = le;
-    }
+    for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
     if (tid < 4) zero[tid] = 0.0f;
+    if (tid < W) pk[n_chunks * W + tid] = 0u;
     if (tid < 16) { // reduction slots of waves that do not exist hold the identity
         red_d[0][tid] = 0.0;
         red_d[1][tid] = 0.0;
@@ -325,33 +363,25 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         red_f[16 + tid] = -inf;
         red_i[tid] = 0;
     }
-    __syncthreads();
-    // general-group entries of this lane: {LDS index of source 0 | LDS index of source 1 << 16, scale}
-    // (the second index of a single-entry item points at the zero); for a long row (bit m of long_mask)
-    // the second word is first | count << 24 into the table of long rows
+    // general-group entries of this lane: {staged position of source 0 | of source 1 << 16, scale};
+    // long rows (bit m of long_mask) and unused slots read the zero
+    const uint32_t zero_at = (uint32_t)(GROUP * a.n_pub);
     int2 item[ITEMS_REG];
     uint32_t long_mask = 0;
 #pragma unroll
     for (int m = 0; m < ITEMS_REG; ++m) {
         const int j = tid + m * nt;
-        item[m] = make_int2(0, 0);
+        item[m] = make_int2((int32_t)(zero_at | (zero_at << 16)), 0);
         if (j < n_items) {
             const int2 e = reinterpret_cast<const int2 *>(a.items)[j];
-            item[m].y = e.y;
-            if (e.x == ITEM_LONG) {
-                long_mask |= 1u << m;
-            } else {
-                const uint32_t s0 = (uint32_t)e.x & 0xffffu, s1 = (uint32_t)e.x >> 16;
-                const uint32_t i0 = (s0 & 7) * S_T + (s0 >> 3);
-                const uint32_t i1 = s1 == 0xffffu ? (uint32_t)(zero - lds) : (s1 & 7) * S_T + (s1 >> 3);
-                item[m].x = (int32_t)(i0 | (i1 << 16)); // float indices into lds, both below 65536
-            }
+            if (e.x == ITEM_LONG) long_mask |= 1u << m;
+            else item[m] = e;
         }
     }
 
     const XT *xbase = reinterpret_cast<const XT *>(a.x);
     Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
-    int64_t row = blockIdx.x;
+    int64_t row = blockIdx.x, done_row = -1;
     if (PREFETCH && row < a.N) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
@@ -360,12 +390,24 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         }
     }
 
+    // rowsum of a finished row: the waves' partial sums are complete once a barrier has passed
+    auto finish_rowsum = [&]() {
+        if (wave == 0 && done_row >= 0) {
+            int32_t s = red_i[lane & 15];
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR1, 0xf, 0xf, false);
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR2, 0xf, 0xf, false);
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_HALF_MIRROR, 0xf, 0xf, false);
+            s += __builtin_amdgcn_update_dpp(0, s, DPP_MIRROR, 0xf, 0xf, false);
+            if (lane == 0) a.rowsum[done_row] = s;
+        }
+    };
+
     for (; row < a.N; row += gridDim.x) {
         // Everything derived from the plan (LDS addresses, masks, shifts) costs a handful of
         // instructions per row to recompute, but a register each to keep: make the optimiser
         // recompute it by hiding that the plan registers do not change from row to row.
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) asm volatile("" : "+v"(desc[it]), "+v"(pass[it]));
+        for (int it = 0; it < ITERS; ++it) asm volatile("" : "+v"(work[it]), "+v"(chunkw[it]));
 #pragma unroll
         for (int m = 0; m < ITEMS_REG; ++m) asm volatile("" : "+v"(item[m].x), "+v"(item[m].y));
 
@@ -389,116 +431,144 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
         }
 
-        // row statistics in fp64 (chunks past C hold zeros: load_raw pads)
+        // row statistics in fp64 (two interleaved partial sums per lane: the additions do not wait for
+        // one another; the order is fixed, so the result is reproducible)
         float mu = 0.0f, rstd = 1.0f;
         if (!LAYER && a.norm == QLLM_NORM_RMS) {
-            double q = 0.0;
+            double q0 = 0.0, q1 = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
                 if (tid + it * nt < n_chunks) {
                     float v[GROUP];
                     widen(raw[it], v);
 #pragma unroll
-                    for (int j = 0; j < GROUP; ++j) {
-                        const double d = (double)v[j];
-                        q = __builtin_fma(d, d, q);
+                    for (int j = 0; j < GROUP; j += 2) {
+                        const double d0 = (double)v[j], d1 = (double)v[j + 1];
+                        q0 = __builtin_fma(d0, d0, q0);
+                        q1 = __builtin_fma(d1, d1, q1);
                     }
                 }
             }
-            q = block_sum(q, red_d[0], wave, lane);
-            rstd = rsqrt_to_f32(q * a.inv_C + (double)a.eps);
+            const double q = wave_sum(q0 + q1);
+            if (lane == 0) red_d[0][wave] = q;
+            __syncthreads(); // also: the previous row's last LDS reads are over
+            finish_rowsum();
+            rstd = rsqrt_to_f32(total16(red_d[0], lane) * a.inv_C + (double)a.eps);
         } else if constexpr (LAYER) {
-            double s = 0.0;
+            double s0 = 0.0, s1 = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
                 if (tid + it * nt < n_chunks) {
                     float v[GROUP];
                     widen(raw[it], v);
 #pragma unroll
-                    for (int j = 0; j < GROUP; ++j) s += (double)v[j];
-                }
-            }
-            s = block_sum(s, red_d[0], wave, lane);
-            const double mu64 = s * a.inv_C;
-            double q = 0.0;
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) {
-                const int c0 = (tid + it * nt) * GROUP;
-                if (c0 < a.C) {
-                    float v[GROUP];
-                    widen(raw[it], v);
-#pragma unroll
-                    for (int j = 0; j < GROUP; ++j) {
-                        const double d = (double)v[j] - mu64;
-                        q = __builtin_fma(d, d, q);
+                    for (int j = 0; j < GROUP; j += 2) {
+                        s0 += (double)v[j];
+                        s1 += (double)v[j + 1];
                     }
                 }
             }
-            q = block_sum(q, red_d[1], wave, lane);
+            const double s = wave_sum(s0 + s1);
+            if (lane == 0) red_d[0][wave] = s;
+            __syncthreads(); // also: the previous row's last LDS reads are over
+            finish_rowsum();
+            const double mu64 = total16(red_d[0], lane) * a.inv_C;
+            double q0 = 0.0, q1 = 0.0;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                if (tid + it * nt < n_chunks) {
+                    float v[GROUP];
+                    widen(raw[it], v);
+#pragma unroll
+                    for (int j = 0; j < GROUP; j += 2) {
+                        const double d0 = (double)v[j] - mu64, d1 = (double)v[j + 1] - mu64;
+                        q0 = __builtin_fma(d0, d0, q0);
+                        q1 = __builtin_fma(d1, d1, q1);
+                    }
+                }
+            }
+            const double q = wave_sum(q0 + q1);
+            if (lane == 0) red_d[1][wave] = q;
+            __syncthreads();
             mu = (float)mu64;
-            rstd = rsqrt_to_f32(q * a.inv_C + (double)a.eps);
+            rstd = rsqrt_to_f32(total16(red_d[1], lane) * a.inv_C + (double)a.eps);
+        } else {
+            __syncthreads(); // the previous row's last LDS reads are over
+            finish_rowsum();
         }
 
-        // ---- y into LDS; min/max over the channels that pass unscaled
+        // ---- y, kept in registers; staged in LDS where a general group reads it; min/max over the
+        //      channels that pass unscaled
+        float y[ITERS][GROUP];
         float mn = inf, mx = -inf;
+        const float *gamma_row = a.gamma; // opaque, so that the per-row loads of gamma stay per row
+        asm volatile("" : "+s"(gamma_row));
         const bool shift = LAYER && a.beta != nullptr;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int i = tid + it * nt;
             float gjit[GROUP];
-            if constexpr (!GAM_REG) load_gamma(gjit, a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
+            if constexpr (!GAM_REG) load_gamma(gjit, gamma_row, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
             const float *g8 = GAM_REG ? gam[GAM_REG ? it : 0] : gjit;
             if (i < n_chunks) {
-                float y[GROUP];
                 forget(raw[it]);
-                widen(raw[it], y);
+                widen(raw[it], y[it]);
 #pragma unroll
                 for (int j = 0; j < GROUP; ++j) {
-                    float t = y[j];
+                    float t = y[it][j];
                     if constexpr (LAYER) t = t - mu;
                     t = t * rstd;
                     t = t * g8[j];
                     if constexpr (LAYER) {
                         if (shift) t = t + a.beta[i * GROUP + j];
                     }
-                    y[j] = t;
-                    ylds[j * S_T + i] = t;
+                    y[it][j] = t;
                 }
-                if (pass[it] == 0xffu) {
+                const uint32_t slot = chunkw[it] >> 8;
+                if (slot != NOT_PUBLISHED) {
+                    float4 *dst = reinterpret_cast<float4 *>(pub + slot * GROUP);
+                    dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
+                    dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
+                }
+                if ((chunkw[it] & 0xffu) == 0xffu) {
 #pragma unroll
-                    for (int j = 0; j < GROUP; ++j) {
-                        mn = fminf(mn, y[j]);
-                        mx = fmaxf(mx, y[j]);
+                    for (int j = 0; j < GROUP; j += 2) {
+                        mn = fminf(fminf(mn, y[it][j]), y[it][j + 1]);
+                        mx = fmaxf(fmaxf(mx, y[it][j]), y[it][j + 1]);
                     }
                 }
+            } else {
+#pragma unroll
+                for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
             }
         }
         // Chunks in which some channel does not pass (an outlier that is split, a merged source) are
         // few, but nearly every wave has a lane with one: handled here, one per lane and turn, so a
         // wave spends as many turns as its busiest lane has such chunks (one or two), not ITERS.
-        // A lane re-reads its own LDS writes: in order, no barrier needed.
+        // Such a chunk is always staged; a lane re-reads its own LDS writes (in order, no barrier).
         {
             uint32_t todo = 0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it)
-                if (pass[it] != 0xffu && pass[it] != 0u) todo |= 1u << it;
+                if ((chunkw[it] & 0xffu) != 0xffu && (chunkw[it] & 0xffu) != 0u) todo |= 1u << it;
             while (todo) {
                 const int it = __builtin_ctz(todo);
                 todo &= todo - 1;
-                uint32_t m = pass[0];
+                uint32_t cw = chunkw[0];
 #pragma unroll
-                for (int q = 1; q < ITERS; ++q) m = it == q ? pass[q] : m;
-                const float *col = ylds + tid + it * nt;
+                for (int q = 1; q < ITERS; ++q) cw = it == q ? chunkw[q] : cw;
+                const float4 *c4 = reinterpret_cast<const float4 *>(pub + (cw >> 8) * GROUP);
+                const float4 lo = c4[0], hi = c4[1];
+                const float yv[GROUP] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
                 for (int j = 0; j < GROUP; ++j) {
-                    const float yv = col[j * S_T];
-                    const bool in = m >> j & 1u;
-                    mn = fminf(mn, in ? yv : inf);
-                    mx = fmaxf(mx, in ? yv : -inf);
+                    const bool in = cw >> j & 1u;
+                    mn = fminf(mn, in ? yv[j] : inf);
+                    mx = fmaxf(mx, in ? yv[j] : -inf);
                 }
             }
         }
-        __syncthreads(); // y complete
+        __syncthreads(); // staged y complete
 
         // ---- steps a2 + a3 for the general groups: sub-channels (scale 1/T), merged channels
         //      (scale 1/g each) and the plain channels that share a group of 8 with them.
@@ -506,7 +576,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         {
             float y0[ITEMS_REG], y1[ITEMS_REG];
 #pragma unroll
-            for (int m = 0; m < ITEMS_REG; ++m) { // long rows and unused slots read index 0, harmlessly
+            for (int m = 0; m < ITEMS_REG; ++m) {
                 const uint32_t p = (uint32_t)item[m].x;
                 y0[m] = lds[p & 0xffffu];
                 y1[m] = lds[p >> 16];
@@ -530,7 +600,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             // ends up with the row's value.
             for (int base = 0; base < a.n_long; base += nt) {
                 const int e = base + tid;
-                int4 le = make_int4(0, -1, 0, 0);
+                int4 le = make_int4((int32_t)zero_at, -1, 0, 0);
                 if (e < a.n_long) le = longs[e];
                 const float p = __int_as_float(le.z) * lds[le.x];
                 float acc = p;
@@ -552,7 +622,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             red_f[wave] = mn;
             red_f[16 + wave] = mx;
         }
-        __syncthreads(); // also: exc complete
+        __syncthreads(); // also: the general groups' values are complete
         mn = red_f[lane & 15];
         mx = red_f[16 + (lane & 15)];
         mn = fminf(mn, dpp_f32<DPP_XOR1>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR1>(mx));
@@ -570,85 +640,66 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         if (fast) beta = -rne_product_fast(mn, inv);
         else beta = (int32_t)fmin(fmax(-rne_product_slow(mn, inv), -2147483647.0), 2147483647.0);
 
-        // ---- step a4: codes
+        // ---- step a4, first half: codes of the lane's own chunks, packed in input order
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int i = tid + it * nt;
+            if (i < n_chunks) {
+                uint32_t w0, w1;
+                quant_pack<BITS>(y[it], 0xffu, fast, inv, beta, w0, w1);
+                if constexpr (W == 1) pk[i] = w0;
+                else reinterpret_cast<uint2 *>(pk)[i] = make_uint2(w0, w1);
+            }
+        }
+        __syncthreads(); // packed words complete
+
+        // ---- step a4, second half: the lane's output groups
         int32_t sum = 0;
         uint8_t *out_row = a.codes + row * a.row_bytes;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int32_t e = desc[it];
+            const int32_t e = work[it];
             const int kind = (uint32_t)e >> 28;
             if (kind != KIND_NONE) {
                 const int g = (e >> 15) & 0x1fff, d = e & 0x7fff;
-                float val[GROUP];
-                uint32_t live = 0xffu;
-                const int vv = d & 7;
-                int rot = vv;
-                const int v0 = __builtin_amdgcn_readfirstlane(vv);
-                if (__all(kind == KIND_PLAIN && vv == v0)) {
-                    // the usual case (the work list is sorted for it): the whole wave reads plain groups
-                    // with the same misalignment, every address is one register plus an immediate
-                    const float *ycol = ylds + (d >> 3);
-                    switch (v0) {
-                    case 0: read_plain<S_T, 0>(ycol, val); break;
-                    case 1: read_plain<S_T, 1>(ycol, val); break;
-                    case 2: read_plain<S_T, 2>(ycol, val); break;
-                    case 3: read_plain<S_T, 3>(ycol, val); break;
-                    case 4: read_plain<S_T, 4>(ycol, val); break;
-                    case 5: read_plain<S_T, 5>(ycol, val); break;
-                    case 6: read_plain<S_T, 6>(ycol, val); break;
-                    default: read_plain<S_T, 7>(ycol, val); break;
-                    }
-                } else if (kind == KIND_PLAIN) {
-                    const int u = d >> 3;
-#pragma unroll
-                    for (int k = 0; k < GROUP; ++k) val[k] = ylds[k * S_T + u + (k < vv ? 1 : 0)];
+                uint32_t w0 = 0, w1 = 0;
+                if (kind == KIND_PLAIN) {
+                    funnel<BITS>(pk, d >> 3, d & 7, w0, w1);
                 } else if (kind == KIND_GENERAL) {
                     const float4 e0 = *reinterpret_cast<const float4 *>(exc + d * GROUP);
                     const float4 e1 = *reinterpret_cast<const float4 *>(exc + d * GROUP + 4);
-                    val[0] = e0.x; val[1] = e0.y; val[2] = e0.z; val[3] = e0.w;
-                    val[4] = e1.x; val[5] = e1.y; val[6] = e1.z; val[7] = e1.w;
-                    rot = 0;
+                    const float val[GROUP] = {e0.x, e0.y, e0.z, e0.w, e1.x, e1.y, e1.z, e1.w};
                     const int left = a.C_out - g * GROUP;
-                    if (left < GROUP) live = (1u << left) - 1u;
-                } else {
-                    rot = 0;
-                    live = 0u;
-#pragma unroll
-                    for (int k = 0; k < GROUP; ++k) val[k] = 0.0f;
+                    quant_pack<BITS>(val, left < GROUP ? (1u << left) - 1u : 0xffu, fast, inv, beta, w0, w1);
                 }
-                sum += pack_store<BITS>(val, live, rot, fast, inv, beta, out_row, g);
+                store_group<BITS>(out_row, g, w0, w1);
+                sum += code_sum<BITS>(w0, w1);
             }
         }
         sum = wave_sum_i32(sum);
-        if (lane == 0) red_i[wave] = sum;
-        __syncthreads(); // row done: LDS may be overwritten, red_i is complete
-        if (wave == 0) {
-            int32_t s = red_i[lane & 15];
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR1, 0xf, 0xf, false);
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR2, 0xf, 0xf, false);
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_HALF_MIRROR, 0xf, 0xf, false);
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_MIRROR, 0xf, 0xf, false);
-            if (lane == 0) {
+        if (lane == 0) red_i[wave] = sum; // read after the next barrier
+        if (tid == 0) {
             a.alpha[row] = alpha;
             a.zero[row] = beta;
-            a.rowsum[row] = s;
-            }
         }
+        done_row = row;
     }
+    __syncthreads();
+    finish_rowsum();
 }
 
 struct Shape {
-    int s_t, iters, nt;
+    int iters, nt;
 };
 
-// Smallest compiled (S, ITERS) that holds `units` 8-channel groups, and the workgroup size for it.
+// Chunks (or output groups) per lane and the workgroup size for a row of `units` of them.
 Shape pick_shape(int units)
 {
     Shape s;
-    if (units <= 256) s = {256, 1, 0};
-    else if (units <= 1024) s = {1024, 2, 0};
-    else if (units <= 2048) s = {2048, 2, 0};
-    else s = {4096, 4, 0};
+    if (units <= 256) s = {1, 0};
+    else if (units <= 2048) s = {2, 0};
+    else if (units <= 3840) s = {5, 0};
+    else s = {4, 0};
     s.nt = ((units + s.iters - 1) / s.iters + 63) / 64 * 64;
     return s;
 }
@@ -698,10 +749,10 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
 template <typename XT, int BITS, bool LAYER>
 int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (sh.s_t == 256) return launch(fused_planned_kernel<XT, BITS, 256, 1, 256, true, LAYER>, a, sh, lds, stream);
-    if (sh.s_t == 1024) return launch(fused_planned_kernel<XT, BITS, 1024, 2, 512, true, LAYER>, a, sh, lds, stream);
-    if (sh.s_t == 2048) return launch(fused_planned_kernel<XT, BITS, 2048, 2, 1024, true, LAYER>, a, sh, lds, stream);
-    return launch(fused_planned_kernel<XT, BITS, 4096, 4, 1024, true, LAYER>, a, sh, lds, stream);
+    if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 256, true, LAYER>, a, sh, lds, stream);
+    if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, LAYER>, a, sh, lds, stream);
+    if (sh.iters == 5) return launch(fused_planned_kernel<XT, BITS, 5, 768, true, LAYER>, a, sh, lds, stream);
+    return launch(fused_planned_kernel<XT, BITS, 4, 1024, false, LAYER>, a, sh, lds, stream);
 }
 
 template <typename XT>
@@ -721,11 +772,11 @@ int32_t dispatch_bits(const FusedArgs &a, int bits, const Shape &sh, size_t lds,
 
 int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t bits, hipStream_t stream)
 {
-    const int n_chunks = (a.C + GROUP - 1) / GROUP;
-    const int units = n_chunks > a.n_groups_pad ? n_chunks : a.n_groups_pad;
+    const int units = a.n_chunks > a.n_work ? a.n_chunks : a.n_work;
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
     const Shape sh = pick_shape(units);
-    const size_t lds = ((size_t)sh.s_t + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16;
+    const size_t lds = ((size_t)a.n_pub + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16 +
+                       ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8);
     if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
     const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
     if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // general-group entries live in registers

@@ -138,7 +138,7 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
 {
     if (!row_ptr || !src || !scale || !plan_len || !n_general) return QLLM_ERR_NULL;
     if (C_in <= 0 || C_out <= 0 || C_in > QLLM_MAX_CHANNELS || C_out > QLLM_MAX_CHANNELS) return QLLM_ERR_SHAPE;
-    const int64_t G = QLLM_MAP_GROUP;
+    const int64_t G = QLLM_MAP_GROUP, HEAD = QLLM_PLAN_HEAD;
     const int64_t n_groups = (C_out + G - 1) / G, n_chunks = (C_in + G - 1) / G;
     auto plain_source = [&](int64_t g) -> int32_t { // first source of a plain group, or -1
         const int64_t c0 = g * G;
@@ -158,44 +158,59 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     // would straddle a multiple of 64.
     constexpr int64_t WAVE = 64;
     auto place_long = [&](int64_t at, int64_t n) { return at % WAVE + n > WAVE ? (at + WAVE - 1) / WAVE * WAVE : at; };
+    // Sizes: general groups, long-row entries, and the input chunks that any general group reads
+    // ("published": the kernel stages their y in LDS, the only y that lanes exchange).
+    std::vector<int32_t> pub_slot((size_t)n_chunks, -1), desc((size_t)n_groups);
+    std::vector<uint8_t> pass((size_t)n_chunks, 0);
     int64_t general = 0, n_long = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
-        if (plain_source(g) >= 0) continue;
+        const int32_t d = desc[(size_t)g] = plain_source(g);
+        if (d >= 0) {
+            for (int j = 0; j < G; ++j) pass[(size_t)((d + j) / G)] |= (uint8_t)(1 << ((d + j) % G));
+            continue;
+        }
         ++general;
         for (int64_t ch = g * G; ch < std::min(C_out, (g + 1) * G); ++ch) {
-            if (row_ptr[ch + 1] <= row_ptr[ch]) return QLLM_ERR_MAP;
+            const int64_t n = row_ptr[ch + 1] - row_ptr[ch];
+            if (n < 1) return QLLM_ERR_MAP;
+            for (int32_t e = row_ptr[ch]; e < row_ptr[ch + 1]; ++e) {
+                if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
+                pub_slot[(size_t)(src[e] / G)] = 0;
+            }
             if (!compact(ch)) {
-                const int64_t n = row_ptr[ch + 1] - row_ptr[ch];
                 if (n > WAVE) return QLLM_ERR_MAP; // a long row is summed inside one wavefront
                 n_long = place_long(n_long, n) + n;
             }
         }
     }
-    if (n_long > 0xffffff) return QLLM_ERR_MAP;
+    // a chunk of which only some channels pass is staged too (the kernel takes its min/max from there)
+    for (int64_t c = 0; c < n_chunks; ++c)
+        if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) pub_slot[(size_t)c] = 0;
+    int64_t n_pub = 0;
+    for (int64_t c = 0; c < n_chunks; ++c)
+        if (pub_slot[(size_t)c] == 0) pub_slot[(size_t)c] = (int32_t)n_pub++;
+    if (n_long > 0xffffff || G * n_pub + 4 > 0xffff) return QLLM_ERR_MAP;
     *n_general = general;
     const int64_t n_work = (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G; // groups incl. zero padding
-    const int64_t items_off = (8 + n_work + 3) / 4 * 4; // items are read 8 bytes at a time
-    const int64_t longs_off = (items_off + general * G * 2 + n_chunks + 3) / 4 * 4; // read 16 bytes at a time
-    *plan_len = longs_off + 4 * n_long;
+    auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
+    const int64_t off_work = HEAD, off_chunks = round4(off_work + n_work), off_items = round4(off_chunks + n_chunks);
+    const int64_t off_longs = round4(off_items + general * G * 2);
+    *plan_len = off_longs + 4 * n_long;
     if (!plan) return QLLM_OK;
 
-    int32_t *work = plan + 8, *items = plan + items_off, *passes = items + general * G * 2;
-    std::vector<int32_t> desc((size_t)n_groups);
     std::fill(plan, plan + *plan_len, 0);
-    plan[0] = 0x514c4d50; plan[1] = 3; plan[2] = (int32_t)C_in; plan[3] = (int32_t)C_out;
-    plan[4] = (int32_t)n_work; plan[5] = (int32_t)general; plan[6] = (int32_t)n_chunks; plan[7] = (int32_t)n_long;
-    std::fill(passes, passes + n_chunks, 0);
-    int32_t *longs = plan + longs_off; // zero-filled: padding entries are {0, 0 (below: -1), 0.0f, 0}
-    for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1;
+    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 4, C_in, C_out, n_work, general, n_chunks, n_long,
+                                          n_pub, off_work, off_chunks, off_items, off_longs, *plan_len, 0, 0};
+    for (int64_t k = 0; k < HEAD; ++k) plan[k] = (int32_t)head[k];
+    int32_t *work = plan + off_work, *chunks = plan + off_chunks, *items = plan + off_items, *longs = plan + off_longs;
+    for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1; // padding entries are {0, -1, 0.0f, 0}
+    const uint32_t zero_at = (uint32_t)(G * n_pub); // the staged zero sits right after the published chunks
+    auto staged = [&](int32_t channel) { return (uint32_t)(pub_slot[(size_t)(channel / G)] * G + channel % G); };
+    for (int64_t c = 0; c < n_chunks; ++c) chunks[c] = (int32_t)(((uint32_t)pub_slot[(size_t)c] << 8) | pass[(size_t)c]); // -1: 0xffffff
     int64_t slot = 0, long_at = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
-        const int32_t d = plain_source(g);
-        if (d >= 0) {
-            desc[g] = d;
-            for (int j = 0; j < G; ++j) passes[(d + j) / G] |= 1 << ((d + j) % G);
-            continue;
-        }
-        desc[g] = (int32_t)(-(slot + 1));
+        if (desc[(size_t)g] >= 0) continue;
+        desc[(size_t)g] = (int32_t)(-(slot + 1));
         for (int k = 0; k < G; ++k) {
             int32_t *it = items + (slot * G + k) * 2;
             const int64_t ch = g * G + k;
@@ -205,40 +220,33 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
                 continue;
             }
             const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
-            if (n < 1) return QLLM_ERR_MAP;
-            for (int32_t e = e0; e < e0 + n; ++e)
-                if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
-            if (!compact(ch)) { // entries go to the table of long rows: {src, destination or -1, scale, position}
+            if (!compact(ch)) { // entries go to the table of long rows: {staged source, destination or -1, scale, position}
                 long_at = place_long(long_at, n);
                 it[0] = -2;
                 it[1] = (int32_t)((uint32_t)long_at | ((uint32_t)n << 24));
                 for (int32_t e = e0; e < e0 + n; ++e, ++long_at) {
-                    longs[4 * long_at] = src[e];
+                    longs[4 * long_at] = (int32_t)staged(src[e]);
                     longs[4 * long_at + 1] = e == e0 + n - 1 ? (int32_t)(slot * G + k) : -1;
                     std::memcpy(&longs[4 * long_at + 2], &scale[e], 4);
                     longs[4 * long_at + 3] = e - e0;
                 }
                 continue;
             }
-            const uint32_t second = n == 2 ? (uint32_t)src[e0 + 1] : 0xffffu;
-            it[0] = (int32_t)((uint32_t)src[e0] | (second << 16));
+            const uint32_t second = n == 2 ? staged(src[e0 + 1]) : zero_at;
+            it[0] = (int32_t)(staged(src[e0]) | (second << 16));
             std::memcpy(&it[1], &scale[e0], 4);
         }
         ++slot;
     }
     // work list of the code-producing step, one entry per group of 8 output channels (zero padding
-    // included): kind << 28 | group << 15 | d.  Plain groups first, ordered by the misalignment d & 7 of
-    // their source so that the lanes of a wavefront mostly share it, then general groups (d = their
-    // number), then padding groups.
-    std::vector<int32_t> order;
-    order.reserve((size_t)n_work);
-    for (int v = 0; v < G; ++v)
-        for (int64_t g = 0; g < n_groups; ++g)
-            if (desc[g] >= 0 && (desc[g] & 7) == v) order.push_back((int32_t)(((uint32_t)g << 15) | (uint32_t)desc[g]));
+    // included): kind << 28 | group << 15 | d.  Plain groups first, then general groups (d = their
+    // number), then padding groups, so that all but two wavefronts of the kernel are of one kind.
+    int64_t at = 0;
     for (int64_t g = 0; g < n_groups; ++g)
-        if (desc[g] < 0) order.push_back((int32_t)((1u << 28) | ((uint32_t)g << 15) | (uint32_t)(-(desc[g] + 1))));
-    for (int64_t g = n_groups; g < n_work; ++g) order.push_back((int32_t)((2u << 28) | ((uint32_t)g << 15)));
-    std::copy(order.begin(), order.end(), work);
+        if (desc[g] >= 0) work[at++] = (int32_t)(((uint32_t)g << 15) | (uint32_t)desc[g]);
+    for (int64_t g = 0; g < n_groups; ++g)
+        if (desc[g] < 0) work[at++] = (int32_t)((1u << 28) | ((uint32_t)g << 15) | (uint32_t)(-(desc[g] + 1)));
+    for (int64_t g = n_groups; g < n_work; ++g) work[at++] = (int32_t)((2u << 28) | ((uint32_t)g << 15));
     return QLLM_OK;
 }
 

@@ -50,7 +50,7 @@ def test_packed_row_bytes_and_workspace():
 
 
 def _structs():
-    m = b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, None, 0, 0)
+    m = b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, None)
     q = b._QAct(0x1000, 0x1000, 0x1000, 0x1000)
     w = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000)
     return m, q, w
@@ -76,12 +76,21 @@ def test_fused_entry_point_rejects_bad_arguments_before_launching():
     assert call(ldx=63) == -2 and call(N=-1) == -2
     assert call(bits=5) == -3 and call(bits=2) == -3
     assert call(gamma=G + 4) == -6
-    bad_map = b._Map(65, 64, 64, 0x1000, 0x1000, 0x1000, None, 0, 0)      # C_in differs from C
+    bad_map = b._Map(65, 64, 64, 0x1000, 0x1000, 0x1000, None)      # C_in differs from C
     assert call(mp=bad_map) == -2
-    assert call(mp=b._Map(64, 64, 64, None, 0x1000, 0x1000, None, 0, 0)) == -1
-    assert call(mp=b._Map(64, 64, 10, 0x1000, 0x1000, 0x1000, None, 0, 0)) == -2
+    assert call(mp=b._Map(64, 64, 64, None, 0x1000, 0x1000, None)) == -1
+    assert call(mp=b._Map(64, 64, 10, 0x1000, 0x1000, 0x1000, None)) == -2
     assert call(qa=b._QAct(0x1008, 0x1000, 0x1000, 0x1000)) == -6
     assert call(qa=b._QAct(0x1000, None, 0x1000, 0x1000)) == -1
+    # a plan whose header (host copy) is not that of this map is refused before anything is launched
+    head = (C.c_int32 * b.PLAN_HEAD)()
+    assert call(mp=b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, 0x4000, head)) == -5
+    head[:] = [0x514C4D50, 4, 64, 64, 32, 0, 8, 0, 0, 16, 48, 56, 56, 56, 0, 0]
+    head[2] = 72                                                      # a plan made for another C_in
+    assert call(mp=b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, 0x4000, head)) == -5
+    head[2], head[13] = 64, 60                                        # length does not match the parts
+    assert call(mp=b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, 0x4000, head)) == -5
+    assert call(mp=b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, 0x4004, head)) == -6
     assert call(N=0) == 0                                             # empty batch: nothing to do
 
 
@@ -144,29 +153,31 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
     assert np.array_equal(r["scale"], c.scale)
     assert b.qllm_check_map_host(r["row_ptr"], r["src"], r["scale"], C) == 0
-    # the plan: header, work list, general-group entries, pass bits, long rows
-    plan, n_general = r["plan"], r["plan_general"]
+    # the plan: header, work list, per-chunk words, general-group entries, long rows
+    plan = r["plan"]
     n_groups, n_chunks, n_work = (c.K + 7) // 8, (C + 7) // 8, (c.K + 255) // 256 * 32
-    assert plan[:7].tolist() == [0x514C4D50, 3, C, c.K, n_work, n_general, n_chunks]
-    work = plan[8:8 + n_work].astype(np.int64) & 0xFFFFFFFF
+    n_general, _, n_long, n_pub, off_work, off_chunks, off_items, off_longs, plan_len = plan[5:14].tolist()
+    assert plan[:5].tolist() == [0x514C4D50, 4, C, c.K, n_work] and plan[6] == n_chunks and plan[14:16].tolist() == [0, 0]
+    assert off_work == 16 and plan_len == plan.size == off_longs + 4 * n_long
+    assert off_chunks >= off_work + n_work and off_items >= off_chunks + n_chunks and off_longs >= off_items + 16 * n_general
+    assert off_chunks % 4 == 0 and off_items % 4 == 0 and off_longs % 4 == 0
+    work = plan[off_work:off_work + n_work].astype(np.int64) & 0xFFFFFFFF
     kind, grp, dd = work >> 28, (work >> 15) & 0x1FFF, work & 0x7FFF
     assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
     assert np.all(np.diff(kind) >= 0) and np.all(kind[grp >= n_groups] == 2) and np.all(kind[grp < n_groups] < 2)
+    assert np.all(np.diff(kind * 8192 + grp) > 0)                # by kind, then by group
     plain = kind == 0
-    key = (dd[plain] & 7) * 8192 + grp[plain]                     # plain groups: by misalignment, then by group
-    assert np.all(np.diff(key) > 0)
     desc = np.full(n_groups, -1, np.int64)
     desc[grp[plain]] = dd[plain]
     gen = kind == 1
     desc[grp[gen]] = -(dd[gen] + 1)
-    items_off = (8 + n_work + 3) // 4 * 4
-    items = plan[items_off:items_off + 16 * n_general].reshape(n_general * 8, 2)
-    passes = plan[items_off + 16 * n_general:items_off + 16 * n_general + n_chunks]
-    longs_off = (items_off + 16 * n_general + n_chunks + 3) // 4 * 4
-    longs = plan[longs_off:].reshape(-1, 4)
-    assert longs.shape[0] == plan[7]
-    used = np.zeros(longs.shape[0], bool)
-    assert passes.size == n_chunks and (desc >= 0).sum() > 0.25 * desc.size and (desc < 0).sum() == n_general
+    chunks = plan[off_chunks:off_chunks + n_chunks].astype(np.int64) & 0xFFFFFFFF
+    passes, slots = chunks & 0xFF, chunks >> 8
+    items = plan[off_items:off_items + 16 * n_general].reshape(n_general * 8, 2)
+    longs = plan[off_longs:].reshape(-1, 4)
+    assert longs.shape[0] == n_long
+    used = np.zeros(n_long, bool)
+    assert (desc >= 0).sum() > 0.25 * desc.size and (desc < 0).sum() == n_general
     expect_pass = np.zeros(n_chunks * 8, bool)
     for g in np.nonzero(desc >= 0)[0]:       # a plain group: 8 single entries, scale 1, consecutive sources
         e = c.row_ptr[8 * g:8 * g + 8]
@@ -175,12 +186,20 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
         expect_pass[desc[g]:desc[g] + 8] = True
     assert np.array_equal(np.unpackbits(passes.astype(np.uint8), bitorder="little"), expect_pass.astype(np.uint8))
     assert sorted((-desc[desc < 0] - 1).tolist()) == list(range(n_general))
+    # staging slots: 0 .. n_pub-1 in chunk order; every chunk a general group reads has one, and so has
+    # every chunk of which only some channels pass
+    has = slots != 0xFFFFFF
+    assert np.array_equal(slots[has], np.arange(n_pub))
+    assert np.all(has[(passes != 0) & (passes != 0xFF)])
+    read = np.zeros(n_chunks, bool)
+    stage = lambda ch: int(slots[ch // 8]) * 8 + ch % 8
     for g in np.nonzero(desc < 0)[0]:        # a general group: its entries, channel by channel
         lo, hi = 8 * g, min(8 * g + 8, c.K)
         e = c.row_ptr[lo:hi]
-        plain = (hi - lo == 8 and np.all(np.diff(c.row_ptr[lo:hi + 1]) == 1) and np.all(c.scale[e] == 1.0)
-                 and np.array_equal(c.src[e], c.src[e[0]] + np.arange(8)))
-        assert not plain
+        is_plain = (hi - lo == 8 and np.all(np.diff(c.row_ptr[lo:hi + 1]) == 1) and np.all(c.scale[e] == 1.0)
+                    and np.array_equal(c.src[e], c.src[e[0]] + np.arange(8)))
+        assert not is_plain
+        read[c.src[c.row_ptr[lo]:c.row_ptr[hi]] // 8] = True
         for k in range(8):
             it = items[(-desc[g] - 1) * 8 + k]
             ch = lo + k
@@ -192,7 +211,7 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
                 first = int(it[1]) & 0xFFFFFF
                 assert it[0] == -2 and (int(it[1]) >> 24) & 0xFF == n
                 assert first // 64 == (first + n - 1) // 64             # inside one wavefront's 64 entries
-                assert np.array_equal(longs[first:first + n, 0], c.src[e0:e0 + n])
+                assert longs[first:first + n, 0].tolist() == [stage(s) for s in c.src[e0:e0 + n]]
                 assert np.array_equal(longs[first:first + n, 2].view(np.float32), c.scale[e0:e0 + n])
                 assert np.array_equal(longs[first:first + n, 3], np.arange(n))
                 assert np.all(longs[first:first + n - 1, 1] == -1)
@@ -200,11 +219,12 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
                 assert not used[first:first + n].any()
                 used[first:first + n] = True
                 continue
-            second = c.src[e0 + 1] if n == 2 else 0xFFFF
-            assert int(it[0]) & 0xFFFFFFFF == int(c.src[e0]) | (int(second) << 16)
+            second = stage(c.src[e0 + 1]) if n == 2 else 8 * n_pub
+            assert int(it[0]) & 0xFFFFFFFF == stage(c.src[e0]) | (second << 16)
             assert it[1:2].view(np.float32)[0] == c.scale[e0]
             if n == 2:
                 assert c.scale[e0 + 1] == c.scale[e0]
+    assert np.all(has[read]) and np.all(read[has] | ((passes[has] != 0) & (passes[has] != 0xFF)))
     assert np.all(longs[~used] == np.array([0, -1, 0, 0]))            # padding entries between rows
     # weights: reassembled, quantized per output channel and packed by the library == the oracle's
     q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, w.w_bits)

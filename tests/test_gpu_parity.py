@@ -28,7 +28,7 @@ def device_map(b, c, use_plan=True):
     assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
     assert np.array_equal(r["scale"], c.scale)
     if use_plan:
-        return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C, r["plan"], r["plan_general"])
+        return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C, r["plan"])
     return b.DeviceMap(r["row_ptr"], r["src"], r["scale"], c.C)
 
 
