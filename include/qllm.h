@@ -189,7 +189,7 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  * in qllm_map.plan_head.  Layout (int32 words; every part starts at a multiple of 4 words):
  *   [0..15]  header: magic, version, C_in, C_out, n_work = groups of 8 output channels including the zero
  *            padding to 256 codes, n_general, n_chunks = ceil(C_in/8), n_long, n_pub, then the offsets of
- *            work, chunks, items, longs, then plan_len, 0, 0
+ *            work, chunks, items, longs, then plan_len, n_mask, offset of masks
  *   work     [n_work]: kind << 28 | group << 15 | d.  kind 0 ("plain"): the 8 channels of the group are
  *            single-entry with scale exactly 1 and sources d, d+1, ..., d+7; kind 1: general group number d;
  *            kind 2: padding.  Sorted by kind, then by group
@@ -201,11 +201,13 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  *            (s1 = 8*n_pub, the zero) or two entries of equal scale, s = staged position of the source
  *            channel; {-2, first | count << 24}: any other row (at most 64 entries), its entries are
  *            longs[first .. first + count); channels past C_out repeat the group's first channel
- *   longs    [n_long][4]: {s, dest, scale, pos}: entry pos (0, 1, ...) of a row that is neither of the
- *            two short forms; dest = 8 * (general group number) + k on the row's last entry, -1 elsewhere.
- *            The kernel gives entry e to lane e % 64 of a wavefront and adds a row up lane by lane, so
- *            the table holds padding entries {0, -1, 0.0f, 0} wherever a row would otherwise straddle a
- *            multiple of 64; n_long counts them
+ *   longs    [n_long][4]: {s, dest, scale, pos | most << 8}: entry pos (0, 1, ...) of a row that is
+ *            neither of the two short forms; dest = 8 * (general group number) + k on the row's last
+ *            entry, -1 elsewhere.  The kernel gives entry e to lane e % 64 of a wavefront and adds a row up
+ *            lane by lane, so the table holds padding entries {0, -1, 0.0f, 0 | most << 8} wherever a row
+ *            would otherwise straddle a multiple of 64; n_long counts them; most = the largest pos among
+ *            the (up to) 64 entries that share a wavefront
+ *   masks    [n_mask]: the chunks words whose pass bits are neither all set nor all clear
  * QLLM_ERR_MAP: malformed map, or a row of more than 64 entries (such a map runs without a plan).
  */
 int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,

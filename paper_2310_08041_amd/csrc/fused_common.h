@@ -26,8 +26,8 @@ struct FusedArgs {
     double inv_C; // 1 / C
     const int32_t *row_ptr, *src, *desc;
     const float *scale;
-    const int32_t *work, *chunks, *items, *longs; // the parts of the plan (see qllm_plan_map_host)
-    int32_t n_general, n_long, n_pub, n_work, n_chunks;
+    const int32_t *work, *chunks, *items, *longs, *masks; // the parts of the plan (see qllm_plan_map_host)
+    int32_t n_general, n_long, n_pub, n_work, n_chunks, n_mask;
     int32_t C_out, n_groups, n_groups_pad, S;
     uint8_t *codes;
     int64_t row_bytes;

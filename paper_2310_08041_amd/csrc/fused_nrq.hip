@@ -454,16 +454,19 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     if (map->plan) { // the host copy of the header says where the parts are: see qllm_plan_map_host
         const int32_t *h = map->plan_head;
         if (reinterpret_cast<uintptr_t>(map->plan) & 15u) return QLLM_ERR_ALIGN;
-        if (h[0] != 0x514c4d50 || h[1] != 4 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
+        if (h[0] != 0x514c4d50 || h[1] != 5 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
         const int64_t n_chunks = (C + GROUP - 1) / GROUP, n_work = (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP;
         if (h[4] != n_work || h[6] != n_chunks || h[5] < 0 || h[5] > n_work || h[7] < 0 || h[8] < 0 || h[8] > n_chunks ||
             h[9] != QLLM_PLAN_HEAD || h[10] < h[9] + n_work || h[11] < h[10] + n_chunks ||
-            h[12] < h[11] + 2 * GROUP * (int64_t)h[5] || h[13] != h[12] + 4 * (int64_t)h[7] || ((h[10] | h[11] | h[12]) & 3))
+            h[12] < h[11] + 2 * GROUP * (int64_t)h[5] || h[15] != h[12] + 4 * (int64_t)h[7] || h[14] < 0 || h[14] > n_chunks ||
+            h[13] != h[15] + (int64_t)h[14] || ((h[10] | h[11] | h[12]) & 3))
             return QLLM_ERR_MAP;
         a.work = map->plan + h[9];
         a.chunks = map->plan + h[10];
         a.items = map->plan + h[11];
         a.longs = map->plan + h[12];
+        a.masks = map->plan + h[15];
+        a.n_mask = h[14];
         a.n_work = h[4];
         a.n_general = h[5];
         a.n_chunks = h[6];

@@ -328,6 +328,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     float *exc = zero + 4;                    // [8 * n_general]  reassembled channels of the general groups
     int4 *longs = reinterpret_cast<int4 *>(exc + GROUP * a.n_general); // [n_long] entries of the long rows
     uint32_t *pk = reinterpret_cast<uint32_t *>(longs + a.n_long);     // [(n_chunks + 1) * PKW] packed codes, input order
+    uint32_t *masks = pk + (a.n_chunks + 1) * PKW<BITS>;               // [n_mask] chunks of which only some channels pass
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
@@ -354,6 +355,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
     }
     for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
+    for (int j = tid; j < a.n_mask; j += nt) masks[j] = (uint32_t)a.masks[j];
     if (tid < 4) zero[tid] = 0.0f;
     if (tid < W) pk[n_chunks * W + tid] = 0u;
     if (tid < 16) { // reduction slots of waves that do not exist hold the identity
@@ -382,11 +384,18 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     const XT *xbase = reinterpret_cast<const XT *>(a.x);
     Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
     int64_t row = blockIdx.x, done_row = -1;
-    if (PREFETCH && row < a.N) {
+    if (PREFETCH && row < a.N) { // the first row, and the one after it
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int i = tid + it * nt;
-            if (i < n_chunks) load_raw(ahead[PREFETCH ? it : 0], xbase + row * a.ldx, i * GROUP);
+            if (i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
+        }
+        if (row + gridDim.x < a.N) {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int i = tid + it * nt;
+                if (i < n_chunks) load_raw(ahead[PREFETCH ? it : 0], xbase + (row + gridDim.x) * a.ldx, i * GROUP);
+            }
         }
     }
 
@@ -411,19 +420,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
 #pragma unroll
         for (int m = 0; m < ITEMS_REG; ++m) asm volatile("" : "+v"(item[m].x), "+v"(item[m].y));
 
-        // ---- step a1.  Take this row (already on its way); put the next row's loads in flight.
-        if constexpr (PREFETCH) {
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) raw[it] = ahead[it];
-            const int64_t next = row + gridDim.x;
-            if (next < a.N) {
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    const int i = tid + it * nt;
-                    if (i < n_chunks) load_raw(ahead[it], xbase + next * a.ldx, i * GROUP);
-                }
-            }
-        } else {
+        // ---- step a1.  bf16 rows are already here or on their way (see the end of the loop body).
+        if constexpr (!PREFETCH) {
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
                 const int i = tid + it * nt;
@@ -542,32 +540,6 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
             }
         }
-        // Chunks in which some channel does not pass (an outlier that is split, a merged source) are
-        // few, but nearly every wave has a lane with one: handled here, one per lane and turn, so a
-        // wave spends as many turns as its busiest lane has such chunks (one or two), not ITERS.
-        // Such a chunk is always staged; a lane re-reads its own LDS writes (in order, no barrier).
-        {
-            uint32_t todo = 0;
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it)
-                if ((chunkw[it] & 0xffu) != 0xffu && (chunkw[it] & 0xffu) != 0u) todo |= 1u << it;
-            while (todo) {
-                const int it = __builtin_ctz(todo);
-                todo &= todo - 1;
-                uint32_t cw = chunkw[0];
-#pragma unroll
-                for (int q = 1; q < ITERS; ++q) cw = it == q ? chunkw[q] : cw;
-                const float4 *c4 = reinterpret_cast<const float4 *>(pub + (cw >> 8) * GROUP);
-                const float4 lo = c4[0], hi = c4[1];
-                const float yv[GROUP] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-                for (int j = 0; j < GROUP; ++j) {
-                    const bool in = cw >> j & 1u;
-                    mn = fminf(mn, in ? yv[j] : inf);
-                    mx = fmaxf(mx, in ? yv[j] : -inf);
-                }
-            }
-        }
         __syncthreads(); // staged y complete
 
         // ---- steps a2 + a3 for the general groups: sub-channels (scale 1/T), merged channels
@@ -592,21 +564,41 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 mx = fmaxf(mx, real ? xv : -inf);
                 if (real) exc[j] = xv;
             }
+            // Chunks of which only some channels pass (the others are split or merged away) enter min/max
+            // here, from their staged copy, one chunk per lane: there are few of them, but every wavefront
+            // owns some, so taking them where y is produced would cost every wavefront a masked pass per
+            // chunk.  Dealt out from the last lane down; the long rows below start at the first lane.
+            for (int base = 0; base < a.n_mask; base += nt) {
+                const int j = base + (nt - 1 - tid);
+                const uint32_t cw = j < a.n_mask ? masks[j] : 0u;
+                if (cw & 0xffu) {
+                    const float4 *c4 = reinterpret_cast<const float4 *>(pub + (cw >> 8) * GROUP);
+                    const float4 lo = c4[0], hi = c4[1];
+                    const float yv[GROUP] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                    for (int k = 0; k < GROUP; k += 2) {
+                        const bool in0 = cw >> k & 1u, in1 = cw >> (k + 1) & 1u;
+                        mn = fminf(fminf(mn, in0 ? yv[k] : inf), in1 ? yv[k + 1] : inf);
+                        mx = fmaxf(fmaxf(mx, in0 ? yv[k] : -inf), in1 ? yv[k + 1] : -inf);
+                    }
+                }
+            }
             // Long rows (a channel merged from three or more, Eq. 4).  The sum runs left to right in
             // fp32, so its order is fixed; its latency need not be.  Entry e of the table belongs to lane
             // e % 64 and a row sits in consecutive lanes of one wavefront: every lane forms its product,
             // then "value of the lane below + own product" is repeated; the lane of entry number pos is
             // final after pos repeats (repeating it again changes nothing) and the row's last lane
-            // ends up with the row's value.
+            // ends up with the row's value.  Every entry carries the largest pos of its wavefront.
             for (int base = 0; base < a.n_long; base += nt) {
                 const int e = base + tid;
                 int4 le = make_int4((int32_t)zero_at, -1, 0, 0);
                 if (e < a.n_long) le = longs[e];
                 const float p = __int_as_float(le.z) * lds[le.x];
+                const int pos = le.w & 0xff, steps = __builtin_amdgcn_readfirstlane(le.w >> 8);
                 float acc = p;
-                for (int t = 1; __builtin_amdgcn_ballot_w64(le.w >= t) != 0; ++t) {
+                for (int t = 0; t < steps; ++t) {
                     const float below = dpp_f32<DPP_WAVE_SHR1>(acc);
-                    acc = le.w > 0 ? below + p : p;
+                    acc = pos > 0 ? below + p : p;
                 }
                 if (le.y >= 0) {
                     exc[le.y] = acc;
@@ -652,6 +644,22 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
         }
         __syncthreads(); // packed words complete
+
+        // The next row moves up and the row after it is requested, BEFORE this row's stores are issued:
+        // loads and stores retire in order through one counter, so a wait for loads that were issued
+        // after stores would wait for those stores too.
+        if constexpr (PREFETCH) {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) raw[it] = ahead[it];
+            const int64_t after = row + 2 * (int64_t)gridDim.x;
+            if (after < a.N) {
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    const int i = tid + it * nt;
+                    if (i < n_chunks) load_raw(ahead[it], xbase + after * a.ldx, i * GROUP);
+                }
+            }
+        }
 
         // ---- step a4, second half: the lane's output groups
         int32_t sum = 0;
@@ -730,9 +738,12 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
             return QLLM_ERR_HIP;
         }
     }
-    // resident workgroups per CU: bounded by LDS (160 KB) and by 2048 lanes
-    int per_cu = (int)((160 * 1024) / (lds + 1024));
-    per_cu = per_cu < 2048 / sh.nt ? per_cu : 2048 / sh.nt;
+    // resident workgroups per CU (registers, LDS, lanes): the grid is exactly what is resident at once
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), sh.nt, lds) != hipSuccess) {
+        (void)hipGetLastError();
+        per_cu = 1;
+    }
     if (per_cu < 1) per_cu = 1;
     int64_t grid = (int64_t)cu_count() * per_cu;
     if (grid > a.N) grid = a.N;
@@ -776,7 +787,7 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
     const Shape sh = pick_shape(units);
     const size_t lds = ((size_t)a.n_pub + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16 +
-                       ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8);
+                       ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8) + (size_t)a.n_mask * 4;
     if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
     const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
     if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // general-group entries live in registers

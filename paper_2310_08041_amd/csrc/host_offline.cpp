@@ -186,27 +186,32 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     // a chunk of which only some channels pass is staged too (the kernel takes its min/max from there)
     for (int64_t c = 0; c < n_chunks; ++c)
         if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) pub_slot[(size_t)c] = 0;
-    int64_t n_pub = 0;
-    for (int64_t c = 0; c < n_chunks; ++c)
+    int64_t n_pub = 0, n_mask = 0;
+    for (int64_t c = 0; c < n_chunks; ++c) {
         if (pub_slot[(size_t)c] == 0) pub_slot[(size_t)c] = (int32_t)n_pub++;
+        if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) ++n_mask;
+    }
     if (n_long > 0xffffff || G * n_pub + 4 > 0xffff) return QLLM_ERR_MAP;
     *n_general = general;
     const int64_t n_work = (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G; // groups incl. zero padding
     auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
     const int64_t off_work = HEAD, off_chunks = round4(off_work + n_work), off_items = round4(off_chunks + n_chunks);
-    const int64_t off_longs = round4(off_items + general * G * 2);
-    *plan_len = off_longs + 4 * n_long;
+    const int64_t off_longs = round4(off_items + general * G * 2), off_masks = off_longs + 4 * n_long;
+    *plan_len = off_masks + n_mask;
     if (!plan) return QLLM_OK;
 
     std::fill(plan, plan + *plan_len, 0);
-    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 4, C_in, C_out, n_work, general, n_chunks, n_long,
-                                          n_pub, off_work, off_chunks, off_items, off_longs, *plan_len, 0, 0};
+    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 5, C_in, C_out, n_work, general, n_chunks, n_long,
+                                          n_pub, off_work, off_chunks, off_items, off_longs, *plan_len, n_mask, off_masks};
     for (int64_t k = 0; k < HEAD; ++k) plan[k] = (int32_t)head[k];
     int32_t *work = plan + off_work, *chunks = plan + off_chunks, *items = plan + off_items, *longs = plan + off_longs;
     for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1; // padding entries are {0, -1, 0.0f, 0}
     const uint32_t zero_at = (uint32_t)(G * n_pub); // the staged zero sits right after the published chunks
     auto staged = [&](int32_t channel) { return (uint32_t)(pub_slot[(size_t)(channel / G)] * G + channel % G); };
-    for (int64_t c = 0; c < n_chunks; ++c) chunks[c] = (int32_t)(((uint32_t)pub_slot[(size_t)c] << 8) | pass[(size_t)c]); // -1: 0xffffff
+    for (int64_t c = 0, m = 0; c < n_chunks; ++c) {
+        chunks[c] = (int32_t)(((uint32_t)pub_slot[(size_t)c] << 8) | pass[(size_t)c]); // -1: 0xffffff
+        if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) plan[off_masks + m++] = chunks[c];
+    }
     int64_t slot = 0, long_at = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
         if (desc[(size_t)g] >= 0) continue;
@@ -237,6 +242,13 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
             std::memcpy(&it[1], &scale[e0], 4);
         }
         ++slot;
+    }
+    // every entry of a block of 64 also carries the block's largest position: the number of additions
+    // the wavefront that owns the block has to make
+    for (int64_t b0 = 0; b0 < n_long; b0 += WAVE) {
+        int32_t most = 0;
+        for (int64_t e = b0; e < std::min(n_long, b0 + WAVE); ++e) most = std::max(most, longs[4 * e + 3]);
+        for (int64_t e = b0; e < std::min(n_long, b0 + WAVE); ++e) longs[4 * e + 3] |= most << 8;
     }
     // work list of the code-producing step, one entry per group of 8 output channels (zero padding
     // included): kind << 28 | group << 15 | d.  Plain groups first, then general groups (d = their

@@ -85,7 +85,7 @@ def test_fused_entry_point_rejects_bad_arguments_before_launching():
     # a plan whose header (host copy) is not that of this map is refused before anything is launched
     head = (C.c_int32 * b.PLAN_HEAD)()
     assert call(mp=b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, 0x4000, head)) == -5
-    head[:] = [0x514C4D50, 4, 64, 64, 32, 0, 8, 0, 0, 16, 48, 56, 56, 56, 0, 0]
+    head[:] = [0x514C4D50, 5, 64, 64, 32, 0, 8, 0, 0, 16, 48, 56, 56, 56, 0, 56]
     head[2] = 72                                                      # a plan made for another C_in
     assert call(mp=b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, 0x4000, head)) == -5
     head[2], head[13] = 64, 60                                        # length does not match the parts
@@ -157,8 +157,9 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     plan = r["plan"]
     n_groups, n_chunks, n_work = (c.K + 7) // 8, (C + 7) // 8, (c.K + 255) // 256 * 32
     n_general, _, n_long, n_pub, off_work, off_chunks, off_items, off_longs, plan_len = plan[5:14].tolist()
-    assert plan[:5].tolist() == [0x514C4D50, 4, C, c.K, n_work] and plan[6] == n_chunks and plan[14:16].tolist() == [0, 0]
-    assert off_work == 16 and plan_len == plan.size == off_longs + 4 * n_long
+    n_mask, off_masks = plan[14:16].tolist()
+    assert plan[:5].tolist() == [0x514C4D50, 5, C, c.K, n_work] and plan[6] == n_chunks
+    assert off_work == 16 and off_masks == off_longs + 4 * n_long and plan_len == plan.size == off_masks + n_mask
     assert off_chunks >= off_work + n_work and off_items >= off_chunks + n_chunks and off_longs >= off_items + 16 * n_general
     assert off_chunks % 4 == 0 and off_items % 4 == 0 and off_longs % 4 == 0
     work = plan[off_work:off_work + n_work].astype(np.int64) & 0xFFFFFFFF
@@ -174,8 +175,14 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     chunks = plan[off_chunks:off_chunks + n_chunks].astype(np.int64) & 0xFFFFFFFF
     passes, slots = chunks & 0xFF, chunks >> 8
     items = plan[off_items:off_items + 16 * n_general].reshape(n_general * 8, 2)
-    longs = plan[off_longs:].reshape(-1, 4)
+    longs = plan[off_longs:off_masks].reshape(-1, 4).copy()
     assert longs.shape[0] == n_long
+    most = longs[:, 3] >> 8                                       # largest position among the 64 entries of a wavefront
+    longs[:, 3] &= 0xFF
+    for b0 in range(0, n_long, 64):
+        assert np.all(most[b0:b0 + 64] == longs[b0:b0 + 64, 3].max())
+    partial = (passes != 0) & (passes != 0xFF)
+    assert np.array_equal(plan[off_masks:].astype(np.int64) & 0xFFFFFFFF, chunks[partial])
     used = np.zeros(n_long, bool)
     assert (desc >= 0).sum() > 0.25 * desc.size and (desc < 0).sum() == n_general
     expect_pass = np.zeros(n_chunks * 8, bool)
