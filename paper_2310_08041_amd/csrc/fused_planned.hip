@@ -43,6 +43,7 @@ namespace {
 constexpr int KIND_PLAIN = 0, KIND_GENERAL = 1, KIND_PAD = 2, KIND_NONE = 3;
 constexpr int32_t WORK_NONE = KIND_NONE << 28;
 constexpr int32_t ITEM_LONG = -2; // first word of a plan item whose entries are in the table of long rows
+constexpr int32_t ITEM_SKIP = 0x7fc00001; // second word the kernel gives such an item in LDS (as a scale: a NaN, never a real one)
 
 template <typename XT>
 struct Raw; // 8 input elements as they sit in memory
@@ -92,6 +93,17 @@ __device__ __forceinline__ void forget(Raw<uint16_t> &r)
     asm volatile("" : "+v"(r.q.x), "+v"(r.q.y), "+v"(r.q.z), "+v"(r.q.w));
 }
 __device__ __forceinline__ void forget(Raw<float> &) {}
+
+// dst = src as a copy the optimiser has to make here and now: the registers of src are then free for
+// the next load, instead of the copy being postponed to the end of the loop body, behind that load.
+__device__ __forceinline__ void move_up(Raw<uint16_t> &dst, const Raw<uint16_t> &src)
+{
+    asm volatile("v_mov_b32 %0, %1" : "=v"(dst.q.x) : "v"(src.q.x));
+    asm volatile("v_mov_b32 %0, %1" : "=v"(dst.q.y) : "v"(src.q.y));
+    asm volatile("v_mov_b32 %0, %1" : "=v"(dst.q.z) : "v"(src.q.z));
+    asm volatile("v_mov_b32 %0, %1" : "=v"(dst.q.w) : "v"(src.q.w));
+}
+__device__ __forceinline__ void move_up(Raw<float> &dst, const Raw<float> &src) { dst = src; }
 
 // (float)(1 / sqrt(t)) for t > 0: the hardware's reciprocal-square-root estimate refined by two Newton
 // steps in fp64 (relative error of a few 1e-16), then rounded to fp32.  It equals the fp32 rounding of
@@ -322,13 +334,16 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
 template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, bool LAYER>
 __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];
     float *pub = lds;                         // [8 * n_pub]      y of the chunks that general groups read
     float *zero = pub + GROUP * a.n_pub;      // [4] a zero: the "second source" of single-entry items
     float *exc = zero + 4;                    // [8 * n_general]  reassembled channels of the general groups
     int4 *longs = reinterpret_cast<int4 *>(exc + GROUP * a.n_general); // [n_long] entries of the long rows
-    uint32_t *pk = reinterpret_cast<uint32_t *>(longs + a.n_long);     // [(n_chunks + 1) * PKW] packed codes, input order
+    int2 *items = reinterpret_cast<int2 *>(longs + a.n_long);          // [8 * n_general] entries of the general groups
+    uint32_t *pk = reinterpret_cast<uint32_t *>(items + GROUP * a.n_general); // [(n_chunks + 1) * PKW] packed codes, input order
     uint32_t *masks = pk + (a.n_chunks + 1) * PKW<BITS>;               // [n_mask] chunks of which only some channels pass
+    uint32_t *chunkw = masks + a.n_mask;                               // [n_chunks] pass bits | staging slot << 8
+    int32_t *work = reinterpret_cast<int32_t *>(chunkw + a.n_chunks); // [n_work] work list of the output groups
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
@@ -345,17 +360,15 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
 
     // ---- per-lane state that outlives the rows
     float gam[GAM_REG ? ITERS : 1][GROUP];
-    uint32_t chunkw[ITERS]; // pass bits | staging slot << 8 of the lane's input chunks
-    int32_t work[ITERS];    // work-list entries of the lane's output groups
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int i = tid + it * nt;
-        chunkw[it] = i < n_chunks ? (uint32_t)a.chunks[i] : NOT_PUBLISHED << 8;
-        work[it] = i < a.n_work ? a.work[i] : WORK_NONE;
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
     }
     for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
     for (int j = tid; j < a.n_mask; j += nt) masks[j] = (uint32_t)a.masks[j];
+    for (int j = tid; j < n_chunks; j += nt) chunkw[j] = (uint32_t)a.chunks[j];
+    for (int j = tid; j < a.n_work; j += nt) work[j] = a.work[j];
     if (tid < 4) zero[tid] = 0.0f;
     if (tid < W) pk[n_chunks * W + tid] = 0u;
     if (tid < 16) { // reduction slots of waves that do not exist hold the identity
@@ -365,37 +378,33 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         red_f[16 + tid] = -inf;
         red_i[tid] = 0;
     }
-    // general-group entries of this lane: {staged position of source 0 | of source 1 << 16, scale};
-    // long rows (bit m of long_mask) and unused slots read the zero
+    // general-group entries {staged position of source 0 | of source 1 << 16, scale}: kept in LDS (a
+    // register pair per entry and lane would be too many); long rows are marked and read the zero
     const uint32_t zero_at = (uint32_t)(GROUP * a.n_pub);
-    int2 item[ITEMS_REG];
-    uint32_t long_mask = 0;
+    for (int j = tid; j < n_items; j += nt) {
+        int2 e = reinterpret_cast<const int2 *>(a.items)[j];
+        if (e.x == ITEM_LONG) e = make_int2((int32_t)(zero_at | (zero_at << 16)), ITEM_SKIP);
+        items[j] = e;
+    }
+
+    // gamma has to have arrived before the row loop is entered: a load still pending there would make
+    // every pass of the loop wait for whatever was requested last, the next row's prefetch included.
+    if constexpr (GAM_REG) {
 #pragma unroll
-    for (int m = 0; m < ITEMS_REG; ++m) {
-        const int j = tid + m * nt;
-        item[m] = make_int2((int32_t)(zero_at | (zero_at << 16)), 0);
-        if (j < n_items) {
-            const int2 e = reinterpret_cast<const int2 *>(a.items)[j];
-            if (e.x == ITEM_LONG) long_mask |= 1u << m;
-            else item[m] = e;
+        for (int it = 0; it < ITERS; ++it) {
+#pragma unroll
+            for (int j = 0; j < GROUP; ++j) asm volatile("" : "+v"(gam[it][j]));
         }
     }
 
     const XT *xbase = reinterpret_cast<const XT *>(a.x);
     Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
     int64_t row = blockIdx.x, done_row = -1;
-    if (PREFETCH && row < a.N) { // the first row, and the one after it
+    if (PREFETCH && row < a.N) { // the first row
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int i = tid + it * nt;
             if (i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
-        }
-        if (row + gridDim.x < a.N) {
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) {
-                const int i = tid + it * nt;
-                if (i < n_chunks) load_raw(ahead[PREFETCH ? it : 0], xbase + (row + gridDim.x) * a.ldx, i * GROUP);
-            }
         }
     }
 
@@ -412,19 +421,25 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     };
 
     for (; row < a.N; row += gridDim.x) {
-        // Everything derived from the plan (LDS addresses, masks, shifts) costs a handful of
-        // instructions per row to recompute, but a register each to keep: make the optimiser
-        // recompute it by hiding that the plan registers do not change from row to row.
+        // Addresses derived from the lane's number cost an instruction or two per row to recompute, but a
+        // register each to keep: hide from the optimiser that the number does not change from row to row.
+        int ltid = threadIdx.x;
+        asm volatile("" : "+v"(ltid));
+        // ---- step a1.  A bf16 row is already here (it was requested while the row before it was worked
+        //      on); request the next one.  Its registers move up further down, before this row's stores.
+        if constexpr (PREFETCH) {
+            const int64_t next = row + gridDim.x;
+            if (next < a.N) {
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) asm volatile("" : "+v"(work[it]), "+v"(chunkw[it]));
-#pragma unroll
-        for (int m = 0; m < ITEMS_REG; ++m) asm volatile("" : "+v"(item[m].x), "+v"(item[m].y));
-
-        // ---- step a1.  bf16 rows are already here or on their way (see the end of the loop body).
-        if constexpr (!PREFETCH) {
+                for (int it = 0; it < ITERS; ++it) {
+                    const int i = ltid + it * nt;
+                    if (i < n_chunks) load_raw(ahead[it], xbase + next * a.ldx, i * GROUP);
+                }
+            }
+        } else {
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                const int i = tid + it * nt;
+                const int i = ltid + it * nt;
                 if (i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
             }
         }
@@ -436,7 +451,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             double q0 = 0.0, q1 = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                if (tid + it * nt < n_chunks) {
+                if (ltid + it * nt < n_chunks) {
                     float v[GROUP];
                     widen(raw[it], v);
 #pragma unroll
@@ -456,7 +471,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             double s0 = 0.0, s1 = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                if (tid + it * nt < n_chunks) {
+                if (ltid + it * nt < n_chunks) {
                     float v[GROUP];
                     widen(raw[it], v);
 #pragma unroll
@@ -474,7 +489,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             double q0 = 0.0, q1 = 0.0;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                if (tid + it * nt < n_chunks) {
+                if (ltid + it * nt < n_chunks) {
                     float v[GROUP];
                     widen(raw[it], v);
 #pragma unroll
@@ -499,18 +514,20 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         //      channels that pass unscaled
         float y[ITERS][GROUP];
         float mn = inf, mx = -inf;
-        const float *gamma_row = a.gamma; // opaque, so that the per-row loads of gamma stay per row
-        asm volatile("" : "+s"(gamma_row));
+        const float *gamma_row = a.gamma, *beta_row = a.beta; // opaque, so that per-row loads stay per row
+        asm volatile("" : "+s"(gamma_row), "+s"(beta_row));
         const bool shift = LAYER && a.beta != nullptr;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int i = tid + it * nt;
+            const int i = ltid + it * nt;
             float gjit[GROUP];
             if constexpr (!GAM_REG) load_gamma(gjit, gamma_row, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
             const float *g8 = GAM_REG ? gam[GAM_REG ? it : 0] : gjit;
             if (i < n_chunks) {
                 forget(raw[it]);
                 widen(raw[it], y[it]);
+                float bj[GROUP];
+                if constexpr (LAYER) load_gamma(bj, beta_row, i * GROUP, a.C, shift); // beta: re-read (from L2) for every row
 #pragma unroll
                 for (int j = 0; j < GROUP; ++j) {
                     float t = y[it][j];
@@ -518,17 +535,17 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                     t = t * rstd;
                     t = t * g8[j];
                     if constexpr (LAYER) {
-                        if (shift) t = t + a.beta[i * GROUP + j];
+                        if (shift) t = t + bj[j];
                     }
                     y[it][j] = t;
                 }
-                const uint32_t slot = chunkw[it] >> 8;
+                const uint32_t cw = chunkw[i], slot = cw >> 8;
                 if (slot != NOT_PUBLISHED) {
                     float4 *dst = reinterpret_cast<float4 *>(pub + slot * GROUP);
                     dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
                     dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
                 }
-                if ((chunkw[it] & 0xffu) == 0xffu) {
+                if ((cw & 0xffu) == 0xffu) {
 #pragma unroll
                     for (int j = 0; j < GROUP; j += 2) {
                         mn = fminf(fminf(mn, y[it][j]), y[it][j + 1]);
@@ -546,7 +563,13 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         //      (scale 1/g each) and the plain channels that share a group of 8 with them.
         //      All LDS reads are issued before any of them is used.
         {
+            int2 item[ITEMS_REG];
             float y0[ITEMS_REG], y1[ITEMS_REG];
+#pragma unroll
+            for (int m = 0; m < ITEMS_REG; ++m) {
+                const int j = ltid + m * nt;
+                item[m] = j < n_items ? items[j] : make_int2((int32_t)(zero_at | (zero_at << 16)), ITEM_SKIP);
+            }
 #pragma unroll
             for (int m = 0; m < ITEMS_REG; ++m) {
                 const uint32_t p = (uint32_t)item[m].x;
@@ -555,21 +578,20 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
 #pragma unroll
             for (int m = 0; m < ITEMS_REG; ++m) {
-                const int j = tid + m * nt;
                 const float sc = __int_as_float(item[m].y);
                 float xv = sc * y0[m];
                 xv = xv + sc * y1[m];
-                const bool real = j < n_items && !(long_mask >> m & 1u);
+                const bool real = item[m].y != ITEM_SKIP;
                 mn = fminf(mn, real ? xv : inf);
                 mx = fmaxf(mx, real ? xv : -inf);
-                if (real) exc[j] = xv;
+                if (real) exc[ltid + m * nt] = xv;
             }
             // Chunks of which only some channels pass (the others are split or merged away) enter min/max
             // here, from their staged copy, one chunk per lane: there are few of them, but every wavefront
             // owns some, so taking them where y is produced would cost every wavefront a masked pass per
             // chunk.  Dealt out from the last lane down; the long rows below start at the first lane.
             for (int base = 0; base < a.n_mask; base += nt) {
-                const int j = base + (nt - 1 - tid);
+                const int j = base + (nt - 1 - ltid);
                 const uint32_t cw = j < a.n_mask ? masks[j] : 0u;
                 if (cw & 0xffu) {
                     const float4 *c4 = reinterpret_cast<const float4 *>(pub + (cw >> 8) * GROUP);
@@ -590,7 +612,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             // final after pos repeats (repeating it again changes nothing) and the row's last lane
             // ends up with the row's value.  Every entry carries the largest pos of its wavefront.
             for (int base = 0; base < a.n_long; base += nt) {
-                const int e = base + tid;
+                const int e = base + ltid;
                 int4 le = make_int4((int32_t)zero_at, -1, 0, 0);
                 if (e < a.n_long) le = longs[e];
                 const float p = __int_as_float(le.z) * lds[le.x];
@@ -635,7 +657,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         // ---- step a4, first half: codes of the lane's own chunks, packed in input order
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int i = tid + it * nt;
+            const int i = ltid + it * nt;
             if (i < n_chunks) {
                 uint32_t w0, w1;
                 quant_pack<BITS>(y[it], 0xffu, fast, inv, beta, w0, w1);
@@ -645,20 +667,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         }
         __syncthreads(); // packed words complete
 
-        // The next row moves up and the row after it is requested, BEFORE this row's stores are issued:
-        // loads and stores retire in order through one counter, so a wait for loads that were issued
-        // after stores would wait for those stores too.
+        // The next row moves up BEFORE this row's stores are issued: loads and stores retire in order
+        // through one counter, so a wait for the loads placed after the stores would wait for the
+        // stores too.
         if constexpr (PREFETCH) {
 #pragma unroll
-            for (int it = 0; it < ITERS; ++it) raw[it] = ahead[it];
-            const int64_t after = row + 2 * (int64_t)gridDim.x;
-            if (after < a.N) {
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    const int i = tid + it * nt;
-                    if (i < n_chunks) load_raw(ahead[it], xbase + after * a.ldx, i * GROUP);
-                }
-            }
+            for (int it = 0; it < ITERS; ++it) move_up(raw[it], ahead[it]);
         }
 
         // ---- step a4, second half: the lane's output groups
@@ -666,7 +680,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         uint8_t *out_row = a.codes + row * a.row_bytes;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int32_t e = work[it];
+            const int i = ltid + it * nt;
+            const int32_t e = i < a.n_work ? work[i] : WORK_NONE;
             const int kind = (uint32_t)e >> 28;
             if (kind != KIND_NONE) {
                 const int g = (e >> 15) & 0x1fff, d = e & 0x7fff;
@@ -787,10 +802,11 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
     const Shape sh = pick_shape(units);
     const size_t lds = ((size_t)a.n_pub + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16 +
-                       ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8) + (size_t)a.n_mask * 4;
+                       (size_t)a.n_general * GROUP * 8 + ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8) +
+                       ((size_t)a.n_mask + (size_t)a.n_chunks + (size_t)a.n_work) * 4;
     if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
     const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
-    if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // general-group entries live in registers
+    if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // a lane takes at most that many general-group entries
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);
     return dispatch_bits<float>(a, bits, sh, lds, stream);
 }
