@@ -120,27 +120,61 @@ __device__ __forceinline__ float rsqrt_to_f32(double t)
     return (float)r;
 }
 
-// ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips).
+// ---- wavefront reductions on the data-parallel-primitive (DPP) path: no LDS round trips.
 // Four butterfly steps inside each row of 16 lanes, then the four row results are combined from
 // lanes 0, 16, 32, 48.  The order of the additions is fixed, so the result is reproducible.
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v)
+// Each step is ONE instruction that takes its first operand from another lane.  They are written
+// out because the optimiser, given the lane movement as a builtin, spends four instructions a step
+// (a zeroed destination, the move, a NaN-quieting pass, the operation).  Every lane of the wavefront
+// must be active; the s_nop covers the two wait states a DPP operand needs after it was written.
+#define QLLM_DPP_STEP(fn, type, cons, op, ctrl)                                                          \
+    __device__ __forceinline__ type fn(type v)                                                           \
+    {                                                                                                    \
+        type r;                                                                                          \
+        asm("s_nop 1\n\t" op " %0, %1, %1 " ctrl " row_mask:0xf bank_mask:0xf" : "=" cons(r) : cons(v)); \
+        return r;                                                                                        \
+    }
+#define QLLM_DPP_FAMILY(name, type, op)                                  \
+    QLLM_DPP_STEP(name##_xor1, type, "v", op, "quad_perm:[1,0,3,2]")     \
+    QLLM_DPP_STEP(name##_xor2, type, "v", op, "quad_perm:[2,3,0,1]")     \
+    QLLM_DPP_STEP(name##_half_mirror, type, "v", op, "row_half_mirror")  \
+    QLLM_DPP_STEP(name##_mirror, type, "v", op, "row_mirror")            \
+    __device__ __forceinline__ type name##_row16(type v) /* all 16 lanes of a row end with the row's result */ \
+    {                                                                    \
+        return name##_mirror(name##_half_mirror(name##_xor2(name##_xor1(v)))); \
+    }
+QLLM_DPP_FAMILY(dpp_min, float, "v_min_f32_dpp")
+QLLM_DPP_FAMILY(dpp_max, float, "v_max_f32_dpp")
+QLLM_DPP_FAMILY(dpp_add, int32_t, "v_add_u32_dpp")
+
+// value of the lane below (lane 0: zero) + p, across the whole wavefront
+__device__ __forceinline__ float below_plus(float acc, float p)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+    float r;
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %2 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "=v"(r) : "v"(acc), "v"(p));
+    return r;
 }
-template <int CTRL>
-__device__ __forceinline__ double dpp_f64(double v)
+
+// v + (v of the partner lane) in fp64: the two halves move separately, the addition is ordinary
+#define QLLM_DPP_ADD_F64(fn, ctrl)                                                                           \
+    __device__ __forceinline__ double fn(double v)                                                           \
+    {                                                                                                        \
+        const uint64_t u = __double_as_longlong(v);                                                          \
+        uint32_t lo, hi;                                                                                     \
+        asm("s_nop 1\n\tv_mov_b32_dpp %0, %2 " ctrl " row_mask:0xf bank_mask:0xf\n\t"                        \
+            "v_mov_b32_dpp %1, %3 " ctrl " row_mask:0xf bank_mask:0xf"                                       \
+            : "=&v"(lo), "=&v"(hi)                                                                           \
+            : "v"((uint32_t)u), "v"((uint32_t)(u >> 32)));                                                   \
+        return v + __longlong_as_double((long long)((uint64_t)lo | ((uint64_t)hi << 32)));                   \
+    }
+QLLM_DPP_ADD_F64(dpp_addd_xor1, "quad_perm:[1,0,3,2]")
+QLLM_DPP_ADD_F64(dpp_addd_xor2, "quad_perm:[2,3,0,1]")
+QLLM_DPP_ADD_F64(dpp_addd_half_mirror, "row_half_mirror")
+QLLM_DPP_ADD_F64(dpp_addd_mirror, "row_mirror")
+__device__ __forceinline__ double dpp_addd_row16(double v)
 {
-    const uint64_t u = __double_as_longlong(v);
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, false);
-    return __longlong_as_double((long long)((uint64_t)lo | ((uint64_t)hi << 32)));
+    return dpp_addd_mirror(dpp_addd_half_mirror(dpp_addd_xor2(dpp_addd_xor1(v))));
 }
-constexpr int DPP_XOR1 = 0xB1;        // quad_perm [1,0,3,2]
-constexpr int DPP_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
-constexpr int DPP_HALF_MIRROR = 0x141; // lane i <-> 7 - i inside each half row
-constexpr int DPP_MIRROR = 0x140;      // lane i <-> 15 - i inside each row
-constexpr int DPP_WAVE_SHR1 = 0x138;   // lane i <- lane i - 1 across the whole wavefront (lane 0 keeps `old`)
 
 __device__ __forceinline__ float lane_f32(float v, int l)
 {
@@ -156,27 +190,19 @@ __device__ __forceinline__ double lane_f64(double v, int l)
 
 __device__ __forceinline__ double wave_sum(double v)
 {
-    v += dpp_f64<DPP_XOR1>(v);
-    v += dpp_f64<DPP_XOR2>(v);
-    v += dpp_f64<DPP_HALF_MIRROR>(v);
-    v += dpp_f64<DPP_MIRROR>(v);
+    v = dpp_addd_row16(v);
     return (lane_f64(v, 0) + lane_f64(v, 16)) + (lane_f64(v, 32) + lane_f64(v, 48));
 }
 __device__ __forceinline__ void wave_minmax(float &mn, float &mx)
 {
-    mn = fminf(mn, dpp_f32<DPP_XOR1>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR1>(mx));
-    mn = fminf(mn, dpp_f32<DPP_XOR2>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR2>(mx));
-    mn = fminf(mn, dpp_f32<DPP_HALF_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_HALF_MIRROR>(mx));
-    mn = fminf(mn, dpp_f32<DPP_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_MIRROR>(mx));
+    mn = dpp_min_row16(mn);
+    mx = dpp_max_row16(mx);
     mn = fminf(fminf(lane_f32(mn, 0), lane_f32(mn, 16)), fminf(lane_f32(mn, 32), lane_f32(mn, 48)));
     mx = fmaxf(fmaxf(lane_f32(mx, 0), lane_f32(mx, 16)), fmaxf(lane_f32(mx, 32), lane_f32(mx, 48)));
 }
 __device__ __forceinline__ int32_t wave_sum_i32(int32_t v)
 {
-    v += __builtin_amdgcn_update_dpp(0, v, DPP_XOR1, 0xf, 0xf, false);
-    v += __builtin_amdgcn_update_dpp(0, v, DPP_XOR2, 0xf, 0xf, false);
-    v += __builtin_amdgcn_update_dpp(0, v, DPP_HALF_MIRROR, 0xf, 0xf, false);
-    v += __builtin_amdgcn_update_dpp(0, v, DPP_MIRROR, 0xf, 0xf, false);
+    v = dpp_add_row16(v);
     return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
            __builtin_amdgcn_readlane(v, 48);
 }
@@ -186,12 +212,7 @@ __device__ __forceinline__ int32_t wave_sum_i32(int32_t v)
 // of LDS reads.  The slots are not reused before another barrier has passed.
 __device__ __forceinline__ double total16(const double *slots, int lane)
 {
-    double v = slots[lane & 15];
-    v += dpp_f64<DPP_XOR1>(v);
-    v += dpp_f64<DPP_XOR2>(v);
-    v += dpp_f64<DPP_HALF_MIRROR>(v);
-    v += dpp_f64<DPP_MIRROR>(v);
-    return v;
+    return dpp_addd_row16(slots[lane & 15]);
 }
 
 // gamma of one 8-channel chunk (held in registers for the lifetime of the workgroup).  NORM_NONE runs
@@ -375,7 +396,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         red_d[0][tid] = 0.0;
         red_d[1][tid] = 0.0;
         red_f[tid] = inf;
-        red_f[16 + tid] = -inf;
+        red_f[16 + tid] = inf; // minus the maximum
         red_i[tid] = 0;
     }
     // general-group entries {staged position of source 0 | of source 1 << 16, scale}: kept in LDS (a
@@ -411,11 +432,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     // rowsum of a finished row: the waves' partial sums are complete once a barrier has passed
     auto finish_rowsum = [&]() {
         if (wave == 0 && done_row >= 0) {
-            int32_t s = red_i[lane & 15];
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR1, 0xf, 0xf, false);
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_XOR2, 0xf, 0xf, false);
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_HALF_MIRROR, 0xf, 0xf, false);
-            s += __builtin_amdgcn_update_dpp(0, s, DPP_MIRROR, 0xf, 0xf, false);
+            const int32_t s = dpp_add_row16(red_i[lane & 15]);
             if (lane == 0) a.rowsum[done_row] = s;
         }
     };
@@ -619,8 +636,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 const int pos = le.w & 0xff, steps = __builtin_amdgcn_readfirstlane(le.w >> 8);
                 float acc = p;
                 for (int t = 0; t < steps; ++t) {
-                    const float below = dpp_f32<DPP_WAVE_SHR1>(acc);
-                    acc = pos > 0 ? below + p : p;
+                    const float sum = below_plus(acc, p);
+                    acc = pos > 0 ? sum : p;
                 }
                 if (le.y >= 0) {
                     exc[le.y] = acc;
@@ -634,17 +651,14 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         wave_minmax(mn, mx);
         if (lane == 0) {
             red_f[wave] = mn;
-            red_f[16 + wave] = mx;
+            red_f[16 + wave] = -mx; // negated: one butterfly of minima then serves both
         }
         __syncthreads(); // also: the general groups' values are complete
-        mn = red_f[lane & 15];
-        mx = red_f[16 + (lane & 15)];
-        mn = fminf(mn, dpp_f32<DPP_XOR1>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR1>(mx));
-        mn = fminf(mn, dpp_f32<DPP_XOR2>(mn)); mx = fmaxf(mx, dpp_f32<DPP_XOR2>(mx));
-        mn = fminf(mn, dpp_f32<DPP_HALF_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_HALF_MIRROR>(mx));
-        mn = fminf(mn, dpp_f32<DPP_MIRROR>(mn)); mx = fmaxf(mx, dpp_f32<DPP_MIRROR>(mx));
-        mn = lane_f32(mn, 0);
-        mx = lane_f32(mx, 0);
+        {
+            const float v = dpp_min_row16(red_f[lane & 31]);
+            mn = lane_f32(v, 0);
+            mx = -lane_f32(v, 16);
+        }
         constexpr int QMAX = (1 << BITS) - 1;
         const float range = mx - mn;
         const float alpha = range > 0.0f ? range / (float)QMAX : 1.0f;
@@ -721,7 +735,6 @@ Shape pick_shape(int units)
     Shape s;
     if (units <= 256) s = {1, 0};
     else if (units <= 2048) s = {2, 0};
-    else if (units <= 3840) s = {5, 0};
     else s = {4, 0};
     s.nt = ((units + s.iters - 1) / s.iters + 63) / 64 * 64;
     return s;
@@ -777,8 +790,8 @@ int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t st
 {
     if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 256, true, LAYER>, a, sh, lds, stream);
     if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, LAYER>, a, sh, lds, stream);
-    if (sh.iters == 5) return launch(fused_planned_kernel<XT, BITS, 5, 768, true, LAYER>, a, sh, lds, stream);
-    return launch(fused_planned_kernel<XT, BITS, 4, 1024, false, LAYER>, a, sh, lds, stream);
+    // 16 waves x 4 chunks: gamma fits in registers next to y and the prefetched row, except with LayerNorm
+    return launch(fused_planned_kernel<XT, BITS, 4, 1024, !LAYER, LAYER>, a, sh, lds, stream);
 }
 
 template <typename XT>
