@@ -64,20 +64,20 @@ __device__ __forceinline__ void expand4(uint32_t w, uint32_t &d0, uint32_t &d1)
     d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u); // lo.b2 hi.b2 lo.b3 hi.b3
 }
 
-// four 6-bit codes in the low 24 bits of t -> four bytes
-__device__ __forceinline__ uint32_t expand6(uint32_t t)
+// four 6-bit codes in the low 24 bits of t (higher bits are ignored) -> four bytes
+__device__ __forceinline__ uint32_t spread6(uint32_t t)
 {
-    return (t & 0x3fu) | ((t << 2) & 0x3f00u) | ((t << 4) & 0x3f0000u) | ((t << 6) & 0x3f000000u);
+    const uint32_t x = (t & 0xfffu) | ((t << 4) & 0x0fff0000u);      // codes 0,1 in the low half, 2,3 in the high half
+    return (x & 0x003f003fu) | ((x << 2) & 0x3f003f00u);
 }
 
-// Expands one unit to 64 bytes and stores it as four 16-byte chunks of LDS row `row` (ROWB bytes per
-// row, chunks XOR-swizzled by row).  PERM: both operands are 4-bit, so the order of the codes inside a
-// unit is free as long as both sides use the same one; even codes then odd codes of each dword is
-// the cheapest (two masks and a shift instead of two more byte permutes).
-template <int BITS, int ROWB, bool PERM>
-__device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, int row, int ku)
+// One unit (64 packed codes) -> 64 bytes, as 16 dwords.  PERM: both operands are 4-bit, so the order of
+// the codes inside a unit is free as long as both sides use the same one; even codes then odd codes of
+// each dword is the cheapest (two masks and a shift instead of two more byte permutes).  8-bit codes
+// become code - 128, a signed byte (the epilogue adds the difference back).
+template <int BITS, bool PERM>
+__device__ __forceinline__ void expand_unit(const Unit<BITS> &u, uint32_t (&d)[16])
 {
-    uint32_t d[16];
     if constexpr (BITS == 4) {
         const uint32_t w[8] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y, u.r[1].z, u.r[1].w};
 #pragma unroll
@@ -95,10 +95,10 @@ __device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, i
 #pragma unroll
         for (int i = 0; i < 4; ++i) { // 3 dwords = 4 groups of 24 bits
             const uint32_t w0 = w[3 * i], w1 = w[3 * i + 1], w2 = w[3 * i + 2];
-            d[4 * i + 0] = expand6(w0);
-            d[4 * i + 1] = expand6((w0 >> 24) | (w1 << 8));
-            d[4 * i + 2] = expand6((w1 >> 16) | (w2 << 16));
-            d[4 * i + 3] = expand6(w2 >> 8);
+            d[4 * i + 0] = spread6(w0);
+            d[4 * i + 1] = spread6(__builtin_amdgcn_alignbit(w1, w0, 24));
+            d[4 * i + 2] = spread6(__builtin_amdgcn_alignbit(w2, w1, 16));
+            d[4 * i + 3] = spread6(w2 >> 8);
         }
     } else {
         const uint32_t w[16] = {u.r[0].x, u.r[0].y, u.r[0].z, u.r[0].w, u.r[1].x, u.r[1].y, u.r[1].z, u.r[1].w,
@@ -106,6 +106,15 @@ __device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, i
 #pragma unroll
         for (int i = 0; i < 16; ++i) d[i] = w[i] ^ 0x80808080u; // code - 128 as a signed byte
     }
+}
+
+// Expands one unit and stores it as four 16-byte chunks of LDS row `row` (ROWB bytes per row, chunks
+// XOR-swizzled by row).
+template <int BITS, int ROWB, bool PERM>
+__device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, int row, int ku)
+{
+    uint32_t d[16];
+    expand_unit<BITS, PERM>(u, d);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         const int chunk = (ku * 4 + c) ^ (row & 7);
@@ -377,6 +386,94 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
     finish_wave_tile<ABITS, WBITS, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
 }
 
+// ---- few tokens (decode): the weights are read once from HBM and that is the whole cost, so nothing
+// is staged.  A workgroup owns 32 output features (two matrix-core row tiles) and all N <= 16 NT tokens (NT 1 or 2);
+// its 8 waves split K: wave w takes the 256-code steps w, w + 8, ...  In a step the lane (r, c) of a
+// wave loads, for each of its rows, the 64 consecutive codes 256 s + 64 c .. + 63 straight from
+// global memory (rows of the weights: HBM; rows of the activations: L2, every workgroup reads them),
+// expands them in registers and issues four matrix-core operations, the m-th on codes 16 m .. 16 m + 15
+// of every lane's 64: which 64 codes of the step one operation sums is free as long as both
+// operands agree.  The waves' partial tiles are added up through LDS.
+constexpr int SK_THREADS = 512, SK_WAVES = 8, SK_RT = 2, SK_STEP = 256;
+
+template <int ABITS, int WBITS, typename YT, int NT>
+__global__ __launch_bounds__(SK_THREADS) void int_gemm_skinny_kernel(const GemmArgs g)
+{
+    extern __shared__ __align__(16) uint8_t sk_lds[]; // [SK_WAVES][NT * SK_RT][64] v4i
+    v4i *red = reinterpret_cast<v4i *>(sk_lds);
+    constexpr bool PERM = ABITS == 4 && WBITS == 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, c = lane >> 4;
+    const int o0 = blockIdx.x * (16 * SK_RT);
+
+    const uint8_t *w_row[SK_RT], *a_row[NT];
+#pragma unroll
+    for (int j = 0; j < SK_RT; ++j) w_row[j] = g.w_codes + (int64_t)min(o0 + 16 * j + r, g.O - 1) * g.w_row_bytes;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) a_row[i] = g.a_codes + (int64_t)min(16 * i + r, g.N - 1) * g.a_row_bytes;
+
+    v4i acc[NT][SK_RT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < SK_RT; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+    Unit<WBITS> uw0[SK_RT], uw1[SK_RT];
+    Unit<ABITS> ua0[NT], ua1[NT];
+    auto fetch = [&](Unit<WBITS> (&uw)[SK_RT], Unit<ABITS> (&ua)[NT], int s) {
+#pragma unroll
+        for (int j = 0; j < SK_RT; ++j) load_unit<WBITS>(uw[j], w_row[j], 4 * s + c);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) load_unit<ABITS>(ua[i], a_row[i], 4 * s + c);
+    };
+    auto work = [&](const Unit<WBITS> (&uw)[SK_RT], const Unit<ABITS> (&ua)[NT]) {
+        uint32_t da[NT][16], dw[SK_RT][16];
+#pragma unroll
+        for (int i = 0; i < NT; ++i) expand_unit<ABITS, PERM>(ua[i], da[i]);
+#pragma unroll
+        for (int j = 0; j < SK_RT; ++j) expand_unit<WBITS, PERM>(uw[j], dw[j]);
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int j = 0; j < SK_RT; ++j) {
+                    const v4i fw = {(int)dw[j][4 * m], (int)dw[j][4 * m + 1], (int)dw[j][4 * m + 2], (int)dw[j][4 * m + 3]};
+                    const v4i fa = {(int)da[i][4 * m], (int)da[i][4 * m + 1], (int)da[i][4 * m + 2], (int)da[i][4 * m + 3]};
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw, fa, acc[i][j], 0, 0, 0);
+                }
+    };
+
+    const int n_steps = g.Kpad / SK_STEP; // rows are padded to a multiple of 256 codes
+    int s = wave;
+    if (s < n_steps) {
+        fetch(uw0, ua0, s);
+        while (true) { // two steps per turn: the buffers alternate without being indexed
+            if (s + SK_WAVES < n_steps) fetch(uw1, ua1, s + SK_WAVES);
+            work(uw0, ua0);
+            s += SK_WAVES;
+            if (s >= n_steps) break;
+            if (s + SK_WAVES < n_steps) fetch(uw0, ua0, s + SK_WAVES);
+            work(uw1, ua1);
+            s += SK_WAVES;
+            if (s >= n_steps) break;
+        }
+    }
+
+    // ---- add the 8 partial tiles up; wave t finishes tile t
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < SK_RT; ++j) red[(wave * (NT * SK_RT) + i * SK_RT + j) * 64 + lane] = acc[i][j];
+    __syncthreads();
+    if (wave < NT * SK_RT) {
+        v4i sum[1][1] = {{red[wave * 64 + lane]}};
+#pragma unroll
+        for (int w = 1; w < SK_WAVES; ++w) sum[0][0] += red[(w * (NT * SK_RT) + wave) * 64 + lane];
+        finish_wave_tile<ABITS, WBITS, YT, 1, 1>(g, sum, 16 * (wave / SK_RT), o0 + 16 * (wave % SK_RT), lane);
+    }
+}
+
 template <typename K>
 int32_t launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const GemmArgs &g, hipStream_t stream)
 {
@@ -407,6 +504,17 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
         if (y_dtype == QLLM_F32)
             return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
         return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, uint16_t>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
+    }
+    if (g.N <= 32) { // decode: stream the weights once
+        const dim3 grid((unsigned)((g.O + 16 * SK_RT - 1) / (16 * SK_RT)));
+        const int nt = g.N <= 16 ? 1 : 2;
+        const size_t lds = (size_t)SK_WAVES * nt * SK_RT * 64 * sizeof(v4i);
+        if (y_dtype == QLLM_F32) {
+            if (nt == 1) return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, float, 1>, grid, dim3(SK_THREADS), lds, g, stream);
+            return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, float, 2>, grid, dim3(SK_THREADS), lds, g, stream);
+        }
+        if (nt == 1) return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, uint16_t, 1>, grid, dim3(SK_THREADS), lds, g, stream);
+        return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, uint16_t, 2>, grid, dim3(SK_THREADS), lds, g, stream);
     }
     const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
     if (y_dtype == QLLM_F32) return launch_kernel(int_gemm_kernel<ABITS, WBITS, float>, grid, dim3(THREADS), 0, g, stream);

@@ -229,7 +229,8 @@ def check_y(oracle, y, ref_f32, y_dtype):
 
 
 @pytest.mark.parametrize("a_bits,w_bits", [(4, 4), (6, 6), (8, 8), (8, 4)])
-@pytest.mark.parametrize("N,K,O", [(1, 1, 1), (16, 64, 16), (130, 300, 200), (257, 1030, 129), (64, 2048, 384)])
+@pytest.mark.parametrize("N,K,O", [(1, 1, 1), (16, 64, 16), (3, 520, 70), (17, 2300, 33), (32, 4352, 64), (130, 300, 200),
+                                   (257, 1030, 129), (64, 2048, 384)])
 @pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
 def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
     rng = np.random.default_rng(N * 1000 + K + O + a_bits)
