@@ -386,31 +386,54 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
     finish_wave_tile<ABITS, WBITS, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
 }
 
-// ---- few tokens (decode): the weights are read once from HBM and that is the whole cost, so nothing
-// is staged.  A workgroup owns 32 output features (two matrix-core row tiles) and all N <= 16 NT tokens (NT 1 or 2);
-// its 8 waves split K: wave w takes the 256-code steps w, w + 8, ...  In a step the lane (r, c) of a
-// wave loads, for each of its rows, the 64 consecutive codes 256 s + 64 c .. + 63 straight from
-// global memory (rows of the weights: HBM; rows of the activations: L2, every workgroup reads them),
-// expands them in registers and issues four matrix-core operations, the m-th on codes 16 m .. 16 m + 15
-// of every lane's 64: which 64 codes of the step one operation sums is free as long as both
-// operands agree.  The waves' partial tiles are added up through LDS.
+// ---- few tokens (decode): the weights are read once from HBM and that is the whole cost.  A
+// workgroup owns 32 output features (two matrix-core row tiles) and all N <= 16 NT tokens (NT 1 or 2);
+// its 8 waves split K: wave w takes the 256-code steps w, w + 8, ... and works on its own, without
+// barriers, until the partial tiles are added up at the end.
+//   * Global loads are laid out for the memory pipeline, not for the matrix cores: consecutive lanes
+//     take consecutive 16-byte pieces of a row's 256 codes, so one load instruction touches whole
+//     cache lines (a lane per matrix-core operand row would touch three to four times as many lines,
+//     and the address unit, one line per cycle, would be the limit).  Two steps' loads are in flight.
+//   * The pieces pass through a wave-private strip of LDS, still packed, and come back as the 64 codes
+//     256 s + 64 c .. + 63 of row r for lane (r, c), are expanded in registers and feed four
+//     matrix-core operations, the m-th on codes 16 m .. 16 m + 15 of every lane's 64: which 64 codes
+//     of the step one operation sums is free as long as both operands agree.
 constexpr int SK_THREADS = 512, SK_WAVES = 8, SK_RT = 2, SK_STEP = 256;
+
+template <int BITS>
+constexpr int SK_ROW = SK_STEP * BITS / 8 + 16; // bytes of LDS per row and step: the packed codes and a pad against bank conflicts
+
+template <int ABITS, int WBITS, int NT>
+constexpr int SK_STRIP = 16 * SK_RT * SK_ROW<WBITS> + 16 * NT * SK_ROW<ABITS>; // LDS bytes per wave
 
 template <int ABITS, int WBITS, typename YT, int NT>
 __global__ __launch_bounds__(SK_THREADS) void int_gemm_skinny_kernel(const GemmArgs g)
 {
-    extern __shared__ __align__(16) uint8_t sk_lds[]; // [SK_WAVES][NT * SK_RT][64] v4i
-    v4i *red = reinterpret_cast<v4i *>(sk_lds);
+    // [SK_WAVES] strips; afterwards reused as [SK_WAVES][NT * SK_RT][64] v4i for the final sum
+    extern __shared__ __align__(16) uint8_t sk_lds[];
     constexpr bool PERM = ABITS == 4 && WBITS == 4;
+    constexpr int WPIECES = SK_STEP * WBITS / 8 / 16, APIECES = SK_STEP * ABITS / 8 / 16; // 16-byte pieces per row and step
+    constexpr int WLOADS = 16 * SK_RT * WPIECES / 64, ALOADS = 16 * NT * APIECES / 64;     // load instructions per step
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, c = lane >> 4;
     const int o0 = blockIdx.x * (16 * SK_RT);
+    uint8_t *w_strip = sk_lds + wave * SK_STRIP<ABITS, WBITS, NT>, *a_strip = w_strip + 16 * SK_RT * SK_ROW<WBITS>;
 
-    const uint8_t *w_row[SK_RT], *a_row[NT];
+    // piece lane + 64 t of a step: where it comes from (without the step's offset) and where it goes
+    const uint8_t *w_src[WLOADS], *a_src[ALOADS];
+    int w_dst[WLOADS], a_dst[ALOADS];
 #pragma unroll
-    for (int j = 0; j < SK_RT; ++j) w_row[j] = g.w_codes + (int64_t)min(o0 + 16 * j + r, g.O - 1) * g.w_row_bytes;
+    for (int t = 0; t < WLOADS; ++t) {
+        const int q = lane + 64 * t, row = q / WPIECES, piece = q % WPIECES;
+        w_src[t] = g.w_codes + (int64_t)min(o0 + row, g.O - 1) * g.w_row_bytes + 16 * piece;
+        w_dst[t] = row * SK_ROW<WBITS> + 16 * piece;
+    }
 #pragma unroll
-    for (int i = 0; i < NT; ++i) a_row[i] = g.a_codes + (int64_t)min(16 * i + r, g.N - 1) * g.a_row_bytes;
+    for (int t = 0; t < ALOADS; ++t) {
+        const int q = lane + 64 * t, row = q / APIECES, piece = q % APIECES;
+        a_src[t] = g.a_codes + (int64_t)min(row, g.N - 1) * g.a_row_bytes + 16 * piece;
+        a_dst[t] = row * SK_ROW<ABITS> + 16 * piece;
+    }
 
     v4i acc[NT][SK_RT];
 #pragma unroll
@@ -418,49 +441,69 @@ __global__ __launch_bounds__(SK_THREADS) void int_gemm_skinny_kernel(const GemmA
 #pragma unroll
         for (int j = 0; j < SK_RT; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
-    Unit<WBITS> uw0[SK_RT], uw1[SK_RT];
-    Unit<ABITS> ua0[NT], ua1[NT];
-    auto fetch = [&](Unit<WBITS> (&uw)[SK_RT], Unit<ABITS> (&ua)[NT], int s) {
+    v4i w0[WLOADS], a0[ALOADS], w1[WLOADS], a1[ALOADS]; // two register stages
+    auto fetch = [&](v4i (&tw)[WLOADS], v4i (&ta)[ALOADS], int s) {
 #pragma unroll
-        for (int j = 0; j < SK_RT; ++j) load_unit<WBITS>(uw[j], w_row[j], 4 * s + c);
+        for (int k = 0; k < WLOADS; ++k) tw[k] = *reinterpret_cast<const v4i *>(w_src[k] + (int64_t)s * (SK_STEP * WBITS / 8));
 #pragma unroll
-        for (int i = 0; i < NT; ++i) load_unit<ABITS>(ua[i], a_row[i], 4 * s + c);
+        for (int k = 0; k < ALOADS; ++k) ta[k] = *reinterpret_cast<const v4i *>(a_src[k] + (int64_t)s * (SK_STEP * ABITS / 8));
     };
-    auto work = [&](const Unit<WBITS> (&uw)[SK_RT], const Unit<ABITS> (&ua)[NT]) {
-        uint32_t da[NT][16], dw[SK_RT][16];
+    auto work = [&](const v4i (&tw)[WLOADS], const v4i (&ta)[ALOADS]) {
+        // a wave's LDS operations complete in order: these writes follow the previous step's reads
 #pragma unroll
-        for (int i = 0; i < NT; ++i) expand_unit<ABITS, PERM>(ua[i], da[i]);
+        for (int k = 0; k < WLOADS; ++k) *reinterpret_cast<v4i *>(w_strip + w_dst[k]) = tw[k];
 #pragma unroll
-        for (int j = 0; j < SK_RT; ++j) expand_unit<WBITS, PERM>(uw[j], dw[j]);
+        for (int k = 0; k < ALOADS; ++k) *reinterpret_cast<v4i *>(a_strip + a_dst[k]) = ta[k];
+        uint32_t da[NT][16];
 #pragma unroll
-        for (int m = 0; m < 4; ++m)
+        for (int i = 0; i < NT; ++i) {
+            Unit<ABITS> u;
+            const uint4 *p = reinterpret_cast<const uint4 *>(a_strip + (16 * i + r) * SK_ROW<ABITS> + c * (SK_STEP * ABITS / 8 / 4));
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+            for (int k = 0; k < ABITS / 2; ++k) u.r[k] = p[k];
+            expand_unit<ABITS, PERM>(u, da[i]);
+        }
 #pragma unroll
-                for (int j = 0; j < SK_RT; ++j) {
-                    const v4i fw = {(int)dw[j][4 * m], (int)dw[j][4 * m + 1], (int)dw[j][4 * m + 2], (int)dw[j][4 * m + 3]};
+        for (int j = 0; j < SK_RT; ++j) {
+            Unit<WBITS> u;
+            const uint4 *p = reinterpret_cast<const uint4 *>(w_strip + (16 * j + r) * SK_ROW<WBITS> + c * (SK_STEP * WBITS / 8 / 4));
+#pragma unroll
+            for (int k = 0; k < WBITS / 2; ++k) u.r[k] = p[k];
+            uint32_t dw[16];
+            expand_unit<WBITS, PERM>(u, dw);
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int i = 0; i < NT; ++i) {
+                    const v4i fw = {(int)dw[4 * m], (int)dw[4 * m + 1], (int)dw[4 * m + 2], (int)dw[4 * m + 3]};
                     const v4i fa = {(int)da[i][4 * m], (int)da[i][4 * m + 1], (int)da[i][4 * m + 2], (int)da[i][4 * m + 3]};
                     acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw, fa, acc[i][j], 0, 0, 0);
                 }
+        }
     };
 
+    // Every fetch is unconditional (past the end a wave re-reads its first step, from cache), so that
+    // the number of loads in flight at each wait is known when the code is compiled.
     const int n_steps = g.Kpad / SK_STEP; // rows are padded to a multiple of 256 codes
     int s = wave;
     if (s < n_steps) {
-        fetch(uw0, ua0, s);
-        while (true) { // two steps per turn: the buffers alternate without being indexed
-            if (s + SK_WAVES < n_steps) fetch(uw1, ua1, s + SK_WAVES);
-            work(uw0, ua0);
+        fetch(w0, a0, s);
+        fetch(w1, a1, s + SK_WAVES < n_steps ? s + SK_WAVES : wave);
+        while (true) { // two steps per turn: the register stages alternate without being indexed
+            work(w0, a0);
+            fetch(w0, a0, s + 2 * SK_WAVES < n_steps ? s + 2 * SK_WAVES : wave);
             s += SK_WAVES;
             if (s >= n_steps) break;
-            if (s + SK_WAVES < n_steps) fetch(uw0, ua0, s + SK_WAVES);
-            work(uw1, ua1);
+            work(w1, a1);
+            fetch(w1, a1, s + 2 * SK_WAVES < n_steps ? s + 2 * SK_WAVES : wave);
             s += SK_WAVES;
             if (s >= n_steps) break;
         }
     }
 
     // ---- add the 8 partial tiles up; wave t finishes tile t
+    __syncthreads(); // the strips are no longer read
+    v4i *red = reinterpret_cast<v4i *>(sk_lds);
 #pragma unroll
     for (int i = 0; i < NT; ++i)
 #pragma unroll
@@ -472,6 +515,14 @@ __global__ __launch_bounds__(SK_THREADS) void int_gemm_skinny_kernel(const GemmA
         for (int w = 1; w < SK_WAVES; ++w) sum[0][0] += red[(w * (NT * SK_RT) + wave) * 64 + lane];
         finish_wave_tile<ABITS, WBITS, YT, 1, 1>(g, sum, 16 * (wave / SK_RT), o0 + 16 * (wave % SK_RT), lane);
     }
+}
+
+template <int ABITS, int WBITS>
+constexpr size_t skinny_lds(int nt)
+{
+    const size_t strips = (size_t)SK_WAVES * (nt == 1 ? SK_STRIP<ABITS, WBITS, 1> : SK_STRIP<ABITS, WBITS, 2>);
+    const size_t red = (size_t)SK_WAVES * nt * SK_RT * 64 * sizeof(v4i);
+    return strips > red ? strips : red;
 }
 
 template <typename K>
@@ -508,7 +559,7 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
     if (g.N <= 32) { // decode: stream the weights once
         const dim3 grid((unsigned)((g.O + 16 * SK_RT - 1) / (16 * SK_RT)));
         const int nt = g.N <= 16 ? 1 : 2;
-        const size_t lds = (size_t)SK_WAVES * nt * SK_RT * 64 * sizeof(v4i);
+        const size_t lds = skinny_lds<ABITS, WBITS>(nt);
         if (y_dtype == QLLM_F32) {
             if (nt == 1) return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, float, 1>, grid, dim3(SK_THREADS), lds, g, stream);
             return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, float, 2>, grid, dim3(SK_THREADS), lds, g, stream);
