@@ -13,6 +13,10 @@ Prints one JSON line.  `value` is 2*N*K*O integer operations per second of the w
 `roofline_fused` the fused kernel against HBM bandwidth; both use the kernel's own average duration,
 taken with HIP events on the launch stream in a second, instrumented pass of the same K steps.
 `cpu_baseline` times the CPU oracle, as it stands, on a bounded sample of the same workload.
+`traffic` (HBM bytes per launch) cannot be measured from inside the process: it is read from the
+committed counter summary profiles/<workload>_hbm_traffic.md if that exists, else null.
+--calibration-copy adds one plain device-to-device copy of 256 MiB before the timed region, so that a
+counter run of this script also holds the reading for a kernel whose traffic is known.
 """
 import argparse
 import json
@@ -29,6 +33,19 @@ N_ROTATE = 4                 # distinct activation / output buffers cycled throu
 #                              finds its inputs in the 256 MB last-level cache
 
 
+def read_traffic(workload):
+    """HBM bytes per launch, by kernel, from the committed counter summary of this workload: table rows
+    `| kernel | FETCH_SIZE KiB | WRITE_SIZE KiB | scale | HBM bytes per launch |`."""
+    path = os.path.join(ROOT, "profiles", workload + "_hbm_traffic.md")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            cells = [c.strip().strip("`") for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and cells[4].replace(".", "", 1).isdigit():
+                out[cells[0].split("<")[0].replace("_kernel", "").replace("_big", "")] = float(cells[4])
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +54,7 @@ def main():
     ap.add_argument("--workload", default="llama70b_down")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--calibration-copy", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over tokens with no "
@@ -79,6 +97,13 @@ def main():
     qa = b.DeviceQAct(w.N, K, w.a_bits)
     setup_s = time.time() - t0
 
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     def step(i):
         b.qllm_reassembled_linear(xs[i % N_ROTATE], norm, gamma, beta, w.eps, dmap, w.a_bits, dw, ys[i % N_ROTATE], ws)
 
@@ -112,6 +137,9 @@ def main():
     gemm_tops = ops / t_gemm / 1e12
     fused_gbs = fused_bytes / t_fused / 1e9
 
+    gemm_kernel = "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits) if w.N > 128 else \
+        "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
+    traffic = read_traffic(w.name)
     result = {
         "metric": "reassembled W4A4 linear TOPS at 70B shapes; fused norm+reassembly+quant GB/s",
         "value": ops / (ms_per_step * 1e-3) / 1e12,
@@ -126,12 +154,13 @@ def main():
                    "merged_pairs": int(cal["src_idx"].size), "T_max": int(cal["num_split"].max()),
                    "rotating_buffers": N_ROTATE},
         "fused_GBps": fused_gbs,
-        "roofline": {"kernel": "int_gemm_kernel<4,4,bf16>", "bound": "mfma", "achieved": gemm_tops,
+        "roofline": {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
-                     "avg_launch_us": t_gemm * 1e6, "traffic": None},
-        "roofline_fused": {"kernel": "fused_nrq_kernel", "bound": "hbm", "achieved": fused_gbs,
+                     "avg_launch_us": t_gemm * 1e6, "traffic": traffic.get("int_gemm")},
+        "roofline_fused": {"kernel": "fused_planned_kernel", "bound": "hbm", "achieved": fused_gbs,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fused_gbs / HBM_PEAK_GBS,
-                           "avg_launch_us": t_fused * 1e6, "algorithmic_bytes": fused_bytes, "traffic": None},
+                           "avg_launch_us": t_fused * 1e6, "algorithmic_bytes": fused_bytes,
+                           "traffic": traffic.get("fused_planned")},
         "setup_s": setup_s,
     }
 
