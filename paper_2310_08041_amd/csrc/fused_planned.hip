@@ -418,6 +418,10 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         }
     }
 
+    // The reduction slots were set by the first lanes of wave 0; the other waves write theirs before
+    // the first barrier of the first row, so the set-up has to be over for everybody first.
+    __syncthreads();
+
     const XT *xbase = reinterpret_cast<const XT *>(a.x);
     Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
     int64_t row = blockIdx.x, done_row = -1;

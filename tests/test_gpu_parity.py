@@ -117,6 +117,54 @@ def test_fused_channels_merged_from_many(oracle, b, counts, planned, C, bits):
     check_fused(oracle, c, run_fused(b, c, bits), bits)
 
 
+def random_csr_map(rng, C_in, C_out, special_every):
+    """Any CSR map, not only those the paper's reassembly makes: mostly shifted unscaled copies (so that
+    plain groups with every misalignment exist), every `special_every`-th row 1..5 entries with arbitrary
+    sources (repeats allowed) and arbitrary scales; some inputs are never referenced."""
+    row_ptr, src, scale = [0], [], []
+    shift = 0
+    for ch in range(C_out):
+        if ch % special_every == special_every - 1:
+            n = int(rng.integers(1, 6))
+            src += rng.integers(0, C_in, n).tolist()
+            kind = rng.integers(0, 3)
+            if kind == 0:
+                scale += [1.0] * n                                  # the "sum" convention of a merge
+            elif kind == 1:
+                scale += [float(np.float32(1.0 / n))] * n
+            else:
+                scale += rng.uniform(-2.0, 2.0, n).astype(np.float32).tolist()
+            shift = int(rng.integers(0, 9))
+        else:
+            src.append(min(max(ch + shift - 4, 0), C_in - 1))
+            scale.append(1.0)
+        row_ptr.append(len(src))
+    return np.array(row_ptr, np.int32), np.array(src, np.int32), np.array(scale, np.float32)
+
+
+@pytest.mark.parametrize("C_in,C_out,special_every,bits", [(2048, 2100, 37, 4), (8200, 8000, 61, 6), (16392, 16500, 97, 8),
+                                                           (1000, 1003, 5, 4)])
+@pytest.mark.parametrize("use_plan", [True, False])
+def test_fused_arbitrary_csr_map(oracle, b, C_in, C_out, special_every, bits, use_plan):
+    import torch
+    rng = np.random.default_rng(C_in + bits)
+    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, special_every)
+    w = wl.WORKLOADS["llama7b_qkv"]
+    x, _, _ = wl.draw_activations(w, 5, C_in, 99)
+    gamma, _ = wl.draw_norm_params(w, C_in, 99)
+    xhat = oracle.apply_map(oracle.norm(x, 2, gamma, None, w.eps), row_ptr, src, scale)
+    codes, alpha, beta, rowsum = oracle.quantize_rows(xhat, bits)
+    plan = b.qllm_plan_map_host(row_ptr, src, scale, C_in)[0] if use_plan else None
+    dm = b.DeviceMap(row_ptr, src, scale, C_in, plan)
+    out = b.DeviceQAct(5, C_out, bits)
+    out.codes.fill_(0xAB)
+    b.qllm_norm_reassemble_quant(to_torch_x(x), 2, torch.from_numpy(gamma).cuda(), None, w.eps, dm, bits, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.codes.cpu().numpy(), oracle.pack_codes(codes, bits, out.codes.shape[1]))
+    assert np.array_equal(out.scale.cpu().numpy().view(np.uint32), alpha.view(np.uint32))
+    assert np.array_equal(out.zero.cpu().numpy(), beta) and np.array_equal(out.rowsum.cpu().numpy(), rowsum)
+
+
 @pytest.mark.parametrize("norm", ["none", "layer", "rms"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_fused_norm_kinds_and_strided_input(oracle, b, norm, dtype):
