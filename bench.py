@@ -137,6 +137,34 @@ def main():
     gemm_tops = ops / t_gemm / 1e12
     fused_gbs = fused_bytes / t_fused / 1e9
 
+    # ---- what the machine delivers on the two resources, with none of the path's work in the way
+    # (same process, same clocks): a loop of nothing but int8 matrix-core operations, and a plain
+    # stream with the fused kernel's 4 : 1 read : write mix over a buffer larger than the last-level cache
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    probe_iters = 4096
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        b.qllm_probe_mfma(cus, probe_iters, sink)
+    pe[0].record()
+    for _ in range(10):
+        b.qllm_probe_mfma(cus, probe_iters, sink)
+    pe[1].record()
+    torch.cuda.synchronize()
+    mfma_probe_tops = 10 * cus * 8 * probe_iters * 32 * 2.0 * 16 * 16 * 64 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+    sbytes = 1 << 30
+    ssrc = torch.empty(sbytes, dtype=torch.uint8, device=dev).fill_(3)
+    sdst = torch.empty(sbytes // 4, dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        b.qllm_probe_stream(ssrc, sdst, cus * 8)
+    pe[0].record()
+    for _ in range(10):
+        b.qllm_probe_stream(ssrc, sdst, cus * 8)
+    pe[1].record()
+    torch.cuda.synchronize()
+    stream_probe_gbs = 10 * (sbytes + sbytes // 4) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
+    del ssrc, sdst
+
     gemm_kernel = "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits) if w.N > 128 else \
         "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
     traffic = read_traffic(w.name)
@@ -156,11 +184,15 @@ def main():
         "fused_GBps": fused_gbs,
         "roofline": {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
-                     "avg_launch_us": t_gemm * 1e6, "traffic": traffic.get("int_gemm")},
+                     "avg_launch_us": t_gemm * 1e6, "traffic": traffic.get("int_gemm"),
+                     "probe": {"what": "loop of int8 matrix-core operations on register operands, all CUs",
+                               "achieved": mfma_probe_tops, "frac_of_probe": gemm_tops / mfma_probe_tops}},
         "roofline_fused": {"kernel": "fused_planned_kernel", "bound": "hbm", "achieved": fused_gbs,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fused_gbs / HBM_PEAK_GBS,
                            "avg_launch_us": t_fused * 1e6, "algorithmic_bytes": fused_bytes,
-                           "traffic": traffic.get("fused_planned")},
+                           "traffic": traffic.get("fused_planned"),
+                           "probe": {"what": "plain stream, 16 bytes read : 4 written, 1.25 GB per pass",
+                                     "achieved": stream_probe_gbs, "frac_of_probe": fused_gbs / stream_probe_gbs}},
         "setup_s": setup_s,
     }
 

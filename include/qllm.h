@@ -241,6 +241,19 @@ int32_t qllm_norm_channel_absmax(const void *x, int32_t x_dtype, int64_t N, int6
                                  int32_t norm, const float *gamma, const float *beta, float eps,
                                  float *absmax, float *y_dump, int64_t n_dump, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement probes (no part of the method; for callers that price the two kernels above against
+ * what the machine delivers rather than against the data-sheet peaks).
+ *   qllm_probe_mfma    `workgroups` workgroups of 8 waves; every wave issues iters * 32 int8 matrix-core
+ *                      operations (16 x 16 x 64 each, i.e. 2 * 16384 integer operations) on register
+ *                      operands shaped like 4-bit codes and touches no memory.  sink: one device int32.
+ *   qllm_probe_stream  reads `bytes` (a multiple of 16) from src and writes bytes / 4 to dst: the 4 : 1
+ *                      read : write mix of the fused kernel with bf16 input and 4-bit codes.
+ * Errors: NULL / SHAPE / ALIGN (src 16-byte, dst 4-byte aligned) / HIP.
+ */
+int32_t qllm_probe_mfma(int32_t workgroups, int32_t iters, int32_t *sink, void *hip_stream);
+int32_t qllm_probe_stream(const void *src, void *dst, int64_t bytes, int32_t workgroups, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -65,6 +65,8 @@ _sigs = {
     "qllm_pack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_unpack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_norm_channel_absmax": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, _vp, _vp, _i64, _vp]),
+    "qllm_probe_mfma": (_i32, [_i32, _i32, _vp, _vp]),
+    "qllm_probe_stream": (_i32, [_vp, _vp, _i64, _i32, _vp]),
 }
 EXPORTS = tuple(_sigs)
 for _name, (_res, _args) in _sigs.items():
@@ -295,6 +297,15 @@ def qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y_dump=None, str
                                        float(eps), _dp(absmax), _dp(y_dump), n_dump, _stream(stream)),
          "qllm_norm_channel_absmax")
     return absmax
+
+
+def qllm_probe_mfma(workgroups, iters, sink, stream=None):
+    _chk(_lib.qllm_probe_mfma(int(workgroups), int(iters), _dp(sink), _stream(stream)), "qllm_probe_mfma")
+
+
+def qllm_probe_stream(src, dst, workgroups, stream=None):
+    _chk(_lib.qllm_probe_stream(_dp(src), _dp(dst), src.numel() * src.element_size(), int(workgroups), _stream(stream)),
+         "qllm_probe_stream")
 
 
 def raw():
