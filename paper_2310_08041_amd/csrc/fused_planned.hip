@@ -32,6 +32,9 @@
 
 #include <stdint.h>
 
+#include <mutex>
+#include <vector>
+
 #include "qllm.h"
 #include "fused_common.h"
 
@@ -758,25 +761,48 @@ int cu_count()
     return n;
 }
 
+// What the runtime is asked once per kernel, workgroup size and LDS size and then remembered (no runtime
+// query sits between a caller's stream capture and the launch): the raised LDS limit and the number of
+// resident workgroups per CU.
+constexpr int MAX_LDS = 159 * 1024; // dynamic LDS a launch may ask for (160 KB per CU, less the static arrays)
+struct LaunchFacts {
+    const void *kernel;
+    int nt;
+    size_t lds;
+    int per_cu;
+};
+std::mutex facts_lock;
+std::vector<LaunchFacts> facts;
+
 template <typename K>
 int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (lds > 48 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            qllm_note_hip_error("planned fused kernel: raising the LDS limit", hipGetErrorName(e));
-            return QLLM_ERR_HIP;
+    const void *fn = reinterpret_cast<const void *>(kernel);
+    int per_cu = 0;
+    {
+        std::lock_guard<std::mutex> hold(facts_lock);
+        for (const LaunchFacts &f : facts)
+            if (f.kernel == fn && f.nt == sh.nt && f.lds == lds) per_cu = f.per_cu;
+        if (per_cu == 0) {
+            bool seen = false;
+            for (const LaunchFacts &f : facts) seen = seen || f.kernel == fn;
+            if (!seen) { // once per kernel, to the most this file ever asks for (see MAX_LDS below)
+                const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);
+                if (e != hipSuccess) {
+                    (void)hipGetLastError();
+                    qllm_note_hip_error("planned fused kernel: raising the LDS limit", hipGetErrorName(e));
+                    return QLLM_ERR_HIP;
+                }
+            }
+            // resident workgroups per CU (registers, LDS, lanes): the grid is exactly what is resident at once
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, sh.nt, lds) != hipSuccess) {
+                (void)hipGetLastError();
+                per_cu = 1;
+            }
+            if (per_cu < 1) per_cu = 1;
+            facts.push_back(LaunchFacts{fn, sh.nt, lds, per_cu});
         }
     }
-    // resident workgroups per CU (registers, LDS, lanes): the grid is exactly what is resident at once
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), sh.nt, lds) != hipSuccess) {
-        (void)hipGetLastError();
-        per_cu = 1;
-    }
-    if (per_cu < 1) per_cu = 1;
     int64_t grid = (int64_t)cu_count() * per_cu;
     if (grid > a.N) grid = a.N;
     (void)hipGetLastError();
@@ -821,7 +847,7 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     const size_t lds = ((size_t)a.n_pub + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16 +
                        (size_t)a.n_general * GROUP * 8 + ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8) +
                        ((size_t)a.n_mask + (size_t)a.n_chunks + (size_t)a.n_work) * 4;
-    if (lds + 1024 > 160 * 1024) return QLLM_ERR_WORKSPACE;
+    if (lds > (size_t)MAX_LDS) return QLLM_ERR_WORKSPACE;
     const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
     if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // a lane takes at most that many general-group entries
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);

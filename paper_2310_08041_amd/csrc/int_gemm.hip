@@ -16,6 +16,9 @@
 
 #include <stdint.h>
 
+#include <mutex>
+#include <vector>
+
 #include "qllm.h"
 
 extern "C" void qllm_note_hip_error(const char *step, const char *name);
@@ -525,16 +528,27 @@ constexpr size_t skinny_lds(int nt)
     return strips > red ? strips : red;
 }
 
+// kernels whose LDS limit has been raised (once each: every kernel here always asks for the same amount,
+// and no runtime call then sits between a caller's stream capture and the launch)
+std::mutex raised_lock;
+std::vector<const void *> raised;
+
 template <typename K>
 int32_t launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const GemmArgs &g, hipStream_t stream)
 {
     if (lds > 48 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            qllm_note_hip_error("int gemm: raising the LDS limit", hipGetErrorName(e));
-            return QLLM_ERR_HIP;
+        const void *fn = reinterpret_cast<const void *>(kernel);
+        std::lock_guard<std::mutex> hold(raised_lock);
+        bool done = false;
+        for (const void *k : raised) done = done || k == fn;
+        if (!done) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                qllm_note_hip_error("int gemm: raising the LDS limit", hipGetErrorName(e));
+                return QLLM_ERR_HIP;
+            }
+            raised.push_back(fn);
         }
     }
     (void)hipGetLastError(); // drop any stale error of the calling thread: only this launch is judged

@@ -349,3 +349,44 @@ def test_reassembled_linear_end_to_end(oracle, b, name, N, C, O, y_dtype):
     full = yn @ c.W.astype(np.float64)
     got = exp["y"].astype(np.float64)
     assert np.sqrt(((got - full) ** 2).mean()) < 0.6 * np.sqrt((full ** 2).mean())
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,N,C,O", [("llama70b_q_decode", 16, 8192, 512), ("llama7b_qkv", 300, 4096, 640)])
+def test_layer_replays_from_a_hip_graph(oracle, b, name, N, C, O):
+    """The two launches of the layer captured once and replayed (decode loops are launch bound): every
+    replay, with eager work and synchronisations in between and fresh inputs each time, must give the
+    eager result bit for bit.  The library allocates nothing and records no memset."""
+    import torch
+    w = wl.WORKLOADS[name]
+    c = make_case(oracle, w, N=N, C=C, O=O)
+    dm = device_map(b, c)
+    dw = device_weight(b, c)
+    g = torch.from_numpy(c.gamma).cuda()
+    ws = torch.empty(b.qllm_workspace_bytes(c.N, c.K, c.O, w.a_bits), dtype=torch.uint8, device="cuda")
+    x_static = to_torch_x(c.x).clone()
+    y_graph = torch.zeros((c.N, c.O), dtype=torch.bfloat16, device="cuda")
+    y_eager = torch.zeros_like(y_graph)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        b.qllm_reassembled_linear(x_static, c.norm, g, None, c.eps, dm, w.a_bits, dw, y_graph, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        b.qllm_reassembled_linear(x_static, c.norm, g, None, c.eps, dm, w.a_bits, dw, y_graph, ws)
+    ws2 = torch.empty_like(ws)
+    for rep in range(4):
+        x_new = to_torch_x(wl.draw_activations(w, c.N, c.C, 1000 + rep)[0])
+        x_static.copy_(x_new)
+        y_graph.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        b.qllm_reassembled_linear(x_new, c.norm, g, None, c.eps, dm, w.a_bits, dw, y_eager, ws2)   # eager, other buffers
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16)), f"replay {rep} differs from eager"
+    # and the last eager result is the oracle's
+    exp = oracle.reassembled_linear(wl.draw_activations(w, c.N, c.C, 1003)[0], c.norm, c.gamma, c.beta, c.eps, c.T, c.src_idx,
+                                    c.dst_idx, w.a_bits, (c.wcodes, c.aw, c.bw, c.cs))
+    check_y(oracle, y_eager, exp["y"], "bf16")
