@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph holding one step per rotating buffer set (launch-bound shapes)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over tokens with no "
@@ -110,9 +112,22 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    if args.graph:
+        if args.steps % N_ROTATE:
+            sys.exit(f"bench.py: --graph needs --steps to be a multiple of {N_ROTATE}")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(N_ROTATE):
+                step(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps // N_ROTATE):
+            graph.replay()
+    else:
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
@@ -180,7 +195,7 @@ def main():
                    "w_bits": w.w_bits, "in_dtype": w.in_dtype, "out_dtype": "bf16", "norm": w.norm,
                    "theta": cal["theta"], "extra_channels": int(cal["nnz"] - w.C),
                    "merged_pairs": int(cal["src_idx"].size), "T_max": int(cal["num_split"].max()),
-                   "rotating_buffers": N_ROTATE},
+                   "rotating_buffers": N_ROTATE, "launch": "hip graph replay" if args.graph else "eager"},
         "fused_GBps": fused_gbs,
         "roofline": {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
