@@ -167,11 +167,12 @@ def test_fused_arbitrary_csr_map(oracle, b, C_in, C_out, special_every, bits, us
 
 @pytest.mark.parametrize("norm", ["none", "layer", "rms"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_fused_norm_kinds_and_strided_input(oracle, b, norm, dtype):
+@pytest.mark.parametrize("C", [1096, 8200, 20488])          # one, two and four chunks per lane
+def test_fused_norm_kinds_and_strided_input(oracle, b, norm, dtype, C):
     import dataclasses
     import torch
     w = dataclasses.replace(wl.WORKLOADS["llama7b_qkv"], norm=norm, in_dtype=dtype)
-    c = make_case(oracle, w, N=9, C=1096, O=8, real_weights=False, theta_rule=("expand", 0.02))
+    c = make_case(oracle, w, N=9, C=C, O=8, real_weights=False, theta_rule=("expand", 0.02))
     if norm == "layer":
         c.beta = np.random.default_rng(0).standard_normal(c.C).astype(np.float32)
         c2 = c
@@ -189,20 +190,21 @@ def test_fused_norm_kinds_and_strided_input(oracle, b, norm, dtype):
     check_fused(oracle, c, run_fused(b, c, 4, x=wide[:, 3:3 + c.C]), 4)
 
 
-def test_fused_degenerate_rows(oracle, b):
+@pytest.mark.parametrize("C", [264, 4104, 17000])
+def test_fused_degenerate_rows(oracle, b, C):
     """Constant rows, a zero row, one-sided rows, a row whose quotients leave the fast rounding path."""
     import dataclasses
     w = dataclasses.replace(wl.WORKLOADS["tiny"], norm="none")
-    c = make_case(oracle, w, N=8, C=264, O=8, real_weights=False, theta_rule=("fixed", 1e9))
+    c = make_case(oracle, w, N=8, C=C, O=8, real_weights=False, theta_rule=("fixed", 1e9))
     assert np.all(c.T == 1)
     x = c.x
     x[0] = 3.25
     x[1] = 0.0
     x[2] = np.abs(x[2]) + 100.0
     x[3] = -np.abs(x[3]) - 100.0
-    x[4] = 1.0e6 + (np.arange(264) % 4).astype(np.float32) * 0.0625   # |x / alpha| > 2^26: slow path
-    x[5] = np.where(np.arange(264) % 2 == 0, -6.0, 9.0)          # alpha = 1 exactly (4 bit)
-    x[6] = np.arange(264, dtype=np.float32) * 0.5 - 60.0         # exact .5 ties after scaling
+    x[4] = 1.0e6 + (np.arange(C) % 4).astype(np.float32) * 0.0625     # |x / alpha| > 2^26: slow path
+    x[5] = np.where(np.arange(C) % 2 == 0, -6.0, 9.0)            # alpha = 1 exactly (4 bit)
+    x[6] = (np.arange(C) % 240).astype(np.float32) * 0.5 - 60.0  # exact .5 ties after scaling
     for bits in (4, 6, 8):
         exp = check_fused(oracle, c, run_fused(b, c, bits), bits)
         assert exp["alpha"][0] == 1.0 and exp["beta"][0] == -3 and exp["beta"][2] < 0 and exp["beta"][3] > 2 ** bits
