@@ -369,19 +369,35 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
             load_unit<WBITS>(uw, w_row, (kt + 2) * 2 + f_ku);
         }
         const uint8_t *ta = cur, *tw = cur + LBM * LROWB;
+        // Operand fragments are requested one group of four matrix-core operations ahead of their use
+        // (the token-side fragment of row i + 1 while row i is multiplied, the feature-side fragments of
+        // the second half during the last rows of the first), so that no operation waits for an LDS
+        // read that was issued just before it.
+        v4i fw[2][4], fa[2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fw[0][j] = load_frag<LROWB>(tw, wn * 64 + j * 16 + (lane & 15), lane >> 4);
+        fa[0] = load_frag<LROWB>(ta, wm * 128 + (lane & 15), lane >> 4);
 #pragma unroll
         for (int ks = 0; ks < LKT / UNIT; ++ks) {
             const int chunk = ks * 4 + (lane >> 4);
-            v4i fa[8], fw[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) fa[i] = load_frag<LROWB>(ta, wm * 128 + i * 16 + (lane & 15), chunk);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) fw[j] = load_frag<LROWB>(tw, wn * 64 + j * 16 + (lane & 15), chunk);
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < 8; ++i) {
+                if (i < 7) fa[(i + 1) & 1] = load_frag<LROWB>(ta, wm * 128 + (i + 1) * 16 + (lane & 15), chunk);
+                else if (ks + 1 < LKT / UNIT) fa[(i + 1) & 1] = load_frag<LROWB>(ta, wm * 128 + (lane & 15), chunk + 4);
+                if (i >= 4 && ks + 1 < LKT / UNIT)
+                    fw[(ks + 1) & 1][i - 4] = load_frag<LROWB>(tw, wn * 64 + (i - 4) * 16 + (lane & 15), chunk + 4);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[ks & 1][j], fa[i & 1], acc[i][j], 0, 0, 0);
+            }
+        }
+        // prescribed order: the first six reads, then four matrix-core operations and the next read(s)
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+        for (int grp = 0; grp < 16; ++grp) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            if (grp >= 4 && grp < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __syncthreads();
     }
