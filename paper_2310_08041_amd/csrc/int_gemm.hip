@@ -126,6 +126,17 @@ __device__ __forceinline__ void store_unit(const Unit<BITS> &u, uint8_t *tile, i
     }
 }
 
+// Chunk c (16 codes -> 16 bytes) of one unit, expanded and stored; c is a constant where this is
+// called, so only that chunk's share of the expansion is left of expand_unit.
+template <int BITS, int ROWB, bool PERM>
+__device__ __forceinline__ void store_chunk(const Unit<BITS> &u, uint8_t *tile, int row, int ku, int c)
+{
+    uint32_t d[16];
+    expand_unit<BITS, PERM>(u, d);
+    const int chunk = (ku * 4 + c) ^ (row & 7);
+    *reinterpret_cast<uint4 *>(tile + row * ROWB + chunk * 16) = make_uint4(d[4 * c], d[4 * c + 1], d[4 * c + 2], d[4 * c + 3]);
+}
+
 template <int ROWB>
 __device__ __forceinline__ v4i load_frag(const uint8_t *tile, int row, int chunk)
 {
@@ -352,55 +363,82 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
     load_unit<WBITS>(uw, w_row, f_ku);
     store_unit<ABITS, LROWB, PERM>(ua, lds, f_row, f_ku);
     store_unit<WBITS, LROWB, PERM>(uw, lds + LBM * LROWB, f_row, f_ku);
-    if (n_kt > 1) {
-        load_unit<ABITS>(ua, a_row, 2 + f_ku);
-        load_unit<WBITS>(uw, w_row, 2 + f_ku);
-    }
+    load_unit<ABITS>(ua, a_row, min(1, n_kt - 1) * 2 + f_ku);
+    load_unit<WBITS>(uw, w_row, min(1, n_kt - 1) * 2 + f_ku);
     __syncthreads();
+
+    // One K-tile = 16 groups of four matrix-core operations: group s multiplies the token-side
+    // fragment s (rows 16 (s & 7) .. of the wave's 128, half s >> 3 of the K-tile) with the four
+    // feature-side fragments of that half.  Everything else is spread over the groups, in an order
+    // fixed by scheduling fences, so that the matrix cores never wait for it:
+    //   * token-side fragment s + DIST is requested in group s (a ring of RING registers), also
+    //     across the K-tile boundary; the feature-side fragments of the second half in groups 0..3,
+    //     those of the next K-tile's first half in the last two groups;
+    //   * the refill of the other buffer (expand one 16-byte chunk of the unit fetched a K-tile
+    //     ago, store it) takes groups 4..11, one chunk each; the fetch of the K-tile after that
+    //     follows in group 12;
+    //   * the one barrier per K-tile sits after group 15 - DIST: every refill store precedes it and
+    //     every read of the next K-tile follows it; every read of this K-tile precedes it and the
+    //     stores that will overwrite this buffer follow the next one.
+    // The last K-tile refills and prefetches like the others (a re-read of the last K-tile into the
+    // buffer nobody reads any more), which keeps the loop body free of branches.
+    constexpr int DIST = 2, RING = 4, GROUPS = 8 * (LKT / UNIT), REFILL0 = 4;
+    static_assert(GROUPS == 16 && GROUPS % RING == 0 && DIST < RING && REFILL0 + 8 <= GROUPS - DIST, "group plan");
+    // The loop is rotated by DIST groups: an iteration starts, right after the barrier, with the last
+    // DIST groups of the previous K-tile (which request the first fragments of this one) and ends
+    // with the barrier, so that no LDS request is pending across the loop's back edge.  Before the
+    // first K-tile those groups multiply zeros; after the last one they run once more on their own.
+    v4i fw[2][4], fa[RING];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fw[1][j] = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int s = GROUPS - DIST; s < GROUPS; ++s) fa[s % RING] = v4i{0, 0, 0, 0};
+    const int frow = lane & 15, fchunk = lane >> 4;
 
     for (int kt = 0; kt < n_kt; ++kt) {
         uint8_t *cur = lds + (kt & 1) * LBUF, *nxt = lds + ((kt + 1) & 1) * LBUF;
-        if (kt + 1 < n_kt) { // nobody reads `nxt` any more: the barrier that ended iteration kt-1 saw to that
-            store_unit<ABITS, LROWB, PERM>(ua, nxt, f_row, f_ku);
-            store_unit<WBITS, LROWB, PERM>(uw, nxt + LBM * LROWB, f_row, f_ku);
-        }
-        if (kt + 2 < n_kt) {
-            load_unit<ABITS>(ua, a_row, (kt + 2) * 2 + f_ku);
-            load_unit<WBITS>(uw, w_row, (kt + 2) * 2 + f_ku);
-        }
-        const uint8_t *ta = cur, *tw = cur + LBM * LROWB;
-        // Operand fragments are requested one group of four matrix-core operations ahead of their use
-        // (the token-side fragment of row i + 1 while row i is multiplied, the feature-side fragments of
-        // the second half during the last rows of the first), so that no operation waits for an LDS
-        // read that was issued just before it.
-        v4i fw[2][4], fa[2];
+        const int kt2 = min(kt + 2, n_kt - 1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fw[0][j] = load_frag<LROWB>(tw, wn * 64 + j * 16 + (lane & 15), lane >> 4);
-        fa[0] = load_frag<LROWB>(ta, wm * 128 + (lane & 15), lane >> 4);
-#pragma unroll
-        for (int ks = 0; ks < LKT / UNIT; ++ks) {
-            const int chunk = ks * 4 + (lane >> 4);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (i < 7) fa[(i + 1) & 1] = load_frag<LROWB>(ta, wm * 128 + (i + 1) * 16 + (lane & 15), chunk);
-                else if (ks + 1 < LKT / UNIT) fa[(i + 1) & 1] = load_frag<LROWB>(ta, wm * 128 + (lane & 15), chunk + 4);
-                if (i >= 4 && ks + 1 < LKT / UNIT)
-                    fw[(ks + 1) & 1][i - 4] = load_frag<LROWB>(tw, wn * 64 + (i - 4) * 16 + (lane & 15), chunk + 4);
+        for (int u = 0; u < GROUPS; ++u) {
+            const int s = (u + GROUPS - DIST) % GROUPS, ks = s >> 3, t = (s + DIST) % GROUPS;
+            auto multiply = [&] {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[ks & 1][j], fa[i & 1], acc[i][j], 0, 0, 0);
+                    acc[s & 7][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[ks][j], fa[s % RING], acc[s & 7][j], 0, 0, 0);
+            };
+            // group 0 is the first to use what the two groups before it asked for: its own requests
+            // come after its operations, so that it waits for nothing newer than it needs
+            if (s == 0) {
+                multiply();
+                __builtin_amdgcn_sched_barrier(0);
             }
-        }
-        // prescribed order: the first six reads, then four matrix-core operations and the next read(s)
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+            // fragment requests (all from this iteration's K-tile)
+            fa[t % RING] = load_frag<LROWB>(cur, wm * 128 + (t & 7) * 16 + frow, (t >> 3) * 4 + fchunk);
+            if (s < 4) fw[1][s] = load_frag<LROWB>(cur + LBM * LROWB, wn * 64 + s * 16 + frow, 4 + fchunk);
+            if (s >= GROUPS - 2) {
 #pragma unroll
-        for (int grp = 0; grp < 16; ++grp) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-            if (grp >= 4 && grp < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                for (int h = 0; h < 2; ++h) {
+                    const int j = (s - (GROUPS - 2)) * 2 + h;
+                    fw[0][j] = load_frag<LROWB>(cur + LBM * LROWB, wn * 64 + j * 16 + frow, fchunk);
+                }
+            }
+            // refill of the other buffer, fetch of the K-tile after it
+            if (s >= REFILL0 && s < REFILL0 + 4) store_chunk<ABITS, LROWB, PERM>(ua, nxt, f_row, f_ku, s - REFILL0);
+            if (s >= REFILL0 + 4 && s < REFILL0 + 8) store_chunk<WBITS, LROWB, PERM>(uw, nxt + LBM * LROWB, f_row, f_ku, s - REFILL0 - 4);
+            if (s == REFILL0 + 8) {
+                load_unit<ABITS>(ua, a_row, kt2 * 2 + f_ku);
+                load_unit<WBITS>(uw, w_row, kt2 * 2 + f_ku);
+            }
+            if (s != 0) multiply();
+            if (u == GROUPS - 1) __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
     }
+#pragma unroll
+    for (int s = GROUPS - DIST; s < GROUPS; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[s & 7][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[1][j], fa[s % RING], acc[s & 7][j], 0, 0, 0);
 
     finish_wave_tile<ABITS, WBITS, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
 }
