@@ -383,7 +383,7 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
     // The last K-tile refills and prefetches like the others (a re-read of the last K-tile into the
     // buffer nobody reads any more), which keeps the loop body free of branches.
     constexpr int DIST = 2, RING = 4, GROUPS = 8 * (LKT / UNIT), REFILL0 = 4;
-    static_assert(GROUPS == 16 && GROUPS % RING == 0 && DIST < RING && REFILL0 + 8 <= GROUPS - DIST, "group plan");
+    static_assert(GROUPS == 16 && GROUPS % RING == 0 && DIST < RING && REFILL0 + 8 < GROUPS - DIST, "group plan");
     // The loop is rotated by DIST groups: an iteration starts, right after the barrier, with the last
     // DIST groups of the previous K-tile (which request the first fragments of this one) and ends
     // with the barrier, so that no LDS request is pending across the loop's back edge.  Before the
@@ -441,6 +441,153 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
             acc[s & 7][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[1][j], fa[s % RING], acc[s & 7][j], 0, 0, 0);
 
     finish_wave_tile<ABITS, WBITS, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
+}
+
+// ---- 4-bit codes on both sides, many tokens: the same 256 x 256 tile and 2 x 4 waves, but the codes
+// stay packed (two per byte) in LDS and are split into bytes in registers, after the operand read.
+// That halves the LDS traffic of the kernel above, which was what held it back: per K-tile of 128
+// codes its expanded stores and operand reads kept LDS busy as long as the matrix cores were.
+//   * LDS row = the 64 packed bytes of a K-tile; a lane (r, q) of an operand read takes the 16 bytes
+//     q of row r: the low nibbles are its 16 codes for one matrix-core operation (m = 0), the high
+//     nibbles those for a second one (m = 1).  Which 64 codes of the K-tile an operation sums is free
+//     as long as both operands agree, and they do: same read, same split.
+//   * Where a row's four 16-byte pieces sit in LDS is chosen for the banks.  Within a block of 16
+//     rows, row r is stored as row place16(r) and its piece q at position q ^ (r & 3): a read by
+//     lanes (r, q) then covers the block's 1 KB exactly once and each lane falls on the same banks
+//     as in the byte-per-code layout of the kernel above (measured free of conflicts; rows kept in
+//     order with any XOR of the piece index cost two passes per read).  The stores go the other way
+//     round: lane t writes the t-th 16 bytes of the buffer half and fetches whichever row and piece
+//     belong there, still four lanes per row.
+//   * One K-tile = 16 groups of four matrix-core operations, (i, m) = (s >> 1, s & 1): token rows
+//     16 i .. of the wave's 128, nibble m, times the wave's four feature-side operands of nibble m.
+//     The eight feature-side operands of a K-tile stay split in registers; the token side streams:
+//     packed read two row blocks ahead (a ring of four), split one group ahead.
+//   * As above the order is fixed by scheduling fences, the loop is rotated by four groups (it
+//     starts, after the barrier, with the last four groups of the previous K-tile, which request
+//     the first operands of this one and multiply zeros the first time round) and refills without
+//     branches.
+constexpr int PROWB = 64;                       // packed bytes per LDS row and K-tile
+constexpr int PBUF = (LBM + LBN) * PROWB;       // 32 KB per buffer
+constexpr int PKT = 128;                        // codes per K-tile
+
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4i nib_lo(v4u p) { return (v4i)(p & 0x0f0f0f0fu); }
+__device__ __forceinline__ v4i nib_hi(v4u p) { return (v4i)((p >> 4) & 0x0f0f0f0fu); }
+// place of row r (0..15) inside its block of 16 rows, and the row stored at place p
+__device__ __forceinline__ int place16(int r) { return ((r & 2) << 2) | ((r & 8) >> 1) | ((r & 1) << 1) | ((r & 4) >> 2); }
+__device__ __forceinline__ int row_at16(int p) { return ((p & 2) >> 1) | ((p & 8) >> 2) | ((p & 1) << 2) | ((p & 4) << 1); }
+
+template <typename YT>
+__global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3; // wave tile: 128 tokens x 64 features
+    const int n0 = blockIdx.y * LBM, o0 = blockIdx.x * LBN;
+
+    // fetch assignment: lane t fills the t-th 16 bytes of each half (128 rows) of an operand's buffer,
+    // that is piece f_piece of row f_row (+ 128)
+    const int f_row = ((tid >> 2) & ~15) | row_at16((tid >> 2) & 15), f_piece = (tid & 3) ^ (f_row & 3);
+    const uint8_t *a_src[2], *w_src[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) { // past the edge: re-read the last row
+        a_src[h] = g.a_codes + (int64_t)min(n0 + h * 128 + f_row, g.N - 1) * g.a_row_bytes + f_piece * 16;
+        w_src[h] = g.w_codes + (int64_t)min(o0 + h * 128 + f_row, g.O - 1) * g.w_row_bytes + f_piece * 16;
+    }
+    const int st_off = tid * 16; // + h * 128 rows, + LBM rows for W
+
+    // operand reads: lane (r, q) takes piece q of row r of a block of 16 rows
+    const int r = lane & 15, q = lane >> 4;
+    const int a_off = (wm * 128 + place16(r)) * PROWB + ((q ^ (r & 3)) << 4);      // + i * 16 rows
+    const int w_off = (LBM + wn * 64 + place16(r)) * PROWB + ((q ^ (r & 3)) << 4); // + j * 16 rows
+
+    v4i acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+    const int n_kt = g.Kpad / PKT;
+    v4u ga[2], gw[2]; // the K-tile being fetched
+    auto fetch = [&](int kt) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) ga[h] = *reinterpret_cast<const v4u *>(a_src[h] + (int64_t)kt * PROWB);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) gw[h] = *reinterpret_cast<const v4u *>(w_src[h] + (int64_t)kt * PROWB);
+    };
+    fetch(0);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        *reinterpret_cast<v4u *>(lds + st_off + h * 128 * PROWB) = ga[h];
+        *reinterpret_cast<v4u *>(lds + st_off + (LBM + h * 128) * PROWB) = gw[h];
+    }
+    fetch(min(1, n_kt - 1));
+    __syncthreads();
+
+    constexpr int GROUPS = 16, ROT = 4, RING = 4, AHEAD = 2;
+    v4u ap[RING], wp[4];
+    v4i fa[2], fw[2][4];
+#pragma unroll
+    for (int k = 0; k < RING; ++k) ap[k] = v4u{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fw[0][j] = fw[1][j] = v4i{0, 0, 0, 0};
+    fa[0] = fa[1] = v4i{0, 0, 0, 0};
+
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const uint8_t *cur = lds + (kt & 1) * PBUF;
+        uint8_t *nxt = lds + ((kt + 1) & 1) * PBUF;
+        const int kt2 = min(kt + 2, n_kt - 1);
+#pragma unroll
+        for (int u = 0; u < GROUPS; ++u) {
+            const int s = (u + GROUPS - ROT) % GROUPS, i = s >> 1, m = s & 1;
+            // requests, all from this iteration's K-tile: token rows two blocks ahead, feature rows
+            // in the first two groups
+            if (m == 0) ap[(i + AHEAD) % RING] = *reinterpret_cast<const v4u *>(cur + a_off + ((i + AHEAD) & 7) * 16 * PROWB);
+            if (u < 2) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wp[2 * u + h] = *reinterpret_cast<const v4u *>(cur + w_off + (2 * u + h) * 16 * PROWB);
+            }
+            // refill of the other buffer, then the fetch of the K-tile after it
+            if (s == 2) *reinterpret_cast<v4u *>(nxt + st_off) = ga[0];
+            if (s == 3) *reinterpret_cast<v4u *>(nxt + st_off + 128 * PROWB) = ga[1];
+            if (s == 4) *reinterpret_cast<v4u *>(nxt + st_off + LBM * PROWB) = gw[0];
+            if (s == 5) *reinterpret_cast<v4u *>(nxt + st_off + (LBM + 128) * PROWB) = gw[1];
+            if (s == 6) fetch(kt2);
+            // the group's four operations
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[m][j], fa[m], acc[i][j], 0, 0, 0);
+            // splits for the next group: the other nibble of this row block, or the next block's low one
+            if (m == 0) fa[1] = nib_hi(ap[i % RING]);
+            else fa[0] = nib_lo(ap[(i + 1) % RING]);
+            // feature side of the new K-tile: low nibbles once the last low group of the old one is
+            // through (group 14), high nibbles after its last high group (15)
+            if (s == GROUPS - 1) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) fw[0][j] = nib_lo(wp[j]);
+            }
+            if (s == 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) fw[1][j] = nib_hi(wp[j]);
+            }
+            if (u == GROUPS - 1) __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // the last four groups of the last K-tile
+#pragma unroll
+    for (int s = GROUPS - ROT; s < GROUPS; ++s) {
+        const int i = s >> 1, m = s & 1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[m][j], fa[m], acc[i][j], 0, 0, 0);
+        if (m == 0) fa[1] = nib_hi(ap[i % RING]);
+        else if (i < 7) fa[0] = nib_lo(ap[(i + 1) % RING]);
+    }
+
+    finish_wave_tile<4, 4, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
 }
 
 // ---- few tokens (decode): the weights are read once from HBM and that is the whole cost.  A
@@ -620,6 +767,11 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     if (g.N > 128) { // enough tokens to fill 256-row tiles
         const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
+        if constexpr (ABITS == 4 && WBITS == 4) {
+            if (y_dtype == QLLM_F32)
+                return launch_kernel(int_gemm_w4a4_kernel<float>, grid, dim3(LTHREADS), 2 * PBUF, g, stream);
+            return launch_kernel(int_gemm_w4a4_kernel<uint16_t>, grid, dim3(LTHREADS), 2 * PBUF, g, stream);
+        }
         if (y_dtype == QLLM_F32)
             return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
         return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, uint16_t>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
