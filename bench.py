@@ -42,7 +42,7 @@ def read_traffic(workload):
         for line in open(path):
             cells = [c.strip().strip("`") for c in line.strip().strip("|").split("|")]
             if len(cells) == 5 and cells[4].replace(".", "", 1).isdigit():
-                out[cells[0].split("<")[0].replace("_kernel", "").replace("_big", "")] = float(cells[4])
+                out[cells[0].split("<")[0].replace("_kernel", "").replace("_big", "").replace("_w4a4", "")] = float(cells[4])
     return out
 
 
@@ -180,7 +180,8 @@ def main():
     stream_probe_gbs = 10 * (sbytes + sbytes // 4) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
     del ssrc, sdst
 
-    gemm_kernel = "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits) if w.N > 128 else \
+    gemm_kernel = ("int_gemm_w4a4_kernel<bf16>" if (w.a_bits, w.w_bits) == (4, 4) else
+                   "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits)) if w.N > 128 else \
         "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
     traffic = read_traffic(w.name)
     result = {

@@ -469,6 +469,10 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_big_kernel(const GemmArgs g
 constexpr int PROWB = 64;                       // packed bytes per LDS row and K-tile
 constexpr int PBUF = (LBM + LBN) * PROWB;       // 32 KB per buffer
 constexpr int PKT = 128;                        // codes per K-tile
+constexpr int NBUF = 4;                         // ring of LDS buffers
+constexpr int WAIT_VM8 = 8 | (7 << 4) | (15 << 8);       // s_waitcnt vmcnt(8) and nothing else
+constexpr int WAIT_VM0 = 0 | (7 << 4) | (15 << 8);       // s_waitcnt vmcnt(0) and nothing else
+constexpr int WAIT_VM8_LGKM0 = 8 | (7 << 4) | (0 << 8);  // s_waitcnt vmcnt(8) lgkmcnt(0)
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
@@ -495,7 +499,6 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs 
         a_src[h] = g.a_codes + (int64_t)min(n0 + h * 128 + f_row, g.N - 1) * g.a_row_bytes + f_piece * 16;
         w_src[h] = g.w_codes + (int64_t)min(o0 + h * 128 + f_row, g.O - 1) * g.w_row_bytes + f_piece * 16;
     }
-    const int st_off = tid * 16; // + h * 128 rows, + LBM rows for W
 
     // operand reads: lane (r, q) takes piece q of row r of a block of 16 rows
     const int r = lane & 15, q = lane >> 4;
@@ -508,24 +511,31 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs 
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
+    // Refill: 16-byte global loads that write LDS directly (lane l of a wave lands at the wave's LDS
+    // base + 16 l, which is why the stores' order above is the lanes' order): no staging registers, no
+    // LDS store instructions.  Wave w brings in rows 16 w .. 16 w + 15 of each half of each operand,
+    // four loads per K-tile, issued three K-tiles ahead into a ring of four buffers.  Loads complete
+    // in order, so "at most eight outstanding" before the barrier means the next K-tile has landed.
     const int n_kt = g.Kpad / PKT;
-    v4u ga[2], gw[2]; // the K-tile being fetched
-    auto fetch = [&](int kt) {
+    auto fetch = [&](int kt) { // K-tile kt (clamped to the last one) -> buffer kt & 3
+        const int ktc = min(kt, n_kt - 1);
+        uint8_t *dst = lds + (kt & (NBUF - 1)) * PBUF + wave * 16 * PROWB;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) ga[h] = *reinterpret_cast<const v4u *>(a_src[h] + (int64_t)kt * PROWB);
+        for (int h = 0; h < 2; ++h)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(a_src[h] + (int64_t)ktc * PROWB),
+                                             (__attribute__((address_space(3))) void *)(dst + h * 128 * PROWB), 16, 0, 0);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) gw[h] = *reinterpret_cast<const v4u *>(w_src[h] + (int64_t)kt * PROWB);
+        for (int h = 0; h < 2; ++h)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[h] + (int64_t)ktc * PROWB),
+                                             (__attribute__((address_space(3))) void *)(dst + (LBM + h * 128) * PROWB), 16, 0, 0);
     };
     fetch(0);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        *reinterpret_cast<v4u *>(lds + st_off + h * 128 * PROWB) = ga[h];
-        *reinterpret_cast<v4u *>(lds + st_off + (LBM + h * 128) * PROWB) = gw[h];
-    }
-    fetch(min(1, n_kt - 1));
+    fetch(1);
+    fetch(2);
+    __builtin_amdgcn_s_waitcnt(WAIT_VM8);
     __syncthreads();
 
-    constexpr int GROUPS = 16, ROT = 4, RING = 4, AHEAD = 2;
+    constexpr int GROUPS = 16, ROT = 5, RING = 4, AHEAD = 3;
     v4u ap[RING], wp[4];
     v4i fa[2], fw[2][4];
 #pragma unroll
@@ -535,26 +545,12 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs 
     fa[0] = fa[1] = v4i{0, 0, 0, 0};
 
     for (int kt = 0; kt < n_kt; ++kt) {
-        const uint8_t *cur = lds + (kt & 1) * PBUF;
-        uint8_t *nxt = lds + ((kt + 1) & 1) * PBUF;
-        const int kt2 = min(kt + 2, n_kt - 1);
+        const uint8_t *cur = lds + (kt & (NBUF - 1)) * PBUF;
 #pragma unroll
         for (int u = 0; u < GROUPS; ++u) {
             const int s = (u + GROUPS - ROT) % GROUPS, i = s >> 1, m = s & 1;
-            // requests, all from this iteration's K-tile: token rows two blocks ahead, feature rows
-            // in the first two groups
-            if (m == 0) ap[(i + AHEAD) % RING] = *reinterpret_cast<const v4u *>(cur + a_off + ((i + AHEAD) & 7) * 16 * PROWB);
-            if (u < 2) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    wp[2 * u + h] = *reinterpret_cast<const v4u *>(cur + w_off + (2 * u + h) * 16 * PROWB);
-            }
-            // refill of the other buffer, then the fetch of the K-tile after it
-            if (s == 2) *reinterpret_cast<v4u *>(nxt + st_off) = ga[0];
-            if (s == 3) *reinterpret_cast<v4u *>(nxt + st_off + 128 * PROWB) = ga[1];
-            if (s == 4) *reinterpret_cast<v4u *>(nxt + st_off + LBM * PROWB) = gw[0];
-            if (s == 5) *reinterpret_cast<v4u *>(nxt + st_off + (LBM + 128) * PROWB) = gw[1];
-            if (s == 6) fetch(kt2);
+            // the K-tile three ahead, into the buffer whose last reader passed the previous barrier
+            if (s == 2) fetch(kt + 3);
             // the group's four operations
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -572,11 +568,30 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs 
 #pragma unroll
                 for (int j = 0; j < 4; ++j) fw[1][j] = nib_hi(wp[j]);
             }
-            if (u == GROUPS - 1) __syncthreads();
+            if (u == GROUPS - 1) {
+                // next K-tile landed (this wave's share; the barrier adds the others'), own reads done
+                __builtin_amdgcn_s_waitcnt(WAIT_VM8_LGKM0);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+            // requests come after the split that had to wait for an earlier one, so that the wait
+            // does not cover them: token rows three blocks ahead (after a high-nibble group), the
+            // feature rows of this iteration's K-tile in its first two groups.  All of them read
+            // this iteration's K-tile: the first group of the iteration is the first to look ahead.
+            __builtin_amdgcn_sched_barrier(0);
+            if (m == 1) ap[(i + AHEAD) % RING] = *reinterpret_cast<const v4u *>(cur + a_off + ((i + AHEAD) & 7) * 16 * PROWB);
+            if (u < 2) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wp[2 * u + h] = *reinterpret_cast<const v4u *>(cur + w_off + (2 * u + h) * 16 * PROWB);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    // the last four groups of the last K-tile
+    // the loads past the last K-tile went to buffers nobody reads; they must not outlive the workgroup
+    __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    // the last groups of the last K-tile
 #pragma unroll
     for (int s = GROUPS - ROT; s < GROUPS; ++s) {
         const int i = s >> 1, m = s & 1;
@@ -769,8 +784,8 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
         const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
         if constexpr (ABITS == 4 && WBITS == 4) {
             if (y_dtype == QLLM_F32)
-                return launch_kernel(int_gemm_w4a4_kernel<float>, grid, dim3(LTHREADS), 2 * PBUF, g, stream);
-            return launch_kernel(int_gemm_w4a4_kernel<uint16_t>, grid, dim3(LTHREADS), 2 * PBUF, g, stream);
+                return launch_kernel(int_gemm_w4a4_kernel<float>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
+            return launch_kernel(int_gemm_w4a4_kernel<uint16_t>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
         }
         if (y_dtype == QLLM_F32)
             return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
