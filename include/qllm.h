@@ -217,6 +217,21 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
 int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
                             int64_t C_in, int64_t C_out, int64_t nnz);
 
+/* Folds the reassembly into a preceding linear layer (Appendix B): when the activations that enter
+ * the quantized layer are the output of a linear layer y = x Wp^T + bp, disassembly and assembly can
+ * be applied to that layer's output channels once, offline, instead of to every token at run time:
+ *   Wp^[ch, :] = sum over the entries e of map row ch of scale[e] * Wp[src[e], :]      (same for bp)
+ * (columns of the paper's W^{l-1} divided by T and repeated for a split channel, averaged for merged
+ * ones).  The run-time path is then plain quantization + GEMM: call the library with norm NONE and
+ * the identity map on x Wp^^T + bp^.
+ * All pointers host.  Wp is [C_in, K_prev] row-major fp32 (one row per OUTPUT channel of the preceding
+ * layer = input channel of the quantized one), bp is [C_in] or NULL; W_out is [C_out, K_prev], b_out
+ * [C_out] (ignored when bp is NULL).  Sums are formed in double precision in entry order and rounded
+ * once.  QLLM_ERR_MAP for a malformed map (checked as by qllm_check_map_host). */
+int32_t qllm_fold_linear_host(const float *Wp, const float *bp, int64_t C_in, int64_t K_prev,
+                              const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_out,
+                              float *W_out, float *b_out);
+
 /* Reassembles and quantizes the weights of one layer (offline half of Sec. 4.1.1 / 4.1.2):
  *   W^[ch, :] = sum of W[src[e], :] over the entries e of map row ch (rows duplicated for
  *   sub-channels as in Eq. (3), summed for merged channels as in Eq. (4)), then Eq. (2) per output

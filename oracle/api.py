@@ -197,6 +197,29 @@ def reassemble_weight(W, T, src_idx, dst_idx):
     return out
 
 
+def fold_preceding_linear(Wp, bp, T, src_idx, dst_idx):
+    """Appendix B in float64: the reassembly moved into the preceding linear layer y = x Wp^T + bp.
+    Wp: [C, K_prev] (row c = output channel c of that layer), bp: [C] or None.
+    Disassembly: channel c becomes T_c rows Wp[c] / T_c (bias likewise).  Assembly: on the disassembled
+    axis, set A = even and set B = odd positions; the A-members src_idx[k] merged into B-member j are
+    replaced, together with j, by their mean (for one pair the appendix's (W_i + W_j) / 2); merged
+    A-members disappear; the rest keeps its order.  Returns (W^ [C^, K_prev], b^ [C^] or None)."""
+    Wp = np.asarray(Wp, np.float64)
+    T = np.asarray(T, np.int64)
+    src_idx, dst_idx = np.asarray(src_idx, np.int64), np.asarray(dst_idx, np.int64)
+    full = Wp if bp is None else np.concatenate([Wp, np.asarray(bp, np.float64)[:, None]], axis=1)
+    d = np.repeat(full / T[:, None], T, axis=0)                 # disassembled rows
+    total = d.copy()
+    count = np.ones(d.shape[0], np.int64)
+    gone = np.zeros(d.shape[0], bool)
+    for a, j in zip(2 * src_idx, 2 * dst_idx + 1):              # positions on the disassembled axis
+        total[j] += d[a]
+        count[j] += 1
+        gone[a] = True
+    out = (total / count[:, None])[~gone]
+    return (out, None) if bp is None else (out[:, :-1], out[:, -1])
+
+
 def int_gemm(a, w):
     """a: [N,K] u8 codes, w: [O,K] u8 codes.  Returns acc [N,O] int32."""
     a, w = _c(a, np.uint8), _c(w, np.uint8)

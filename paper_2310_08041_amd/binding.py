@@ -62,6 +62,7 @@ _sigs = {
     "qllm_plan_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, C.POINTER(_i64), C.POINTER(_i64)]),
     "qllm_check_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64]),
     "qllm_quantize_weight_host": (_i32, [_vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp]),
+    "qllm_fold_linear_host": (_i32, [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _i64, _vp, _vp]),
     "qllm_pack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_unpack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_norm_channel_absmax": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, _vp, _vp, _i64, _vp]),
@@ -177,6 +178,22 @@ def qllm_quantize_weight_host(W, row_ptr, src, bits):
     _chk(_lib.qllm_quantize_weight_host(_hp(W), c_in, O, _hp(row_ptr), _hp(src), K, int(bits), _hp(codes),
                                         _hp(scale), _hp(zero), _hp(colsum)), "qllm_quantize_weight_host")
     return dict(codes=codes, scale=scale, zero=zero, colsum=colsum, O=O, K=K, bits=int(bits))
+
+
+def qllm_fold_linear_host(Wp, bp, row_ptr, src, scale):
+    """Wp [C_in, K_prev] float32 (rows = output channels of the preceding layer), bp [C_in] or None ->
+    (W_out [C_out, K_prev], b_out [C_out] or None)."""
+    Wp = _np(Wp, np.float32)
+    row_ptr, src, scale = _np(row_ptr, np.int32), _np(src, np.int32), _np(scale, np.float32)
+    c_in, kp = Wp.shape
+    c_out = row_ptr.size - 1
+    bp = None if bp is None else _np(bp, np.float32)
+    W_out = np.empty((c_out, kp), np.float32)
+    b_out = None if bp is None else np.empty(c_out, np.float32)
+    _chk(_lib.qllm_fold_linear_host(_hp(Wp), None if bp is None else _hp(bp), c_in, kp, _hp(row_ptr), _hp(src),
+                                    _hp(scale), c_out, _hp(W_out), None if bp is None else _hp(b_out)),
+         "qllm_fold_linear_host")
+    return W_out, b_out
 
 
 def qllm_pack_codes_host(codes, bits):

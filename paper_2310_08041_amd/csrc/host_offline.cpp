@@ -378,6 +378,37 @@ int32_t qllm_unpack_codes_host(const uint8_t *packed, int64_t R, int64_t K, int3
     return QLLM_OK;
 }
 
+int32_t qllm_fold_linear_host(const float *Wp, const float *bp, int64_t C_in, int64_t K_prev,
+                              const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_out,
+                              float *W_out, float *b_out)
+{
+    if (!Wp || !row_ptr || !src || !scale || !W_out || (bp && !b_out)) return QLLM_ERR_NULL;
+    if (C_in <= 0 || K_prev <= 0 || C_out <= 0) return QLLM_ERR_SHAPE;
+    if (row_ptr[0] != 0) return QLLM_ERR_MAP;
+    for (int64_t c = 0; c < C_out; ++c)
+        if (row_ptr[c + 1] <= row_ptr[c]) return QLLM_ERR_MAP;
+    const int32_t st = qllm_check_map_host(row_ptr, src, scale, C_in, C_out, row_ptr[C_out]);
+    if (st != QLLM_OK) return st;
+    constexpr int64_t BLK = 16; // output rows per task
+    parallel_blocks((C_out + BLK - 1) / BLK, [&](int64_t b) {
+        std::vector<double> acc((size_t)K_prev);
+        for (int64_t c = b * BLK; c < std::min(C_out, (b + 1) * BLK); ++c) {
+            std::fill(acc.begin(), acc.end(), 0.0);
+            double bacc = 0.0;
+            for (int32_t e = row_ptr[c]; e < row_ptr[c + 1]; ++e) {
+                const double sc = (double)scale[e];
+                const float *w = Wp + (int64_t)src[e] * K_prev;
+                for (int64_t k = 0; k < K_prev; ++k) acc[(size_t)k] += sc * (double)w[k];
+                if (bp) bacc += sc * (double)bp[src[e]];
+            }
+            float *out = W_out + c * K_prev;
+            for (int64_t k = 0; k < K_prev; ++k) out[k] = (float)acc[(size_t)k];
+            if (bp) b_out[c] = (float)bacc;
+        }
+    });
+    return QLLM_OK;
+}
+
 int32_t qllm_quantize_weight_host(const float *W, int64_t C_in, int64_t O, const int32_t *row_ptr,
                                   const int32_t *src, int64_t C_out, int32_t bits, uint8_t *codes,
                                   float *scale, int32_t *zero, int32_t *colsum)

@@ -274,3 +274,37 @@ def test_build_map_rejects_malformed_merge_lists():
     bad_src = ok["src"].copy()
     bad_src[0] = 6
     assert b.qllm_check_map_host(ok["row_ptr"], bad_src, ok["scale"], 6) == -5
+
+
+def test_fold_linear_host_matches_the_oracle(oracle):
+    """Appendix B through the library's host helper (driven by the CSR map) against the oracle's
+    float64 statement of it (driven by T and the index pairs)."""
+    rng = np.random.default_rng(5)
+    C, Kp = 200, 37
+    absmax = np.abs(rng.standard_normal(C)).astype(np.float32) + 0.1
+    absmax[[3, 50, 120]] = [9.0, 14.5, 6.1]
+    theta = 3.0
+    T = oracle.num_split(absmax, theta)
+    chan_of = np.repeat(np.arange(C), T)
+    elig = T[chan_of] == 1
+    pa = np.arange(0, chan_of.size, 2)
+    pb = np.arange(1, chan_of.size, 2)
+    pa, pb = pa[elig[pa]], pb[elig[pb]]
+    sp = rng.choice(pa, size=11, replace=False)
+    dp = rng.choice(pb, size=11, replace=True)
+    src_idx, dst_idx = (sp // 2).astype(np.int32), ((dp - 1) // 2).astype(np.int32)
+    m = b.qllm_build_map_host(absmax, theta, src_idx, dst_idx, with_plan=False)
+    Wp = rng.standard_normal((C, Kp)).astype(np.float32)
+    bp = rng.standard_normal(C).astype(np.float32)
+    W_hat, b_hat = b.qllm_fold_linear_host(Wp, bp, m["row_ptr"], m["src"], m["scale"])
+    W_ref, b_ref = oracle.fold_preceding_linear(Wp, bp, T, src_idx, dst_idx)
+    assert W_hat.shape == W_ref.shape == (m["row_ptr"].size - 1, Kp)
+    assert np.abs(W_hat - W_ref).max() <= 2e-7 * np.abs(W_ref).max()
+    assert np.abs(b_hat - b_ref).max() <= 2e-7 * np.abs(b_ref).max()
+    W_only, none = b.qllm_fold_linear_host(Wp, None, m["row_ptr"], m["src"], m["scale"])
+    assert none is None and np.array_equal(W_only, W_hat)
+    # argument checks
+    bad = m["src"].copy()
+    bad[0] = C
+    with pytest.raises(RuntimeError):
+        b.qllm_fold_linear_host(Wp, bp, m["row_ptr"], bad, m["scale"])

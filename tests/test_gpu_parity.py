@@ -280,7 +280,10 @@ def check_y(oracle, y, ref_f32, y_dtype):
 
 @pytest.mark.parametrize("a_bits,w_bits", [(4, 4), (6, 6), (8, 8), (8, 4)])
 @pytest.mark.parametrize("N,K,O", [(1, 1, 1), (16, 64, 16), (3, 520, 70), (17, 2300, 33), (32, 4352, 64), (130, 300, 200),
-                                   (257, 1030, 129), (64, 2048, 384)])
+                                   (257, 1030, 129), (64, 2048, 384),
+                                   # 256-row tiles: two K-tiles only (the fetch ring runs past the end at once),
+                                   # three ragged tiles each way, a long K with one row past a tile
+                                   (300, 200, 260), (513, 256, 513), (129, 5000, 257)])
 @pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
 def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
     rng = np.random.default_rng(N * 1000 + K + O + a_bits)
@@ -392,3 +395,52 @@ def test_layer_replays_from_a_hip_graph(oracle, b, name, N, C, O):
     exp = oracle.reassembled_linear(wl.draw_activations(w, c.N, c.C, 1003)[0], c.norm, c.gamma, c.beta, c.eps, c.T, c.src_idx,
                                     c.dst_idx, w.a_bits, (c.wcodes, c.aw, c.bw, c.cs))
     check_y(oracle, y_eager, exp["y"], "bf16")
+
+
+# ---------------------------------------------------------------- Appendix B: reassembly folded into the preceding layer
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("C,Kp,O,N,bits", [(1100, 96, 200, 150, 4), (4200, 64, 130, 40, 6)])
+def test_folded_preceding_linear_path(oracle, b, C, Kp, O, N, bits):
+    """When the activations come out of a linear layer, Appendix B moves Eq. (3) and Eq. (4) into that
+    layer's weights and the run-time path is plain quantization + GEMM (no norm, identity map).  The
+    library must (1) reproduce the oracle on that path exactly as on any other, and (2) give what the
+    run-time reassembly gives, up to the few codes that fp32 rounding of the activations moves."""
+    import torch
+    from oracle import calibrate
+    rng = np.random.default_rng(C + Kp)
+    Wp = (rng.standard_normal((C, Kp)) / np.sqrt(Kp)).astype(np.float32)
+    Wp[rng.choice(C, 6, replace=False)] *= rng.uniform(8, 30, size=(6, 1)).astype(np.float32)   # outlier channels
+    bp = (0.1 * rng.standard_normal(C)).astype(np.float32)
+    xp = rng.standard_normal((N, Kp)).astype(np.float32)
+    y = (xp.astype(np.float64) @ Wp.astype(np.float64).T + bp).astype(np.float32)
+    cal = calibrate.calibrate(y, ("tmax", 6))
+    T, src_idx, dst_idx = cal["T"], cal["src_idx"], cal["dst_idx"]
+    assert int((T > 1).sum()) >= 3 and src_idx.size > 0
+    m = b.qllm_build_map_host(cal["absmax"], cal["theta"], src_idx, dst_idx)
+    K = m["row_ptr"].size - 1
+    W = (rng.standard_normal((C, O)) / np.sqrt(C)).astype(np.float32)
+    q = b.qllm_quantize_weight_host(W, m["row_ptr"], m["src"], bits)
+    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, bits)
+    wq = (b.qllm_unpack_codes_host(q["codes"], K, bits), q["scale"], q["zero"], q["colsum"])
+    ws = torch.empty(b.qllm_workspace_bytes(N, K, O, bits), dtype=torch.uint8, device="cuda")
+
+    def run(x, dm):
+        out = torch.full((N, O), float("nan"), dtype=torch.float32, device="cuda")
+        b.qllm_reassembled_linear(torch.from_numpy(x).cuda(), 0, None, None, 0.0, dm, bits, dw, out, ws)
+        torch.cuda.synchronize()
+        return out
+
+    # run-time reassembly of y
+    y_rt = run(y, b.DeviceMap(m["row_ptr"], m["src"], m["scale"], C, m["plan"]))
+    exp_rt = oracle.reassembled_linear(y, 0, None, None, 0.0, T, src_idx, dst_idx, bits, wq)
+    check_y(oracle, y_rt, exp_rt["y"], "f32")
+    # folded: the preceding layer produces the reassembled activations itself
+    W_hat, b_hat = b.qllm_fold_linear_host(Wp, bp, m["row_ptr"], m["src"], m["scale"])
+    y_hat = (xp.astype(np.float64) @ W_hat.astype(np.float64).T + b_hat).astype(np.float32)
+    ident = b.qllm_build_map_host(np.zeros(K, np.float32), 1.0, [], [])
+    y_fold = run(y_hat, b.DeviceMap(ident["row_ptr"], ident["src"], ident["scale"], K, ident["plan"]))
+    exp_fold = oracle.reassembled_linear(y_hat, 0, None, None, 0.0, np.ones(K, np.int32), [], [], bits, wq)
+    check_y(oracle, y_fold, exp_fold["y"], "f32")
+    a, f = y_rt.cpu().numpy().astype(np.float64), y_fold.cpu().numpy().astype(np.float64)
+    assert np.sqrt(((a - f) ** 2).sum()) <= 2e-2 * np.sqrt((a ** 2).sum())

@@ -180,3 +180,39 @@ def test_calibration_restores_channel_count(oracle):
     th = calibrate.theta_from_rule(cal["absmax"], ("expand", 0.05))
     extra = int((oracle.num_split(cal["absmax"], th) - 1).sum())
     assert extra >= 5 and extra <= 7
+
+
+# ---------------------------------------------------------------- Appendix B: folded into the preceding layer
+
+def test_fold_worked_example(oracle):
+    """Appendix B by hand: channel 1 split in three (columns divided by 3 and repeated), then the
+    A-member at disassembled position 0 merged into the B-member at position 5: their mean."""
+    Wp = np.array([[2.0, 4.0], [9.0, 3.0], [6.0, 8.0], [1.0, 1.0]])
+    bp = np.array([1.0, 6.0, 3.0, 5.0])
+    T = np.array([1, 3, 1, 1], np.int32)
+    # disassembled axis: [c0, c1/3, c1/3, c1/3, c2, c3]; A = positions 0, 2, 4; B = 1, 3, 5
+    W_hat, b_hat = oracle.fold_preceding_linear(Wp, bp, T, [0], [2])
+    assert W_hat.tolist() == [[3.0, 1.0], [3.0, 1.0], [3.0, 1.0], [6.0, 8.0], [1.5, 2.5]]
+    assert b_hat.tolist() == [2.0, 2.0, 2.0, 3.0, 3.0]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_fold_equals_runtime_reassembly(oracle, seed):
+    """What Appendix B claims: reassembling the output of y = x Wp^T + bp at run time (Eq. 3 then
+    Eq. 4, the oracle's two literal stages) gives the activations that the folded layer produces
+    directly.  The left side runs in the oracle's fp32, so agreement is to fp32 round-off."""
+    rng = np.random.default_rng(seed)
+    C, Kp, N = 96, 33, 9
+    _, T, src_idx, dst_idx = random_case(rng, C, 9, 6, 20)
+    Wp = rng.standard_normal((C, Kp))
+    bp = rng.standard_normal(C)
+    x = rng.standard_normal((N, Kp))
+    y = x @ Wp.T + bp
+    runtime = oracle.assemble(oracle.disassemble(y.astype(np.float32), T), src_idx, dst_idx).astype(np.float64)
+    W_hat, b_hat = oracle.fold_preceding_linear(Wp, bp, T, src_idx, dst_idx)
+    folded = x @ W_hat.T + b_hat
+    assert folded.shape == runtime.shape
+    assert np.abs(folded - runtime).max() <= 2e-6 * np.abs(runtime).max()
+    # without a bias, and with nothing to do, the fold is the identity
+    W_same, none = oracle.fold_preceding_linear(Wp, None, np.ones(C, np.int32), [], [])
+    assert none is None and np.array_equal(W_same, Wp)
