@@ -11,8 +11,9 @@ Sec. 4.1.2, Appendix A, Algorithm 1) needed to manufacture a reassembly map for 
           r = sum(T_c - 1) shortest edges are merged.  Sub-channels of disassembled channels take
           no part (Sec. 4.1.2).
 
-The edge length here is the plain L2 distance between activation columns over the first
-`n_match_tokens` tokens (benchmark policy), not the paper's Eq. (5), which also involves the weights.
+Two edge lengths are provided: the plain L2 distance between activation columns over the first
+`n_match_tokens` tokens (the benchmark's policy for synthetic data: `nearest_pairs`), and the paper's
+Eq. (5), which also involves the weights (`pair_distance`, `nearest_by_eq5`, `match_pairs_eq5`).
 """
 import numpy as np
 
@@ -76,6 +77,72 @@ def nearest_pairs(y, T, r, n_match_tokens=256, chunk=2048):
     src_idx = (pos_a[pick] // 2).astype(np.int32)
     dst_idx = ((pos_b[best_j[pick]] - 1) // 2).astype(np.int32)
     return src_idx, dst_idx
+
+
+def matching_sets(T):
+    """Appendix A step 1 on the disassembled axis: (chan_of, pos_a, pos_b) with set A = even and
+    set B = odd positions, sub-channels of disassembled channels left out (Sec. 4.1.2)."""
+    T = np.asarray(T, np.int64)
+    chan_of = np.repeat(np.arange(T.size), T)
+    eligible = T[chan_of] == 1
+    pos_a = np.arange(0, chan_of.size, 2)
+    pos_b = np.arange(1, chan_of.size, 2)
+    return chan_of, pos_a[eligible[pos_a]], pos_b[eligible[pos_b]]
+
+
+def pair_distance(xi, xj, wi, wj):
+    """Eq. (5) as printed: the squared norm of x_i (W_i - W_j) / 2 + x_j (W_j - W_i) / 2, the error
+    that merging channels i and j by Eq. (4) leaves in the layer's output.  xi, xj: activation columns
+    over the calibration tokens; wi, wj: weight rows over the output features.  float64."""
+    xi, xj = np.asarray(xi, np.float64), np.asarray(xj, np.float64)
+    wi, wj = np.asarray(wi, np.float64), np.asarray(wj, np.float64)
+    e = np.outer(xi, wi - wj) / 2.0 + np.outer(xj, wj - wi) / 2.0
+    return float((e * e).sum())
+
+
+def nearest_by_eq5(y, W, T, n_match_tokens=256, rows=None):
+    """Appendix A step 2 with the distance of Eq. (5): for every member of set A (or those listed in
+    `rows`, as indices into set A's eligible members) its nearest member of set B, lowest index on
+    ties.  The error term of Eq. (5) is the outer product of (x_i - x_j) / 2 and (W_i - W_j), so its
+    squared norm is |x_i - x_j|^2 |W_i - W_j|^2 / 4: the differences are formed explicitly, in float64.
+    y: [N, C] activations, W: [C, O].  Returns (best_j, best_d): index into set B's eligible members
+    and the distance, plus (pos_a, pos_b) for the caller."""
+    chan_of, pos_a, pos_b = matching_sets(T)
+    ys = np.asarray(y[:n_match_tokens], np.float64)
+    Wd = np.asarray(W, np.float64)
+    xb = ys[:, chan_of[pos_b]].T                          # [|B|, n]
+    wb = Wd[chan_of[pos_b]]                               # [|B|, O]
+    rows = np.arange(pos_a.size) if rows is None else np.asarray(rows, np.int64)
+    best_j = np.empty(rows.size, np.int64)
+    best_d = np.empty(rows.size, np.float64)
+    for k, i in enumerate(rows):
+        c = chan_of[pos_a[i]]
+        dx = xb - ys[:, c][None, :]
+        dw = wb - Wd[c][None, :]
+        d = 0.25 * (dx * dx).sum(1) * (dw * dw).sum(1)
+        j = int(d.argmin())                               # numpy returns the first minimum
+        best_j[k], best_d[k] = j, d[j]
+    return best_j, best_d, pos_a, pos_b
+
+
+def select_edges(best_d, best_j, pos_a, pos_b, r):
+    """Appendix A step 3: the r shortest edges (ties to the lower A index), as (src_idx, dst_idx) in
+    the A / B indexing of the run-time pseudo-code, ascending in src_idx."""
+    r = min(int(r), pos_a.size)
+    if r == 0 or pos_b.size == 0:
+        return np.zeros(0, np.int32), np.zeros(0, np.int32)
+    pick = np.argsort(best_d, kind="stable")[:r]
+    pick.sort()
+    return (pos_a[pick] // 2).astype(np.int32), ((pos_b[best_j[pick]] - 1) // 2).astype(np.int32)
+
+
+def match_pairs_eq5(y, W, T, r, n_match_tokens=256):
+    """Appendix A steps 1-3 with Eq. (5).  Returns (src_idx, dst_idx)."""
+    chan_of, pos_a, pos_b = matching_sets(T)
+    if r == 0 or pos_a.size == 0 or pos_b.size == 0:
+        return np.zeros(0, np.int32), np.zeros(0, np.int32)
+    best_j, best_d, pos_a, pos_b = nearest_by_eq5(y, W, T, n_match_tokens)
+    return select_edges(best_d, best_j, pos_a, pos_b, r)
 
 
 def calibrate(y, theta_rule, merge=True, n_match_tokens=256):

@@ -1,0 +1,93 @@
+"""Pins for the oracle's bipartite soft matching with the distance of Eq. (5) (Sec. 4.1.2,
+Appendix A): the distance against the merging error it is defined to measure (computed through the
+oracle's own, independent assembly code), brute force on tiny inputs, a case worked by hand."""
+import numpy as np
+import pytest
+
+from oracle import calibrate
+
+
+def test_distance_is_the_output_error_of_merging(oracle):
+    """Eq. (5) is the error Eq. (4) leaves in the layer's output.  Merge one pair with the oracle's
+    literal assembly (activations averaged, weight rows summed) and compare ||Y - Y^||_F^2 with
+    D(i, j).  Small dyadic values keep every fp32 step exact."""
+    rng = np.random.default_rng(3)
+    C, N, O = 12, 5, 4
+    y = (rng.integers(-8, 9, (N, C)) / 4.0).astype(np.float32)
+    W = (rng.integers(-8, 9, (C, O)) / 2.0).astype(np.float32)
+    T = np.ones(C, np.int32)
+    for a_idx, b_idx in [(0, 0), (2, 5), (5, 1)]:
+        i, j = 2 * a_idx, 2 * b_idx + 1                   # channels (positions: nothing is split)
+        y_hat = oracle.assemble(oracle.disassemble(y, T), [a_idx], [b_idx])
+        W_hat = oracle.reassemble_weight(W, T, [a_idx], [b_idx])
+        err = y.astype(np.float64) @ W.astype(np.float64) - y_hat.astype(np.float64) @ W_hat.astype(np.float64)
+        assert (err * err).sum() == calibrate.pair_distance(y[:, i], y[:, j], W[i], W[j])
+
+
+def test_distance_properties():
+    rng = np.random.default_rng(4)
+    xi, xj, wi, wj = rng.standard_normal(7), rng.standard_normal(7), rng.standard_normal(5), rng.standard_normal(5)
+    d = calibrate.pair_distance(xi, xj, wi, wj)
+    assert d > 0
+    assert np.isclose(d, calibrate.pair_distance(xj, xi, wj, wi), rtol=1e-14)          # symmetric
+    assert calibrate.pair_distance(xi, xi, wi, wj) == 0.0                                # same activations: no error
+    assert calibrate.pair_distance(xi, xj, wi, wi) == 0.0                                # same weights: no error
+    assert np.isclose(calibrate.pair_distance(3 * xi, 3 * xj, wi, wj), 9 * d, rtol=1e-14)
+    # the rank-one structure: |u v^T|_F^2 = |u|^2 |v|^2
+    assert np.isclose(d, 0.25 * ((xi - xj) ** 2).sum() * ((wi - wj) ** 2).sum(), rtol=1e-13)
+
+
+def test_nearest_by_eq5_against_brute_force():
+    rng = np.random.default_rng(5)
+    C, N, O = 31, 6, 5
+    y = rng.standard_normal((N, C)).astype(np.float32)
+    W = rng.standard_normal((C, O)).astype(np.float32)
+    T = np.ones(C, np.int32)
+    T[[4, 17]] = [3, 2]                                   # their sub-channels take no part
+    best_j, best_d, pos_a, pos_b = calibrate.nearest_by_eq5(y, W, T)
+    chan_of = np.repeat(np.arange(C), T)
+    assert not np.isin(chan_of[pos_a], [4, 17]).any() and not np.isin(chan_of[pos_b], [4, 17]).any()
+    assert pos_a.size + pos_b.size == C - 2 and np.all(pos_a % 2 == 0) and np.all(pos_b % 2 == 1)
+    for k, pa in enumerate(pos_a):
+        i = chan_of[pa]
+        ds = [calibrate.pair_distance(y[:, i], y[:, chan_of[pb]], W[i], W[chan_of[pb]]) for pb in pos_b]
+        assert int(np.argmin(ds)) == best_j[k]
+        assert np.isclose(best_d[k], min(ds), rtol=1e-12)
+    # a subset of rows gives the same answers
+    sub_j, sub_d, _, _ = calibrate.nearest_by_eq5(y, W, T, rows=[3, 0, 9])
+    assert sub_j.tolist() == best_j[[3, 0, 9]].tolist() and np.array_equal(sub_d, best_d[[3, 0, 9]])
+
+
+def test_matching_by_hand():
+    """Six channels, one token, one output feature: D(i, j) = (x_i - x_j)^2 (w_i - w_j)^2 / 4.
+    A = channels 0, 2, 4; B = 1, 3, 5."""
+    y = np.array([[1.0, 1.0, 5.0, 4.0, 9.0, 2.0]], np.float32)
+    W = np.array([[1.0], [3.0], [2.0], [2.0], [0.0], [7.0]], np.float32)
+    T = np.ones(6, np.int32)
+    best_j, best_d, pos_a, pos_b = calibrate.nearest_by_eq5(y, W, T)
+    # channel 0: to 1: 0; to 3: 9*1/4; to 5: 1*36/4  -> B-member 0, distance 0
+    # channel 2: to 1: 16*1/4 = 4; to 3: 1*0/4 = 0; to 5: 9*25/4 -> B-member 1, distance 0
+    # channel 4: to 1: 64*9/4 = 144; to 3: 25*4/4 = 25; to 5: 49*49/4 -> B-member 1, distance 25
+    assert best_j.tolist() == [0, 1, 1] and best_d.tolist() == [0.0, 0.0, 25.0]
+    src_idx, dst_idx = calibrate.select_edges(best_d, best_j, pos_a, pos_b, 2)
+    assert src_idx.tolist() == [0, 1] and dst_idx.tolist() == [0, 1]     # the tie of the two zeros: both taken
+    src_idx, dst_idx = calibrate.select_edges(best_d, best_j, pos_a, pos_b, 1)
+    assert src_idx.tolist() == [0] and dst_idx.tolist() == [0]           # tie: the lower A index
+    src_idx, dst_idx = calibrate.match_pairs_eq5(y, W, T, 3)
+    assert src_idx.tolist() == [0, 1, 2] and dst_idx.tolist() == [0, 1, 1]   # two sources may share a destination
+
+
+def test_matching_prefers_pairs_that_cost_nothing():
+    """Channels built in identical pairs (same activations, same weights) across the two sets are found
+    and merged first, and merging them leaves the layer's output unchanged."""
+    rng = np.random.default_rng(6)
+    C, N, O = 40, 16, 8
+    y = rng.standard_normal((N, C)).astype(np.float32)
+    W = rng.standard_normal((C, O)).astype(np.float32)
+    twins = [(0, 7), (10, 3), (22, 39)]                   # (even channel, odd channel)
+    for a, b_ in twins:
+        y[:, b_] = y[:, a]
+        W[b_] = W[a]
+    T = np.ones(C, np.int32)
+    src_idx, dst_idx = calibrate.match_pairs_eq5(y, W, T, 3)
+    assert sorted(zip((2 * src_idx).tolist(), (2 * dst_idx + 1).tolist())) == sorted(twins)
