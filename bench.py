@@ -46,6 +46,78 @@ def read_traffic(workload):
     return out
 
 
+def bench_matching(args, w, norm, dev):
+    """The step before the path: Appendix A steps 1-2 with the distance of Eq. (5) for the workload's
+    layer, 256 calibration tokens.  A step = one qllm_match_nearest call (norms + nearest-member search)."""
+    import numpy as np
+    import torch
+
+    from paper_2310_08041_amd import binding as b
+    from paper_2310_08041_amd import calibrate, workloads as wl
+
+    n_match = min(256, w.N)
+    x_host, _, _ = wl.draw_activations(w)
+    gamma_h, beta_h = wl.draw_norm_params(w)
+    x0 = (torch.from_numpy(x_host.view(np.int16)).to(dev).view(torch.bfloat16) if x_host.dtype == np.uint16
+          else torch.from_numpy(x_host).to(dev))
+    gamma = torch.from_numpy(gamma_h).to(dev)
+    beta = None if beta_h is None else torch.from_numpy(beta_h).to(dev)
+    absmax = torch.zeros(w.C, dtype=torch.float32, device=dev)
+    y = torch.empty((n_match, w.C), dtype=torch.float32, device=dev)
+    b.qllm_norm_channel_absmax(x0, norm, gamma, beta, w.eps, absmax, y)
+    m = absmax.cpu().numpy()
+    theta = calibrate.choose_theta(m, w.theta_rule)
+    T = b.qllm_build_map_host(m, theta, [], [], with_plan=False)["num_split"]
+    W_host = wl.draw_weight(w)
+    W = torch.from_numpy(W_host).to(dev)
+    chan_of, pos_a, pos_b = calibrate.matching_sets(T, dev)
+    chan_a, chan_b = chan_of[pos_a].to(torch.int32).contiguous(), chan_of[pos_b].to(torch.int32).contiguous()
+    nA, nB = chan_a.numel(), chan_b.numel()
+    best_j = torch.empty(nA, dtype=torch.int32, device=dev)
+    best_d = torch.empty(nA, dtype=torch.float64, device=dev)
+    ws = torch.empty(b.qllm_match_workspace_bytes(nA, nB), dtype=torch.uint8, device=dev)
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        b.qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, ws)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    t_start = time.perf_counter()
+    ev[0].record()
+    for _ in range(steps):
+        b.qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, ws)
+    ev[1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    t_kernel = ev[0].elapsed_time(ev[1]) * 1e-3 / steps
+    flops = 2.0 * nA * nB * (n_match + w.O)             # two Gram matrices, one multiply-add per pair and index
+    result = {
+        "metric": "channel matching (Eq. 5, Appendix A steps 1-2): fp64 TFLOP/s of the two Gram contractions",
+        "value": flops / (wall / steps) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64 (fp64 matrix cores; fp32 inputs widened exactly)", "data": "synthetic",
+        "config": {"workload": w.name + " / offline matching", "C": w.C, "O": w.O, "calibration_tokens": n_match,
+                   "set_A": nA, "set_B": nB, "split_channels": int((T > 1).sum()), "pairs": nA * nB},
+        "roofline": {"kernel": "match_nearest_kernel (+ match_norms_kernel)", "bound": "mfma", "achieved": flops / t_kernel / 1e12,
+                     "peak": 78.6, "unit": "TFLOP/s", "frac": flops / t_kernel / 1e12 / 78.6,
+                     "avg_launch_us": t_kernel * 1e6, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import calibrate as ocal
+        from oracle import api as oracle
+        rows = np.arange(0, nA, max(1, nA // 8))[:8]
+        y_h = y.cpu().numpy()
+        t0 = time.perf_counter()
+        ref_j, ref_d, _, _ = ocal.nearest_by_eq5(y_h, W_host, T, n_match_tokens=n_match, rows=rows)
+        dt = time.perf_counter() - t0
+        got_j = best_j.cpu().numpy()[rows]
+        same = int((got_j == ref_j).sum())
+        result["cpu_baseline"] = {"value": 2.0 * rows.size * nB * (n_match + w.O) / dt / 1e12, "unit": "TFLOP/s",
+                                  "cores": oracle.max_threads(), "kind": "oracle",
+                                  "sample": f"{rows.size} of {nA} members of set A against all {nB} members of set B, {dt:.1f} s "
+                                            f"(setup included); nearest member agrees for {same} of {rows.size}"}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +129,9 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph holding one step per rotating buffer set (launch-bound shapes)")
+    ap.add_argument("--stage", default="layer", choices=["layer", "match"],
+                    help="layer: the hot path (the default, the line the contract asks for); match: the offline "
+                         "channel matching of Eq. (5) / Appendix A at the workload's channel count")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over tokens with no "
@@ -73,6 +148,8 @@ def main():
     dev = torch.device("cuda:0")
     w = wl.WORKLOADS[args.workload]
     norm = {"none": b.NORM_NONE, "layer": b.NORM_LAYER, "rms": b.NORM_RMS}[w.norm]
+    if args.stage == "match":
+        return bench_matching(args, w, norm, dev)
 
     # ---- synthetic inputs, resident in HBM before anything is timed
     t0 = time.time()

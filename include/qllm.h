@@ -153,6 +153,30 @@ int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64
                                 int32_t y_dtype, int64_t ldy, void *workspace, int64_t workspace_bytes,
                                 void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Offline, on the device: which channels to merge (Sec. 4.1.2, Appendix A steps 1-2).  The caller
+ * has split the candidates into set A and set B (Appendix A step 1; on the disassembled axis, even and
+ * odd positions, sub-channels of split channels left out) and names each member's channel.  For every
+ * member i of A this finds its nearest member of B under the distance of Eq. (5),
+ *     D(i, j) = | x_i (W_i - W_j) / 2 + x_j (W_j - W_i) / 2 |^2 = |x_i - x_j|^2 |W_i - W_j|^2 / 4,
+ * x_c = column c of y over the n calibration tokens, W_c = row c of W over the O output features.
+ * Arithmetic in double precision on the fp64 matrix cores; ties go to the lower j.
+ *   y        [n, ldy] fp32 activations after the norm (ldy >= C); W [C, ldw] fp32 (ldw >= O)
+ *   chan_a   [nA], chan_b [nB] int32 channel numbers in [0, C) (device arrays, trusted)
+ *   best_j   [nA] int32: index into chan_b;   best_d [nA] double: the distance
+ *   workspace  qllm_match_workspace_bytes(nA, nB) bytes, 8-byte aligned
+ * Errors: NULL / SHAPE (also nB == 0 with nA > 0) / WORKSPACE / ALIGN / HIP.  nA == 0 is a no-op.
+ * qllm_select_edges_host (host pointers) is Appendix A step 3: the r shortest edges, ties to the lower
+ * member of A; pick_out receives min(r, nA) indices into set A in ascending order and the count is
+ * returned (negative = qllm_status).
+ */
+int64_t qllm_match_workspace_bytes(int64_t nA, int64_t nB);
+int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, const float *W, int64_t C, int64_t O,
+                           int64_t ldw, const int32_t *chan_a, int64_t nA, const int32_t *chan_b, int64_t nB,
+                           int32_t *best_j, double *best_d, void *workspace, int64_t workspace_bytes,
+                           void *hip_stream);
+int64_t qllm_select_edges_host(const double *best_d, int64_t nA, int64_t r, int32_t *pick_out);
+
 /* Sizes.  Negative return = qllm_status. */
 int64_t qllm_packed_row_bytes(int64_t K, int32_t bits);
 int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);

@@ -66,6 +66,9 @@ _sigs = {
     "qllm_pack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_unpack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_norm_channel_absmax": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, _vp, _vp, _i64, _vp]),
+    "qllm_match_workspace_bytes": (_i64, [_i64, _i64]),
+    "qllm_match_nearest": (_i32, [_vp, _i64, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp]),
+    "qllm_select_edges_host": (_i64, [_vp, _i64, _i64, _vp]),
     "qllm_probe_mfma": (_i32, [_i32, _i32, _vp, _vp]),
     "qllm_probe_stream": (_i32, [_vp, _vp, _i64, _i32, _vp]),
 }
@@ -314,6 +317,30 @@ def qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y_dump=None, str
                                        float(eps), _dp(absmax), _dp(y_dump), n_dump, _stream(stream)),
          "qllm_norm_channel_absmax")
     return absmax
+
+
+def qllm_match_workspace_bytes(nA, nB):
+    return int(_lib.qllm_match_workspace_bytes(int(nA), int(nB)))
+
+
+def qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, workspace, stream=None):
+    """y [n, C] fp32, W [C, O] fp32, chan_a / chan_b int32, best_j [nA] int32, best_d [nA] float64: device tensors."""
+    n, Cc = y.shape
+    _chk(_lib.qllm_match_nearest(_dp(y), n, y.stride(0), _dp(W), Cc, W.shape[1], W.stride(0), _dp(chan_a),
+                                 chan_a.numel(), _dp(chan_b), chan_b.numel(), _dp(best_j), _dp(best_d),
+                                 _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                 _stream(stream)), "qllm_match_nearest")
+    return best_j, best_d
+
+
+def qllm_select_edges_host(best_d, r):
+    """best_d [nA] float64 (host) -> the min(r, nA) members of A with the shortest edges, ascending."""
+    best_d = _np(best_d, np.float64)
+    pick = np.empty(min(int(r), best_d.size), np.int32)
+    n = int(_lib.qllm_select_edges_host(_hp(best_d), best_d.size, int(r), _hp(pick)))
+    if n < 0:
+        _chk(n, "qllm_select_edges_host")
+    return pick[:n]
 
 
 def qllm_probe_mfma(workgroups, iters, sink, stream=None):

@@ -4,9 +4,11 @@ This is NOT the hot path: it runs once per layer, before inference (Sec. 4.3: th
 pre-computed from calibration data).  The per-channel statistic comes from the library's own kernel
 (qllm_norm_channel_absmax); T and the CSR map come from qllm_build_map_host.  The pair selection in
 between (Appendix A: one edge from every member of set A to its nearest member of set B, keep the r
-shortest) uses torch matrix products on the device as a library primitive.  The edge length is the
-plain L2 distance between activation columns over the first `n_match` tokens -- the benchmark's
-policy for synthetic data -- not the paper's Eq. (5).
+shortest) comes in two forms: with the layer's weights at hand, the distance of Eq. (5) through the
+library's own kernel (qllm_match_nearest, fp64 matrix cores) and qllm_select_edges_host
+(`match_pairs_eq5`); without weights -- the benchmark's policy for synthetic activations -- the plain
+L2 distance between activation columns over the first `n_match` tokens with torch matrix products
+as a library primitive (`match_pairs`).
 """
 import numpy as np
 import torch
@@ -71,9 +73,39 @@ def match_pairs(y, num_split, r, chunk=4096):
     return src_idx, dst_idx
 
 
-def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256):
-    """x: [N, C] device tensor (fp32 / bf16).  Returns the dict of qllm_build_map_host plus theta,
-    absmax, src_idx, dst_idx."""
+def matching_sets(num_split, device):
+    """Appendix A step 1 on the disassembled axis: positions of set A (even) and set B (odd), without the
+    sub-channels of split channels (Sec. 4.1.2), and the channel of every position."""
+    T = torch.as_tensor(num_split, device=device, dtype=torch.int64)
+    chan_of = torch.repeat_interleave(torch.arange(T.numel(), device=device), T)
+    eligible = T[chan_of] == 1
+    pos = torch.arange(chan_of.numel(), device=device)
+    return chan_of, pos[(pos % 2 == 0) & eligible], pos[(pos % 2 == 1) & eligible]
+
+
+def match_pairs_eq5(y, W, num_split, r):
+    """y: [n, C] fp32 device tensor of norm outputs, W: [C, O] fp32 device tensor of the layer's weights.
+    Returns (src_idx, dst_idx) int32 numpy arrays, and the per-member (best_j, best_d) device tensors."""
+    chan_of, pos_a, pos_b = matching_sets(num_split, y.device)
+    nA, nB = pos_a.numel(), pos_b.numel()
+    if r == 0 or nA == 0 or nB == 0:
+        return np.zeros(0, np.int32), np.zeros(0, np.int32), None, None
+    chan_a = chan_of[pos_a].to(torch.int32).contiguous()
+    chan_b = chan_of[pos_b].to(torch.int32).contiguous()
+    best_j = torch.empty(nA, dtype=torch.int32, device=y.device)
+    best_d = torch.empty(nA, dtype=torch.float64, device=y.device)
+    ws = torch.empty(b.qllm_match_workspace_bytes(nA, nB), dtype=torch.uint8, device=y.device)
+    b.qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, ws)
+    pick = torch.from_numpy(b.qllm_select_edges_host(best_d.cpu().numpy(), r).astype(np.int64)).to(y.device)
+    src_idx = (pos_a[pick] // 2).to(torch.int32).cpu().numpy()
+    dst_idx = ((pos_b[best_j[pick].long()] - 1) // 2).to(torch.int32).cpu().numpy()
+    return src_idx, dst_idx, best_j, best_d
+
+
+def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256, W=None):
+    """x: [N, C] device tensor (fp32 / bf16); W: None, or the layer's [C, O] fp32 device weights, which
+    switches the pair selection to the distance of Eq. (5).  Returns the dict of qllm_build_map_host plus
+    theta, absmax, src_idx, dst_idx."""
     N, C = x.shape
     absmax = torch.zeros(C, dtype=torch.float32, device=x.device)
     y = torch.empty((min(N, n_match), C), dtype=torch.float32, device=x.device)
@@ -83,7 +115,10 @@ def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256):
     sizing = b.qllm_build_map_host(m, theta, [], [], with_plan=False)
     T = sizing["num_split"]
     r = int(sizing["nnz"] - C) if merge else 0
-    src_idx, dst_idx = match_pairs(y, T, r)
+    if W is None:
+        src_idx, dst_idx = match_pairs(y, T, r)
+    else:
+        src_idx, dst_idx, _, _ = match_pairs_eq5(y, W, T, r)
     out = b.qllm_build_map_host(m, theta, src_idx, dst_idx)
     out.update(theta=theta, absmax=m, src_idx=src_idx, dst_idx=dst_idx)
     return out

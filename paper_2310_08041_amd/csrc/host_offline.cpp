@@ -378,6 +378,20 @@ int32_t qllm_unpack_codes_host(const uint8_t *packed, int64_t R, int64_t K, int3
     return QLLM_OK;
 }
 
+int64_t qllm_select_edges_host(const double *best_d, int64_t nA, int64_t r, int32_t *pick_out)
+{
+    if (nA < 0 || r < 0) return QLLM_ERR_SHAPE;
+    const int64_t take = std::min(r, nA);
+    if (take == 0) return 0;
+    if (!best_d || !pick_out) return QLLM_ERR_NULL;
+    std::vector<int32_t> order((size_t)nA);
+    for (int64_t i = 0; i < nA; ++i) order[(size_t)i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return best_d[a] < best_d[b]; });
+    std::sort(order.begin(), order.begin() + take);
+    for (int64_t k = 0; k < take; ++k) pick_out[k] = order[(size_t)k];
+    return take;
+}
+
 int32_t qllm_fold_linear_host(const float *Wp, const float *bp, int64_t C_in, int64_t K_prev,
                               const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_out,
                               float *W_out, float *b_out)

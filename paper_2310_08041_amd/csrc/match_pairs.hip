@@ -1,0 +1,298 @@
+// Offline channel matching on the device: Appendix A steps 1-2 (every member of set A gets an edge to
+// its most similar member of set B) with the distance of Sec. 4.1.2, Eq. (5).
+//
+// Eq. (5) is the squared norm of the error that merging channels i and j leaves in the layer's
+// output, x_i (W_i - W_j) / 2 + x_j (W_j - W_i) / 2 = (x_i - x_j) (W_i - W_j)^T / 2, an outer product of
+// a vector over the calibration tokens and a vector over the output features, so
+//     D(i, j) = |x_i - x_j|^2 |W_i - W_j|^2 / 4,    |a - b|^2 = |a|^2 + |b|^2 - 2 a.b.
+// The two sets of inner products are Gram matrices: dense contractions, done here on the fp64 matrix
+// cores (v_mfma_f64_16x16x4_f64) so that the argmin is taken in the precision the definition is
+// written in.  Nothing of size |A| x |B| is ever stored: a workgroup owns 64 members of A, walks over
+// B in tiles of 128, forms both Gram tiles, the distances, and keeps a running minimum per row.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "qllm.h"
+
+extern "C" void qllm_note_hip_error(const char *step, const char *name);
+
+namespace {
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+constexpr int TA = 64, TB = 128, KT = 16, THREADS = 256, PAD = KT + 1; // PAD: row stride in doubles, odd against bank conflicts
+
+struct MatchArgs {
+    const float *y;  // [n, ldy]: activations, token-major
+    const float *w;  // [C, ldw]: weights, one row per input channel
+    int64_t ldy, ldw;
+    int32_t n, O, nA, nB;
+    const int32_t *chan_a, *chan_b;
+    const double *norms; // workspace: |x|^2 of A members [nA], |W|^2 of A [nA], |x|^2 of B [nB], |W|^2 of B [nB]
+    int32_t *best_j;
+    double *best_d;
+};
+
+// ---- squared norms of every set member's activation column and weight row, in double
+__global__ __launch_bounds__(THREADS) void match_norms_kernel(const MatchArgs g, double *out)
+{
+    __shared__ double red[2][THREADS / 64];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const bool in_a = m < g.nA;
+    const int c = in_a ? g.chan_a[m] : g.chan_b[m - g.nA];
+    double sx = 0.0, sw = 0.0;
+    for (int t = tid; t < g.n; t += THREADS) {
+        const double v = (double)g.y[(int64_t)t * g.ldy + c];
+        sx += v * v;
+    }
+    const float *wr = g.w + (int64_t)c * g.ldw;
+    for (int k = tid; k < g.O; k += THREADS) {
+        const double v = (double)wr[k];
+        sw += v * v;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        sx += __shfl_xor(sx, off);
+        sw += __shfl_xor(sw, off);
+    }
+    if ((tid & 63) == 0) {
+        red[0][tid >> 6] = sx;
+        red[1][tid >> 6] = sw;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double a = 0.0, b = 0.0;
+        for (int q = 0; q < THREADS / 64; ++q) {
+            a += red[0][q];
+            b += red[1][q];
+        }
+        if (in_a) {
+            out[m] = a;
+            out[g.nA + m] = b;
+        } else {
+            out[2 * (int64_t)g.nA + (m - g.nA)] = a;
+            out[2 * (int64_t)g.nA + g.nB + (m - g.nA)] = b;
+        }
+    }
+}
+
+// One K-step of operands: 64 x 16 values of the A tile (4 per lane), 128 x 16 of the B tile (8 per lane).
+// XPASS: element (member i, token t) = y[t][chan[i]], consecutive lanes take consecutive members;
+// otherwise element (member i, feature k) = w[chan[i]][k], consecutive lanes take consecutive features.
+template <bool XPASS>
+__device__ __forceinline__ void fetch_step(const MatchArgs &g, const int32_t *ca, const int32_t *cb, int k0, int tid,
+                                           float (&pa)[4], float (&pb)[8])
+{
+    const int K = XPASS ? g.n : g.O;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = tid + q * THREADS;
+        const int i = XPASS ? (e & (TA - 1)) : (e / KT), k = XPASS ? (e / TA) : (e % KT);
+        const bool ok = k0 + k < K;
+        const int kk = ok ? k0 + k : 0;
+        const float v = XPASS ? g.y[(int64_t)kk * g.ldy + ca[i]] : g.w[(int64_t)ca[i] * g.ldw + kk];
+        pa[q] = ok ? v : 0.0f;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = tid + q * THREADS;
+        const int i = XPASS ? (e & (TB - 1)) : (e / KT), k = XPASS ? (e / TB) : (e % KT);
+        const bool ok = k0 + k < K;
+        const int kk = ok ? k0 + k : 0;
+        const float v = XPASS ? g.y[(int64_t)kk * g.ldy + cb[i]] : g.w[(int64_t)cb[i] * g.ldw + kk];
+        pb[q] = ok ? v : 0.0f;
+    }
+}
+
+template <bool XPASS>
+__device__ __forceinline__ void stage_step(double *as, double *bs, int tid, const float (&pa)[4], const float (&pb)[8])
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = tid + q * THREADS;
+        const int i = XPASS ? (e & (TA - 1)) : (e / KT), k = XPASS ? (e / TA) : (e % KT);
+        as[i * PAD + k] = (double)pa[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = tid + q * THREADS;
+        const int i = XPASS ? (e & (TB - 1)) : (e / KT), k = XPASS ? (e / TB) : (e % KT);
+        bs[i * PAD + k] = (double)pb[q];
+    }
+}
+
+// acc[ti][tj] += A tile rows 16 ti.. times B tile rows 32 wave + 16 tj.., over K (n tokens or O features)
+template <bool XPASS>
+__device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca, const int32_t *cb, double *as, double *bs,
+                                          int tid, v4d (&acc)[4][2])
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int K = XPASS ? g.n : g.O;
+    const int steps = (K + KT - 1) / KT;
+    float pa[4], pb[8];
+    fetch_step<XPASS>(g, ca, cb, 0, tid, pa, pb);
+    for (int s = 0; s < steps; ++s) {
+        double *a_buf = as + (s & 1) * TA * PAD, *b_buf = bs + (s & 1) * TB * PAD;
+        stage_step<XPASS>(a_buf, b_buf, tid, pa, pb);
+        // one barrier per step: the buffer written now was last read two steps ago, before the previous barrier
+        __syncthreads();
+        if (s + 1 < steps) fetch_step<XPASS>(g, ca, cb, (s + 1) * KT, tid, pa, pb);
+#pragma unroll
+        for (int kk = 0; kk < KT / 4; ++kk) {
+            double a[4], b[2];
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti) a[ti] = a_buf[(16 * ti + (lane & 15)) * PAD + 4 * kk + (lane >> 4)];
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) b[tj] = b_buf[(32 * wave + 16 * tj + (lane & 15)) * PAD + 4 * kk + (lane >> 4)];
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj)
+                    acc[ti][tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ti], b[tj], acc[ti][tj], 0, 0, 0);
+        }
+    }
+    __syncthreads(); // the next pass starts writing buffer 0 again
+}
+
+__global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs g)
+{
+    __shared__ double as[2 * TA * PAD], bs[2 * TB * PAD];
+    __shared__ double na_x[TA], na_w[TA], nb_x[TB], nb_w[TB];
+    __shared__ int32_t ca[TA], cb[TB];
+    __shared__ double fin_d[THREADS / 64][TA];
+    __shared__ int32_t fin_j[THREADS / 64][TA];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int a0 = blockIdx.x * TA;
+    if (tid < TA) {
+        const int m = min(a0 + tid, g.nA - 1); // past the end: the last member again, its result is dropped
+        ca[tid] = g.chan_a[m];
+        na_x[tid] = g.norms[m];
+        na_w[tid] = g.norms[g.nA + m];
+    }
+
+    // running minimum for the 16 rows this lane sees: rows 16 ti + (lane >> 4) + 4 r
+    double best_d[4][4];
+    int32_t best_j[4][4];
+#pragma unroll
+    for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            best_d[ti][r] = __builtin_huge_val();
+            best_j[ti][r] = 0x7fffffff;
+        }
+
+    for (int b0 = 0; b0 < g.nB; b0 += TB) {
+        __syncthreads(); // everybody is done with the previous tile's cb / norms
+        if (tid < TB) {
+            const int m = min(b0 + tid, g.nB - 1);
+            cb[tid] = g.chan_b[m];
+            nb_x[tid] = g.norms[2 * (int64_t)g.nA + m];
+            nb_w[tid] = g.norms[2 * (int64_t)g.nA + g.nB + m];
+        }
+        __syncthreads();
+        v4d gx[4][2], gw[4][2];
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) gx[ti][tj] = gw[ti][tj] = v4d{0.0, 0.0, 0.0, 0.0};
+        gram_pass<true>(g, ca, cb, as, bs, tid, gx);
+        gram_pass<false>(g, ca, cb, as, bs, tid, gw);
+        // distances of this tile; element r of an accumulator: row (lane >> 4) + 4 r, column lane & 15
+        // (checked against the oracle: the fp64 operation interleaves the rows of its four result registers)
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            const int jl = 32 * wave + 16 * tj + (lane & 15), j = b0 + jl;
+            const double bx = nb_x[jl], bw = nb_w[jl];
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int il = 16 * ti + (lane >> 4) + 4 * r;
+                    double sx = na_x[il] + bx - 2.0 * gx[ti][tj][r];
+                    double sw = na_w[il] + bw - 2.0 * gw[ti][tj][r];
+                    sx = sx < 0.0 ? 0.0 : sx; // round-off of a difference that is zero
+                    sw = sw < 0.0 ? 0.0 : sw;
+                    const double d = 0.25 * sx * sw;
+                    if (j < g.nB && (d < best_d[ti][r] || (d == best_d[ti][r] && j < best_j[ti][r]))) {
+                        best_d[ti][r] = d;
+                        best_j[ti][r] = j;
+                    }
+                }
+        }
+    }
+
+    // the 16 lanes that share lane >> 4 hold different columns of the same rows; then the four waves
+#pragma unroll
+    for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            double d = best_d[ti][r];
+            int32_t j = best_j[ti][r];
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                const double od = __shfl_xor(d, off);
+                const int32_t oj = __shfl_xor(j, off);
+                if (od < d || (od == d && oj < j)) {
+                    d = od;
+                    j = oj;
+                }
+            }
+            if ((lane & 15) == 0) {
+                fin_d[wave][16 * ti + (lane >> 4) + 4 * r] = d;
+                fin_j[wave][16 * ti + (lane >> 4) + 4 * r] = j;
+            }
+        }
+    __syncthreads();
+    if (tid < TA && a0 + tid < g.nA) {
+        double d = fin_d[0][tid];
+        int32_t j = fin_j[0][tid];
+#pragma unroll
+        for (int w = 1; w < THREADS / 64; ++w)
+            if (fin_d[w][tid] < d || (fin_d[w][tid] == d && fin_j[w][tid] < j)) {
+                d = fin_d[w][tid];
+                j = fin_j[w][tid];
+            }
+        g.best_d[a0 + tid] = d;
+        g.best_j[a0 + tid] = j;
+    }
+}
+
+} // namespace
+
+extern "C" int64_t qllm_match_workspace_bytes(int64_t nA, int64_t nB)
+{
+    if (nA < 0 || nB < 0) return QLLM_ERR_SHAPE;
+    return 2 * (nA + nB) * (int64_t)sizeof(double);
+}
+
+extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, const float *W, int64_t C, int64_t O,
+                                      int64_t ldw, const int32_t *chan_a, int64_t nA, const int32_t *chan_b,
+                                      int64_t nB, int32_t *best_j, double *best_d, void *workspace,
+                                      int64_t workspace_bytes, void *hip_stream)
+{
+    if (!y || !W || !chan_a || !chan_b || !best_j || !best_d) return QLLM_ERR_NULL;
+    if (n <= 0 || C <= 0 || O <= 0 || ldy < C || ldw < O || nA < 0 || nB < 0) return QLLM_ERR_SHAPE;
+    if (n > INT32_MAX || O > INT32_MAX || C > INT32_MAX || nA > INT32_MAX - TA || nB > INT32_MAX - TB) return QLLM_ERR_SHAPE;
+    if (nA == 0) return QLLM_OK;
+    if (nB == 0) return QLLM_ERR_SHAPE; // nothing to match against
+    if (workspace_bytes < qllm_match_workspace_bytes(nA, nB) || !workspace) return QLLM_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 7u) return QLLM_ERR_ALIGN;
+    MatchArgs g{};
+    g.y = y; g.w = W; g.ldy = ldy; g.ldw = ldw;
+    g.n = (int32_t)n; g.O = (int32_t)O; g.nA = (int32_t)nA; g.nB = (int32_t)nB;
+    g.chan_a = chan_a; g.chan_b = chan_b;
+    g.norms = static_cast<const double *>(workspace);
+    g.best_j = best_j; g.best_d = best_d;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(match_norms_kernel, dim3((unsigned)(nA + nB)), dim3(THREADS), 0, stream, g,
+                       static_cast<double *>(workspace));
+    hipLaunchKernelGGL(match_nearest_kernel, dim3((unsigned)((nA + TA - 1) / TA)), dim3(THREADS), 0, stream, g);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        qllm_note_hip_error("channel matching: launch", hipGetErrorName(e));
+        return QLLM_ERR_HIP;
+    }
+    return QLLM_OK;
+}

@@ -308,3 +308,38 @@ def test_fold_linear_host_matches_the_oracle(oracle):
     bad[0] = C
     with pytest.raises(RuntimeError):
         b.qllm_fold_linear_host(Wp, bp, m["row_ptr"], bad, m["scale"])
+
+
+def test_matching_entry_point_rejects_bad_arguments_before_launching():
+    f = b.raw().qllm_match_nearest
+    P = 0x1000                # never dereferenced: every call below fails validation first
+    ok = dict(y=P, n=16, ldy=64, W=P, C=64, O=32, ldw=32, ca=P, nA=10, cb=P, nB=12, bj=P, bd=P, ws=P, wsb=1 << 20)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["y"], a["n"], a["ldy"], a["W"], a["C"], a["O"], a["ldw"], a["ca"], a["nA"], a["cb"], a["nB"],
+                 a["bj"], a["bd"], a["ws"], a["wsb"], None)
+
+    for k in ("y", "W", "ca", "cb", "bj", "bd"):
+        assert call(**{k: None}) == -1
+    assert call(n=0) == -2 and call(O=0) == -2 and call(ldy=63) == -2 and call(ldw=31) == -2 and call(nA=-1) == -2
+    assert call(nB=0) == -2
+    assert call(ws=None) == -7 and call(wsb=b.qllm_match_workspace_bytes(10, 12) - 1) == -7
+    assert call(ws=P + 4) == -6
+    assert call(nA=0) == 0                                            # nothing to match
+    assert b.qllm_match_workspace_bytes(10, 12) == 2 * 22 * 8 and b.qllm_match_workspace_bytes(-1, 3) == -2
+
+
+def test_select_edges_host_matches_the_oracle():
+    """Appendix A step 3 with ties: the library's host helper against the oracle's selection."""
+    from oracle import calibrate
+    rng = np.random.default_rng(8)
+    nA = 500
+    best_d = rng.integers(0, 40, nA).astype(np.float64)              # many ties
+    best_j = rng.integers(0, 300, nA)
+    pos_a, pos_b = 2 * np.arange(nA), 2 * np.arange(300) + 1
+    for r in (0, 1, 37, 499, 500, 800):
+        pick = b.qllm_select_edges_host(best_d, r)
+        src_idx, dst_idx = calibrate.select_edges(best_d, best_j, pos_a, pos_b, r)
+        assert pick.tolist() == src_idx.tolist()
+        assert (dst_idx.tolist() == best_j[pick].tolist())

@@ -7,7 +7,7 @@ scales bit-exact (same fp32 operations on both sides); dequantised outputs withi
 import numpy as np
 import pytest
 
-from helpers import expected_qact, make_case, rel_err, to_torch_x
+from helpers import NORM_ID, expected_qact, make_case, rel_err, to_torch_x
 from paper_2310_08041_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -444,3 +444,106 @@ def test_folded_preceding_linear_path(oracle, b, C, Kp, O, N, bits):
     check_y(oracle, y_fold, exp_fold["y"], "f32")
     a, f = y_rt.cpu().numpy().astype(np.float64), y_fold.cpu().numpy().astype(np.float64)
     assert np.sqrt(((a - f) ** 2).sum()) <= 2e-2 * np.sqrt((a ** 2).sum())
+
+
+# ---------------------------------------------------------------- offline: which channels to merge (Eq. 5, Appendix A)
+
+def matching_case(rng, C, n, O, n_split, twins=0):
+    y = rng.standard_normal((n, C)).astype(np.float32) * rng.uniform(0.2, 3.0, C).astype(np.float32)
+    W = (rng.standard_normal((C, O)) / np.sqrt(C)).astype(np.float32)
+    for k in range(twins):                                # identical pairs across the two sets
+        a, b_ = 2 * rng.integers(0, C // 2), 2 * rng.integers(0, C // 2) + 1
+        y[:, b_], W[b_] = y[:, a], W[a]
+    T = np.ones(C, np.int32)
+    T[rng.choice(C, n_split, replace=False)] = rng.integers(2, 6, n_split)
+    return y, W, T
+
+
+def run_matching(b, y, W, T):
+    import torch
+    from paper_2310_08041_amd import calibrate as dev_cal
+    yd, Wd = torch.from_numpy(y).cuda(), torch.from_numpy(W).cuda()
+    chan_of, pos_a, pos_b = dev_cal.matching_sets(T, yd.device)
+    chan_a, chan_b = chan_of[pos_a].to(torch.int32).contiguous(), chan_of[pos_b].to(torch.int32).contiguous()
+    best_j = torch.full((pos_a.numel(),), -7, dtype=torch.int32, device="cuda")
+    best_d = torch.full((pos_a.numel(),), float("nan"), dtype=torch.float64, device="cuda")
+    ws = torch.empty(b.qllm_match_workspace_bytes(pos_a.numel(), pos_b.numel()), dtype=torch.uint8, device="cuda")
+    b.qllm_match_nearest(yd, Wd, chan_a, chan_b, best_j, best_d, ws)
+    torch.cuda.synchronize()
+    return best_j.cpu().numpy(), best_d.cpu().numpy(), chan_of.cpu().numpy(), pos_a.cpu().numpy(), pos_b.cpu().numpy()
+
+
+def check_matching(y, W, rows, chan_of, pos_a, pos_b, got_j, got_d, ref_j, ref_d):
+    """Distances to double-precision round-off of the inner products; where the device picked another
+    member of B than the oracle, that member must be as near (a tie up to that round-off)."""
+    from oracle import calibrate
+    nx = (y.astype(np.float64) ** 2).sum(0)
+    nw = (W.astype(np.float64) ** 2).sum(1)
+    for k, i in enumerate(rows):
+        ca = chan_of[pos_a[i]]
+        cj = chan_of[pos_b[got_j[i]]]
+        tol = 1e-12 * (nx[ca] + nx[cj]) * (nw[ca] + nw[cj])           # |a|^2 + |b|^2 - 2 a.b in double
+        assert abs(got_d[i] - ref_d[k]) <= tol, (i, got_d[i], ref_d[k])
+        if got_j[i] != ref_j[k]:
+            d_other = calibrate.pair_distance(y[:, ca], y[:, cj], W[ca], W[cj])
+            assert abs(d_other - ref_d[k]) <= tol, (i, got_j[i], ref_j[k])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("C,n,O,n_split,twins", [(70, 5, 3, 4, 2), (301, 40, 70, 9, 3), (2500, 256, 520, 30, 5)])
+def test_match_nearest_small(oracle, b, C, n, O, n_split, twins):
+    """One, a few and many tiles each way, ragged tails in members, tokens and features."""
+    from oracle import calibrate
+    rng = np.random.default_rng(C + n)
+    y, W, T = matching_case(rng, C, n, O, n_split, twins)
+    got_j, got_d, chan_of, pos_a, pos_b = run_matching(b, y, W, T)
+    ref_j, ref_d, ref_a, ref_b = calibrate.nearest_by_eq5(y, W, T, n_match_tokens=n)
+    assert np.array_equal(pos_a, ref_a) and np.array_equal(pos_b, ref_b)
+    assert got_j.min() >= 0 and got_j.max() < pos_b.size
+    check_matching(y, W, np.arange(pos_a.size), chan_of, pos_a, pos_b, got_j, got_d, ref_j, ref_d)
+    assert (got_j != ref_j).mean() <= 0.01
+
+
+@pytest.mark.gpu
+def test_match_nearest_full_70b_sampled(oracle, b):
+    """The 70B down-projection's channel count, 256 calibration tokens, all 8192 output features; the
+    oracle checks sampled members of set A against every member of set B."""
+    from oracle import calibrate
+    w = wl.WORKLOADS["llama70b_down"]
+    rng = np.random.default_rng(77)
+    y, _, _ = wl.draw_activations(w, 256, w.C, 5)
+    y = oracle.widen_bf16(y) if y.dtype == np.uint16 else y
+    W = wl.draw_weight(w, w.C, w.O, 5)
+    absmax = np.abs(y).max(0)
+    T = oracle.num_split(absmax, np.float32(absmax.max() / 8))
+    got_j, got_d, chan_of, pos_a, pos_b = run_matching(b, y, W, T)
+    rows = np.sort(rng.choice(pos_a.size, 6, replace=False))
+    ref_j, ref_d, _, _ = calibrate.nearest_by_eq5(y, W, T, rows=rows)
+    check_matching(y, W, rows, chan_of, pos_a, pos_b, got_j, got_d, ref_j, ref_d)
+    # a property at full size: the reported distance is the distance of the reported pair
+    for i in rng.choice(pos_a.size, 40, replace=False):
+        ca, cj = chan_of[pos_a[i]], chan_of[pos_b[got_j[i]]]
+        d = calibrate.pair_distance(y[:, ca], y[:, cj], W[ca], W[cj])
+        assert abs(d - got_d[i]) <= 1e-9 * max(d, 1e-30) + 1e-12 * (y[:, ca].astype(np.float64) ** 2).sum() * (W[ca].astype(np.float64) ** 2).sum()
+
+
+@pytest.mark.gpu
+def test_calibration_with_eq5_matches_the_oracle(oracle, b):
+    """The whole offline step with weights at hand: statistic kernel, T, Eq. (5) matching on the device,
+    selection, map -- against the oracle's pairs."""
+    import torch
+    from oracle import calibrate
+    from paper_2310_08041_amd import calibrate as dev_cal
+    w = wl.WORKLOADS["llama7b_qkv"]
+    C, O, N = 1536, 320, 96
+    x, _, _ = wl.draw_activations(w, N, C, 9)
+    gamma, beta = wl.draw_norm_params(w, C, 9)
+    W = wl.draw_weight(w, C, O, 9)
+    y = oracle.norm(x, NORM_ID[w.norm], gamma, beta, w.eps)
+    cal = calibrate.calibrate(y, w.theta_rule)
+    r = int((cal["T"].astype(np.int64) - 1).sum())
+    src_ref, dst_ref = calibrate.match_pairs_eq5(y, W, cal["T"], r, n_match_tokens=N)
+    out = dev_cal.calibrate(to_torch_x(x), NORM_ID[w.norm], torch.from_numpy(gamma).cuda(), None, w.eps, w.theta_rule,
+                            n_match=N, W=torch.from_numpy(W).cuda())
+    assert np.array_equal(out["num_split"], cal["T"])
+    assert np.array_equal(out["src_idx"], src_ref) and np.array_equal(out["dst_idx"], dst_ref)
