@@ -21,7 +21,9 @@ namespace {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-constexpr int TA = 64, TB = 128, KT = 16, THREADS = 256, PAD = KT + 1; // PAD: row stride in doubles, odd against bank conflicts
+constexpr int TA = 64, TB = 128, KT = 32, THREADS = 256, PAD = KT + 1; // PAD: row stride in doubles, odd against bank conflicts
+constexpr int NA_STEP = TA * KT / THREADS, NB_STEP = TB * KT / THREADS;     // values per lane and K-step: 8 and 16
+constexpr size_t TILE_LDS = (size_t)2 * (TA + TB) * PAD * sizeof(double);   // two buffers of both tiles: 101376 bytes
 
 struct MatchArgs {
     const float *y;  // [n, ldy]: activations, token-major
@@ -76,67 +78,82 @@ __global__ __launch_bounds__(THREADS) void match_norms_kernel(const MatchArgs g,
     }
 }
 
-// One K-step of operands: 64 x 16 values of the A tile (4 per lane), 128 x 16 of the B tile (8 per lane).
+// One K-step of operands: 64 x 32 values of the A tile (8 per lane), 128 x 32 of the B tile (16 per lane).
 // XPASS: element (member i, token t) = y[t][chan[i]], consecutive lanes take consecutive members;
-// otherwise element (member i, feature k) = w[chan[i]][k], consecutive lanes take consecutive features.
-template <bool XPASS>
-__device__ __forceinline__ void fetch_step(const MatchArgs &g, const int32_t *ca, const int32_t *cb, int k0, int tid,
-                                           float (&pa)[4], float (&pb)[8])
+// otherwise element (member i, feature k) = w[chan[i]][k], a lane takes four consecutive features
+// (one 16-byte load when VEC: rows 16-byte aligned; four 4-byte loads otherwise).
+template <bool XPASS, bool VEC, int ROWS, int PER>
+__device__ __forceinline__ void fetch_tile(const MatchArgs &g, const int32_t *chan, int k0, int tid, float (&p)[PER])
 {
     const int K = XPASS ? g.n : g.O;
+    if constexpr (XPASS) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int e = tid + q * THREADS;
-        const int i = XPASS ? (e & (TA - 1)) : (e / KT), k = XPASS ? (e / TA) : (e % KT);
-        const bool ok = k0 + k < K;
-        const int kk = ok ? k0 + k : 0;
-        const float v = XPASS ? g.y[(int64_t)kk * g.ldy + ca[i]] : g.w[(int64_t)ca[i] * g.ldw + kk];
-        pa[q] = ok ? v : 0.0f;
-    }
+        for (int q = 0; q < PER; ++q) {
+            const int e = tid + q * THREADS, i = e & (ROWS - 1), k = e / ROWS;
+            const bool ok = k0 + k < K;
+            const float v = g.y[(int64_t)(ok ? k0 + k : 0) * g.ldy + chan[i]];
+            p[q] = ok ? v : 0.0f;
+        }
+    } else {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int e = tid + q * THREADS;
-        const int i = XPASS ? (e & (TB - 1)) : (e / KT), k = XPASS ? (e / TB) : (e % KT);
-        const bool ok = k0 + k < K;
-        const int kk = ok ? k0 + k : 0;
-        const float v = XPASS ? g.y[(int64_t)kk * g.ldy + cb[i]] : g.w[(int64_t)cb[i] * g.ldw + kk];
-        pb[q] = ok ? v : 0.0f;
+        for (int q = 0; q < PER / 4; ++q) {
+            const int e = tid + q * THREADS, i = e / (KT / 4), k = 4 * (e % (KT / 4));
+            const float *row = g.w + (int64_t)chan[i] * g.ldw;
+            if (VEC && k0 + k + 3 < K) {
+                const float4 v = *reinterpret_cast<const float4 *>(row + k0 + k);
+                p[4 * q] = v.x; p[4 * q + 1] = v.y; p[4 * q + 2] = v.z; p[4 * q + 3] = v.w;
+            } else {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const bool ok = k0 + k + d < K;
+                    const float v = row[ok ? k0 + k + d : 0];
+                    p[4 * q + d] = ok ? v : 0.0f;
+                }
+            }
+        }
     }
 }
 
-template <bool XPASS>
-__device__ __forceinline__ void stage_step(double *as, double *bs, int tid, const float (&pa)[4], const float (&pb)[8])
+template <bool XPASS, int ROWS, int PER>
+__device__ __forceinline__ void stage_tile(double *tile, int tid, const float (&p)[PER])
 {
+    if constexpr (XPASS) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int e = tid + q * THREADS;
-        const int i = XPASS ? (e & (TA - 1)) : (e / KT), k = XPASS ? (e / TA) : (e % KT);
-        as[i * PAD + k] = (double)pa[q];
-    }
+        for (int q = 0; q < PER; ++q) {
+            const int e = tid + q * THREADS, i = e & (ROWS - 1), k = e / ROWS;
+            tile[i * PAD + k] = (double)p[q];
+        }
+    } else {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int e = tid + q * THREADS;
-        const int i = XPASS ? (e & (TB - 1)) : (e / KT), k = XPASS ? (e / TB) : (e % KT);
-        bs[i * PAD + k] = (double)pb[q];
+        for (int q = 0; q < PER / 4; ++q) {
+            const int e = tid + q * THREADS, i = e / (KT / 4), k = 4 * (e % (KT / 4));
+#pragma unroll
+            for (int d = 0; d < 4; ++d) tile[i * PAD + k + d] = (double)p[4 * q + d];
+        }
     }
 }
 
 // acc[ti][tj] += A tile rows 16 ti.. times B tile rows 32 wave + 16 tj.., over K (n tokens or O features)
-template <bool XPASS>
+template <bool XPASS, bool VEC>
 __device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca, const int32_t *cb, double *as, double *bs,
                                           int tid, v4d (&acc)[4][2])
 {
     const int lane = tid & 63, wave = tid >> 6;
     const int K = XPASS ? g.n : g.O;
     const int steps = (K + KT - 1) / KT;
-    float pa[4], pb[8];
-    fetch_step<XPASS>(g, ca, cb, 0, tid, pa, pb);
+    float pa[NA_STEP], pb[NB_STEP];
+    fetch_tile<XPASS, VEC, TA, NA_STEP>(g, ca, 0, tid, pa);
+    fetch_tile<XPASS, VEC, TB, NB_STEP>(g, cb, 0, tid, pb);
     for (int s = 0; s < steps; ++s) {
         double *a_buf = as + (s & 1) * TA * PAD, *b_buf = bs + (s & 1) * TB * PAD;
-        stage_step<XPASS>(a_buf, b_buf, tid, pa, pb);
+        stage_tile<XPASS, TA, NA_STEP>(a_buf, tid, pa);
+        stage_tile<XPASS, TB, NB_STEP>(b_buf, tid, pb);
         // one barrier per step: the buffer written now was last read two steps ago, before the previous barrier
         __syncthreads();
-        if (s + 1 < steps) fetch_step<XPASS>(g, ca, cb, (s + 1) * KT, tid, pa, pb);
+        if (s + 1 < steps) {
+            fetch_tile<XPASS, VEC, TA, NA_STEP>(g, ca, (s + 1) * KT, tid, pa);
+            fetch_tile<XPASS, VEC, TB, NB_STEP>(g, cb, (s + 1) * KT, tid, pb);
+        }
 #pragma unroll
         for (int kk = 0; kk < KT / 4; ++kk) {
             double a[4], b[2];
@@ -154,9 +171,11 @@ __device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca,
     __syncthreads(); // the next pass starts writing buffer 0 again
 }
 
+template <bool VEC>
 __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs g)
 {
-    __shared__ double as[2 * TA * PAD], bs[2 * TB * PAD];
+    extern __shared__ __align__(16) double tiles[];
+    double *as = tiles, *bs = tiles + 2 * TA * PAD;
     __shared__ double na_x[TA], na_w[TA], nb_x[TB], nb_w[TB];
     __shared__ int32_t ca[TA], cb[TB];
     __shared__ double fin_d[THREADS / 64][TA];
@@ -196,8 +215,8 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
         for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
             for (int tj = 0; tj < 2; ++tj) gx[ti][tj] = gw[ti][tj] = v4d{0.0, 0.0, 0.0, 0.0};
-        gram_pass<true>(g, ca, cb, as, bs, tid, gx);
-        gram_pass<false>(g, ca, cb, as, bs, tid, gw);
+        gram_pass<true, VEC>(g, ca, cb, as, bs, tid, gx);
+        gram_pass<false, VEC>(g, ca, cb, as, bs, tid, gw);
         // distances of this tile; element r of an accumulator: row (lane >> 4) + 4 r, column lane & 15
         // (checked against the oracle: the fp64 operation interleaves the rows of its four result registers)
 #pragma unroll
@@ -288,7 +307,21 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     (void)hipGetLastError();
     hipLaunchKernelGGL(match_norms_kernel, dim3((unsigned)(nA + nB)), dim3(THREADS), 0, stream, g,
                        static_cast<double *>(workspace));
-    hipLaunchKernelGGL(match_nearest_kernel, dim3((unsigned)((nA + TA - 1) / TA)), dim3(THREADS), 0, stream, g);
+    // 16-byte loads of weight rows where every row allows them
+    const bool vec = (reinterpret_cast<uintptr_t>(W) & 15u) == 0 && (ldw & 3) == 0;
+    const void *fn = vec ? reinterpret_cast<const void *>(&match_nearest_kernel<true>)
+                         : reinterpret_cast<const void *>(&match_nearest_kernel<false>);
+    {
+        const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TILE_LDS);
+        if (ea != hipSuccess) {
+            (void)hipGetLastError();
+            qllm_note_hip_error("channel matching: raising the LDS limit", hipGetErrorName(ea));
+            return QLLM_ERR_HIP;
+        }
+    }
+    const dim3 grid((unsigned)((nA + TA - 1) / TA));
+    if (vec) hipLaunchKernelGGL(match_nearest_kernel<true>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    else hipLaunchKernelGGL(match_nearest_kernel<false>, grid, dim3(THREADS), TILE_LDS, stream, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         qllm_note_hip_error("channel matching: launch", hipGetErrorName(e));
