@@ -155,3 +155,38 @@ def calibrate(y, theta_rule, merge=True, n_match_tokens=256):
     r = int((T.astype(np.int64) - 1).sum()) if merge else 0
     src_idx, dst_idx = nearest_pairs(y, T, r, n_match_tokens)
     return dict(absmax=absmax, theta=theta, T=T, src_idx=src_idx, dst_idx=dst_idx)
+
+
+def theta_grid(absmax, P):
+    """Algorithm 1: theta_p = min(m) + p / P (max(m) - min(m)), p = 1..P, each rounded once to float32."""
+    m = np.asarray(absmax, np.float32).astype(np.float64)
+    lo, hi = m.min(), m.max()
+    return [float(np.float32(lo + (p / P) * (hi - lo))) for p in range(1, P + 1)]
+
+
+def reassembly_loss(x, norm_kind, gamma, beta, eps, W, theta, a_bits, w_bits, n_match_tokens=256):
+    """Algorithm 1's function ReAssembly(theta) for one linear layer: disassemble with T = ceil(m / theta),
+    merge the sum(T - 1) nearest pairs under Eq. (5), quantize reassembled activations and weights, and
+    return the squared error of the layer's output against the full-precision norm -> linear.  (The
+    paper evaluates Eq. (6) on a whole attention block; one layer has no softmax to go through, so the
+    error is taken at the layer's own output.)  Returns (loss, T, src_idx, dst_idx)."""
+    y = api.norm(x, norm_kind, gamma, beta, eps)
+    absmax = api.channel_absmax(y)
+    T = api.num_split(absmax, np.float32(theta))
+    r = int((T.astype(np.int64) - 1).sum())
+    src_idx, dst_idx = match_pairs_eq5(y, W, T, r, n_match_tokens)
+    What = api.reassemble_weight(W, T, src_idx, dst_idx)
+    wq = api.quantize_weight(What, w_bits)
+    out = api.reassembled_linear(x, norm_kind, gamma, beta, eps, T, src_idx, dst_idx, a_bits, wq, want_acc=False)
+    ref = y.astype(np.float64) @ np.asarray(W, np.float64)
+    err = out["y"].astype(np.float64) - ref
+    return float((err * err).sum()), T, src_idx, dst_idx
+
+
+def grid_search_theta(x, norm_kind, gamma, beta, eps, W, a_bits, w_bits, P, n_match_tokens=256):
+    """Algorithm 1: the theta of the grid with the smallest reassembly error (the first one on ties).
+    Returns (theta_star, losses)."""
+    y = api.norm(x, norm_kind, gamma, beta, eps)
+    thetas = theta_grid(api.channel_absmax(y), P)
+    losses = [reassembly_loss(x, norm_kind, gamma, beta, eps, W, t, a_bits, w_bits, n_match_tokens)[0] for t in thetas]
+    return thetas[int(np.argmin(losses))], thetas, losses

@@ -122,3 +122,39 @@ def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256, W=
     out = b.qllm_build_map_host(m, theta, src_idx, dst_idx)
     out.update(theta=theta, absmax=m, src_idx=src_idx, dst_idx=dst_idx)
     return out
+
+
+def theta_grid(absmax, P):
+    """Algorithm 1: theta_p = min(m) + p / P (max(m) - min(m)) for p = 1..P, rounded once to float32."""
+    m = np.asarray(absmax, np.float32).astype(np.float64)
+    return [float(np.float32(m.min() + (p / P) * (m.max() - m.min()))) for p in range(1, P + 1)]
+
+
+def grid_search_theta(x, norm, gamma, beta, eps, W, a_bits, w_bits, P, n_match=256):
+    """Algorithm 1 for one linear layer: for every theta of the grid, disassemble, merge the nearest pairs
+    under Eq. (5), quantize, run the reassembled layer (the library's hot path) on the calibration batch
+    and take the squared error of its output against the full-precision norm -> linear; keep the theta
+    with the smallest error.  x: [N, C] device tensor, W: [C, O] fp32 device tensor.  The full-precision
+    reference is a torch matrix product in float64 (a library primitive).
+    Returns dict(theta, thetas, losses, map) with `map` the result of `calibrate` at the chosen theta."""
+    N, C = x.shape
+    absmax = torch.zeros(C, dtype=torch.float32, device=x.device)
+    y = torch.empty((N, C), dtype=torch.float32, device=x.device)
+    b.qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y)
+    ref = y.double() @ W.double()
+    W_host = W.cpu().numpy()
+    thetas = theta_grid(absmax.cpu().numpy(), P)
+    losses, maps = [], []
+    for theta in thetas:
+        cal = calibrate(x, norm, gamma, beta, eps, ("fixed", theta), n_match=n_match, W=W)
+        dmap = b.DeviceMap(cal["row_ptr"], cal["src"], cal["scale"], C, cal["plan"])
+        q = b.qllm_quantize_weight_host(W_host, cal["row_ptr"], cal["src"], w_bits)
+        dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], dmap.C_out, w_bits)
+        out = torch.empty((N, W.shape[1]), dtype=torch.float32, device=x.device)
+        ws = torch.empty(b.qllm_workspace_bytes(N, dmap.C_out, W.shape[1], a_bits), dtype=torch.uint8, device=x.device)
+        b.qllm_reassembled_linear(x, norm, gamma, beta, eps, dmap, a_bits, dw, out, ws)
+        err = out.double() - ref
+        losses.append(float((err * err).sum().item()))
+        maps.append(cal)
+    best = int(np.argmin(losses))
+    return dict(theta=thetas[best], thetas=thetas, losses=losses, map=maps[best])

@@ -547,3 +547,27 @@ def test_calibration_with_eq5_matches_the_oracle(oracle, b):
                             n_match=N, W=torch.from_numpy(W).cuda())
     assert np.array_equal(out["num_split"], cal["T"])
     assert np.array_equal(out["src_idx"], src_ref) and np.array_equal(out["dst_idx"], dst_ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("bits", [4, 6])
+def test_theta_grid_search_matches_the_oracle(oracle, b, bits):
+    """Algorithm 1 for one layer (the reassembly error taken at the layer's own output): the device-side
+    search -- statistic kernel, Eq. (5) matching, host map and weight helpers, the hot path itself as the
+    thing being scored -- against the oracle's, grid point by grid point."""
+    import torch
+    from oracle import calibrate
+    from paper_2310_08041_amd import calibrate as dev_cal
+    w = wl.WORKLOADS["llama7b_qkv"]
+    C, O, N, P = 512, 192, 96, 6
+    x, _, _ = wl.draw_activations(w, N, C, 21)
+    gamma, _ = wl.draw_norm_params(w, C, 21)
+    W = wl.draw_weight(w, C, O, 21)
+    theta_ref, thetas_ref, losses_ref = calibrate.grid_search_theta(x, NORM_ID[w.norm], gamma, None, w.eps, W, bits, bits, P,
+                                                                    n_match_tokens=N)
+    got = dev_cal.grid_search_theta(to_torch_x(x), NORM_ID[w.norm], torch.from_numpy(gamma).cuda(), None, w.eps,
+                                    torch.from_numpy(W).cuda(), bits, bits, P, n_match=N)
+    assert got["thetas"] == thetas_ref
+    assert np.allclose(got["losses"], losses_ref, rtol=1e-5, atol=0)
+    assert got["theta"] == theta_ref
+    assert got["map"]["C_out"] >= C - 1

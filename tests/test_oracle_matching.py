@@ -91,3 +91,30 @@ def test_matching_prefers_pairs_that_cost_nothing():
     T = np.ones(C, np.int32)
     src_idx, dst_idx = calibrate.match_pairs_eq5(y, W, T, 3)
     assert sorted(zip((2 * src_idx).tolist(), (2 * dst_idx + 1).tolist())) == sorted(twins)
+
+
+def test_theta_grid_is_algorithm_1():
+    m = np.array([0.5, 2.0, 8.5, 1.0], np.float32)
+    assert calibrate.theta_grid(m, 4) == [2.5, 4.5, 6.5, 8.5]          # min + p/P (max - min)
+    assert calibrate.theta_grid(m, 1) == [8.5]                          # p = P: nothing is disassembled
+
+
+def test_grid_search_prefers_reassembly_when_there_are_outliers(oracle):
+    """Algorithm 1 on a small layer with massive outlier channels at 4 bits: the last grid point
+    (theta = max: no disassembly, plain quantization) must lose against some smaller theta, and the loss
+    reported for a theta is the squared output error of exactly that reassembled, quantized layer."""
+    rng = np.random.default_rng(12)
+    N, C, O = 48, 96, 40
+    x = rng.standard_normal((N, C)).astype(np.float32)
+    x[:, [5, 40, 77]] *= np.array([30.0, 55.0, 24.0], np.float32)
+    W = (rng.standard_normal((C, O)) / np.sqrt(C)).astype(np.float32)
+    theta, thetas, losses = calibrate.grid_search_theta(x, 0, None, None, 0.0, W, 4, 4, 8, n_match_tokens=N)
+    assert len(losses) == 8 and theta == thetas[int(np.argmin(losses))]
+    assert min(losses) < 0.7 * losses[-1] and theta < thetas[-1]
+    # the last grid point is the layer without reassembly
+    loss_plain, T, src_idx, dst_idx = calibrate.reassembly_loss(x, 0, None, None, 0.0, W, thetas[-1], 4, 4, N)
+    assert np.all(T == 1) and src_idx.size == 0 and loss_plain == losses[-1]
+    wq = oracle.quantize_weight(W, 4)
+    plain = oracle.reassembled_linear(x, 0, None, None, 0.0, np.ones(C, np.int32), [], [], 4, wq)["y"]
+    ref = x.astype(np.float64) @ W.astype(np.float64)
+    assert np.isclose(((plain - ref) ** 2).sum(), loss_plain, rtol=1e-12)
