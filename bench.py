@@ -129,6 +129,9 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph holding one step per rotating buffer set (launch-bound shapes)")
+    ap.add_argument("--assemble-more", type=float, default=0.0,
+                    help="merge this fraction of C more channel pairs than disassembly added (C^ < C: the paper's "
+                         "speed-up variant); 0 keeps C^ = C as in the paper's experiments")
     ap.add_argument("--stage", default="layer", choices=["layer", "match"],
                     help="layer: the hot path (the default, the line the contract asks for); match: the offline "
                          "channel matching of Eq. (5) / Appendix A at the workload's channel count")
@@ -163,7 +166,7 @@ def main():
     beta = None if beta_h is None else torch.from_numpy(beta_h).to(dev)
 
     # ---- offline: calibration -> map; weight reassembly + quantization (library host helpers)
-    cal = calibrate.calibrate(x0, norm, gamma, beta, w.eps, w.theta_rule)
+    cal = calibrate.calibrate(x0, norm, gamma, beta, w.eps, w.theta_rule, assemble_more=args.assemble_more)
     dmap = b.DeviceMap(cal["row_ptr"], cal["src"], cal["scale"], w.C, cal["plan"])
     K = dmap.C_out
     W = wl.draw_weight(w)

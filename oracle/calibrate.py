@@ -145,14 +145,16 @@ def match_pairs_eq5(y, W, T, r, n_match_tokens=256):
     return select_edges(best_d, best_j, pos_a, pos_b, r)
 
 
-def calibrate(y, theta_rule, merge=True, n_match_tokens=256):
+def calibrate(y, theta_rule, merge=True, n_match_tokens=256, assemble_more=0.0):
     """y: norm output [N, C] float32 (from the oracle).  Returns a dict with absmax, theta, T,
-    src_idx, dst_idx.  With merge=True sum(T-1) pairs are merged, so C^ == C (fewer only if set A
+    src_idx, dst_idx.  With merge=True sum(T-1) + assemble_more * C pairs are merged, so C^ == C for
+    assemble_more == 0 and C^ < C above it (the speed-up variant of the introduction; fewer only if set A
     has fewer eligible members than that)."""
     absmax = api.channel_absmax(y)
     theta = theta_from_rule(absmax, theta_rule)
     T = api.num_split(absmax, theta)
     r = int((T.astype(np.int64) - 1).sum()) if merge else 0
+    r += int(round(assemble_more * T.size))             # "assemble more than disassembled": C^ < C (Sec. 1)
     src_idx, dst_idx = nearest_pairs(y, T, r, n_match_tokens)
     return dict(absmax=absmax, theta=theta, T=T, src_idx=src_idx, dst_idx=dst_idx)
 

@@ -102,7 +102,7 @@ def match_pairs_eq5(y, W, num_split, r):
     return src_idx, dst_idx, best_j, best_d
 
 
-def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256, W=None):
+def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256, W=None, assemble_more=0.0):
     """x: [N, C] device tensor (fp32 / bf16); W: None, or the layer's [C, O] fp32 device weights, which
     switches the pair selection to the distance of Eq. (5).  Returns the dict of qllm_build_map_host plus
     theta, absmax, src_idx, dst_idx."""
@@ -115,6 +115,7 @@ def calibrate(x, norm, gamma, beta, eps, theta_rule, merge=True, n_match=256, W=
     sizing = b.qllm_build_map_host(m, theta, [], [], with_plan=False)
     T = sizing["num_split"]
     r = int(sizing["nnz"] - C) if merge else 0
+    r += int(round(assemble_more * C))   # assemble more channels than were disassembled: C^ < C, a shorter GEMM
     if W is None:
         src_idx, dst_idx = match_pairs(y, T, r)
     else:

@@ -11,7 +11,8 @@ class Case:
     pass
 
 
-def make_case(oracle, w, N=None, C=None, O=None, seed=None, merge=True, real_weights=True, theta_rule=None):
+def make_case(oracle, w, N=None, C=None, O=None, seed=None, merge=True, real_weights=True, theta_rule=None,
+              assemble_more=0.0):
     """Draws a workload (optionally resized), calibrates it with the oracle and returns a Case with
     inputs (x, gamma, beta), the paper-form map (absmax, theta, T, src_idx, dst_idx), the oracle's
     CSR map and the oracle's weights (one byte per code)."""
@@ -24,7 +25,7 @@ def make_case(oracle, w, N=None, C=None, O=None, seed=None, merge=True, real_wei
     c.x, c.out_ch, c.out_fac = wl.draw_activations(w, c.N, c.C, seed)
     c.gamma, c.beta = wl.draw_norm_params(w, c.C, seed)
     y = oracle.norm(c.x, c.norm, c.gamma, c.beta, c.eps)
-    cal = calibrate.calibrate(y, theta_rule or w.theta_rule, merge=merge)
+    cal = calibrate.calibrate(y, theta_rule or w.theta_rule, merge=merge, assemble_more=assemble_more)
     c.absmax, c.theta, c.T, c.src_idx, c.dst_idx = (cal[k] for k in ("absmax", "theta", "T", "src_idx", "dst_idx"))
     c.row_ptr, c.src, c.scale = oracle.build_map(c.T, c.src_idx, c.dst_idx)
     c.K = c.row_ptr.size - 1

@@ -571,3 +571,31 @@ def test_theta_grid_search_matches_the_oracle(oracle, b, bits):
     assert np.allclose(got["losses"], losses_ref, rtol=1e-5, atol=0)
     assert got["theta"] == theta_ref
     assert got["map"]["C_out"] >= C - 1
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("more", [0.1, 0.4])
+def test_assemble_more_than_disassembled(oracle, b, more):
+    """C^ < C: more pairs merged than disassembly added (the variant the paper's introduction names for
+    speed).  Same kernels, a map with many merged rows, a shorter GEMM; parity as everywhere else, and
+    the output error grows with the number of merged channels."""
+    import torch
+    w = wl.WORKLOADS["llama7b_qkv"]
+    N, C, O = 150, 2048, 320
+    errs = []
+    for frac in (0.0, more):
+        c = make_case(oracle, w, N=N, C=C, O=O, assemble_more=frac)
+        if frac:
+            assert c.K <= C - int(0.9 * frac * C)
+        exp = oracle.reassembled_linear(c.x, c.norm, c.gamma, c.beta, c.eps, c.T, c.src_idx, c.dst_idx, w.a_bits,
+                                        (c.wcodes, c.aw, c.bw, c.cs))
+        dm = device_map(b, c)
+        dw = device_weight(b, c)
+        y = torch.full((N, O), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(b.qllm_workspace_bytes(N, c.K, O, w.a_bits), dtype=torch.uint8, device="cuda")
+        b.qllm_reassembled_linear(to_torch_x(c.x), c.norm, torch.from_numpy(c.gamma).cuda(), None, c.eps, dm, w.a_bits, dw, y, ws)
+        torch.cuda.synchronize()
+        check_y(oracle, y, exp["y"], "f32")
+        full = oracle.norm(c.x, c.norm, c.gamma, c.beta, c.eps).astype(np.float64) @ c.W.astype(np.float64)
+        errs.append(float(((exp["y"] - full) ** 2).mean()))
+    assert errs[1] > errs[0]
