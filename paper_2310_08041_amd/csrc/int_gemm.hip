@@ -329,10 +329,11 @@ __global__ __launch_bounds__(THREADS) void int_gemm_kernel(const GemmArgs g)
     finish_wave_tile<ABITS, WBITS, YT, 4, 4>(g, acc, n0 + wm * 64, o0 + wn * 64, lane);
 }
 
-// ---- the large-tile kernel: 512 lanes (8 waves, 2 x 4), a 256 x 256 tile of Y, K-tiles of 128 codes,
-// two LDS buffers.  While the matrix cores work through buffer `cur`, the lanes expand the next
-// K-tile (fetched one iteration earlier) into the other buffer and fetch the one after it: one
-// barrier per K-tile, and the expansion overlaps the multiplication of the other wave on the SIMD.
+// ---- the large-tile kernel for bit pairs other than 4/4: 512 lanes (8 waves, 2 x 4), a 256 x 256 tile
+// of Y, K-tiles of 128 codes, one byte per code in two LDS buffers.  While the matrix cores work
+// through buffer `cur`, the lanes expand the next K-tile (fetched one iteration earlier) into the other
+// buffer, one 16-byte chunk per group of four matrix-core operations, and fetch the one after it: one
+// barrier per K-tile.
 constexpr int LBM = 256, LBN = 256, LKT = 128, LTHREADS = 512, LROWB = LKT; // one byte per code in LDS
 constexpr int LBUF = (LBM + LBN) * LROWB;                                   // 64 KB per buffer
 
@@ -786,10 +787,11 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
             if (y_dtype == QLLM_F32)
                 return launch_kernel(int_gemm_w4a4_kernel<float>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
             return launch_kernel(int_gemm_w4a4_kernel<uint16_t>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
+        } else {
+            if (y_dtype == QLLM_F32)
+                return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
+            return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, uint16_t>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
         }
-        if (y_dtype == QLLM_F32)
-            return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
-        return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, uint16_t>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);
     }
     if (g.N <= 32) { // decode: stream the weights once
         const dim3 grid((unsigned)((g.O + 16 * SK_RT - 1) / (16 * SK_RT)));
