@@ -171,7 +171,75 @@ __device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca,
     __syncthreads(); // the next pass starts writing buffer 0 again
 }
 
-template <bool VEC>
+// The weight pass when every row allows 16-byte loads and O is a multiple of the K-step: the operands
+// go from global memory straight into LDS (global_load_lds_dwordx4: lane l of a wave lands at the
+// wave's LDS base + 16 l), as fp32, three K-steps ahead in a ring of four stages, and are widened to
+// double when the matrix-core operands are read.  No staging registers, no conversion and store pass;
+// with one wave per SIMD the latency of the loads was what the register path spent half its time on.
+// A stage holds 192 rows (64 of the A tile, 128 of the B tile) of 32 floats; a wave load covers 8 rows;
+// the 16-byte chunk c of row R sits at position c ^ ((R >> 1) & 7), chosen on the global side (which
+// chunk a lane fetches), so that the 64 lanes of an operand read fall on 64 different banks.
+constexpr int STAGE_F = (TA + TB) * KT, NSTAGE = 4;                 // floats per stage (24 KB), stages
+constexpr int WAIT_VM12_LGKM0 = 12 | (7 << 4) | (0 << 8);          // s_waitcnt vmcnt(12) lgkmcnt(0)
+constexpr int WAIT_VM0_ONLY = 0 | (7 << 4) | (15 << 8);            // s_waitcnt vmcnt(0)
+static_assert((size_t)NSTAGE * STAGE_F * sizeof(float) <= TILE_LDS, "the fp32 ring fits where the fp64 tiles are");
+
+__device__ __forceinline__ void gram_pass_w_dma(const MatchArgs &g, const int32_t *ca, const int32_t *cb, float *ring, int tid,
+                                                v4d (&acc)[4][2])
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int steps = g.O / KT;
+    // this wave's six loads per K-step: blocks wave, wave + 4, .. of 8 rows each (blocks 0..7: A tile)
+    const float *src[6];
+#pragma unroll
+    for (int t = 0; t < 6; ++t) {
+        const int row = 8 * (wave + 4 * t) + (lane >> 3);
+        const int chan = row < TA ? ca[row] : cb[row - TA];
+        src[t] = g.w + (int64_t)chan * g.ldw + 4 * ((lane & 7) ^ ((row >> 1) & 7));
+    }
+    auto fetch = [&](int s) { // K-step s (clamped to the last one) -> stage s & 3
+        const int sc = min(s, steps - 1);
+        float *dst = ring + (s & (NSTAGE - 1)) * STAGE_F;
+#pragma unroll
+        for (int t = 0; t < 6; ++t)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[t] + (int64_t)sc * KT),
+                                             (__attribute__((address_space(3))) void *)(dst + 8 * (wave + 4 * t) * KT), 16, 0, 0);
+    };
+    const int r = lane & 15, kq = lane >> 4, f = (r >> 1) & 7;
+    fetch(0);
+    fetch(1);
+    fetch(2);
+    for (int s = 0; s < steps; ++s) {
+        // loads complete in order: at most the two newest steps outstanding = step s has landed (this
+        // wave's share; the barrier adds the others').  The stage written next was read in step s - 1.
+        __builtin_amdgcn_s_waitcnt(WAIT_VM12_LGKM0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        fetch(s + 3);
+        const float *sb = ring + (s & (NSTAGE - 1)) * STAGE_F;
+#pragma unroll
+        for (int kk = 0; kk < KT / 4; ++kk) {
+            const int off = 4 * (kk ^ f) + kq;
+            double a[4], b[2];
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti) a[ti] = (double)sb[(16 * ti + r) * KT + off];
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) b[tj] = (double)sb[(TA + 32 * wave + 16 * tj + r) * KT + off];
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj)
+                    acc[ti][tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ti], b[tj], acc[ti][tj], 0, 0, 0);
+        }
+    }
+    // the loads past the last step went to stages nobody reads; they must have landed before the
+    // memory is used for anything else (the next tile's first pass, or another workgroup)
+    __builtin_amdgcn_s_waitcnt(WAIT_VM0_ONLY);
+    __syncthreads();
+}
+
+template <int MODE> // 0: 4-byte loads; 1: 16-byte loads of weight rows; 2: weight rows straight into LDS
 __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs g)
 {
     extern __shared__ __align__(16) double tiles[];
@@ -215,8 +283,9 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
         for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
             for (int tj = 0; tj < 2; ++tj) gx[ti][tj] = gw[ti][tj] = v4d{0.0, 0.0, 0.0, 0.0};
-        gram_pass<true, VEC>(g, ca, cb, as, bs, tid, gx);
-        gram_pass<false, VEC>(g, ca, cb, as, bs, tid, gw);
+        gram_pass<true, MODE != 0>(g, ca, cb, as, bs, tid, gx);
+        if constexpr (MODE == 2) gram_pass_w_dma(g, ca, cb, reinterpret_cast<float *>(tiles), tid, gw);
+        else gram_pass<false, MODE != 0>(g, ca, cb, as, bs, tid, gw);
         // distances of this tile; element r of an accumulator: row (lane >> 4) + 4 r, column lane & 15
         // (checked against the oracle: the fp64 operation interleaves the rows of its four result registers)
 #pragma unroll
@@ -307,10 +376,12 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     (void)hipGetLastError();
     hipLaunchKernelGGL(match_norms_kernel, dim3((unsigned)(nA + nB)), dim3(THREADS), 0, stream, g,
                        static_cast<double *>(workspace));
-    // 16-byte loads of weight rows where every row allows them
+    // 16-byte loads of weight rows where every row allows them, straight into LDS where the K-steps come out even
     const bool vec = (reinterpret_cast<uintptr_t>(W) & 15u) == 0 && (ldw & 3) == 0;
-    const void *fn = vec ? reinterpret_cast<const void *>(&match_nearest_kernel<true>)
-                         : reinterpret_cast<const void *>(&match_nearest_kernel<false>);
+    const int mode = vec ? (O % KT == 0 ? 2 : 1) : 0;
+    const void *fn = mode == 2   ? reinterpret_cast<const void *>(&match_nearest_kernel<2>)
+                     : mode == 1 ? reinterpret_cast<const void *>(&match_nearest_kernel<1>)
+                                 : reinterpret_cast<const void *>(&match_nearest_kernel<0>);
     {
         const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TILE_LDS);
         if (ea != hipSuccess) {
@@ -320,8 +391,9 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
         }
     }
     const dim3 grid((unsigned)((nA + TA - 1) / TA));
-    if (vec) hipLaunchKernelGGL(match_nearest_kernel<true>, grid, dim3(THREADS), TILE_LDS, stream, g);
-    else hipLaunchKernelGGL(match_nearest_kernel<false>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    if (mode == 2) hipLaunchKernelGGL(match_nearest_kernel<2>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    else if (mode == 1) hipLaunchKernelGGL(match_nearest_kernel<1>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    else hipLaunchKernelGGL(match_nearest_kernel<0>, grid, dim3(THREADS), TILE_LDS, stream, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         qllm_note_hip_error("channel matching: launch", hipGetErrorName(e));
