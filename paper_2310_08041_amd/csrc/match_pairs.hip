@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 
 #include "qllm.h"
 
@@ -382,12 +383,18 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     const void *fn = mode == 2   ? reinterpret_cast<const void *>(&match_nearest_kernel<2>)
                      : mode == 1 ? reinterpret_cast<const void *>(&match_nearest_kernel<1>)
                                  : reinterpret_cast<const void *>(&match_nearest_kernel<0>);
-    {
-        const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TILE_LDS);
-        if (ea != hipSuccess) {
-            (void)hipGetLastError();
-            qllm_note_hip_error("channel matching: raising the LDS limit", hipGetErrorName(ea));
-            return QLLM_ERR_HIP;
+    { // the LDS limit is raised once per kernel; later calls (also under stream capture) only launch
+        static std::mutex lock;
+        static bool raised[3] = {false, false, false};
+        std::lock_guard<std::mutex> hold(lock);
+        if (!raised[mode]) {
+            const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TILE_LDS);
+            if (ea != hipSuccess) {
+                (void)hipGetLastError();
+                qllm_note_hip_error("channel matching: raising the LDS limit", hipGetErrorName(ea));
+                return QLLM_ERR_HIP;
+            }
+            raised[mode] = true;
         }
     }
     const dim3 grid((unsigned)((nA + TA - 1) / TA));
