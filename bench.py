@@ -138,7 +138,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over tokens with no "
-                 "communication; see DESIGN.md). Run with --gpus 1.")
+                 "communication between GPUs). Run with --gpus 1.")
 
     import numpy as np
     import torch
