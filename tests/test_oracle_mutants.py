@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 import test_oracle_gemm as tg
+import test_oracle_matching as tm
 import test_oracle_golden as tgold
 import test_oracle_norm as tn
 import test_oracle_quant as tq
@@ -136,6 +137,24 @@ def weight_quantized_per_tensor(o, What, bits):
     return codes, np.full(O, a1[0], np.float32), np.full(O, b1[0], np.int32), codes.sum(1).astype(np.int32)
 
 
+def fold_sums_the_group(o, Wp, bp, T, src_idx, dst_idx):
+    W_hat, b_hat = o.fold_preceding_linear(Wp, bp, T, src_idx, dst_idx)
+    rp, _, _ = o.build_map(np.asarray(T, np.int32), src_idx, dst_idx)
+    members = np.where(np.diff(rp) > 1, np.diff(rp), 1)[:, None].astype(np.float64)
+    return W_hat * members, None if b_hat is None else b_hat * members[:, 0]   # (W_i + W_j) where Appendix B has the mean
+
+
+def fold_forgets_the_division_by_T(o, Wp, bp, T, src_idx, dst_idx):
+    W_hat, b_hat = o.fold_preceding_linear(Wp, bp, T, src_idx, dst_idx)
+    if len(src_idx) == 0 and np.all(np.asarray(T) == 1):
+        return W_hat, b_hat
+    rp, src, sc = o.build_map(np.asarray(T, np.int32), src_idx, dst_idx)
+    rows = np.diff(rp) == 1
+    scale_of_row = np.asarray(sc, np.float64)[rp[:-1]]
+    fix = np.where(rows, 1.0 / scale_of_row, 1.0)[:, None]                      # sub-channels copied, not divided by T
+    return W_hat * fix, None if b_hat is None else b_hat * fix[:, 0]
+
+
 CASES = [
     ("LayerNorm divides the variance by C - 1", dict(norm=unbiased_variance),
      [lambda o: tn.test_layernorm_matches_torch_fp64(o, 64, "f32"), tn.test_layernorm_closed_form_biased_variance]),
@@ -168,6 +187,10 @@ CASES = [
      [tr.test_merging_identical_channels_is_exact_and_error_closed_form]),
     ("weights quantized per tensor", dict(quantize_weight=weight_quantized_per_tensor),
      [tq.test_per_output_channel_weight_quantization]),
+    ("Appendix B: merged columns summed instead of averaged", dict(fold_preceding_linear=fold_sums_the_group),
+     [tr.test_fold_worked_example, lambda o: tr.test_fold_equals_runtime_reassembly(o, 0)]),
+    ("Appendix B: sub-channel columns not divided by T", dict(fold_preceding_linear=fold_forgets_the_division_by_T),
+     [tr.test_fold_worked_example, lambda o: tr.test_fold_equals_runtime_reassembly(o, 1)]),
 ]
 
 
@@ -180,6 +203,84 @@ def test_a_planted_mistake_fails_a_pin(oracle, what, planted, pins):
     for pin in pins:
         try:
             pin(mutant)
+        except AssertionError:
+            caught += 1
+    assert caught > 0, f"no pin noticed: {what}"
+
+
+# ---- the same for the offline matching (functions of oracle.calibrate, planted by replacing the
+#      module's attribute, so that the functions which call them see the mistake too)
+
+def _distance_second_term_sign(xi, xj, wi, wj):
+    xi, xj, wi, wj = (np.asarray(v, np.float64) for v in (xi, xj, wi, wj))
+    e = np.outer(xi, wi - wj) / 2.0 + np.outer(xj, wi - wj) / 2.0     # x_j (W_i - W_j): the sign of Eq. (5)'s second term
+    return float((e * e).sum())
+
+
+def _nearest(real, keep_quarter=True, use_weights=True, ties_high=False):
+    def planted(y, W, T, n_match_tokens=256, rows=None):
+        from oracle import calibrate
+        chan_of, pos_a, pos_b = calibrate.matching_sets(T)
+        ys, Wd = np.asarray(y[:n_match_tokens], np.float64), np.asarray(W, np.float64)
+        rows_ = np.arange(pos_a.size) if rows is None else np.asarray(rows, np.int64)
+        best_j, best_d = np.empty(rows_.size, np.int64), np.empty(rows_.size)
+        for k, i in enumerate(rows_):
+            c = chan_of[pos_a[i]]
+            dx = ((ys[:, chan_of[pos_b]].T - ys[:, c][None, :]) ** 2).sum(1)
+            dw = ((Wd[chan_of[pos_b]] - Wd[c][None, :]) ** 2).sum(1) if use_weights else 1.0
+            d = (0.25 if keep_quarter else 1.0) * dx * dw
+            j = int(np.flatnonzero(d == d.min())[-1]) if ties_high else int(d.argmin())
+            best_j[k], best_d[k] = j, d[j]
+        return best_j, best_d, pos_a, pos_b
+    return planted
+
+
+def _sets_with_sub_channels(T):
+    T = np.asarray(T, np.int64)
+    chan_of = np.repeat(np.arange(T.size), T)
+    return chan_of, np.arange(0, chan_of.size, 2), np.arange(1, chan_of.size, 2)
+
+
+def _select_longest(best_d, best_j, pos_a, pos_b, r):
+    r = min(int(r), pos_a.size)
+    pick = np.sort(np.argsort(-np.asarray(best_d), kind="stable")[:r])
+    return (pos_a[pick] // 2).astype(np.int32), ((pos_b[np.asarray(best_j)[pick]] - 1) // 2).astype(np.int32)
+
+
+def _grid_from_zero(absmax, P):
+    m = np.asarray(absmax, np.float32).astype(np.float64)
+    return [float(np.float32(m.min() + (p / P) * (m.max() - m.min()))) for p in range(0, P)]
+
+
+MATCHING_CASES = [
+    ("Eq. (5): second term with the wrong sign", "pair_distance", _distance_second_term_sign,
+     [tm.test_distance_is_the_output_error_of_merging, tm.test_distance_properties]),
+    ("Eq. (5): the factor 1/4 dropped", "nearest_by_eq5", _nearest(None, keep_quarter=False),
+     [tm.test_nearest_by_eq5_against_brute_force, tm.test_matching_by_hand]),
+    ("matching on activations only", "nearest_by_eq5", _nearest(None, use_weights=False),
+     [tm.test_nearest_by_eq5_against_brute_force, tm.test_matching_by_hand]),
+    ("sub-channels of split channels take part", "matching_sets", _sets_with_sub_channels,
+     [tm.test_nearest_by_eq5_against_brute_force]),
+    ("the r longest edges are merged", "select_edges", _select_longest, [tm.test_matching_by_hand]),
+    ("theta grid starts at min(m)", "theta_grid", _grid_from_zero, [tm.test_theta_grid_is_algorithm_1]),
+]
+
+
+@pytest.mark.parametrize("what,name,planted,pins", MATCHING_CASES, ids=[c[0] for c in MATCHING_CASES])
+def test_a_planted_matching_mistake_fails_a_pin(oracle, monkeypatch, what, name, planted, pins):
+    import inspect
+    from oracle import calibrate
+
+    def run(pin):
+        return pin(oracle) if inspect.signature(pin).parameters else pin()
+
+    for pin in pins:
+        run(pin)
+    monkeypatch.setattr(calibrate, name, planted)
+    caught = 0
+    for pin in pins:
+        try:
+            run(pin)
         except AssertionError:
             caught += 1
     assert caught > 0, f"no pin noticed: {what}"
