@@ -76,6 +76,12 @@ def bench_matching(args, w, norm, dev):
     best_j = torch.empty(nA, dtype=torch.int32, device=dev)
     best_d = torch.empty(nA, dtype=torch.float64, device=dev)
     ws = torch.empty(b.qllm_match_workspace_bytes(nA, nB), dtype=torch.uint8, device=dev)
+    if args.calibration_copy:      # a device copy of known size, for scaling the HBM counters of a profiler run
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     steps, warmup = min(args.steps, 20), min(args.warmup, 3)
     for _ in range(warmup):
         b.qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, ws)
@@ -99,7 +105,7 @@ def bench_matching(args, w, norm, dev):
                    "set_A": nA, "set_B": nB, "split_channels": int((T > 1).sum()), "pairs": nA * nB},
         "roofline": {"kernel": "match_nearest_kernel (+ match_norms_kernel)", "bound": "mfma", "achieved": flops / t_kernel / 1e12,
                      "peak": 78.6, "unit": "TFLOP/s", "frac": flops / t_kernel / 1e12 / 78.6,
-                     "avg_launch_us": t_kernel * 1e6, "traffic": None},
+                     "avg_launch_us": t_kernel * 1e6, "traffic": read_traffic(w.name + "_match").get("match_nearest")},
     }
     if not args.no_cpu_baseline:
         from oracle import calibrate as ocal
