@@ -35,6 +35,11 @@ struct MatchArgs {
     const double *norms; // workspace: |x|^2 of A members [nA], |W|^2 of A [nA], |x|^2 of B [nB], |W|^2 of B [nB]
     int32_t *best_j;
     double *best_d;
+    // the members of set B are dealt out to `splits` workgroups per tile of A; each writes its own
+    // minimum here ([splits][nA]) and match_combine_kernel takes the minimum of those
+    int32_t splits;
+    double *part_d;
+    int32_t *part_j;
 };
 
 // ---- squared norms of every set member's activation column and weight row, in double
@@ -180,6 +185,7 @@ __device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca,
 // A stage holds 192 rows (64 of the A tile, 128 of the B tile) of 32 floats; a wave load covers 8 rows;
 // the 16-byte chunk c of row R sits at position c ^ ((R >> 1) & 7), chosen on the global side (which
 // chunk a lane fetches), so that the 64 lanes of an operand read fall on 64 different banks.
+constexpr int MAX_SPLITS = 8;
 constexpr int STAGE_F = (TA + TB) * KT, NSTAGE = 4;                 // floats per stage (24 KB), stages
 constexpr int WAIT_VM12_LGKM0 = 12 | (7 << 4) | (0 << 8);          // s_waitcnt vmcnt(12) lgkmcnt(0)
 constexpr int WAIT_VM0_ONLY = 0 | (7 << 4) | (15 << 8);            // s_waitcnt vmcnt(0)
@@ -251,7 +257,17 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
     __shared__ int32_t fin_j[THREADS / 64][TA];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int a0 = blockIdx.x * TA;
+    // Workgroup number -> (tile of A, split of B).  Workgroups are handed to the eight XCDs round robin
+    // and each XCD has its own L2: the `splits` workgroups that share a tile of A (and sweep the same
+    // 64 weight rows, each against its own part of B) get numbers that are equal modulo 8, so that
+    // they run side by side on one XCD and the rows come from HBM once for all of them.
+    const int group = blockIdx.x / (8 * g.splits), in_group = blockIdx.x % (8 * g.splits);
+    const int a_tile = group * 8 + (in_group & 7), split = in_group >> 3;
+    const int n_a_tiles = (g.nA + TA - 1) / TA, n_b_tiles = (g.nB + TB - 1) / TB;
+    if (a_tile >= n_a_tiles) return; // the last group of eight may be short; whole workgroups leave, before any barrier
+    const int a0 = a_tile * TA;
+    const int b_begin = (int)((int64_t)n_b_tiles * split / g.splits) * TB;
+    const int b_end = min(g.nB, (int)((int64_t)n_b_tiles * (split + 1) / g.splits) * TB);
     if (tid < TA) {
         const int m = min(a0 + tid, g.nA - 1); // past the end: the last member again, its result is dropped
         ca[tid] = g.chan_a[m];
@@ -270,7 +286,7 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
             best_j[ti][r] = 0x7fffffff;
         }
 
-    for (int b0 = 0; b0 < g.nB; b0 += TB) {
+    for (int b0 = b_begin; b0 < b_end; b0 += TB) {
         __syncthreads(); // everybody is done with the previous tile's cb / norms
         if (tid < TB) {
             const int m = min(b0 + tid, g.nB - 1);
@@ -342,9 +358,27 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
                 d = fin_d[w][tid];
                 j = fin_j[w][tid];
             }
-        g.best_d[a0 + tid] = d;
-        g.best_j[a0 + tid] = j;
+        g.part_d[(int64_t)split * g.nA + a0 + tid] = d; // a split without members of B leaves (inf, INT_MAX)
+        g.part_j[(int64_t)split * g.nA + a0 + tid] = j;
     }
+}
+
+// minimum over the splits; their parts of B ascend with the split number, so ties go to the lower split
+__global__ __launch_bounds__(THREADS) void match_combine_kernel(const MatchArgs g)
+{
+    const int64_t i = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+    if (i >= g.nA) return;
+    double d = g.part_d[i];
+    int32_t j = g.part_j[i];
+    for (int s = 1; s < g.splits; ++s) {
+        const double ds = g.part_d[(int64_t)s * g.nA + i];
+        if (ds < d) {
+            d = ds;
+            j = g.part_j[(int64_t)s * g.nA + i];
+        }
+    }
+    g.best_d[i] = d;
+    g.best_j[i] = j;
 }
 
 } // namespace
@@ -352,7 +386,8 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
 extern "C" int64_t qllm_match_workspace_bytes(int64_t nA, int64_t nB)
 {
     if (nA < 0 || nB < 0) return QLLM_ERR_SHAPE;
-    return 2 * (nA + nB) * (int64_t)sizeof(double);
+    // squared norms (two per member), and a (distance, index) pair per member of A and split of B
+    return 2 * (nA + nB) * (int64_t)sizeof(double) + MAX_SPLITS * nA * (int64_t)(sizeof(double) + sizeof(int32_t));
 }
 
 extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, const float *W, int64_t C, int64_t O,
@@ -373,6 +408,10 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     g.chan_a = chan_a; g.chan_b = chan_b;
     g.norms = static_cast<const double *>(workspace);
     g.best_j = best_j; g.best_d = best_d;
+    const int64_t n_b_tiles = (nB + TB - 1) / TB;
+    g.splits = (int32_t)(n_b_tiles < MAX_SPLITS ? n_b_tiles : MAX_SPLITS);
+    g.part_d = static_cast<double *>(workspace) + 2 * (nA + nB);
+    g.part_j = reinterpret_cast<int32_t *>(g.part_d + (int64_t)MAX_SPLITS * nA);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
     hipLaunchKernelGGL(match_norms_kernel, dim3((unsigned)(nA + nB)), dim3(THREADS), 0, stream, g,
@@ -397,10 +436,12 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
             raised[mode] = true;
         }
     }
-    const dim3 grid((unsigned)((nA + TA - 1) / TA));
+    const int64_t n_a_tiles = (nA + TA - 1) / TA;
+    const dim3 grid((unsigned)((n_a_tiles + 7) / 8 * 8 * g.splits));
     if (mode == 2) hipLaunchKernelGGL(match_nearest_kernel<2>, grid, dim3(THREADS), TILE_LDS, stream, g);
     else if (mode == 1) hipLaunchKernelGGL(match_nearest_kernel<1>, grid, dim3(THREADS), TILE_LDS, stream, g);
     else hipLaunchKernelGGL(match_nearest_kernel<0>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    hipLaunchKernelGGL(match_combine_kernel, dim3((unsigned)((nA + THREADS - 1) / THREADS)), dim3(THREADS), 0, stream, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         qllm_note_hip_error("channel matching: launch", hipGetErrorName(e));
