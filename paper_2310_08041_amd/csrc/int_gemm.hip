@@ -483,95 +483,103 @@ __device__ __forceinline__ v4i nib_hi(v4u p) { return (v4i)((p >> 4) & 0x0f0f0f0
 __device__ __forceinline__ int place16(int r) { return ((r & 2) << 2) | ((r & 8) >> 1) | ((r & 1) << 1) | ((r & 4) >> 2); }
 __device__ __forceinline__ int row_at16(int p) { return ((p & 2) >> 1) | ((p & 8) >> 2) | ((p & 1) << 2) | ((p & 4) << 1); }
 
-template <typename YT>
-__global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs g)
+// MI x NJ matrix-core tiles per wave: 8 x 4 (a 256 x 256 tile of Y per workgroup, the shape for many
+// tokens) or 4 x 2 (128 x 128: four times as many workgroups, two of which share a CU, for shapes
+// whose 256 x 256 tiles would leave most of the chip idle).
+template <typename YT, int MI, int NJ>
+__global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void int_gemm_w4a4_kernel(const GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int TM = 2 * MI * 16, TN = 4 * NJ * 16;     // the workgroup's tile of Y: 2 x 4 waves
+    constexpr int STAGE = (TM + TN) * PROWB;              // bytes of one buffer of the ring
+    constexpr int BLOCKS = (TM + TN) / 16, NLOAD = BLOCKS / 8; // 16-row blocks per K-tile; loads per wave and K-tile
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3; // wave tile: 128 tokens x 64 features
-    const int n0 = blockIdx.y * LBM, o0 = blockIdx.x * LBN;
+    const int wm = wave >> 2, wn = wave & 3; // wave tile: 16 MI tokens x 16 NJ features
+    const int n0 = blockIdx.y * TM, o0 = blockIdx.x * TN;
 
-    // fetch assignment: lane t fills the t-th 16 bytes of each half (128 rows) of an operand's buffer,
-    // that is piece f_piece of row f_row (+ 128)
-    const int f_row = ((tid >> 2) & ~15) | row_at16((tid >> 2) & 15), f_piece = (tid & 3) ^ (f_row & 3);
-    const uint8_t *a_src[2], *w_src[2];
+    // fetch assignment: wave w brings in the 16-row blocks w, w + 8, .. of the buffer (the tile's token
+    // rows first, then its feature rows); lane l fills the l-th 16 bytes of a block, that is piece
+    // f_piece of the block's row f_row
+    const int f_row = row_at16(lane >> 2), f_piece = (lane & 3) ^ (f_row & 3);
+    const uint8_t *src[NLOAD];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) { // past the edge: re-read the last row
-        a_src[h] = g.a_codes + (int64_t)min(n0 + h * 128 + f_row, g.N - 1) * g.a_row_bytes + f_piece * 16;
-        w_src[h] = g.w_codes + (int64_t)min(o0 + h * 128 + f_row, g.O - 1) * g.w_row_bytes + f_piece * 16;
+    for (int t = 0; t < NLOAD; ++t) { // past the edge: re-read the last row
+        const int blk = wave + 8 * t;
+        src[t] = blk < TM / 16
+                     ? g.a_codes + (int64_t)min(n0 + blk * 16 + f_row, g.N - 1) * g.a_row_bytes + f_piece * 16
+                     : g.w_codes + (int64_t)min(o0 + (blk - TM / 16) * 16 + f_row, g.O - 1) * g.w_row_bytes + f_piece * 16;
     }
 
     // operand reads: lane (r, q) takes piece q of row r of a block of 16 rows
     const int r = lane & 15, q = lane >> 4;
-    const int a_off = (wm * 128 + place16(r)) * PROWB + ((q ^ (r & 3)) << 4);      // + i * 16 rows
-    const int w_off = (LBM + wn * 64 + place16(r)) * PROWB + ((q ^ (r & 3)) << 4); // + j * 16 rows
+    const int a_off = (wm * 16 * MI + place16(r)) * PROWB + ((q ^ (r & 3)) << 4);      // + i * 16 rows
+    const int w_off = (TM + wn * 16 * NJ + place16(r)) * PROWB + ((q ^ (r & 3)) << 4); // + j * 16 rows
 
-    v4i acc[8][4];
+    v4i acc[MI][NJ];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+        for (int j = 0; j < NJ; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
     // Refill: 16-byte global loads that write LDS directly (lane l of a wave lands at the wave's LDS
-    // base + 16 l, which is why the stores' order above is the lanes' order): no staging registers, no
-    // LDS store instructions.  Wave w brings in rows 16 w .. 16 w + 15 of each half of each operand,
-    // four loads per K-tile, issued three K-tiles ahead into a ring of four buffers.  Loads complete
-    // in order, so "at most eight outstanding" before the barrier means the next K-tile has landed.
+    // base + 16 l, which is why a block's order above is the lanes' order): no staging registers, no
+    // LDS store instructions; NLOAD loads per wave and K-tile, issued three K-tiles ahead into a ring
+    // of four buffers.  Loads complete in order, so "at most 2 NLOAD outstanding" before the barrier
+    // means the next K-tile has landed.
+    constexpr int WAIT_LANDED = 2 * NLOAD | (7 << 4) | (15 << 8);    // s_waitcnt vmcnt(2 NLOAD)
+    constexpr int WAIT_LANDED_LGKM0 = 2 * NLOAD | (7 << 4) | (0 << 8); // ... and lgkmcnt(0)
     const int n_kt = g.Kpad / PKT;
     auto fetch = [&](int kt) { // K-tile kt (clamped to the last one) -> buffer kt & 3
         const int ktc = min(kt, n_kt - 1);
-        uint8_t *dst = lds + (kt & (NBUF - 1)) * PBUF + wave * 16 * PROWB;
+        uint8_t *dst = lds + (kt & (NBUF - 1)) * STAGE + wave * 16 * PROWB;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(a_src[h] + (int64_t)ktc * PROWB),
-                                             (__attribute__((address_space(3))) void *)(dst + h * 128 * PROWB), 16, 0, 0);
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[h] + (int64_t)ktc * PROWB),
-                                             (__attribute__((address_space(3))) void *)(dst + (LBM + h * 128) * PROWB), 16, 0, 0);
+        for (int t = 0; t < NLOAD; ++t)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[t] + (int64_t)ktc * PROWB),
+                                             (__attribute__((address_space(3))) void *)(dst + t * 8 * 16 * PROWB), 16, 0, 0);
     };
     fetch(0);
     fetch(1);
     fetch(2);
-    __builtin_amdgcn_s_waitcnt(WAIT_VM8);
+    __builtin_amdgcn_s_waitcnt(WAIT_LANDED);
     __syncthreads();
 
-    constexpr int GROUPS = 16, ROT = 5, RING = 4, AHEAD = 3;
-    v4u ap[RING], wp[4];
-    v4i fa[2], fw[2][4];
+    constexpr int GROUPS = 2 * MI, ROT = 5, RING = 4, AHEAD = 3;
+    static_assert(MI % RING == 0 && ROT == 2 * AHEAD - 1 && ROT < GROUPS && NJ % 2 == 0, "group plan");
+    v4u ap[RING], wp[NJ];
+    v4i fa[2], fw[2][NJ];
 #pragma unroll
     for (int k = 0; k < RING; ++k) ap[k] = v4u{0, 0, 0, 0};
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fw[0][j] = fw[1][j] = v4i{0, 0, 0, 0};
+    for (int j = 0; j < NJ; ++j) fw[0][j] = fw[1][j] = v4i{0, 0, 0, 0};
     fa[0] = fa[1] = v4i{0, 0, 0, 0};
 
     for (int kt = 0; kt < n_kt; ++kt) {
-        const uint8_t *cur = lds + (kt & (NBUF - 1)) * PBUF;
+        const uint8_t *cur = lds + (kt & (NBUF - 1)) * STAGE;
 #pragma unroll
         for (int u = 0; u < GROUPS; ++u) {
             const int s = (u + GROUPS - ROT) % GROUPS, i = s >> 1, m = s & 1;
             // the K-tile three ahead, into the buffer whose last reader passed the previous barrier
-            if (s == 2) fetch(kt + 3);
-            // the group's four operations
+            if (s == 0) fetch(kt + 3);
+            // the group's operations
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[m][j], fa[m], acc[i][j], 0, 0, 0);
             // splits for the next group: the other nibble of this row block, or the next block's low one
             if (m == 0) fa[1] = nib_hi(ap[i % RING]);
             else fa[0] = nib_lo(ap[(i + 1) % RING]);
             // feature side of the new K-tile: low nibbles once the last low group of the old one is
-            // through (group 14), high nibbles after its last high group (15)
+            // through (the last but one), high nibbles after its last high group (the last)
             if (s == GROUPS - 1) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) fw[0][j] = nib_lo(wp[j]);
+                for (int j = 0; j < NJ; ++j) fw[0][j] = nib_lo(wp[j]);
             }
             if (s == 0) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) fw[1][j] = nib_hi(wp[j]);
+                for (int j = 0; j < NJ; ++j) fw[1][j] = nib_hi(wp[j]);
             }
             if (u == GROUPS - 1) {
                 // next K-tile landed (this wave's share; the barrier adds the others'), own reads done
-                __builtin_amdgcn_s_waitcnt(WAIT_VM8_LGKM0);
+                __builtin_amdgcn_s_waitcnt(WAIT_LANDED_LGKM0);
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
@@ -581,11 +589,11 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs 
             // feature rows of this iteration's K-tile in its first two groups.  All of them read
             // this iteration's K-tile: the first group of the iteration is the first to look ahead.
             __builtin_amdgcn_sched_barrier(0);
-            if (m == 1) ap[(i + AHEAD) % RING] = *reinterpret_cast<const v4u *>(cur + a_off + ((i + AHEAD) & 7) * 16 * PROWB);
+            if (m == 1) ap[(i + AHEAD) % RING] = *reinterpret_cast<const v4u *>(cur + a_off + ((i + AHEAD) % MI) * 16 * PROWB);
             if (u < 2) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    wp[2 * u + h] = *reinterpret_cast<const v4u *>(cur + w_off + (2 * u + h) * 16 * PROWB);
+                for (int h = 0; h < NJ / 2; ++h)
+                    wp[(NJ / 2) * u + h] = *reinterpret_cast<const v4u *>(cur + w_off + ((NJ / 2) * u + h) * 16 * PROWB);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -597,13 +605,13 @@ __global__ __launch_bounds__(LTHREADS) void int_gemm_w4a4_kernel(const GemmArgs 
     for (int s = GROUPS - ROT; s < GROUPS; ++s) {
         const int i = s >> 1, m = s & 1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[m][j], fa[m], acc[i][j], 0, 0, 0);
         if (m == 0) fa[1] = nib_hi(ap[i % RING]);
-        else if (i < 7) fa[0] = nib_lo(ap[(i + 1) % RING]);
+        else if (i < MI - 1) fa[0] = nib_lo(ap[(i + 1) % RING]);
     }
 
-    finish_wave_tile<4, 4, YT, 8, 4>(g, acc, n0 + wm * 128, o0 + wn * 64, lane);
+    finish_wave_tile<4, 4, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane);
 }
 
 // ---- few tokens (decode): the weights are read once from HBM and that is the whole cost.  A
@@ -781,12 +789,24 @@ int32_t launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const GemmArg
 template <int ABITS, int WBITS>
 int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
+    if constexpr (ABITS == 4 && WBITS == 4) {
+        // 4-bit codes on both sides, more than 32 tokens: 256 x 256 tiles when they fill at least three
+        // quarters of the CUs, else 128 x 128 tiles (four times the workgroups, two per CU)
+        const int64_t big_tiles = (int64_t)((g.O + LBN - 1) / LBN) * ((g.N + LBM - 1) / LBM);
+        if (g.N > 32 && (g.N <= 128 || big_tiles < 192)) {
+            const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
+            constexpr size_t lds = (size_t)NBUF * 256 * PROWB;
+            if (y_dtype == QLLM_F32)
+                return launch_kernel(int_gemm_w4a4_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+            return launch_kernel(int_gemm_w4a4_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+        }
+    }
     if (g.N > 128) { // enough tokens to fill 256-row tiles
         const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
         if constexpr (ABITS == 4 && WBITS == 4) {
             if (y_dtype == QLLM_F32)
-                return launch_kernel(int_gemm_w4a4_kernel<float>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
-            return launch_kernel(int_gemm_w4a4_kernel<uint16_t>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
+                return launch_kernel(int_gemm_w4a4_kernel<float, 8, 4>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
+            return launch_kernel(int_gemm_w4a4_kernel<uint16_t, 8, 4>, grid, dim3(LTHREADS), NBUF * PBUF, g, stream);
         } else {
             if (y_dtype == QLLM_F32)
                 return launch_kernel(int_gemm_big_kernel<ABITS, WBITS, float>, grid, dim3(LTHREADS), 2 * LBUF, g, stream);

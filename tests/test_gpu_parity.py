@@ -295,6 +295,20 @@ def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
     check_y(oracle, y, ref_y, y_dtype)
 
 
+@pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
+def test_gemm_large_tiles_ragged(oracle, b, y_dtype):
+    """W4A4 with enough 256 x 256 tiles (9 x 22) for the large-tile kernel to be chosen, ragged in both
+    directions (one token and 124 features past a tile), two K-tiles only."""
+    N, K, O = 2049, 256, 5500
+    rng = np.random.default_rng(N + O)
+    a, w, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, 4, 4)
+    y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 4, 4, y_dtype)
+    ref_acc = oracle.int_gemm(a, w)
+    assert np.array_equal(acc.cpu().numpy(), ref_acc)
+    ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
+    check_y(oracle, y, ref_y, y_dtype)
+
+
 def test_gemm_extreme_codes(oracle, b):
     """All codes at their maximum: the largest accumulators the shapes allow."""
     for bits, K in [(4, 28672), (6, 8192), (8, 28672)]:
