@@ -790,10 +790,15 @@ template <int ABITS, int WBITS>
 int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     if constexpr (ABITS == 4 && WBITS == 4) {
-        // 4-bit codes on both sides, more than 32 tokens: 256 x 256 tiles when they fill at least three
-        // quarters of the CUs, else 128 x 128 tiles (four times the workgroups, two per CU)
+        // 4-bit codes on both sides, more than 32 tokens.  256 x 256 tiles run one workgroup per CU, 128 x 128
+        // tiles two, at about three quarters of the large tile's rate per matrix-core operation: the
+        // small tile is taken where it fills the chip's rounds that much better (few tiles, or a last
+        // round that is mostly empty: 384 large tiles are 1.5 rounds, 1536 small ones 3).
         const int64_t big_tiles = (int64_t)((g.O + LBN - 1) / LBN) * ((g.N + LBM - 1) / LBM);
-        if (g.N > 32 && (g.N <= 128 || big_tiles < 192)) {
+        const int64_t small_tiles = (int64_t)((g.O + 127) / 128) * ((g.N + 127) / 128);
+        const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
+        const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
+        if (g.N > 32 && (g.N <= 128 || big_fill < 0.78 * small_fill)) {
             const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
             constexpr size_t lds = (size_t)NBUF * 256 * PROWB;
             if (y_dtype == QLLM_F32)
