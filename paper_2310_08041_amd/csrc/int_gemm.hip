@@ -42,6 +42,8 @@ struct GemmArgs {
     void *y;
     int64_t ldy;
     int32_t *acc_dump;
+    int32_t *partial; // [splits][N][O] raw accumulators when K is split over workgroups, else unused
+    int32_t splits;
 };
 
 template <int BITS>
@@ -486,7 +488,10 @@ __device__ __forceinline__ int row_at16(int p) { return ((p & 2) >> 1) | ((p & 8
 // MI x NJ matrix-core tiles per wave: 8 x 4 (a 256 x 256 tile of Y per workgroup, the shape for many
 // tokens) or 4 x 2 (128 x 128: four times as many workgroups, two of which share a CU, for shapes
 // whose 256 x 256 tiles would leave most of the chip idle).
-template <typename YT, int MI, int NJ>
+// SPLIT: K is dealt out to gridDim.z workgroups per tile of Y (shapes with so few tiles that most CUs
+// would idle through a long K loop); each writes its raw accumulators to g.partial and
+// splitk_finish_kernel adds them up and does the epilogue.
+template <typename YT, int MI, int NJ, bool SPLIT = false>
 __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void int_gemm_w4a4_kernel(const GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -528,9 +533,11 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void int_gemm_w4a4_kerne
     // means the next K-tile has landed.
     constexpr int WAIT_LANDED = 2 * NLOAD | (7 << 4) | (15 << 8);    // s_waitcnt vmcnt(2 NLOAD)
     constexpr int WAIT_LANDED_LGKM0 = 2 * NLOAD | (7 << 4) | (0 << 8); // ... and lgkmcnt(0)
-    const int n_kt = g.Kpad / PKT;
-    auto fetch = [&](int kt) { // K-tile kt (clamped to the last one) -> buffer kt & 3
-        const int ktc = min(kt, n_kt - 1);
+    const int all_kt = g.Kpad / PKT;
+    const int kt_first = SPLIT ? (int)((int64_t)all_kt * blockIdx.z / gridDim.z) : 0;
+    const int n_kt = (SPLIT ? (int)((int64_t)all_kt * (blockIdx.z + 1) / gridDim.z) : all_kt) - kt_first; // this workgroup's K-tiles
+    auto fetch = [&](int kt) { // its K-tile kt (clamped to the last one) -> buffer kt & 3
+        const int ktc = kt_first + min(kt, n_kt - 1);
         uint8_t *dst = lds + (kt & (NBUF - 1)) * STAGE + wave * 16 * PROWB;
 #pragma unroll
         for (int t = 0; t < NLOAD; ++t)
@@ -611,7 +618,49 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void int_gemm_w4a4_kerne
         else if (i < MI - 1) fa[0] = nib_lo(ap[(i + 1) % RING]);
     }
 
-    finish_wave_tile<4, 4, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane);
+    if constexpr (SPLIT) {
+        // raw accumulators of this part of K: token n, four consecutive features per lane and tile
+        int32_t *part = g.partial + (int64_t)blockIdx.z * g.N * g.O;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int n = n0 + wm * 16 * MI + i * 16 + (lane & 15);
+            if (n >= g.N) continue;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int o = o0 + wn * 16 * NJ + j * 16 + 4 * (lane >> 4);
+                int32_t *p = part + (int64_t)n * g.O + o;
+                if (o + 3 < g.O && (g.O & 3) == 0) {
+                    *reinterpret_cast<v4i *>(p) = acc[i][j];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (o + e < g.O) p[e] = acc[i][j][e];
+                }
+            }
+        }
+    } else {
+        finish_wave_tile<4, 4, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane);
+    }
+}
+
+// Sum of the parts of a split K and the dequantising epilogue (4-bit codes on both sides: no offsets),
+// one output per lane; the bracket in 64-bit arithmetic, which gives the same float as the narrow form.
+template <typename YT>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const GemmArgs g)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)g.N * g.O) return;
+    const int n = (int)(idx / g.O), o = (int)(idx % g.O);
+    int32_t raw = 0; // the true accumulator fits int32 (checked by the launcher), so wrapping sums are exact
+    for (int z = 0; z < g.splits; ++z) raw += g.partial[(int64_t)z * g.N * g.O + idx];
+    const int64_t bx = g.bx[n], bw = g.bw[o];
+    const int64_t t = (int64_t)raw - bx * g.cs[o] - bw * g.rs[n] + (int64_t)g.K * bx * bw;
+    float v = (float)t;
+    v = v * g.ax[n];
+    v = v * g.aw[o];
+    if constexpr (sizeof(YT) == 4) reinterpret_cast<float *>(g.y)[(int64_t)n * g.ldy + o] = v;
+    else reinterpret_cast<uint16_t *>(g.y)[(int64_t)n * g.ldy + o] = f32_to_bf16_rne(v);
+    if (g.acc_dump) g.acc_dump[idx] = raw;
 }
 
 // ---- few tokens (decode): the weights are read once from HBM and that is the whole cost.  A
@@ -799,8 +848,15 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
         const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
         const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
         if (g.N > 32 && (g.N <= 128 || big_fill < 0.78 * small_fill)) {
-            const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
+            const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128), (unsigned)(g.splits > 1 ? g.splits : 1));
             constexpr size_t lds = (size_t)NBUF * 256 * PROWB;
+            if (g.splits > 1) {
+                const int32_t st = launch_kernel(int_gemm_w4a4_kernel<float, 4, 2, true>, grid, dim3(LTHREADS), lds, g, stream);
+                if (st != QLLM_OK) return st;
+                const dim3 fgrid((unsigned)(((int64_t)g.N * g.O + 255) / 256));
+                if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float>, fgrid, dim3(256), 0, g, stream);
+                return launch_kernel(splitk_finish_kernel<uint16_t>, fgrid, dim3(256), 0, g, stream);
+            }
             if (y_dtype == QLLM_F32)
                 return launch_kernel(int_gemm_w4a4_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
             return launch_kernel(int_gemm_w4a4_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
@@ -846,20 +902,36 @@ int32_t small_zero_bound(int64_t K, int32_t a_bits, int32_t w_bits)
     return (int32_t)(L > (1 << 20) ? (1 << 20) : L);
 }
 
+// Into how many parts K is split (1: not at all).  Only 4-bit codes with 128 x 128 tiles that leave
+// most CUs without a workgroup (up to 64 tiles: four parts, up to 128: two; beyond that the parts'
+// accumulators, written and read back, cost what the shorter K loop gains); every part keeps at least
+// eight K-tiles.
+int32_t k_splits(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    if (a_bits != 4 || N <= 32) return 1;
+    const int64_t tiles = ((O + 127) / 128) * ((N + 127) / 128);
+    const int64_t n_kt = (K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / PKT;
+    if (tiles > 128) return 1;
+    int64_t s = 256 / tiles;
+    if (s > 4) s = 4;
+    if (s > n_kt / 8) s = n_kt / 8;
+    return s < 2 ? 1 : (int32_t)s;
+}
+
 } // namespace
 
 extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
 {
     if (a_bits != 4 && a_bits != 6 && a_bits != 8) return QLLM_ERR_BITS;
     if (N < 0 || K <= 0 || O <= 0) return QLLM_ERR_SHAPE;
-    return 0;
+    const int32_t s = k_splits(N, K, O, a_bits);
+    return s > 1 ? (int64_t)s * N * O * (int64_t)sizeof(int32_t) : 0;
 }
 
 extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
                                  int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
                                  int64_t workspace_bytes, void *hip_stream)
 {
-    (void)workspace;
     if (!a || !w || !y) return QLLM_ERR_NULL;
     if (!a->codes || !a->scale || !a->zero || !a->rowsum) return QLLM_ERR_NULL;
     if (!w->codes || !w->scale || !w->zero || !w->colsum) return QLLM_ERR_NULL;
@@ -887,6 +959,9 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     g.N = (int32_t)N; g.O = (int32_t)w->O; g.K = (int32_t)w->K;
     g.Kpad = (int32_t)((w->K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD);
     g.y = y; g.ldy = ldy; g.acc_dump = acc_dump;
+    g.splits = (a_bits == 4 && wb == 4) ? k_splits(N, w->K, w->O, a_bits) : 1;
+    g.partial = static_cast<int32_t *>(workspace);
+    if (g.splits > 1 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u))) return workspace ? QLLM_ERR_ALIGN : QLLM_ERR_WORKSPACE;
     g.small_zero = small_zero_bound(w->K, a_bits, wb);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (a_bits == 4) return launch<4, 4>(g, y_dtype, stream);

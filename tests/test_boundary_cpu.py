@@ -47,6 +47,11 @@ def test_packed_row_bytes_and_workspace():
         b.qllm_packed_row_bytes(0, 4)
     ws = b.qllm_workspace_bytes(2048, 28672, 8192, 4)
     assert ws >= 2048 * 14336 + 3 * 2048 * 4 and ws % 256 == 0
+    # the GEMM needs scratch only where it splits K over workgroups: 4-bit codes, few tiles, a long K
+    assert b.qllm_gemm_workspace_bytes(2048, 28672, 8192, 4) == 0 and b.qllm_gemm_workspace_bytes(16, 8192, 8192, 4) == 0
+    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 4) == 4 * 128 * 8192 * 4
+    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 6) == 0 and b.qllm_gemm_workspace_bytes(128, 512, 8192, 4) == 0
+    assert b.qllm_workspace_bytes(128, 8192, 8192, 4) >= 128 * 4096 + 4 * 128 * 8192 * 4
 
 
 def _structs():

@@ -262,7 +262,9 @@ def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True):
     dw = b.DeviceWeight(b.qllm_pack_codes_host(w, w_bits), aw, bw, w.astype(np.int64).sum(1).astype(np.int32), K, w_bits)
     y = torch.full((N, O), float("nan"), dtype=torch.float32 if y_dtype == "f32" else torch.bfloat16, device="cuda")
     acc = torch.full((N, O), -1, dtype=torch.int32, device="cuda") if dump else None
-    b.qllm_int_gemm(qa, dw, y, acc)
+    ws_bytes = b.qllm_gemm_workspace_bytes(N, K, O, a_bits)     # non-zero where K is split over workgroups
+    ws = torch.full((ws_bytes,), 0xCD, dtype=torch.uint8, device="cuda") if ws_bytes else None
+    b.qllm_int_gemm(qa, dw, y, acc, ws)
     torch.cuda.synchronize()
     return y, acc
 
@@ -283,7 +285,9 @@ def check_y(oracle, y, ref_f32, y_dtype):
                                    (257, 1030, 129), (64, 2048, 384),
                                    # 256-row tiles: two K-tiles only (the fetch ring runs past the end at once),
                                    # three ragged tiles each way, a long K with one row past a tile
-                                   (300, 200, 260), (513, 256, 513), (129, 5000, 257)])
+                                   (300, 200, 260), (513, 256, 513), (129, 5000, 257),
+                                   # K split over workgroups (few tiles, long K): 2 and 4 parts, ragged
+                                   (100, 2100, 250), (40, 4100, 130)])
 @pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
 def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
     rng = np.random.default_rng(N * 1000 + K + O + a_bits)
