@@ -135,8 +135,9 @@ int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, in
  *   a, a_bits   quantized activations [N, K]; a_bits must equal w->bits, or be 8 with w->bits 4.
  *   y           [N, ldy] y_dtype (fp32, or bf16 rounded to nearest even); ldy >= O in elements.
  *   acc_dump    NULL, or [N, O] int32 that receives the raw accumulators.
- *   workspace   scratch of at least qllm_gemm_workspace_bytes(N, w->K, w->O, a_bits) bytes (may be
- *               NULL when that is 0); contents undefined afterwards.
+ *   workspace   scratch of at least qllm_gemm_workspace_bytes(N, w->K, w->O, a_bits) bytes, 16-byte
+ *               aligned (may be NULL when that is 0: it is non-zero only where the sum over K is
+ *               split over workgroups); contents undefined afterwards.
  */
 int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
                       int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
