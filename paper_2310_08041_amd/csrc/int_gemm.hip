@@ -885,9 +885,13 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
         if (nt == 1) return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, uint16_t, 1>, grid, dim3(SK_THREADS), lds, g, stream);
         return launch_kernel(int_gemm_skinny_kernel<ABITS, WBITS, uint16_t, 2>, grid, dim3(SK_THREADS), lds, g, stream);
     }
-    const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
-    if (y_dtype == QLLM_F32) return launch_kernel(int_gemm_kernel<ABITS, WBITS, float>, grid, dim3(THREADS), 0, g, stream);
-    return launch_kernel(int_gemm_kernel<ABITS, WBITS, uint16_t>, grid, dim3(THREADS), 0, g, stream);
+    if constexpr (ABITS == 4 && WBITS == 4) {
+        return QLLM_ERR_SHAPE; // not reached: every 4-bit shape was placed above
+    } else { // 33..128 tokens, 6- or 8-bit codes
+        const dim3 grid((unsigned)((g.O + BN - 1) / BN), (unsigned)((g.N + BM - 1) / BM));
+        if (y_dtype == QLLM_F32) return launch_kernel(int_gemm_kernel<ABITS, WBITS, float>, grid, dim3(THREADS), 0, g, stream);
+        return launch_kernel(int_gemm_kernel<ABITS, WBITS, uint16_t>, grid, dim3(THREADS), 0, g, stream);
+    }
 }
 
 // Largest L such that |beta_x| < L and |beta_w| < L keep the epilogue inside narrow integers:
