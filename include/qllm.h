@@ -72,9 +72,9 @@ typedef struct {
     const int32_t *src;     /* [nnz] 0 <= src < C_in */
     const float *scale;     /* [nnz] */
     const int32_t *plan;    /* optional: device copy of the array qllm_plan_map_host makes from this very
-                               map (an index of it for the fused kernel: which groups of 8 output channels
-                               are plain shifted copies, the entries of all others, which inputs pass
-                               unscaled).  NULL: the kernel walks the CSR for every channel (much slower). */
+                               map (an index of it for the fused kernel: which output channels copy an input
+                               channel, which are computed, how groups of 8 are put together).  NULL: the
+                               kernel walks the CSR for every channel (much slower). */
     int32_t plan_head[QLLM_PLAN_HEAD]; /* host copy of the plan's first QLLM_PLAN_HEAD words (ignored with NULL) */
 } qllm_map;
 
@@ -211,28 +211,41 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
 /* Indexes a CSR map for the fused kernel (see qllm_map.plan).  Call once with plan == NULL to get
  * *plan_len (int32 words) and *n_general, then with plan pointing at that many words.  The plan
  * depends only on the map; upload it next to the CSR arrays and keep its first QLLM_PLAN_HEAD words
- * in qllm_map.plan_head.  Layout (int32 words; every part starts at a multiple of 4 words):
+ * in qllm_map.plan_head.
+ *
+ * The kernel quantizes every input channel where it sits and then moves CODES, so the plan sorts the
+ * output channels into three kinds:
+ *   copied    one entry with scale exactly 1: the channel's code is the code of its source channel;
+ *   computed  one entry with another scale (a sub-channel, Eq. 3) or two entries of equal scale (a merged
+ *             pair, Eq. 4): the value is formed from the sources and quantized on its own;
+ *   long      any other row (at most 64 entries): summed entry by entry, then as a computed channel.
+ * and the groups of 8 output channels into "plain" (8 copied channels with consecutive sources d .. d+7:
+ * one 8-code window of the input-order codes) and "composite" (anything else: a few windows, each masked
+ * to the channels it supplies, plus the codes of its computed and long channels).
+ *
+ * Layout (int32 words; every part starts at a multiple of 4 words, in this order):
  *   [0..15]  header: magic, version, C_in, C_out, n_work = groups of 8 output channels including the zero
- *            padding to 256 codes, n_general, n_chunks = ceil(C_in/8), n_long, n_pub, then the offsets of
- *            work, chunks, items, longs, then plan_len, n_mask, offset of masks
- *   work     [n_work]: kind << 28 | group << 15 | d.  kind 0 ("plain"): the 8 channels of the group are
- *            single-entry with scale exactly 1 and sources d, d+1, ..., d+7; kind 1: general group number d;
- *            kind 2: padding.  Sorted by kind, then by group
- *   chunks   [n_chunks]: bits 0..7: bit j set = input channel 8*chunk + j is a source of some plain group;
- *            bits 8..31: p if some general group reads a channel of this chunk (the kernel then stages
- *            the chunk's y at floats 8p .. 8p+7 of its on-chip table; p = 0 .. n_pub-1 in chunk order),
- *            0xffffff otherwise.  Float 8*n_pub of that table is a zero
- *   items    [n_general * 8][2]: for channel k of a general group {s0 | s1 << 16, scale}: one entry
- *            (s1 = 8*n_pub, the zero) or two entries of equal scale, s = staged position of the source
- *            channel; {-2, first | count << 24}: any other row (at most 64 entries), its entries are
- *            longs[first .. first + count); channels past C_out repeat the group's first channel
- *   longs    [n_long][4]: {s, dest, scale, pos | most << 8}: entry pos (0, 1, ...) of a row that is
- *            neither of the two short forms; dest = 8 * (general group number) + k on the row's last
- *            entry, -1 elsewhere.  The kernel gives entry e to lane e % 64 of a wavefront and adds a row up
- *            lane by lane, so the table holds padding entries {0, -1, 0.0f, 0 | most << 8} wherever a row
- *            would otherwise straddle a multiple of 64; n_long counts them; most = the largest pos among
- *            the (up to) 64 entries that share a wavefront
- *   masks    [n_mask]: the chunks words whose pass bits are neither all set nor all clear
+ *            padding to 256 codes, n_comp = composite groups (*n_general), n_chunks = ceil(C_in/8), n_long,
+ *            n_pub, n_spec, n_dest, n_segw, offset of chunks, plan_len, offset of spec, offset of longs
+ *   work     [n_work] at word 16: kind << 30 | group << 17 | field.  kind 0 (plain): field = d; kind 1
+ *            (composite): field = offset of the group's segment list inside `segs`; kind 2: padding (all
+ *            codes zero).  Sorted by kind, then by group
+ *   chunks   [n_chunks]: bits 0..7: bit j set = input channel 8*chunk + j is the source of some copied
+ *            channel; bits 8..31: p if some computed or long channel reads a channel of this chunk (the
+ *            kernel then stages the chunk's x at floats 8p .. 8p+7 of its on-chip table; p = 0 ..
+ *            n_pub-1 in chunk order), 0xffffff otherwise.  Float 8*n_pub of that table is a zero
+ *   spec     [n_spec][2]: a computed channel: {s0 | s1 << 16, scale}, s = staged position of the source
+ *            channel (s1 = 8*n_pub, the zero, for one entry)
+ *   dest     [n_dest]: where the code of computed channel i (i < n_spec) or of long row i - n_spec goes:
+ *            number of its composite group << 3 | position in the group
+ *   longs    [n_long][4]: {s, value slot or -1, scale, pos | most << 8}: entry pos (0, 1, ...) of a long row;
+ *            the row's last entry names its slot in `dest`, the others -1.  The kernel gives entry e to lane
+ *            e % 64 of a wavefront and adds a row up lane by lane, so the table holds padding entries
+ *            {0, -1, 0.0f, 0 | most << 8} wherever a row would otherwise straddle a multiple of 64; n_long
+ *            counts them; most = the largest pos among the (up to) 64 entries that share a wavefront
+ *   segs     [n_segw]: per composite group {count | number << 8, then count x {d, mask, 0}}: the group's
+ *            copied channels at positions k with bit k of mask set have sources d + k (d may be negative or
+ *            reach past C_in - 8: only the masked positions are real channels)
  * QLLM_ERR_MAP: malformed map, or a row of more than 64 entries (such a map runs without a plan).
  */
 int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,

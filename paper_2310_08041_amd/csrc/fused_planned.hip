@@ -32,6 +32,7 @@
 
 #include <stdint.h>
 
+#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -42,11 +43,9 @@ using namespace qllm_detail;
 
 namespace {
 
-// work-list entries (see qllm_plan_map_host): kind << 28 | group << 15 | d
-constexpr int KIND_PLAIN = 0, KIND_GENERAL = 1, KIND_PAD = 2, KIND_NONE = 3;
-constexpr int32_t WORK_NONE = KIND_NONE << 28;
-constexpr int32_t ITEM_LONG = -2; // first word of a plan item whose entries are in the table of long rows
-constexpr int32_t ITEM_SKIP = 0x7fc00001; // second word the kernel gives such an item in LDS (as a scale: a NaN, never a real one)
+// work-list entries (see qllm_plan_map_host): kind << 30 | group << 17 | field
+constexpr int KIND_PLAIN = 0, KIND_COMP = 1, KIND_PAD = 2, KIND_NONE = 3;
+constexpr int32_t WORK_NONE = (int32_t)(3u << 30);
 
 template <typename XT>
 struct Raw; // 8 input elements as they sit in memory
@@ -150,11 +149,11 @@ QLLM_DPP_FAMILY(dpp_min, float, "v_min_f32_dpp")
 QLLM_DPP_FAMILY(dpp_max, float, "v_max_f32_dpp")
 QLLM_DPP_FAMILY(dpp_add, int32_t, "v_add_u32_dpp")
 
-// value of the lane below (lane 0: zero) + p, across the whole wavefront
-__device__ __forceinline__ float below_plus(float acc, float p)
+// value of the lane below (lane 0: zero), across the whole wavefront
+__device__ __forceinline__ float below(float v)
 {
     float r;
-    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %2 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "=v"(r) : "v"(acc), "v"(p));
+    asm("s_nop 1\n\tv_mov_b32_dpp %0, %1 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "=v"(r) : "v"(v));
     return r;
 }
 
@@ -353,67 +352,165 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
     }
 }
 
-// GAM_REG: the lane's share of gamma stays in registers for the lifetime of the workgroup; otherwise it
-// is re-read (from L2) for every row, which frees 8 registers per chunk.
-template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, bool LAYER>
+// The row loop is software-pipelined over three barrier intervals, so that work bound by latency (LDS
+// round trips, cross-lane reductions, dependent scalar chains) has dense arithmetic of another step of
+// the path next to it in the same interval:
+//   interval 1   step a1 of row r, first half: widen the row (it was requested one row earlier), request
+//                row r + 1, x of the chunks that hold a source of a computed channel staged in LDS,
+//                partial sums of the row statistics; and the LAST step of row r - 1: its output groups are
+//                assembled from the packed words and stored.
+//   interval 2   rstd (mu) from the partial sums; y = norm(x) in registers; min/max; steps a2 + a3 for the
+//                computed channels, which normalise the staged x of their sources themselves (gamma and
+//                beta of the staged chunks sit in LDS for the lifetime of the workgroup), so that no
+//                barrier separates them from the rest of the row.
+//   interval 3   range (Eq. 2), codes of the lane's own chunks packed in input order, codes of the
+//                computed channels.
+// LayerNorm has one more barrier inside interval 2 (the mean has to be known before the squared
+// deviations are summed).
+//
+// Two kinds of lanes.  The first n_main lanes ("row lanes") own ITERS chunks of the row and as many plain
+// output groups: the regular, dense part.  The irregular part -- computed channels, long rows, composite
+// output groups -- is a few hundred items per row whose cost is LDS latency; it goes to up to two extra
+// wavefronts ("side lanes") when the workgroup has room for them, which also evens out the wavefronts
+// per SIMD (14 row wavefronts are 4 + 4 + 3 + 3).  Without room the row lanes do it as well.
+//
+// Input channels that no output channel copies (split channels, channels merged away or into) must stay
+// out of min/max, and their codes must not spill into their neighbours' bits.  The lane's own copy of
+// gamma holds a NaN for them: y is then a NaN, which min/max skip and which the clamp of the quantizer
+// turns into code 0, at no cost per row.
+//
+// NORM: QLLM_NORM_NONE / LAYER / RMS.  GAM_REG: the lane's share of gamma stays in registers for the
+// lifetime of the workgroup; otherwise it is re-read (from L2) for every row, which frees 8 registers per chunk.
+// FULL: the row fills the row lanes exactly (chunks = ITERS x row lanes): no bounds tests.
+template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, int NORM, bool FULL>
 __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
 {
+    constexpr bool LAYER = NORM == QLLM_NORM_LAYER, RMS = NORM == QLLM_NORM_RMS;
+    constexpr int W = PKW<BITS>;
+    constexpr int QMAX = (1 << BITS) - 1;
+    constexpr uint32_t NOT_PUBLISHED = 0xffffffu;
     extern __shared__ __align__(16) float lds[];
-    float *pub = lds;                         // [8 * n_pub]      y of the chunks that general groups read
-    float *zero = pub + GROUP * a.n_pub;      // [4] a zero: the "second source" of single-entry items
-    float *exc = zero + 4;                    // [8 * n_general]  reassembled channels of the general groups
-    int4 *longs = reinterpret_cast<int4 *>(exc + GROUP * a.n_general); // [n_long] entries of the long rows
-    int2 *items = reinterpret_cast<int2 *>(longs + a.n_long);          // [8 * n_general] entries of the general groups
-    uint32_t *pk = reinterpret_cast<uint32_t *>(items + GROUP * a.n_general); // [(n_chunks + 1) * PKW] packed codes, input order
-    uint32_t *masks = pk + (a.n_chunks + 1) * PKW<BITS>;               // [n_mask] chunks of which only some channels pass
-    uint32_t *chunkw = masks + a.n_mask;                               // [n_chunks] pass bits | staging slot << 8
-    int32_t *work = reinterpret_cast<int32_t *>(chunkw + a.n_chunks); // [n_work] work list of the output groups
+    const bool shift = LAYER && a.beta != nullptr;
+    const int nm = a.n_main;                  // row lanes
+    const int n_stage = GROUP * a.n_pub + 4;  // staged positions: the chunks that hold sources, then a zero
+    const int goff = NORM != QLLM_NORM_NONE ? n_stage : 0, boff = goff + (shift ? n_stage : 0);
+    float *pub = lds;                          // [n_stage] x of the staged chunks; [8 n_pub ..] stays zero
+    float *pubg = lds + goff;                  // [n_stage] gamma at the same positions, 0 for the zero (not with NORM_NONE)
+    float *pubb = lds + boff;                  // [n_stage] beta likewise (LayerNorm with a shift only)
+    float *specv = lds + boff + n_stage;       // [n_dest4] values of the computed channels
+    const int n_dest4 = (a.n_dest + 3) & ~3;
+    int4 *longs = reinterpret_cast<int4 *>(specv + n_dest4);           // [n_long] entries of the long rows
+    uint4 *rec = reinterpret_cast<uint4 *>(longs + a.n_long);          // [n_comp][2] a composite group: its first two segments, its number
+    int2 *spec = reinterpret_cast<int2 *>(rec + 2 * a.n_comp);         // [n_spec] {staged sources, scale}
+    uint32_t *ins = reinterpret_cast<uint32_t *>(spec + a.n_spec);     // [n_comp * W] codes of the computed channels, in place
+    uint32_t *pk = ins + a.n_comp * W + W;                             // [-1 .. n_chunks] * W packed codes, input order; both ends zero
+    int32_t *dest = reinterpret_cast<int32_t *>(pk + (a.n_chunks + 1) * W); // [n_dest] composite group << 3 | position
+    uint32_t *segs = reinterpret_cast<uint32_t *>(dest + a.n_dest);    // [n_segw] segments of the composite groups
+    uint32_t *chunkw = segs + a.n_segw;                                // [ITERS * row lanes] pass bits | staging slot << 8
+    int32_t *work = reinterpret_cast<int32_t *>(chunkw + ITERS * nm); // [ITERS * row lanes] plain and padding output groups
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
     // bf16 rows are prefetched one row ahead; fp32 rows would need twice the registers and are not
     constexpr bool PREFETCH = sizeof(XT) == 2;
-    constexpr int ITEMS_REG = ITERS >= 4 ? ITERS : ITERS + 1; // general-group entries a lane keeps in registers
-    constexpr int W = PKW<BITS>;
-    constexpr uint32_t NOT_PUBLISHED = 0xffffffu;
 
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int n_chunks = a.n_chunks;
-    const int n_items = a.n_general * GROUP;
-    const float inf = __builtin_inff();
+    const float inf = __builtin_inff(), nan = __uint_as_float(0xffffffffu);
+    // row lanes and side lanes (uniform per wavefront); the irregular items are dealt out to `side_n` lanes
+    const int wave_first = __builtin_amdgcn_readfirstlane(tid); // a scalar: the tests below are branches, not lane masks
+    const bool is_row = wave_first < nm, is_side = nt > nm ? wave_first >= nm : true;
+    const int side_n = nt > nm ? nt - nm : nm;
 
-    // ---- per-lane state that outlives the rows
-    float gam[GAM_REG ? ITERS : 1][GROUP];
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int i = tid + it * nt;
-        if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
-    }
+    // ---- the plan, once per workgroup
     for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
-    for (int j = tid; j < a.n_mask; j += nt) masks[j] = (uint32_t)a.masks[j];
-    for (int j = tid; j < n_chunks; j += nt) chunkw[j] = (uint32_t)a.chunks[j];
-    for (int j = tid; j < a.n_work; j += nt) work[j] = a.work[j];
-    if (tid < 4) zero[tid] = 0.0f;
-    if (tid < W) pk[n_chunks * W + tid] = 0u;
-    if (tid < 16) { // reduction slots of waves that do not exist hold the identity
+    for (int j = tid; j < a.n_spec; j += nt) spec[j] = reinterpret_cast<const int2 *>(a.spec)[j];
+    for (int j = tid; j < a.n_dest; j += nt) dest[j] = a.dest[j];
+    for (int j = tid; j < a.n_comp * W; j += nt) ins[j] = 0u;
+    {
+        // The plan lists plain groups, then composite groups, then padding.  Plain and padding groups keep
+        // the plan's order in the row lanes' slots (slot it * row lanes + lane), so that neighbouring lanes
+        // store neighbouring groups.
+        const int n_p = a.n_groups - a.n_comp;
+        for (int sl = tid; sl < ITERS * nm; sl += nt) {
+            const int idx = sl < n_p ? sl : sl + a.n_comp;
+            work[sl] = idx < a.n_work ? a.work[idx] : WORK_NONE;
+        }
+        // A composite group's segments {count | number << 8, {d, mask, -} ...}: masks widened to code fields;
+        // the first two segments and the group's number also go to a record that one pair of wide LDS reads fetches.
+        for (int c = tid; c < a.n_comp; c += nt) {
+            const int32_t e = a.work[n_p + c];
+            const int off = e & 0x1ffff;
+            const uint32_t hdr = (uint32_t)a.segs[off];
+            const int n_seg = hdr & 0xffu, comp = hdr >> 8;
+            uint32_t r8[8] = {(uint32_t)n_seg | ((uint32_t)off << 8), 0u, 0u, 0u, 0u, 0u, 0u, (uint32_t)(e >> 17) & 0x1fffu};
+            segs[off] = hdr;
+            for (int sg = 0; sg < n_seg; ++sg) {
+                const uint32_t m8 = (uint32_t)a.segs[off + 2 + 3 * sg], ds = (uint32_t)a.segs[off + 1 + 3 * sg];
+                uint64_t m = 0;
+#pragma unroll
+                for (int k = 0; k < GROUP; ++k)
+                    if (m8 >> k & 1u) m |= (uint64_t)QMAX << (BITS * k);
+                segs[off + 1 + 3 * sg] = ds;
+                segs[off + 2 + 3 * sg] = (uint32_t)m;
+                segs[off + 3 + 3 * sg] = (uint32_t)(m >> 32);
+                if (sg < 2) {
+                    r8[1 + 3 * sg] = ds;
+                    r8[2 + 3 * sg] = (uint32_t)m;
+                    r8[3 + 3 * sg] = (uint32_t)(m >> 32);
+                }
+            }
+            rec[2 * comp] = make_uint4(r8[0], r8[1], r8[2], r8[3]);
+            rec[2 * comp + 1] = make_uint4(r8[4], r8[5], r8[6], r8[7]);
+        }
+    }
+    for (int j = tid; j < ITERS * nm; j += nt) {
+        const uint32_t cw = j < n_chunks ? (uint32_t)a.chunks[j] : (NOT_PUBLISHED << 8), slot = cw >> 8;
+        chunkw[j] = cw;
+        if (NORM != QLLM_NORM_NONE && slot != NOT_PUBLISHED) { // norm parameters of the staged chunks
+            float g8[GROUP];
+            load_gamma(g8, a.gamma, j * GROUP, a.C, true);
+#pragma unroll
+            for (int k = 0; k < GROUP; ++k) pubg[slot * GROUP + k] = g8[k];
+            if (shift) {
+                load_gamma(g8, a.beta, j * GROUP, a.C, true);
+#pragma unroll
+                for (int k = 0; k < GROUP; ++k) pubb[slot * GROUP + k] = g8[k];
+            }
+        }
+    }
+    if (tid < 4) { // the zero: x = 0, gamma = 0, beta = 0, so that its y is a zero whatever the row's statistics
+        pub[GROUP * a.n_pub + tid] = 0.0f;
+        if (NORM != QLLM_NORM_NONE) pubg[GROUP * a.n_pub + tid] = 0.0f;
+        if (shift) pubb[GROUP * a.n_pub + tid] = 0.0f;
+    }
+    if (tid < W) {
+        pk[n_chunks * W + tid] = 0u;
+        pk[tid - W] = 0u;
+    }
+    if (tid < 16) { // reduction slots of waves that do not exist (or take no part) hold the identity
         red_d[0][tid] = 0.0;
         red_d[1][tid] = 0.0;
         red_f[tid] = inf;
         red_f[16 + tid] = inf; // minus the maximum
         red_i[tid] = 0;
     }
-    // general-group entries {staged position of source 0 | of source 1 << 16, scale}: kept in LDS (a
-    // register pair per entry and lane would be too many); long rows are marked and read the zero
-    const uint32_t zero_at = (uint32_t)(GROUP * a.n_pub);
-    for (int j = tid; j < n_items; j += nt) {
-        int2 e = reinterpret_cast<const int2 *>(a.items)[j];
-        if (e.x == ITEM_LONG) e = make_int2((int32_t)(zero_at | (zero_at << 16)), ITEM_SKIP);
-        items[j] = e;
-    }
-
-    // gamma has to have arrived before the row loop is entered: a load still pending there would make
-    // every pass of the loop wait for whatever was requested last, the next row's prefetch included.
+    // gamma of the lane's chunks; NaN where the input channel is copied by no output channel (see above)
+    // and for chunks past the end of the row.  NORM_NONE multiplies by 1 (exact) or NaN.
+    auto mask_gamma = [&](float *g, uint32_t passes) {
+#pragma unroll
+        for (int j = 0; j < GROUP; ++j) g[j] = (passes >> j & 1u) ? g[j] : nan;
+    };
+    float gam[GAM_REG ? ITERS : 1][GROUP];
     if constexpr (GAM_REG) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int i = tid + it * nm;
+            load_gamma(gam[it], a.gamma, i * GROUP, a.C, NORM != QLLM_NORM_NONE && is_row);
+            mask_gamma(gam[it], is_row && i < n_chunks ? (uint32_t)a.chunks[i] & 0xffu : 0u);
+        }
+        // gamma has to have arrived before the row loop is entered: a load still pending there would make
+        // every pass of the loop wait for whatever was requested last, the next row's prefetch included.
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
 #pragma unroll
@@ -426,22 +523,88 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     __syncthreads();
 
     const XT *xbase = reinterpret_cast<const XT *>(a.x);
-    Raw<XT> raw[ITERS], ahead[PREFETCH ? ITERS : 1];
-    int64_t row = blockIdx.x, done_row = -1;
-    if (PREFETCH && row < a.N) { // the first row
+    const uint32_t zero_at = (uint32_t)(GROUP * a.n_pub);
+    Raw<XT> raw[ITERS];
+    int64_t row = blockIdx.x, prev = -1;
+    if (PREFETCH && is_row && row < a.N) { // the first row
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int i = tid + it * nt;
-            if (i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
+            const int i = tid + it * nm;
+            load_raw(raw[it], xbase + row * a.ldx, (FULL || i < n_chunks ? i : n_chunks - 1) * GROUP);
         }
     }
 
     // rowsum of a finished row: the waves' partial sums are complete once a barrier has passed
-    auto finish_rowsum = [&]() {
-        if (wave == 0 && done_row >= 0) {
+    auto finish_rowsum = [&](int64_t r) {
+        if (wave == 0 && r >= 0) {
             const int32_t s = dpp_add_row16(red_i[lane & 15]);
-            if (lane == 0) a.rowsum[done_row] = s;
+            if (lane == 0) a.rowsum[r] = s;
         }
+    };
+    // Eq. (2) for one value
+    auto one_code = [&](float v, int32_t fast, float inv, int32_t beta) -> uint32_t {
+        if (fast) {
+            const float lo = __int_as_float(MAGIC_BITS - beta), hi = __int_as_float(MAGIC_BITS - beta + QMAX);
+            return __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(v, inv, MAGIC), lo, hi)) - (uint32_t)(MAGIC_BITS - beta);
+        }
+        return slow_code(v, inv, beta, QMAX);
+    };
+
+    // ---- step a4, second half, of the row before: the output groups.  A plain group is two neighbouring
+    //      packed words funnel-shifted; a composite group is several such windows, each masked to the
+    //      channels it supplies, plus the codes of its computed channels.
+    auto output_pass = [&](int64_t prev, int ltid) {
+        int32_t sum = 0;
+        uint8_t *out_row = a.codes + prev * a.row_bytes;
+        if (is_row) {
+            // every LDS read of a kind is issued for all of the lane's groups before any is used
+            int32_t e[ITERS];
+            uint32_t w0[ITERS], w1[ITERS];
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) e[it] = work[ltid + it * nm];
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) { // padding groups read the row's first words and drop them
+                const bool plain = ((uint32_t)e[it] >> 30) == KIND_PLAIN;
+                const int d = plain ? e[it] & 0x1ffff : 0;
+                funnel<BITS>(pk, d >> 3, d & 7, w0[it], w1[it]);
+                w0[it] = plain ? w0[it] : 0u;
+                w1[it] = plain ? w1[it] : 0u;
+            }
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                if (((uint32_t)e[it] >> 30) != KIND_NONE) {
+                    store_group<BITS>(out_row, (e[it] >> 17) & 0x1fff, w0[it], w1[it]);
+                    sum += code_sum<BITS>(w0[it], w1[it]);
+                }
+            }
+        }
+        if (is_side) {
+            for (int comp = ltid - (nt > nm ? nm : 0); comp < a.n_comp; comp += side_n) {
+                const uint4 r0 = rec[2 * comp], r1 = rec[2 * comp + 1]; // {count | list << 8, d0, mask0}, {d1, mask1, group}
+                uint32_t i0 = ins[comp * W], i1 = 0u;
+                ins[comp * W] = 0u; // ready for the next row's codes
+                if constexpr (W == 2) {
+                    i1 = ins[comp * W + 1];
+                    ins[comp * W + 1] = 0u;
+                }
+                uint32_t f0, f1, g0, g1;
+                funnel<BITS>(pk, (int)r0.y >> 3, r0.y & 7, f0, f1);
+                funnel<BITS>(pk, (int)r1.x >> 3, r1.x & 7, g0, g1);
+                i0 |= (f0 & r0.z) | (g0 & r1.y);
+                if constexpr (W == 2) i1 |= (f1 & r0.w) | (g1 & r1.z);
+                const int n_seg = r0.x & 0xffu, off = r0.x >> 8;
+                for (int sg = 2; sg < n_seg; ++sg) {
+                    const int ds = (int)segs[off + 1 + 3 * sg];
+                    funnel<BITS>(pk, ds >> 3, ds & 7, f0, f1);
+                    i0 |= f0 & segs[off + 2 + 3 * sg];
+                    if constexpr (W == 2) i1 |= f1 & segs[off + 3 + 3 * sg];
+                }
+                store_group<BITS>(out_row, (int)r1.w, i0, i1);
+                sum += code_sum<BITS>(i0, i1);
+            }
+        }
+        sum = wave_sum_i32(sum);
+        if (lane == 0) red_i[wave] = sum; // read after the next barrier
     };
 
     for (; row < a.N; row += gridDim.x) {
@@ -449,185 +612,206 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         // register each to keep: hide from the optimiser that the number does not change from row to row.
         int ltid = threadIdx.x;
         asm volatile("" : "+v"(ltid));
-        // ---- step a1.  A bf16 row is already here (it was requested while the row before it was worked
-        //      on); request the next one.  Its registers move up further down, before this row's stores.
-        if constexpr (PREFETCH) {
-            const int64_t next = row + gridDim.x;
-            if (next < a.N) {
+        const int sid = ltid - (nt > nm ? nm : 0); // the lane's number among the side lanes (if it is one)
+
+        // ================= interval 1
+        // ---- step a1, first half.  A bf16 row is already here (it was requested while the row before it
+        //      was worked on): widen it and request the next one into the same registers.  This comes before
+        //      the stores of the row before: loads and stores retire through one counter, and a wait for
+        //      the row placed after those stores would wait for them as well.
+        float y[ITERS][GROUP]; // x until interval 2 turns it into y in place
+        if (is_row) {
+            if constexpr (!PREFETCH) {
 #pragma unroll
                 for (int it = 0; it < ITERS; ++it) {
-                    const int i = ltid + it * nt;
-                    if (i < n_chunks) load_raw(ahead[it], xbase + next * a.ldx, i * GROUP);
+                    const int i = ltid + it * nm;
+                    if (FULL || i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
                 }
             }
-        } else {
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                const int i = ltid + it * nt;
-                if (i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
+                if (FULL || ltid + it * nm < n_chunks) {
+                    widen(raw[it], y[it]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
+                }
+                // here and now: the optimiser would rather widen where x is first used, further down, and
+                // keep the row's packed form alive next to the registers the next row is loaded into
+#pragma unroll
+                for (int j = 0; j < GROUP; ++j) asm volatile("" : "+v"(y[it][j]));
+            }
+            if constexpr (PREFETCH) {
+                // Unconditional, so that the loaded registers ARE the next pass's row (a load under a condition
+                // would be merged with the old contents at the end of the condition, which waits for it): the
+                // last pass requests its own row again, lanes past the end of the row the row's last chunk.
+                const int64_t next = row + gridDim.x, again = next < a.N ? next : row;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    const int i = ltid + it * nm;
+                    load_raw(raw[it], xbase + again * a.ldx, (FULL || i < n_chunks ? i : n_chunks - 1) * GROUP);
+                }
             }
         }
 
-        // row statistics in fp64 (two interleaved partial sums per lane: the additions do not wait for
-        // one another; the order is fixed, so the result is reproducible)
-        float mu = 0.0f, rstd = 1.0f;
-        if (!LAYER && a.norm == QLLM_NORM_RMS) {
-            double q0 = 0.0, q1 = 0.0;
+        if (prev >= 0) output_pass(prev, ltid);
+
+        if (is_row) {
+            // x of the chunks that hold a source of a computed channel (normalised by its readers in interval 2)
+            uint32_t slot[ITERS];
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) slot[it] = chunkw[ltid + it * nm] >> 8;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                if (ltid + it * nt < n_chunks) {
-                    float v[GROUP];
-                    widen(raw[it], v);
-#pragma unroll
-                    for (int j = 0; j < GROUP; j += 2) {
-                        const double d0 = (double)v[j], d1 = (double)v[j + 1];
-                        q0 = __builtin_fma(d0, d0, q0);
-                        q1 = __builtin_fma(d1, d1, q1);
-                    }
+                if (slot[it] != NOT_PUBLISHED) {
+                    float4 *dst = reinterpret_cast<float4 *>(pub + slot[it] * GROUP);
+                    dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
+                    dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
                 }
             }
-            const double q = wave_sum(q0 + q1);
-            if (lane == 0) red_d[0][wave] = q;
-            __syncthreads(); // also: the previous row's last LDS reads are over
-            finish_rowsum();
+            // row statistics in fp64 (two interleaved partial sums per lane: the additions do not wait for
+            // one another; the order is fixed, so the result is reproducible).  Slots past the row hold 0.
+            if constexpr (NORM != QLLM_NORM_NONE) {
+                double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+#pragma unroll
+                    for (int j = 0; j < GROUP; j += 2) {
+                        const double d0 = (double)y[it][j], d1 = (double)y[it][j + 1];
+                        if constexpr (RMS) {
+                            s0 = __builtin_fma(d0, d0, s0);
+                            s1 = __builtin_fma(d1, d1, s1);
+                        } else {
+                            s0 += d0;
+                            s1 += d1;
+                        }
+                    }
+                }
+                const double s = wave_sum(s0 + s1);
+                if (lane == 0) red_d[0][wave] = s;
+            }
+        }
+        __syncthreads(); // partial statistics, staged x, partial rowsum; the packed words and the codes of the
+                         // computed channels of the row before are no longer needed
+        finish_rowsum(prev);
+
+        // ================= interval 2
+        // What a computed channel reads does not depend on the row's statistics: the first pass's entries and
+        // the staged x, gamma (beta) of their sources are requested now and used after rstd is known.
+        struct Staged {
+            float x, g, b;
+        };
+        auto staged_fetch = [&](uint32_t pos) -> Staged {
+            Staged v;
+            v.x = pub[pos];
+            v.g = NORM != QLLM_NORM_NONE ? pubg[pos] : 1.0f;
+            v.b = shift ? pubb[pos] : 0.0f;
+            return v;
+        };
+        const bool spec0 = is_side && sid < a.n_spec;
+        const int2 item0 = spec0 ? spec[sid] : make_int2((int32_t)(zero_at | (zero_at << 16)), 0);
+        const Staged src0 = staged_fetch((uint32_t)item0.x & 0xffffu), src1 = staged_fetch((uint32_t)item0.x >> 16);
+
+        float mu = 0.0f, rstd = 1.0f;
+        if constexpr (RMS) {
             rstd = rsqrt_to_f32(total16(red_d[0], lane) * a.inv_C + (double)a.eps);
         } else if constexpr (LAYER) {
-            double s0 = 0.0, s1 = 0.0;
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) {
-                if (ltid + it * nt < n_chunks) {
-                    float v[GROUP];
-                    widen(raw[it], v);
-#pragma unroll
-                    for (int j = 0; j < GROUP; j += 2) {
-                        s0 += (double)v[j];
-                        s1 += (double)v[j + 1];
-                    }
-                }
-            }
-            const double s = wave_sum(s0 + s1);
-            if (lane == 0) red_d[0][wave] = s;
-            __syncthreads(); // also: the previous row's last LDS reads are over
-            finish_rowsum();
             const double mu64 = total16(red_d[0], lane) * a.inv_C;
-            double q0 = 0.0, q1 = 0.0;
+            double q = 0.0;
+            if (is_row) {
+                double q0 = 0.0, q1 = 0.0;
 #pragma unroll
-            for (int it = 0; it < ITERS; ++it) {
-                if (ltid + it * nt < n_chunks) {
-                    float v[GROUP];
-                    widen(raw[it], v);
+                for (int it = 0; it < ITERS; ++it) {
+                    if (FULL || ltid + it * nm < n_chunks) {
 #pragma unroll
-                    for (int j = 0; j < GROUP; j += 2) {
-                        const double d0 = (double)v[j] - mu64, d1 = (double)v[j + 1] - mu64;
-                        q0 = __builtin_fma(d0, d0, q0);
-                        q1 = __builtin_fma(d1, d1, q1);
+                        for (int j = 0; j < GROUP; j += 2) {
+                            const double d0 = (double)y[it][j] - mu64, d1 = (double)y[it][j + 1] - mu64;
+                            q0 = __builtin_fma(d0, d0, q0);
+                            q1 = __builtin_fma(d1, d1, q1);
+                        }
                     }
                 }
+                q = q0 + q1;
             }
-            const double q = wave_sum(q0 + q1);
+            q = wave_sum(q);
             if (lane == 0) red_d[1][wave] = q;
             __syncthreads();
             mu = (float)mu64;
             rstd = rsqrt_to_f32(total16(red_d[1], lane) * a.inv_C + (double)a.eps);
-        } else {
-            __syncthreads(); // the previous row's last LDS reads are over
-            finish_rowsum();
         }
 
-        // ---- y, kept in registers; staged in LDS where a general group reads it; min/max over the
-        //      channels that pass unscaled
-        float y[ITERS][GROUP];
+        // y of a staged position (a source of a computed channel), normalised exactly as its owner does below
+        auto staged_norm = [&](const Staged &v) -> float {
+            float t = v.x;
+            if constexpr (NORM != QLLM_NORM_NONE) {
+                if constexpr (LAYER) t = t - mu;
+                t = t * rstd;
+                t = t * v.g;
+                if constexpr (LAYER) {
+                    if (shift) t = t + v.b;
+                }
+            }
+            return t;
+        };
+        auto staged_y = [&](uint32_t pos) -> float { return staged_norm(staged_fetch(pos)); };
+
+        // ---- y in registers, in place; min/max over the channels that some output channel copies (all
+        //      others are NaN by now)
         float mn = inf, mx = -inf;
-        const float *gamma_row = a.gamma, *beta_row = a.beta; // opaque, so that per-row loads stay per row
-        asm volatile("" : "+s"(gamma_row), "+s"(beta_row));
-        const bool shift = LAYER && a.beta != nullptr;
+        if (is_row) {
+            const float *gamma_row = a.gamma, *beta_row = a.beta; // opaque, so that per-row loads stay per row
+            asm volatile("" : "+s"(gamma_row), "+s"(beta_row));
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int i = ltid + it * nt;
-            float gjit[GROUP];
-            if constexpr (!GAM_REG) load_gamma(gjit, gamma_row, i * GROUP, a.C, a.norm != QLLM_NORM_NONE);
-            const float *g8 = GAM_REG ? gam[GAM_REG ? it : 0] : gjit;
-            if (i < n_chunks) {
-                forget(raw[it]);
-                widen(raw[it], y[it]);
+            for (int it = 0; it < ITERS; ++it) {
+                const int i = ltid + it * nm;
+                float gjit[GROUP];
+                if constexpr (!GAM_REG) {
+                    load_gamma(gjit, gamma_row, i * GROUP, a.C, NORM != QLLM_NORM_NONE);
+                    mask_gamma(gjit, chunkw[i] & 0xffu);
+                }
+                const float *g8 = GAM_REG ? gam[GAM_REG ? it : 0] : gjit;
                 float bj[GROUP];
                 if constexpr (LAYER) load_gamma(bj, beta_row, i * GROUP, a.C, shift); // beta: re-read (from L2) for every row
 #pragma unroll
                 for (int j = 0; j < GROUP; ++j) {
                     float t = y[it][j];
                     if constexpr (LAYER) t = t - mu;
-                    t = t * rstd;
+                    if constexpr (NORM != QLLM_NORM_NONE) t = t * rstd;
                     t = t * g8[j];
                     if constexpr (LAYER) {
                         if (shift) t = t + bj[j];
                     }
                     y[it][j] = t;
                 }
-                const uint32_t cw = chunkw[i], slot = cw >> 8;
-                if (slot != NOT_PUBLISHED) {
-                    float4 *dst = reinterpret_cast<float4 *>(pub + slot * GROUP);
-                    dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
-                    dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
-                }
-                if ((cw & 0xffu) == 0xffu) {
 #pragma unroll
-                    for (int j = 0; j < GROUP; j += 2) {
-                        mn = fminf(fminf(mn, y[it][j]), y[it][j + 1]);
-                        mx = fmaxf(fmaxf(mx, y[it][j]), y[it][j + 1]);
-                    }
+                for (int j = 0; j < GROUP; j += 2) {
+                    mn = fminf(fminf(mn, y[it][j]), y[it][j + 1]);
+                    mx = fmaxf(fmaxf(mx, y[it][j]), y[it][j + 1]);
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
             }
         }
-        __syncthreads(); // staged y complete
 
-        // ---- steps a2 + a3 for the general groups: sub-channels (scale 1/T), merged channels
-        //      (scale 1/g each) and the plain channels that share a group of 8 with them.
-        //      All LDS reads are issued before any of them is used.
-        {
-            int2 item[ITEMS_REG];
-            float y0[ITEMS_REG], y1[ITEMS_REG];
-#pragma unroll
-            for (int m = 0; m < ITEMS_REG; ++m) {
-                const int j = ltid + m * nt;
-                item[m] = j < n_items ? items[j] : make_int2((int32_t)(zero_at | (zero_at << 16)), ITEM_SKIP);
-            }
-#pragma unroll
-            for (int m = 0; m < ITEMS_REG; ++m) {
-                const uint32_t p = (uint32_t)item[m].x;
-                y0[m] = lds[p & 0xffffu];
-                y1[m] = lds[p >> 16];
-            }
-#pragma unroll
-            for (int m = 0; m < ITEMS_REG; ++m) {
-                const float sc = __int_as_float(item[m].y);
-                float xv = sc * y0[m];
-                xv = xv + sc * y1[m];
-                const bool real = item[m].y != ITEM_SKIP;
-                mn = fminf(mn, real ? xv : inf);
-                mx = fmaxf(mx, real ? xv : -inf);
-                if (real) exc[ltid + m * nt] = xv;
-            }
-            // Chunks of which only some channels pass (the others are split or merged away) enter min/max
-            // here, from their staged copy, one chunk per lane: there are few of them, but every wavefront
-            // owns some, so taking them where y is produced would cost every wavefront a masked pass per
-            // chunk.  Dealt out from the last lane down; the long rows below start at the first lane.
-            for (int base = 0; base < a.n_mask; base += nt) {
-                const int j = base + (nt - 1 - ltid);
-                const uint32_t cw = j < a.n_mask ? masks[j] : 0u;
-                if (cw & 0xffu) {
-                    const float4 *c4 = reinterpret_cast<const float4 *>(pub + (cw >> 8) * GROUP);
-                    const float4 lo = c4[0], hi = c4[1];
-                    const float yv[GROUP] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-                    for (int k = 0; k < GROUP; k += 2) {
-                        const bool in0 = cw >> k & 1u, in1 = cw >> (k + 1) & 1u;
-                        mn = fminf(fminf(mn, in0 ? yv[k] : inf), in1 ? yv[k + 1] : inf);
-                        mx = fmaxf(fmaxf(mx, in0 ? yv[k] : -inf), in1 ? yv[k + 1] : -inf);
-                    }
+        if (is_side) {
+            // ---- steps a2 + a3 for the computed channels of one entry (sub-channels, scale 1/T, Eq. 3) or of
+            //      two entries of equal scale (a merged pair, Eq. 4); one per lane and pass.
+            {
+                const float sc = __int_as_float(item0.y);
+                float xv = sc * staged_norm(src0);
+                xv = xv + sc * staged_norm(src1);
+                if (spec0) {
+                    mn = fminf(mn, xv);
+                    mx = fmaxf(mx, xv);
+                    specv[sid] = xv;
                 }
+            }
+            for (int j = sid + side_n; j < a.n_spec; j += side_n) {
+                const int2 item = spec[j];
+                const float sc = __int_as_float(item.y);
+                float xv = sc * staged_y((uint32_t)item.x & 0xffffu);
+                xv = xv + sc * staged_y((uint32_t)item.x >> 16);
+                mn = fminf(mn, xv);
+                mx = fmaxf(mx, xv);
+                specv[j] = xv;
             }
             // Long rows (a channel merged from three or more, Eq. 4).  The sum runs left to right in
             // fp32, so its order is fixed; its latency need not be.  Entry e of the table belongs to lane
@@ -635,19 +819,24 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             // then "value of the lane below + own product" is repeated; the lane of entry number pos is
             // final after pos repeats (repeating it again changes nothing) and the row's last lane
             // ends up with the row's value.  Every entry carries the largest pos of its wavefront.
-            for (int base = 0; base < a.n_long; base += nt) {
-                const int e = base + ltid;
+            for (int base = 0; base < a.n_long; base += side_n) {
+                const int e = base + sid;
                 int4 le = make_int4((int32_t)zero_at, -1, 0, 0);
                 if (e < a.n_long) le = longs[e];
-                const float p = __int_as_float(le.z) * lds[le.x];
-                const int pos = le.w & 0xff, steps = __builtin_amdgcn_readfirstlane(le.w >> 8);
+                const float p = __int_as_float(le.z) * staged_y((uint32_t)le.x);
+                // keep = 1 takes the value of the lane below, keep = 0 (a row's first entry) drops it: fma(v, 1, p) is
+                // the correctly rounded v + p, fma(v, 0, p) is p
+                const float keep = (le.w & 0xff) > 0 ? 1.0f : 0.0f;
+                const int steps = __builtin_amdgcn_readfirstlane(le.w >> 8);
                 float acc = p;
-                for (int t = 0; t < steps; ++t) {
-                    const float sum = below_plus(acc, p);
-                    acc = pos > 0 ? sum : p;
+                int t = 0;
+                for (; t + 4 <= steps; t += 4) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc = __builtin_fmaf(below(acc), keep, p);
                 }
+                for (; t < steps; ++t) acc = __builtin_fmaf(below(acc), keep, p);
                 if (le.y >= 0) {
-                    exc[le.y] = acc;
+                    specv[le.y] = acc;
                     mn = fminf(mn, acc);
                     mx = fmaxf(mx, acc);
                 }
@@ -660,13 +849,17 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             red_f[wave] = mn;
             red_f[16 + wave] = -mx; // negated: one butterfly of minima then serves both
         }
-        __syncthreads(); // also: the general groups' values are complete
+        __syncthreads(); // also: the computed channels' values are complete
+
+        // ================= interval 3
+        const bool code0 = is_side && sid < a.n_dest;
+        const float spec_v0 = code0 ? specv[sid] : 0.0f; // first pass of the computed channels' codes:
+        const int32_t spec_d0 = code0 ? dest[sid] : 0;    // requested now, used after the range is known
         {
             const float v = dpp_min_row16(red_f[lane & 31]);
             mn = lane_f32(v, 0);
             mx = -lane_f32(v, 16);
         }
-        constexpr int QMAX = (1 << BITS) - 1;
         const float range = mx - mn;
         const float alpha = range > 0.0f ? range / (float)QMAX : 1.0f;
         const float inv = 1.0f / alpha;
@@ -675,75 +868,77 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         if (fast) beta = -rne_product_fast(mn, inv);
         else beta = (int32_t)fmin(fmax(-rne_product_slow(mn, inv), -2147483647.0), 2147483647.0);
 
-        // ---- step a4, first half: codes of the lane's own chunks, packed in input order
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int i = ltid + it * nt;
-            if (i < n_chunks) {
-                uint32_t w0, w1;
-                quant_pack<BITS>(y[it], 0xffu, fast, inv, beta, w0, w1);
-                if constexpr (W == 1) pk[i] = w0;
-                else reinterpret_cast<uint2 *>(pk)[i] = make_uint2(w0, w1);
-            }
-        }
-        __syncthreads(); // packed words complete
-
-        // The next row moves up BEFORE this row's stores are issued: loads and stores retire in order
-        // through one counter, so a wait for the loads placed after the stores would wait for the
-        // stores too.
-        if constexpr (PREFETCH) {
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) move_up(raw[it], ahead[it]);
-        }
-
-        // ---- step a4, second half: the lane's output groups
-        int32_t sum = 0;
-        uint8_t *out_row = a.codes + row * a.row_bytes;
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int i = ltid + it * nt;
-            const int32_t e = i < a.n_work ? work[i] : WORK_NONE;
-            const int kind = (uint32_t)e >> 28;
-            if (kind != KIND_NONE) {
-                const int g = (e >> 15) & 0x1fff, d = e & 0x7fff;
-                uint32_t w0 = 0, w1 = 0;
-                if (kind == KIND_PLAIN) {
-                    funnel<BITS>(pk, d >> 3, d & 7, w0, w1);
-                } else if (kind == KIND_GENERAL) {
-                    const float4 e0 = *reinterpret_cast<const float4 *>(exc + d * GROUP);
-                    const float4 e1 = *reinterpret_cast<const float4 *>(exc + d * GROUP + 4);
-                    const float val[GROUP] = {e0.x, e0.y, e0.z, e0.w, e1.x, e1.y, e1.z, e1.w};
-                    const int left = a.C_out - g * GROUP;
-                    quant_pack<BITS>(val, left < GROUP ? (1u << left) - 1u : 0xffu, fast, inv, beta, w0, w1);
-                }
-                store_group<BITS>(out_row, g, w0, w1);
-                sum += code_sum<BITS>(w0, w1);
-            }
-        }
-        sum = wave_sum_i32(sum);
-        if (lane == 0) red_i[wave] = sum; // read after the next barrier
-        if (tid == 0) {
+        if (tid == 0) { // early, so that the stores have retired when the next row is waited for
             a.alpha[row] = alpha;
             a.zero[row] = beta;
         }
-        done_row = row;
+
+        // ---- step a4, first half: codes of the lane's own chunks, packed in input order
+        if (is_row) {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int i = ltid + it * nm;
+                if (FULL || i < n_chunks) {
+                    uint32_t w0, w1;
+                    quant_pack<BITS>(y[it], 0xffu, fast, inv, beta, w0, w1);
+                    if constexpr (W == 1) pk[i] = w0;
+                    else reinterpret_cast<uint2 *>(pk)[i] = make_uint2(w0, w1);
+                }
+            }
+        }
+        // codes of the computed channels, straight into their place in their group's word
+        if (is_side) {
+            auto put_code = [&](float v, int32_t dj) {
+                const uint32_t code = one_code(v, fast, inv, beta);
+                if constexpr (W == 1) {
+                    atomicOr(&ins[dj >> 3], code << (BITS * (dj & 7)));
+                } else {
+                    atomicOr(reinterpret_cast<unsigned long long *>(ins) + (dj >> 3), (unsigned long long)code << (BITS * (dj & 7)));
+                }
+            };
+            if (code0) put_code(spec_v0, spec_d0);
+            for (int j = sid + side_n; j < a.n_dest; j += side_n) put_code(specv[j], dest[j]);
+        }
+        __syncthreads(); // packed words and computed channels' codes complete
+        prev = row;
     }
+    // the last row's output groups
+    int ltid = threadIdx.x;
+    if (prev >= 0) output_pass(prev, ltid);
     __syncthreads();
-    finish_rowsum();
+    finish_rowsum(prev);
 }
 
 struct Shape {
-    int iters, nt;
+    int iters, main, nt; // chunks per row lane, row lanes, lanes (row lanes + side lanes)
 };
+
+// Extra wavefronts for the irregular items.  Measured at the LLaMA-70B down-projection shape: two side
+// wavefronts take longer over the long rows and the composite groups than the row wavefronts take over
+// the row (66 against 57 us), so none are used; QLLM_FUSED_SIDE_WAVES (0..2) is there for measurements.
+int side_waves(const Shape &s)
+{
+    static int want = -1;
+    if (want < 0) {
+        const char *e = getenv("QLLM_FUSED_SIDE_WAVES");
+        want = e ? atoi(e) : 0;
+        if (want < 0 || want > 2) want = 0;
+    }
+    const int most = s.iters == 1 ? 384 : 1024;
+    int n = want;
+    while (n > 0 && s.main + 64 * n > most) --n;
+    return n;
+}
 
 // Chunks (or output groups) per lane and the workgroup size for a row of `units` of them.
 Shape pick_shape(int units)
 {
     Shape s;
-    if (units <= 256) s = {1, 0};
-    else if (units <= 2048) s = {2, 0};
-    else s = {4, 0};
-    s.nt = ((units + s.iters - 1) / s.iters + 63) / 64 * 64;
+    if (units <= 256) s = {1, 0, 0};
+    else if (units <= 2048) s = {2, 0, 0};
+    else s = {4, 0, 0};
+    s.main = ((units + s.iters - 1) / s.iters + 63) / 64 * 64;
+    s.nt = s.main + 64 * side_waves(s);
     return s;
 }
 
@@ -805,8 +1000,10 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
     }
     int64_t grid = (int64_t)cu_count() * per_cu;
     if (grid > a.N) grid = a.N;
+    FusedArgs b = a;
+    b.n_main = sh.main;
     (void)hipGetLastError();
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3((unsigned)sh.nt), lds, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3((unsigned)sh.nt), lds, stream, b);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         qllm_note_hip_error("planned fused kernel: launch", hipGetErrorName(e));
@@ -815,26 +1012,36 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
     return QLLM_OK;
 }
 
-template <typename XT, int BITS, bool LAYER>
+template <typename XT, int BITS, int NORM, bool FULL>
 int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 256, true, LAYER>, a, sh, lds, stream);
-    if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, LAYER>, a, sh, lds, stream);
+    if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 384, true, NORM, FULL>, a, sh, lds, stream);
+    if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, NORM, FULL>, a, sh, lds, stream);
     // 16 waves x 4 chunks: gamma fits in registers next to y and the prefetched row, except with LayerNorm
-    return launch(fused_planned_kernel<XT, BITS, 4, 1024, !LAYER, LAYER>, a, sh, lds, stream);
+    return launch(fused_planned_kernel<XT, BITS, 4, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
+}
+
+template <typename XT, int BITS, int NORM>
+int32_t dispatch_full(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+{
+    const bool full = a.n_chunks == sh.iters * sh.main;
+    return full ? dispatch<XT, BITS, NORM, true>(a, sh, lds, stream) : dispatch<XT, BITS, NORM, false>(a, sh, lds, stream);
+}
+
+template <typename XT, int BITS>
+int32_t dispatch_norm(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+{
+    if (a.norm == QLLM_NORM_LAYER) return dispatch_full<XT, BITS, QLLM_NORM_LAYER>(a, sh, lds, stream);
+    if (a.norm == QLLM_NORM_RMS) return dispatch_full<XT, BITS, QLLM_NORM_RMS>(a, sh, lds, stream);
+    return dispatch_full<XT, BITS, QLLM_NORM_NONE>(a, sh, lds, stream);
 }
 
 template <typename XT>
 int32_t dispatch_bits(const FusedArgs &a, int bits, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (a.norm == QLLM_NORM_LAYER) {
-        if (bits == 4) return dispatch<XT, 4, true>(a, sh, lds, stream);
-        if (bits == 6) return dispatch<XT, 6, true>(a, sh, lds, stream);
-        return dispatch<XT, 8, true>(a, sh, lds, stream);
-    }
-    if (bits == 4) return dispatch<XT, 4, false>(a, sh, lds, stream);
-    if (bits == 6) return dispatch<XT, 6, false>(a, sh, lds, stream);
-    return dispatch<XT, 8, false>(a, sh, lds, stream);
+    if (bits == 4) return dispatch_norm<XT, 4>(a, sh, lds, stream);
+    if (bits == 6) return dispatch_norm<XT, 6>(a, sh, lds, stream);
+    return dispatch_norm<XT, 8>(a, sh, lds, stream);
 }
 
 } // namespace
@@ -844,12 +1051,13 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
     const int units = a.n_chunks > a.n_work ? a.n_chunks : a.n_work;
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
     const Shape sh = pick_shape(units);
-    const size_t lds = ((size_t)a.n_pub + (size_t)a.n_general) * GROUP * sizeof(float) + 16 + (size_t)a.n_long * 16 +
-                       (size_t)a.n_general * GROUP * 8 + ((size_t)a.n_chunks + 1) * (bits == 4 ? 4 : 8) +
-                       ((size_t)a.n_mask + (size_t)a.n_chunks + (size_t)a.n_work) * 4;
+    // staged x, and gamma / beta at the same positions when there is a norm / a shift
+    const size_t n_stage = (size_t)a.n_pub * GROUP + 4, w = bits == 4 ? 1 : 2;
+    const size_t stage_sets = 1 + (a.norm != QLLM_NORM_NONE ? 1 : 0) + (a.norm == QLLM_NORM_LAYER && a.beta ? 1 : 0);
+    const size_t lds = (stage_sets * n_stage + (((size_t)a.n_dest + 3) & ~(size_t)3)) * sizeof(float) + (size_t)a.n_long * 16 +
+                       (size_t)a.n_comp * 32 + (size_t)a.n_spec * 8 + ((size_t)a.n_comp * w + w + ((size_t)a.n_chunks + 1) * w) * 4 +
+                       ((size_t)a.n_dest + (size_t)a.n_segw + 2 * (size_t)sh.iters * sh.main) * 4;
     if (lds > (size_t)MAX_LDS) return QLLM_ERR_WORKSPACE;
-    const int items_reg = sh.iters >= 4 ? sh.iters : sh.iters + 1;
-    if ((int64_t)a.n_general * GROUP > (int64_t)items_reg * sh.nt) return QLLM_ERR_WORKSPACE; // a lane takes at most that many general-group entries
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);
     return dispatch_bits<float>(a, bits, sh, lds, stream);
 }

@@ -140,6 +140,15 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     if (C_in <= 0 || C_out <= 0 || C_in > QLLM_MAX_CHANNELS || C_out > QLLM_MAX_CHANNELS) return QLLM_ERR_SHAPE;
     const int64_t G = QLLM_MAP_GROUP, HEAD = QLLM_PLAN_HEAD;
     const int64_t n_groups = (C_out + G - 1) / G, n_chunks = (C_in + G - 1) / G;
+    constexpr int64_t WAVE = 64;
+    enum { PASS = 0, COMPACT = 1, LONG = 2 };
+    // What an output channel is to the fused kernel: a copy of one input channel (its code is the code of
+    // that input channel), a value of one entry or of two entries of equal scale, or a longer sum.
+    auto classify = [&](int64_t ch) {
+        const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
+        if (n == 1) return scale[e0] == 1.0f ? PASS : COMPACT;
+        return n == 2 && std::memcmp(&scale[e0], &scale[e0 + 1], 4) == 0 ? COMPACT : LONG;
+    };
     auto plain_source = [&](int64_t g) -> int32_t { // first source of a plain group, or -1
         const int64_t c0 = g * G;
         if (c0 + G > C_out) return -1;
@@ -149,99 +158,111 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
             if (row_ptr[c0 + j] != e0 + j || src[e0 + j] != src[e0] + j || scale[e0 + j] != 1.0f) return -1;
         return src[e0] + G <= C_in && src[e0] >= 0 ? src[e0] : -1;
     };
-    auto compact = [&](int64_t ch) { // one entry, or two entries of equal scale
-        const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
-        return n == 1 || (n == 2 && std::memcmp(&scale[e0], &scale[e0 + 1], 4) == 0);
-    };
-    // Rows that are neither short form go to the table of long rows, one entry per lane of the fused
-    // kernel: a row occupies consecutive lanes of ONE wavefront, so the table is padded wherever a row
-    // would straddle a multiple of 64.
-    constexpr int64_t WAVE = 64;
+    // A long row occupies consecutive lanes of ONE wavefront of the kernel, so the table of long-row entries is
+    // padded wherever a row would otherwise straddle a multiple of 64.
     auto place_long = [&](int64_t at, int64_t n) { return at % WAVE + n > WAVE ? (at + WAVE - 1) / WAVE * WAVE : at; };
-    // Sizes: general groups, long-row entries, and the input chunks that any general group reads
-    // ("published": the kernel stages their y in LDS, the only y that lanes exchange).
+
+    // ---- first pass: sizes
     std::vector<int32_t> pub_slot((size_t)n_chunks, -1), desc((size_t)n_groups);
     std::vector<uint8_t> pass((size_t)n_chunks, 0);
-    int64_t general = 0, n_long = 0;
-    for (int64_t g = 0; g < n_groups; ++g) {
-        const int32_t d = desc[(size_t)g] = plain_source(g);
-        if (d >= 0) {
-            for (int j = 0; j < G; ++j) pass[(size_t)((d + j) / G)] |= (uint8_t)(1 << ((d + j) % G));
+    int64_t n_comp = 0, n_long = 0, n_spec = 0, n_rows_long = 0, n_segw = 0;
+    for (int64_t ch = 0; ch < C_out; ++ch) {
+        const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
+        if (n < 1) return QLLM_ERR_MAP;
+        for (int32_t e = e0; e < e0 + n; ++e)
+            if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
+        const int kind = classify(ch);
+        if (kind == PASS) {
+            pass[(size_t)(src[e0] / G)] |= (uint8_t)(1 << (src[e0] % G));
             continue;
         }
-        ++general;
-        for (int64_t ch = g * G; ch < std::min(C_out, (g + 1) * G); ++ch) {
-            const int64_t n = row_ptr[ch + 1] - row_ptr[ch];
-            if (n < 1) return QLLM_ERR_MAP;
-            for (int32_t e = row_ptr[ch]; e < row_ptr[ch + 1]; ++e) {
-                if (src[e] < 0 || src[e] >= C_in) return QLLM_ERR_MAP;
-                pub_slot[(size_t)(src[e] / G)] = 0;
-            }
-            if (!compact(ch)) {
-                if (n > WAVE) return QLLM_ERR_MAP; // a long row is summed inside one wavefront
-                n_long = place_long(n_long, n) + n;
-            }
+        for (int32_t e = e0; e < e0 + n; ++e) pub_slot[(size_t)(src[e] / G)] = 0; // the kernel stages this chunk's x
+        if (kind == COMPACT) {
+            ++n_spec;
+        } else {
+            if (n > WAVE) return QLLM_ERR_MAP; // a long row is summed inside one wavefront
+            n_long = place_long(n_long, n) + n;
+            ++n_rows_long;
         }
     }
-    // a chunk of which only some channels pass is staged too (the kernel takes its min/max from there)
-    for (int64_t c = 0; c < n_chunks; ++c)
-        if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) pub_slot[(size_t)c] = 0;
-    int64_t n_pub = 0, n_mask = 0;
-    for (int64_t c = 0; c < n_chunks; ++c) {
-        if (pub_slot[(size_t)c] == 0) pub_slot[(size_t)c] = (int32_t)n_pub++;
-        if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) ++n_mask;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        const int32_t d = desc[(size_t)g] = plain_source(g);
+        if (d >= 0) continue;
+        // segments of a composite group: the copied channels, grouped by d = source - position
+        int32_t ds[8];
+        int n_seg = 0;
+        for (int64_t ch = g * G; ch < std::min(C_out, (g + 1) * G); ++ch) {
+            if (classify(ch) != PASS) continue;
+            const int32_t dk = src[row_ptr[ch]] - (int32_t)(ch - g * G);
+            int s = 0;
+            while (s < n_seg && ds[s] != dk) ++s;
+            if (s == n_seg) ds[n_seg++] = dk;
+        }
+        n_segw += 1 + 3 * n_seg;
+        ++n_comp;
     }
-    if (n_long > 0xffffff || G * n_pub + 4 > 0xffff) return QLLM_ERR_MAP;
-    *n_general = general;
+    int64_t n_pub = 0;
+    for (int64_t c = 0; c < n_chunks; ++c)
+        if (pub_slot[(size_t)c] == 0) pub_slot[(size_t)c] = (int32_t)n_pub++;
+    const int64_t n_dest = n_spec + n_rows_long;
+    if (n_long > 0xffffff || G * n_pub + 4 > 0xffff || n_segw > 0x1ffff || n_comp > 0xffffff) return QLLM_ERR_MAP;
+    *n_general = n_comp;
     const int64_t n_work = (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G; // groups incl. zero padding
     auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
-    const int64_t off_work = HEAD, off_chunks = round4(off_work + n_work), off_items = round4(off_chunks + n_chunks);
-    const int64_t off_longs = round4(off_items + general * G * 2), off_masks = off_longs + 4 * n_long;
-    *plan_len = off_masks + n_mask;
+    const int64_t off_work = HEAD, off_chunks = round4(off_work + n_work), off_spec = round4(off_chunks + n_chunks);
+    const int64_t off_dest = round4(off_spec + 2 * n_spec), off_longs = round4(off_dest + n_dest);
+    const int64_t off_segs = off_longs + 4 * n_long;
+    *plan_len = off_segs + n_segw;
     if (!plan) return QLLM_OK;
 
+    // ---- second pass: the tables
     std::fill(plan, plan + *plan_len, 0);
-    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 5, C_in, C_out, n_work, general, n_chunks, n_long,
-                                          n_pub, off_work, off_chunks, off_items, off_longs, *plan_len, n_mask, off_masks};
+    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 6, C_in, C_out, n_work, n_comp, n_chunks, n_long,
+                                          n_pub, n_spec, n_dest, n_segw, off_chunks, *plan_len, off_spec, off_longs};
     for (int64_t k = 0; k < HEAD; ++k) plan[k] = (int32_t)head[k];
-    int32_t *work = plan + off_work, *chunks = plan + off_chunks, *items = plan + off_items, *longs = plan + off_longs;
+    int32_t *work = plan + off_work, *chunks = plan + off_chunks, *spec = plan + off_spec, *dest = plan + off_dest;
+    int32_t *longs = plan + off_longs, *segs = plan + off_segs;
     for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1; // padding entries are {0, -1, 0.0f, 0}
     const uint32_t zero_at = (uint32_t)(G * n_pub); // the staged zero sits right after the published chunks
     auto staged = [&](int32_t channel) { return (uint32_t)(pub_slot[(size_t)(channel / G)] * G + channel % G); };
-    for (int64_t c = 0, m = 0; c < n_chunks; ++c) {
-        chunks[c] = (int32_t)(((uint32_t)pub_slot[(size_t)c] << 8) | pass[(size_t)c]); // -1: 0xffffff
-        if (pass[(size_t)c] != 0 && pass[(size_t)c] != 0xff) plan[off_masks + m++] = chunks[c];
-    }
-    int64_t slot = 0, long_at = 0;
+    for (int64_t c = 0; c < n_chunks; ++c)
+        chunks[c] = (int32_t)(((uint32_t)pub_slot[(size_t)c] << 8) | pass[(size_t)c]); // no slot: 0xffffff
+    int64_t comp = 0, spec_at = 0, long_row = 0, long_at = 0, seg_at = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
         if (desc[(size_t)g] >= 0) continue;
-        desc[(size_t)g] = (int32_t)(-(slot + 1));
-        for (int k = 0; k < G; ++k) {
-            int32_t *it = items + (slot * G + k) * 2;
-            const int64_t ch = g * G + k;
-            if (ch >= C_out) { // padding past C_out: repeats the group's first channel (its code is forced to 0)
-                it[0] = items[slot * G * 2];
-                it[1] = items[slot * G * 2 + 1];
-                continue;
-            }
+        int32_t *hdr = segs + seg_at;
+        int n_seg = 0;
+        for (int64_t ch = g * G; ch < std::min(C_out, (g + 1) * G); ++ch) {
+            const int k = (int)(ch - g * G);
             const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
-            if (!compact(ch)) { // entries go to the table of long rows: {staged source, destination or -1, scale, position}
+            const int kind = classify(ch);
+            if (kind == PASS) {
+                const int32_t dk = src[e0] - k;
+                int s = 0;
+                while (s < n_seg && hdr[1 + 3 * s] != dk) ++s;
+                if (s == n_seg) hdr[1 + 3 * n_seg++] = dk;
+                hdr[2 + 3 * s] |= 1 << k;
+            } else if (kind == COMPACT) { // {staged source | second staged source << 16, scale}; destination apart
+                const uint32_t second = n == 2 ? staged(src[e0 + 1]) : zero_at;
+                spec[2 * spec_at] = (int32_t)(staged(src[e0]) | (second << 16));
+                std::memcpy(&spec[2 * spec_at + 1], &scale[e0], 4);
+                dest[spec_at++] = (int32_t)((comp << 3) | k);
+            } else { // entries go to the table of long rows: {staged source, value slot or -1, scale, position}
                 long_at = place_long(long_at, n);
-                it[0] = -2;
-                it[1] = (int32_t)((uint32_t)long_at | ((uint32_t)n << 24));
+                const int64_t id = n_spec + long_row++;
+                dest[id] = (int32_t)((comp << 3) | k);
                 for (int32_t e = e0; e < e0 + n; ++e, ++long_at) {
                     longs[4 * long_at] = (int32_t)staged(src[e]);
-                    longs[4 * long_at + 1] = e == e0 + n - 1 ? (int32_t)(slot * G + k) : -1;
+                    longs[4 * long_at + 1] = e == e0 + n - 1 ? (int32_t)id : -1;
                     std::memcpy(&longs[4 * long_at + 2], &scale[e], 4);
                     longs[4 * long_at + 3] = e - e0;
                 }
-                continue;
             }
-            const uint32_t second = n == 2 ? staged(src[e0 + 1]) : zero_at;
-            it[0] = (int32_t)(staged(src[e0]) | (second << 16));
-            std::memcpy(&it[1], &scale[e0], 4);
         }
-        ++slot;
+        hdr[0] = (int32_t)((uint32_t)n_seg | ((uint32_t)comp << 8));
+        desc[(size_t)g] = (int32_t)(-(seg_at + 1));
+        seg_at += 1 + 3 * n_seg;
+        ++comp;
     }
     // every entry of a block of 64 also carries the block's largest position: the number of additions
     // the wavefront that owns the block has to make
@@ -251,14 +272,14 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         for (int64_t e = b0; e < std::min(n_long, b0 + WAVE); ++e) longs[4 * e + 3] |= most << 8;
     }
     // work list of the code-producing step, one entry per group of 8 output channels (zero padding
-    // included): kind << 28 | group << 15 | d.  Plain groups first, then general groups (d = their
-    // number), then padding groups, so that all but two wavefronts of the kernel are of one kind.
+    // included): kind << 30 | group << 17 | field.  Plain groups first, then composite groups, then
+    // padding groups, so that all but two wavefronts of the kernel are of one kind.
     int64_t at = 0;
     for (int64_t g = 0; g < n_groups; ++g)
-        if (desc[g] >= 0) work[at++] = (int32_t)(((uint32_t)g << 15) | (uint32_t)desc[g]);
+        if (desc[g] >= 0) work[at++] = (int32_t)(((uint32_t)g << 17) | (uint32_t)desc[g]);
     for (int64_t g = 0; g < n_groups; ++g)
-        if (desc[g] < 0) work[at++] = (int32_t)((1u << 28) | ((uint32_t)g << 15) | (uint32_t)(-(desc[g] + 1)));
-    for (int64_t g = n_groups; g < n_work; ++g) work[at++] = (int32_t)((2u << 28) | ((uint32_t)g << 15));
+        if (desc[g] < 0) work[at++] = (int32_t)((1u << 30) | ((uint32_t)g << 17) | (uint32_t)(-(desc[g] + 1)));
+    for (int64_t g = n_groups; g < n_work; ++g) work[at++] = (int32_t)((2u << 30) | ((uint32_t)g << 17));
     return QLLM_OK;
 }
 

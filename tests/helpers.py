@@ -59,3 +59,28 @@ def rel_err(got, ref):
     ref = ref.astype(np.float64)
     floor = 1e-3 * np.sqrt((ref * ref).mean()) + 1e-30
     return np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), floor)
+
+
+def random_csr_map(rng, C_in, C_out, special_every):
+    """Any CSR map, not only those the paper's reassembly makes: mostly shifted unscaled copies (so that
+    plain groups with every misalignment exist), every `special_every`-th row 1..5 entries with arbitrary
+    sources (repeats allowed) and arbitrary scales; some inputs are never referenced."""
+    row_ptr, src, scale = [0], [], []
+    shift = 0
+    for ch in range(C_out):
+        if ch % special_every == special_every - 1:
+            n = int(rng.integers(1, 6))
+            src += rng.integers(0, C_in, n).tolist()
+            kind = rng.integers(0, 3)
+            if kind == 0:
+                scale += [1.0] * n                                  # the "sum" convention of a merge
+            elif kind == 1:
+                scale += [float(np.float32(1.0 / n))] * n
+            else:
+                scale += rng.uniform(-2.0, 2.0, n).astype(np.float32).tolist()
+            shift = int(rng.integers(0, 9))
+        else:
+            src.append(min(max(ch + shift - 4, 0), C_in - 1))
+            scale.append(1.0)
+        row_ptr.append(len(src))
+    return np.array(row_ptr, np.int32), np.array(src, np.int32), np.array(scale, np.float32)

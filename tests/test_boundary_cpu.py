@@ -8,7 +8,7 @@ import re
 import numpy as np
 import pytest
 
-from helpers import make_case
+from helpers import make_case, random_csr_map
 from paper_2310_08041_amd import binding as b
 from paper_2310_08041_amd import workloads as wl
 
@@ -148,6 +148,107 @@ def test_build_map_matches_hand_worked_example():
     assert (r["C_out"], r["nnz"]) == (6, 7)
 
 
+def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
+    """Reads a plan the way its layout is documented in include/qllm.h and rebuilds, for every output channel,
+    the list of (source, scale) entries it stands for; that has to be the CSR map the plan was made from."""
+    n_groups, n_chunks, n_work = (K + 7) // 8, (C + 7) // 8, (K + 255) // 256 * 32
+    magic, version, c_in, c_out, nw, n_comp, nc, n_long, n_pub, n_spec, n_dest, n_segw, off_chunks, plan_len, off_spec, \
+        off_longs = plan[:16].tolist()
+    assert (magic, version, c_in, c_out, nw, nc) == (0x514C4D50, 6, C, K, n_work, n_chunks)
+    r4 = lambda v: (v + 3) // 4 * 4
+    off_work = 16
+    assert off_chunks == r4(off_work + n_work) and off_spec == r4(off_chunks + n_chunks)
+    off_dest = r4(off_spec + 2 * n_spec)
+    assert off_longs == r4(off_dest + n_dest)
+    off_segs = off_longs + 4 * n_long
+    assert plan_len == plan.size == off_segs + n_segw
+    work = plan[off_work:off_work + n_work].astype(np.int64) & 0xFFFFFFFF
+    kind, grp, field = work >> 30, (work >> 17) & 0x1FFF, work & 0x1FFFF
+    assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
+    assert np.all(np.diff(kind * 8192 + grp) > 0)                # by kind, then by group
+    assert np.all(kind[grp >= n_groups] == 2) and np.all(kind[grp < n_groups] < 2) and (kind == 1).sum() == n_comp
+    chunks = plan[off_chunks:off_chunks + n_chunks].astype(np.int64) & 0xFFFFFFFF
+    passes, slots = chunks & 0xFF, chunks >> 8
+    staged = slots != 0xFFFFFF
+    assert staged.sum() == n_pub and np.array_equal(slots[staged], np.arange(n_pub))
+    chan_of_pos = {int(slots[ch]) * 8 + j: ch * 8 + j for ch in np.nonzero(staged)[0] for j in range(8)}
+    zero_at = 8 * n_pub
+    spec = plan[off_spec:off_spec + 2 * n_spec].reshape(n_spec, 2)
+    dest = plan[off_dest:off_dest + n_dest]
+    longs = plan[off_longs:off_segs].reshape(-1, 4).copy()
+    segs = plan[off_segs:]
+    most = longs[:, 3] >> 8                                       # largest position among the 64 entries of a wavefront
+    longs[:, 3] &= 0xFF
+    for b0 in range(0, n_long, 64):
+        assert np.all(most[b0:b0 + 64] == longs[b0:b0 + 64, 3].max())
+    as_f = lambda w: np.array([w], np.int32).view(np.float32)[0]
+    rebuilt = {}                                                   # output channel -> [(source, scale bits)]
+    comp_group = {}
+    for kd, g, f in zip(kind, grp, field):
+        if kd == 0:                                                # plain: 8 copies of consecutive sources
+            assert 0 <= f <= C - 8
+            for k in range(8):
+                rebuilt[8 * g + k] = [(int(f) + k, np.float32(1.0))]
+        elif kd == 1:                                              # composite: masked windows
+            hdr = int(segs[f]) & 0xFFFFFFFF
+            n_seg, number = hdr & 0xFF, hdr >> 8
+            comp_group[number] = int(g)
+            seen = 0
+            for sg in range(n_seg):
+                d, m8, pad = (int(v) for v in segs[f + 1 + 3 * sg:f + 4 + 3 * sg])
+                assert pad == 0 and 0 < m8 < 256 and not (seen & m8)
+                seen |= m8
+                for k in range(8):
+                    if m8 >> k & 1:
+                        assert 0 <= d + k < C
+                        rebuilt[8 * g + k] = [(d + k, np.float32(1.0))]
+    assert sorted(comp_group) == list(range(n_comp))
+    for i in range(n_spec):                                        # computed channels
+        word, sbits = int(spec[i, 0]) & 0xFFFFFFFF, spec[i, 1]
+        s0, s1 = word & 0xFFFF, word >> 16
+        ch = 8 * comp_group[int(dest[i]) >> 3] + (int(dest[i]) & 7)
+        assert ch not in rebuilt
+        rebuilt[ch] = [(chan_of_pos[s0], as_f(sbits))] + ([] if s1 == zero_at else [(chan_of_pos[s1], as_f(sbits))])
+    at, seen_rows = 0, 0
+    while at < n_long:                                             # long rows; padding entries have slot -1 and scale bits 0
+        if longs[at, 1] == -1 and longs[at, 3] == 0 and longs[at, 2] == 0 and (at + 1 >= n_long or longs[at + 1, 3] == 0):
+            at += 1                                                # padding
+            continue
+        entries, first = [], at
+        while True:
+            assert longs[at, 3] == at - first and at // 64 == first // 64   # positions count up inside one wavefront
+            entries.append((chan_of_pos[int(longs[at, 0])], as_f(longs[at, 2])))
+            at += 1
+            if longs[at - 1, 1] >= 0:
+                break
+        slot = int(longs[at - 1, 1])
+        assert n_spec <= slot < n_dest
+        ch = 8 * comp_group[int(dest[slot]) >> 3] + (int(dest[slot]) & 7)
+        assert ch not in rebuilt and len(entries) >= 2
+        rebuilt[ch] = entries
+        seen_rows += 1
+    assert seen_rows == n_dest - n_spec
+    assert sorted(rebuilt) == list(range(K))
+    expect_pass = np.zeros(n_chunks * 8, bool)
+    for ch in range(K):
+        e0, e1 = row_ptr[ch], row_ptr[ch + 1]
+        want = [(int(src[e]), np.float32(scale[e])) for e in range(e0, e1)]
+        assert rebuilt[ch] == want, (ch, rebuilt[ch], want)
+        if e1 - e0 == 1 and scale[e0] == 1.0:
+            expect_pass[src[e0]] = True
+    assert np.array_equal(np.unpackbits(passes.astype(np.uint8), bitorder="little"), expect_pass.astype(np.uint8))
+
+
+@pytest.mark.parametrize("C_in,C_out,special_every", [(2048, 2100, 37), (8200, 8000, 61), (1000, 1003, 5), (64, 9, 2)])
+def test_plan_of_an_arbitrary_map_decodes_to_it(C_in, C_out, special_every):
+    # repeated and unreferenced sources, rows of 1..5 entries with any scales, plain groups at every misalignment
+    rng = np.random.default_rng(C_in + special_every)
+    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, special_every)
+    plan, n_comp = b.qllm_plan_map_host(row_ptr, src, scale, C_in)
+    assert plan[5] == n_comp
+    check_plan_decodes_to_map(plan, row_ptr, src, scale, C_in, C_out)
+
+
 @pytest.mark.parametrize("name,N,C,O", [("tiny", 64, 512, 96), ("llama7b_qkv", 48, 1000, 40),
                                         ("llama70b_down", 32, 2050, 24), ("llama70b_q_decode", 16, 777, 33)])
 def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
@@ -158,92 +259,9 @@ def test_host_helpers_match_the_oracle(oracle, name, N, C, O):
     assert np.array_equal(r["row_ptr"], c.row_ptr) and np.array_equal(r["src"], c.src)
     assert np.array_equal(r["scale"], c.scale)
     assert b.qllm_check_map_host(r["row_ptr"], r["src"], r["scale"], C) == 0
-    # the plan: header, work list, per-chunk words, general-group entries, long rows
-    plan = r["plan"]
-    n_groups, n_chunks, n_work = (c.K + 7) // 8, (C + 7) // 8, (c.K + 255) // 256 * 32
-    n_general, _, n_long, n_pub, off_work, off_chunks, off_items, off_longs, plan_len = plan[5:14].tolist()
-    n_mask, off_masks = plan[14:16].tolist()
-    assert plan[:5].tolist() == [0x514C4D50, 5, C, c.K, n_work] and plan[6] == n_chunks
-    assert off_work == 16 and off_masks == off_longs + 4 * n_long and plan_len == plan.size == off_masks + n_mask
-    assert off_chunks >= off_work + n_work and off_items >= off_chunks + n_chunks and off_longs >= off_items + 16 * n_general
-    assert off_chunks % 4 == 0 and off_items % 4 == 0 and off_longs % 4 == 0
-    work = plan[off_work:off_work + n_work].astype(np.int64) & 0xFFFFFFFF
-    kind, grp, dd = work >> 28, (work >> 15) & 0x1FFF, work & 0x7FFF
-    assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
-    assert np.all(np.diff(kind) >= 0) and np.all(kind[grp >= n_groups] == 2) and np.all(kind[grp < n_groups] < 2)
-    assert np.all(np.diff(kind * 8192 + grp) > 0)                # by kind, then by group
-    plain = kind == 0
-    desc = np.full(n_groups, -1, np.int64)
-    desc[grp[plain]] = dd[plain]
-    gen = kind == 1
-    desc[grp[gen]] = -(dd[gen] + 1)
-    chunks = plan[off_chunks:off_chunks + n_chunks].astype(np.int64) & 0xFFFFFFFF
-    passes, slots = chunks & 0xFF, chunks >> 8
-    items = plan[off_items:off_items + 16 * n_general].reshape(n_general * 8, 2)
-    longs = plan[off_longs:off_masks].reshape(-1, 4).copy()
-    assert longs.shape[0] == n_long
-    most = longs[:, 3] >> 8                                       # largest position among the 64 entries of a wavefront
-    longs[:, 3] &= 0xFF
-    for b0 in range(0, n_long, 64):
-        assert np.all(most[b0:b0 + 64] == longs[b0:b0 + 64, 3].max())
-    partial = (passes != 0) & (passes != 0xFF)
-    assert np.array_equal(plan[off_masks:].astype(np.int64) & 0xFFFFFFFF, chunks[partial])
-    used = np.zeros(n_long, bool)
-    assert (desc >= 0).sum() > 0.25 * desc.size and (desc < 0).sum() == n_general
-    expect_pass = np.zeros(n_chunks * 8, bool)
-    for g in np.nonzero(desc >= 0)[0]:       # a plain group: 8 single entries, scale 1, consecutive sources
-        e = c.row_ptr[8 * g:8 * g + 8]
-        assert np.all(np.diff(c.row_ptr[8 * g:8 * g + 9]) == 1)
-        assert np.array_equal(c.src[e], desc[g] + np.arange(8)) and np.all(c.scale[e] == 1.0)
-        expect_pass[desc[g]:desc[g] + 8] = True
-    assert np.array_equal(np.unpackbits(passes.astype(np.uint8), bitorder="little"), expect_pass.astype(np.uint8))
-    assert sorted((-desc[desc < 0] - 1).tolist()) == list(range(n_general))
-    # staging slots: 0 .. n_pub-1 in chunk order; every chunk a general group reads has one, and so has
-    # every chunk of which only some channels pass
-    has = slots != 0xFFFFFF
-    assert np.array_equal(slots[has], np.arange(n_pub))
-    assert np.all(has[(passes != 0) & (passes != 0xFF)])
-    read = np.zeros(n_chunks, bool)
-    stage = lambda ch: int(slots[ch // 8]) * 8 + ch % 8
-    for g in np.nonzero(desc < 0)[0]:        # a general group: its entries, channel by channel
-        lo, hi = 8 * g, min(8 * g + 8, c.K)
-        e = c.row_ptr[lo:hi]
-        is_plain = (hi - lo == 8 and np.all(np.diff(c.row_ptr[lo:hi + 1]) == 1) and np.all(c.scale[e] == 1.0)
-                    and np.array_equal(c.src[e], c.src[e[0]] + np.arange(8)))
-        assert not is_plain
-        read[c.src[c.row_ptr[lo]:c.row_ptr[hi]] // 8] = True
-        for k in range(8):
-            it = items[(-desc[g] - 1) * 8 + k]
-            ch = lo + k
-            if ch >= c.K:
-                assert np.array_equal(it, items[(-desc[g] - 1) * 8])      # padding repeats the first channel
-                continue
-            e0, n = c.row_ptr[ch], c.row_ptr[ch + 1] - c.row_ptr[ch]
-            if n > 2:
-                first = int(it[1]) & 0xFFFFFF
-                assert it[0] == -2 and (int(it[1]) >> 24) & 0xFF == n
-                assert first // 64 == (first + n - 1) // 64             # inside one wavefront's 64 entries
-                assert longs[first:first + n, 0].tolist() == [stage(s) for s in c.src[e0:e0 + n]]
-                assert np.array_equal(longs[first:first + n, 2].view(np.float32), c.scale[e0:e0 + n])
-                assert np.array_equal(longs[first:first + n, 3], np.arange(n))
-                assert np.all(longs[first:first + n - 1, 1] == -1)
-                assert longs[first + n - 1, 1] == (-desc[g] - 1) * 8 + k
-                assert not used[first:first + n].any()
-                used[first:first + n] = True
-                continue
-            second = stage(c.src[e0 + 1]) if n == 2 else 8 * n_pub
-            assert int(it[0]) & 0xFFFFFFFF == stage(c.src[e0]) | (second << 16)
-            assert it[1:2].view(np.float32)[0] == c.scale[e0]
-            if n == 2:
-                assert c.scale[e0 + 1] == c.scale[e0]
-    assert np.all(has[read]) and np.all(read[has] | ((passes[has] != 0) & (passes[has] != 0xFF)))
-    assert np.all(longs[~used] == np.array([0, -1, 0, 0]))            # padding entries between rows
-    # weights: reassembled, quantized per output channel and packed by the library == the oracle's
-    q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, w.w_bits)
-    assert np.array_equal(q["scale"], c.aw) and np.array_equal(q["zero"], c.bw) and np.array_equal(q["colsum"], c.cs)
-    assert q["codes"].shape[1] == b.qllm_packed_row_bytes(c.K, w.w_bits)
-    assert np.array_equal(q["codes"], oracle.pack_codes(c.wcodes, w.w_bits, q["codes"].shape[1]))
-    assert np.array_equal(b.qllm_unpack_codes_host(q["codes"], c.K, w.w_bits), c.wcodes)
+    # the plan decodes back to exactly this map
+    check_plan_decodes_to_map(r["plan"], c.row_ptr, c.src, c.scale, C, c.K)
+
 
 
 @pytest.mark.parametrize("bits", [4, 6, 8])

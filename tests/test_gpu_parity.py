@@ -7,7 +7,7 @@ scales bit-exact (same fp32 operations on both sides); dequantised outputs withi
 import numpy as np
 import pytest
 
-from helpers import NORM_ID, expected_qact, make_case, rel_err, to_torch_x
+from helpers import random_csr_map, NORM_ID, expected_qact, make_case, rel_err, to_torch_x
 from paper_2310_08041_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -115,31 +115,6 @@ def test_fused_channels_merged_from_many(oracle, b, counts, planned, C, bits):
     r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
     assert (r["plan"] is not None) == planned
     check_fused(oracle, c, run_fused(b, c, bits), bits)
-
-
-def random_csr_map(rng, C_in, C_out, special_every):
-    """Any CSR map, not only those the paper's reassembly makes: mostly shifted unscaled copies (so that
-    plain groups with every misalignment exist), every `special_every`-th row 1..5 entries with arbitrary
-    sources (repeats allowed) and arbitrary scales; some inputs are never referenced."""
-    row_ptr, src, scale = [0], [], []
-    shift = 0
-    for ch in range(C_out):
-        if ch % special_every == special_every - 1:
-            n = int(rng.integers(1, 6))
-            src += rng.integers(0, C_in, n).tolist()
-            kind = rng.integers(0, 3)
-            if kind == 0:
-                scale += [1.0] * n                                  # the "sum" convention of a merge
-            elif kind == 1:
-                scale += [float(np.float32(1.0 / n))] * n
-            else:
-                scale += rng.uniform(-2.0, 2.0, n).astype(np.float32).tolist()
-            shift = int(rng.integers(0, 9))
-        else:
-            src.append(min(max(ch + shift - 4, 0), C_in - 1))
-            scale.append(1.0)
-        row_ptr.append(len(src))
-    return np.array(row_ptr, np.int32), np.array(src, np.int32), np.array(scale, np.float32)
 
 
 @pytest.mark.parametrize("C_in,C_out,special_every,bits", [(2048, 2100, 37, 4), (8200, 8000, 61, 6), (16392, 16500, 97, 8),
