@@ -1,7 +1,9 @@
 """numpy-facing wrappers over oracle/liboracle.so (ctypes).  TEST INFRASTRUCTURE ONLY.
 
-Every function takes and returns host numpy arrays; nothing here does arithmetic of its own: each
-wrapper sizes the outputs, calls one C routine of qllm_oracle.c and raises on a non-zero status.
+Every function takes and returns host numpy arrays.  The wrappers of the hot path do no arithmetic of
+their own: each sizes the outputs, calls one C routine of qllm_oracle.c and raises on a non-zero status.
+The one exception is `fold_preceding_linear` (Appendix B, an offline weight rewrite), which is written
+out here in numpy float64.
 """
 import ctypes as C
 import os

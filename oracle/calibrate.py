@@ -12,15 +12,25 @@ Sec. 4.1.2, Appendix A, Algorithm 1) needed to manufacture a reassembly map for 
           no part (Sec. 4.1.2).
 
 Two edge lengths are provided: the plain L2 distance between activation columns over the first
-`n_match_tokens` tokens (the benchmark's policy for synthetic data: `nearest_pairs`), and the paper's
-Eq. (5), which also involves the weights (`pair_distance`, `nearest_by_eq5`, `match_pairs_eq5`).
+`n_match_tokens` tokens (the benchmark's policy for synthetic data: `nearest_by_l2`, `nearest_pairs`), and
+the paper's Eq. (5), which also involves the weights (`pair_distance`, `nearest_by_eq5`, `match_pairs_eq5`).
+Every distance is formed from explicit differences in float64, member by member.
 """
 import numpy as np
 
 from . import api
 
 
+def extra_channels(absmax, theta):
+    """sum(T_c - 1): how many channels disassembly with this threshold adds (Sec. 4.1.1)."""
+    return int((api.num_split(absmax, np.float32(theta)).astype(np.int64) - 1).sum())
+
+
 def theta_from_rule(absmax, rule):
+    """("fixed", theta) | ("tmax", T_max): theta = max(m) / T_max | ("expand", ratio): the LARGEST float32
+    threshold whose disassembly adds at least round(ratio * C) channels (Sec. 5.2 fixes theta through the
+    expansion ratio).  The number of added channels never grows with theta, so the largest such float32 is
+    found by bisection over the float32 values themselves (positive floats order like their bit patterns)."""
     kind, val = rule
     m = np.asarray(absmax, np.float32)
     if kind == "fixed":
@@ -29,54 +39,48 @@ def theta_from_rule(absmax, rule):
         return float(np.float32(m.max()) / np.float32(val))
     if kind == "expand":
         target = max(1, int(round(val * m.size)))
-        lo, hi = 0.0, float(m.max())          # extra(hi) == 0 < target; extra(lo -> 0) -> inf
-        lo = hi / 1e6
-        for _ in range(200):
-            mid = 0.5 * (lo + hi)
-            extra = int((api.num_split(m, np.float32(mid)).astype(np.int64) - 1).sum())
-            if extra >= target:
+        as_f32 = lambda bits: np.array([bits], np.uint32).view(np.float32)[0]
+        hi = int(np.array([m.max()], np.float32).view(np.uint32)[0])   # adds nothing: T = 1 everywhere
+        lo = int(np.array([m.max() * np.float32(2.0 ** -20)], np.float32).view(np.uint32)[0])  # T up to 2^20: the search floor
+        if extra_channels(m, as_f32(lo)) < target:
+            raise ValueError("no threshold above max(m) / 2^20 adds that many channels")
+        while hi - lo > 1:                                              # invariant: lo adds enough, hi does not
+            mid = (lo + hi) // 2
+            if extra_channels(m, as_f32(mid)) >= target:
                 lo = mid
             else:
                 hi = mid
-            if hi - lo <= 1e-7 * hi:
-                break
-        return float(np.float32(lo))
+        return float(as_f32(lo))
     raise ValueError(kind)
 
 
-def nearest_pairs(y, T, r, n_match_tokens=256, chunk=2048):
-    """Bipartite soft matching on the disassembled axis.  Returns (src_idx, dst_idx), int32 [r],
-    as indices into set A / set B.  Deterministic: ties go to the lower index."""
-    T = np.asarray(T, np.int64)
-    if r == 0:
-        return np.zeros(0, np.int32), np.zeros(0, np.int32)
-    chan_of = np.repeat(np.arange(T.size), T)           # disassembled position -> source channel
-    Cp = chan_of.size
-    eligible = T[chan_of] == 1
-    pos_a = np.arange(0, Cp, 2)
-    pos_b = np.arange(1, Cp, 2)
-    pos_a = pos_a[eligible[pos_a]]
-    pos_b = pos_b[eligible[pos_b]]
-    if pos_a.size == 0 or pos_b.size == 0:
-        return np.zeros(0, np.int32), np.zeros(0, np.int32)
-    r = min(r, pos_a.size)                              # tiny layers: merge what can be merged
+def nearest_by_l2(y, T, n_match_tokens=256):
+    """Appendix A step 2 with the plain squared L2 distance between activation columns,
+    D(i, j) = sum over tokens of (y[n, i] - y[n, j])^2: for every member of set A its nearest member of
+    set B, the lowest index on ties.  Differences formed explicitly, in float64.
+    Returns (best_j, best_d, pos_a, pos_b) like nearest_by_eq5."""
+    chan_of, pos_a, pos_b = matching_sets(T)
     ys = np.asarray(y[:n_match_tokens], np.float64)
-    cols_a = ys[:, chan_of[pos_a]]                      # [n, |A|]
-    cols_b = ys[:, chan_of[pos_b]]                      # [n, |B|]
-    nb2 = (cols_b * cols_b).sum(0)
-    best_d = np.empty(pos_a.size)
+    xb = ys[:, chan_of[pos_b]].T                          # [|B|, n]
     best_j = np.empty(pos_a.size, np.int64)
-    for s in range(0, pos_a.size, chunk):
-        a = cols_a[:, s:s + chunk]
-        d2 = (a * a).sum(0)[:, None] + nb2[None, :] - 2.0 * (a.T @ cols_b)
-        j = d2.argmin(1)
-        best_j[s:s + chunk] = j
-        best_d[s:s + chunk] = d2[np.arange(j.size), j]
-    pick = np.argsort(best_d, kind="stable")[:r]
-    pick.sort()
-    src_idx = (pos_a[pick] // 2).astype(np.int32)
-    dst_idx = ((pos_b[best_j[pick]] - 1) // 2).astype(np.int32)
-    return src_idx, dst_idx
+    best_d = np.empty(pos_a.size, np.float64)
+    for k in range(pos_a.size):
+        dx = xb - ys[:, chan_of[pos_a[k]]][None, :]
+        d = (dx * dx).sum(1)
+        j = int(d.argmin())                               # numpy returns the first minimum
+        best_j[k], best_d[k] = j, d[j]
+    return best_j, best_d, pos_a, pos_b
+
+
+def nearest_pairs(y, T, r, n_match_tokens=256):
+    """Appendix A steps 1-3 with the plain L2 distance (the benchmark's policy for synthetic activations,
+    which come without trained weights).  Returns (src_idx, dst_idx), int32 [min(r, |A|)], as indices into
+    set A / set B."""
+    chan_of, pos_a, pos_b = matching_sets(T)
+    if r == 0 or pos_a.size == 0 or pos_b.size == 0:
+        return np.zeros(0, np.int32), np.zeros(0, np.int32)
+    best_j, best_d, pos_a, pos_b = nearest_by_l2(y, T, n_match_tokens)
+    return select_edges(best_d, best_j, pos_a, pos_b, r)
 
 
 def matching_sets(T):

@@ -1,6 +1,7 @@
-"""Pins for the oracle's bipartite soft matching with the distance of Eq. (5) (Sec. 4.1.2,
-Appendix A): the distance against the merging error it is defined to measure (computed through the
-oracle's own, independent assembly code), brute force on tiny inputs, a case worked by hand."""
+"""Pins for the oracle's bipartite soft matching (Sec. 4.1.2, Appendix A) with the distance of Eq. (5) and
+with the plain L2 distance of the benchmark configurations: the distance against the merging error it
+is defined to measure (computed through the oracle's own, independent assembly code), brute force on
+tiny inputs, cases worked by hand including ties; and the threshold rule of the configurations."""
 import numpy as np
 import pytest
 
@@ -118,3 +119,74 @@ def test_grid_search_prefers_reassembly_when_there_are_outliers(oracle):
     plain = oracle.reassembled_linear(x, 0, None, None, 0.0, np.ones(C, np.int32), [], [], 4, wq)["y"]
     ref = x.astype(np.float64) @ W.astype(np.float64)
     assert np.isclose(((plain - ref) ** 2).sum(), loss_plain, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- plain L2 matching (the configurations' "nearest-L2 pairs")
+
+def test_l2_matching_by_hand():
+    """Six channels, two tokens.  A = channels 0, 2, 4; B = 1, 3, 5.  Squared distances, token by token:
+         channel 0 = (0, 0): to 1 = (3, 4): 25;  to 3 = (0, 5): 25;  to 5 = (1, 1): 2    -> B-member 2, distance 2
+         channel 2 = (3, 0): to 1: 0 + 16 = 16;  to 3: 9 + 25 = 34;  to 5: 4 + 1 = 5     -> B-member 2, distance 5
+         channel 4 = (0, 1): to 1: 9 + 9 = 18;   to 3: 0 + 16 = 16;  to 5: 1 + 0 = 1     -> B-member 2, distance 1
+       and with channel 5 moved to (6, 8): channel 0 sees 25, 25, 100: a tie, which goes to the LOWER member."""
+    y = np.array([[0, 3, 3, 0, 0, 1], [0, 4, 0, 5, 1, 1]], np.float32)
+    T = np.ones(6, np.int32)
+    best_j, best_d, pos_a, pos_b = calibrate.nearest_by_l2(y, T)
+    assert best_j.tolist() == [2, 2, 2] and best_d.tolist() == [2.0, 5.0, 1.0]
+    assert pos_a.tolist() == [0, 2, 4] and pos_b.tolist() == [1, 3, 5]
+    src_idx, dst_idx = calibrate.nearest_pairs(y, T, 2)                 # the two shortest edges: from channels 4 and 0
+    assert src_idx.tolist() == [0, 2] and dst_idx.tolist() == [2, 2]
+    y[:, 5] = [6, 8]
+    best_j, best_d, _, _ = calibrate.nearest_by_l2(y, T)
+    # channel 0: 25, 25, 100 -> member 0 (tie);  channel 2: 16, 34, 9 + 64 -> member 0;  channel 4: 18, 16, 36 + 49 -> member 1
+    assert best_j.tolist() == [0, 0, 1] and best_d.tolist() == [25.0, 16.0, 16.0]
+    src_idx, dst_idx = calibrate.nearest_pairs(y, T, 1)                 # 16 twice: the lower member of A (channel 2) wins
+    assert src_idx.tolist() == [1] and dst_idx.tolist() == [0]
+    # only the first n_match_tokens tokens count
+    best_j, best_d, _, _ = calibrate.nearest_by_l2(y, T, n_match_tokens=1)
+    assert best_d.tolist() == [0.0, 0.0, 0.0] and best_j.tolist() == [1, 0, 1]   # token 0 alone: (0, 3, 3, 0, 0, 6)
+
+
+def test_l2_matching_against_brute_force():
+    """Every A x B pair with explicit differences in Python floats; sub-channels of split channels excluded."""
+    rng = np.random.default_rng(15)
+    C, N = 29, 4
+    y = rng.integers(-2, 3, (N, C)).astype(np.float32)          # small integers: distances are exact, ties do occur
+    T = np.ones(C, np.int32)
+    T[[3, 20]] = [2, 4]
+    best_j, best_d, pos_a, pos_b = calibrate.nearest_by_l2(y, T)
+    chan_of = np.repeat(np.arange(C), T)
+    assert not np.isin(chan_of[pos_a], [3, 20]).any() and not np.isin(chan_of[pos_b], [3, 20]).any()
+    ties = 0
+    for k, pa in enumerate(pos_a):
+        ds = [sum((float(y[n, chan_of[pa]]) - float(y[n, chan_of[pb]])) ** 2 for n in range(N)) for pb in pos_b]
+        assert best_d[k] == min(ds) and best_j[k] == ds.index(min(ds))     # list.index: the first minimum
+        ties += ds.count(min(ds)) > 1
+    assert ties > 0
+    r = 6
+    src_idx, dst_idx = calibrate.nearest_pairs(y, T, r)
+    order = sorted(range(pos_a.size), key=lambda k: (best_d[k], k))[:r]     # shortest edges, ties to the lower A member
+    assert src_idx.tolist() == sorted(int(pos_a[k]) // 2 for k in order)
+    assert sorted(zip(src_idx.tolist(), dst_idx.tolist())) == sorted((int(pos_a[k]) // 2, (int(pos_b[best_j[k]]) - 1) // 2) for k in order)
+
+
+def test_expansion_threshold_is_the_largest_that_adds_enough(oracle):
+    """("expand", ratio): theta adds at least round(ratio * C) channels and the next float32 above it does not;
+    on a hand case the breakpoints are known: m = (1, 2, 12), one added channel needs theta < 12, two need
+    theta < 6 (12 -> 3 sub-channels) ... the largest float32 below each breakpoint."""
+    m = np.array([1.0, 2.0, 12.0], np.float32)
+    below = lambda v: float(np.nextafter(np.float32(v), np.float32(0)))
+    for target, edge in [(1, 12.0), (2, 6.0), (3, 4.0), (4, 3.0), (5, 2.4)]:
+        th = calibrate.theta_from_rule(m, ("expand", target / 3.0))
+        assert calibrate.extra_channels(m, th) >= target
+        assert calibrate.extra_channels(m, np.nextafter(np.float32(th), np.float32(np.inf))) < target
+        if edge in (12.0, 6.0, 4.0, 3.0):                                   # exact quotients: theta is the float below the edge
+            assert th == below(edge)
+    rng = np.random.default_rng(16)
+    m = np.abs(rng.standard_normal(300)).astype(np.float32)
+    m[[7, 90]] *= 40
+    for ratio in (0.01, 0.05, 0.3):
+        th = calibrate.theta_from_rule(m, ("expand", ratio))
+        target = max(1, int(round(ratio * m.size)))
+        assert int((oracle.num_split(m, th).astype(np.int64) - 1).sum()) >= target
+        assert int((oracle.num_split(m, np.nextafter(np.float32(th), np.float32(np.inf))).astype(np.int64) - 1).sum()) < target

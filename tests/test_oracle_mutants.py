@@ -235,6 +235,28 @@ def _nearest(real, keep_quarter=True, use_weights=True, ties_high=False):
     return planted
 
 
+def _nearest_l2(farthest=False, ties_high=False):
+    def planted(y, T, n_match_tokens=256):
+        from oracle import calibrate
+        chan_of, pos_a, pos_b = calibrate.matching_sets(T)
+        ys = np.asarray(y[:n_match_tokens], np.float64)
+        best_j, best_d = np.empty(pos_a.size, np.int64), np.empty(pos_a.size)
+        for k in range(pos_a.size):
+            d = ((ys[:, chan_of[pos_b]].T - ys[:, chan_of[pos_a[k]]][None, :]) ** 2).sum(1)
+            want = d.max() if farthest else d.min()
+            hits = np.flatnonzero(d == want)
+            j = int(hits[-1] if ties_high else hits[0])
+            best_j[k], best_d[k] = j, d[j]
+        return best_j, best_d, pos_a, pos_b
+    return planted
+
+
+def _theta_one_float_up(absmax, rule):
+    from oracle import calibrate
+    th = _REAL_THETA_RULE(absmax, rule)
+    return float(np.nextafter(np.float32(th), np.float32(np.inf))) if rule[0] == "expand" else th
+
+
 def _sets_with_sub_channels(T):
     T = np.asarray(T, np.int64)
     chan_of = np.repeat(np.arange(T.size), T)
@@ -252,6 +274,9 @@ def _grid_from_zero(absmax, P):
     return [float(np.float32(m.min() + (p / P) * (m.max() - m.min()))) for p in range(0, P)]
 
 
+from oracle import calibrate as _calibrate_module
+_REAL_THETA_RULE = _calibrate_module.theta_from_rule
+
 MATCHING_CASES = [
     ("Eq. (5): second term with the wrong sign", "pair_distance", _distance_second_term_sign,
      [tm.test_distance_is_the_output_error_of_merging, tm.test_distance_properties]),
@@ -263,6 +288,12 @@ MATCHING_CASES = [
      [tm.test_nearest_by_eq5_against_brute_force]),
     ("the r longest edges are merged", "select_edges", _select_longest, [tm.test_matching_by_hand]),
     ("theta grid starts at min(m)", "theta_grid", _grid_from_zero, [tm.test_theta_grid_is_algorithm_1]),
+    ("L2 matching: the FARTHEST member of B", "nearest_by_l2", _nearest_l2(farthest=True),
+     [tm.test_l2_matching_by_hand, tm.test_l2_matching_against_brute_force]),
+    ("L2 matching: ties to the higher member", "nearest_by_l2", _nearest_l2(ties_high=True),
+     [tm.test_l2_matching_by_hand, tm.test_l2_matching_against_brute_force]),
+    ("expansion threshold one float32 too large", "theta_from_rule", _theta_one_float_up,
+     [tm.test_expansion_threshold_is_the_largest_that_adds_enough]),
 ]
 
 
