@@ -70,8 +70,8 @@ def bench_matching(args, w, norm, dev):
     T = b.qllm_build_map_host(m, theta, [], [], with_plan=False)["num_split"]
     W_host = wl.draw_weight(w)
     W = torch.from_numpy(W_host).to(dev)
-    chan_of, pos_a, pos_b = calibrate.matching_sets(T, dev)
-    chan_a, chan_b = chan_of[pos_a].to(torch.int32).contiguous(), chan_of[pos_b].to(torch.int32).contiguous()
+    sets = b.qllm_matching_sets_host(T)
+    chan_a, chan_b = torch.from_numpy(sets["chan_a"]).to(dev), torch.from_numpy(sets["chan_b"]).to(dev)
     nA, nB = chan_a.numel(), chan_b.numel()
     best_j = torch.empty(nA, dtype=torch.int32, device=dev)
     best_d = torch.empty(nA, dtype=torch.float64, device=dev)

@@ -162,6 +162,8 @@ int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64
  *     D(i, j) = | x_i (W_i - W_j) / 2 + x_j (W_j - W_i) / 2 |^2 = |x_i - x_j|^2 |W_i - W_j|^2 / 4,
  * x_c = column c of y over the n calibration tokens, W_c = row c of W over the O output features.
  * Arithmetic in double precision on the fp64 matrix cores; ties go to the lower j.
+ * With W == NULL (O, ldw ignored) the distance is the plain D(i, j) = |x_i - x_j|^2: matching on the
+ * activations alone, for layers whose weights are not at hand.
  *   y        [n, ldy] fp32 activations after the norm (ldy >= C); W [C, ldw] fp32 (ldw >= O)
  *   chan_a   [nA], chan_b [nB] int32 channel numbers in [0, C) (device arrays, trusted)
  *   best_j   [nA] int32: index into chan_b;   best_d [nA] double: the distance
@@ -177,6 +179,43 @@ int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, const float *
                            int32_t *best_j, double *best_d, void *workspace, int64_t workspace_bytes,
                            void *hip_stream);
 int64_t qllm_select_edges_host(const double *best_d, int64_t nA, int64_t r, int32_t *pick_out);
+
+/* The host-side steps around that search.  HOST pointers.
+ * qllm_matching_sets_host: Appendix A step 1 on the disassembled axis (channel c occupies num_split[c]
+ *   adjacent positions): set A = even positions, set B = odd positions, and only channels that were not split
+ *   take part (Sec. 4.1.2).  Outputs, each sized C by the caller: the members' channels and positions, in
+ *   ascending order, and their counts.  QLLM_ERR_MAP for a split count below 1.
+ * qllm_pairs_host: Appendix A step 3 in the indexing of the paper's run-time pseudo-code: the min(r, nA)
+ *   shortest edges (ties to the lower member of A, as qllm_select_edges_host), written as src_idx[k] = number of
+ *   the A-member among the even positions, dst_idx[k] = number of its B-member among the odd positions, ascending
+ *   in src_idx: the arguments qllm_build_map_host takes.  best_j / best_d as qllm_match_nearest returns them
+ *   (copied to the host).  Returns the count (negative = qllm_status).
+ * qllm_theta_for_expansion_host: the largest float32 theta whose disassembly adds at least extra_target
+ *   channels, sum_c (T_c - 1) >= extra_target (Sec. 5.2 fixes theta through the expansion ratio; the count never
+ *   grows with theta).  QLLM_ERR_SHAPE if no theta above max(m) / 2^20 does.
+ * qllm_theta_grid_host: Algorithm 1's candidates theta_p = min(m) + p / P (max(m) - min(m)), p = 1 .. P, formed in
+ *   double and rounded once. */
+int32_t qllm_matching_sets_host(const int32_t *num_split, int64_t C, int32_t *chan_a, int32_t *pos_a, int64_t *nA,
+                                int32_t *chan_b, int32_t *pos_b, int64_t *nB);
+int64_t qllm_pairs_host(const double *best_d, const int32_t *best_j, const int32_t *pos_a, const int32_t *pos_b, int64_t nA,
+                        int64_t nB, int64_t r, int32_t *src_idx, int32_t *dst_idx);
+int32_t qllm_theta_for_expansion_host(const float *chan_absmax, int64_t C, int64_t extra_target, float *theta);
+int32_t qllm_theta_grid_host(const float *chan_absmax, int64_t C, int32_t P, float *thetas);
+
+/* What Algorithm 1 scores a candidate theta with, for one linear layer: the squared error of the quantized
+ * layer's output against the full-precision layer (the paper scores a whole attention block through Eq. (6);
+ * a single linear layer has no softmax to go through, so the error is taken at the layer's own output).
+ * DEVICE pointers.
+ *   qllm_linear_f64   out[n, o] = sum_c y[n, c] W[c, o], products and sums in double, c ascending.
+ *                     y [N, ldy] fp32, W [C, ldw] fp32, out [N, ldo] double.
+ *   qllm_sq_error     *result (one device double) = sum over n, o of (got[n, o] - ref[n, o])^2 in double, in a
+ *                     fixed order.  got [N, ldg] fp32 or bf16, ref [N, ldr] double; workspace of
+ *                     qllm_sq_error_workspace_bytes(N) bytes, 8-byte aligned. */
+int32_t qllm_linear_f64(const float *y, int64_t N, int64_t C, int64_t ldy, const float *W, int64_t O, int64_t ldw,
+                        double *out, int64_t ldo, void *hip_stream);
+int64_t qllm_sq_error_workspace_bytes(int64_t N);
+int32_t qllm_sq_error(const void *got, int32_t got_dtype, int64_t N, int64_t O, int64_t ldg, const double *ref,
+                      int64_t ldr, double *result, void *workspace, int64_t workspace_bytes, void *hip_stream);
 
 /* Sizes.  Negative return = qllm_status. */
 int64_t qllm_packed_row_bytes(int64_t K, int32_t bits);
@@ -293,19 +332,6 @@ int32_t qllm_unpack_codes_host(const uint8_t *packed, int64_t R, int64_t K, int3
 int32_t qllm_norm_channel_absmax(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
                                  int32_t norm, const float *gamma, const float *beta, float eps,
                                  float *absmax, float *y_dump, int64_t n_dump, void *hip_stream);
-
-/* ------------------------------------------------------------------------------------------
- * Measurement probes (no part of the method; for callers that price the two kernels above against
- * what the machine delivers rather than against the data-sheet peaks).
- *   qllm_probe_mfma    `workgroups` workgroups of 8 waves; every wave issues iters * 32 int8 matrix-core
- *                      operations (16 x 16 x 64 each, i.e. 2 * 16384 integer operations) on register
- *                      operands shaped like 4-bit codes and touches no memory.  sink: one device int32.
- *   qllm_probe_stream  reads `bytes` (a multiple of 16) from src and writes bytes / 4 to dst: the 4 : 1
- *                      read : write mix of the fused kernel with bf16 input and 4-bit codes.
- * Errors: NULL / SHAPE / ALIGN (src 16-byte, dst 4-byte aligned) / HIP.
- */
-int32_t qllm_probe_mfma(int32_t workgroups, int32_t iters, int32_t *sink, void *hip_stream);
-int32_t qllm_probe_stream(const void *src, void *dst, int64_t bytes, int32_t workgroups, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -69,6 +69,13 @@ _sigs = {
     "qllm_match_workspace_bytes": (_i64, [_i64, _i64]),
     "qllm_match_nearest": (_i32, [_vp, _i64, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp]),
     "qllm_select_edges_host": (_i64, [_vp, _i64, _i64, _vp]),
+    "qllm_matching_sets_host": (_i32, [_vp, _i64, _vp, _vp, C.POINTER(_i64), _vp, _vp, C.POINTER(_i64)]),
+    "qllm_pairs_host": (_i64, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp]),
+    "qllm_theta_for_expansion_host": (_i32, [_vp, _i64, _i64, C.POINTER(_f)]),
+    "qllm_theta_grid_host": (_i32, [_vp, _i64, _i32, _vp]),
+    "qllm_linear_f64": (_i32, [_vp, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
+    "qllm_sq_error_workspace_bytes": (_i64, [_i64]),
+    "qllm_sq_error": (_i32, [_vp, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp]),
     "qllm_probe_mfma": (_i32, [_i32, _i32, _vp, _vp]),
     "qllm_probe_stream": (_i32, [_vp, _vp, _i64, _i32, _vp]),
 }
@@ -324,9 +331,11 @@ def qllm_match_workspace_bytes(nA, nB):
 
 
 def qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, workspace, stream=None):
-    """y [n, C] fp32, W [C, O] fp32, chan_a / chan_b int32, best_j [nA] int32, best_d [nA] float64: device tensors."""
+    """y [n, C] fp32, W [C, O] fp32 or None (plain L2 on the activations), chan_a / chan_b int32, best_j [nA] int32,
+    best_d [nA] float64: device tensors."""
     n, Cc = y.shape
-    _chk(_lib.qllm_match_nearest(_dp(y), n, y.stride(0), _dp(W), Cc, W.shape[1], W.stride(0), _dp(chan_a),
+    O, ldw = (0, 0) if W is None else (W.shape[1], W.stride(0))
+    _chk(_lib.qllm_match_nearest(_dp(y), n, y.stride(0), _dp(W), Cc, O, ldw, _dp(chan_a),
                                  chan_a.numel(), _dp(chan_b), chan_b.numel(), _dp(best_j), _dp(best_d),
                                  _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
                                  _stream(stream)), "qllm_match_nearest")
@@ -341,6 +350,68 @@ def qllm_select_edges_host(best_d, r):
     if n < 0:
         _chk(n, "qllm_select_edges_host")
     return pick[:n]
+
+
+def qllm_matching_sets_host(num_split):
+    """num_split [C] int32 (host) -> dict(chan_a, pos_a, chan_b, pos_b) of int32 arrays: Appendix A step 1."""
+    T = _np(num_split, np.int32)
+    out = [np.empty(T.size, np.int32) for _ in range(4)]
+    nA, nB = _i64(0), _i64(0)
+    _chk(_lib.qllm_matching_sets_host(_hp(T), T.size, _hp(out[0]), _hp(out[1]), C.byref(nA), _hp(out[2]), _hp(out[3]),
+                                      C.byref(nB)), "qllm_matching_sets_host")
+    return dict(chan_a=out[0][:nA.value].copy(), pos_a=out[1][:nA.value].copy(), chan_b=out[2][:nB.value].copy(),
+                pos_b=out[3][:nB.value].copy())
+
+
+def qllm_pairs_host(best_d, best_j, pos_a, pos_b, r):
+    """Appendix A step 3: (src_idx, dst_idx) int32 arrays of the min(r, |A|) shortest edges."""
+    best_d, best_j = _np(best_d, np.float64), _np(best_j, np.int32)
+    pos_a, pos_b = _np(pos_a, np.int32), _np(pos_b, np.int32)
+    n_max = min(int(r), pos_a.size)
+    src_idx, dst_idx = np.empty(max(n_max, 1), np.int32), np.empty(max(n_max, 1), np.int32)
+    n = int(_lib.qllm_pairs_host(_hp(best_d), _hp(best_j), _hp(pos_a), _hp(pos_b), pos_a.size, pos_b.size, int(r),
+                                 _hp(src_idx), _hp(dst_idx)))
+    if n < 0:
+        _chk(n, "qllm_pairs_host")
+    return src_idx[:n].copy(), dst_idx[:n].copy()
+
+
+def qllm_theta_for_expansion_host(chan_absmax, extra_target):
+    m = _np(chan_absmax, np.float32)
+    theta = _f(0.0)
+    _chk(_lib.qllm_theta_for_expansion_host(_hp(m), m.size, int(extra_target), C.byref(theta)), "qllm_theta_for_expansion_host")
+    return float(theta.value)
+
+
+def qllm_theta_grid_host(chan_absmax, P):
+    m = _np(chan_absmax, np.float32)
+    out = np.empty(int(P), np.float32)
+    _chk(_lib.qllm_theta_grid_host(_hp(m), m.size, int(P), _hp(out)), "qllm_theta_grid_host")
+    return [float(v) for v in out]
+
+
+def qllm_linear_f64(y, W, out, stream=None):
+    """y [N, C] fp32, W [C, O] fp32, out [N, O] float64: device tensors."""
+    assert y.is_cuda and W.is_cuda and out.is_cuda and y.dtype == W.dtype == torch.float32 and out.dtype == torch.float64
+    assert y.shape[1] == W.shape[0] and out.shape == (y.shape[0], W.shape[1])
+    assert y.stride(1) == 1 and W.stride(1) == 1 and out.stride(1) == 1
+    _chk(_lib.qllm_linear_f64(_dp(y), y.shape[0], y.shape[1], y.stride(0), _dp(W), W.shape[1], W.stride(0), _dp(out),
+                              out.stride(0), _stream(stream)), "qllm_linear_f64")
+    return out
+
+
+def qllm_sq_error_workspace_bytes(N):
+    return int(_lib.qllm_sq_error_workspace_bytes(int(N)))
+
+
+def qllm_sq_error(got, ref, result, workspace, stream=None):
+    """got [N, O] fp32 / bf16, ref [N, O] float64, result [1] float64, workspace uint8: device tensors."""
+    assert got.is_cuda and ref.is_cuda and result.is_cuda and ref.dtype == result.dtype == torch.float64
+    assert got.shape == ref.shape and got.stride(1) == 1 and ref.stride(1) == 1 and result.numel() >= 1
+    _chk(_lib.qllm_sq_error(_dp(got), _x_dtype(got), got.shape[0], got.shape[1], got.stride(0), _dp(ref), ref.stride(0),
+                            _dp(result), _dp(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+         "qllm_sq_error")
+    return result
 
 
 def qllm_probe_mfma(workgroups, iters, sink, stream=None):

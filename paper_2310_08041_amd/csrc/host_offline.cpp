@@ -283,6 +283,118 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     return QLLM_OK;
 }
 
+// ---------------------------------------------------------------- offline: thresholds, matching sets, edges
+
+namespace {
+
+inline int64_t split_count(float m, float theta)
+{
+    const double q = std::ceil((double)m / (double)theta); // Sec. 4.1.1: T = ceil(max|x| / theta), at least 1
+    return q < 1.0 ? 1 : (int64_t)q;
+}
+
+int64_t extra_channels(const float *m, int64_t C, float theta)
+{
+    int64_t extra = 0;
+    for (int64_t c = 0; c < C; ++c) extra += split_count(m[c], theta) - 1;
+    return extra;
+}
+
+inline float from_bits(uint32_t u)
+{
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+inline uint32_t to_bits(float f)
+{
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    return u;
+}
+
+} // namespace
+
+int32_t qllm_theta_for_expansion_host(const float *chan_absmax, int64_t C, int64_t extra_target, float *theta)
+{
+    if (!chan_absmax || !theta) return QLLM_ERR_NULL;
+    if (C <= 0 || extra_target <= 0) return QLLM_ERR_SHAPE;
+    float top = 0.0f;
+    for (int64_t c = 0; c < C; ++c) {
+        if (!(chan_absmax[c] >= 0.0f) || !std::isfinite(chan_absmax[c])) return QLLM_ERR_SHAPE;
+        top = std::max(top, chan_absmax[c]);
+    }
+    // Channels added never increase with theta, and positive floats order like their bit patterns: step
+    // through the patterns between max(m) / 2^20 (every T at most 2^20) and max(m) (nothing is split).
+    uint32_t lo = to_bits(top * 9.5367431640625e-07f), hi = to_bits(top);
+    if (top <= 0.0f || extra_channels(chan_absmax, C, from_bits(lo)) < extra_target) return QLLM_ERR_SHAPE;
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if (extra_channels(chan_absmax, C, from_bits(mid)) >= extra_target) lo = mid;
+        else hi = mid;
+    }
+    *theta = from_bits(lo);
+    return QLLM_OK;
+}
+
+int32_t qllm_theta_grid_host(const float *chan_absmax, int64_t C, int32_t P, float *thetas)
+{
+    if (!chan_absmax || !thetas) return QLLM_ERR_NULL;
+    if (C <= 0 || P <= 0) return QLLM_ERR_SHAPE;
+    double lo = chan_absmax[0], hi = chan_absmax[0];
+    for (int64_t c = 1; c < C; ++c) {
+        lo = std::min(lo, (double)chan_absmax[c]);
+        hi = std::max(hi, (double)chan_absmax[c]);
+    }
+    for (int32_t p = 1; p <= P; ++p) thetas[p - 1] = (float)(lo + ((double)p / (double)P) * (hi - lo));
+    return QLLM_OK;
+}
+
+int32_t qllm_matching_sets_host(const int32_t *num_split, int64_t C, int32_t *chan_a, int32_t *pos_a, int64_t *nA,
+                                int32_t *chan_b, int32_t *pos_b, int64_t *nB)
+{
+    if (!num_split || !chan_a || !pos_a || !nA || !chan_b || !pos_b || !nB) return QLLM_ERR_NULL;
+    if (C <= 0) return QLLM_ERR_SHAPE;
+    int64_t at = 0, na = 0, nb = 0; // position on the disassembled axis
+    for (int64_t c = 0; c < C; ++c) {
+        const int32_t T = num_split[c];
+        if (T < 1) return QLLM_ERR_MAP;
+        if (T == 1) { // only channels that were not split take part
+            if (at > INT32_MAX) return QLLM_ERR_SHAPE;
+            if (at % 2 == 0) {
+                chan_a[na] = (int32_t)c;
+                pos_a[na++] = (int32_t)at;
+            } else {
+                chan_b[nb] = (int32_t)c;
+                pos_b[nb++] = (int32_t)at;
+            }
+        }
+        at += T;
+    }
+    *nA = na;
+    *nB = nb;
+    return QLLM_OK;
+}
+
+int64_t qllm_pairs_host(const double *best_d, const int32_t *best_j, const int32_t *pos_a, const int32_t *pos_b, int64_t nA,
+                        int64_t nB, int64_t r, int32_t *src_idx, int32_t *dst_idx)
+{
+    if (nA < 0 || nB < 0 || r < 0) return QLLM_ERR_SHAPE;
+    if (r == 0 || nA == 0 || nB == 0) return 0;
+    if (!best_d || !best_j || !pos_a || !pos_b || !src_idx || !dst_idx) return QLLM_ERR_NULL;
+    std::vector<int32_t> pick((size_t)std::min(r, nA));
+    const int64_t n = qllm_select_edges_host(best_d, nA, r, pick.data());
+    if (n < 0) return n;
+    for (int64_t k = 0; k < n; ++k) {
+        const int32_t i = pick[(size_t)k], j = best_j[i];
+        if (j < 0 || j >= nB || pos_a[i] % 2 != 0 || pos_b[j] % 2 != 1) return QLLM_ERR_MAP;
+        src_idx[k] = pos_a[i] / 2;       // member number in set A: the even positions
+        dst_idx[k] = (pos_b[j] - 1) / 2; // member number in set B: the odd positions
+    }
+    return n;
+}
+
 int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale,
                             int64_t C_in, int64_t C_out, int64_t nnz)
 {

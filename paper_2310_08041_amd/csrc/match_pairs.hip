@@ -54,10 +54,12 @@ __global__ __launch_bounds__(THREADS) void match_norms_kernel(const MatchArgs g,
         const double v = (double)g.y[(int64_t)t * g.ldy + c];
         sx += v * v;
     }
-    const float *wr = g.w + (int64_t)c * g.ldw;
-    for (int k = tid; k < g.O; k += THREADS) {
-        const double v = (double)wr[k];
-        sw += v * v;
+    if (g.w) {
+        const float *wr = g.w + (int64_t)c * g.ldw;
+        for (int k = tid; k < g.O; k += THREADS) {
+            const double v = (double)wr[k];
+            sw += v * v;
+        }
     }
     for (int off = 32; off > 0; off >>= 1) {
         sx += __shfl_xor(sx, off);
@@ -246,7 +248,9 @@ __device__ __forceinline__ void gram_pass_w_dma(const MatchArgs &g, const int32_
     __syncthreads();
 }
 
-template <int MODE> // 0: 4-byte loads; 1: 16-byte loads of weight rows; 2: weight rows straight into LDS
+// MODE 0: 4-byte loads; 1: 16-byte loads of weight rows; 2: weight rows straight into LDS.
+// L2: no weights, the distance is |x_i - x_j|^2 alone.
+template <int MODE, bool L2 = false>
 __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs g)
 {
     extern __shared__ __align__(16) double tiles[];
@@ -301,8 +305,12 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
 #pragma unroll
             for (int tj = 0; tj < 2; ++tj) gx[ti][tj] = gw[ti][tj] = v4d{0.0, 0.0, 0.0, 0.0};
         gram_pass<true, MODE != 0>(g, ca, cb, as, bs, tid, gx);
-        if constexpr (MODE == 2) gram_pass_w_dma(g, ca, cb, reinterpret_cast<float *>(tiles), tid, gw);
-        else gram_pass<false, MODE != 0>(g, ca, cb, as, bs, tid, gw);
+        if constexpr (L2) {
+        } else if constexpr (MODE == 2) {
+            gram_pass_w_dma(g, ca, cb, reinterpret_cast<float *>(tiles), tid, gw);
+        } else {
+            gram_pass<false, MODE != 0>(g, ca, cb, as, bs, tid, gw);
+        }
         // distances of this tile; element r of an accumulator: row (lane >> 4) + 4 r, column lane & 15
         // (checked against the oracle: the fp64 operation interleaves the rows of its four result registers)
 #pragma unroll
@@ -318,7 +326,7 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
                     double sw = na_w[il] + bw - 2.0 * gw[ti][tj][r];
                     sx = sx < 0.0 ? 0.0 : sx; // round-off of a difference that is zero
                     sw = sw < 0.0 ? 0.0 : sw;
-                    const double d = 0.25 * sx * sw;
+                    const double d = L2 ? sx : 0.25 * sx * sw;
                     if (j < g.nB && (d < best_d[ti][r] || (d == best_d[ti][r] && j < best_j[ti][r]))) {
                         best_d[ti][r] = d;
                         best_j[ti][r] = j;
@@ -395,8 +403,9 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
                                       int64_t nB, int32_t *best_j, double *best_d, void *workspace,
                                       int64_t workspace_bytes, void *hip_stream)
 {
-    if (!y || !W || !chan_a || !chan_b || !best_j || !best_d) return QLLM_ERR_NULL;
-    if (n <= 0 || C <= 0 || O <= 0 || ldy < C || ldw < O || nA < 0 || nB < 0) return QLLM_ERR_SHAPE;
+    if (!y || !chan_a || !chan_b || !best_j || !best_d) return QLLM_ERR_NULL;
+    if (n <= 0 || C <= 0 || ldy < C || nA < 0 || nB < 0) return QLLM_ERR_SHAPE;
+    if (W && (O <= 0 || ldw < O)) return QLLM_ERR_SHAPE;
     if (n > INT32_MAX || O > INT32_MAX || C > INT32_MAX || nA > INT32_MAX - TA || nB > INT32_MAX - TB) return QLLM_ERR_SHAPE;
     if (nA == 0) return QLLM_OK;
     if (nB == 0) return QLLM_ERR_SHAPE; // nothing to match against
@@ -417,14 +426,15 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     hipLaunchKernelGGL(match_norms_kernel, dim3((unsigned)(nA + nB)), dim3(THREADS), 0, stream, g,
                        static_cast<double *>(workspace));
     // 16-byte loads of weight rows where every row allows them, straight into LDS where the K-steps come out even
-    const bool vec = (reinterpret_cast<uintptr_t>(W) & 15u) == 0 && (ldw & 3) == 0;
-    const int mode = vec ? (O % KT == 0 ? 2 : 1) : 0;
-    const void *fn = mode == 2   ? reinterpret_cast<const void *>(&match_nearest_kernel<2>)
+    const bool vec = W && (reinterpret_cast<uintptr_t>(W) & 15u) == 0 && (ldw & 3) == 0;
+    const int mode = !W ? 3 : vec ? (O % KT == 0 ? 2 : 1) : 0; // 3: plain L2, no weights
+    const void *fn = mode == 3   ? reinterpret_cast<const void *>(&match_nearest_kernel<0, true>)
+                     : mode == 2 ? reinterpret_cast<const void *>(&match_nearest_kernel<2>)
                      : mode == 1 ? reinterpret_cast<const void *>(&match_nearest_kernel<1>)
                                  : reinterpret_cast<const void *>(&match_nearest_kernel<0>);
     { // the LDS limit is raised once per kernel; later calls (also under stream capture) only launch
         static std::mutex lock;
-        static bool raised[3] = {false, false, false};
+        static bool raised[4] = {false, false, false, false};
         std::lock_guard<std::mutex> hold(lock);
         if (!raised[mode]) {
             const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TILE_LDS);
@@ -438,7 +448,8 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     }
     const int64_t n_a_tiles = (nA + TA - 1) / TA;
     const dim3 grid((unsigned)((n_a_tiles + 7) / 8 * 8 * g.splits));
-    if (mode == 2) hipLaunchKernelGGL(match_nearest_kernel<2>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    if (mode == 3) hipLaunchKernelGGL((match_nearest_kernel<0, true>), grid, dim3(THREADS), TILE_LDS, stream, g);
+    else if (mode == 2) hipLaunchKernelGGL(match_nearest_kernel<2>, grid, dim3(THREADS), TILE_LDS, stream, g);
     else if (mode == 1) hipLaunchKernelGGL(match_nearest_kernel<1>, grid, dim3(THREADS), TILE_LDS, stream, g);
     else hipLaunchKernelGGL(match_nearest_kernel<0>, grid, dim3(THREADS), TILE_LDS, stream, g);
     hipLaunchKernelGGL(match_combine_kernel, dim3((unsigned)((nA + THREADS - 1) / THREADS)), dim3(THREADS), 0, stream, g);

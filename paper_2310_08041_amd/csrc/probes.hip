@@ -9,6 +9,7 @@
 #include <stdint.h>
 
 #include "qllm.h"
+#include "qllm_probes.h"
 
 extern "C" void qllm_note_hip_error(const char *step, const char *name);
 

@@ -16,9 +16,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "qllm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(qllm_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(qllm_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -343,8 +346,10 @@ def test_matching_entry_point_rejects_bad_arguments_before_launching():
         return f(a["y"], a["n"], a["ldy"], a["W"], a["C"], a["O"], a["ldw"], a["ca"], a["nA"], a["cb"], a["nB"],
                  a["bj"], a["bd"], a["ws"], a["wsb"], None)
 
-    for k in ("y", "W", "ca", "cb", "bj", "bd"):
+    for k in ("y", "ca", "cb", "bj", "bd"):
         assert call(**{k: None}) == -1
+    assert call(W=None, O=0, ldw=0, nA=0) == 0                        # no weights: the plain L2 distance (O, ldw ignored)
+    assert call(W=None, O=0, ldw=0, ws=None) == -7                    # ... and the same checks after that
     assert call(n=0) == -2 and call(O=0) == -2 and call(ldy=63) == -2 and call(ldw=31) == -2 and call(nA=-1) == -2
     assert call(nB=0) == -2
     assert call(ws=None) == -7 and call(wsb=b.qllm_match_workspace_bytes(10, 12) - 1) == -7
@@ -366,3 +371,40 @@ def test_select_edges_host_matches_the_oracle():
         src_idx, dst_idx = calibrate.select_edges(best_d, best_j, pos_a, pos_b, r)
         assert pick.tolist() == src_idx.tolist()
         assert (dst_idx.tolist() == best_j[pick].tolist())
+
+
+# ---------------------------------------------------------------- offline host helpers around the channel matching
+
+def test_matching_sets_and_pairs_host_match_the_oracle():
+    from oracle import calibrate
+    rng = np.random.default_rng(31)
+    T = np.ones(41, np.int32)
+    T[[0, 13, 40]] = [3, 2, 5]
+    sets = b.qllm_matching_sets_host(T)
+    chan_of, pos_a, pos_b = calibrate.matching_sets(T)
+    assert np.array_equal(sets["pos_a"], pos_a) and np.array_equal(sets["pos_b"], pos_b)
+    assert np.array_equal(sets["chan_a"], chan_of[pos_a]) and np.array_equal(sets["chan_b"], chan_of[pos_b])
+    best_d = rng.integers(0, 4, pos_a.size).astype(np.float64)               # many ties
+    best_j = rng.integers(0, pos_b.size, pos_a.size).astype(np.int32)
+    for r in (0, 1, 5, pos_a.size, pos_a.size + 9):
+        src_idx, dst_idx = b.qllm_pairs_host(best_d, best_j, pos_a, pos_b, r)
+        ref_s, ref_d = calibrate.select_edges(best_d, best_j.astype(np.int64), pos_a, pos_b, r)
+        assert np.array_equal(src_idx, ref_s) and np.array_equal(dst_idx, ref_d)
+    with pytest.raises(b.QllmError):
+        b.qllm_matching_sets_host(np.array([1, 0, 2], np.int32))               # a split count below 1
+
+
+def test_theta_helpers_match_the_oracle():
+    from oracle import calibrate
+    rng = np.random.default_rng(32)
+    m = np.abs(rng.standard_normal(500)).astype(np.float32)
+    m[[3, 77, 300]] *= [40, 90, 25]
+    for ratio in (0.002, 0.01, 0.05, 0.1, 0.6):
+        target = max(1, int(round(ratio * m.size)))
+        assert b.qllm_theta_for_expansion_host(m, target) == calibrate.theta_from_rule(m, ("expand", ratio))
+    assert b.qllm_theta_for_expansion_host(np.array([1.0, 2.0, 12.0], np.float32), 2) == float(np.nextafter(np.float32(6), np.float32(0)))
+    for P in (1, 4, 7):
+        assert b.qllm_theta_grid_host(m, P) == calibrate.theta_grid(m, P)
+    assert b.qllm_theta_grid_host(np.array([0.5, 2.0, 8.5, 1.0], np.float32), 4) == [2.5, 4.5, 6.5, 8.5]
+    with pytest.raises(b.QllmError):
+        b.qllm_theta_for_expansion_host(np.zeros(4, np.float32), 1)

@@ -453,17 +453,20 @@ def matching_case(rng, C, n, O, n_split, twins=0):
 
 
 def run_matching(b, y, W, T):
+    """W None: the plain L2 distance on the activations."""
     import torch
-    from paper_2310_08041_amd import calibrate as dev_cal
-    yd, Wd = torch.from_numpy(y).cuda(), torch.from_numpy(W).cuda()
-    chan_of, pos_a, pos_b = dev_cal.matching_sets(T, yd.device)
-    chan_a, chan_b = chan_of[pos_a].to(torch.int32).contiguous(), chan_of[pos_b].to(torch.int32).contiguous()
-    best_j = torch.full((pos_a.numel(),), -7, dtype=torch.int32, device="cuda")
-    best_d = torch.full((pos_a.numel(),), float("nan"), dtype=torch.float64, device="cuda")
-    ws = torch.empty(b.qllm_match_workspace_bytes(pos_a.numel(), pos_b.numel()), dtype=torch.uint8, device="cuda")
+    yd, Wd = torch.from_numpy(y).cuda(), None if W is None else torch.from_numpy(W).cuda()
+    sets = b.qllm_matching_sets_host(T)
+    pos_a, pos_b = sets["pos_a"], sets["pos_b"]
+    chan_of = np.repeat(np.arange(len(T)), T)
+    assert np.array_equal(chan_of[pos_a], sets["chan_a"]) and np.array_equal(chan_of[pos_b], sets["chan_b"])
+    chan_a, chan_b = torch.from_numpy(sets["chan_a"]).cuda(), torch.from_numpy(sets["chan_b"]).cuda()
+    best_j = torch.full((pos_a.size,), -7, dtype=torch.int32, device="cuda")
+    best_d = torch.full((pos_a.size,), float("nan"), dtype=torch.float64, device="cuda")
+    ws = torch.empty(b.qllm_match_workspace_bytes(pos_a.size, pos_b.size), dtype=torch.uint8, device="cuda")
     b.qllm_match_nearest(yd, Wd, chan_a, chan_b, best_j, best_d, ws)
     torch.cuda.synchronize()
-    return best_j.cpu().numpy(), best_d.cpu().numpy(), chan_of.cpu().numpy(), pos_a.cpu().numpy(), pos_b.cpu().numpy()
+    return best_j.cpu().numpy(), best_d.cpu().numpy(), chan_of, pos_a, pos_b
 
 
 def check_matching(y, W, rows, chan_of, pos_a, pos_b, got_j, got_d, ref_j, ref_d):
@@ -540,6 +543,84 @@ def test_calibration_with_eq5_matches_the_oracle(oracle, b):
                             n_match=N, W=torch.from_numpy(W).cuda())
     assert np.array_equal(out["num_split"], cal["T"])
     assert np.array_equal(out["src_idx"], src_ref) and np.array_equal(out["dst_idx"], dst_ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("C,n,n_split,twins,integers", [(301, 40, 7, 3, False), (2048, 256, 30, 0, False), (130, 5, 4, 0, True)])
+def test_match_nearest_plain_l2(oracle, b, C, n, n_split, twins, integers):
+    """W == NULL: nearest member of B under |x_i - x_j|^2, against the oracle's explicit differences.  With small
+    integer activations every distance is exact on both sides and ties are frequent: the same member must win."""
+    from oracle import calibrate
+    rng = np.random.default_rng(C + n)
+    y, _, T = matching_case(rng, C, n, 8, n_split, twins)
+    if integers:
+        y = rng.integers(-2, 3, y.shape).astype(np.float32)
+    got_j, got_d, chan_of, pos_a, pos_b = run_matching(b, y, None, T)
+    ref_j, ref_d, ref_pa, ref_pb = calibrate.nearest_by_l2(y, T, n_match_tokens=n)
+    assert np.array_equal(pos_a, ref_pa) and np.array_equal(pos_b, ref_pb)
+    if integers:
+        assert np.array_equal(got_j, ref_j) and np.array_equal(got_d, ref_d) and (ref_d == 0).sum() < ref_d.size
+        return
+    y64 = y.astype(np.float64)
+    for i in range(pos_a.size):
+        ca, cb = chan_of[pos_a[i]], chan_of[pos_b[got_j[i]]]
+        d = ((y64[:, ca] - y64[:, cb]) ** 2).sum()
+        tol = 1e-12 * ((y64[:, ca] ** 2).sum() + (y64[:, cb] ** 2).sum())   # round-off of |a|^2 + |b|^2 - 2 a.b
+        assert abs(d - got_d[i]) <= tol
+        assert got_j[i] == ref_j[i] or abs(d - ref_d[i]) <= 2 * tol         # another member only if as near
+    if twins:
+        assert (ref_d == 0).sum() >= 1
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,N,C", [("tiny", 64, 512), ("llama7b_qkv", 300, 4096), ("llama13b_upgate", 256, 5120)])
+def test_calibration_without_weights_matches_the_oracle(oracle, b, name, N, C):
+    """The map every benchmark number is measured with: statistic kernel, threshold rule, sets, plain-L2 matching
+    on the device, edge selection, map -- against the oracle's calibration of the same batch."""
+    import torch
+    from oracle import calibrate
+    from paper_2310_08041_amd import calibrate as dev_cal
+    w = wl.WORKLOADS[name]
+    x, _, _ = wl.draw_activations(w, N, C)
+    gamma, beta = wl.draw_norm_params(w, C)
+    cal = calibrate.calibrate(oracle.norm(x, NORM_ID[w.norm], gamma, beta, w.eps), w.theta_rule)
+    out = dev_cal.calibrate(to_torch_x(x), NORM_ID[w.norm], torch.from_numpy(gamma).cuda(),
+                            None if beta is None else torch.from_numpy(beta).cuda(), w.eps, w.theta_rule)
+    assert np.array_equal(out["absmax"].view(np.uint32), cal["absmax"].view(np.uint32))
+    assert out["theta"] == cal["theta"] and np.array_equal(out["num_split"], cal["T"])
+    assert cal["src_idx"].size == int((cal["T"].astype(np.int64) - 1).sum()) > 0
+    assert np.array_equal(out["src_idx"], cal["src_idx"]) and np.array_equal(out["dst_idx"], cal["dst_idx"])
+    row_ptr, src, scale = oracle.build_map(cal["T"], cal["src_idx"], cal["dst_idx"])
+    assert np.array_equal(out["row_ptr"], row_ptr) and np.array_equal(out["src"], src) and np.array_equal(out["scale"], scale)
+
+
+@pytest.mark.gpu
+def test_reference_output_and_squared_error_kernels(b):
+    """qllm_linear_f64 against numpy's float64 product (sums in another order: to round-off), qllm_sq_error against
+    the same sum in numpy; bf16 and strided operands; integer data make both exact."""
+    import torch
+    rng = np.random.default_rng(77)
+    N, C, O = 70, 333, 150
+    y = rng.standard_normal((N, C)).astype(np.float32)
+    W = rng.standard_normal((C + 3, O + 5)).astype(np.float32)[:C, :O]           # a strided view
+    yd, Wd = torch.from_numpy(y).cuda(), torch.from_numpy(np.ascontiguousarray(W)).cuda()
+    Wd = torch.from_numpy(np.ascontiguousarray(rng.standard_normal((C, O + 5)).astype(np.float32))).cuda()[:, :O]
+    W = Wd.cpu().numpy()
+    ref = torch.full((N, O), float("nan"), dtype=torch.float64, device="cuda")
+    b.qllm_linear_f64(yd, Wd, ref)
+    want = y.astype(np.float64) @ W.astype(np.float64)
+    assert np.allclose(ref.cpu().numpy(), want, rtol=0, atol=1e-12 * np.abs(want).max() * C)
+    yi = rng.integers(-8, 9, (N, C)).astype(np.float32)
+    Wi = rng.integers(-8, 9, (C, O)).astype(np.float32)
+    b.qllm_linear_f64(torch.from_numpy(yi).cuda(), torch.from_numpy(Wi).cuda(), ref)
+    assert np.array_equal(ref.cpu().numpy(), yi.astype(np.float64) @ Wi.astype(np.float64))
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = torch.empty(b.qllm_sq_error_workspace_bytes(N), dtype=torch.uint8, device="cuda")
+    for dt in (torch.float32, torch.bfloat16):
+        got = (ref + torch.from_numpy(rng.integers(-3, 4, (N, O)).astype(np.float64)).cuda()).to(dt)
+        b.qllm_sq_error(got, ref, loss, ws)
+        e = got.double().cpu().numpy() - ref.cpu().numpy()
+        assert np.isclose(loss.cpu().numpy()[0], (e * e).sum(), rtol=1e-13) and loss.cpu().numpy()[0] > 0
 
 
 @pytest.mark.gpu
