@@ -289,5 +289,21 @@ def reassembled_linear(x, norm_kind, gamma, beta, eps, T, src_idx, dst_idx, a_bi
     return out
 
 
+def nearest_member(y, W, chan_a, chan_b):
+    """For every member of set A (its channel in chan_a) the nearest member of set B: plain squared L2 distance
+    between the activation columns of y [n, C] (W None), or the distance of Eq. (5) with the weights W [C, O].
+    Explicit differences in double; lowest index on ties.  Returns (best_j int64 [nA], best_d float64 [nA])."""
+    y = _c(y, np.float32)
+    W = _c(W, np.float32)
+    chan_a, chan_b = _c(chan_a, np.int32), _c(chan_b, np.int32)
+    best_j = np.empty(chan_a.size, np.int64)
+    best_d = np.empty(chan_a.size, np.float64)
+    O, ldw = (0, 0) if W is None else (W.shape[1], W.shape[1])
+    _chk(lib().oracle_nearest_member(_p(y), _i64(y.shape[0]), _i64(y.shape[1]), _p(W), _i64(O), _i64(ldw), _p(chan_a),
+                                     _i64(chan_a.size), _p(chan_b), _i64(chan_b.size), _p(best_j), _p(best_d)),
+         "nearest_member")
+    return best_j, best_d
+
+
 def max_threads():
     return int(lib().oracle_max_threads())

@@ -635,6 +635,61 @@ done:
     return rc;
 }
 
+/*
+ * Appendix A step 2 with the plain squared L2 distance between activation columns (the matching the
+ * benchmark configurations name: "nearest-L2 channel pairs"): for every member i of set A, the member j
+ * of set B with the smallest D(i, j) = sum over the n calibration tokens of (y[t, a_i] - y[t, b_j])^2,
+ * the lowest j on ties.  Differences, squares and sums in double, tokens in ascending order.
+ * With W != NULL the distance is that of Eq. (5) instead, |x_i - x_j|^2 |W_i - W_j|^2 / 4 (W is
+ * [C, ldw], O features): the error Eq. (4) leaves in the layer's output when i is merged into j.
+ */
+int oracle_nearest_member(const float *y, int64_t n, int64_t ldy, const float *W, int64_t O, int64_t ldw,
+                          const int32_t *chan_a, int64_t nA, const int32_t *chan_b, int64_t nB,
+                          int64_t *best_j, double *best_d)
+{
+    if (!y || !chan_a || !chan_b || !best_j || !best_d) return 1;
+    if (n <= 0 || nA < 0 || nB <= 0 || (W && O <= 0)) return 2;
+    /* the columns of set B, gathered once: [nB][n] */
+    double *xb = (double *)malloc((size_t)nB * (size_t)n * sizeof(double));
+    if (!xb) return 3;
+    for (int64_t j = 0; j < nB; ++j)
+        for (int64_t t = 0; t < n; ++t) xb[j * n + t] = (double)y[t * ldy + chan_b[j]];
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t i = 0; i < nA; ++i) {
+        double *xa = (double *)malloc((size_t)n * sizeof(double));
+        for (int64_t t = 0; t < n; ++t) xa[t] = (double)y[t * ldy + chan_a[i]];
+        const float *wa = W ? W + (int64_t)chan_a[i] * ldw : NULL;
+        double bd = 0.0;
+        int64_t bj = -1;
+        for (int64_t j = 0; j < nB; ++j) {
+            double dx = 0.0;
+            for (int64_t t = 0; t < n; ++t) {
+                const double e = xa[t] - xb[j * n + t];
+                dx += e * e;
+            }
+            double d = dx;
+            if (W) {
+                const float *wb = W + (int64_t)chan_b[j] * ldw;
+                double dw = 0.0;
+                for (int64_t k = 0; k < O; ++k) {
+                    const double e = (double)wa[k] - (double)wb[k];
+                    dw += e * e;
+                }
+                d = 0.25 * dx * dw;
+            }
+            if (bj < 0 || d < bd) { /* strict: the first of equal minima stays */
+                bd = d;
+                bj = j;
+            }
+        }
+        free(xa);
+        best_j[i] = bj;
+        best_d[i] = bd;
+    }
+    free(xb);
+    return 0;
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP

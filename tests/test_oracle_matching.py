@@ -190,3 +190,17 @@ def test_expansion_threshold_is_the_largest_that_adds_enough(oracle):
         target = max(1, int(round(ratio * m.size)))
         assert int((oracle.num_split(m, th).astype(np.int64) - 1).sum()) >= target
         assert int((oracle.num_split(m, np.nextafter(np.float32(th), np.float32(np.inf))).astype(np.int64) - 1).sum()) < target
+
+
+def test_c_routine_agrees_with_the_numpy_form_of_eq5(oracle):
+    """oracle_nearest_member with weights against nearest_by_eq5 (numpy): same members, distances to round-off."""
+    rng = np.random.default_rng(17)
+    C, N, O = 37, 9, 6
+    y = rng.standard_normal((N, C)).astype(np.float32)
+    W = rng.standard_normal((C, O)).astype(np.float32)
+    T = np.ones(C, np.int32)
+    T[[8, 30]] = [2, 3]
+    ref_j, ref_d, pos_a, pos_b = calibrate.nearest_by_eq5(y, W, T)
+    chan_of = np.repeat(np.arange(C), T)
+    got_j, got_d = oracle.nearest_member(y, W, chan_of[pos_a], chan_of[pos_b])
+    assert np.array_equal(got_j, ref_j) and np.allclose(got_d, ref_d, rtol=1e-13, atol=0)
