@@ -349,6 +349,100 @@ def test_reassembled_linear_end_to_end(oracle, b, name, N, C, O, y_dtype):
     assert np.sqrt(((got - full) ** 2).mean()) < 0.6 * np.sqrt((full ** 2).mean())
 
 
+@pytest.mark.parametrize("name", ["llama7b_qkv", "llama13b_upgate", "llama70b_down"])
+def test_reassembled_linear_full_configs_sampled(oracle, b, name):
+    """The whole layer at the full benchmark shapes with real (reassembled, quantized) weights, in the launch
+    configuration the benchmark times.  Exact: the packed weight codes and their parameters against the oracle's
+    offline half, the activation codes of every token, the int32 accumulators of all tokens x 48 sampled output
+    features and 24 sampled tokens x all features.  Y of the sampled tokens within the bf16 tolerance, from
+    qllm_reassembled_linear itself."""
+    import torch
+    w = wl.WORKLOADS[name]
+    c = make_case(oracle, w)
+    dm = device_map(b, c)
+    q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, w.w_bits)
+    assert np.array_equal(q["codes"], oracle.pack_codes(c.wcodes, w.w_bits, q["codes"].shape[1]))
+    assert np.array_equal(q["scale"].view(np.uint32), c.aw.view(np.uint32)) and np.array_equal(q["zero"], c.bw)
+    assert np.array_equal(q["colsum"], c.cs)
+    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], c.K, w.w_bits)
+    del q
+    c.W = None
+    g = torch.from_numpy(c.gamma).cuda()
+    x = to_torch_x(c.x)
+    y = torch.full((c.N, c.O), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(b.qllm_workspace_bytes(c.N, c.K, c.O, w.a_bits), dtype=torch.uint8, device="cuda")
+    b.qllm_reassembled_linear(x, c.norm, g, None, c.eps, dm, w.a_bits, dw, y, ws)
+    # the same two steps apart, for the codes and the raw accumulators
+    qa = b.DeviceQAct(c.N, c.K, w.a_bits)
+    b.qllm_norm_reassemble_quant(x, c.norm, g, None, c.eps, dm, w.a_bits, qa)
+    y2 = torch.empty_like(y)
+    acc = torch.empty((c.N, c.O), dtype=torch.int32, device="cuda")
+    gws = torch.empty(max(b.qllm_gemm_workspace_bytes(c.N, c.K, c.O, w.a_bits), 16), dtype=torch.uint8, device="cuda")
+    b.qllm_int_gemm(qa, dw, y2, acc_dump=acc, workspace=gws)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))          # one call or two: the same bits
+    exp = check_fused(oracle, c, qa, w.a_bits)
+    rng = np.random.default_rng(w.seed + 1)
+    cols = np.sort(rng.choice(c.O, 48, replace=False))
+    rows = np.sort(rng.choice(c.N, 24, replace=False))
+    acc = acc.cpu().numpy()
+    assert np.array_equal(acc[:, cols], oracle.int_gemm(exp["codes"], c.wcodes[cols]))
+    acc_rows = oracle.int_gemm(exp["codes"][rows], c.wcodes)
+    assert np.array_equal(acc[rows], acc_rows)
+    ref_rows = oracle.epilogue(acc_rows, c.K, exp["alpha"][rows], exp["beta"][rows], exp["rowsum"][rows], c.aw, c.bw, c.cs)
+    got_rows = oracle.widen_bf16(y[torch.from_numpy(rows).cuda()].view(torch.int16).cpu().numpy().view(np.uint16))
+    assert rel_err(got_rows, ref_rows).max() <= TOL["bf16"]
+    assert np.array_equal(got_rows, oracle.widen_bf16(oracle.round_to_bf16(ref_rows)))     # in practice: bit for bit
+
+
+@pytest.mark.parametrize("name,N,C,O,y_dtype", [("tiny", 40, 512, 96, "f32"), ("llama7b_qkv", 300, 4096, 640, "bf16"),
+                                               ("llama70b_q_decode", 16, 8192, 256, "bf16")])
+def test_reassembled_linear_w4a8_end_to_end(oracle, b, name, N, C, O, y_dtype):
+    """Sec. 5 "Quantization settings": 4-bit weights with 8-bit activations, through the whole layer (decode-size,
+    small and more than 128 tokens: three different GEMM kernels)."""
+    import dataclasses
+    import torch
+    w = dataclasses.replace(wl.WORKLOADS[name], a_bits=8, w_bits=4)
+    c = make_case(oracle, w, N=N, C=C, O=O)
+    exp = oracle.reassembled_linear(c.x, c.norm, c.gamma, c.beta, c.eps, c.T, c.src_idx, c.dst_idx, 8,
+                                    (c.wcodes, c.aw, c.bw, c.cs))
+    dm = device_map(b, c)
+    q = b.qllm_quantize_weight_host(c.W, c.row_ptr, c.src, 4)
+    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], c.K, 4)
+    y = torch.full((c.N, c.O), float("nan"), dtype=torch.float32 if y_dtype == "f32" else torch.bfloat16, device="cuda")
+    ws = torch.empty(b.qllm_workspace_bytes(c.N, c.K, c.O, 8), dtype=torch.uint8, device="cuda")
+    g = torch.from_numpy(c.gamma).cuda()
+    be = None if c.beta is None else torch.from_numpy(c.beta).cuda()
+    b.qllm_reassembled_linear(to_torch_x(c.x), c.norm, g, be, c.eps, dm, 8, dw, y, ws)
+    torch.cuda.synchronize()
+    check_y(oracle, y, exp["y"], y_dtype)
+    # the codes and accumulators behind it
+    qa = run_fused(b, c, 8)
+    check_fused(oracle, c, qa, 8)
+    acc = torch.empty((c.N, c.O), dtype=torch.int32, device="cuda")
+    gws = torch.empty(max(b.qllm_gemm_workspace_bytes(c.N, c.K, c.O, 8), 16), dtype=torch.uint8, device="cuda")
+    b.qllm_int_gemm(qa, dw, torch.empty_like(y), acc_dump=acc, workspace=gws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), exp["acc"])
+    # 8-bit activations hurt less than 4-bit ones on the same weights
+    yn = oracle.norm(c.x, c.norm, c.gamma, c.beta, c.eps).astype(np.float64)
+    full = yn @ c.W.astype(np.float64)
+    exp4 = oracle.reassembled_linear(c.x, c.norm, c.gamma, c.beta, c.eps, c.T, c.src_idx, c.dst_idx, 4,
+                                     (c.wcodes, c.aw, c.bw, c.cs))
+    assert ((exp["y"] - full) ** 2).sum() < ((exp4["y"] - full) ** 2).sum()
+
+
+def test_fused_full_down_projection_without_norm(oracle, b):
+    """The down-projection as LLaMA has it: its input comes from the gated activation, not from a norm
+    (reassembly is applied before every linear layer but the attention output projection): QLLM_NORM_NONE at the
+    full 70B shape."""
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["llama70b_down"], norm="none")
+    c = make_case(oracle, w, real_weights=False)
+    assert c.K == w.C and c.norm == 0
+    check_fused(oracle, c, run_fused(b, c, w.a_bits), w.a_bits)
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("name,N,C,O", [("llama70b_q_decode", 16, 8192, 512), ("llama7b_qkv", 300, 4096, 640)])
 def test_layer_replays_from_a_hip_graph(oracle, b, name, N, C, O):
