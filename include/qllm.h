@@ -155,6 +155,23 @@ int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64
                                 void *hip_stream);
 
 /* ------------------------------------------------------------------------------------------
+ * qllm_reassembled_linear for callers that cannot allocate device memory or have none to spare for a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without the workspace, same kernels, same results bit for bit; the workspace is a device array
+ * inside the library, QLLM_STATIC_WORKSPACE_BYTES per GPU, held until the process ends.  The call allocates and
+ * frees nothing.  QLLM_ERR_WORKSPACE if qllm_workspace_bytes(N, map->C_out, w->O, a_bits) exceeds that size
+ * (decode and small-batch shapes fit: 16 tokens x 8192 channels need 0.1 MB, 512 tokens x 28672 channels at 4
+ * bits 7.4 MB).  All calls on one GPU share the array: two of them in flight at once on different streams race;
+ * calls on one stream are ordered like any other work.  The first call on a device asks the runtime for the
+ * array's address there (no allocation, but not under stream capture): make that call before capturing.
+ */
+#define QLLM_STATIC_WORKSPACE_BYTES (32 << 20)
+int32_t qllm_reassembled_linear_static(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
+                                       int32_t norm, const float *gamma, const float *beta, float eps,
+                                       const qllm_map *map, int32_t a_bits, const qllm_weight *w, void *y,
+                                       int32_t y_dtype, int64_t ldy, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
  * Offline, on the device: which channels to merge (Sec. 4.1.2, Appendix A steps 1-2).  The caller
  * has split the candidates into set A and set B (Appendix A step 1; on the disassembled axis, even and
  * odd positions, sub-channels of split channels left out) and names each member's channel.  For every

@@ -52,6 +52,8 @@ _sigs = {
     "qllm_int_gemm": (_i32, [C.POINTER(_QAct), _i32, _i64, C.POINTER(_Weight), _vp, _i32, _i64, _vp, _vp, _i64, _vp]),
     "qllm_reassembled_linear": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, C.POINTER(_Map), _i32,
                                        C.POINTER(_Weight), _vp, _i32, _i64, _vp, _i64, _vp]),
+    "qllm_reassembled_linear_static": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, C.POINTER(_Map), _i32,
+                                              C.POINTER(_Weight), _vp, _i32, _i64, _vp]),
     "qllm_packed_row_bytes": (_i64, [_i64, _i32]),
     "qllm_gemm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
@@ -314,6 +316,18 @@ def qllm_reassembled_linear(x, norm, gamma, beta, eps, dmap, a_bits, weight, y, 
                                       float(eps), C.byref(dmap.c), int(a_bits), C.byref(weight.c), _dp(y),
                                       _x_dtype(y), y.stride(0), _dp(workspace), workspace.numel(), _stream(stream)),
          "qllm_reassembled_linear")
+    return y
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def qllm_reassembled_linear_static(x, norm, gamma, beta, eps, dmap, a_bits, weight, y, stream=None):
+    """The layer with the library's built-in workspace: allocates nothing."""
+    N, Cc = x.shape
+    _chk(_lib.qllm_reassembled_linear_static(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
+                                             float(eps), C.byref(dmap.c), int(a_bits), C.byref(weight.c), _dp(y),
+                                             _x_dtype(y), y.stride(0), _stream(stream)), "qllm_reassembled_linear_static")
     return y
 
 

@@ -994,7 +994,8 @@ extern "C" int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64
     if (N < 0) return QLLM_ERR_SHAPE;
     const int64_t need = qllm_workspace_bytes(N, map->C_out, w->O, a_bits);
     if (need < 0) return (int32_t)need;
-    if (N > 0 && (!workspace || workspace_bytes < need)) return QLLM_ERR_WORKSPACE;
+    if (N == 0) return QLLM_OK; // nothing to do, whatever the workspace
+    if (!workspace || workspace_bytes < need) return QLLM_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QLLM_ERR_ALIGN;
     auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
     uint8_t *p = static_cast<uint8_t *>(workspace);
@@ -1011,4 +1012,63 @@ extern "C" int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64
     if (rc != QLLM_OK) return rc;
     return qllm_int_gemm(&q, a_bits, N, w, y, y_dtype, ldy, nullptr, p, workspace_bytes - (p - static_cast<uint8_t *>(workspace)),
                          hip_stream);
+}
+
+// ---- the layer for callers that cannot allocate: its workspace is a device array of this library
+
+namespace {
+
+// Device memory beyond the inputs and outputs of the layer: the quantized activations between the two kernels
+// and, where the sum over K is split over workgroups, their partial accumulators.  One copy per GPU, held from
+// the moment the code object is loaded on it until the process ends.  In host code this name is only a handle:
+// the address on the current device comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[QLLM_STATIC_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_lock;
+void *scratch_at[MAX_DEVICES]; // the array's address on each device, asked for once
+
+int32_t scratch_pointer(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        qllm_note_hip_error("static workspace: current device", e != hipSuccess ? hipGetErrorName(e) : "device number out of range");
+        return QLLM_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_at[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            qllm_note_hip_error("static workspace: address of the device array", e != hipSuccess ? hipGetErrorName(e) : "null address");
+            return QLLM_ERR_HIP;
+        }
+        scratch_at[dev] = p;
+    }
+    *out = scratch_at[dev];
+    return QLLM_OK;
+}
+
+} // namespace
+
+extern "C" int32_t qllm_reassembled_linear_static(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
+                                                  int32_t norm, const float *gamma, const float *beta, float eps,
+                                                  const qllm_map *map, int32_t a_bits, const qllm_weight *w, void *y,
+                                                  int32_t y_dtype, int64_t ldy, void *hip_stream)
+{
+    if (!map || !w) return QLLM_ERR_NULL;
+    if (w->K != map->C_out) return QLLM_ERR_SHAPE;
+    if (N < 0) return QLLM_ERR_SHAPE;
+    const int64_t need = qllm_workspace_bytes(N, map->C_out, w->O, a_bits);
+    if (need < 0) return (int32_t)need;
+    if (need > (int64_t)QLLM_STATIC_WORKSPACE_BYTES) return QLLM_ERR_WORKSPACE; // too large a batch for the built-in workspace
+    if (N == 0) return QLLM_OK;
+    void *ws = nullptr;
+    const int32_t rc = scratch_pointer(&ws);
+    if (rc != QLLM_OK) return rc;
+    return qllm_reassembled_linear(x, x_dtype, N, C, ldx, norm, gamma, beta, eps, map, a_bits, w, y, y_dtype, ldy, ws,
+                                   (int64_t)QLLM_STATIC_WORKSPACE_BYTES, hip_stream);
 }
