@@ -9,10 +9,14 @@ dequantising epilogue -- over one batch of synthetic activations that is already
 The default workload is the LLaMA-2-70B down-projection shape (N=2048, C=28672, O=8192, W4A4).
 
 Prints one JSON line.  `value` is 2*N*K*O integer operations per second of the whole step;
-`roofline` prices the dominant kernel (the GEMM) against the dense int8 matrix-core peak, and
-`roofline_fused` the fused kernel against HBM bandwidth; both use the kernel's own average duration,
-taken with HIP events on the launch stream in a second, instrumented pass of the same K steps.
-`cpu_baseline` times the CPU oracle, as it stands, on a bounded sample of the same workload.
+`roofline` prices the dominant kernel (the GEMM) against the dense int8 matrix-core peak (against HBM
+bandwidth for decode-sized batches, where the weights stream once), and `roofline_fused` the fused kernel
+against HBM bandwidth; both use the kernel's own average duration, taken with HIP events on the launch
+stream in a second, instrumented pass of the same K steps (median and minimum next to the mean).
+Before anything is timed the GPU runs the step for at least 100 ms, whatever --warmup says (the clocks
+settle over the first tens of milliseconds).  `cpu_baseline` times the CPU oracle, as it stands, on a
+bounded sample of the same workload, from its own calibration and weights; `parity_checked` compares
+what the TIMED launches wrote with that oracle run.
 `traffic` (HBM bytes per launch) cannot be measured from inside the process: it is read from the
 committed counter summary profiles/<workload>_hbm_traffic.md if that exists, else null.
 --calibration-copy adds one plain device-to-device copy of 256 MiB before the timed region, so that a
@@ -29,6 +33,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix-core peak, published
+MIN_WARMUP_MS = 100.0        # GPU time spent on the step before anything is timed, whatever --warmup says
 N_ROTATE = 4                 # distinct activation / output buffers cycled through, so that no step
 #                              finds its inputs in the 256 MB last-level cache
 
@@ -183,6 +188,7 @@ def main():
     ys = [torch.empty((w.N, w.O), dtype=torch.bfloat16, device=dev) for _ in range(N_ROTATE)]
     ws = torch.empty(b.qllm_workspace_bytes(w.N, K, w.O, w.a_bits), dtype=torch.uint8, device=dev)
     qa = b.DeviceQAct(w.N, K, w.a_bits)
+    gws = torch.empty(max(b.qllm_gemm_workspace_bytes(w.N, K, w.O, w.a_bits), 16), dtype=torch.uint8, device=dev)
     setup_s = time.time() - t0
 
     if args.calibration_copy:
@@ -195,9 +201,18 @@ def main():
     def step(i):
         b.qllm_reassembled_linear(xs[i % N_ROTATE], norm, gamma, beta, w.eps, dmap, w.a_bits, dw, ys[i % N_ROTATE], ws)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
+    # ---- warm-up: at least --warmup steps AND at least 100 ms of GPU time
+    warm_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    warm_steps, warm_ms = 0, 0.0
+    while warm_steps < args.warmup or warm_ms < MIN_WARMUP_MS:
+        n = max(N_ROTATE, min(64, args.warmup - warm_steps))
+        warm_ev[0].record()
+        for i in range(n):
+            step(warm_steps + i)
+        warm_ev[1].record()
+        torch.cuda.synchronize()
+        warm_steps += n
+        warm_ms += warm_ev[0].elapsed_time(warm_ev[1])
     if args.graph:
         if args.steps % N_ROTATE:
             sys.exit(f"bench.py: --graph needs --steps to be a multiple of {N_ROTATE}")
@@ -217,6 +232,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
+    # what the timed launches wrote, kept for the parity check below (the instrumented pass writes ys again)
+    ys_timed = [y.cpu() for y in ys[:min(N_ROTATE, args.steps)]]
+    ws_codes_timed = ws[:w.N * b.qllm_packed_row_bytes(K, w.a_bits)].cpu()      # activation codes of the last timed step
+    last_buf = (args.steps - 1) % N_ROTATE
 
     # ---- instrumented pass: the same K steps as two calls with HIP events (recorded on the launch
     # stream, torch's current stream) around each kernel
@@ -225,11 +244,13 @@ def main():
         ev[i][0].record()
         b.qllm_norm_reassemble_quant(xs[i % N_ROTATE], norm, gamma, beta, w.eps, dmap, w.a_bits, qa)
         ev[i][1].record()
-        b.qllm_int_gemm(qa, dw, ys[i % N_ROTATE])
+        b.qllm_int_gemm(qa, dw, ys[i % N_ROTATE], workspace=gws)
         ev[i][2].record()
     torch.cuda.synchronize()
-    t_fused = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps * 1e-3
-    t_gemm = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps * 1e-3
+    fused_us = np.array([e[0].elapsed_time(e[1]) for e in ev]) * 1e3
+    gemm_us = np.array([e[1].elapsed_time(e[2]) for e in ev]) * 1e3
+    t_fused, t_gemm = fused_us.mean() * 1e-6, gemm_us.mean() * 1e-6
+    spread = lambda v: {"mean": float(v.mean()), "median": float(np.median(v)), "min": float(v.min())}
 
     ops = 2.0 * w.N * K * w.O
     x_bytes = w.N * w.C * x0.element_size()
@@ -270,6 +291,22 @@ def main():
                    "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits)) if w.N > 128 else \
         "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
     traffic = read_traffic(w.name)
+    if w.N <= 32:
+        # decode-sized batch: the GEMM streams the packed weights once and does little arithmetic per byte
+        gemm_bytes = (w.O * b.qllm_packed_row_bytes(K, w.w_bits) + w.N * b.qllm_packed_row_bytes(K, w.a_bits)
+                      + w.N * w.O * 2 + 12 * (w.N + w.O))
+        gemm_gbs = gemm_bytes / t_gemm / 1e9
+        roofline = {"kernel": gemm_kernel, "bound": "hbm", "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gemm_gbs / HBM_PEAK_GBS, "avg_launch_us": t_gemm * 1e6, "launch_us": spread(gemm_us),
+                    "algorithmic_bytes": gemm_bytes, "traffic": traffic.get("int_gemm"), "int8_TOPs": gemm_tops,
+                    "probe": {"what": "plain stream, 16 bytes read : 4 written, 1.25 GB per pass",
+                              "achieved": stream_probe_gbs, "frac_of_probe": gemm_gbs / stream_probe_gbs}}
+    else:
+        roofline = {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
+                    "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
+                    "avg_launch_us": t_gemm * 1e6, "launch_us": spread(gemm_us), "traffic": traffic.get("int_gemm"),
+                    "probe": {"what": "loop of int8 matrix-core operations on register operands, all CUs",
+                              "achieved": mfma_probe_tops, "frac_of_probe": gemm_tops / mfma_probe_tops}}
     result = {
         "metric": "reassembled W4A4 linear TOPS at 70B shapes; fused norm+reassembly+quant GB/s",
         "value": ops / (ms_per_step * 1e-3) / 1e12,
@@ -282,16 +319,13 @@ def main():
                    "w_bits": w.w_bits, "in_dtype": w.in_dtype, "out_dtype": "bf16", "norm": w.norm,
                    "theta": cal["theta"], "extra_channels": int(cal["nnz"] - w.C),
                    "merged_pairs": int(cal["src_idx"].size), "T_max": int(cal["num_split"].max()),
-                   "rotating_buffers": N_ROTATE, "launch": "hip graph replay" if args.graph else "eager"},
+                   "rotating_buffers": N_ROTATE, "launch": "hip graph replay" if args.graph else "eager",
+                   "warmup_done": {"steps": warm_steps, "gpu_ms": warm_ms}},
         "fused_GBps": fused_gbs,
-        "roofline": {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
-                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
-                     "avg_launch_us": t_gemm * 1e6, "traffic": traffic.get("int_gemm"),
-                     "probe": {"what": "loop of int8 matrix-core operations on register operands, all CUs",
-                               "achieved": mfma_probe_tops, "frac_of_probe": gemm_tops / mfma_probe_tops}},
+        "roofline": roofline,
         "roofline_fused": {"kernel": "fused_planned_kernel", "bound": "hbm", "achieved": fused_gbs,
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fused_gbs / HBM_PEAK_GBS,
-                           "avg_launch_us": t_fused * 1e6, "algorithmic_bytes": fused_bytes,
+                           "avg_launch_us": t_fused * 1e6, "launch_us": spread(fused_us), "algorithmic_bytes": fused_bytes,
                            "traffic": traffic.get("fused_planned"),
                            "probe": {"what": "plain stream, 16 bytes read : 4 written, 1.25 GB per pass",
                                      "achieved": stream_probe_gbs, "frac_of_probe": fused_gbs / stream_probe_gbs}},
@@ -299,24 +333,51 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        # cpu_baseline leg only: the oracle as it stands, fed from the seeded generators and its own
-        # calibration (nothing computed by the HIP path enters it)
+        # cpu_baseline leg only: the oracle as it stands, fed from the seeded generators, with its OWN calibration
+        # (over all tokens, as the device's) and its own reassembled and quantized weights: nothing computed by the
+        # HIP path enters it.  The timed part is the whole path on the first `ns` tokens.
         from oracle import api as oracle
         from oracle import calibrate as oracle_cal
         ns = min(args.cpu_sample_tokens, w.N)
-        xs_host = np.ascontiguousarray(x_host[:ns])
-        ocal = oracle_cal.calibrate(oracle.norm(xs_host, norm, gamma_h, beta_h, w.eps), w.theta_rule)
-        Ko = int(ocal["T"].astype(np.int64).sum()) - ocal["src_idx"].size
-        wcodes, aw, bw = wl.draw_weight_codes(w, Ko)
-        cs = wcodes.astype(np.int64).sum(1).astype(np.int32)
         t1 = time.perf_counter()
-        oracle.reassembled_linear(xs_host, norm, gamma_h, beta_h, w.eps, ocal["T"], ocal["src_idx"], ocal["dst_idx"],
-                                  w.a_bits, (wcodes, aw, bw, cs), want_acc=False)
+        ocal = oracle_cal.calibrate(oracle.norm(x_host, norm, gamma_h, beta_h, w.eps), w.theta_rule,
+                                    assemble_more=args.assemble_more)
+        W = wl.draw_weight(w)
+        wq = oracle.quantize_weight(oracle.reassemble_weight(W, ocal["T"], ocal["src_idx"], ocal["dst_idx"]), w.w_bits)
+        del W
+        prep_s = time.perf_counter() - t1
+        xs_host = np.ascontiguousarray(x_host[:ns])
+        t1 = time.perf_counter()
+        ref = oracle.reassembled_linear(xs_host, norm, gamma_h, beta_h, w.eps, ocal["T"], ocal["src_idx"], ocal["dst_idx"],
+                                        w.a_bits, wq, want_acc=False)
         cpu_s = time.perf_counter() - t1
-        result["cpu_baseline"] = {"value": 2.0 * ns * K * w.O / cpu_s / 1e12, "unit": "TOP/s",
+        Ko = ref["codes"].shape[1]
+        result["cpu_baseline"] = {"value": 2.0 * ns * Ko * w.O / cpu_s / 1e12, "unit": "TOP/s",
                                   "cores": oracle.max_threads(), "kind": "oracle",
-                                  "sample": f"first {ns} of {w.N} tokens through the whole path (all {K} channels, "
-                                            f"all {w.O} output features), {cpu_s:.1f} s"}
+                                  "sample": f"first {ns} of {w.N} tokens through the whole path (all {Ko} channels, "
+                                            f"all {w.O} output features), {cpu_s:.1f} s; its own calibration and "
+                                            f"weight quantization before that, {prep_s:.1f} s, are not in the rate"}
+        # ---- parity of what the TIMED launches wrote: buffer i holds the rows of the batch rotated by i
+        same_map = (np.array_equal(ocal["T"], cal["num_split"]) and np.array_equal(ocal["src_idx"], cal["src_idx"])
+                    and np.array_equal(ocal["dst_idx"], cal["dst_idx"]) and float(ocal["theta"]) == float(cal["theta"]))
+        ref_y = oracle.widen_bf16(oracle.round_to_bf16(ref["y"]))
+        rows_checked, y_exact, y_max_rel = 0, True, 0.0
+        for i, yt in enumerate(ys_timed):
+            rows = (np.arange(ns) + i) % w.N                       # row r of the batch sits at row r + i of buffer i
+            got = oracle.widen_bf16(yt.view(torch.int16).numpy().view(np.uint16)[rows])
+            y_exact = y_exact and bool(np.array_equal(got, ref_y))
+            den = np.maximum(np.abs(ref["y"]), 1e-3 * np.sqrt((ref["y"].astype(np.float64) ** 2).mean()))
+            y_max_rel = max(y_max_rel, float((np.abs(got - ref["y"]) / den).max()))
+            rows_checked += ns
+        rows = (np.arange(ns) + last_buf) % w.N
+        got_codes = ws_codes_timed.numpy().reshape(w.N, -1)[rows]
+        codes_exact = bool(Ko == K and np.array_equal(got_codes, oracle.pack_codes(ref["codes"], w.a_bits, got_codes.shape[1])))
+        result["parity_checked"] = {"against": "the cpu_baseline oracle run (its own map and weights)",
+                                    "maps_identical": bool(same_map), "timed_buffers": len(ys_timed),
+                                    "token_rows_x_all_features": rows_checked, "y_bit_exact_bf16": bool(y_exact),
+                                    "y_max_rel_err": y_max_rel, "y_tolerance": 2e-2,
+                                    "activation_codes_rows": int(ns), "activation_codes_exact": codes_exact,
+                                    "ok": bool(same_map and codes_exact and y_max_rel <= 2e-2)}
     print(json.dumps(result))
 
 
