@@ -302,6 +302,9 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  *   segs     [n_segw]: per composite group {count | number << 8, then count x {d, mask, 0}}: the group's
  *            copied channels at positions k with bit k of mask set have sources d + k (d may be negative or
  *            reach past C_in - 8: only the masked positions are real channels)
+ *   recs     [n_comp][8]: the same once more as records of fixed size, by composite group number:
+ *            {count | offset of the group's list in segs << 8, d0, mask0, d1, mask1, group, 0, 0} (what the kernel
+ *            reads for the first two segments; a group with more takes the rest from segs)
  * QLLM_ERR_MAP: malformed map, or a row of more than 64 entries (such a map runs without a plan).
  */
 int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,

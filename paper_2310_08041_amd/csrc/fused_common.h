@@ -26,9 +26,8 @@ struct FusedArgs {
     double inv_C; // 1 / C
     const int32_t *row_ptr, *src, *desc;
     const float *scale;
-    const int32_t *work, *chunks, *spec, *dest, *longs, *segs; // the parts of the plan (see qllm_plan_map_host)
+    const int32_t *work, *chunks, *spec, *dest, *longs, *segs, *recs; // the parts of the plan (see qllm_plan_map_host)
     int32_t n_comp, n_long, n_pub, n_work, n_chunks, n_spec, n_dest, n_segw;
-    int32_t n_main; // row lanes of the planned kernel's workgroup (set by its launcher)
     int32_t C_out, n_groups, n_groups_pad, S;
     uint8_t *codes;
     int64_t row_bytes;

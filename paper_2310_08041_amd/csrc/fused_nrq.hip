@@ -454,7 +454,7 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     if (map->plan) { // the host copy of the header says where the parts are: see qllm_plan_map_host
         const int32_t *h = map->plan_head;
         if (reinterpret_cast<uintptr_t>(map->plan) & 15u) return QLLM_ERR_ALIGN;
-        if (h[0] != 0x514c4d50 || h[1] != 6 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
+        if (h[0] != 0x514c4d50 || h[1] != 7 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
         const int64_t n_chunks = (C + GROUP - 1) / GROUP, n_work = (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP;
         auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
         if (h[4] != n_work || h[6] != n_chunks || h[5] < 0 || h[5] > n_work || h[7] < 0 || h[8] < 0 || h[8] > n_chunks ||
@@ -463,13 +463,15 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
         const int64_t off_work = QLLM_PLAN_HEAD, off_chunks = round4(off_work + n_work), off_spec = round4(off_chunks + n_chunks);
         const int64_t off_dest = round4(off_spec + 2 * (int64_t)h[9]), off_longs = round4(off_dest + h[10]);
         const int64_t off_segs = off_longs + 4 * (int64_t)h[7];
-        if (h[12] != off_chunks || h[14] != off_spec || h[15] != off_longs || h[13] != off_segs + h[11]) return QLLM_ERR_MAP;
+        const int64_t off_recs = round4(off_segs + h[11]);
+        if (h[12] != off_chunks || h[14] != off_spec || h[15] != off_longs || h[13] != off_recs + 8 * (int64_t)h[5]) return QLLM_ERR_MAP;
         a.work = map->plan + off_work;
         a.chunks = map->plan + off_chunks;
         a.spec = map->plan + off_spec;
         a.dest = map->plan + off_dest;
         a.longs = map->plan + off_longs;
         a.segs = map->plan + off_segs;
+        a.recs = map->plan + off_recs;
         a.n_work = h[4];
         a.n_comp = h[5];
         a.n_chunks = h[6];

@@ -32,7 +32,6 @@
 
 #include <stdint.h>
 
-#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -237,6 +236,17 @@ __device__ __noinline__ uint32_t slow_code(float x, float inv, int32_t beta, int
     return (uint32_t)fmin(fmax(q, 0.0), (double)qmax);
 }
 
+// bit k of m8 -> the k-th code field of a packed chunk, all ones
+template <int BITS>
+__device__ __forceinline__ uint64_t widen_mask(uint32_t m8)
+{
+    uint64_t m = 0;
+#pragma unroll
+    for (int k = 0; k < GROUP; ++k)
+        if (m8 >> k & 1u) m |= (uint64_t)((1u << BITS) - 1u) << (BITS * k);
+    return m;
+}
+
 // dwords of LDS per packed chunk of 8 codes (6-bit chunks take 48 of the 64 bits)
 template <int BITS>
 constexpr int PKW = BITS == 4 ? 1 : 2;
@@ -329,17 +339,36 @@ __device__ __forceinline__ void store_group(uint8_t *out_row, int g, uint32_t w0
 }
 
 // The 8 codes that start v codes into packed chunk u (0 <= v < 8): chunks u and u + 1 funnel-shifted.
-// The word after the last chunk exists (and is only ever shifted out).
+// The word after the last chunk exists (and is only ever shifted out), and so does the one before the first.
+// In two halves, so that the LDS reads can be issued long before the words are needed.
 template <int BITS>
-__device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_t &w0, uint32_t &w1)
+struct Window {
+    uint32_t a0, a1, b0, b1; // chunk u, chunk u + 1 (a1, b1: 6 and 8 bits only)
+};
+
+template <int BITS>
+__device__ __forceinline__ Window<BITS> funnel_fetch(const uint32_t *pk, int u)
 {
+    Window<BITS> w;
     if constexpr (BITS == 4) {
-        const uint32_t lo = pk[u], hi = pk[u + 1];
-        w0 = __builtin_amdgcn_alignbit(hi, lo, 4 * v); // ({hi, lo} >> 4v), low 32 bits
-        w1 = 0;
+        w.a0 = pk[u];
+        w.b0 = pk[u + 1];
+        w.a1 = w.b1 = 0;
     } else {
         const uint2 a = reinterpret_cast<const uint2 *>(pk)[u], b = reinterpret_cast<const uint2 *>(pk)[u + 1];
-        const uint64_t A = (uint64_t)a.x | ((uint64_t)a.y << 32), B = (uint64_t)b.x | ((uint64_t)b.y << 32);
+        w.a0 = a.x; w.a1 = a.y; w.b0 = b.x; w.b1 = b.y;
+    }
+    return w;
+}
+
+template <int BITS>
+__device__ __forceinline__ void funnel_shift(const Window<BITS> &w, int v, uint32_t &w0, uint32_t &w1)
+{
+    if constexpr (BITS == 4) {
+        w0 = __builtin_amdgcn_alignbit(w.b0, w.a0, 4 * v); // ({hi, lo} >> 4v), low 32 bits
+        w1 = 0;
+    } else {
+        const uint64_t A = (uint64_t)w.a0 | ((uint64_t)w.a1 << 32), B = (uint64_t)w.b0 | ((uint64_t)w.b1 << 32);
         uint64_t r;
         if constexpr (BITS == 6) {
             r = ((A >> (6 * v)) | (B << (48 - 6 * v))) & 0xffffffffffffull;
@@ -350,6 +379,12 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
         w0 = (uint32_t)r;
         w1 = (uint32_t)(r >> 32);
     }
+}
+
+template <int BITS>
+__device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_t &w0, uint32_t &w1)
+{
+    funnel_shift<BITS>(funnel_fetch<BITS>(pk, u), v, w0, w1);
 }
 
 // The row loop is software-pipelined over three barrier intervals, so that work bound by latency (LDS
@@ -368,11 +403,11 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
 // LayerNorm has one more barrier inside interval 2 (the mean has to be known before the squared
 // deviations are summed).
 //
-// Two kinds of lanes.  The first n_main lanes ("row lanes") own ITERS chunks of the row and as many plain
-// output groups: the regular, dense part.  The irregular part -- computed channels, long rows, composite
-// output groups -- is a few hundred items per row whose cost is LDS latency; it goes to up to two extra
-// wavefronts ("side lanes") when the workgroup has room for them, which also evens out the wavefronts
-// per SIMD (14 row wavefronts are 4 + 4 + 3 + 3).  Without room the row lanes do it as well.
+// Every lane owns ITERS chunks of the row and as many plain output groups: the regular, dense part.  The
+// irregular part -- computed channels, long rows, composite output groups -- is a few hundred items per row,
+// dealt out over the lanes in order.  (Giving it to two extra wavefronts of its own, which would also even out
+// the wavefronts per SIMD -- 14 are 4 + 4 + 3 + 3 -- was measured: they take longer over the long rows and
+// the composite groups than the others take over the row, 66 against 57 us at the 70B shape.)
 //
 // Input channels that no output channel copies (split channels, channels merged away or into) must stay
 // out of min/max, and their codes must not spill into their neighbours' bits.  The lane's own copy of
@@ -381,7 +416,7 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
 //
 // NORM: QLLM_NORM_NONE / LAYER / RMS.  GAM_REG: the lane's share of gamma stays in registers for the
 // lifetime of the workgroup; otherwise it is re-read (from L2) for every row, which frees 8 registers per chunk.
-// FULL: the row fills the row lanes exactly (chunks = ITERS x row lanes): no bounds tests.
+// FULL: the row fills the workgroup exactly (chunks = ITERS x lanes): no bounds tests.
 template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, int NORM, bool FULL>
 __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
 {
@@ -391,7 +426,6 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     constexpr uint32_t NOT_PUBLISHED = 0xffffffu;
     extern __shared__ __align__(16) float lds[];
     const bool shift = LAYER && a.beta != nullptr;
-    const int nm = a.n_main;                  // row lanes
     const int n_stage = GROUP * a.n_pub + 4;  // staged positions: the chunks that hold sources, then a zero
     const int goff = NORM != QLLM_NORM_NONE ? n_stage : 0, boff = goff + (shift ? n_stage : 0);
     float *pub = lds;                          // [n_stage] x of the staged chunks; [8 n_pub ..] stays zero
@@ -406,8 +440,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     uint32_t *pk = ins + a.n_comp * W + W;                             // [-1 .. n_chunks] * W packed codes, input order; both ends zero
     int32_t *dest = reinterpret_cast<int32_t *>(pk + (a.n_chunks + 1) * W); // [n_dest] composite group << 3 | position
     uint32_t *segs = reinterpret_cast<uint32_t *>(dest + a.n_dest);    // [n_segw] segments of the composite groups
-    uint32_t *chunkw = segs + a.n_segw;                                // [ITERS * row lanes] pass bits | staging slot << 8
-    int32_t *work = reinterpret_cast<int32_t *>(chunkw + ITERS * nm); // [ITERS * row lanes] plain and padding output groups
+    uint32_t *chunkw = segs + a.n_segw;                                // [ITERS * lanes] pass bits | staging slot << 8
+    int32_t *work = reinterpret_cast<int32_t *>(chunkw + ITERS * blockDim.x); // [ITERS * lanes] plain and padding output groups
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
@@ -417,68 +451,66 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int n_chunks = a.n_chunks;
     const float inf = __builtin_inff(), nan = __uint_as_float(0xffffffffu);
-    // row lanes and side lanes (uniform per wavefront); the irregular items are dealt out to `side_n` lanes
-    const int wave_first = __builtin_amdgcn_readfirstlane(tid); // a scalar: the tests below are branches, not lane masks
-    const bool is_row = wave_first < nm, is_side = nt > nm ? wave_first >= nm : true;
-    const int side_n = nt > nm ? nt - nm : nm;
 
-    // ---- the plan, once per workgroup
-    for (int j = tid; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
-    for (int j = tid; j < a.n_spec; j += nt) spec[j] = reinterpret_cast<const int2 *>(a.spec)[j];
-    for (int j = tid; j < a.n_dest; j += nt) dest[j] = a.dest[j];
+    // ---- the plan, once per workgroup.  Every lane first requests all it is going to need -- the first row,
+    //      gamma, its shares of the plan's lists -- and only then starts to put things into LDS, so that the set-up
+    //      costs about one trip to memory and not one per list.
+    const XT *xbase = reinterpret_cast<const XT *>(a.x);
+    Raw<XT> raw[ITERS];
+    int64_t row = blockIdx.x;
+    if (PREFETCH && row < a.N) { // the first row
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int i = tid + it * nt;
+            load_raw(raw[it], xbase + row * a.ldx, (FULL || i < n_chunks ? i : n_chunks - 1) * GROUP);
+        }
+    }
+    // composite groups that have a slot in the lanes' last pass, and those that have not
+    const int comp_slot0 = max(a.n_work - a.n_comp, (ITERS - 1) * nt);
+    const int n_loop = max(0, a.n_comp - max(0, ITERS * nt - comp_slot0));
+    // The plan lists plain groups, then composite groups, then padding.  Plain and padding groups keep
+    // the plan's order in the lanes' slots (slot it * lanes + lane), so that neighbouring lanes store
+    // neighbouring groups.  Composite groups take the slots that are left in the lanes' last pass, as
+    // kind << 30 | number; those that do not fit there (the first n_loop) are dealt out in a loop of their own.
+    const int n_p = a.n_groups - a.n_comp, n_np = a.n_work - a.n_comp;
+    uint32_t cw0[ITERS];
+    int32_t we0[ITERS];
+    float gam[GAM_REG ? ITERS : 1][GROUP];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int sl = tid + it * nt;
+        cw0[it] = sl < n_chunks ? (uint32_t)a.chunks[sl] : (NOT_PUBLISHED << 8);
+        we0[it] = WORK_NONE;
+        if (sl < n_np) we0[it] = a.work[sl < n_p ? sl : sl + a.n_comp];
+        else if (sl >= comp_slot0 && sl - comp_slot0 < a.n_comp - n_loop) we0[it] = (int32_t)((1u << 30) | (uint32_t)(n_loop + sl - comp_slot0));
+        if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, sl * GROUP, a.C, NORM != QLLM_NORM_NONE);
+    }
+    // the first lanes' worth of every list in flight at once; what is left of a longer list follows below
+    const bool has_long = tid < a.n_long, has_spec = tid < a.n_spec, has_dest = tid < a.n_dest, has_rec = tid < a.n_comp;
+    int4 l0 = make_int4(0, 0, 0, 0);
+    int2 s0 = make_int2(0, 0);
+    int32_t d0 = 0;
+    uint4 ra = make_uint4(0, 0, 0, 0), rb = ra;
+    if (has_long) l0 = reinterpret_cast<const int4 *>(a.longs)[tid];
+    if (has_spec) s0 = reinterpret_cast<const int2 *>(a.spec)[tid];
+    if (has_dest) d0 = a.dest[tid];
+    if (has_rec) {
+        ra = reinterpret_cast<const uint4 *>(a.recs)[2 * tid];
+        rb = reinterpret_cast<const uint4 *>(a.recs)[2 * tid + 1];
+    }
+    uint32_t sg0[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) sg0[it] = tid + it * nt < a.n_segw ? (uint32_t)a.segs[tid + it * nt] : 0u;
+
+    // A composite group's record {count | list << 8, d0, mask0, d1, mask1, group}: masks widened to code fields,
+    // laid out for one pair of wide LDS reads.  The list itself (for groups of more than two segments) stays as
+    // it is: {d, mask, -} per segment, widened where it is used.
+    auto put_rec = [&](int c, const uint4 &p, const uint4 &q) {
+        const uint64_t m0 = widen_mask<BITS>(p.z), m1 = widen_mask<BITS>(q.x);
+        rec[2 * c] = make_uint4(p.x, p.y, (uint32_t)m0, (uint32_t)(m0 >> 32));
+        rec[2 * c + 1] = make_uint4(p.w, (uint32_t)m1, (uint32_t)(m1 >> 32), q.y);
+    };
     for (int j = tid; j < a.n_comp * W; j += nt) ins[j] = 0u;
-    {
-        // The plan lists plain groups, then composite groups, then padding.  Plain and padding groups keep
-        // the plan's order in the row lanes' slots (slot it * row lanes + lane), so that neighbouring lanes
-        // store neighbouring groups.
-        const int n_p = a.n_groups - a.n_comp;
-        for (int sl = tid; sl < ITERS * nm; sl += nt) {
-            const int idx = sl < n_p ? sl : sl + a.n_comp;
-            work[sl] = idx < a.n_work ? a.work[idx] : WORK_NONE;
-        }
-        // A composite group's segments {count | number << 8, {d, mask, -} ...}: masks widened to code fields;
-        // the first two segments and the group's number also go to a record that one pair of wide LDS reads fetches.
-        for (int c = tid; c < a.n_comp; c += nt) {
-            const int32_t e = a.work[n_p + c];
-            const int off = e & 0x1ffff;
-            const uint32_t hdr = (uint32_t)a.segs[off];
-            const int n_seg = hdr & 0xffu, comp = hdr >> 8;
-            uint32_t r8[8] = {(uint32_t)n_seg | ((uint32_t)off << 8), 0u, 0u, 0u, 0u, 0u, 0u, (uint32_t)(e >> 17) & 0x1fffu};
-            segs[off] = hdr;
-            for (int sg = 0; sg < n_seg; ++sg) {
-                const uint32_t m8 = (uint32_t)a.segs[off + 2 + 3 * sg], ds = (uint32_t)a.segs[off + 1 + 3 * sg];
-                uint64_t m = 0;
-#pragma unroll
-                for (int k = 0; k < GROUP; ++k)
-                    if (m8 >> k & 1u) m |= (uint64_t)QMAX << (BITS * k);
-                segs[off + 1 + 3 * sg] = ds;
-                segs[off + 2 + 3 * sg] = (uint32_t)m;
-                segs[off + 3 + 3 * sg] = (uint32_t)(m >> 32);
-                if (sg < 2) {
-                    r8[1 + 3 * sg] = ds;
-                    r8[2 + 3 * sg] = (uint32_t)m;
-                    r8[3 + 3 * sg] = (uint32_t)(m >> 32);
-                }
-            }
-            rec[2 * comp] = make_uint4(r8[0], r8[1], r8[2], r8[3]);
-            rec[2 * comp + 1] = make_uint4(r8[4], r8[5], r8[6], r8[7]);
-        }
-    }
-    for (int j = tid; j < ITERS * nm; j += nt) {
-        const uint32_t cw = j < n_chunks ? (uint32_t)a.chunks[j] : (NOT_PUBLISHED << 8), slot = cw >> 8;
-        chunkw[j] = cw;
-        if (NORM != QLLM_NORM_NONE && slot != NOT_PUBLISHED) { // norm parameters of the staged chunks
-            float g8[GROUP];
-            load_gamma(g8, a.gamma, j * GROUP, a.C, true);
-#pragma unroll
-            for (int k = 0; k < GROUP; ++k) pubg[slot * GROUP + k] = g8[k];
-            if (shift) {
-                load_gamma(g8, a.beta, j * GROUP, a.C, true);
-#pragma unroll
-                for (int k = 0; k < GROUP; ++k) pubb[slot * GROUP + k] = g8[k];
-            }
-        }
-    }
     if (tid < 4) { // the zero: x = 0, gamma = 0, beta = 0, so that its y is a zero whatever the row's statistics
         pub[GROUP * a.n_pub + tid] = 0.0f;
         if (NORM != QLLM_NORM_NONE) pubg[GROUP * a.n_pub + tid] = 0.0f;
@@ -495,20 +527,55 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         red_f[16 + tid] = inf; // minus the maximum
         red_i[tid] = 0;
     }
+    if (has_long) longs[tid] = l0;
+    if (has_spec) spec[tid] = s0;
+    if (has_dest) dest[tid] = d0;
+    if (has_rec) put_rec(tid, ra, rb);
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int sl = tid + it * nt;
+        chunkw[sl] = cw0[it];
+        work[sl] = we0[it];
+        if (sl < a.n_segw) segs[sl] = sg0[it];
+    }
+    for (int j = tid + nt; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
+    for (int j = tid + nt; j < a.n_spec; j += nt) spec[j] = reinterpret_cast<const int2 *>(a.spec)[j];
+    for (int j = tid + nt; j < a.n_dest; j += nt) dest[j] = a.dest[j];
+    for (int j = tid + nt; j < a.n_comp; j += nt) put_rec(j, reinterpret_cast<const uint4 *>(a.recs)[2 * j], reinterpret_cast<const uint4 *>(a.recs)[2 * j + 1]);
+    for (int j = tid + ITERS * nt; j < a.n_segw; j += nt) segs[j] = (uint32_t)a.segs[j];
+    // norm parameters of the staged chunks
+    if constexpr (NORM != QLLM_NORM_NONE) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int sl = tid + it * nt;
+            const uint32_t slot = cw0[it] >> 8;
+            if (slot != NOT_PUBLISHED) {
+                float g8[GROUP];
+                if constexpr (GAM_REG) {
+#pragma unroll
+                    for (int k = 0; k < GROUP; ++k) g8[k] = gam[it][k];
+                } else {
+                    load_gamma(g8, a.gamma, sl * GROUP, a.C, true);
+                }
+#pragma unroll
+                for (int k = 0; k < GROUP; ++k) pubg[slot * GROUP + k] = g8[k];
+                if (shift) {
+                    load_gamma(g8, a.beta, sl * GROUP, a.C, true);
+#pragma unroll
+                    for (int k = 0; k < GROUP; ++k) pubb[slot * GROUP + k] = g8[k];
+                }
+            }
+        }
+    }
     // gamma of the lane's chunks; NaN where the input channel is copied by no output channel (see above)
     // and for chunks past the end of the row.  NORM_NONE multiplies by 1 (exact) or NaN.
     auto mask_gamma = [&](float *g, uint32_t passes) {
 #pragma unroll
         for (int j = 0; j < GROUP; ++j) g[j] = (passes >> j & 1u) ? g[j] : nan;
     };
-    float gam[GAM_REG ? ITERS : 1][GROUP];
     if constexpr (GAM_REG) {
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int i = tid + it * nm;
-            load_gamma(gam[it], a.gamma, i * GROUP, a.C, NORM != QLLM_NORM_NONE && is_row);
-            mask_gamma(gam[it], is_row && i < n_chunks ? (uint32_t)a.chunks[i] & 0xffu : 0u);
-        }
+        for (int it = 0; it < ITERS; ++it) mask_gamma(gam[it], tid + it * nt < n_chunks ? cw0[it] & 0xffu : 0u);
         // gamma has to have arrived before the row loop is entered: a load still pending there would make
         // every pass of the loop wait for whatever was requested last, the next row's prefetch included.
 #pragma unroll
@@ -522,21 +589,14 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     // the first barrier of the first row, so the set-up has to be over for everybody first.
     __syncthreads();
 
-    const XT *xbase = reinterpret_cast<const XT *>(a.x);
     const uint32_t zero_at = (uint32_t)(GROUP * a.n_pub);
-    Raw<XT> raw[ITERS];
-    int64_t row = blockIdx.x, prev = -1;
-    if (PREFETCH && is_row && row < a.N) { // the first row
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int i = tid + it * nm;
-            load_raw(raw[it], xbase + row * a.ldx, (FULL || i < n_chunks ? i : n_chunks - 1) * GROUP);
-        }
-    }
+    // `prev`: the row whose output groups are still to be stored.  At first the first row itself: its place in
+    // the output then receives codes made of whatever LDS holds, and the real ones one pass later.
+    int64_t prev = row;
 
     // rowsum of a finished row: the waves' partial sums are complete once a barrier has passed
     auto finish_rowsum = [&](int64_t r) {
-        if (wave == 0 && r >= 0) {
+        if (wave == 0) {
             const int32_t s = dpp_add_row16(red_i[lane & 15]);
             if (lane == 0) a.rowsum[r] = s;
         }
@@ -553,58 +613,78 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     // ---- step a4, second half, of the row before: the output groups.  A plain group is two neighbouring
     //      packed words funnel-shifted; a composite group is several such windows, each masked to the
     //      channels it supplies, plus the codes of its computed channels.
-    auto output_pass = [&](int64_t prev, int ltid) {
+    auto composite = [&](int comp, uint32_t &w0, uint32_t &w1) -> int {
+        const uint4 r0 = rec[2 * comp], r1 = rec[2 * comp + 1]; // {count | list << 8, d0, mask0}, {d1, mask1, group}
+        uint32_t i0 = ins[comp * W], i1 = 0u;
+        ins[comp * W] = 0u; // ready for the next row's codes
+        if constexpr (W == 2) {
+            i1 = ins[comp * W + 1];
+            ins[comp * W + 1] = 0u;
+        }
+        uint32_t f0, f1, g0, g1;
+        funnel<BITS>(pk, (int)r0.y >> 3, r0.y & 7, f0, f1);
+        funnel<BITS>(pk, (int)r1.x >> 3, r1.x & 7, g0, g1);
+        i0 |= (f0 & r0.z) | (g0 & r1.y);
+        if constexpr (W == 2) i1 |= (f1 & r0.w) | (g1 & r1.z);
+        const int n_seg = r0.x & 0xffu, off = r0.x >> 8;
+        for (int sg = 2; sg < n_seg; ++sg) {
+            const int ds = (int)segs[off + 1 + 3 * sg];
+            const uint64_t m = widen_mask<BITS>(segs[off + 2 + 3 * sg]);
+            funnel<BITS>(pk, ds >> 3, ds & 7, f0, f1);
+            i0 |= f0 & (uint32_t)m;
+            if constexpr (W == 2) i1 |= f1 & (uint32_t)(m >> 32);
+        }
+        w0 = i0;
+        w1 = i1;
+        return (int)r1.w;
+    };
+    // The output pass in pieces, so that the row loop can put other work between its LDS reads and their use.
+    struct OutState {
+        int32_t e[ITERS];
+        Window<BITS> win[ITERS];
+    };
+    auto out_read_work = [&](OutState &o, int ltid) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) o.e[it] = work[ltid + it * nt];
+    };
+    auto out_read_codes = [&](OutState &o) { // padding and composite groups read the row's first words and drop them
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int d = ((uint32_t)o.e[it] >> 30) == KIND_PLAIN ? o.e[it] & 0x1ffff : 0;
+            o.win[it] = funnel_fetch<BITS>(pk, d >> 3);
+        }
+    };
+    auto out_store = [&](OutState &o, int64_t prev, int ltid) {
         int32_t sum = 0;
         uint8_t *out_row = a.codes + prev * a.row_bytes;
-        if (is_row) {
-            // every LDS read of a kind is issued for all of the lane's groups before any is used
-            int32_t e[ITERS];
-            uint32_t w0[ITERS], w1[ITERS];
+        int g[ITERS];
+        uint32_t w0[ITERS], w1[ITERS];
 #pragma unroll
-            for (int it = 0; it < ITERS; ++it) e[it] = work[ltid + it * nm];
+        for (int it = 0; it < ITERS; ++it) {
+            const bool plain = ((uint32_t)o.e[it] >> 30) == KIND_PLAIN;
+            funnel_shift<BITS>(o.win[it], plain ? o.e[it] & 7 : 0, w0[it], w1[it]);
+            w0[it] = plain ? w0[it] : 0u;
+            w1[it] = plain ? w1[it] : 0u;
+            g[it] = (o.e[it] >> 17) & 0x1fff;
+        }
+        // composite groups sit in slots of the last pass only
+        if (((uint32_t)o.e[ITERS - 1] >> 30) == KIND_COMP) g[ITERS - 1] = composite(o.e[ITERS - 1] & 0x1ffff, w0[ITERS - 1], w1[ITERS - 1]);
 #pragma unroll
-            for (int it = 0; it < ITERS; ++it) { // padding groups read the row's first words and drop them
-                const bool plain = ((uint32_t)e[it] >> 30) == KIND_PLAIN;
-                const int d = plain ? e[it] & 0x1ffff : 0;
-                funnel<BITS>(pk, d >> 3, d & 7, w0[it], w1[it]);
-                w0[it] = plain ? w0[it] : 0u;
-                w1[it] = plain ? w1[it] : 0u;
-            }
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) {
-                if (((uint32_t)e[it] >> 30) != KIND_NONE) {
-                    store_group<BITS>(out_row, (e[it] >> 17) & 0x1fff, w0[it], w1[it]);
-                    sum += code_sum<BITS>(w0[it], w1[it]);
-                }
+        for (int it = 0; it < ITERS; ++it) {
+            if (FULL || ((uint32_t)o.e[it] >> 30) != KIND_NONE) {
+                store_group<BITS>(out_row, g[it], w0[it], w1[it]);
+                sum += code_sum<BITS>(w0[it], w1[it]);
             }
         }
-        if (is_side) {
-            for (int comp = ltid - (nt > nm ? nm : 0); comp < a.n_comp; comp += side_n) {
-                const uint4 r0 = rec[2 * comp], r1 = rec[2 * comp + 1]; // {count | list << 8, d0, mask0}, {d1, mask1, group}
-                uint32_t i0 = ins[comp * W], i1 = 0u;
-                ins[comp * W] = 0u; // ready for the next row's codes
-                if constexpr (W == 2) {
-                    i1 = ins[comp * W + 1];
-                    ins[comp * W + 1] = 0u;
-                }
-                uint32_t f0, f1, g0, g1;
-                funnel<BITS>(pk, (int)r0.y >> 3, r0.y & 7, f0, f1);
-                funnel<BITS>(pk, (int)r1.x >> 3, r1.x & 7, g0, g1);
-                i0 |= (f0 & r0.z) | (g0 & r1.y);
-                if constexpr (W == 2) i1 |= (f1 & r0.w) | (g1 & r1.z);
-                const int n_seg = r0.x & 0xffu, off = r0.x >> 8;
-                for (int sg = 2; sg < n_seg; ++sg) {
-                    const int ds = (int)segs[off + 1 + 3 * sg];
-                    funnel<BITS>(pk, ds >> 3, ds & 7, f0, f1);
-                    i0 |= f0 & segs[off + 2 + 3 * sg];
-                    if constexpr (W == 2) i1 |= f1 & segs[off + 3 + 3 * sg];
-                }
-                store_group<BITS>(out_row, (int)r1.w, i0, i1);
-                sum += code_sum<BITS>(i0, i1);
+        if (n_loop > 0) { // more composite groups than free slots
+            for (int comp = ltid; comp < n_loop; comp += nt) {
+                uint32_t c0, c1;
+                const int gc = composite(comp, c0, c1);
+                store_group<BITS>(out_row, gc, c0, c1);
+                sum += code_sum<BITS>(c0, c1);
             }
         }
-        sum = wave_sum_i32(sum);
-        if (lane == 0) red_i[wave] = sum; // read after the next barrier
+        return sum;
     };
 
     for (; row < a.N; row += gridDim.x) {
@@ -612,69 +692,64 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         // register each to keep: hide from the optimiser that the number does not change from row to row.
         int ltid = threadIdx.x;
         asm volatile("" : "+v"(ltid));
-        const int sid = ltid - (nt > nm ? nm : 0); // the lane's number among the side lanes (if it is one)
 
         // ================= interval 1
-        // ---- step a1, first half.  A bf16 row is already here (it was requested while the row before it
-        //      was worked on): widen it and request the next one into the same registers.  This comes before
-        //      the stores of the row before: loads and stores retire through one counter, and a wait for
-        //      the row placed after those stores would wait for them as well.
-        float y[ITERS][GROUP]; // x until interval 2 turns it into y in place
-        if (is_row) {
-            if constexpr (!PREFETCH) {
+        // In the order the hardware should see it (scheduling fences in between): LDS reads first, dense
+        // arithmetic while they are under way, and the next row's loads spread out between blocks of
+        // arithmetic instead of in one burst (14 wavefronts asking for 57 KB at once queue up in the address unit).
+        OutState o;
+        uint32_t slot[ITERS];
+        out_read_work(o, ltid);
 #pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    const int i = ltid + it * nm;
-                    if (FULL || i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
-                }
-            }
+        for (int it = 0; it < ITERS; ++it) slot[it] = chunkw[ltid + it * nt] >> 8;
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- step a1, first half.  A bf16 row is already here (it was requested while the row before it
+        //      was worked on): widen it; the next one goes into the same registers further down.
+        float y[ITERS][GROUP]; // x until interval 2 turns it into y in place
+        if constexpr (!PREFETCH) {
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                if (FULL || ltid + it * nm < n_chunks) {
-                    widen(raw[it], y[it]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
-                }
-                // here and now: the optimiser would rather widen where x is first used, further down, and
-                // keep the row's packed form alive next to the registers the next row is loaded into
-#pragma unroll
-                for (int j = 0; j < GROUP; ++j) asm volatile("" : "+v"(y[it][j]));
-            }
-            if constexpr (PREFETCH) {
-                // Unconditional, so that the loaded registers ARE the next pass's row (a load under a condition
-                // would be merged with the old contents at the end of the condition, which waits for it): the
-                // last pass requests its own row again, lanes past the end of the row the row's last chunk.
-                const int64_t next = row + gridDim.x, again = next < a.N ? next : row;
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    const int i = ltid + it * nm;
-                    load_raw(raw[it], xbase + again * a.ldx, (FULL || i < n_chunks ? i : n_chunks - 1) * GROUP);
-                }
+                const int i = ltid + it * nt;
+                if (FULL || i < n_chunks) load_raw(raw[it], xbase + row * a.ldx, i * GROUP);
             }
         }
-
-        if (prev >= 0) output_pass(prev, ltid);
-
-        if (is_row) {
-            // x of the chunks that hold a source of a computed channel (normalised by its readers in interval 2)
-            uint32_t slot[ITERS];
 #pragma unroll
-            for (int it = 0; it < ITERS; ++it) slot[it] = chunkw[ltid + it * nm] >> 8;
+        for (int it = 0; it < ITERS; ++it) {
+            if (FULL || ltid + it * nt < n_chunks) {
+                widen(raw[it], y[it]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
+            }
+            // here and now: the optimiser would rather widen where x is first used, further down, and
+            // keep the row's packed form alive next to the registers the next row is loaded into
+#pragma unroll
+            for (int j = 0; j < GROUP; ++j) asm volatile("" : "+v"(y[it][j]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- the packed words the output groups of the row before are made of (used after the statistics)
+        out_read_codes(o);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- row statistics in fp64 (two interleaved partial sums per lane: the additions do not wait for one
+        //      another; the order is fixed, so the result is reproducible; slots past the row hold 0), with
+        //      the next row's loads in between.  Those are unconditional, so that the loaded registers ARE the
+        //      next pass's row (a load under a condition would be merged with the old contents at the end of
+        //      the condition, which waits for it): the last pass requests its own row again, lanes past the end
+        //      of the row the row's last chunk.  They come before the stores of the row before: loads and stores
+        //      retire through one counter, and a wait for the row placed after those stores would wait for them too.
+        double s0 = 0.0, s1 = 0.0;
+        {
+            const int64_t next = row + gridDim.x, again = next < a.N ? next : row;
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                if (slot[it] != NOT_PUBLISHED) {
-                    float4 *dst = reinterpret_cast<float4 *>(pub + slot[it] * GROUP);
-                    dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
-                    dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
+                if constexpr (PREFETCH) {
+                    const int i = ltid + it * nt;
+                    load_raw(raw[it], xbase + again * a.ldx, (FULL || i < n_chunks ? i : n_chunks - 1) * GROUP);
                 }
-            }
-            // row statistics in fp64 (two interleaved partial sums per lane: the additions do not wait for
-            // one another; the order is fixed, so the result is reproducible).  Slots past the row hold 0.
-            if constexpr (NORM != QLLM_NORM_NONE) {
-                double s0 = 0.0, s1 = 0.0;
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
+                if constexpr (NORM != QLLM_NORM_NONE) {
 #pragma unroll
                     for (int j = 0; j < GROUP; j += 2) {
                         const double d0 = (double)y[it][j], d1 = (double)y[it][j + 1];
@@ -687,10 +762,29 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                         }
                     }
                 }
-                const double s = wave_sum(s0 + s1);
-                if (lane == 0) red_d[0][wave] = s;
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+
+        // ---- step a4, second half, of the row before: its output groups, stored
+        int32_t sum = out_store(o, prev, ltid);
+
+        // ---- x of the chunks that hold a source of a computed channel (normalised by its readers in interval 2)
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            if (slot[it] != NOT_PUBLISHED) {
+                float4 *dst = reinterpret_cast<float4 *>(pub + slot[it] * GROUP);
+                dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
+                dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
+            }
+        }
+        // ---- the wavefront's shares of the two sums
+        if constexpr (NORM != QLLM_NORM_NONE) {
+            const double s = wave_sum(s0 + s1);
+            if (lane == 0) red_d[0][wave] = s;
+        }
+        sum = wave_sum_i32(sum);
+        if (lane == 0) red_i[wave] = sum; // read after the barrier
         __syncthreads(); // partial statistics, staged x, partial rowsum; the packed words and the codes of the
                          // computed channels of the row before are no longer needed
         finish_rowsum(prev);
@@ -708,8 +802,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             v.b = shift ? pubb[pos] : 0.0f;
             return v;
         };
-        const bool spec0 = is_side && sid < a.n_spec;
-        const int2 item0 = spec0 ? spec[sid] : make_int2((int32_t)(zero_at | (zero_at << 16)), 0);
+        const bool spec0 = ltid < a.n_spec;
+        const int2 item0 = spec0 ? spec[ltid] : make_int2((int32_t)(zero_at | (zero_at << 16)), 0);
         const Staged src0 = staged_fetch((uint32_t)item0.x & 0xffffu), src1 = staged_fetch((uint32_t)item0.x >> 16);
 
         float mu = 0.0f, rstd = 1.0f;
@@ -718,11 +812,11 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         } else if constexpr (LAYER) {
             const double mu64 = total16(red_d[0], lane) * a.inv_C;
             double q = 0.0;
-            if (is_row) {
+            {
                 double q0 = 0.0, q1 = 0.0;
 #pragma unroll
                 for (int it = 0; it < ITERS; ++it) {
-                    if (FULL || ltid + it * nm < n_chunks) {
+                    if (FULL || ltid + it * nt < n_chunks) {
 #pragma unroll
                         for (int j = 0; j < GROUP; j += 2) {
                             const double d0 = (double)y[it][j] - mu64, d1 = (double)y[it][j + 1] - mu64;
@@ -758,12 +852,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         // ---- y in registers, in place; min/max over the channels that some output channel copies (all
         //      others are NaN by now)
         float mn = inf, mx = -inf;
-        if (is_row) {
+        {
             const float *gamma_row = a.gamma, *beta_row = a.beta; // opaque, so that per-row loads stay per row
             asm volatile("" : "+s"(gamma_row), "+s"(beta_row));
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                const int i = ltid + it * nm;
+                const int i = ltid + it * nt;
                 float gjit[GROUP];
                 if constexpr (!GAM_REG) {
                     load_gamma(gjit, gamma_row, i * GROUP, a.C, NORM != QLLM_NORM_NONE);
@@ -791,7 +885,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
         }
 
-        if (is_side) {
+        {
             // ---- steps a2 + a3 for the computed channels of one entry (sub-channels, scale 1/T, Eq. 3) or of
             //      two entries of equal scale (a merged pair, Eq. 4); one per lane and pass.
             {
@@ -801,10 +895,11 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 if (spec0) {
                     mn = fminf(mn, xv);
                     mx = fmaxf(mx, xv);
-                    specv[sid] = xv;
+                    specv[ltid] = xv;
                 }
             }
-            for (int j = sid + side_n; j < a.n_spec; j += side_n) {
+            if (a.n_spec > nt)
+            for (int j = ltid + nt; j < a.n_spec; j += nt) {
                 const int2 item = spec[j];
                 const float sc = __int_as_float(item.y);
                 float xv = sc * staged_y((uint32_t)item.x & 0xffffu);
@@ -819,8 +914,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             // then "value of the lane below + own product" is repeated; the lane of entry number pos is
             // final after pos repeats (repeating it again changes nothing) and the row's last lane
             // ends up with the row's value.  Every entry carries the largest pos of its wavefront.
-            for (int base = 0; base < a.n_long; base += side_n) {
-                const int e = base + sid;
+            for (int base = 0; base < a.n_long; base += nt) {
+                const int e = base + ltid;
                 int4 le = make_int4((int32_t)zero_at, -1, 0, 0);
                 if (e < a.n_long) le = longs[e];
                 const float p = __int_as_float(le.z) * staged_y((uint32_t)le.x);
@@ -852,9 +947,9 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         __syncthreads(); // also: the computed channels' values are complete
 
         // ================= interval 3
-        const bool code0 = is_side && sid < a.n_dest;
-        const float spec_v0 = code0 ? specv[sid] : 0.0f; // first pass of the computed channels' codes:
-        const int32_t spec_d0 = code0 ? dest[sid] : 0;    // requested now, used after the range is known
+        const bool code0 = ltid < a.n_dest;
+        const float spec_v0 = code0 ? specv[ltid] : 0.0f; // first pass of the computed channels' codes:
+        const int32_t spec_d0 = code0 ? dest[ltid] : 0;    // requested now, used after the range is known
         {
             const float v = dpp_min_row16(red_f[lane & 31]);
             mn = lane_f32(v, 0);
@@ -863,7 +958,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         const float range = mx - mn;
         const float alpha = range > 0.0f ? range / (float)QMAX : 1.0f;
         const float inv = 1.0f / alpha;
-        const int32_t fast = fabsf(mn * inv) < FAST_LIMIT && fabsf(mx * inv) < FAST_LIMIT;
+        const int32_t fast = __builtin_amdgcn_readfirstlane(fabsf(mn * inv) < FAST_LIMIT && fabsf(mx * inv) < FAST_LIMIT); // a scalar: a branch, not a lane mask
         int32_t beta;
         if (fast) beta = -rne_product_fast(mn, inv);
         else beta = (int32_t)fmin(fmax(-rne_product_slow(mn, inv), -2147483647.0), 2147483647.0);
@@ -874,10 +969,10 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         }
 
         // ---- step a4, first half: codes of the lane's own chunks, packed in input order
-        if (is_row) {
+        {
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
-                const int i = ltid + it * nm;
+                const int i = ltid + it * nt;
                 if (FULL || i < n_chunks) {
                     uint32_t w0, w1;
                     quant_pack<BITS>(y[it], 0xffu, fast, inv, beta, w0, w1);
@@ -887,7 +982,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
         }
         // codes of the computed channels, straight into their place in their group's word
-        if (is_side) {
+        {
             auto put_code = [&](float v, int32_t dj) {
                 const uint32_t code = one_code(v, fast, inv, beta);
                 if constexpr (W == 1) {
@@ -897,50 +992,29 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 }
             };
             if (code0) put_code(spec_v0, spec_d0);
-            for (int j = sid + side_n; j < a.n_dest; j += side_n) put_code(specv[j], dest[j]);
+            if (a.n_dest > nt)
+                for (int j = ltid + nt; j < a.n_dest; j += nt) put_code(specv[j], dest[j]);
         }
         __syncthreads(); // packed words and computed channels' codes complete
         prev = row;
     }
     // the last row's output groups
-    int ltid = threadIdx.x;
-    if (prev >= 0) output_pass(prev, ltid);
-    __syncthreads();
-    finish_rowsum(prev);
+    {
+        const int ltid = threadIdx.x;
+        OutState o;
+        out_read_work(o, ltid);
+        out_read_codes(o);
+        int32_t sum = out_store(o, prev, ltid);
+        sum = wave_sum_i32(sum);
+        if (lane == 0) red_i[wave] = sum;
+        __syncthreads();
+        finish_rowsum(prev);
+    }
 }
 
 struct Shape {
-    int iters, main, nt; // chunks per row lane, row lanes, lanes (row lanes + side lanes)
+    int iters, nt; // chunks per lane, lanes
 };
-
-// Extra wavefronts for the irregular items.  Measured at the LLaMA-70B down-projection shape: two side
-// wavefronts take longer over the long rows and the composite groups than the row wavefronts take over
-// the row (66 against 57 us), so none are used; QLLM_FUSED_SIDE_WAVES (0..2) is there for measurements.
-int side_waves(const Shape &s)
-{
-    static int want = -1;
-    if (want < 0) {
-        const char *e = getenv("QLLM_FUSED_SIDE_WAVES");
-        want = e ? atoi(e) : 0;
-        if (want < 0 || want > 2) want = 0;
-    }
-    const int most = s.iters == 1 ? 384 : 1024;
-    int n = want;
-    while (n > 0 && s.main + 64 * n > most) --n;
-    return n;
-}
-
-// Chunks (or output groups) per lane and the workgroup size for a row of `units` of them.
-Shape pick_shape(int units)
-{
-    Shape s;
-    if (units <= 256) s = {1, 0, 0};
-    else if (units <= 2048) s = {2, 0, 0};
-    else s = {4, 0, 0};
-    s.main = ((units + s.iters - 1) / s.iters + 63) / 64 * 64;
-    s.nt = s.main + 64 * side_waves(s);
-    return s;
-}
 
 int cu_count()
 {
@@ -954,6 +1028,27 @@ int cu_count()
     }
     cached = n;
     return n;
+}
+
+// Chunks (or output groups) per lane and the workgroup size for N rows of `units` of them.  A workgroup's
+// waves go to the CU's four SIMDs in turn, so the SIMD with the most of them, ceil(waves / 4), sets the pace:
+// the cost of a row is that count times (chunks per lane + the fixed work of a wave and row, about one
+// chunk's worth).  With fewer rows than CUs every workgroup has one row and the fewest chunks per lane win.
+Shape pick_shape(int units, int64_t N)
+{
+    Shape best{0, 0};
+    int best_cost = 0;
+    for (int iters = 1; iters <= 4; ++iters) {
+        const int nt = ((units + iters - 1) / iters + 63) / 64 * 64;
+        if (nt > 1024) continue;
+        const int waves = nt / 64;
+        const int cost = N <= cu_count() ? iters : (waves + 3) / 4 * (iters + 1);
+        if (best.iters == 0 || cost < best_cost) {
+            best = {iters, nt};
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 // What the runtime is asked once per kernel, workgroup size and LDS size and then remembered (no runtime
@@ -1000,10 +1095,8 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
     }
     int64_t grid = (int64_t)cu_count() * per_cu;
     if (grid > a.N) grid = a.N;
-    FusedArgs b = a;
-    b.n_main = sh.main;
     (void)hipGetLastError();
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3((unsigned)sh.nt), lds, stream, b);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3((unsigned)sh.nt), lds, stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         qllm_note_hip_error("planned fused kernel: launch", hipGetErrorName(e));
@@ -1015,8 +1108,9 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
 template <typename XT, int BITS, int NORM, bool FULL>
 int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 384, true, NORM, FULL>, a, sh, lds, stream);
+    if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 1024, true, NORM, FULL>, a, sh, lds, stream);
     if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, NORM, FULL>, a, sh, lds, stream);
+    if (sh.iters == 3) return launch(fused_planned_kernel<XT, BITS, 3, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
     // 16 waves x 4 chunks: gamma fits in registers next to y and the prefetched row, except with LayerNorm
     return launch(fused_planned_kernel<XT, BITS, 4, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
 }
@@ -1024,7 +1118,7 @@ int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t st
 template <typename XT, int BITS, int NORM>
 int32_t dispatch_full(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
 {
-    const bool full = a.n_chunks == sh.iters * sh.main;
+    const bool full = a.n_chunks == sh.iters * sh.nt && a.n_work == a.n_chunks; // every lane has its chunks and every slot a group
     return full ? dispatch<XT, BITS, NORM, true>(a, sh, lds, stream) : dispatch<XT, BITS, NORM, false>(a, sh, lds, stream);
 }
 
@@ -1050,13 +1144,13 @@ int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t b
 {
     const int units = a.n_chunks > a.n_work ? a.n_chunks : a.n_work;
     if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
-    const Shape sh = pick_shape(units);
+    const Shape sh = pick_shape(units, a.N);
     // staged x, and gamma / beta at the same positions when there is a norm / a shift
     const size_t n_stage = (size_t)a.n_pub * GROUP + 4, w = bits == 4 ? 1 : 2;
     const size_t stage_sets = 1 + (a.norm != QLLM_NORM_NONE ? 1 : 0) + (a.norm == QLLM_NORM_LAYER && a.beta ? 1 : 0);
     const size_t lds = (stage_sets * n_stage + (((size_t)a.n_dest + 3) & ~(size_t)3)) * sizeof(float) + (size_t)a.n_long * 16 +
                        (size_t)a.n_comp * 32 + (size_t)a.n_spec * 8 + ((size_t)a.n_comp * w + w + ((size_t)a.n_chunks + 1) * w) * 4 +
-                       ((size_t)a.n_dest + (size_t)a.n_segw + 2 * (size_t)sh.iters * sh.main) * 4;
+                       ((size_t)a.n_dest + (size_t)a.n_segw + 2 * (size_t)sh.iters * sh.nt) * 4;
     if (lds > (size_t)MAX_LDS) return QLLM_ERR_WORKSPACE;
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);
     return dispatch_bits<float>(a, bits, sh, lds, stream);

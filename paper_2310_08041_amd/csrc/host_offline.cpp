@@ -211,17 +211,17 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
     const int64_t off_work = HEAD, off_chunks = round4(off_work + n_work), off_spec = round4(off_chunks + n_chunks);
     const int64_t off_dest = round4(off_spec + 2 * n_spec), off_longs = round4(off_dest + n_dest);
-    const int64_t off_segs = off_longs + 4 * n_long;
-    *plan_len = off_segs + n_segw;
+    const int64_t off_segs = off_longs + 4 * n_long, off_recs = round4(off_segs + n_segw);
+    *plan_len = off_recs + 8 * n_comp;
     if (!plan) return QLLM_OK;
 
     // ---- second pass: the tables
     std::fill(plan, plan + *plan_len, 0);
-    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 6, C_in, C_out, n_work, n_comp, n_chunks, n_long,
+    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 7, C_in, C_out, n_work, n_comp, n_chunks, n_long,
                                           n_pub, n_spec, n_dest, n_segw, off_chunks, *plan_len, off_spec, off_longs};
     for (int64_t k = 0; k < HEAD; ++k) plan[k] = (int32_t)head[k];
     int32_t *work = plan + off_work, *chunks = plan + off_chunks, *spec = plan + off_spec, *dest = plan + off_dest;
-    int32_t *longs = plan + off_longs, *segs = plan + off_segs;
+    int32_t *longs = plan + off_longs, *segs = plan + off_segs, *recs = plan + off_recs;
     for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1; // padding entries are {0, -1, 0.0f, 0}
     const uint32_t zero_at = (uint32_t)(G * n_pub); // the staged zero sits right after the published chunks
     auto staged = [&](int32_t channel) { return (uint32_t)(pub_slot[(size_t)(channel / G)] * G + channel % G); };
@@ -260,6 +260,14 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
             }
         }
         hdr[0] = (int32_t)((uint32_t)n_seg | ((uint32_t)comp << 8));
+        // the same group as one record of fixed size: {count | list offset << 8, d0, mask0, d1, mask1, group, 0, 0}
+        int32_t *rc = recs + 8 * comp;
+        rc[0] = (int32_t)((uint32_t)n_seg | ((uint32_t)seg_at << 8));
+        for (int sg = 0; sg < std::min(n_seg, 2); ++sg) {
+            rc[1 + 2 * sg] = hdr[1 + 3 * sg];
+            rc[2 + 2 * sg] = hdr[2 + 3 * sg];
+        }
+        rc[5] = (int32_t)g;
         desc[(size_t)g] = (int32_t)(-(seg_at + 1));
         seg_at += 1 + 3 * n_seg;
         ++comp;

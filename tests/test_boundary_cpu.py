@@ -157,14 +157,15 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
     n_groups, n_chunks, n_work = (K + 7) // 8, (C + 7) // 8, (K + 255) // 256 * 32
     magic, version, c_in, c_out, nw, n_comp, nc, n_long, n_pub, n_spec, n_dest, n_segw, off_chunks, plan_len, off_spec, \
         off_longs = plan[:16].tolist()
-    assert (magic, version, c_in, c_out, nw, nc) == (0x514C4D50, 6, C, K, n_work, n_chunks)
+    assert (magic, version, c_in, c_out, nw, nc) == (0x514C4D50, 7, C, K, n_work, n_chunks)
     r4 = lambda v: (v + 3) // 4 * 4
     off_work = 16
     assert off_chunks == r4(off_work + n_work) and off_spec == r4(off_chunks + n_chunks)
     off_dest = r4(off_spec + 2 * n_spec)
     assert off_longs == r4(off_dest + n_dest)
     off_segs = off_longs + 4 * n_long
-    assert plan_len == plan.size == off_segs + n_segw
+    off_recs = r4(off_segs + n_segw)
+    assert plan_len == plan.size == off_recs + 8 * n_comp
     work = plan[off_work:off_work + n_work].astype(np.int64) & 0xFFFFFFFF
     kind, grp, field = work >> 30, (work >> 17) & 0x1FFF, work & 0x1FFFF
     assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
@@ -179,7 +180,8 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
     spec = plan[off_spec:off_spec + 2 * n_spec].reshape(n_spec, 2)
     dest = plan[off_dest:off_dest + n_dest]
     longs = plan[off_longs:off_segs].reshape(-1, 4).copy()
-    segs = plan[off_segs:]
+    segs = plan[off_segs:off_segs + n_segw]
+    recs = plan[off_recs:].reshape(n_comp, 8)
     most = longs[:, 3] >> 8                                       # largest position among the 64 entries of a wavefront
     longs[:, 3] &= 0xFF
     for b0 in range(0, n_long, 64):
@@ -196,6 +198,8 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
             hdr = int(segs[f]) & 0xFFFFFFFF
             n_seg, number = hdr & 0xFF, hdr >> 8
             comp_group[number] = int(g)
+            first_two = [int(v) for sg in range(min(n_seg, 2)) for v in segs[f + 1 + 3 * sg:f + 3 + 3 * sg]]
+            assert recs[number].tolist() == [n_seg | (int(f) << 8)] + first_two + [0] * (4 - len(first_two)) + [int(g), 0, 0]
             seen = 0
             for sg in range(n_seg):
                 d, m8, pad = (int(v) for v in segs[f + 1 + 3 * sg:f + 4 + 3 * sg])
