@@ -274,7 +274,8 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  *   copied    one entry with scale exactly 1: the channel's code is the code of its source channel;
  *   computed  one entry with another scale (a sub-channel, Eq. 3) or two entries of equal scale (a merged
  *             pair, Eq. 4): the value is formed from the sources and quantized on its own;
- *   long      any other row (at most 64 entries): summed entry by entry, then as a computed channel.
+ *   long      any other row: summed entry by entry, then as a computed channel (rows of up to 64 entries by
+ *             the lanes of one wavefront in one go, longer ones block by block).
  * and the groups of 8 output channels into "plain" (8 copied channels with consecutive sources d .. d+7:
  * one 8-code window of the input-order codes) and "composite" (anything else: a few windows, each masked
  * to the channels it supplies, plus the codes of its computed and long channels).
@@ -282,18 +283,21 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  * Layout (int32 words; every part starts at a multiple of 4 words, in this order):
  *   [0..15]  header: magic, version, C_in, C_out, n_work = groups of 8 output channels including the zero
  *            padding to 256 codes, n_comp = composite groups (*n_general), n_chunks = ceil(C_in/8), n_long,
- *            n_pub, n_spec, n_dest, n_segw, offset of chunks, plan_len, offset of spec, offset of longs
+ *            n_pub, n_spec, n_dest, n_segw, offset of chunks, plan_len, n_xl = rows of more than 64 entries,
+ *            n_xle = their entries
  *   work     [n_work] at word 16: kind << 30 | group << 17 | field.  kind 0 (plain): field = d; kind 1
  *            (composite): field = offset of the group's segment list inside `segs`; kind 2: padding (all
  *            codes zero).  Sorted by kind, then by group
  *   chunks   [n_chunks]: bits 0..7: bit j set = input channel 8*chunk + j is the source of some copied
  *            channel; bits 8..31: p if some computed or long channel reads a channel of this chunk (the
  *            kernel then stages the chunk's x at floats 8p .. 8p+7 of its on-chip table; p = 0 ..
- *            n_pub-1 in chunk order), 0xffffff otherwise.  Float 8*n_pub of that table is a zero
+ *            n_pub-1 in chunk order), 0xffffff otherwise.  Float 8*n_pub of that table is a zero.  A map whose
+ *            lists could not be held on chip at every setting of the kernel has all chunks staged instead
+ *            (n_pub == n_chunks, p == chunk): a staged position is then the channel number
  *   spec     [n_spec][2]: a computed channel: {s0 | s1 << 16, scale}, s = staged position of the source
  *            channel (s1 = 8*n_pub, the zero, for one entry)
- *   dest     [n_dest]: where the code of computed channel i (i < n_spec) or of long row i - n_spec goes:
- *            number of its composite group << 3 | position in the group
+ *   dest     [n_dest]: where the code of computed channel i (i < n_spec), of long row i - n_spec, or (last) of a
+ *            row of more than 64 entries goes: number of its composite group << 3 | position in the group
  *   longs    [n_long][4]: {s, value slot or -1, scale, pos | most << 8}: entry pos (0, 1, ...) of a long row;
  *            the row's last entry names its slot in `dest`, the others -1.  The kernel gives entry e to lane
  *            e % 64 of a wavefront and adds a row up lane by lane, so the table holds padding entries
@@ -305,7 +309,9 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
  *   recs     [n_comp][8]: the same once more as records of fixed size, by composite group number:
  *            {count | offset of the group's list in segs << 8, d0, mask0, d1, mask1, group, 0, 0} (what the kernel
  *            reads for the first two segments; a group with more takes the rest from segs)
- * QLLM_ERR_MAP: malformed map, or a row of more than 64 entries (such a map runs without a plan).
+ *   xlrows   [n_xl][4]: a row of more than 64 entries: {its first entry in xlent, entries, its slot in dest, 0}
+ *   xlent    [n_xle][2]: {s, scale}, the rows' entries in order
+ * QLLM_ERR_MAP: malformed map, or one whose counts do not fit the fields above.
  */
 int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const float *scale, int64_t C_in,
                            int64_t C_out, int32_t *plan, int64_t *plan_len, int64_t *n_general);
@@ -342,6 +348,23 @@ int32_t qllm_quantize_weight_host(const float *W, int64_t C_in, int64_t O, const
 /* Packs / unpacks rows of one-byte codes into the storage format above (R rows of K codes). */
 int32_t qllm_pack_codes_host(const uint8_t *codes, int64_t R, int64_t K, int32_t bits, uint8_t *packed);
 int32_t qllm_unpack_codes_host(const uint8_t *packed, int64_t R, int64_t K, int32_t bits, uint8_t *codes);
+
+/* Which form of the fused kernel qllm_norm_reassemble_quant runs for this map and these arguments (a host-side
+ * answer: nothing is launched, no device memory is read; map->plan may be a device pointer, map->plan_head is
+ * read on the host).  The per-channel work of Sec. 4.1 (Eq. 3, Eq. 4) is the same in all three; they differ in
+ * where the map's lists live while a row is worked on.
+ *   QLLM_FUSED_WALKS_MAP       no plan, or it fits neither way: every output channel walks its CSR row
+ *   QLLM_FUSED_LISTS_IN_LDS    the planned kernel with the plan's lists copied to LDS once per workgroup
+ *   QLLM_FUSED_LISTS_STREAMED  the planned kernel reading the lists from global memory (L2) row by row: maps
+ *                              with thousands of computed channels on the longest rows
+ * x is assumed 16-byte aligned; ldx in elements as in qllm_norm_reassemble_quant; has_beta != 0: a LayerNorm shift
+ * is given.  Returns one of the three (>= 0) or a QLLM_ERR_* (< 0) for arguments qllm_norm_reassemble_quant
+ * would reject too. */
+#define QLLM_FUSED_WALKS_MAP 0
+#define QLLM_FUSED_LISTS_IN_LDS 1
+#define QLLM_FUSED_LISTS_STREAMED 2
+int32_t qllm_fused_kernel_choice(const qllm_map *map, int32_t x_dtype, int64_t N, int64_t ldx, int32_t norm,
+                                 int32_t has_beta, int32_t bits);
 
 /* ------------------------------------------------------------------------------------------
  * Calibration statistic on the device: the norm of each row as in qllm_norm_reassemble_quant,

@@ -67,6 +67,7 @@ _sigs = {
     "qllm_fold_linear_host": (_i32, [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _i64, _vp, _vp]),
     "qllm_pack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
     "qllm_unpack_codes_host": (_i32, [_vp, _i64, _i64, _i32, _vp]),
+    "qllm_fused_kernel_choice": (_i32, [C.POINTER(_Map), _i32, _i64, _i64, _i32, _i32, _i32]),
     "qllm_norm_channel_absmax": (_i32, [_vp, _i32, _i64, _i64, _i64, _i32, _vp, _vp, _f, _vp, _vp, _i64, _vp]),
     "qllm_match_workspace_bytes": (_i64, [_i64, _i64]),
     "qllm_match_nearest": (_i32, [_vp, _i64, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp]),
@@ -301,6 +302,20 @@ def qllm_norm_reassemble_quant(x, norm, gamma, beta, eps, dmap, bits, out, strea
                                          float(eps), C.byref(dmap.c), int(bits), C.byref(out.c), _stream(stream)),
          "qllm_norm_reassemble_quant")
     return out
+
+
+FUSED_WALKS_MAP, FUSED_LISTS_IN_LDS, FUSED_LISTS_STREAMED = 0, 1, 2
+
+
+def qllm_fused_kernel_choice(dmap, x_dtype, N, ldx, norm, has_beta, bits):
+    """FUSED_* : the form of the fused kernel qllm_norm_reassemble_quant runs for this map and these arguments.
+    x_dtype: F32 / BF16 (or a torch dtype)."""
+    if not isinstance(x_dtype, int):
+        x_dtype = BF16 if "bfloat16" in str(x_dtype) else F32
+    rc = _lib.qllm_fused_kernel_choice(C.byref(dmap.c), int(x_dtype), int(N), int(ldx), int(norm), int(bool(has_beta)), int(bits))
+    if rc < 0:
+        raise QllmError(rc, "qllm_fused_kernel_choice")
+    return rc
 
 
 def qllm_int_gemm(a, weight, y, acc_dump=None, workspace=None, stream=None):

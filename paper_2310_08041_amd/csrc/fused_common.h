@@ -26,8 +26,8 @@ struct FusedArgs {
     double inv_C; // 1 / C
     const int32_t *row_ptr, *src, *desc;
     const float *scale;
-    const int32_t *work, *chunks, *spec, *dest, *longs, *segs, *recs; // the parts of the plan (see qllm_plan_map_host)
-    int32_t n_comp, n_long, n_pub, n_work, n_chunks, n_spec, n_dest, n_segw;
+    const int32_t *work, *chunks, *spec, *dest, *longs, *segs, *recs, *xlrows, *xlent; // the parts of the plan (see qllm_plan_map_host)
+    int32_t n_comp, n_long, n_pub, n_work, n_chunks, n_spec, n_dest, n_segw, n_xl;
     int32_t C_out, n_groups, n_groups_pad, S;
     uint8_t *codes;
     int64_t row_bytes;
@@ -69,5 +69,7 @@ __device__ __forceinline__ int32_t quant_code(float x, float inv, int32_t beta, 
 // Launches the planned kernel (fused_planned.hip).  Returns QLLM_ERR_WORKSPACE if the shape or the
 // general groups are more than it holds on chip: the caller then takes the plain kernel.
 int32_t qllm_launch_fused_planned(const qllm_detail::FusedArgs &a, int32_t x_dtype, int32_t bits, hipStream_t stream);
+// QLLM_FUSED_*: the form of the fused kernel that qllm_launch_fused_planned would run for these arguments
+int32_t qllm_choose_fused_planned(const qllm_detail::FusedArgs &a, int32_t x_dtype, int32_t bits);
 
 #endif

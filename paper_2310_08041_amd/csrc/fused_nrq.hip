@@ -428,6 +428,45 @@ void fill_input(FusedArgs &a, const void *x, int32_t x_dtype, int64_t N, int64_t
     a.S = (int32_t)((C + GROUP - 1) / GROUP);
 }
 
+// The parts of a map's plan: the host copy of its header says where they are (see qllm_plan_map_host).
+int32_t fill_plan(FusedArgs &a, const qllm_map *map, int64_t C)
+{
+    if (!map->plan) return QLLM_OK;
+    const int32_t *h = map->plan_head;
+    if (reinterpret_cast<uintptr_t>(map->plan) & 15u) return QLLM_ERR_ALIGN;
+    if (h[0] != 0x514c4d50 || h[1] != 8 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
+    const int64_t n_chunks = (C + GROUP - 1) / GROUP, n_work = (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP;
+    auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
+    if (h[4] != n_work || h[6] != n_chunks || h[5] < 0 || h[5] > n_work || h[7] < 0 || h[8] < 0 || h[8] > n_chunks ||
+        h[9] < 0 || h[10] < h[9] || h[11] < h[5] || h[14] < 0 || h[14] > h[10] - h[9] || h[15] < 64 * (int64_t)h[14])
+        return QLLM_ERR_MAP;
+    const int64_t off_work = QLLM_PLAN_HEAD, off_chunks = round4(off_work + n_work), off_spec = round4(off_chunks + n_chunks);
+    const int64_t off_dest = round4(off_spec + 2 * (int64_t)h[9]), off_longs = round4(off_dest + h[10]);
+    const int64_t off_segs = off_longs + 4 * (int64_t)h[7];
+    const int64_t off_recs = round4(off_segs + h[11]);
+    const int64_t off_xlrows = off_recs + 8 * (int64_t)h[5], off_xlent = off_xlrows + 4 * (int64_t)h[14];
+    if (h[12] != off_chunks || h[13] != off_xlent + 2 * (int64_t)h[15]) return QLLM_ERR_MAP;
+    a.work = map->plan + off_work;
+    a.chunks = map->plan + off_chunks;
+    a.spec = map->plan + off_spec;
+    a.dest = map->plan + off_dest;
+    a.longs = map->plan + off_longs;
+    a.segs = map->plan + off_segs;
+    a.recs = map->plan + off_recs;
+    a.xlrows = map->plan + off_xlrows;
+    a.xlent = map->plan + off_xlent;
+    a.n_xl = h[14];
+    a.n_work = h[4];
+    a.n_comp = h[5];
+    a.n_chunks = h[6];
+    a.n_long = h[7];
+    a.n_pub = h[8];
+    a.n_spec = h[9];
+    a.n_dest = h[10];
+    a.n_segw = h[11];
+    return QLLM_OK;
+}
+
 } // namespace
 
 extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
@@ -451,36 +490,8 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     a.row_ptr = map->row_ptr;
     a.src = map->src;
     a.scale = map->scale;
-    if (map->plan) { // the host copy of the header says where the parts are: see qllm_plan_map_host
-        const int32_t *h = map->plan_head;
-        if (reinterpret_cast<uintptr_t>(map->plan) & 15u) return QLLM_ERR_ALIGN;
-        if (h[0] != 0x514c4d50 || h[1] != 7 || h[2] != C || h[3] != map->C_out) return QLLM_ERR_MAP;
-        const int64_t n_chunks = (C + GROUP - 1) / GROUP, n_work = (map->C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / GROUP;
-        auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
-        if (h[4] != n_work || h[6] != n_chunks || h[5] < 0 || h[5] > n_work || h[7] < 0 || h[8] < 0 || h[8] > n_chunks ||
-            h[9] < 0 || h[10] < h[9] || h[11] < h[5])
-            return QLLM_ERR_MAP;
-        const int64_t off_work = QLLM_PLAN_HEAD, off_chunks = round4(off_work + n_work), off_spec = round4(off_chunks + n_chunks);
-        const int64_t off_dest = round4(off_spec + 2 * (int64_t)h[9]), off_longs = round4(off_dest + h[10]);
-        const int64_t off_segs = off_longs + 4 * (int64_t)h[7];
-        const int64_t off_recs = round4(off_segs + h[11]);
-        if (h[12] != off_chunks || h[14] != off_spec || h[15] != off_longs || h[13] != off_recs + 8 * (int64_t)h[5]) return QLLM_ERR_MAP;
-        a.work = map->plan + off_work;
-        a.chunks = map->plan + off_chunks;
-        a.spec = map->plan + off_spec;
-        a.dest = map->plan + off_dest;
-        a.longs = map->plan + off_longs;
-        a.segs = map->plan + off_segs;
-        a.recs = map->plan + off_recs;
-        a.n_work = h[4];
-        a.n_comp = h[5];
-        a.n_chunks = h[6];
-        a.n_long = h[7];
-        a.n_pub = h[8];
-        a.n_spec = h[9];
-        a.n_dest = h[10];
-        a.n_segw = h[11];
-    }
+    rc = fill_plan(a, map, C);
+    if (rc != QLLM_OK) return rc;
     a.C_out = (int32_t)map->C_out;
     a.n_groups = (int32_t)((map->C_out + GROUP - 1) / GROUP);
     a.row_bytes = qllm_packed_row_bytes(map->C_out, bits);
@@ -497,6 +508,25 @@ extern "C" int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, in
     }
     if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, max_units, stream);
     return dispatch_bits<float>(a, bits, max_units, stream);
+}
+
+extern "C" int32_t qllm_fused_kernel_choice(const qllm_map *map, int32_t x_dtype, int64_t N, int64_t ldx, int32_t norm,
+                                            int32_t has_beta, int32_t bits)
+{
+    if (!map) return QLLM_ERR_NULL;
+    if (x_dtype != QLLM_F32 && x_dtype != QLLM_BF16) return QLLM_ERR_DTYPE;
+    if (norm != QLLM_NORM_NONE && norm != QLLM_NORM_LAYER && norm != QLLM_NORM_RMS) return QLLM_ERR_DTYPE;
+    if (bits != 4 && bits != 6 && bits != 8) return QLLM_ERR_BITS;
+    const int64_t C = map->C_in;
+    if (N < 0 || N > INT32_MAX || C <= 0 || C > QLLM_MAX_CHANNELS || ldx < C || map->C_out <= 0 || map->C_out > QLLM_MAX_CHANNELS)
+        return QLLM_ERR_SHAPE;
+    FusedArgs a{};
+    // stand-ins for the buffers: 16-byte aligned, and only their being there or not matters here
+    static const float present[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    fill_input(a, nullptr, x_dtype, N, C, ldx, norm, present, has_beta ? present : nullptr, 0.0f);
+    const int32_t rc = fill_plan(a, map, C);
+    if (rc != QLLM_OK) return rc;
+    return qllm_choose_fused_planned(a, x_dtype, bits);
 }
 
 extern "C" int32_t qllm_norm_channel_absmax(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,

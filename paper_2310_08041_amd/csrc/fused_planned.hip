@@ -37,6 +37,7 @@
 
 #include "qllm.h"
 #include "fused_common.h"
+#include "plan_budget.h"
 
 using namespace qllm_detail;
 
@@ -79,6 +80,9 @@ __device__ __forceinline__ void widen(const Raw<uint16_t> &r, float *v)
         v[2 * p + 1] = __uint_as_float(w[p] & 0xffff0000u);
     }
 }
+
+__device__ __forceinline__ float widen_one(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ float widen_one(float f) { return f; }
 
 __device__ __forceinline__ void widen(const Raw<float> &r, float *v)
 {
@@ -154,6 +158,18 @@ __device__ __forceinline__ float below(float v)
     float r;
     asm("s_nop 1\n\tv_mov_b32_dpp %0, %1 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "=v"(r) : "v"(v));
     return r;
+}
+
+// One step of the lane-by-lane addition of a long row: (value of the lane below) * keep + p in one rounding,
+// the shift folded into the multiply-add.  The copy of p does not depend on the step before, so only the
+// multiply-add (and the two idle states a DPP read needs after the write of its source) sit on the chain.
+__device__ __forceinline__ float chain_step(float acc, float keep, float p)
+{
+    float t;
+    asm("v_mov_b32 %0, %3\n\ts_nop 0\n\tv_fmac_f32_dpp %0, %1, %2 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0"
+        : "=&v"(t)
+        : "v"(acc), "v"(keep), "v"(p));
+    return t;
 }
 
 // v + (v of the partner lane) in fp64: the two halves move separately, the addition is ordinary
@@ -417,7 +433,12 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
 // NORM: QLLM_NORM_NONE / LAYER / RMS.  GAM_REG: the lane's share of gamma stays in registers for the
 // lifetime of the workgroup; otherwise it is re-read (from L2) for every row, which frees 8 registers per chunk.
 // FULL: the row fills the workgroup exactly (chunks = ITERS x lanes): no bounds tests.
-template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, int NORM, bool FULL>
+// STREAM: for maps whose lists do not fit in LDS next to the row (a 28 672-channel row with a few thousand
+// computed channels).  The lists of the irregular part stay in global memory (every workgroup reads the same
+// few hundred KB: they live in L2), every chunk of the row is staged, in the input's own type, at its own
+// position (the plan then has n_pub == n_chunks, so a staged position IS the channel number), and gamma /
+// beta of a source are read from global memory by that number.
+template <typename XT, int BITS, int ITERS, int NT_MAX, bool GAM_REG, int NORM, bool FULL, bool STREAM = false>
 __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a)
 {
     constexpr bool LAYER = NORM == QLLM_NORM_LAYER, RMS = NORM == QLLM_NORM_RMS;
@@ -431,17 +452,33 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     float *pub = lds;                          // [n_stage] x of the staged chunks; [8 n_pub ..] stays zero
     float *pubg = lds + goff;                  // [n_stage] gamma at the same positions, 0 for the zero (not with NORM_NONE)
     float *pubb = lds + boff;                  // [n_stage] beta likewise (LayerNorm with a shift only)
-    float *specv = lds + boff + n_stage;       // [n_dest4] values of the computed channels
+    XT *pubx = reinterpret_cast<XT *>(lds);    // STREAM: [C + 8] the row as it came; [C ..] stays zero
+    const int n_stage_words = STREAM ? (int)(((size_t)(a.C + GROUP) * sizeof(XT) + 15) / 16 * 4) : boff + n_stage;
+    float *specv = lds + n_stage_words;        // [n_dest4] values of the computed channels
     const int n_dest4 = (a.n_dest + 3) & ~3;
-    int4 *longs = reinterpret_cast<int4 *>(specv + n_dest4);           // [n_long] entries of the long rows
-    uint4 *rec = reinterpret_cast<uint4 *>(longs + a.n_long);          // [n_comp][2] a composite group: its first two segments, its number
-    int2 *spec = reinterpret_cast<int2 *>(rec + 2 * a.n_comp);         // [n_spec] {staged sources, scale}
-    uint32_t *ins = reinterpret_cast<uint32_t *>(spec + a.n_spec);     // [n_comp * W] codes of the computed channels, in place
+    // the lists of the irregular part: copies in LDS, or (STREAM) the plan's own in global memory
+    int4 *longs_w = reinterpret_cast<int4 *>(specv + n_dest4);         // [n_long] entries of the long rows
+    uint4 *rec_w = reinterpret_cast<uint4 *>(longs_w + a.n_long);      // [n_comp][2] a composite group: its first two segments, its number
+    int2 *spec_w = reinterpret_cast<int2 *>(rec_w + 2 * a.n_comp);     // [n_spec] {staged sources, scale}
+    uint32_t *ins = STREAM ? reinterpret_cast<uint32_t *>(specv + n_dest4)
+                           : reinterpret_cast<uint32_t *>(spec_w + a.n_spec); // [n_comp * W] codes of the computed channels, in place
     uint32_t *pk = ins + a.n_comp * W + W;                             // [-1 .. n_chunks] * W packed codes, input order; both ends zero
-    int32_t *dest = reinterpret_cast<int32_t *>(pk + (a.n_chunks + 1) * W); // [n_dest] composite group << 3 | position
-    uint32_t *segs = reinterpret_cast<uint32_t *>(dest + a.n_dest);    // [n_segw] segments of the composite groups
-    uint32_t *chunkw = segs + a.n_segw;                                // [ITERS * lanes] pass bits | staging slot << 8
+    int32_t *dest_w = reinterpret_cast<int32_t *>(pk + (a.n_chunks + 1) * W); // [n_dest] composite group << 3 | position
+    uint32_t *segs_w = reinterpret_cast<uint32_t *>(dest_w + a.n_dest); // [n_segw] segments of the composite groups
+    uint32_t *chunkw = STREAM ? pk + (a.n_chunks + 1) * W : segs_w + a.n_segw; // [ITERS * lanes] pass bits | staging slot << 8
     int32_t *work = reinterpret_cast<int32_t *>(chunkw + ITERS * blockDim.x); // [ITERS * lanes] plain and padding output groups
+    const int4 *longs = longs_w;
+    const uint4 *rec = rec_w;
+    const int2 *spec = spec_w;
+    const int32_t *dest = dest_w;
+    const uint32_t *segs = segs_w;
+    if constexpr (STREAM) {
+        longs = reinterpret_cast<const int4 *>(a.longs);
+        rec = reinterpret_cast<const uint4 *>(a.recs);
+        spec = reinterpret_cast<const int2 *>(a.spec);
+        dest = a.dest;
+        segs = reinterpret_cast<const uint32_t *>(a.segs);
+    }
     __shared__ double red_d[2][16];
     __shared__ float red_f[32];
     __shared__ int32_t red_i[16];
@@ -486,7 +523,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         if constexpr (GAM_REG) load_gamma(gam[it], a.gamma, sl * GROUP, a.C, NORM != QLLM_NORM_NONE);
     }
     // the first lanes' worth of every list in flight at once; what is left of a longer list follows below
-    const bool has_long = tid < a.n_long, has_spec = tid < a.n_spec, has_dest = tid < a.n_dest, has_rec = tid < a.n_comp;
+    const bool has_long = !STREAM && tid < a.n_long, has_spec = !STREAM && tid < a.n_spec, has_dest = !STREAM && tid < a.n_dest,
+               has_rec = !STREAM && tid < a.n_comp;
     int4 l0 = make_int4(0, 0, 0, 0);
     int2 s0 = make_int2(0, 0);
     int32_t d0 = 0;
@@ -500,18 +538,20 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     }
     uint32_t sg0[ITERS];
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) sg0[it] = tid + it * nt < a.n_segw ? (uint32_t)a.segs[tid + it * nt] : 0u;
+    for (int it = 0; it < ITERS; ++it) sg0[it] = !STREAM && tid + it * nt < a.n_segw ? (uint32_t)a.segs[tid + it * nt] : 0u;
 
     // A composite group's record {count | list << 8, d0, mask0, d1, mask1, group}: masks widened to code fields,
     // laid out for one pair of wide LDS reads.  The list itself (for groups of more than two segments) stays as
     // it is: {d, mask, -} per segment, widened where it is used.
     auto put_rec = [&](int c, const uint4 &p, const uint4 &q) {
         const uint64_t m0 = widen_mask<BITS>(p.z), m1 = widen_mask<BITS>(q.x);
-        rec[2 * c] = make_uint4(p.x, p.y, (uint32_t)m0, (uint32_t)(m0 >> 32));
-        rec[2 * c + 1] = make_uint4(p.w, (uint32_t)m1, (uint32_t)(m1 >> 32), q.y);
+        rec_w[2 * c] = make_uint4(p.x, p.y, (uint32_t)m0, (uint32_t)(m0 >> 32));
+        rec_w[2 * c + 1] = make_uint4(p.w, (uint32_t)m1, (uint32_t)(m1 >> 32), q.y);
     };
     for (int j = tid; j < a.n_comp * W; j += nt) ins[j] = 0u;
-    if (tid < 4) { // the zero: x = 0, gamma = 0, beta = 0, so that its y is a zero whatever the row's statistics
+    if constexpr (STREAM) {
+        if (tid < GROUP) pubx[a.C + tid] = (XT)0; // the zero (bf16 bits or a float); gamma and beta of it read as 0
+    } else if (tid < 4) { // the zero: x = 0, gamma = 0, beta = 0, so that its y is a zero whatever the row's statistics
         pub[GROUP * a.n_pub + tid] = 0.0f;
         if (NORM != QLLM_NORM_NONE) pubg[GROUP * a.n_pub + tid] = 0.0f;
         if (shift) pubb[GROUP * a.n_pub + tid] = 0.0f;
@@ -527,24 +567,26 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         red_f[16 + tid] = inf; // minus the maximum
         red_i[tid] = 0;
     }
-    if (has_long) longs[tid] = l0;
-    if (has_spec) spec[tid] = s0;
-    if (has_dest) dest[tid] = d0;
+    if (has_long) longs_w[tid] = l0;
+    if (has_spec) spec_w[tid] = s0;
+    if (has_dest) dest_w[tid] = d0;
     if (has_rec) put_rec(tid, ra, rb);
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int sl = tid + it * nt;
         chunkw[sl] = cw0[it];
         work[sl] = we0[it];
-        if (sl < a.n_segw) segs[sl] = sg0[it];
+        if (!STREAM && sl < a.n_segw) segs_w[sl] = sg0[it];
     }
-    for (int j = tid + nt; j < a.n_long; j += nt) longs[j] = reinterpret_cast<const int4 *>(a.longs)[j];
-    for (int j = tid + nt; j < a.n_spec; j += nt) spec[j] = reinterpret_cast<const int2 *>(a.spec)[j];
-    for (int j = tid + nt; j < a.n_dest; j += nt) dest[j] = a.dest[j];
-    for (int j = tid + nt; j < a.n_comp; j += nt) put_rec(j, reinterpret_cast<const uint4 *>(a.recs)[2 * j], reinterpret_cast<const uint4 *>(a.recs)[2 * j + 1]);
-    for (int j = tid + ITERS * nt; j < a.n_segw; j += nt) segs[j] = (uint32_t)a.segs[j];
+    if constexpr (!STREAM) {
+        for (int j = tid + nt; j < a.n_long; j += nt) longs_w[j] = reinterpret_cast<const int4 *>(a.longs)[j];
+        for (int j = tid + nt; j < a.n_spec; j += nt) spec_w[j] = reinterpret_cast<const int2 *>(a.spec)[j];
+        for (int j = tid + nt; j < a.n_dest; j += nt) dest_w[j] = a.dest[j];
+        for (int j = tid + nt; j < a.n_comp; j += nt) put_rec(j, reinterpret_cast<const uint4 *>(a.recs)[2 * j], reinterpret_cast<const uint4 *>(a.recs)[2 * j + 1]);
+        for (int j = tid + ITERS * nt; j < a.n_segw; j += nt) segs_w[j] = (uint32_t)a.segs[j];
+    }
     // norm parameters of the staged chunks
-    if constexpr (NORM != QLLM_NORM_NONE) {
+    if constexpr (NORM != QLLM_NORM_NONE && !STREAM) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int sl = tid + it * nt;
@@ -613,8 +655,17 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     // ---- step a4, second half, of the row before: the output groups.  A plain group is two neighbouring
     //      packed words funnel-shifted; a composite group is several such windows, each masked to the
     //      channels it supplies, plus the codes of its computed channels.
-    auto composite = [&](int comp, uint32_t &w0, uint32_t &w1) -> int {
-        const uint4 r0 = rec[2 * comp], r1 = rec[2 * comp + 1]; // {count | list << 8, d0, mask0}, {d1, mask1, group}
+    struct RecPair {
+        uint4 r0, r1;
+    };
+    auto rec_fetch = [&](int comp) -> RecPair { return RecPair{rec[2 * comp], rec[2 * comp + 1]}; };
+    auto composite_of = [&](const RecPair &rp, int comp, uint32_t &w0, uint32_t &w1) -> int {
+        uint4 r0 = rp.r0, r1 = rp.r1; // {count | list << 8, d0, mask0}, {d1, mask1, group}
+        if constexpr (STREAM) { // the plan's own record {count | list << 8, d0, mask0, d1}, {mask1, group, -, -}: masks still one bit per code
+            const uint64_t m0 = widen_mask<BITS>(r0.z), m1 = widen_mask<BITS>(r1.x);
+            r1 = make_uint4(r0.w, (uint32_t)m1, (uint32_t)(m1 >> 32), r1.y);
+            r0 = make_uint4(r0.x, r0.y, (uint32_t)m0, (uint32_t)(m0 >> 32));
+        }
         uint32_t i0 = ins[comp * W], i1 = 0u;
         ins[comp * W] = 0u; // ready for the next row's codes
         if constexpr (W == 2) {
@@ -638,10 +689,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         w1 = i1;
         return (int)r1.w;
     };
+    auto composite = [&](int comp, uint32_t &w0, uint32_t &w1) -> int { return composite_of(rec_fetch(comp), comp, w0, w1); };
     // The output pass in pieces, so that the row loop can put other work between its LDS reads and their use.
     struct OutState {
         int32_t e[ITERS];
         Window<BITS> win[ITERS];
+        RecPair rp; // STREAM: the record of the last slot's composite group, requested together with the packed words
     };
     auto out_read_work = [&](OutState &o, int ltid) {
 #pragma unroll
@@ -652,6 +705,10 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         for (int it = 0; it < ITERS; ++it) {
             const int d = ((uint32_t)o.e[it] >> 30) == KIND_PLAIN ? o.e[it] & 0x1ffff : 0;
             o.win[it] = funnel_fetch<BITS>(pk, d >> 3);
+        }
+        if constexpr (STREAM) {
+            const bool comp = ((uint32_t)o.e[ITERS - 1] >> 30) == KIND_COMP;
+            o.rp = rec_fetch(comp ? o.e[ITERS - 1] & 0x1ffff : 0);
         }
     };
     auto out_store = [&](OutState &o, int64_t prev, int ltid) {
@@ -668,7 +725,11 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             g[it] = (o.e[it] >> 17) & 0x1fff;
         }
         // composite groups sit in slots of the last pass only
-        if (((uint32_t)o.e[ITERS - 1] >> 30) == KIND_COMP) g[ITERS - 1] = composite(o.e[ITERS - 1] & 0x1ffff, w0[ITERS - 1], w1[ITERS - 1]);
+        if (((uint32_t)o.e[ITERS - 1] >> 30) == KIND_COMP) {
+            const int comp = o.e[ITERS - 1] & 0x1ffff;
+            if constexpr (STREAM) g[ITERS - 1] = composite_of(o.rp, comp, w0[ITERS - 1], w1[ITERS - 1]);
+            else g[ITERS - 1] = composite(comp, w0[ITERS - 1], w1[ITERS - 1]);
+        }
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             if (FULL || ((uint32_t)o.e[it] >> 30) != KIND_NONE) {
@@ -676,10 +737,13 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 sum += code_sum<BITS>(w0[it], w1[it]);
             }
         }
-        if (n_loop > 0) { // more composite groups than free slots
+        if (n_loop > 0) { // more composite groups than free slots; the next one's record is under way while this one is put together
+            RecPair next = rec_fetch(ltid < n_loop ? ltid : 0);
             for (int comp = ltid; comp < n_loop; comp += nt) {
+                const RecPair cur = next;
+                if (comp + nt < n_loop) next = rec_fetch(comp + nt);
                 uint32_t c0, c1;
-                const int gc = composite(comp, c0, c1);
+                const int gc = composite_of(cur, comp, c0, c1);
                 store_group<BITS>(out_row, gc, c0, c1);
                 sum += code_sum<BITS>(c0, c1);
             }
@@ -718,6 +782,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         for (int it = 0; it < ITERS; ++it) {
             if (FULL || ltid + it * nt < n_chunks) {
                 widen(raw[it], y[it]);
+                if constexpr (STREAM) *reinterpret_cast<Raw<XT> *>(pubx + (ltid + it * nt) * GROUP) = raw[it]; // the whole row is staged
             } else {
 #pragma unroll
                 for (int j = 0; j < GROUP; ++j) y[it][j] = 0.0f;
@@ -772,7 +837,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         // ---- x of the chunks that hold a source of a computed channel (normalised by its readers in interval 2)
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            if (slot[it] != NOT_PUBLISHED) {
+            if (!STREAM && slot[it] != NOT_PUBLISHED) {
                 float4 *dst = reinterpret_cast<float4 *>(pub + slot[it] * GROUP);
                 dst[0] = make_float4(y[it][0], y[it][1], y[it][2], y[it][3]);
                 dst[1] = make_float4(y[it][4], y[it][5], y[it][6], y[it][7]);
@@ -797,9 +862,16 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         };
         auto staged_fetch = [&](uint32_t pos) -> Staged {
             Staged v;
-            v.x = pub[pos];
-            v.g = NORM != QLLM_NORM_NONE ? pubg[pos] : 1.0f;
-            v.b = shift ? pubb[pos] : 0.0f;
+            if constexpr (STREAM) {
+                const bool real = pos < (uint32_t)a.C; // else the zero
+                v.x = widen_one(pubx[pos]);
+                v.g = NORM != QLLM_NORM_NONE ? (real ? a.gamma[pos] : 0.0f) : 1.0f;
+                v.b = shift && real ? a.beta[pos] : 0.0f;
+            } else {
+                v.x = pub[pos];
+                v.g = NORM != QLLM_NORM_NONE ? pubg[pos] : 1.0f;
+                v.b = shift ? pubb[pos] : 0.0f;
+            }
             return v;
         };
         const bool spec0 = ltid < a.n_spec;
@@ -927,13 +999,55 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                 int t = 0;
                 for (; t + 4 <= steps; t += 4) {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) acc = __builtin_fmaf(below(acc), keep, p);
+                    for (int u = 0; u < 4; ++u) acc = chain_step(acc, keep, p);
                 }
-                for (; t < steps; ++t) acc = __builtin_fmaf(below(acc), keep, p);
+                for (; t < steps; ++t) acc = chain_step(acc, keep, p);
                 if (le.y >= 0) {
                     specv[le.y] = acc;
                     mn = fminf(mn, acc);
                     mx = fmaxf(mx, acc);
+                }
+            }
+            // Rows of more than 64 entries (a few "hub" channels that very many others were merged into): one
+            // wavefront per row, 64 entries at a time by the same lane-by-lane addition; the sum so far enters the
+            // next block as "sum + first product", which is the next step of the same left-to-right order.  Their
+            // lists are read from global memory (they are short and rare).
+            if (a.n_xl > 0) {
+                for (int r = wave; r < a.n_xl; r += nt >> 6) {
+                    const int4 hd = reinterpret_cast<const int4 *>(a.xlrows)[r];
+                    const int first = __builtin_amdgcn_readfirstlane(hd.x), n = __builtin_amdgcn_readfirstlane(hd.y);
+                    const int value_slot = __builtin_amdgcn_readfirstlane(hd.z);
+                    const float keep = lane > 0 ? 1.0f : 0.0f;
+                    float sum = 0.0f;
+                    for (int e0 = 0; e0 < n; e0 += 256) { // four blocks' entries and staged values requested at once
+                        int2 item[4];
+                        Staged sv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int e = e0 + 64 * u + lane;
+                            item[u] = make_int2((int32_t)zero_at, 0);
+                            if (e < n) item[u] = reinterpret_cast<const int2 *>(a.xlent)[first + e];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) sv[u] = staged_fetch((uint32_t)item[u].x);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int b0 = e0 + 64 * u;
+                            if (b0 < n) {
+                                float p = __int_as_float(item[u].y) * staged_norm(sv[u]);
+                                if (b0 > 0 && lane == 0) p = sum + p;
+                                const int steps = n - b0 - 1 < 63 ? n - b0 - 1 : 63; // the block's last entry sits in this lane
+                                float acc = p;
+                                for (int t = 0; t < steps; ++t) acc = chain_step(acc, keep, p);
+                                sum = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(acc), steps));
+                            }
+                        }
+                    }
+                    if (lane == 0) {
+                        specv[value_slot] = sum;
+                        mn = fminf(mn, sum);
+                        mx = fmaxf(mx, sum);
+                    }
                 }
             }
         }
@@ -1054,7 +1168,7 @@ Shape pick_shape(int units, int64_t N)
 // What the runtime is asked once per kernel, workgroup size and LDS size and then remembered (no runtime
 // query sits between a caller's stream capture and the launch): the raised LDS limit and the number of
 // resident workgroups per CU.
-constexpr int MAX_LDS = 159 * 1024; // dynamic LDS a launch may ask for (160 KB per CU, less the static arrays)
+constexpr int MAX_LDS = (int)qllm_detail::FUSED_MAX_LDS; // dynamic LDS a launch may ask for
 struct LaunchFacts {
     const void *kernel;
     int nt;
@@ -1106,52 +1220,80 @@ int32_t launch(K kernel, const FusedArgs &a, const Shape &sh, size_t lds, hipStr
 }
 
 template <typename XT, int BITS, int NORM, bool FULL>
-int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, bool stream_lists, hipStream_t stream)
 {
+    // 4 chunks per lane: gamma fits in registers next to y and the prefetched row, except with LayerNorm
+    if (stream_lists) return launch(fused_planned_kernel<XT, BITS, 4, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL, true>, a, sh, lds, stream);
     if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 1024, true, NORM, FULL>, a, sh, lds, stream);
     if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, NORM, FULL>, a, sh, lds, stream);
     if (sh.iters == 3) return launch(fused_planned_kernel<XT, BITS, 3, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
-    // 16 waves x 4 chunks: gamma fits in registers next to y and the prefetched row, except with LayerNorm
     return launch(fused_planned_kernel<XT, BITS, 4, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
 }
 
 template <typename XT, int BITS, int NORM>
-int32_t dispatch_full(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+int32_t dispatch_full(const FusedArgs &a, const Shape &sh, size_t lds, bool stream_lists, hipStream_t stream)
 {
-    const bool full = a.n_chunks == sh.iters * sh.nt && a.n_work == a.n_chunks; // every lane has its chunks and every slot a group
-    return full ? dispatch<XT, BITS, NORM, true>(a, sh, lds, stream) : dispatch<XT, BITS, NORM, false>(a, sh, lds, stream);
+    // every lane has its chunks and every slot a group (the composite groups all fit in the last pass's slots;
+    // otherwise the slots before that pass that the plain groups leave over stay empty)
+    const bool full = a.n_chunks == sh.iters * sh.nt && a.n_work == a.n_chunks && a.n_comp <= sh.nt;
+    return full ? dispatch<XT, BITS, NORM, true>(a, sh, lds, stream_lists, stream) : dispatch<XT, BITS, NORM, false>(a, sh, lds, stream_lists, stream);
 }
 
 template <typename XT, int BITS>
-int32_t dispatch_norm(const FusedArgs &a, const Shape &sh, size_t lds, hipStream_t stream)
+int32_t dispatch_norm(const FusedArgs &a, const Shape &sh, size_t lds, bool stream_lists, hipStream_t stream)
 {
-    if (a.norm == QLLM_NORM_LAYER) return dispatch_full<XT, BITS, QLLM_NORM_LAYER>(a, sh, lds, stream);
-    if (a.norm == QLLM_NORM_RMS) return dispatch_full<XT, BITS, QLLM_NORM_RMS>(a, sh, lds, stream);
-    return dispatch_full<XT, BITS, QLLM_NORM_NONE>(a, sh, lds, stream);
+    if (a.norm == QLLM_NORM_LAYER) return dispatch_full<XT, BITS, QLLM_NORM_LAYER>(a, sh, lds, stream_lists, stream);
+    if (a.norm == QLLM_NORM_RMS) return dispatch_full<XT, BITS, QLLM_NORM_RMS>(a, sh, lds, stream_lists, stream);
+    return dispatch_full<XT, BITS, QLLM_NORM_NONE>(a, sh, lds, stream_lists, stream);
 }
 
 template <typename XT>
-int32_t dispatch_bits(const FusedArgs &a, int bits, const Shape &sh, size_t lds, hipStream_t stream)
+int32_t dispatch_bits(const FusedArgs &a, int bits, const Shape &sh, size_t lds, bool stream_lists, hipStream_t stream)
 {
-    if (bits == 4) return dispatch_norm<XT, 4>(a, sh, lds, stream);
-    if (bits == 6) return dispatch_norm<XT, 6>(a, sh, lds, stream);
-    return dispatch_norm<XT, 8>(a, sh, lds, stream);
+    if (bits == 4) return dispatch_norm<XT, 4>(a, sh, lds, stream_lists, stream);
+    if (bits == 6) return dispatch_norm<XT, 6>(a, sh, lds, stream_lists, stream);
+    return dispatch_norm<XT, 8>(a, sh, lds, stream_lists, stream);
+}
+
+// Which form of the kernel a map gets, with its launch shape and LDS size: the lists of the irregular part in
+// LDS when they fit there next to the row's packed codes; else, if the plan stages every chunk, the lists
+// streamed from global memory; else none (the caller then runs the kernel that walks the CSR map).
+struct Choice {
+    int kind; // QLLM_FUSED_WALKS_MAP / QLLM_FUSED_LISTS_IN_LDS / QLLM_FUSED_LISTS_STREAMED
+    Shape sh;
+    size_t lds;
+};
+
+Choice choose(const FusedArgs &a, int32_t x_dtype, int32_t bits)
+{
+    Choice c{QLLM_FUSED_WALKS_MAP, {0, 0}, 0};
+    const int units = a.n_chunks > a.n_work ? a.n_chunks : a.n_work;
+    if (!a.work || units > 4096 || !a.vec_ok || a.C % GROUP != 0) return c;
+    const qllm_detail::PlanCounts p{a.n_comp, a.n_long, a.n_pub, a.n_chunks, a.n_spec, a.n_dest, a.n_segw};
+    const int64_t w = bits == 4 ? 1 : 2;
+    {
+        const Shape sh = pick_shape(units, a.N);
+        // staged x, and gamma / beta at the same positions when there is a norm / a shift
+        const int64_t stage_sets = 1 + (a.norm != QLLM_NORM_NONE ? 1 : 0) + (a.norm == QLLM_NORM_LAYER && a.beta ? 1 : 0);
+        const int64_t lds = qllm_detail::fused_lists_lds_bytes(p, w, stage_sets, (int64_t)sh.iters * sh.nt);
+        if (lds <= MAX_LDS) return Choice{QLLM_FUSED_LISTS_IN_LDS, sh, (size_t)lds};
+    }
+    if (a.n_pub != a.n_chunks) return c; // staged positions are not channel numbers
+    const Shape sh{4, ((units + 3) / 4 + 63) / 64 * 64};
+    const int64_t lds = qllm_detail::fused_streamed_lds_bytes(p, w, a.C, x_dtype == QLLM_BF16 ? 2 : 4, (int64_t)sh.iters * sh.nt);
+    if (lds <= MAX_LDS) return Choice{QLLM_FUSED_LISTS_STREAMED, sh, (size_t)lds};
+    return c;
 }
 
 } // namespace
 
+int32_t qllm_choose_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t bits) { return choose(a, x_dtype, bits).kind; }
+
 int32_t qllm_launch_fused_planned(const FusedArgs &a, int32_t x_dtype, int32_t bits, hipStream_t stream)
 {
-    const int units = a.n_chunks > a.n_work ? a.n_chunks : a.n_work;
-    if (units > 4096 || !a.vec_ok || a.C % GROUP != 0) return QLLM_ERR_WORKSPACE;
-    const Shape sh = pick_shape(units, a.N);
-    // staged x, and gamma / beta at the same positions when there is a norm / a shift
-    const size_t n_stage = (size_t)a.n_pub * GROUP + 4, w = bits == 4 ? 1 : 2;
-    const size_t stage_sets = 1 + (a.norm != QLLM_NORM_NONE ? 1 : 0) + (a.norm == QLLM_NORM_LAYER && a.beta ? 1 : 0);
-    const size_t lds = (stage_sets * n_stage + (((size_t)a.n_dest + 3) & ~(size_t)3)) * sizeof(float) + (size_t)a.n_long * 16 +
-                       (size_t)a.n_comp * 32 + (size_t)a.n_spec * 8 + ((size_t)a.n_comp * w + w + ((size_t)a.n_chunks + 1) * w) * 4 +
-                       ((size_t)a.n_dest + (size_t)a.n_segw + 2 * (size_t)sh.iters * sh.nt) * 4;
-    if (lds > (size_t)MAX_LDS) return QLLM_ERR_WORKSPACE;
-    if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, sh, lds, stream);
-    return dispatch_bits<float>(a, bits, sh, lds, stream);
+    const Choice c = choose(a, x_dtype, bits);
+    if (c.kind == QLLM_FUSED_WALKS_MAP) return QLLM_ERR_WORKSPACE;
+    const bool stream_lists = c.kind == QLLM_FUSED_LISTS_STREAMED;
+    if (x_dtype == QLLM_BF16) return dispatch_bits<uint16_t>(a, bits, c.sh, c.lds, stream_lists, stream);
+    return dispatch_bits<float>(a, bits, c.sh, c.lds, stream_lists, stream);
 }

@@ -5,6 +5,7 @@
 // bipartite A/B split of Appendix A, uniform quantizer Eq. (2), per-output-channel weights
 // (Sec. 5 "Quantization settings"), weight-side rewrites of Appendix B.
 #include "qllm.h"
+#include "plan_budget.h"
 
 #include <algorithm>
 #include <cmath>
@@ -165,7 +166,8 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
     // ---- first pass: sizes
     std::vector<int32_t> pub_slot((size_t)n_chunks, -1), desc((size_t)n_groups);
     std::vector<uint8_t> pass((size_t)n_chunks, 0);
-    int64_t n_comp = 0, n_long = 0, n_spec = 0, n_rows_long = 0, n_segw = 0;
+    int64_t n_comp = 0, n_long = 0, n_spec = 0, n_rows_long = 0, n_segw = 0, n_xl = 0, n_xle = 0;
+    std::vector<std::pair<int32_t, int32_t>> long_rows; // {entries, channel}
     for (int64_t ch = 0; ch < C_out; ++ch) {
         const int32_t e0 = row_ptr[ch], n = row_ptr[ch + 1] - e0;
         if (n < 1) return QLLM_ERR_MAP;
@@ -179,11 +181,22 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         for (int32_t e = e0; e < e0 + n; ++e) pub_slot[(size_t)(src[e] / G)] = 0; // the kernel stages this chunk's x
         if (kind == COMPACT) {
             ++n_spec;
+        } else if (n > WAVE) { // too long for one pass of a wavefront: listed apart and summed block by block
+            ++n_xl;
+            n_xle += n;
         } else {
-            if (n > WAVE) return QLLM_ERR_MAP; // a long row is summed inside one wavefront
-            n_long = place_long(n_long, n) + n;
+            long_rows.push_back({n, (int32_t)ch});
             ++n_rows_long;
         }
+    }
+    // The wavefront that owns 64 entries of the table repeats its addition as often as the longest row among them
+    // has entries, so rows of like length go together: longest first (channel order among equals).
+    std::stable_sort(long_rows.begin(), long_rows.end(), [](const auto &x, const auto &y) { return x.first > y.first; });
+    std::vector<int32_t> long_start((size_t)C_out, -1);
+    for (const auto &row : long_rows) {
+        n_long = place_long(n_long, row.first);
+        long_start[(size_t)row.second] = (int32_t)n_long;
+        n_long += row.first;
     }
     for (int64_t g = 0; g < n_groups; ++g) {
         const int32_t d = desc[(size_t)g] = plain_source(g);
@@ -201,33 +214,47 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
         n_segw += 1 + 3 * n_seg;
         ++n_comp;
     }
+    // Chunks that hold a source of a computed channel are staged.  If the lists would then not fit in LDS next
+    // to the row at the kernel's most demanding setting (8-bit codes, LayerNorm with a shift), all chunks are: a
+    // staged position then is the channel number, which lets the kernel fetch gamma and beta of a source by it
+    // while the lists stay in global memory.
     int64_t n_pub = 0;
+    for (int64_t c = 0; c < n_chunks; ++c) n_pub += pub_slot[(size_t)c] == 0;
+    {
+        const int64_t units = std::max(n_chunks, (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G);
+        const qllm_detail::PlanCounts p{n_comp, n_long, n_pub, n_chunks, n_spec, n_spec + n_rows_long + n_xl, n_segw};
+        if (qllm_detail::fused_lists_lds_bytes(p, 2, 3, units + 256) > qllm_detail::FUSED_MAX_LDS)
+            std::fill(pub_slot.begin(), pub_slot.end(), 0);
+    }
+    n_pub = 0;
     for (int64_t c = 0; c < n_chunks; ++c)
         if (pub_slot[(size_t)c] == 0) pub_slot[(size_t)c] = (int32_t)n_pub++;
-    const int64_t n_dest = n_spec + n_rows_long;
-    if (n_long > 0xffffff || G * n_pub + 4 > 0xffff || n_segw > 0x1ffff || n_comp > 0xffffff) return QLLM_ERR_MAP;
+    const int64_t n_dest = n_spec + n_rows_long + n_xl;
+    if (n_long > 0xffffff || G * n_pub + 4 > 0xffff || n_segw > 0x1ffff || n_comp > 0xffffff || n_xle > 0xffffff) return QLLM_ERR_MAP;
     *n_general = n_comp;
     const int64_t n_work = (C_out + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / G; // groups incl. zero padding
     auto round4 = [](int64_t v) { return (v + 3) / 4 * 4; };
     const int64_t off_work = HEAD, off_chunks = round4(off_work + n_work), off_spec = round4(off_chunks + n_chunks);
     const int64_t off_dest = round4(off_spec + 2 * n_spec), off_longs = round4(off_dest + n_dest);
     const int64_t off_segs = off_longs + 4 * n_long, off_recs = round4(off_segs + n_segw);
-    *plan_len = off_recs + 8 * n_comp;
+    const int64_t off_xlrows = off_recs + 8 * n_comp, off_xlent = off_xlrows + 4 * n_xl;
+    *plan_len = off_xlent + 2 * n_xle;
     if (!plan) return QLLM_OK;
 
     // ---- second pass: the tables
     std::fill(plan, plan + *plan_len, 0);
-    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 7, C_in, C_out, n_work, n_comp, n_chunks, n_long,
-                                          n_pub, n_spec, n_dest, n_segw, off_chunks, *plan_len, off_spec, off_longs};
+    const int64_t head[QLLM_PLAN_HEAD] = {0x514c4d50, 8, C_in, C_out, n_work, n_comp, n_chunks, n_long,
+                                          n_pub, n_spec, n_dest, n_segw, off_chunks, *plan_len, n_xl, n_xle};
     for (int64_t k = 0; k < HEAD; ++k) plan[k] = (int32_t)head[k];
     int32_t *work = plan + off_work, *chunks = plan + off_chunks, *spec = plan + off_spec, *dest = plan + off_dest;
     int32_t *longs = plan + off_longs, *segs = plan + off_segs, *recs = plan + off_recs;
+    int32_t *xlrows = plan + off_xlrows, *xlent = plan + off_xlent;
     for (int64_t e = 0; e < n_long; ++e) longs[4 * e + 1] = -1; // padding entries are {0, -1, 0.0f, 0}
     const uint32_t zero_at = (uint32_t)(G * n_pub); // the staged zero sits right after the published chunks
     auto staged = [&](int32_t channel) { return (uint32_t)(pub_slot[(size_t)(channel / G)] * G + channel % G); };
     for (int64_t c = 0; c < n_chunks; ++c)
         chunks[c] = (int32_t)(((uint32_t)pub_slot[(size_t)c] << 8) | pass[(size_t)c]); // no slot: 0xffffff
-    int64_t comp = 0, spec_at = 0, long_row = 0, long_at = 0, seg_at = 0;
+    int64_t comp = 0, spec_at = 0, long_row = 0, long_at = 0, seg_at = 0, xl_row = 0, xl_at = 0;
     for (int64_t g = 0; g < n_groups; ++g) {
         if (desc[(size_t)g] >= 0) continue;
         int32_t *hdr = segs + seg_at;
@@ -247,8 +274,19 @@ int32_t qllm_plan_map_host(const int32_t *row_ptr, const int32_t *src, const flo
                 spec[2 * spec_at] = (int32_t)(staged(src[e0]) | (second << 16));
                 std::memcpy(&spec[2 * spec_at + 1], &scale[e0], 4);
                 dest[spec_at++] = (int32_t)((comp << 3) | k);
+            } else if (n > WAVE) { // {first entry, entries, value slot, 0} and the entries {staged source, scale}
+                const int64_t id = n_spec + n_rows_long + xl_row;
+                dest[id] = (int32_t)((comp << 3) | k);
+                xlrows[4 * xl_row] = (int32_t)xl_at;
+                xlrows[4 * xl_row + 1] = n;
+                xlrows[4 * xl_row + 2] = (int32_t)id;
+                ++xl_row;
+                for (int32_t e = e0; e < e0 + n; ++e, ++xl_at) {
+                    xlent[2 * xl_at] = (int32_t)staged(src[e]);
+                    std::memcpy(&xlent[2 * xl_at + 1], &scale[e], 4);
+                }
             } else { // entries go to the table of long rows: {staged source, value slot or -1, scale, position}
-                long_at = place_long(long_at, n);
+                long_at = long_start[(size_t)ch];
                 const int64_t id = n_spec + long_row++;
                 dest[id] = (int32_t)((comp << 3) | k);
                 for (int32_t e = e0; e < e0 + n; ++e, ++long_at) {

@@ -61,15 +61,15 @@ def rel_err(got, ref):
     return np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), floor)
 
 
-def random_csr_map(rng, C_in, C_out, special_every):
+def random_csr_map(rng, C_in, C_out, special_every, longest=5):
     """Any CSR map, not only those the paper's reassembly makes: mostly shifted unscaled copies (so that
-    plain groups with every misalignment exist), every `special_every`-th row 1..5 entries with arbitrary
+    plain groups with every misalignment exist), every `special_every`-th row 1..longest entries with arbitrary
     sources (repeats allowed) and arbitrary scales; some inputs are never referenced."""
     row_ptr, src, scale = [0], [], []
     shift = 0
     for ch in range(C_out):
         if ch % special_every == special_every - 1:
-            n = int(rng.integers(1, 6))
+            n = int(rng.integers(1, longest + 1))
             src += rng.integers(0, C_in, n).tolist()
             kind = rng.integers(0, 3)
             if kind == 0:

@@ -1,6 +1,7 @@
 """The C-ABI library without a GPU: exported symbols, argument validation (every check happens
 before a launch), and the host helpers against the oracle."""
 import ctypes as C
+import types
 import json
 import os
 import re
@@ -155,17 +156,20 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
     """Reads a plan the way its layout is documented in include/qllm.h and rebuilds, for every output channel,
     the list of (source, scale) entries it stands for; that has to be the CSR map the plan was made from."""
     n_groups, n_chunks, n_work = (K + 7) // 8, (C + 7) // 8, (K + 255) // 256 * 32
-    magic, version, c_in, c_out, nw, n_comp, nc, n_long, n_pub, n_spec, n_dest, n_segw, off_chunks, plan_len, off_spec, \
-        off_longs = plan[:16].tolist()
-    assert (magic, version, c_in, c_out, nw, nc) == (0x514C4D50, 7, C, K, n_work, n_chunks)
+    magic, version, c_in, c_out, nw, n_comp, nc, n_long, n_pub, n_spec, n_dest, n_segw, off_chunks, plan_len, n_xl, \
+        n_xle = plan[:16].tolist()
+    assert (magic, version, c_in, c_out, nw, nc) == (0x514C4D50, 8, C, K, n_work, n_chunks)
     r4 = lambda v: (v + 3) // 4 * 4
     off_work = 16
-    assert off_chunks == r4(off_work + n_work) and off_spec == r4(off_chunks + n_chunks)
+    assert off_chunks == r4(off_work + n_work)
+    off_spec = r4(off_chunks + n_chunks)
     off_dest = r4(off_spec + 2 * n_spec)
-    assert off_longs == r4(off_dest + n_dest)
+    off_longs = r4(off_dest + n_dest)
     off_segs = off_longs + 4 * n_long
     off_recs = r4(off_segs + n_segw)
-    assert plan_len == plan.size == off_recs + 8 * n_comp
+    off_xlrows = off_recs + 8 * n_comp
+    off_xlent = off_xlrows + 4 * n_xl
+    assert plan_len == plan.size == off_xlent + 2 * n_xle
     work = plan[off_work:off_work + n_work].astype(np.int64) & 0xFFFFFFFF
     kind, grp, field = work >> 30, (work >> 17) & 0x1FFF, work & 0x1FFFF
     assert sorted(grp.tolist()) == list(range(n_work))          # every group exactly once
@@ -181,7 +185,9 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
     dest = plan[off_dest:off_dest + n_dest]
     longs = plan[off_longs:off_segs].reshape(-1, 4).copy()
     segs = plan[off_segs:off_segs + n_segw]
-    recs = plan[off_recs:].reshape(n_comp, 8)
+    recs = plan[off_recs:off_xlrows].reshape(n_comp, 8)
+    xlrows = plan[off_xlrows:off_xlent].reshape(n_xl, 4)
+    xlent = plan[off_xlent:].reshape(n_xle, 2)
     most = longs[:, 3] >> 8                                       # largest position among the 64 entries of a wavefront
     longs[:, 3] &= 0xFF
     for b0 in range(0, n_long, 64):
@@ -229,12 +235,21 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
             if longs[at - 1, 1] >= 0:
                 break
         slot = int(longs[at - 1, 1])
-        assert n_spec <= slot < n_dest
+        assert n_spec <= slot < n_dest - n_xl
         ch = 8 * comp_group[int(dest[slot]) >> 3] + (int(dest[slot]) & 7)
-        assert ch not in rebuilt and len(entries) >= 2
+        assert ch not in rebuilt and 2 <= len(entries) <= 64
         rebuilt[ch] = entries
         seen_rows += 1
-    assert seen_rows == n_dest - n_spec
+    assert seen_rows == n_dest - n_spec - n_xl
+    at = 0
+    for r in range(n_xl):                                          # rows of more than 64 entries, entries back to back
+        first, n, slot, pad = (int(v) for v in xlrows[r])
+        assert first == at and n > 64 and slot == n_dest - n_xl + r and pad == 0
+        ch = 8 * comp_group[int(dest[slot]) >> 3] + (int(dest[slot]) & 7)
+        assert ch not in rebuilt
+        rebuilt[ch] = [(chan_of_pos[int(xlent[e, 0])], as_f(xlent[e, 1])) for e in range(first, first + n)]
+        at += n
+    assert at == n_xle
     assert sorted(rebuilt) == list(range(K))
     expect_pass = np.zeros(n_chunks * 8, bool)
     for ch in range(K):
@@ -244,16 +259,71 @@ def check_plan_decodes_to_map(plan, row_ptr, src, scale, C, K):
         if e1 - e0 == 1 and scale[e0] == 1.0:
             expect_pass[src[e0]] = True
     assert np.array_equal(np.unpackbits(passes.astype(np.uint8), bitorder="little"), expect_pass.astype(np.uint8))
+    # staged: the chunks that hold a source of a computed or long channel, or all chunks
+    needed = np.zeros(n_chunks, bool)
+    for ch in range(K):
+        e0, e1 = row_ptr[ch], row_ptr[ch + 1]
+        if not (e1 - e0 == 1 and scale[e0] == 1.0):
+            needed[src[e0:e1] // 8] = True
+    assert np.array_equal(staged, needed) or staged.all()
 
 
 @pytest.mark.parametrize("C_in,C_out,special_every", [(2048, 2100, 37), (8200, 8000, 61), (1000, 1003, 5), (64, 9, 2)])
-def test_plan_of_an_arbitrary_map_decodes_to_it(C_in, C_out, special_every):
-    # repeated and unreferenced sources, rows of 1..5 entries with any scales, plain groups at every misalignment
+@pytest.mark.parametrize("longest", [5, 150])
+def test_plan_of_an_arbitrary_map_decodes_to_it(C_in, C_out, special_every, longest):
+    # repeated and unreferenced sources, rows of 1..longest entries with any scales, plain groups at every misalignment
     rng = np.random.default_rng(C_in + special_every)
-    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, special_every)
+    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, special_every, longest)
     plan, n_comp = b.qllm_plan_map_host(row_ptr, src, scale, C_in)
     assert plan[5] == n_comp
     check_plan_decodes_to_map(plan, row_ptr, src, scale, C_in, C_out)
+
+
+def host_map(row_ptr, src, scale, C_in, plan):
+    """A qllm_map whose pointers are host arrays: enough for the calls that only read sizes and the plan's header."""
+    keep = [np.ascontiguousarray(row_ptr, np.int32), np.ascontiguousarray(src, np.int32), np.ascontiguousarray(scale, np.float32)]
+    head = (C.c_int32 * b.PLAN_HEAD)()
+    plan_ptr = None
+    if plan is not None:
+        keep.append(np.ascontiguousarray(plan, np.int32))
+        head[:] = [int(v) for v in keep[3][:b.PLAN_HEAD]]
+        plan_ptr = keep[3].ctypes.data
+    m = b._Map(C_in, keep[0].size - 1, keep[1].size, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data, plan_ptr, head)
+    m.keep = keep
+    return types.SimpleNamespace(c=m)
+
+
+def test_fused_kernel_choice_follows_what_fits_on_chip():
+    rng = np.random.default_rng(5)
+    # a benchmark-like map: a few special rows; its lists fit in LDS
+    small = random_csr_map(rng, 4096, 4096, 97)
+    plan = b.qllm_plan_map_host(*small, 4096)[0]
+    m = host_map(*small, 4096, plan)
+    assert b.qllm_fused_kernel_choice(m, b.BF16, 2048, 4096, b.NORM_RMS, False, 4) == b.FUSED_LISTS_IN_LDS
+    assert b.qllm_fused_kernel_choice(m, b.F32, 1, 4096, b.NORM_LAYER, True, 8) == b.FUSED_LISTS_IN_LDS
+    # rows that are not 16-byte aligned, and a map without a plan: the kernel that walks the CSR rows
+    assert b.qllm_fused_kernel_choice(m, b.BF16, 2048, 4099, b.NORM_RMS, False, 4) == b.FUSED_WALKS_MAP
+    assert b.qllm_fused_kernel_choice(host_map(*small, 4096, None), b.BF16, 2048, 4096, b.NORM_RMS, False, 4) == b.FUSED_WALKS_MAP
+    # every other channel computed, on a long row: the lists no longer fit in LDS and are streamed
+    big = random_csr_map(rng, 16384, 16000, 2)
+    plan = b.qllm_plan_map_host(*big, 16384)[0]
+    assert plan[8] == plan[6]                                   # every chunk staged
+    m = host_map(*big, 16384, plan)
+    for dt in (b.BF16, b.F32):
+        for bits in (4, 6, 8):
+            assert b.qllm_fused_kernel_choice(m, dt, 64, 16384, b.NORM_LAYER, True, bits) == b.FUSED_LISTS_STREAMED
+    # ... unless the row itself does not fit next to its codes (fp32 input of 28 672 channels)
+    huge = random_csr_map(rng, 28672, 28672, 4)
+    plan = b.qllm_plan_map_host(*huge, 28672)[0]
+    m = host_map(*huge, 28672, plan)
+    assert b.qllm_fused_kernel_choice(m, b.BF16, 64, 28672, b.NORM_RMS, False, 4) == b.FUSED_LISTS_STREAMED
+    assert b.qllm_fused_kernel_choice(m, b.F32, 64, 28672, b.NORM_RMS, False, 4) == b.FUSED_WALKS_MAP
+    # arguments the kernel's entry point would reject
+    for bad in [dict(x_dtype=7), dict(norm=9), dict(bits=5), dict(N=-1), dict(ldx=100)]:
+        args = dict(x_dtype=b.BF16, N=64, ldx=28672, norm=b.NORM_RMS, has_beta=False, bits=4)
+        args.update(bad)
+        with pytest.raises(b.QllmError):
+            b.qllm_fused_kernel_choice(m, **args)
 
 
 @pytest.mark.parametrize("name,N,C,O", [("tiny", 64, 512, 96), ("llama7b_qkv", 48, 1000, 40),

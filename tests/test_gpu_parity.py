@@ -107,23 +107,25 @@ def many_to_one_case(oracle, counts, N, C, name="llama7b_qkv"):
     return c
 
 
-@pytest.mark.parametrize("counts,planned", [([63, 40, 30, 2, 2, 17, 63, 5], True), ([3] * 150, True), ([70, 2], False)])
+@pytest.mark.parametrize("counts", [[63, 40, 30, 2, 2, 17, 63, 5], [3] * 150, [70, 2], [64, 127, 128, 129, 400, 63] + [65] * 20])
 @pytest.mark.parametrize("C,bits", [(16392, 4), (8200, 6)])
-def test_fused_channels_merged_from_many(oracle, b, counts, planned, C, bits):
-    # a long row is summed lane by lane inside one wavefront; more than 64 entries: no plan, CSR walk
+def test_fused_channels_merged_from_many(oracle, b, counts, C, bits):
+    # a row of up to 64 entries is summed lane by lane inside one wavefront in one go, a longer one 64 entries at
+    # a time with the sum carried over; the order of the additions is the oracle's left-to-right order either way
     c = many_to_one_case(oracle, counts, N=9, C=C)
     r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
-    assert (r["plan"] is not None) == planned
+    assert r["plan"] is not None and r["plan"][14] == sum(n + 1 > 64 for n in counts)
     check_fused(oracle, c, run_fused(b, c, bits), bits)
 
 
-@pytest.mark.parametrize("C_in,C_out,special_every,bits", [(2048, 2100, 37, 4), (8200, 8000, 61, 6), (16392, 16500, 97, 8),
-                                                           (1000, 1003, 5, 4)])
+@pytest.mark.parametrize("C_in,C_out,special_every,bits,longest", [
+    (2048, 2100, 37, 4, 5), (8200, 8000, 61, 6, 5), (16392, 16500, 97, 8, 5), (1000, 1003, 5, 4, 5),
+    (8200, 8000, 61, 4, 300), (2048, 2100, 7, 8, 130)])
 @pytest.mark.parametrize("use_plan", [True, False])
-def test_fused_arbitrary_csr_map(oracle, b, C_in, C_out, special_every, bits, use_plan):
+def test_fused_arbitrary_csr_map(oracle, b, C_in, C_out, special_every, bits, longest, use_plan):
     import torch
     rng = np.random.default_rng(C_in + bits)
-    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, special_every)
+    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, special_every, longest)
     w = wl.WORKLOADS["llama7b_qkv"]
     x, _, _ = wl.draw_activations(w, 5, C_in, 99)
     gamma, _ = wl.draw_norm_params(w, C_in, 99)
@@ -138,6 +140,56 @@ def test_fused_arbitrary_csr_map(oracle, b, C_in, C_out, special_every, bits, us
     assert np.array_equal(out.codes.cpu().numpy(), oracle.pack_codes(codes, bits, out.codes.shape[1]))
     assert np.array_equal(out.scale.cpu().numpy().view(np.uint32), alpha.view(np.uint32))
     assert np.array_equal(out.zero.cpu().numpy(), beta) and np.array_equal(out.rowsum.cpu().numpy(), rowsum)
+
+
+@pytest.mark.parametrize("norm,shift", [("rms", False), ("layer", True), ("layer", False), ("none", False)])
+@pytest.mark.parametrize("dtype,bits", [("bf16", 4), ("f32", 4), ("bf16", 6), ("f32", 8)])
+@pytest.mark.parametrize("C_in,C_out,N", [(16384, 16000, 5), (16392, 16500, 3)])
+def test_fused_big_map_with_streamed_lists(oracle, b, norm, shift, dtype, bits, C_in, C_out, N):
+    # every other output channel computed or long on a 16K-channel row: the plan's lists no longer fit in LDS
+    # and are read from global memory row by row; every chunk of the row is staged, in the input's own type
+    import torch
+    rng = np.random.default_rng(C_out + bits)
+    row_ptr, src, scale = random_csr_map(rng, C_in, C_out, 2)
+    w = wl.WORKLOADS["llama7b_qkv"]
+    x, _, _ = wl.draw_activations(w, N, C_in, 7)
+    gamma, _ = wl.draw_norm_params(w, C_in, 7)
+    beta = rng.standard_normal(C_in).astype(np.float32) if shift else None
+    if dtype == "f32":
+        x = wl.bf16_bits_to_f32(x) * np.float32(1.0009765625)    # no longer bf16 values
+    kind = NORM_ID[norm]
+    xhat = oracle.apply_map(oracle.norm(x, kind, gamma if kind else None, beta, w.eps), row_ptr, src, scale)
+    codes, alpha, zero, rowsum = oracle.quantize_rows(xhat, bits)
+    dm = b.DeviceMap(row_ptr, src, scale, C_in, b.qllm_plan_map_host(row_ptr, src, scale, C_in)[0])
+    xt = to_torch_x(x)
+    assert b.qllm_fused_kernel_choice(dm, xt.dtype, N, C_in, kind, shift, bits) == b.FUSED_LISTS_STREAMED
+    out = b.DeviceQAct(N, C_out, bits)
+    out.codes.fill_(0xAB)
+    g = torch.from_numpy(gamma).cuda() if kind else None
+    b.qllm_norm_reassemble_quant(xt, kind, g, None if beta is None else torch.from_numpy(beta).cuda(), w.eps, dm, bits, out)
+    torch.cuda.synchronize()
+    got = out.codes.cpu().numpy()
+    bad = np.nonzero(got != oracle.pack_codes(codes, bits, out.codes.shape[1]))
+    assert bad[0].size == 0, f"{bad[0].size} bytes differ, first at row {bad[0][:3]} byte {bad[1][:3]}"
+    assert np.array_equal(out.scale.cpu().numpy().view(np.uint32), alpha.view(np.uint32))
+    assert np.array_equal(out.zero.cpu().numpy(), zero) and np.array_equal(out.rowsum.cpu().numpy(), rowsum)
+
+
+@pytest.mark.parametrize("name,N,expand,more,choice", [
+    ("llama7b_qkv", 40, 0.05, 0.0, 1), ("llama7b_qkv", 40, 0.1, 0.0, 1), ("llama7b_qkv", 40, 0.01, 0.25, 1),
+    ("llama7b_qkv", 300, 0.1, 0.0, 1),        # more rows than CUs: two chunks per lane, more composite groups than lanes
+    ("llama13b_upgate", 24, 0.1, 0.0, 1), ("llama13b_upgate", 24, 0.05, 0.25, 1),
+    ("llama70b_down", 16, 0.05, 0.0, 2), ("llama70b_down", 16, 0.1, 0.0, 2), ("llama70b_down", 16, 0.01, 0.25, 2)])
+def test_fused_at_the_expansion_ratios_of_the_ablation(oracle, b, name, N, expand, more, choice):
+    # Sec. 5.2 varies the expansion ratio up to 0.1, and Sec. 1 names assembling more channels than were
+    # disassembled (C^ < C): such maps have thousands of computed channels, and none may fall back to the kernel
+    # that walks the CSR rows
+    w = wl.WORKLOADS[name]
+    c = make_case(oracle, w, N=N, O=8, real_weights=False, theta_rule=("expand", expand), assemble_more=more)
+    assert c.K == w.C - int(round(more * w.C))
+    dm = device_map(b, c)
+    assert b.qllm_fused_kernel_choice(dm, b.BF16 if w.in_dtype == "bf16" else b.F32, N, w.C, c.norm, c.beta is not None, 4) == choice
+    check_fused(oracle, c, run_fused(b, c, 4), 4)
 
 
 @pytest.mark.parametrize("norm", ["none", "layer", "rms"])
