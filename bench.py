@@ -143,6 +143,10 @@ def main():
     ap.add_argument("--assemble-more", type=float, default=0.0,
                     help="merge this fraction of C more channel pairs than disassembly added (C^ < C: the paper's "
                          "speed-up variant); 0 keeps C^ = C as in the paper's experiments")
+    ap.add_argument("--expand", type=float, default=None,
+                    help="expansion ratio that fixes theta (Sec. 5.2 varies it up to 0.1); default: the workload's own")
+    ap.add_argument("--allow-map-walk", action="store_true",
+                    help="do not stop when the fused kernel would fall back to walking the map's CSR rows")
     ap.add_argument("--stage", default="layer", choices=["layer", "match"],
                     help="layer: the hot path (the default, the line the contract asks for); match: the offline "
                          "channel matching of Eq. (5) / Appendix A at the workload's channel count")
@@ -177,9 +181,14 @@ def main():
     beta = None if beta_h is None else torch.from_numpy(beta_h).to(dev)
 
     # ---- offline: calibration -> map; weight reassembly + quantization (library host helpers)
-    cal = calibrate.calibrate(x0, norm, gamma, beta, w.eps, w.theta_rule, assemble_more=args.assemble_more)
+    theta_rule = w.theta_rule if args.expand is None else ("expand", args.expand)
+    cal = calibrate.calibrate(x0, norm, gamma, beta, w.eps, theta_rule, assemble_more=args.assemble_more)
     dmap = b.DeviceMap(cal["row_ptr"], cal["src"], cal["scale"], w.C, cal["plan"])
     K = dmap.C_out
+    form = b.qllm_fused_kernel_choice(dmap, x0.dtype, w.N, w.C, norm, beta is not None, w.a_bits)
+    if form == b.FUSED_WALKS_MAP and not args.allow_map_walk:
+        sys.exit("bench.py: this map does not fit the planned fused kernel; the timed kernel would be the one that "
+                 "walks the CSR rows (--allow-map-walk to time that)")
     W = wl.draw_weight(w)
     q = b.qllm_quantize_weight_host(W, cal["row_ptr"], cal["src"], w.w_bits)
     del W
@@ -317,7 +326,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "C": w.C, "C_hat": K, "O": w.O, "a_bits": w.a_bits,
                    "w_bits": w.w_bits, "in_dtype": w.in_dtype, "out_dtype": "bf16", "norm": w.norm,
-                   "theta": cal["theta"], "extra_channels": int(cal["nnz"] - w.C),
+                   "theta": cal["theta"], "theta_rule": list(theta_rule), "assemble_more": args.assemble_more,
+                   "fused_kernel_form": {b.FUSED_WALKS_MAP: "walks the map", b.FUSED_LISTS_IN_LDS: "planned, lists in LDS",
+                                         b.FUSED_LISTS_STREAMED: "planned, lists streamed"}[form],
+                   "extra_channels": int(cal["nnz"] - w.C),
                    "merged_pairs": int(cal["src_idx"].size), "T_max": int(cal["num_split"].max()),
                    "rotating_buffers": N_ROTATE, "launch": "hip graph replay" if args.graph else "eager",
                    "warmup_done": {"steps": warm_steps, "gpu_ms": warm_ms}},
@@ -340,7 +352,7 @@ def main():
         from oracle import calibrate as oracle_cal
         ns = min(args.cpu_sample_tokens, w.N)
         t1 = time.perf_counter()
-        ocal = oracle_cal.calibrate(oracle.norm(x_host, norm, gamma_h, beta_h, w.eps), w.theta_rule,
+        ocal = oracle_cal.calibrate(oracle.norm(x_host, norm, gamma_h, beta_h, w.eps), theta_rule,
                                     assemble_more=args.assemble_more)
         W = wl.draw_weight(w)
         wq = oracle.quantize_weight(oracle.reassemble_weight(W, ocal["T"], ocal["src_idx"], ocal["dst_idx"]), w.w_bits)

@@ -264,6 +264,15 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
                             const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
                             float *scale, int64_t *C_out, int64_t *nnz, int32_t *num_split_out);
 
+/* The comparison of Sec. 4.1.2: the same disassembly (Eq. 3), but the r listed members of set A (src_idx, as for
+ * qllm_build_map_host) are DROPPED instead of merged into a member of set B, so every row of the map has one
+ * entry and nnz = sum(T) - r = C_out.  Arguments, the sizing call (row_ptr == NULL) and errors as for
+ * qllm_build_map_host.  The result is an ordinary map: the kernels, qllm_plan_map_host and
+ * qllm_quantize_weight_host take it like any other. */
+int32_t qllm_build_pruned_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx, int64_t r,
+                                   int32_t *row_ptr, int32_t *src, float *scale, int64_t *C_out, int64_t *nnz,
+                                   int32_t *num_split);
+
 /* Indexes a CSR map for the fused kernel (see qllm_map.plan).  Call once with plan == NULL to get
  * *plan_len (int32 words) and *n_general, then with plan pointing at that many words.  The plan
  * depends only on the map; upload it next to the CSR arrays and keep its first QLLM_PLAN_HEAD words

@@ -11,6 +11,8 @@ Sec. 4.1.2, Appendix A, Algorithm 1) needed to manufacture a reassembly map for 
           r = sum(T_c - 1) shortest edges are merged.  Sub-channels of disassembled channels take
           no part (Sec. 4.1.2).
 
+`pruned_linear` and `layer_output_errors` serve the comparison of Sec. 4.1.2 (channels dropped instead of merged).
+
 Two edge lengths are provided: the plain L2 distance between activation columns over the first
 `n_match_tokens` tokens (the benchmark's policy for synthetic data: `nearest_by_l2`, `nearest_pairs`), and
 the paper's Eq. (5), which also involves the weights (`pair_distance`, `nearest_by_eq5`, `match_pairs_eq5`).
@@ -191,3 +193,46 @@ def grid_search_theta(x, norm_kind, gamma, beta, eps, W, a_bits, w_bits, P, n_ma
     thetas = theta_grid(api.channel_absmax(y), P)
     losses = [reassembly_loss(x, norm_kind, gamma, beta, eps, W, t, a_bits, w_bits, n_match_tokens)[0] for t in thetas]
     return thetas[int(np.argmin(losses))], thetas, losses
+
+
+def build_pruned_map(T, src_idx):
+    """The comparison of Sec. 4.1.2 as a map: disassembly (Eq. 3) as in build_map, but the members of set A
+    listed in src_idx (A = even positions of the disassembled axis) are dropped instead of merged into a
+    member of set B.  Returns (row_ptr, src, scale): one entry per kept position, scale 1/T."""
+    T = np.asarray(T, np.int64)
+    chan_of = np.repeat(np.arange(T.size), T)
+    keep = np.ones(chan_of.size, bool)
+    keep[2 * np.asarray(src_idx, np.int64)] = False
+    src = chan_of[keep].astype(np.int32)
+    scale = (np.float64(1.0) / T[src]).astype(np.float32)
+    return np.arange(src.size + 1, dtype=np.int32), src, scale
+
+
+def map_linear(x, norm_kind, gamma, beta, eps, row_ptr, src, scale, W, a_bits, w_bits):
+    """norm -> the map -> per-token quantization (Eq. 2) -> integer GEMM against per-output-channel quantized
+    weights -> dequantising epilogue (Eq. 1), for ANY map: a weight row of an output channel is the sum of the
+    weight rows of its sources (for one source, that row).  Returns the layer's output [N, O] float32."""
+    xhat = api.apply_map(api.norm(x, norm_kind, gamma, beta, eps), row_ptr, src, scale)
+    codes, alpha, zero, rowsum = api.quantize_rows(xhat, a_bits)
+    W = np.asarray(W, np.float32)
+    What = np.empty((row_ptr.size - 1, W.shape[1]), np.float32)
+    for ch in range(row_ptr.size - 1):
+        acc = W[src[row_ptr[ch]]].copy()
+        for e in range(row_ptr[ch] + 1, row_ptr[ch + 1]):
+            acc = acc + W[src[e]]                       # float32, entry by entry (Eq. 4: the rows add up)
+        What[ch] = acc
+    wcodes, aw, bw, cs = api.quantize_weight(What, w_bits)
+    return api.epilogue(api.int_gemm(codes, wcodes), codes.shape[1], alpha, zero, rowsum, aw, bw, cs)
+
+
+def layer_output_errors(x, norm_kind, gamma, beta, eps, W, T, src_idx, dst_idx, a_bits, w_bits):
+    """Squared error of the layer's output against the full-precision norm -> linear, for the map that merges the
+    listed pairs (Eq. 4) and for the map that drops the same members of set A instead (Sec. 4.1.2's comparison).
+    Returns dict(assembly=..., pruning=...)."""
+    y = api.norm(x, norm_kind, gamma, beta, eps)
+    ref = y.astype(np.float64) @ np.asarray(W, np.float64)
+    out = {}
+    for name, m in (("assembly", api.build_map(T, src_idx, dst_idx)), ("pruning", build_pruned_map(T, src_idx))):
+        err = map_linear(x, norm_kind, gamma, beta, eps, *m, W, a_bits, w_bits).astype(np.float64) - ref
+        out[name] = float((err * err).sum())
+    return out

@@ -61,6 +61,7 @@ _sigs = {
     "qllm_last_hip_error": (C.c_char_p, []),
     "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64),
                                    _vp]),
+    "qllm_build_pruned_map_host": (_i32, [_vp, _i64, _f, _vp, _i64, _vp, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64), _vp]),
     "qllm_plan_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, C.POINTER(_i64), C.POINTER(_i64)]),
     "qllm_check_map_host": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64]),
     "qllm_quantize_weight_host": (_i32, [_vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp]),
@@ -156,6 +157,26 @@ def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx, with_plan=True):
                 raise
             # a channel merged from more than 64: no plan, the fused kernel walks the CSR instead
             out["plan"] = None
+    return out
+
+
+def qllm_build_pruned_map_host(chan_absmax, theta, src_idx, with_plan=True):
+    """As qllm_build_map_host, with the members of set A listed in src_idx dropped instead of merged (Sec. 4.1.2)."""
+    m = _np(chan_absmax, np.float32)
+    si = _np(src_idx, np.int32)
+    Cc, r = m.size, si.size
+    c_out, nnz = _i64(0), _i64(0)
+    T = np.empty(Cc, np.int32)
+    _chk(_lib.qllm_build_pruned_map_host(_hp(m), Cc, theta, _hp(si), r, None, None, None, C.byref(c_out), C.byref(nnz),
+                                         _hp(T)), "qllm_build_pruned_map_host(size)")
+    row_ptr = np.empty(c_out.value + 1, np.int32)
+    src = np.empty(nnz.value, np.int32)
+    scale = np.empty(nnz.value, np.float32)
+    _chk(_lib.qllm_build_pruned_map_host(_hp(m), Cc, theta, _hp(si), r, _hp(row_ptr), _hp(src), _hp(scale),
+                                         C.byref(c_out), C.byref(nnz), _hp(T)), "qllm_build_pruned_map_host")
+    out = dict(row_ptr=row_ptr, src=src, scale=scale, num_split=T, C_in=Cc, C_out=c_out.value, nnz=nnz.value)
+    if with_plan:
+        out["plan"] = qllm_plan_map_host(row_ptr, src, scale, Cc)[0]
     return out
 
 

@@ -454,12 +454,18 @@ int32_t qllm_check_map_host(const int32_t *row_ptr, const int32_t *src, const fl
     return QLLM_OK;
 }
 
-int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx,
-                            const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
-                            float *scale, int64_t *C_out, int64_t *nnz, int32_t *num_split_out)
+} // extern "C"
+
+namespace {
+
+// Disassembly (Eq. 3) followed by assembly (Eq. 4) as a CSR map; with `prune` the listed A-members are dropped
+// instead of merged into their B-members (the comparison of Sec. 4.1.2) and dst_idx is not read.
+int32_t build_map(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx, const int32_t *dst_idx,
+                  int64_t r, bool prune, int32_t *row_ptr, int32_t *src, float *scale, int64_t *C_out, int64_t *nnz,
+                  int32_t *num_split_out)
 {
     if (!chan_absmax || !C_out || !nnz) return QLLM_ERR_NULL;
-    if (r > 0 && (!src_idx || !dst_idx)) return QLLM_ERR_NULL;
+    if (r > 0 && (!src_idx || (!prune && !dst_idx))) return QLLM_ERR_NULL;
     if (C <= 0 || r < 0 || !(theta > 0.0f)) return QLLM_ERR_SHAPE;
 
     // T = ceil(max|x| / theta), never below 1 (Sec. 4.1.1)
@@ -473,7 +479,7 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
     }
     if (total > std::numeric_limits<int32_t>::max() || r > total) return QLLM_ERR_SHAPE;
     *C_out = total - r;
-    *nnz = total;
+    *nnz = prune ? total - r : total;
     if (num_split_out) std::copy(T.begin(), T.end(), num_split_out);
     if (!row_ptr) return QLLM_OK; // sizing call
     if (!src || !scale) return QLLM_ERR_NULL;
@@ -487,29 +493,35 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
     }
     const int64_t n_a = (total + 1) / 2, n_b = total / 2;
     for (int64_t k = 0; k < r; ++k) {
-        if (src_idx[k] < 0 || src_idx[k] >= n_a || dst_idx[k] < 0 || dst_idx[k] >= n_b) return QLLM_ERR_MAP;
+        if (src_idx[k] < 0 || src_idx[k] >= n_a) return QLLM_ERR_MAP;
         Position &a = pos[2 * (size_t)src_idx[k]];
+        if (a.target != -1) return QLLM_ERR_MAP; // an A-member can be merged (dropped) once
+        if (a.splits != 1) return QLLM_ERR_MAP;  // sub-channels stay out of assembly
+        if (prune) {
+            a.target = -2; // dropped
+            continue;
+        }
+        if (dst_idx[k] < 0 || dst_idx[k] >= n_b) return QLLM_ERR_MAP;
         Position &b = pos[2 * (size_t)dst_idx[k] + 1];
-        if (a.target != -1) return QLLM_ERR_MAP;                 // an A-member can be merged once
-        if (a.splits != 1 || b.splits != 1) return QLLM_ERR_MAP; // sub-channels stay out of assembly
+        if (b.splits != 1) return QLLM_ERR_MAP;
         a.target = 2 * dst_idx[k] + 1;
         b.members += 1;
     }
     // sources of every destination, ascending: bucket the A-positions by target
     std::vector<int32_t> first((size_t)total + 1, 0);
     for (int64_t p = 0; p < total; p += 2)
-        if (pos[p].target != -1) first[(size_t)pos[p].target + 1] += 1;
+        if (pos[p].target >= 0) first[(size_t)pos[p].target + 1] += 1;
     for (int64_t p = 0; p < total; ++p) first[p + 1] += first[p];
     std::vector<int32_t> merged_src((size_t)std::max<int64_t>(r, 1));
     {
         std::vector<int32_t> fill(first.begin(), first.end() - 1);
         for (int64_t p = 0; p < total; p += 2)
-            if (pos[p].target != -1) merged_src[fill[pos[p].target]++] = (int32_t)p;
+            if (pos[p].target >= 0) merged_src[fill[pos[p].target]++] = (int32_t)p;
     }
     int64_t ch = 0, e = 0;
     for (int64_t p = 0; p < total; ++p) {
         const Position &q = pos[p];
-        if (q.target != -1) continue; // merged away
+        if (q.target != -1) continue; // merged away, or dropped
         row_ptr[ch++] = (int32_t)e;
         if (q.members == 1) {
             src[e] = q.channel;
@@ -527,6 +539,24 @@ int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, co
     row_ptr[ch] = (int32_t)e;
     if (ch != *C_out || e != *nnz) return QLLM_ERR_MAP;
     return QLLM_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int32_t qllm_build_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx,
+                            const int32_t *dst_idx, int64_t r, int32_t *row_ptr, int32_t *src,
+                            float *scale, int64_t *C_out, int64_t *nnz, int32_t *num_split_out)
+{
+    return build_map(chan_absmax, C, theta, src_idx, dst_idx, r, false, row_ptr, src, scale, C_out, nnz, num_split_out);
+}
+
+int32_t qllm_build_pruned_map_host(const float *chan_absmax, int64_t C, float theta, const int32_t *src_idx, int64_t r,
+                                   int32_t *row_ptr, int32_t *src, float *scale, int64_t *C_out, int64_t *nnz,
+                                   int32_t *num_split_out)
+{
+    return build_map(chan_absmax, C, theta, src_idx, nullptr, r, true, row_ptr, src, scale, C_out, nnz, num_split_out);
 }
 
 int32_t qllm_pack_codes_host(const uint8_t *codes, int64_t R, int64_t K, int32_t bits, uint8_t *packed)

@@ -819,3 +819,31 @@ def test_assemble_more_than_disassembled(oracle, b, more):
         full = oracle.norm(c.x, c.norm, c.gamma, c.beta, c.eps).astype(np.float64) @ c.W.astype(np.float64)
         errs.append(float(((exp["y"] - full) ** 2).mean()))
     assert errs[1] > errs[0]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("bits,more", [(4, 0.0), (4, 0.25), (8, 0.25)])
+def test_assembly_against_pruning_matches_the_oracle(oracle, b, bits, more):
+    """The comparison of Sec. 4.1.2 on one synthetic layer: the members of set A that assembly merges are
+    dropped instead, both maps run through the library's hot path, and the squared output errors are the
+    oracle's for the same two maps."""
+    import torch
+    from oracle import calibrate
+    from paper_2310_08041_amd import calibrate as dev_cal
+    w = wl.WORKLOADS["llama7b_qkv"]
+    C, O, N = 1024, 256, 128
+    x, _, _ = wl.draw_activations(w, N, C, 33)
+    gamma, _ = wl.draw_norm_params(w, C, 33)
+    W = wl.draw_weight(w, C, O, 33)
+    got = dev_cal.assembly_against_pruning(to_torch_x(x), NORM_ID[w.norm], torch.from_numpy(gamma).cuda(), None, w.eps,
+                                           torch.from_numpy(W).cuda(), bits, bits, ("expand", 0.02), assemble_more=more,
+                                           n_match=N)
+    cal = calibrate.calibrate(oracle.norm(x, NORM_ID[w.norm], gamma, None, w.eps), ("expand", 0.02), assemble_more=more,
+                              n_match_tokens=N)
+    assert np.array_equal(got["map"]["src_idx"], cal["src_idx"]) and np.array_equal(got["map"]["dst_idx"], cal["dst_idx"])
+    want = calibrate.layer_output_errors(x, NORM_ID[w.norm], gamma, None, w.eps, W, cal["T"], cal["src_idx"], cal["dst_idx"],
+                                         bits, bits)
+    assert np.isclose(got["assembly"], want["assembly"], rtol=1e-5, atol=0)
+    assert np.isclose(got["pruning"], want["pruning"], rtol=1e-5, atol=0)
+    if more:
+        assert got["C_out"] < C
