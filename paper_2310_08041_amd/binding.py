@@ -317,8 +317,63 @@ class DeviceQAct:
         self.c = _QAct(_dp(self.codes), _dp(self.scale), _dp(self.zero), _dp(self.rowsum))
 
 
-def qllm_norm_reassemble_quant(x, norm, gamma, beta, eps, dmap, bits, out, stream=None):
+def _need(cond, what):
+    """The C ABI cannot see how large a device buffer is: whatever it would trust is checked here first."""
+    if not cond:
+        raise ValueError("libqllm binding: " + what)
+
+
+def _check_tensor(t, name, dtypes=None, shape=None, numel=None, optional=False):
+    """A device tensor whose rows are dense (stride 1 along the last axis)."""
+    if t is None:
+        _need(optional, f"{name} is required")
+        return
+    torch = _torch()
+    _need(isinstance(t, torch.Tensor), f"{name} must be a torch tensor")
+    if dtypes is not None:
+        _need(t.dtype in dtypes, f"{name} has dtype {t.dtype}, expected one of {[str(d) for d in dtypes]}")
+    if shape is not None:
+        _need(tuple(t.shape) == tuple(shape), f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if numel is not None:
+        _need(t.numel() == numel and t.is_contiguous(), f"{name} must hold {numel} contiguous elements, has {t.numel()}")
+    _need(t.dim() == 0 or t.numel() == 0 or t.stride(-1) == 1, f"{name} must have stride 1 along its last axis")
+
+
+def _check_on_device(**tensors):
+    """Last of a wrapper's checks, so that shapes and dtypes can be tested without a GPU."""
+    for name, t in tensors.items():
+        _need(t is None or t.is_cuda, f"{name} must be a device (cuda) tensor")
+
+
+def _check_activation_args(x, norm, gamma, beta, dmap):
+    torch = _torch()
+    _need(hasattr(x, "dim") and x.dim() == 2, "x must be a 2-d tensor [tokens, channels]")
     N, Cc = x.shape
+    _need(int(norm) in (NORM_NONE, NORM_LAYER, NORM_RMS), f"unknown norm kind {norm}")
+    if dmap is not None:
+        _need(dmap.C_in == Cc, f"the map takes {dmap.C_in} channels, x has {Cc}")
+    if int(norm) != NORM_NONE:
+        _check_tensor(gamma, "gamma", (torch.float32,), numel=Cc)
+    _check_tensor(beta, "beta", (torch.float32,), numel=Cc, optional=True)
+    _check_tensor(x, "x", (torch.float32, torch.bfloat16))
+    return N, Cc
+
+
+def _check_qact(out, N, K, bits, name="out"):
+    _need(out.N >= N, f"{name} holds {out.N} tokens, {N} needed")
+    _need(out.K == K, f"{name} was made for {out.K} channels, the map makes {K}")
+    _need(out.bits == int(bits), f"{name} was made for {out.bits}-bit codes, {bits} asked for")
+
+
+def _check_output(y, N, O, name="y"):
+    torch = _torch()
+    _check_tensor(y, name, (torch.float32, torch.bfloat16), shape=(N, O))
+
+
+def qllm_norm_reassemble_quant(x, norm, gamma, beta, eps, dmap, bits, out, stream=None):
+    N, Cc = _check_activation_args(x, norm, gamma, beta, dmap)
+    _check_qact(out, N, dmap.C_out, bits)
+    _check_on_device(x=x, gamma=gamma, beta=beta)
     _chk(_lib.qllm_norm_reassemble_quant(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
                                          float(eps), C.byref(dmap.c), int(bits), C.byref(out.c), _stream(stream)),
          "qllm_norm_reassemble_quant")
@@ -340,6 +395,12 @@ def qllm_fused_kernel_choice(dmap, x_dtype, N, ldx, norm, has_beta, bits):
 
 
 def qllm_int_gemm(a, weight, y, acc_dump=None, workspace=None, stream=None):
+    torch = _torch()
+    _need(a.K == weight.K, f"activations have {a.K} channels, weights {weight.K}")
+    _check_output(y, a.N, weight.O)
+    _check_tensor(acc_dump, "acc_dump", (torch.int32,), numel=a.N * weight.O, optional=True)
+    _check_tensor(workspace, "workspace", (torch.uint8,), optional=True)
+    _check_on_device(y=y, acc_dump=acc_dump, workspace=workspace)
     _chk(_lib.qllm_int_gemm(C.byref(a.c), a.bits, a.N, C.byref(weight.c), _dp(y), _x_dtype(y), y.stride(0),
                             _dp(acc_dump), _dp(workspace), 0 if workspace is None else workspace.numel(),
                             _stream(stream)), "qllm_int_gemm")
@@ -347,7 +408,11 @@ def qllm_int_gemm(a, weight, y, acc_dump=None, workspace=None, stream=None):
 
 
 def qllm_reassembled_linear(x, norm, gamma, beta, eps, dmap, a_bits, weight, y, workspace, stream=None):
-    N, Cc = x.shape
+    N, Cc = _check_activation_args(x, norm, gamma, beta, dmap)
+    _need(dmap.C_out == weight.K, f"the map makes {dmap.C_out} channels, the weights take {weight.K}")
+    _check_output(y, N, weight.O)
+    _check_tensor(workspace, "workspace", (_torch().uint8,))
+    _check_on_device(y=y, workspace=workspace, x=x, gamma=gamma, beta=beta)
     _chk(_lib.qllm_reassembled_linear(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
                                       float(eps), C.byref(dmap.c), int(a_bits), C.byref(weight.c), _dp(y),
                                       _x_dtype(y), y.stride(0), _dp(workspace), workspace.numel(), _stream(stream)),
@@ -360,7 +425,10 @@ STATIC_WORKSPACE_BYTES = 32 << 20
 
 def qllm_reassembled_linear_static(x, norm, gamma, beta, eps, dmap, a_bits, weight, y, stream=None):
     """The layer with the library's built-in workspace: allocates nothing."""
-    N, Cc = x.shape
+    N, Cc = _check_activation_args(x, norm, gamma, beta, dmap)
+    _need(dmap.C_out == weight.K, f"the map makes {dmap.C_out} channels, the weights take {weight.K}")
+    _check_output(y, N, weight.O)
+    _check_on_device(y=y, x=x, gamma=gamma, beta=beta)
     _chk(_lib.qllm_reassembled_linear_static(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
                                              float(eps), C.byref(dmap.c), int(a_bits), C.byref(weight.c), _dp(y),
                                              _x_dtype(y), y.stride(0), _stream(stream)), "qllm_reassembled_linear_static")
@@ -368,7 +436,14 @@ def qllm_reassembled_linear_static(x, norm, gamma, beta, eps, dmap, a_bits, weig
 
 
 def qllm_norm_channel_absmax(x, norm, gamma, beta, eps, absmax, y_dump=None, stream=None):
-    N, Cc = x.shape
+    torch = _torch()
+    N, Cc = _check_activation_args(x, norm, gamma, beta, None)
+    _check_tensor(absmax, "absmax", (torch.float32,), numel=Cc)
+    if y_dump is not None:
+        _need(y_dump.dim() == 2 and y_dump.shape[1] == Cc and y_dump.shape[0] <= N and y_dump.is_contiguous(),
+              f"y_dump must be a contiguous [at most {N}, {Cc}] tensor, is {tuple(y_dump.shape)}")
+        _check_tensor(y_dump, "y_dump", (torch.float32,))
+    _check_on_device(absmax=absmax, y_dump=y_dump, x=x, gamma=gamma, beta=beta)
     n_dump = 0 if y_dump is None else y_dump.shape[0]
     _chk(_lib.qllm_norm_channel_absmax(_dp(x), _x_dtype(x), N, Cc, x.stride(0), int(norm), _dp(gamma), _dp(beta),
                                        float(eps), _dp(absmax), _dp(y_dump), n_dump, _stream(stream)),
@@ -383,7 +458,19 @@ def qllm_match_workspace_bytes(nA, nB):
 def qllm_match_nearest(y, W, chan_a, chan_b, best_j, best_d, workspace, stream=None):
     """y [n, C] fp32, W [C, O] fp32 or None (plain L2 on the activations), chan_a / chan_b int32, best_j [nA] int32,
     best_d [nA] float64: device tensors."""
+    torch = _torch()
+    _need(hasattr(y, "dim") and y.dim() == 2, "y must be a 2-d tensor [tokens, channels]")
     n, Cc = y.shape
+    if W is not None:
+        _need(W.dim() == 2 and W.shape[0] == Cc, f"W must have one row per channel of y ({Cc}), has shape {tuple(W.shape)}")
+    _check_tensor(W, "W", (torch.float32,), optional=True)
+    _check_tensor(y, "y", (torch.float32,))
+    _check_tensor(chan_a, "chan_a", (torch.int32,), numel=chan_a.numel())
+    _check_tensor(chan_b, "chan_b", (torch.int32,), numel=chan_b.numel())
+    _check_tensor(best_j, "best_j", (torch.int32,), numel=chan_a.numel())
+    _check_tensor(best_d, "best_d", (torch.float64,), numel=chan_a.numel())
+    _check_tensor(workspace, "workspace", (torch.uint8,), optional=True)
+    _check_on_device(y=y, W=W, chan_a=chan_a, chan_b=chan_b, best_j=best_j, best_d=best_d, workspace=workspace)
     O, ldw = (0, 0) if W is None else (W.shape[1], W.stride(0))
     _chk(_lib.qllm_match_nearest(_dp(y), n, y.stride(0), _dp(W), Cc, O, ldw, _dp(chan_a),
                                  chan_a.numel(), _dp(chan_b), chan_b.numel(), _dp(best_j), _dp(best_d),

@@ -894,16 +894,18 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
     }
 }
 
-// Largest L such that |beta_x| < L and |beta_w| < L keep the epilogue inside narrow integers:
-// row and column sums below 2^23, K*beta_x below 2^23, and each of the three products below 2^29,
-// so that their sum with the accumulator stays below 2^31.
+// Largest L such that |beta_x| < L and |beta_w| < L keep the epilogue inside narrow integers: row and column
+// sums and K * beta_x below 2^23 (24-bit multiplies), and the accumulator together with the three correction
+// terms -- in whatever order they are added -- below 2^31 in magnitude:
+//     K * (qa * qw + (qa + qw) * L + L * L)  <  2^31,
+// the largest value sum((a - beta_x) * (w - beta_w)) and each of its partial sums can take.
 int32_t small_zero_bound(int64_t K, int32_t a_bits, int32_t w_bits)
 {
     const int64_t qa = (1 << a_bits) - 1, qw = (1 << w_bits) - 1, qm = qa > qw ? qa : qw;
-    if (qm * K >= (1 << 23)) return 0;
-    int64_t L = (1ll << 29) / (qm * K);
-    while (L > 0 && (K * L >= (1 << 23) || K * L * L >= (1ll << 29))) L /= 2;
-    return (int32_t)(L > (1 << 20) ? (1 << 20) : L);
+    if (qm * K >= (1 << 23) || qa * qw * K >= (1ll << 31)) return 0;
+    int64_t L = 1 << 20;
+    while (L > 0 && (K * L >= (1 << 23) || K * (qa * qw + (qa + qw) * L + L * L) >= (1ll << 31))) L /= 2;
+    return (int32_t)L;
 }
 
 // Into how many parts K is split (1: not at all).  Only 4-bit codes with 128 x 128 tiles that leave

@@ -482,3 +482,49 @@ def test_theta_helpers_match_the_oracle():
     assert b.qllm_theta_grid_host(np.array([0.5, 2.0, 8.5, 1.0], np.float32), 4) == [2.5, 4.5, 6.5, 8.5]
     with pytest.raises(b.QllmError):
         b.qllm_theta_for_expansion_host(np.zeros(4, np.float32), 1)
+
+
+def test_binding_wrappers_reject_mismatched_tensors_before_calling_the_library():
+    """The C ABI trusts the sizes it is told; the Python wrappers check what they can see (shape, dtype, dense
+    rows, device) and raise before anything reaches the library.  Runs on CPU tensors: every case below fails on a
+    shape or dtype check, or at last on "must be a device tensor"."""
+    import torch
+    N, Cc, K, O = 4, 64, 72, 16
+    x = torch.zeros((N, Cc), dtype=torch.float32)
+    gamma = torch.ones(Cc)
+    dmap = types.SimpleNamespace(C_in=Cc, C_out=K, c=None)
+    out = types.SimpleNamespace(N=N, K=K, bits=4, c=None)
+    weight = types.SimpleNamespace(O=O, K=K, bits=4, c=None)
+    y = torch.zeros((N, O))
+    ws = torch.zeros(1024, dtype=torch.uint8)
+    fused = lambda **kw: b.qllm_norm_reassemble_quant(**{**dict(x=x, norm=b.NORM_RMS, gamma=gamma, beta=None, eps=1e-5,
+                                                                dmap=dmap, bits=4, out=out), **kw})
+    cases = [
+        (lambda: fused(x=torch.zeros((N, Cc + 8))), "the map takes"),
+        (lambda: fused(gamma=torch.ones(Cc - 1)), "gamma must hold"),
+        (lambda: fused(gamma=None), "gamma is required"),
+        (lambda: fused(beta=torch.ones(Cc, dtype=torch.float64)), "beta has dtype"),
+        (lambda: fused(x=torch.zeros((N, 2 * Cc))[:, ::2]), "stride 1"),
+        (lambda: fused(x=torch.zeros((N, Cc), dtype=torch.float16)), "x has dtype"),
+        (lambda: fused(out=types.SimpleNamespace(N=N - 1, K=K, bits=4)), "holds 3 tokens"),
+        (lambda: fused(out=types.SimpleNamespace(N=N, K=K + 8, bits=4)), "channels"),
+        (lambda: fused(out=types.SimpleNamespace(N=N, K=K, bits=8)), "8-bit codes"),
+        (lambda: fused(norm=7), "unknown norm"),
+        (lambda: fused(), "x must be a device"),
+        (lambda: b.qllm_int_gemm(out, types.SimpleNamespace(O=O, K=K + 8, bits=4), y), "weights"),
+        (lambda: b.qllm_int_gemm(out, weight, torch.zeros((N, O + 1))), "y has shape"),
+        (lambda: b.qllm_int_gemm(out, weight, y, acc_dump=torch.zeros(N * O, dtype=torch.int64)), "acc_dump has dtype"),
+        (lambda: b.qllm_reassembled_linear(x, b.NORM_NONE, None, None, 0.0, dmap, 4, types.SimpleNamespace(O=O, K=K - 8, bits=4), y, ws),
+         "the weights take"),
+        (lambda: b.qllm_reassembled_linear(x, b.NORM_NONE, None, None, 0.0, dmap, 4, weight, torch.zeros((N + 1, O)), ws), "y has shape"),
+        (lambda: b.qllm_reassembled_linear_static(x, b.NORM_NONE, None, None, 0.0, dmap, 4, weight, y.to(torch.float64)), "y has dtype"),
+        (lambda: b.qllm_norm_channel_absmax(x, b.NORM_RMS, gamma, None, 1e-5, torch.zeros(Cc + 1)), "absmax must hold"),
+        (lambda: b.qllm_norm_channel_absmax(x, b.NORM_RMS, gamma, None, 1e-5, torch.zeros(Cc), torch.zeros((2, Cc + 1))), "y_dump"),
+        (lambda: b.qllm_match_nearest(x, torch.zeros((Cc + 1, O)), *[torch.zeros(3, dtype=torch.int32)] * 3, torch.zeros(3, dtype=torch.float64), ws),
+         "one row per channel"),
+        (lambda: b.qllm_match_nearest(x, None, torch.zeros(3, dtype=torch.int32), torch.zeros(3, dtype=torch.int32),
+                                      torch.zeros(2, dtype=torch.int32), torch.zeros(3, dtype=torch.float64), ws), "best_j must hold"),
+    ]
+    for call, text in cases:
+        with pytest.raises(ValueError, match=text):
+            call()

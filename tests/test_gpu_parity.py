@@ -351,6 +351,27 @@ def test_gemm_extreme_codes(oracle, b):
         assert np.all(acc.cpu().numpy() == (2 ** bits - 1) ** 2 * K)
 
 
+@pytest.mark.parametrize("N", [17, 300])
+@pytest.mark.parametrize("zx,zw", [(-72, -72), (-16, -15), (-15, -15), (40, -100), (0, -128)])
+def test_gemm_extreme_codes_with_negative_zero_points(oracle, b, N, zx, zw):
+    """8-bit codes all at 255 on the longest K and zero-points far below zero: sum((a - zx)(w - zw)) reaches
+    28672 * 327^2 = 3.07e9, past 32 bits, so the epilogue's narrow-integer shortcut must not be taken there
+    (its bound on the zero-points has to leave room for the accumulator itself)."""
+    K, O = 28672, 40
+    a = np.full((N, K), 255, np.uint8)
+    w = np.full((O, K), 255, np.uint8)
+    w[1::2, ::3] = 7                                                # not every column the same
+    ax, aw = np.full(N, 2.0 ** -20, np.float32), np.full(O, 0.5, np.float32)
+    bx, bw = np.full(N, zx, np.int32), np.full(O, zw, np.int32)
+    y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 8, 8, "f32")
+    ref_acc = oracle.int_gemm(a, w)
+    assert np.array_equal(acc.cpu().numpy(), ref_acc)
+    ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
+    exact = (a.astype(np.int64) - zx) @ (w.astype(np.int64) - zw).T   # the bracket itself, in 64 bits
+    assert np.allclose(ref_y, exact.astype(np.float64) * 2.0 ** -21, rtol=1e-6)
+    check_y(oracle, y, ref_y, "f32")
+
+
 @pytest.mark.parametrize("name", FULL)
 def test_gemm_full_configs_sampled(oracle, b, name):
     """Full benchmark shapes; the oracle checks all tokens x 48 sampled output features and
