@@ -377,20 +377,22 @@ __device__ __forceinline__ Window<BITS> funnel_fetch(const uint32_t *pk, int u)
     return w;
 }
 
+// `vb` = BITS * v in its low 6 bits (whatever sits above them is ignored)
 template <int BITS>
-__device__ __forceinline__ void funnel_shift(const Window<BITS> &w, int v, uint32_t &w0, uint32_t &w1)
+__device__ __forceinline__ void funnel_shift(const Window<BITS> &w, uint32_t vb, uint32_t &w0, uint32_t &w1)
 {
     if constexpr (BITS == 4) {
-        w0 = __builtin_amdgcn_alignbit(w.b0, w.a0, 4 * v); // ({hi, lo} >> 4v), low 32 bits
+        w0 = __builtin_amdgcn_alignbit(w.b0, w.a0, vb); // ({hi, lo} >> 4v), low 32 bits; the instruction reads 5 bits of vb
         w1 = 0;
     } else {
         const uint64_t A = (uint64_t)w.a0 | ((uint64_t)w.a1 << 32), B = (uint64_t)w.b0 | ((uint64_t)w.b1 << 32);
+        const uint32_t sh = vb & 63u;
         uint64_t r;
         if constexpr (BITS == 6) {
-            r = ((A >> (6 * v)) | (B << (48 - 6 * v))) & 0xffffffffffffull;
+            r = ((A >> sh) | (B << (48 - sh))) & 0xffffffffffffull;
         } else {
-            const uint64_t up = B << ((64 - 8 * v) & 63);
-            r = (A >> (8 * v)) | (v ? up : 0ull);
+            const uint64_t up = B << ((64 - sh) & 63);
+            r = (A >> sh) | (sh ? up : 0ull);
         }
         w0 = (uint32_t)r;
         w1 = (uint32_t)(r >> 32);
@@ -400,7 +402,7 @@ __device__ __forceinline__ void funnel_shift(const Window<BITS> &w, int v, uint3
 template <int BITS>
 __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_t &w0, uint32_t &w1)
 {
-    funnel_shift<BITS>(funnel_fetch<BITS>(pk, u), v, w0, w1);
+    funnel_shift<BITS>(funnel_fetch<BITS>(pk, u), (uint32_t)(BITS * v), w0, w1);
 }
 
 // The row loop is software-pipelined over three barrier intervals, so that work bound by latency (LDS
@@ -466,7 +468,10 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     int32_t *dest_w = reinterpret_cast<int32_t *>(pk + (a.n_chunks + 1) * W); // [n_dest] composite group << 3 | position
     uint32_t *segs_w = reinterpret_cast<uint32_t *>(dest_w + a.n_dest); // [n_segw] segments of the composite groups
     uint32_t *chunkw = STREAM ? pk + (a.n_chunks + 1) * W : segs_w + a.n_segw; // [ITERS * lanes] pass bits | staging slot << 8
-    int32_t *work = reinterpret_cast<int32_t *>(chunkw + ITERS * blockDim.x); // [ITERS * lanes] plain and padding output groups
+    // [ITERS * lanes] the lanes' output slots, ready to use: {byte offset of the first of the group's two packed
+    // chunks from pk (a plain group; else that of the zero chunk before pk), BITS * position in that chunk (6 bits) |
+    // group or composite number << 8 | kind << 30}
+    int2 *work = reinterpret_cast<int2 *>(chunkw + ((ITERS * blockDim.x + ((chunkw - reinterpret_cast<uint32_t *>(lds)) & 1)) )); // 8-byte aligned
     const int4 *longs = longs_w;
     const uint4 *rec = rec_w;
     const int2 *spec = spec_w;
@@ -575,7 +580,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     for (int it = 0; it < ITERS; ++it) {
         const int sl = tid + it * nt;
         chunkw[sl] = cw0[it];
-        work[sl] = we0[it];
+        {
+            const uint32_t e = (uint32_t)we0[it], kind = e >> 30;
+            const int d = kind == KIND_PLAIN ? (int)(e & 0x1ffffu) : -GROUP; // non-plain: the zero chunk, not shifted
+            const uint32_t number = kind == KIND_COMP ? e & 0x1ffffu : (e >> 17) & 0x1fffu;
+            work[sl] = make_int2((d >> 3) * (W * 4), (int32_t)((uint32_t)(BITS * (d & 7)) | (number << 8) | (kind << 30)));
+        }
         if (!STREAM && sl < a.n_segw) segs_w[sl] = sg0[it];
     }
     if constexpr (!STREAM) {
@@ -692,7 +702,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     auto composite = [&](int comp, uint32_t &w0, uint32_t &w1) -> int { return composite_of(rec_fetch(comp), comp, w0, w1); };
     // The output pass in pieces, so that the row loop can put other work between its LDS reads and their use.
     struct OutState {
-        int32_t e[ITERS];
+        int2 e[ITERS];
         Window<BITS> win[ITERS];
         RecPair rp; // STREAM: the record of the last slot's composite group, requested together with the packed words
     };
@@ -703,12 +713,11 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     auto out_read_codes = [&](OutState &o) { // padding and composite groups read the row's first words and drop them
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int d = ((uint32_t)o.e[it] >> 30) == KIND_PLAIN ? o.e[it] & 0x1ffff : 0;
-            o.win[it] = funnel_fetch<BITS>(pk, d >> 3);
+            o.win[it] = funnel_fetch<BITS>(reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(pk) + o.e[it].x), 0);
         }
         if constexpr (STREAM) {
-            const bool comp = ((uint32_t)o.e[ITERS - 1] >> 30) == KIND_COMP;
-            o.rp = rec_fetch(comp ? o.e[ITERS - 1] & 0x1ffff : 0);
+            const bool comp = ((uint32_t)o.e[ITERS - 1].y >> 30) == KIND_COMP;
+            o.rp = rec_fetch(comp ? (o.e[ITERS - 1].y >> 8) & 0x3fffff : 0);
         }
     };
     auto out_store = [&](OutState &o, int64_t prev, int ltid) {
@@ -718,21 +727,18 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         uint32_t w0[ITERS], w1[ITERS];
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const bool plain = ((uint32_t)o.e[it] >> 30) == KIND_PLAIN;
-            funnel_shift<BITS>(o.win[it], plain ? o.e[it] & 7 : 0, w0[it], w1[it]);
-            w0[it] = plain ? w0[it] : 0u;
-            w1[it] = plain ? w1[it] : 0u;
-            g[it] = (o.e[it] >> 17) & 0x1fff;
+            funnel_shift<BITS>(o.win[it], (uint32_t)o.e[it].y, w0[it], w1[it]); // not a plain group: all zero
+            g[it] = (o.e[it].y >> 8) & 0x3fffff;
         }
         // composite groups sit in slots of the last pass only
-        if (((uint32_t)o.e[ITERS - 1] >> 30) == KIND_COMP) {
-            const int comp = o.e[ITERS - 1] & 0x1ffff;
+        if (((uint32_t)o.e[ITERS - 1].y >> 30) == KIND_COMP) {
+            const int comp = g[ITERS - 1];
             if constexpr (STREAM) g[ITERS - 1] = composite_of(o.rp, comp, w0[ITERS - 1], w1[ITERS - 1]);
             else g[ITERS - 1] = composite(comp, w0[ITERS - 1], w1[ITERS - 1]);
         }
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            if (FULL || ((uint32_t)o.e[it] >> 30) != KIND_NONE) {
+            if (FULL || ((uint32_t)o.e[it].y >> 30) != KIND_NONE) {
                 store_group<BITS>(out_row, g[it], w0[it], w1[it]);
                 sum += code_sum<BITS>(w0[it], w1[it]);
             }
