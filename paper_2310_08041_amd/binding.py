@@ -155,7 +155,7 @@ def qllm_build_map_host(chan_absmax, theta, src_idx, dst_idx, with_plan=True):
         except QllmError as e:
             if e.status != QLLM_ERR_MAP:
                 raise
-            # a channel merged from more than 64: no plan, the fused kernel walks the CSR instead
+            # counts that do not fit the plan's fields: no plan, the fused kernel walks the CSR instead
             out["plan"] = None
     return out
 

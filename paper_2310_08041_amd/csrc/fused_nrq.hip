@@ -12,11 +12,12 @@
 // LDS rows, the dword next to its neighbour lane's: reads and writes are bank-conflict free also
 // when the map shifts the source channels by an amount that is not a multiple of 8.
 //
-// Two kernels.  fused_planned_kernel is the fast one: persistent workgroups (each keeps its share of
-// gamma and of the map's plan in registers across the rows it processes), the next row's loads in
-// flight while the current row is worked on, no global reads of the map per row.  It needs the plan
-// of qllm_plan_map_host.  fused_nrq_kernel is the plain one that walks the CSR; it serves maps
-// without a plan, or whose general groups do not fit in LDS next to the row.
+// Two kernels.  fused_planned_kernel (fused_planned.hip) is the fast one: persistent workgroups (each keeps
+// its share of gamma in registers and the map's plan in LDS across the rows it processes, or, for maps too
+// big for that, reads the plan's lists from L2), the next row's loads in flight while the current row is
+// worked on.  It needs the plan of qllm_plan_map_host.  fused_nrq_kernel is the plain one that walks the
+// CSR; it serves maps without a plan, rows that are not 16-byte aligned or whole chunks long, and the few
+// shapes whose row does not fit on chip next to its codes.  qllm_fused_kernel_choice tells which runs.
 //
 // Compiled with -ffp-contract=off: every fp32 product and sum is rounded on its own; the only fused
 // multiply-adds are the explicit ones of the quantizer, whose single rounding is the definition.
