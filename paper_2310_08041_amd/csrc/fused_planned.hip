@@ -405,20 +405,26 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
     funnel_shift<BITS>(funnel_fetch<BITS>(pk, u), (uint32_t)(BITS * v), w0, w1);
 }
 
-// The row loop is software-pipelined over three barrier intervals, so that work bound by latency (LDS
-// round trips, cross-lane reductions, dependent scalar chains) has dense arithmetic of another step of
-// the path next to it in the same interval:
-//   interval 1   step a1 of row r, first half: widen the row (it was requested one row earlier), request
-//                row r + 1, x of the chunks that hold a source of a computed channel staged in LDS,
-//                partial sums of the row statistics; and the LAST step of row r - 1: its output groups are
-//                assembled from the packed words and stored.
-//   interval 2   rstd (mu) from the partial sums; y = norm(x) in registers; min/max; steps a2 + a3 for the
-//                computed channels, which normalise the staged x of their sources themselves (gamma and
-//                beta of the staged chunks sit in LDS for the lifetime of the workgroup), so that no
-//                barrier separates them from the rest of the row.
-//   interval 3   range (Eq. 2), codes of the lane's own chunks packed in input order, codes of the
-//                computed channels.
-// LayerNorm has one more barrier inside interval 2 (the mean has to be known before the squared
+// The row loop is software-pipelined over three phases with TWO barriers per row, so that work bound by
+// latency (LDS round trips, cross-lane reductions, dependent scalar chains) has dense arithmetic of another
+// step of the path next to it between the same two barriers:
+//   phase 1   step a1 of row r, first half: widen the row (it was requested one row earlier), request
+//             row r + 1, x of the chunks that hold a source of a computed channel staged in LDS,
+//             partial sums of the row statistics.
+//   -- barrier (also: every wave has finished phase 3 of row r - 1)
+//   phase 2   the LAST step of row r - 1: its output groups are assembled from the packed words and stored;
+//             rstd (mu) from the partial sums; y = norm(x) in registers; min/max; steps a2 + a3 for the
+//             computed channels, which normalise the staged x of their sources themselves (gamma and
+//             beta of the staged chunks sit in LDS for the lifetime of the workgroup), so that no
+//             barrier separates them from the rest of the row.
+//   -- barrier
+//   phase 3   range (Eq. 2), codes of the lane's own chunks packed in input order, codes of the
+//             computed channels; runs on into phase 1 of row r + 1 without a barrier.
+// Every buffer in LDS is written in one phase and read in the next, with one of the two barriers in between,
+// and written again no earlier than a barrier after its last read: the packed words and the computed
+// channels' codes of row r are written in its phase 3, read in phase 2 of row r + 1 (behind the first barrier)
+// and written again in phase 3 of row r + 1 (behind the second).
+// LayerNorm has one more barrier inside phase 2 (the mean has to be known before the squared
 // deviations are summed).
 //
 // Every lane owns ITERS chunks of the row and as many plain output groups: the regular, dense part.  The
@@ -489,6 +495,10 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     __shared__ int32_t red_i[16];
     // bf16 rows are prefetched one row ahead; fp32 rows would need twice the registers and are not
     constexpr bool PREFETCH = sizeof(XT) == 2;
+    // The streamed form puts the output groups of the row before together in phase 1 and pays a third barrier at
+    // the end of phase 3 for it: its phase 2 is the long one (long rows, lists from L2), and the composite groups'
+    // records come from L2 as well.
+    constexpr bool OUT_IN_PHASE_1 = STREAM;
 
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int n_chunks = a.n_chunks;
@@ -709,15 +719,15 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
     auto out_read_work = [&](OutState &o, int ltid) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) o.e[it] = work[ltid + it * nt];
+        if constexpr (STREAM) { // the record of the last slot's composite group comes from global memory: asked for early
+            const bool comp = ((uint32_t)o.e[ITERS - 1].y >> 30) == KIND_COMP;
+            o.rp = rec_fetch(comp ? (o.e[ITERS - 1].y >> 8) & 0x3fffff : 0);
+        }
     };
     auto out_read_codes = [&](OutState &o) { // padding and composite groups read the row's first words and drop them
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             o.win[it] = funnel_fetch<BITS>(reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(pk) + o.e[it].x), 0);
-        }
-        if constexpr (STREAM) {
-            const bool comp = ((uint32_t)o.e[ITERS - 1].y >> 30) == KIND_COMP;
-            o.rp = rec_fetch(comp ? (o.e[ITERS - 1].y >> 8) & 0x3fffff : 0);
         }
     };
     auto out_store = [&](OutState &o, int64_t prev, int ltid) {
@@ -763,13 +773,16 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         int ltid = threadIdx.x;
         asm volatile("" : "+v"(ltid));
 
-        // ================= interval 1
+        // ================= phase 1
         // In the order the hardware should see it (scheduling fences in between): LDS reads first, dense
         // arithmetic while they are under way, and the next row's loads spread out between blocks of
         // arithmetic instead of in one burst (14 wavefronts asking for 57 KB at once queue up in the address unit).
         OutState o;
         uint32_t slot[ITERS];
-        out_read_work(o, ltid);
+        if constexpr (OUT_IN_PHASE_1) {
+            out_read_work(o, ltid);
+            out_read_codes(o);
+        }
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) slot[it] = chunkw[ltid + it * nt] >> 8;
         __builtin_amdgcn_sched_barrier(0);
@@ -798,10 +811,6 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
 #pragma unroll
             for (int j = 0; j < GROUP; ++j) asm volatile("" : "+v"(y[it][j]));
         }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- the packed words the output groups of the row before are made of (used after the statistics)
-        out_read_codes(o);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- row statistics in fp64 (two interleaved partial sums per lane: the additions do not wait for one
@@ -837,10 +846,12 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             }
         }
 
-        // ---- step a4, second half, of the row before: its output groups, stored
-        int32_t sum = out_store(o, prev, ltid);
-
-        // ---- x of the chunks that hold a source of a computed channel (normalised by its readers in interval 2)
+        if constexpr (OUT_IN_PHASE_1) {
+            int32_t sum = out_store(o, prev, ltid);
+            sum = wave_sum_i32(sum);
+            if (lane == 0) red_i[wave] = sum;
+        }
+        // ---- x of the chunks that hold a source of a computed channel (normalised by its readers in phase 2)
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             if (!STREAM && slot[it] != NOT_PUBLISHED) {
@@ -854,13 +865,14 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             const double s = wave_sum(s0 + s1);
             if (lane == 0) red_d[0][wave] = s;
         }
-        sum = wave_sum_i32(sum);
-        if (lane == 0) red_i[wave] = sum; // read after the barrier
-        __syncthreads(); // partial statistics, staged x, partial rowsum; the packed words and the codes of the
-                         // computed channels of the row before are no longer needed
-        finish_rowsum(prev);
+        __syncthreads(); // partial statistics, staged x; and every wave is done with interval 3 of the row before:
+                         // its packed words and the codes of its computed channels are complete
 
-        // ================= interval 2
+        // ================= phase 2
+        // ---- step a4, second half, of the row before: the words its output groups are made of are requested
+        //      first and put together further down, after the dense arithmetic of this row
+        if constexpr (OUT_IN_PHASE_1) finish_rowsum(prev);
+        else out_read_work(o, ltid);
         // What a computed channel reads does not depend on the row's statistics: the first pass's entries and
         // the staged x, gamma (beta) of their sources are requested now and used after rstd is known.
         struct Staged {
@@ -961,6 +973,15 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
                     mx = fmaxf(fmaxf(mx, y[it][j]), y[it][j + 1]);
                 }
             }
+        }
+
+        // ---- step a4, second half, of the row before: its output groups put together and stored; the wavefront's
+        //      share of that row's code sum goes through the same barrier as this row's min/max
+        if constexpr (!OUT_IN_PHASE_1) {
+            out_read_codes(o);
+            int32_t sum = out_store(o, prev, ltid);
+            sum = wave_sum_i32(sum);
+            if (lane == 0) red_i[wave] = sum;
         }
 
         {
@@ -1066,7 +1087,8 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         }
         __syncthreads(); // also: the computed channels' values are complete
 
-        // ================= interval 3
+        // ================= phase 3
+        if constexpr (!OUT_IN_PHASE_1) finish_rowsum(prev);
         const bool code0 = ltid < a.n_dest;
         const float spec_v0 = code0 ? specv[ltid] : 0.0f; // first pass of the computed channels' codes:
         const int32_t spec_d0 = code0 ? dest[ltid] : 0;    // requested now, used after the range is known
@@ -1115,11 +1137,14 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             if (a.n_dest > nt)
                 for (int j = ltid + nt; j < a.n_dest; j += nt) put_code(specv[j], dest[j]);
         }
-        __syncthreads(); // packed words and computed channels' codes complete
+        // no barrier here: what this phase wrote is read behind the first barrier of the next row and written
+        // again behind its second
+        if constexpr (OUT_IN_PHASE_1) __syncthreads(); // packed words and computed channels' codes complete
         prev = row;
     }
     // the last row's output groups
     {
+        __syncthreads(); // packed words and computed channels' codes complete
         const int ltid = threadIdx.x;
         OutState o;
         out_read_work(o, ltid);
@@ -1154,13 +1179,13 @@ int cu_count()
 // waves go to the CU's four SIMDs in turn, so the SIMD with the most of them, ceil(waves / 4), sets the pace:
 // the cost of a row is that count times (chunks per lane + the fixed work of a wave and row, about one
 // chunk's worth).  With fewer rows than CUs every workgroup has one row and the fewest chunks per lane win.
-Shape pick_shape(int units, int64_t N)
+Shape pick_shape(int units, int64_t N, bool layer_norm)
 {
     Shape best{0, 0};
     int best_cost = 0;
-    for (int iters = 1; iters <= 4; ++iters) {
+    for (int iters = 1; iters <= (layer_norm ? 4 : 5); ++iters) { // LayerNorm at five chunks per lane spills
         const int nt = ((units + iters - 1) / iters + 63) / 64 * 64;
-        if (nt > 1024) continue;
+        if (nt > (iters == 5 ? 768 : 1024)) continue; // five chunks per lane need the registers of three waves per SIMD
         const int waves = nt / 64;
         const int cost = N <= cu_count() ? iters : (waves + 3) / 4 * (iters + 1);
         if (best.iters == 0 || cost < best_cost) {
@@ -1233,6 +1258,9 @@ int32_t dispatch(const FusedArgs &a, const Shape &sh, size_t lds, bool stream_li
     if (sh.iters == 1) return launch(fused_planned_kernel<XT, BITS, 1, 1024, true, NORM, FULL>, a, sh, lds, stream);
     if (sh.iters == 2) return launch(fused_planned_kernel<XT, BITS, 2, 1024, true, NORM, FULL>, a, sh, lds, stream);
     if (sh.iters == 3) return launch(fused_planned_kernel<XT, BITS, 3, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
+    if constexpr (NORM != QLLM_NORM_LAYER) {
+        if (sh.iters == 5) return launch(fused_planned_kernel<XT, BITS, 5, 768, true, NORM, FULL>, a, sh, lds, stream);
+    }
     return launch(fused_planned_kernel<XT, BITS, 4, 1024, NORM != QLLM_NORM_LAYER, NORM, FULL>, a, sh, lds, stream);
 }
 
@@ -1278,7 +1306,7 @@ Choice choose(const FusedArgs &a, int32_t x_dtype, int32_t bits)
     const qllm_detail::PlanCounts p{a.n_comp, a.n_long, a.n_pub, a.n_chunks, a.n_spec, a.n_dest, a.n_segw};
     const int64_t w = bits == 4 ? 1 : 2;
     {
-        const Shape sh = pick_shape(units, a.N);
+        const Shape sh = pick_shape(units, a.N, a.norm == QLLM_NORM_LAYER);
         // staged x, and gamma / beta at the same positions when there is a norm / a shift
         const int64_t stage_sets = 1 + (a.norm != QLLM_NORM_NONE ? 1 : 0) + (a.norm == QLLM_NORM_LAYER && a.beta ? 1 : 0);
         const int64_t lds = qllm_detail::fused_lists_lds_bytes(p, w, stage_sets, (int64_t)sh.iters * sh.nt);
