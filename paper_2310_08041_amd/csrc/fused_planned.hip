@@ -429,9 +429,9 @@ __device__ __forceinline__ void funnel(const uint32_t *pk, int u, int v, uint32_
 //
 // Every lane owns ITERS chunks of the row and as many plain output groups: the regular, dense part.  The
 // irregular part -- computed channels, long rows, composite output groups -- is a few hundred items per row,
-// dealt out over the lanes in order.  (Giving it to two extra wavefronts of its own, which would also even out
-// the wavefronts per SIMD -- 14 are 4 + 4 + 3 + 3 -- was measured: they take longer over the long rows and
-// the composite groups than the others take over the row, 66 against 57 us at the 70B shape.)
+// dealt out over the lanes in order.  (Giving it to two extra wavefronts of its own was measured with 14 + 2
+// wavefronts at the 70B shape: they take longer over the long rows and the composite groups than the others
+// take over the row, 66 against 57 us.)
 //
 // Input channels that no output channel copies (split channels, channels merged away or into) must stay
 // out of min/max, and their codes must not spill into their neighbours' bits.  The lane's own copy of
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
         // ================= phase 1
         // In the order the hardware should see it (scheduling fences in between): LDS reads first, dense
         // arithmetic while they are under way, and the next row's loads spread out between blocks of
-        // arithmetic instead of in one burst (14 wavefronts asking for 57 KB at once queue up in the address unit).
+        // arithmetic instead of in one burst (a dozen wavefronts asking for 57 KB at once queue up in the address unit).
         OutState o;
         uint32_t slot[ITERS];
         if constexpr (OUT_IN_PHASE_1) {
@@ -789,7 +789,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
 
         // ---- step a1, first half.  A bf16 row is already here (it was requested while the row before it
         //      was worked on): widen it; the next one goes into the same registers further down.
-        float y[ITERS][GROUP]; // x until interval 2 turns it into y in place
+        float y[ITERS][GROUP]; // x until phase 2 turns it into y in place
         if constexpr (!PREFETCH) {
 #pragma unroll
             for (int it = 0; it < ITERS; ++it) {
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(NT_MAX) void fused_planned_kernel(const FusedArgs a
             const double s = wave_sum(s0 + s1);
             if (lane == 0) red_d[0][wave] = s;
         }
-        __syncthreads(); // partial statistics, staged x; and every wave is done with interval 3 of the row before:
+        __syncthreads(); // partial statistics, staged x; and every wave is done with phase 3 of the row before:
                          // its packed words and the codes of its computed channels are complete
 
         // ================= phase 2
