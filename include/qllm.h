@@ -97,6 +97,9 @@ typedef struct {
     const float *scale;     /* [O] alpha_w */
     const int32_t *zero;    /* [O] beta_w */
     const int32_t *colsum;  /* [O] sum_k codes[o, k] */
+    const uint8_t *tiles6;  /* optional, bits == 4 only: device copy of the codes in the layout qllm_pack_tiles6
+                               makes, qllm_tiles6_bytes(O, K) bytes, 16-byte aligned.  With it (and room in the
+                               workspace, see qllm_int_gemm) the GEMM runs on the FP6 matrix cores.  NULL: int8. */
 } qllm_weight;
 
 /* Per-token quantized activations: output of the fused kernel, input of the GEMM. */
@@ -135,9 +138,18 @@ int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, in
  *   a, a_bits   quantized activations [N, K]; a_bits must equal w->bits, or be 8 with w->bits 4.
  *   y           [N, ldy] y_dtype (fp32, or bf16 rounded to nearest even); ldy >= O in elements.
  *   acc_dump    NULL, or [N, O] int32 that receives the raw accumulators.
- *   workspace   scratch of at least qllm_gemm_workspace_bytes(N, w->K, w->O, a_bits) bytes, 16-byte
- *               aligned (may be NULL when that is 0: it is non-zero only where the sum over K is
- *               split over workgroups); contents undefined afterwards.
+ *   workspace   scratch, 16-byte aligned, contents undefined afterwards.  qllm_gemm_workspace_bytes(N,
+ *               w->K, w->O, a_bits) bytes serve every path; at least qllm_gemm_workspace_floor_bytes(...)
+ *               are required (may be NULL when that is 0: it is non-zero only where the sum over K is
+ *               split over workgroups), else QLLM_ERR_WORKSPACE.
+ *
+ * The FP6 path.  For 4-bit codes on both sides and N > 32 the same acc[n,o] is also available from the FP6
+ * matrix cores at close to twice the int8 rate: a code c, zero-extended to 6 bits, is the E2M3 number c/8, the
+ * products a*w/64 and all their partial sums (multiples of 1/64 below 2^18, K <= 74564) are exact in fp32, and
+ * 64 times the fp32 accumulator is the integer accumulator of Eq. (1), bit for bit.  It is taken when
+ * w->tiles6 is set, qllm_gemm_workspace_floor_bytes(...) is 0 for the shape (K not split) and the workspace
+ * holds at least qllm_tiles6_bytes(N, w->K) bytes (the activations are re-laid into it first, a few per cent of
+ * the GEMM's time); otherwise the int8 path runs.  Same results either way.
  */
 int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
                       int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
@@ -145,8 +157,10 @@ int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_
 
 /* ------------------------------------------------------------------------------------------
  * The whole layer a1..a6: qllm_norm_reassemble_quant into workspace, then qllm_int_gemm, on one
- * stream.  workspace must hold qllm_workspace_bytes(N, map->C_out, w->O, a_bits) bytes, 256-byte
- * aligned.  Arguments as in the two calls above.
+ * stream.  workspace: 256-byte aligned; qllm_workspace_bytes(N, map->C_out, w->O, a_bits) bytes serve every
+ * path (the quantized activations, the GEMM's own need, and for 4-bit codes the room its FP6 path wants);
+ * with less, down to qllm_workspace_floor_bytes(...), the layer still runs, the GEMM on its int8 path.
+ * Arguments as in the two calls above.
  */
 int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
                                 int32_t norm, const float *gamma, const float *beta, float eps,
@@ -159,7 +173,7 @@ int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64
  * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments without the workspace, same kernels, same results bit for bit; the workspace is a device array
  * inside the library, QLLM_STATIC_WORKSPACE_BYTES per GPU, held until the process ends.  The call allocates and
- * frees nothing.  QLLM_ERR_WORKSPACE if qllm_workspace_bytes(N, map->C_out, w->O, a_bits) exceeds that size
+ * frees nothing.  QLLM_ERR_WORKSPACE if qllm_workspace_floor_bytes(N, map->C_out, w->O, a_bits) exceeds that size
  * (decode and small-batch shapes fit: 16 tokens x 8192 channels need 0.1 MB, 512 tokens x 28672 channels at 4
  * bits 7.4 MB).  All calls on one GPU share the array: two of them in flight at once on different streams race;
  * calls on one stream are ordered like any other work.  The first call on a device asks the runtime for the
@@ -237,7 +251,23 @@ int32_t qllm_sq_error(const void *got, int32_t got_dtype, int64_t N, int64_t O, 
 /* Sizes.  Negative return = qllm_status. */
 int64_t qllm_packed_row_bytes(int64_t K, int32_t bits);
 int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
+int64_t qllm_gemm_workspace_floor_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
 int64_t qllm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
+int64_t qllm_workspace_floor_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);
+
+/* ------------------------------------------------------------------------------------------
+ * 4-bit codes re-laid for the FP6 matrix-core path of qllm_int_gemm (Eq. 1 on the codes; see there).
+ *   codes   device, [rows, qllm_packed_row_bytes(K, 4)] in the packed format above, 16-byte aligned.
+ *   tiles   device, qllm_tiles6_bytes(rows, K) bytes, 16-byte aligned, fully overwritten:
+ *           rows in blocks of 16 (the last one filled with zero codes), K in tiles of 128 codes up to the
+ *           padded row length; block b, K-tile t is the 1536 bytes at (b * tiles_per_row + t) * 1536; for
+ *           l = 0..63, r = l % 16, q = l / 16 the 32 codes 128 t + 32 q + e (e = 0..31) of row 16 b + r form a
+ *           192-bit little-endian number with code e in bits 6 e .. 6 e + 3 (bits 6 e + 4, 6 e + 5 zero); its
+ *           first 16 bytes lie at 16 l of the block, its last 8 at 1024 + 8 l.
+ * For a weight: once, offline, into qllm_weight.tiles6.  Errors: NULL / SHAPE / ALIGN / HIP.  rows == 0: no-op.
+ */
+int64_t qllm_tiles6_bytes(int64_t rows, int64_t K);
+int32_t qllm_pack_tiles6(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *tiles, void *hip_stream);
 
 const char *qllm_status_string(int32_t status);
 

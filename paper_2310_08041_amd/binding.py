@@ -38,7 +38,7 @@ class _Map(C.Structure):
 
 class _Weight(C.Structure):
     _fields_ = [("O", C.c_int64), ("K", C.c_int64), ("bits", C.c_int32), ("codes", C.c_void_p),
-                ("scale", C.c_void_p), ("zero", C.c_void_p), ("colsum", C.c_void_p)]
+                ("scale", C.c_void_p), ("zero", C.c_void_p), ("colsum", C.c_void_p), ("tiles6", C.c_void_p)]
 
 
 class _QAct(C.Structure):
@@ -57,6 +57,10 @@ _sigs = {
     "qllm_packed_row_bytes": (_i64, [_i64, _i32]),
     "qllm_gemm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i32]),
+    "qllm_workspace_floor_bytes": (_i64, [_i64, _i64, _i64, _i32]),
+    "qllm_gemm_workspace_floor_bytes": (_i64, [_i64, _i64, _i64, _i32]),
+    "qllm_tiles6_bytes": (_i64, [_i64, _i64]),
+    "qllm_pack_tiles6": (_i32, [_vp, _i64, _i64, _vp, _vp]),
     "qllm_status_string": (C.c_char_p, [_i32]),
     "qllm_last_hip_error": (C.c_char_p, []),
     "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64),
@@ -123,6 +127,33 @@ def qllm_workspace_bytes(N, K, O, a_bits):
     v = _lib.qllm_workspace_bytes(int(N), int(K), int(O), int(a_bits))
     _chk(v if v < 0 else 0, "qllm_workspace_bytes")
     return v
+
+
+def qllm_workspace_floor_bytes(N, K, O, a_bits):
+    v = _lib.qllm_workspace_floor_bytes(int(N), int(K), int(O), int(a_bits))
+    _chk(v if v < 0 else 0, "qllm_workspace_floor_bytes")
+    return int(v)
+
+
+def qllm_gemm_workspace_floor_bytes(N, K, O, a_bits):
+    v = _lib.qllm_gemm_workspace_floor_bytes(int(N), int(K), int(O), int(a_bits))
+    _chk(v if v < 0 else 0, "qllm_gemm_workspace_floor_bytes")
+    return int(v)
+
+
+def qllm_tiles6_bytes(rows, K):
+    v = _lib.qllm_tiles6_bytes(int(rows), int(K))
+    _chk(v if v < 0 else 0, "qllm_tiles6_bytes")
+    return int(v)
+
+
+def qllm_pack_tiles6(codes, rows, K, tiles, stream=None):
+    """codes [rows, packed_row_bytes(K, 4)] uint8, tiles [tiles6_bytes(rows, K)] uint8: device tensors."""
+    torch = _torch()
+    _check_tensor(codes, "codes", (torch.uint8,), numel=int(rows) * qllm_packed_row_bytes(K, 4))
+    _check_tensor(tiles, "tiles", (torch.uint8,), numel=qllm_tiles6_bytes(rows, K))
+    _check_on_device(codes=codes, tiles=tiles)
+    _chk(_lib.qllm_pack_tiles6(_dp(codes), int(rows), int(K), _dp(tiles), _stream(stream)), "qllm_pack_tiles6")
 
 
 def qllm_gemm_workspace_bytes(N, K, O, a_bits):
@@ -292,7 +323,8 @@ class DeviceMap:
 class DeviceWeight:
     """Device copy of packed per-output-channel quantized weights."""
 
-    def __init__(self, codes, scale, zero, colsum, K, bits, device="cuda"):
+    def __init__(self, codes, scale, zero, colsum, K, bits, device="cuda", tiles6=True):
+        """tiles6: for 4-bit codes also keep the copy laid out for the FP6 matrix-core path (1.5 x the packed size)."""
         torch = _torch()
         self.codes = torch.as_tensor(np.ascontiguousarray(codes, np.uint8)).to(device)
         self.scale = torch.as_tensor(np.ascontiguousarray(scale, np.float32)).to(device)
@@ -300,8 +332,12 @@ class DeviceWeight:
         self.colsum = torch.as_tensor(np.ascontiguousarray(colsum, np.int32)).to(device)
         self.O, self.K, self.bits = int(self.codes.shape[0]), int(K), int(bits)
         assert self.codes.shape[1] == qllm_packed_row_bytes(K, bits)
+        self.tiles6 = None
+        if tiles6 and self.bits == 4:
+            self.tiles6 = torch.empty(qllm_tiles6_bytes(self.O, self.K), dtype=torch.uint8, device=device)
+            qllm_pack_tiles6(self.codes, self.O, self.K, self.tiles6)
         self.c = _Weight(self.O, self.K, self.bits, _dp(self.codes), _dp(self.scale), _dp(self.zero),
-                         _dp(self.colsum))
+                         _dp(self.colsum), _dp(self.tiles6))
 
 
 class DeviceQAct:

@@ -17,6 +17,7 @@
 #include <stdint.h>
 
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "qllm.h"
@@ -44,6 +45,7 @@ struct GemmArgs {
     int32_t *acc_dump;
     int32_t *partial; // [splits][N][O] raw accumulators when K is split over workgroups, else unused
     int32_t splits;
+    const uint8_t *a_tiles, *w_tiles; // both operands as 6-bit fields in matrix-core order (see TILES6 below), or null
 };
 
 template <int BITS>
@@ -643,6 +645,205 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void int_gemm_w4a4_kerne
     }
 }
 
+// ---- 4-bit codes on both sides on the FP6 matrix cores.
+// gfx950 multiplies 6-bit floating-point operands (E2M3: sign, 2 exponent bits, 3 mantissa bits, no
+// infinities or NaNs) at twice the rate of int8, 128 values of K per operation.  The 6-bit pattern
+// 00cccc, a 4-bit code c zero-extended, IS the E2M3 number c / 8 (exponent field 0: c / 8 for c < 8;
+// exponent field 1: (8 + (c - 8)) / 8), so the product of two codes is a * w / 64 exactly, and the
+// fp32 accumulation is exact as well: every partial sum, whatever the order and grouping the hardware
+// adds in, is a multiple of 1/64 below 225 K / 64 < 2^24 / 64 (K < 74565; the entry point allows
+// 32768), hence a representable fp32 number, so no addition ever rounds.  64 acc is the int32
+// accumulator of Eq. (1), bit for bit.
+//
+// TILES6, the operand format (made once per weight by qllm_pack_tiles6, per call for the activations):
+// rows in blocks of 16, K in tiles of 128 codes; block b, K-tile t is the 1536 bytes at
+// (b * tiles + t) * 1536 and holds what the 64 lanes of one operand read need, lane l = 16 q + r having
+// row 16 b + r and codes 128 t + 32 q + e, e = 0..31, code e in bits 6 e .. 6 e + 3 of a 192-bit
+// little-endian number: its first 16 bytes at 16 l, its last 8 at 1024 + 8 l.  Rows past the matrix
+// are zero codes.  A stage of LDS is such blocks one after the other exactly as they lie in memory,
+// so the refill is a plain copy (16-byte loads that write LDS directly) and both operand reads
+// (ds_read_b128 of 1 KB, ds_read_b64 of 512 bytes per wave) are contiguous: no bank conflicts, and no
+// vector instruction between LDS and the matrix cores.
+//
+// Same tiling as the int8 kernel above (2 x 4 waves, MI x NJ operations of 16 x 16 per wave and
+// K-tile), a ring of three stages (48 KB each for the 256 x 256 tile), fetches two K-tiles ahead.
+// One K-tile = MI groups of NJ operations (group i: token rows 16 i ..); token-side operands are
+// requested AHEAD groups before their use into a ring of four, the feature side at the start of the
+// iteration into the register set the previous K-tile does not use; the loop is rotated by AHEAD
+// groups (an iteration starts with the last groups of the K-tile before, zeros the first time), and
+// unrolled by two so that the alternation of the feature-side register sets is static.
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr int T6_BLOCK = 1536, T6_X = 1024, T6_KT = 128, T6_STAGES = 3;
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+struct Frag6 {
+    v4i x;
+    v2i y;
+};
+__device__ __forceinline__ v8i operand6(const Frag6 &f) { return v8i{f.x[0], f.x[1], f.x[2], f.x[3], f.y[0], f.y[1], 0, 0}; }
+__device__ __forceinline__ Frag6 read6(const uint8_t *block, int lane)
+{
+    Frag6 f;
+    f.x = *reinterpret_cast<const v4i *>(block + 16 * lane);
+    f.y = *reinterpret_cast<const v2i *>(block + T6_X + 8 * lane);
+    return f;
+}
+
+template <typename YT, int MI, int NJ>
+__global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kernel(const GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int TM = 2 * MI * 16, TN = 4 * NJ * 16;
+    constexpr int BLOCKS = (TM + TN) / 16, STAGE = BLOCKS * T6_BLOCK, NLOAD = STAGE / (8 * 1024);
+    static_assert(STAGE % (8 * 1024) == 0, "a stage is a whole number of 1 KB loads per wave");
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int n0 = blockIdx.y * TM, o0 = blockIdx.x * TN;
+    const int all_kt = g.Kpad / T6_KT;
+    const int a_blocks = (g.N + 15) / 16, w_blocks = (g.O + 15) / 16;
+
+    // fetch assignment: load t of wave w fills bytes 1024 (NLOAD w + t) .. of the stage, lane l its l-th 16.  The
+    // token side of a stage is a whole number of such loads, so a load is all token side or all feature side: one
+    // base for the wave, a 32-bit offset per lane that never changes (the K-tile moves the base).
+    uint32_t src_off[NLOAD];
+#pragma unroll
+    for (int t = 0; t < NLOAD; ++t) {
+        const int off = (wave * NLOAD + t) * 1024 + lane * 16, blk = off / T6_BLOCK, within = off % T6_BLOCK;
+        const bool token = blk < TM / 16; // past the edge: the last block again (its results are not stored)
+        const int rb = token ? min(n0 / 16 + blk, a_blocks - 1) : min(o0 / 16 + blk - TM / 16, w_blocks - 1);
+        src_off[t] = (uint32_t)rb * (uint32_t)all_kt * T6_BLOCK + within;
+    }
+    static_assert((TM / 16 * T6_BLOCK) % 1024 == 0, "token side = whole loads");
+    auto fetch = [&](int kt, int stage) { // K-tile kt (clamped to the last one) -> that stage of the ring
+        const int ktc = min(kt, all_kt - 1);
+        uint8_t *dst = lds + stage * STAGE + wave * NLOAD * 1024;
+#pragma unroll
+        for (int t = 0; t < NLOAD; ++t) {
+            const bool token = (wave * NLOAD + t) * 1024 < TM / 16 * T6_BLOCK;
+            const uint8_t *base = (token ? g.a_tiles : g.w_tiles) + (int64_t)ktc * T6_BLOCK;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + src_off[t]),
+                                             (__attribute__((address_space(3))) void *)(dst + t * 1024), 16, 0, 0);
+        }
+    };
+    constexpr int WAIT_LANDED = NLOAD | (7 << 4) | (15 << 8);       // s_waitcnt vmcnt(NLOAD): all but the newest fetch
+    constexpr int WAIT_LANDED_LGKM0 = NLOAD | (7 << 4) | (0 << 8);  // ... and lgkmcnt(0)
+
+    v4f acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    fetch(0, 0);
+    fetch(1, 1);
+    __builtin_amdgcn_s_waitcnt(WAIT_LANDED);
+    __syncthreads();
+
+    constexpr int RING = 4, AHEAD = 2;
+    static_assert(MI % RING == 0 && AHEAD < RING && AHEAD < MI, "group plan");
+    Frag6 ar[RING], wr[2][NJ];
+#pragma unroll
+    for (int k = 0; k < RING; ++k) ar[k] = Frag6{v4i{0, 0, 0, 0}, v2i{0, 0}};
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) wr[0][j] = wr[1][j] = Frag6{v4i{0, 0, 0, 0}, v2i{0, 0}};
+
+    const int a_blk0 = wm * MI, w_blk0 = TM / 16 + wn * NJ; // the wave's first token-side and feature-side block of a stage
+    int stage = 0, fetch_stage = 2;
+    // one K-tile, P = which feature-side register set it reads into (the other one still serves the
+    // AHEAD groups left of the K-tile before)
+    auto k_tile = [&](auto parity, int kt) {
+        constexpr int P = decltype(parity)::value;
+        const uint8_t *cur = lds + stage * STAGE;
+        fetch(kt + 2, fetch_stage); // into the stage whose last reader passed the previous barrier
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            wr[P][j] = read6(cur + (w_blk0 + j) * T6_BLOCK, lane);
+            __builtin_amdgcn_sched_barrier(0); // also keeps the 8-byte reads of neighbouring blocks from being merged
+        }
+#pragma unroll
+        for (int u = 0; u < MI; ++u) {
+            const bool old = u < AHEAD;
+            const int i = old ? MI - AHEAD + u : u - AHEAD;
+            ar[u % RING] = read6(cur + (a_blk0 + u) * T6_BLOCK, lane); // for the group AHEAD steps on
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[old ? 1 - P : P][j]), operand6(ar[i % RING]),
+                                                                             acc[i][j], 2, 2, 0, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the next K-tile has landed (this wave's share; the barrier adds the others'), own reads done
+        __builtin_amdgcn_s_waitcnt(WAIT_LANDED_LGKM0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        fetch_stage = stage;
+        stage = stage == T6_STAGES - 1 ? 0 : stage + 1;
+    };
+    int kt = 0;
+    for (; kt + 1 < all_kt; kt += 2) {
+        k_tile(std::integral_constant<int, 0>{}, kt);
+        k_tile(std::integral_constant<int, 1>{}, kt + 1);
+    }
+    if (kt < all_kt) k_tile(std::integral_constant<int, 0>{}, kt);
+    // the loads past the last K-tile went to stages nobody reads; they must not outlive the workgroup
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    // the last groups of the last K-tile
+    auto last_groups = [&](auto parity) {
+        constexpr int P = decltype(parity)::value;
+#pragma unroll
+        for (int i = MI - AHEAD; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[P][j]), operand6(ar[i % RING]), acc[i][j], 2, 2,
+                                                                             0, 0, 0, 0);
+    };
+    if (all_kt & 1) last_groups(std::integral_constant<int, 0>{});
+    else last_groups(std::integral_constant<int, 1>{});
+
+    v4i sums[MI][NJ]; // 64 acc: the integer accumulators, exactly
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sums[i][j][e] = (int)(acc[i][j][e] * 64.0f);
+    finish_wave_tile<4, 4, YT, MI, NJ>(g, sums, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane);
+}
+
+// 4 nibbles in bits 0..15 -> four 6-bit fields in bits 0..23
+__device__ __forceinline__ uint32_t spread4(uint32_t x)
+{
+    const uint32_t y = (x & 0xffu) | ((x & 0xff00u) << 4); // nibbles 0, 1 in bits 0..7; 2, 3 in bits 12..19
+    return (y & 0x00f00fu) | ((y & 0x0f00f0u) << 2);       // nibble k in bits 6 k .. 6 k + 3
+}
+
+// Packed 4-bit rows -> TILES6; one lane per (block, K-tile, lane of the operand read).
+__global__ __launch_bounds__(256) void tiles6_kernel(const uint8_t *codes, int64_t row_bytes, int32_t rows, int32_t n_kt,
+                                                    uint8_t *tiles, int64_t n_items)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_items) return;
+    const int l = (int)(idx & 63), r = l & 15, q = l >> 4;
+    const int64_t bk = idx >> 6, b = bk / n_kt;
+    const int kt = (int)(bk - b * n_kt);
+    const int64_t row = b * 16 + r;
+    uint4 p = make_uint4(0u, 0u, 0u, 0u);
+    if (row < rows) p = *reinterpret_cast<const uint4 *>(codes + row * row_bytes + kt * (T6_KT / 2) + q * 16);
+    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+    uint32_t s[8]; // eight pieces of 24 bits
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s[2 * i] = spread4(w[i] & 0xffffu);
+        s[2 * i + 1] = spread4(w[i] >> 16);
+    }
+    uint8_t *blk = tiles + bk * T6_BLOCK;
+    *reinterpret_cast<uint4 *>(blk + 16 * l) =
+        make_uint4(s[0] | (s[1] << 24), (s[1] >> 8) | (s[2] << 16), (s[2] >> 16) | (s[3] << 8), s[4] | (s[5] << 24));
+    *reinterpret_cast<uint2 *>(blk + T6_X + 8 * l) = make_uint2((s[5] >> 8) | (s[6] << 16), (s[6] >> 16) | (s[7] << 8));
+}
+
 // Sum of the parts of a split K and the dequantising epilogue (4-bit codes on both sides: no offsets),
 // one output per lane; the bracket in 64-bit arithmetic, which gives the same float as the narrow form.
 template <typename YT>
@@ -835,10 +1036,48 @@ int32_t launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const GemmArg
     return QLLM_OK;
 }
 
+// Packed 4-bit rows (device) -> TILES6 (device).
+int32_t launch_tiles6(const uint8_t *codes, int64_t row_bytes, int64_t rows, int64_t Kpad, uint8_t *tiles, hipStream_t stream)
+{
+    const int64_t n_kt = Kpad / T6_KT, n_items = (rows + 15) / 16 * n_kt * 64;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(tiles6_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, stream, codes, row_bytes, (int32_t)rows,
+                       (int32_t)n_kt, tiles, n_items);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        qllm_note_hip_error("tiles6: launch", hipGetErrorName(e));
+        return QLLM_ERR_HIP;
+    }
+    return QLLM_OK;
+}
+
+// 4-bit codes on both sides, more than 32 tokens, on the FP6 matrix cores: the activations are re-laid
+// into g.a_tiles first; then the same choice between 256 x 256 and 128 x 128 tiles as on the int8 path.
+int32_t launch_fp6(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
+{
+    const int32_t st = launch_tiles6(g.a_codes, g.a_row_bytes, g.N, g.Kpad, const_cast<uint8_t *>(g.a_tiles), stream);
+    if (st != QLLM_OK) return st;
+    const int64_t big_tiles = (int64_t)((g.O + LBN - 1) / LBN) * ((g.N + LBM - 1) / LBM);
+    const int64_t small_tiles = (int64_t)((g.O + 127) / 128) * ((g.N + 127) / 128);
+    const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
+    const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
+    if (g.N <= 128 || big_fill < 0.78 * small_fill) {
+        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
+        constexpr size_t lds = (size_t)T6_STAGES * 16 * T6_BLOCK;
+        if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+        return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+    }
+    const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
+    constexpr size_t lds = (size_t)T6_STAGES * 32 * T6_BLOCK;
+    if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
+    return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
+}
+
 template <int ABITS, int WBITS>
 int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     if constexpr (ABITS == 4 && WBITS == 4) {
+        if (g.a_tiles && g.w_tiles) return launch_fp6(g, y_dtype, stream);
         // 4-bit codes on both sides, more than 32 tokens.  256 x 256 tiles run one workgroup per CU, 128 x 128
         // tiles two, at about three quarters of the large tile's rate per matrix-core operation: the
         // small tile is taken where it fills the chip's rounds that much better (few tiles, or a last
@@ -926,12 +1165,19 @@ int32_t k_splits(int64_t N, int64_t K, int64_t O, int32_t a_bits)
 
 } // namespace
 
-extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+extern "C" int64_t qllm_gemm_workspace_floor_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
 {
     if (a_bits != 4 && a_bits != 6 && a_bits != 8) return QLLM_ERR_BITS;
     if (N < 0 || K <= 0 || O <= 0) return QLLM_ERR_SHAPE;
     const int32_t s = k_splits(N, K, O, a_bits);
     return s > 1 ? (int64_t)s * N * O * (int64_t)sizeof(int32_t) : 0;
+}
+
+extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    const int64_t floor_bytes = qllm_gemm_workspace_floor_bytes(N, K, O, a_bits);
+    if (floor_bytes != 0) return floor_bytes; // an error, or K is split (then the FP6 path is not taken)
+    return a_bits == 4 && N > 32 && 225 * K < (1 << 24) ? qllm_tiles6_bytes(N, K) : 0;
 }
 
 extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
@@ -952,7 +1198,7 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     if (qa * qw * w->K > INT32_MAX) return QLLM_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(a->codes) & 15u) || (reinterpret_cast<uintptr_t>(w->codes) & 15u))
         return QLLM_ERR_ALIGN;
-    if (workspace_bytes < qllm_gemm_workspace_bytes(N, w->K, w->O, a_bits)) return QLLM_ERR_WORKSPACE;
+    if (workspace_bytes < qllm_gemm_workspace_floor_bytes(N, w->K, w->O, a_bits)) return QLLM_ERR_WORKSPACE;
     if (N == 0) return QLLM_OK;
 
     GemmArgs g{};
@@ -968,6 +1214,14 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     g.splits = (a_bits == 4 && wb == 4) ? k_splits(N, w->K, w->O, a_bits) : 1;
     g.partial = static_cast<int32_t *>(workspace);
     if (g.splits > 1 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u))) return workspace ? QLLM_ERR_ALIGN : QLLM_ERR_WORKSPACE;
+    // the FP6 matrix-core path: 4-bit codes, more than 32 tokens, K not split, the weight's tiles at hand and room
+    // for the activations' in the workspace
+    if (a_bits == 4 && wb == 4 && w->tiles6 && N > 32 && g.splits == 1 && workspace && 225 * w->K < (1 << 24) &&
+        workspace_bytes >= qllm_tiles6_bytes(N, w->K)) {
+        if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (reinterpret_cast<uintptr_t>(w->tiles6) & 15u)) return QLLM_ERR_ALIGN;
+        g.a_tiles = static_cast<const uint8_t *>(workspace);
+        g.w_tiles = w->tiles6;
+    }
     g.small_zero = small_zero_bound(w->K, a_bits, wb);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (a_bits == 4) return launch<4, 4>(g, y_dtype, stream);
@@ -976,13 +1230,49 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     return launch<8, 4>(g, y_dtype, stream);
 }
 
-extern "C" int64_t qllm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+extern "C" int64_t qllm_tiles6_bytes(int64_t rows, int64_t K)
 {
-    const int64_t gw = qllm_gemm_workspace_bytes(N, K, O, a_bits);
+    if (rows < 0 || K <= 0) return QLLM_ERR_SHAPE;
+    const int64_t Kpad = (K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD;
+    return (rows + 15) / 16 * (Kpad / T6_KT) * T6_BLOCK;
+}
+
+extern "C" int32_t qllm_pack_tiles6(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *tiles, void *hip_stream)
+{
+    if (!codes || !tiles) return QLLM_ERR_NULL;
+    if (rows < 0 || rows > INT32_MAX || K <= 0 || K > (1 << 24)) return QLLM_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(codes) & 15u) || (reinterpret_cast<uintptr_t>(tiles) & 15u)) return QLLM_ERR_ALIGN;
+    if (rows == 0) return QLLM_OK;
+    const int64_t Kpad = (K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD;
+    return launch_tiles6(codes, qllm_packed_row_bytes(K, 4), rows, Kpad, tiles, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+namespace {
+
+// What the layer needs at least (quantized activations + what the GEMM needs whatever path it takes), and the
+// room that lets the GEMM take its FP6 path when the weight comes with tiles.
+int64_t layer_workspace_floor(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    const int64_t gw = qllm_gemm_workspace_floor_bytes(N, K, O, a_bits);
     if (gw < 0) return gw;
     const int64_t rb = qllm_packed_row_bytes(K, a_bits);
     auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
     return up(N * rb) + 3 * up(N * 4) + up(gw);
+}
+
+} // namespace
+
+extern "C" int64_t qllm_workspace_floor_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    return layer_workspace_floor(N, K, O, a_bits);
+}
+
+extern "C" int64_t qllm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
+{
+    const int64_t floor_bytes = layer_workspace_floor(N, K, O, a_bits);
+    if (floor_bytes < 0) return floor_bytes;
+    auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
+    return floor_bytes - up(qllm_gemm_workspace_floor_bytes(N, K, O, a_bits)) + up(qllm_gemm_workspace_bytes(N, K, O, a_bits));
 }
 
 extern "C" int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64_t N, int64_t C, int64_t ldx,
@@ -994,7 +1284,7 @@ extern "C" int32_t qllm_reassembled_linear(const void *x, int32_t x_dtype, int64
     if (!map || !w) return QLLM_ERR_NULL;
     if (w->K != map->C_out) return QLLM_ERR_SHAPE;
     if (N < 0) return QLLM_ERR_SHAPE;
-    const int64_t need = qllm_workspace_bytes(N, map->C_out, w->O, a_bits);
+    const int64_t need = layer_workspace_floor(N, map->C_out, w->O, a_bits); // more lets the GEMM take its FP6 path
     if (need < 0) return (int32_t)need;
     if (N == 0) return QLLM_OK; // nothing to do, whatever the workspace
     if (!workspace || workspace_bytes < need) return QLLM_ERR_WORKSPACE;
@@ -1064,7 +1354,7 @@ extern "C" int32_t qllm_reassembled_linear_static(const void *x, int32_t x_dtype
     if (!map || !w) return QLLM_ERR_NULL;
     if (w->K != map->C_out) return QLLM_ERR_SHAPE;
     if (N < 0) return QLLM_ERR_SHAPE;
-    const int64_t need = qllm_workspace_bytes(N, map->C_out, w->O, a_bits);
+    const int64_t need = layer_workspace_floor(N, map->C_out, w->O, a_bits);
     if (need < 0) return (int32_t)need;
     if (need > (int64_t)QLLM_STATIC_WORKSPACE_BYTES) return QLLM_ERR_WORKSPACE; // too large a batch for the built-in workspace
     if (N == 0) return QLLM_OK;

@@ -277,7 +277,9 @@ def random_gemm_case(rng, N, K, O, a_bits, w_bits):
     return a, w, ax, aw, bx, bw
 
 
-def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True):
+def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True, tiles6=True):
+    """tiles6 (4-bit weights only): give the weight its FP6-path copy; the workspace has room for that path either way,
+    so False is what sends a 4-bit shape down the int8 path."""
     import torch
     N, K = a.shape
     O = w.shape[0]
@@ -286,10 +288,11 @@ def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True):
     qa.scale.copy_(torch.from_numpy(ax))
     qa.zero.copy_(torch.from_numpy(bx))
     qa.rowsum.copy_(torch.from_numpy(a.astype(np.int64).sum(1).astype(np.int32)))
-    dw = b.DeviceWeight(b.qllm_pack_codes_host(w, w_bits), aw, bw, w.astype(np.int64).sum(1).astype(np.int32), K, w_bits)
+    dw = b.DeviceWeight(b.qllm_pack_codes_host(w, w_bits), aw, bw, w.astype(np.int64).sum(1).astype(np.int32), K, w_bits,
+                        tiles6=tiles6)
     y = torch.full((N, O), float("nan"), dtype=torch.float32 if y_dtype == "f32" else torch.bfloat16, device="cuda")
     acc = torch.full((N, O), -1, dtype=torch.int32, device="cuda") if dump else None
-    ws_bytes = b.qllm_gemm_workspace_bytes(N, K, O, a_bits)     # non-zero where K is split over workgroups
+    ws_bytes = b.qllm_gemm_workspace_bytes(N, K, O, a_bits)     # partial sums where K is split, else room for the FP6 path
     ws = torch.full((ws_bytes,), 0xCD, dtype=torch.uint8, device="cuda") if ws_bytes else None
     b.qllm_int_gemm(qa, dw, y, acc, ws)
     torch.cuda.synchronize()
@@ -319,11 +322,49 @@ def check_y(oracle, y, ref_f32, y_dtype):
 def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
     rng = np.random.default_rng(N * 1000 + K + O + a_bits)
     a, w, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, a_bits, w_bits)
-    y, acc = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype)
     ref_acc = oracle.int_gemm(a, w)
-    assert np.array_equal(acc.cpu().numpy(), ref_acc)
     ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
-    check_y(oracle, y, ref_y, y_dtype)
+    for tiles6 in ((True, False) if a_bits == 4 and w_bits == 4 and N > 32 else (True,)):   # both matrix-core paths
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, tiles6=tiles6)
+        assert np.array_equal(acc.cpu().numpy(), ref_acc), tiles6
+        check_y(oracle, y, ref_y, y_dtype)
+
+
+def decode_tiles6(tiles, rows, K):
+    """The documented layout of qllm_pack_tiles6, read back: [rows rounded up to 16, padded K] codes, and whether the two
+    spare bits of every 6-bit field are clear."""
+    n_kt = -(-K // 256) * 2
+    nb = -(-rows // 16)
+    t = tiles.reshape(nb, n_kt, 1536)
+    out = np.zeros((nb * 16, n_kt * 128), np.uint8)
+    clean = True
+    for l in range(64):
+        r, q = l % 16, l // 16
+        number = np.concatenate([t[:, :, 16 * l:16 * l + 16], t[:, :, 1024 + 8 * l:1024 + 8 * l + 8]], axis=2)   # 24 bytes
+        bits = np.unpackbits(number, axis=2, bitorder="little").reshape(nb, n_kt, 32, 6)
+        clean = clean and not bits[..., 4:].any()
+        vals = (bits[..., :4] * np.array([1, 2, 4, 8], np.uint8)).sum(3).astype(np.uint8)          # [nb, n_kt, 32]
+        for kt in range(n_kt):
+            out[r::16, 128 * kt + 32 * q:128 * kt + 32 * q + 32] = vals[:, kt, :]
+    return out, clean
+
+
+@pytest.mark.parametrize("rows,K", [(1, 1), (16, 128), (37, 700), (300, 5000)])
+def test_tiles6_layout(b, rows, K):
+    """qllm_pack_tiles6 against its documented layout: every code where the header says, zero codes in the padding
+    (rows up to a multiple of 16, K up to the padded row length), spare bits clear."""
+    import torch
+    rng = np.random.default_rng(rows * 7 + K)
+    codes = rng.integers(0, 16, (rows, K), dtype=np.uint8)
+    packed = torch.from_numpy(b.qllm_pack_codes_host(codes, 4)).cuda()
+    tiles = torch.full((b.qllm_tiles6_bytes(rows, K),), 0xEE, dtype=torch.uint8, device="cuda")
+    b.qllm_pack_tiles6(packed, rows, K, tiles)
+    torch.cuda.synchronize()
+    got, clean = decode_tiles6(tiles.cpu().numpy(), rows, K)
+    assert clean
+    want = np.zeros_like(got)
+    want[:rows, :K] = codes
+    assert np.array_equal(got, want)
 
 
 @pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
@@ -333,11 +374,12 @@ def test_gemm_large_tiles_ragged(oracle, b, y_dtype):
     N, K, O = 2049, 256, 5500
     rng = np.random.default_rng(N + O)
     a, w, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, 4, 4)
-    y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 4, 4, y_dtype)
     ref_acc = oracle.int_gemm(a, w)
-    assert np.array_equal(acc.cpu().numpy(), ref_acc)
     ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
-    check_y(oracle, y, ref_y, y_dtype)
+    for tiles6 in (True, False):                                    # FP6 and int8 matrix-core paths
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 4, 4, y_dtype, tiles6=tiles6)
+        assert np.array_equal(acc.cpu().numpy(), ref_acc), tiles6
+        check_y(oracle, y, ref_y, y_dtype)
 
 
 def test_gemm_extreme_codes(oracle, b):
@@ -349,6 +391,28 @@ def test_gemm_extreme_codes(oracle, b):
         bx, bw = np.zeros(17, np.int32), np.zeros(33, np.int32)
         y, acc = run_gemm(b, a, w, ax, aw, bx, bw, bits, bits, "f32")
         assert np.all(acc.cpu().numpy() == (2 ** bits - 1) ** 2 * K)
+
+
+@pytest.mark.parametrize("order", ["all", "small_last", "small_first"])
+def test_gemm_fp6_path_exact_at_the_largest_sums(oracle, b, order):
+    """The FP6 matrix-core path keeps the sum in fp32: exact as long as every partial sum is a multiple of 1/64 below
+    2^24 / 64.  The longest K the layer allows with every code at 15 is the largest sum there is (7.4e6 of 1.7e7);
+    with 0/1 codes in the last (first) 128 places, terms of 1/64 meet a sum of 1e5 (a sum of 1e5 meets sums of 1/64)."""
+    N, K, O = 300, 32768, 200
+    rng = np.random.default_rng(5)
+    a = np.full((N, K), 15, np.uint8)
+    w = np.full((O, K), 15, np.uint8)
+    if order != "all":
+        sl = slice(K - 128, K) if order == "small_last" else slice(0, 128)
+        a[:, sl] = rng.integers(0, 2, (N, 128), dtype=np.uint8)
+        w[:, sl] = 1
+    ax, aw = np.ones(N, np.float32), np.ones(O, np.float32)
+    bx, bw = np.zeros(N, np.int32), np.zeros(O, np.int32)
+    ref = oracle.int_gemm(a, w)
+    for tiles6 in (True, False):
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 4, 4, "f32", tiles6=tiles6)
+        assert np.array_equal(acc.cpu().numpy(), ref), tiles6
+        assert np.array_equal(y.cpu().numpy(), ref.astype(np.float32)), tiles6
 
 
 @pytest.mark.parametrize("N", [17, 300])
@@ -379,18 +443,21 @@ def test_gemm_full_configs_sampled(oracle, b, name):
     w = wl.WORKLOADS[name]
     rng = np.random.default_rng(w.seed)
     a, wc, ax, aw, bx, bw = random_gemm_case(rng, w.N, w.C, w.O, w.a_bits, w.w_bits)
-    y, acc = run_gemm(b, a, wc, ax, aw, bx, bw, w.a_bits, w.w_bits, "bf16")
-    acc = acc.cpu().numpy()
     cols = np.sort(rng.choice(w.O, 48, replace=False))
     rows = np.sort(rng.choice(w.N, min(24, w.N), replace=False))
-    assert np.array_equal(acc[:, cols], oracle.int_gemm(a, wc[cols]))
-    assert np.array_equal(acc[rows], oracle.int_gemm(a[rows], wc))
-    # a property that holds at any size: sums over the output axis, against numpy int64
-    assert np.array_equal(acc.astype(np.int64).sum(1), a.astype(np.int64) @ wc.astype(np.int64).sum(0))
+    ref_cols, ref_rows_acc = oracle.int_gemm(a, wc[cols]), oracle.int_gemm(a[rows], wc)
+    row_sums = a.astype(np.int64) @ wc.astype(np.int64).sum(0)
     rs, cs = a.astype(np.int64).sum(1), wc.astype(np.int64).sum(1)
-    ref_rows = oracle.epilogue(acc[rows], w.C, ax[rows], bx[rows], rs[rows], aw, bw, cs)
-    got_rows = oracle.widen_bf16(y[__import__("torch").from_numpy(rows).cuda()].view(__import__("torch").int16).cpu().numpy().view(np.uint16))
-    assert rel_err(got_rows, ref_rows).max() <= TOL["bf16"]
+    for tiles6 in ((True, False) if w.a_bits == 4 and w.w_bits == 4 else (True,)):   # FP6 and int8 matrix-core paths
+        y, acc = run_gemm(b, a, wc, ax, aw, bx, bw, w.a_bits, w.w_bits, "bf16", tiles6=tiles6)
+        acc = acc.cpu().numpy()
+        assert np.array_equal(acc[:, cols], ref_cols)
+        assert np.array_equal(acc[rows], ref_rows_acc)
+        # a property that holds at any size: sums over the output axis, against numpy int64
+        assert np.array_equal(acc.astype(np.int64).sum(1), row_sums)
+        ref_rows = oracle.epilogue(acc[rows], w.C, ax[rows], bx[rows], rs[rows], aw, bw, cs)
+        got_rows = oracle.widen_bf16(y[__import__("torch").from_numpy(rows).cuda()].view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+        assert rel_err(got_rows, ref_rows).max() <= TOL["bf16"]
 
 
 # ---------------------------------------------------------------- the whole layer (a1..a6)
