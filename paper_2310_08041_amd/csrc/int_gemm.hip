@@ -685,6 +685,10 @@ __device__ __forceinline__ v8i operand6(const Frag6 &f) { return v8i{f.x[0], f.x
 __device__ __forceinline__ Frag6 read6(const uint8_t *block, int lane)
 {
     Frag6 f;
+#ifdef T6_NO_READS // timing experiment only
+    asm volatile("" : "=v"(f.x), "=v"(f.y) : "v"(block), "v"(lane)); // whatever the registers hold
+    return f;
+#endif
     f.x = *reinterpret_cast<const v4i *>(block + 16 * lane);
     f.y = *reinterpret_cast<const v2i *>(block + T6_X + 8 * lane);
     return f;
@@ -715,16 +719,21 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
         src_off[t] = (uint32_t)rb * (uint32_t)all_kt * T6_BLOCK + within;
     }
     static_assert((TM / 16 * T6_BLOCK) % 1024 == 0, "token side = whole loads");
-    auto fetch = [&](int kt, int stage) { // K-tile kt (clamped to the last one) -> that stage of the ring
+    // load t of K-tile kt (clamped to the last one) -> that stage of the ring
+    auto fetch_one = [&](int kt, int stage, int t) {
+#ifdef T6_FETCH_MASK
+        if (!((T6_FETCH_MASK >> t) & 1) && kt > 2) return; // timing experiment only: some of the loads left out
+#endif
         const int ktc = min(kt, all_kt - 1);
-        uint8_t *dst = lds + stage * STAGE + wave * NLOAD * 1024;
+        const bool token = (wave * NLOAD + t) * 1024 < TM / 16 * T6_BLOCK;
+        const uint8_t *base = (token ? g.a_tiles : g.w_tiles) + (int64_t)ktc * T6_BLOCK;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + src_off[t]),
+                                         (__attribute__((address_space(3))) void *)(lds + stage * STAGE + (wave * NLOAD + t) * 1024), 16, 0,
+                                         0);
+    };
+    auto fetch = [&](int kt, int stage) {
 #pragma unroll
-        for (int t = 0; t < NLOAD; ++t) {
-            const bool token = (wave * NLOAD + t) * 1024 < TM / 16 * T6_BLOCK;
-            const uint8_t *base = (token ? g.a_tiles : g.w_tiles) + (int64_t)ktc * T6_BLOCK;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + src_off[t]),
-                                             (__attribute__((address_space(3))) void *)(dst + t * 1024), 16, 0, 0);
-        }
+        for (int t = 0; t < NLOAD; ++t) fetch_one(kt, stage, t);
     };
     constexpr int WAIT_LANDED = NLOAD | (7 << 4) | (15 << 8);       // s_waitcnt vmcnt(NLOAD): all but the newest fetch
     constexpr int WAIT_LANDED_LGKM0 = NLOAD | (7 << 4) | (0 << 8);  // ... and lgkmcnt(0)
@@ -740,8 +749,12 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
     __builtin_amdgcn_s_waitcnt(WAIT_LANDED);
     __syncthreads();
 
-    constexpr int RING = 4, AHEAD = 2;
-    static_assert(MI % RING == 0 && AHEAD < RING && AHEAD < MI, "group plan");
+    // Token-side operands: all MI blocks of a K-tile have registers of their own; the large tile requests them two
+    // per group in the first MI / 2 groups of the iteration, so that the wait for "own reads done" before the
+    // barrier finds them long back.
+    constexpr int RING = MI, AHEAD = 2, PER_STEP = MI == 8 ? 2 : 1;
+    // block b is requested in step b / PER_STEP, after the group of the K-tile before that used its registers (step b + AHEAD - MI)
+    static_assert(MI % PER_STEP == 0 && (MI - 1) / PER_STEP > AHEAD - 1 && (MI - AHEAD) / PER_STEP > 0, "group plan");
     Frag6 ar[RING], wr[2][NJ];
 #pragma unroll
     for (int k = 0; k < RING; ++k) ar[k] = Frag6{v4i{0, 0, 0, 0}, v2i{0, 0}};
@@ -755,7 +768,6 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
     auto k_tile = [&](auto parity, int kt) {
         constexpr int P = decltype(parity)::value;
         const uint8_t *cur = lds + stage * STAGE;
-        fetch(kt + 2, fetch_stage); // into the stage whose last reader passed the previous barrier
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             wr[P][j] = read6(cur + (w_blk0 + j) * T6_BLOCK, lane);
@@ -765,18 +777,29 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
         for (int u = 0; u < MI; ++u) {
             const bool old = u < AHEAD;
             const int i = old ? MI - AHEAD + u : u - AHEAD;
-            ar[u % RING] = read6(cur + (a_blk0 + u) * T6_BLOCK, lane); // for the group AHEAD steps on
-            __builtin_amdgcn_sched_barrier(0);
+            // The K-tile two ahead, into the stage whose last reader passed the previous barrier: one load per group,
+            // not all at once (the eight waves' loads of a K-tile keep the CU's address unit busy for three quarters of
+            // a K-tile's matrix-core time; a wave whose load is not accepted yet issues nothing else either).
+            if (u < NLOAD) fetch_one(kt + 2, fetch_stage, u);
+            if (PER_STEP * u < MI) {
+#pragma unroll
+                for (int h = 0; h < PER_STEP; ++h) {
+                    ar[PER_STEP * u + h] = read6(cur + (a_blk0 + PER_STEP * u + h) * T6_BLOCK, lane);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[old ? 1 - P : P][j]), operand6(ar[i % RING]),
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[old ? 1 - P : P][j]), operand6(ar[i]),
                                                                              acc[i][j], 2, 2, 0, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         // the next K-tile has landed (this wave's share; the barrier adds the others'), own reads done
         __builtin_amdgcn_s_waitcnt(WAIT_LANDED_LGKM0);
         asm volatile("" ::: "memory");
+#ifndef T6_NO_BARRIER // timing experiment only, together with T6_FETCH_MASK=0: nothing is written to LDS then
         __builtin_amdgcn_s_barrier();
+#endif
         asm volatile("" ::: "memory");
         fetch_stage = stage;
         stage = stage == T6_STAGES - 1 ? 0 : stage + 1;
@@ -796,7 +819,7 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
         for (int i = MI - AHEAD; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[P][j]), operand6(ar[i % RING]), acc[i][j], 2, 2,
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[P][j]), operand6(ar[i]), acc[i][j], 2, 2,
                                                                              0, 0, 0, 0);
     };
     if (all_kt & 1) last_groups(std::integral_constant<int, 0>{});
