@@ -4,13 +4,17 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 
 A "step" is one pass of the whole hot path -- qllm_reassembled_linear: fused norm + channel
-disassembly + channel assembly + per-token quantization, then the int8 matrix-core GEMM with its
+disassembly + channel assembly + per-token quantization, then the matrix-core GEMM on the codes with its
 dequantising epilogue -- over one batch of synthetic activations that is already resident in HBM.
 The default workload is the LLaMA-2-70B down-projection shape (N=2048, C=28672, O=8192, W4A4).
+With 4-bit codes on both sides and more than 32 tokens the GEMM runs on the FP6 matrix cores (the codes
+are exact FP6 numbers, the fp32 sums exact integers / 64: same accumulators bit for bit, `config.gemm_path`);
+--int8 keeps it on the int8 matrix cores.
 
 Prints one JSON line.  `value` is 2*N*K*O integer operations per second of the whole step;
-`roofline` prices the dominant kernel (the GEMM) against the dense int8 matrix-core peak (against HBM
-bandwidth for decode-sized batches, where the weights stream once), and `roofline_fused` the fused kernel
+`roofline` prices the dominant kernel (the GEMM) against the dense matrix-core peak of the operations it
+issues (FP6 10.1 POP/s, int8 5.0 POP/s; against HBM bandwidth for decode-sized batches, where the weights
+stream once), and `roofline_fused` the fused kernel
 against HBM bandwidth; both use the kernel's own average duration, taken with HIP events on the launch
 stream in a second, instrumented pass: the same K launches of that kernel back to back with one event pair
 around them (`avg_launch_us`; an event pair around a single launch also spans the few microseconds before the
@@ -36,6 +40,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix-core peak, published
+FP6_PEAK_TOPS = 10100.0      # MI355X dense FP6 / FP4 matrix-core peak, published
 MIN_WARMUP_MS = 100.0        # GPU time spent on the step before anything is timed, whatever --warmup says
 N_ROTATE = 4                 # distinct activation / output buffers cycled through, so that no step
 #                              finds its inputs in the 256 MB last-level cache
@@ -139,6 +144,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)   # ~50 ms: the clocks settle over the first tens of ms
     ap.add_argument("--workload", default="llama70b_down")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--int8", action="store_true",
+                    help="4-bit codes: keep the GEMM on the int8 matrix cores (no FP6-path copy of the weight)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -195,7 +202,9 @@ def main():
     W = wl.draw_weight(w)
     q = b.qllm_quantize_weight_host(W, cal["row_ptr"], cal["src"], w.w_bits)
     del W
-    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, w.w_bits)
+    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, w.w_bits, tiles6=not args.int8)
+    # 4-bit codes, more than 32 tokens, K not split over workgroups: the GEMM runs on the FP6 matrix cores
+    fp6_path = dw.tiles6 is not None and w.N > 32 and b.qllm_gemm_workspace_floor_bytes(w.N, K, w.O, w.a_bits) == 0
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, N_ROTATE)]   # same rows, other addresses
     ys = [torch.empty((w.N, w.O), dtype=torch.bfloat16, device=dev) for _ in range(N_ROTATE)]
     ws = torch.empty(b.qllm_workspace_bytes(w.N, K, w.O, w.a_bits), dtype=torch.uint8, device=dev)
@@ -282,12 +291,27 @@ def main():
     bev[3].record()
     torch.cuda.synchronize()
     t_fused, t_gemm = bev[0].elapsed_time(bev[1]) * 1e-3 / args.steps, bev[2].elapsed_time(bev[3]) * 1e-3 / args.steps
+    t_pack = 0.0
+    if fp6_path:
+        # the GEMM call is two kernels on this path: the activations re-laid for the FP6 matrix cores, then the
+        # product; the first one alone, back to back in the same way, gives the split
+        tiles = torch.empty(b.qllm_tiles6_bytes(w.N, K), dtype=torch.uint8, device=dev)
+        for i in range(N_ROTATE):
+            b.qllm_pack_tiles6(qas[i].codes, w.N, K, tiles)
+        bev[0].record()
+        for i in range(args.steps):
+            b.qllm_pack_tiles6(qas[i % N_ROTATE].codes, w.N, K, tiles)
+        bev[1].record()
+        torch.cuda.synchronize()
+        t_pack = bev[0].elapsed_time(bev[1]) * 1e-3 / args.steps
+        del tiles
+    t_gemm_kernel = t_gemm - t_pack
 
     ops = 2.0 * w.N * K * w.O
     x_bytes = w.N * w.C * x0.element_size()
     code_bytes = w.N * K * w.a_bits // 8
     fused_bytes = x_bytes + code_bytes + 12 * w.N            # read X once, write codes + (alpha, beta, rowsum)
-    gemm_tops = ops / t_gemm / 1e12
+    gemm_tops = ops / t_gemm_kernel / 1e12
     fused_gbs = fused_bytes / t_fused / 1e9
 
     # ---- what the machine delivers on the two resources, with none of the path's work in the way
@@ -305,6 +329,16 @@ def main():
     pe[1].record()
     torch.cuda.synchronize()
     mfma_probe_tops = 10 * cus * 8 * probe_iters * 32 * 2.0 * 16 * 16 * 64 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+    if fp6_path:
+        fsink = torch.zeros(1, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            b.qllm_probe_mfma_fp6(cus, probe_iters, fsink)
+        pe[0].record()
+        for _ in range(10):
+            b.qllm_probe_mfma_fp6(cus, probe_iters, fsink)
+        pe[1].record()
+        torch.cuda.synchronize()
+        fp6_probe_tops = 10 * cus * 8 * probe_iters * 32 * 2.0 * 16 * 16 * 128 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
     sbytes = 1 << 30
     ssrc = torch.empty(sbytes, dtype=torch.uint8, device=dev).fill_(3)
     sdst = torch.empty(sbytes // 4, dtype=torch.uint8, device=dev)
@@ -318,9 +352,13 @@ def main():
     stream_probe_gbs = 10 * (sbytes + sbytes // 4) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
     del ssrc, sdst
 
-    gemm_kernel = ("int_gemm_w4a4_kernel<bf16>" if (w.a_bits, w.w_bits) == (4, 4) else
-                   "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits)) if w.N > 128 else \
-        "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
+    if fp6_path:
+        gemm_kernel = "gemm_w4a4_fp6_kernel<bf16>"
+    elif w.N > 128:
+        gemm_kernel = ("int_gemm_w4a4_kernel<bf16>" if (w.a_bits, w.w_bits) == (4, 4) else
+                       "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits))
+    else:
+        gemm_kernel = "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
     traffic = read_traffic(w.name)
     if w.N <= 32:
         # decode-sized batch: the GEMM streams the packed weights once and does little arithmetic per byte
@@ -332,6 +370,18 @@ def main():
                     "algorithmic_bytes": gemm_bytes, "traffic": traffic.get("int_gemm"), "int8_TOPs": gemm_tops,
                     "probe": {"what": "plain stream, 16 bytes read : 4 written, 1.25 GB per pass",
                               "achieved": stream_probe_gbs, "frac_of_probe": gemm_gbs / stream_probe_gbs}}
+    elif fp6_path:
+        # the operations are those of Eq. (1) on the codes (2 N K O), done by FP6 matrix-core operations: priced
+        # against the FP6 peak
+        roofline = {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
+                    "peak": FP6_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / FP6_PEAK_TOPS,
+                    "avg_launch_us": t_gemm_kernel * 1e6, "single_launch_event_us": spread(gemm_us),
+                    "note": "single_launch_event_us spans both kernels of the GEMM call; avg_launch_us is the product kernel alone",
+                    "tiles6_kernel_us": t_pack * 1e6, "gemm_call_us": t_gemm * 1e6, "traffic": traffic.get("gemm_fp6"),
+                    "frac_of_int8_peak": gemm_tops / INT8_PEAK_TOPS,
+                    "probe": {"what": "loop of FP6 matrix-core operations on register operands that hold 4-bit codes, all CUs",
+                              "achieved": fp6_probe_tops, "frac_of_probe": gemm_tops / fp6_probe_tops,
+                              "int8_loop": mfma_probe_tops}}
     else:
         roofline = {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
@@ -344,7 +394,9 @@ def main():
         "unit": "TOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 (4-bit codes on the int8 matrix cores, int32 accumulate); fp32 norm/quantizer",
+        "dtype": ("fp6 E2M3 (4-bit codes as FP6 numbers on the FP6 matrix cores, fp32 sums that are exact integers / 64); "
+                  "fp32 norm/quantizer" if fp6_path else
+                  "int8 (4-bit codes on the int8 matrix cores, int32 accumulate); fp32 norm/quantizer"),
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "C": w.C, "C_hat": K, "O": w.O, "a_bits": w.a_bits,
                    "w_bits": w.w_bits, "in_dtype": w.in_dtype, "out_dtype": "bf16", "norm": w.norm,
@@ -353,7 +405,7 @@ def main():
                                          b.FUSED_LISTS_STREAMED: "planned, lists streamed"}[form],
                    "extra_channels": int(cal["nnz"] - w.C),
                    "merged_pairs": int(cal["src_idx"].size), "T_max": int(cal["num_split"].max()),
-                   "rotating_buffers": N_ROTATE, "launch": "hip graph replay" if args.graph else "eager",
+                   "gemm_path": "fp6 matrix cores" if fp6_path else "int8 matrix cores", "rotating_buffers": N_ROTATE, "launch": "hip graph replay" if args.graph else "eager",
                    "warmup_done": {"steps": warm_steps, "gpu_ms": warm_ms}},
         "fused_GBps": fused_gbs,
         "roofline": roofline,

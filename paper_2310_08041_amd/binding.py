@@ -85,6 +85,7 @@ _sigs = {
     "qllm_sq_error_workspace_bytes": (_i64, [_i64]),
     "qllm_sq_error": (_i32, [_vp, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp]),
     "qllm_probe_mfma": (_i32, [_i32, _i32, _vp, _vp]),
+    "qllm_probe_mfma_fp6": (_i32, [_i32, _i32, _vp, _vp]),
     "qllm_probe_stream": (_i32, [_vp, _vp, _i64, _i32, _vp]),
 }
 EXPORTS = tuple(_sigs)
@@ -589,6 +590,10 @@ def qllm_sq_error(got, ref, result, workspace, stream=None):
 
 def qllm_probe_mfma(workgroups, iters, sink, stream=None):
     _chk(_lib.qllm_probe_mfma(int(workgroups), int(iters), _dp(sink), _stream(stream)), "qllm_probe_mfma")
+
+
+def qllm_probe_mfma_fp6(workgroups, iters, sink, stream=None):
+    _chk(_lib.qllm_probe_mfma_fp6(int(workgroups), int(iters), _dp(sink), _stream(stream)), "qllm_probe_mfma_fp6")
 
 
 def qllm_probe_stream(src, dst, workgroups, stream=None):

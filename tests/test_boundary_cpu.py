@@ -51,17 +51,27 @@ def test_packed_row_bytes_and_workspace():
         b.qllm_packed_row_bytes(0, 4)
     ws = b.qllm_workspace_bytes(2048, 28672, 8192, 4)
     assert ws >= 2048 * 14336 + 3 * 2048 * 4 and ws % 256 == 0
-    # the GEMM needs scratch only where it splits K over workgroups: 4-bit codes, few tiles, a long K
-    assert b.qllm_gemm_workspace_bytes(2048, 28672, 8192, 4) == 0 and b.qllm_gemm_workspace_bytes(16, 8192, 8192, 4) == 0
-    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 4) == 4 * 128 * 8192 * 4
-    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 6) == 0 and b.qllm_gemm_workspace_bytes(128, 512, 8192, 4) == 0
+    # the GEMM must have scratch only where it splits K over workgroups: 4-bit codes, few tiles, a long K
+    floor = b.qllm_gemm_workspace_floor_bytes
+    assert floor(2048, 28672, 8192, 4) == 0 and floor(16, 8192, 8192, 4) == 0
+    assert floor(128, 8192, 8192, 4) == 4 * 128 * 8192 * 4
+    assert floor(128, 8192, 8192, 6) == 0 and floor(128, 512, 8192, 4) == 0
     assert b.qllm_workspace_bytes(128, 8192, 8192, 4) >= 128 * 4096 + 4 * 128 * 8192 * 4
+    # what serves every path: the same where K is split; else, for 4-bit codes and more than 32 tokens, room for the
+    # activations in the FP6 path's layout (1536 bytes per 16 rows and 128 codes of the padded row)
+    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 4) == floor(128, 8192, 8192, 4)
+    assert b.qllm_tiles6_bytes(2048, 28672) == 2048 // 16 * (28672 // 128) * 1536
+    assert b.qllm_tiles6_bytes(17, 100) == 2 * 2 * 1536                     # rows up to 32, K up to 256
+    assert b.qllm_gemm_workspace_bytes(2048, 28672, 8192, 4) == b.qllm_tiles6_bytes(2048, 28672)
+    assert b.qllm_gemm_workspace_bytes(16, 8192, 8192, 4) == 0 and b.qllm_gemm_workspace_bytes(2048, 8192, 8192, 6) == 0
+    assert b.qllm_workspace_bytes(2048, 28672, 8192, 4) == b.qllm_workspace_floor_bytes(2048, 28672, 8192, 4) + b.qllm_tiles6_bytes(2048, 28672)
+    assert b.qllm_workspace_floor_bytes(2048, 28672, 8192, 4) == 2048 * 14336 + 3 * 2048 * 4
 
 
 def _structs():
     m = b._Map(64, 64, 64, 0x1000, 0x1000, 0x1000, None)
     q = b._QAct(0x1000, 0x1000, 0x1000, 0x1000)
-    w = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000)
+    w = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000, None)
     return m, q, w
 
 
@@ -124,6 +134,22 @@ def test_gemm_entry_point_rejects_bad_arguments_before_launching():
     assert call(wt=b._Weight(32, 64, 4, 0x1004, 0x1000, 0x1000, 0x1000)) == -6
     assert call(qa=b._QAct(0x1000, 0x1000, None, 0x1000)) == -1
     assert call(N=0) == 0
+    # a weight that comes with tiles for the FP6 path, more than 32 tokens, room in the workspace: the tiles' and the
+    # workspace's alignment are checked before anything is launched
+    big = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000, 0x5008)
+    assert f(C.byref(q), 4, 64, C.byref(big), Y, b.F32, 32, None, 0x4000, 1 << 20, None) == -6
+    good = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000, 0x5000)
+    assert f(C.byref(q), 4, 64, C.byref(good), Y, b.F32, 32, None, 0x4008, 1 << 20, None) == -6
+
+
+def test_tiles6_entry_points_reject_bad_arguments_before_launching():
+    lib = b.raw()
+    f = lib.qllm_pack_tiles6
+    assert f(None, 16, 128, 0x2000, None) == -1 and f(0x1000, 16, 128, None, None) == -1
+    assert f(0x1000, -1, 128, 0x2000, None) == -2 and f(0x1000, 16, 0, 0x2000, None) == -2
+    assert f(0x1008, 16, 128, 0x2000, None) == -6 and f(0x1000, 16, 128, 0x2004, None) == -6
+    assert f(0x1000, 0, 128, 0x2000, None) == 0
+    assert lib.qllm_tiles6_bytes(-1, 128) == -2 and lib.qllm_tiles6_bytes(16, 0) == -2
 
 
 def test_linear_entry_point_rejects_bad_arguments_before_launching():
