@@ -685,10 +685,6 @@ __device__ __forceinline__ v8i operand6(const Frag6 &f) { return v8i{f.x[0], f.x
 __device__ __forceinline__ Frag6 read6(const uint8_t *block, int lane)
 {
     Frag6 f;
-#ifdef T6_NO_READS // timing experiment only
-    asm volatile("" : "=v"(f.x), "=v"(f.y) : "v"(block), "v"(lane)); // whatever the registers hold
-    return f;
-#endif
     f.x = *reinterpret_cast<const v4i *>(block + 16 * lane);
     f.y = *reinterpret_cast<const v2i *>(block + T6_X + 8 * lane);
     return f;
@@ -721,9 +717,6 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
     static_assert((TM / 16 * T6_BLOCK) % 1024 == 0, "token side = whole loads");
     // load t of K-tile kt (clamped to the last one) -> that stage of the ring
     auto fetch_one = [&](int kt, int stage, int t) {
-#ifdef T6_FETCH_MASK
-        if (!((T6_FETCH_MASK >> t) & 1) && kt > 2) return; // timing experiment only: some of the loads left out
-#endif
         const int ktc = min(kt, all_kt - 1);
         const bool token = (wave * NLOAD + t) * 1024 < TM / 16 * T6_BLOCK;
         const uint8_t *base = (token ? g.a_tiles : g.w_tiles) + (int64_t)ktc * T6_BLOCK;
@@ -797,9 +790,7 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
         // the next K-tile has landed (this wave's share; the barrier adds the others'), own reads done
         __builtin_amdgcn_s_waitcnt(WAIT_LANDED_LGKM0);
         asm volatile("" ::: "memory");
-#ifndef T6_NO_BARRIER // timing experiment only, together with T6_FETCH_MASK=0: nothing is written to LDS then
         __builtin_amdgcn_s_barrier();
-#endif
         asm volatile("" ::: "memory");
         fetch_stage = stage;
         stage = stage == T6_STAGES - 1 ? 0 : stage + 1;
@@ -1240,7 +1231,8 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     // the FP6 matrix-core path: 4-bit codes, more than 32 tokens, K not split, the weight's tiles at hand and room
     // for the activations' in the workspace
     if (a_bits == 4 && wb == 4 && w->tiles6 && N > 32 && g.splits == 1 && workspace && 225 * w->K < (1 << 24) &&
-        workspace_bytes >= qllm_tiles6_bytes(N, w->K)) {
+        workspace_bytes >= qllm_tiles6_bytes(N, w->K) && qllm_tiles6_bytes(N, w->K) < (1ll << 32) &&
+        qllm_tiles6_bytes(w->O, w->K) < (1ll << 32)) { // the kernel addresses either operand with 32-bit offsets
         if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (reinterpret_cast<uintptr_t>(w->tiles6) & 15u)) return QLLM_ERR_ALIGN;
         g.a_tiles = static_cast<const uint8_t *>(workspace);
         g.w_tiles = w->tiles6;
