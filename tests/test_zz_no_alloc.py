@@ -13,9 +13,11 @@ def test_static_workspace_entry_point_matches_the_workspace_one(oracle):
     import torch
     from paper_2310_08041_amd import binding as b
     assert torch.cuda.is_available(), "this test needs the MI355X"
-    # first a small-batch 4-bit shape whose GEMM splits K over workgroups (partial accumulators in the workspace),
-    # then a smaller decode-sized 6-bit one: stale contents of the shared array must not matter
-    for name, N, C, O, y_dtype in [("llama7b_qkv", 96, 4096, 2048, torch.bfloat16), ("llama70b_q_decode", 16, 2048, 512, torch.float32)]:
+    # first a 4-bit shape whose GEMM takes the FP6 path (the activations re-laid into the workspace), then a small-batch
+    # 4-bit shape whose GEMM splits K over workgroups (partial accumulators in the workspace), then a smaller
+    # decode-sized 6-bit one: stale contents of the shared array must not matter
+    for name, N, C, O, y_dtype in [("llama7b_qkv", 300, 4096, 8192, torch.bfloat16), ("llama7b_qkv", 96, 4096, 2048, torch.bfloat16),
+                                   ("llama70b_q_decode", 16, 2048, 512, torch.float32)]:
         w = wl.WORKLOADS[name]
         c = make_case(oracle, w, N=N, C=C, O=O)
         r = b.qllm_build_map_host(c.absmax, c.theta, c.src_idx, c.dst_idx)
@@ -27,7 +29,10 @@ def test_static_workspace_entry_point_matches_the_workspace_one(oracle):
         need = b.qllm_workspace_bytes(c.N, c.K, c.O, w.a_bits)
         assert 0 < need <= b.STATIC_WORKSPACE_BYTES
         if N == 96:
-            assert b.qllm_gemm_workspace_bytes(c.N, c.K, c.O, w.a_bits) > 0      # partial accumulators live there too
+            assert b.qllm_gemm_workspace_floor_bytes(c.N, c.K, c.O, w.a_bits) > 0      # partial accumulators live there too
+        if N == 300:                                                                    # K not split, room for the tiles
+            assert b.qllm_gemm_workspace_floor_bytes(c.N, c.K, c.O, w.a_bits) == 0 and dw.tiles6 is not None
+            assert need >= b.qllm_workspace_floor_bytes(c.N, c.K, c.O, w.a_bits) + b.qllm_tiles6_bytes(c.N, c.K)
         ws = torch.empty(need, dtype=torch.uint8, device="cuda")
         y_ref = torch.full((c.N, c.O), float("nan"), dtype=y_dtype, device="cuda")
         b.qllm_reassembled_linear(x, c.norm, g, None, c.eps, dm, w.a_bits, dw, y_ref, ws)
