@@ -155,6 +155,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Two floats -> two bfloat16 in one dword, round to nearest even: the hardware's packed conversion
+// (v_cvt_pk_bf16_f32), one instruction where the integer form above takes about ten for the pair.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_rne(float lo, float hi)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+
 // Stores 4 consecutive output features of one token (16 bytes per lane for fp32, 8 for bf16) and,
 // if asked for, the raw accumulators.
 template <typename YT>
@@ -171,8 +180,7 @@ __device__ __forceinline__ void store4(const GemmArgs &g, const float *out, cons
             }
         } else {
             uint16_t *yp = reinterpret_cast<uint16_t *>(g.y) + (int64_t)n * g.ldy + ob;
-            const uint32_t p0 = f32_to_bf16_rne(out[0]) | ((uint32_t)f32_to_bf16_rne(out[1]) << 16);
-            const uint32_t p1 = f32_to_bf16_rne(out[2]) | ((uint32_t)f32_to_bf16_rne(out[3]) << 16);
+            const uint32_t p0 = f32x2_to_bf16x2_rne(out[0], out[1]), p1 = f32x2_to_bf16x2_rne(out[2], out[3]);
             if ((reinterpret_cast<uintptr_t>(yp) & 7u) == 0) {
                 *reinterpret_cast<uint2 *>(yp) = make_uint2(p0, p1);
             } else {
