@@ -212,8 +212,13 @@ __device__ __forceinline__ void store4(const GemmArgs &g, const float *out, cons
 // When both zero-points are small (the usual case: |beta| < g.small_zero, a bound the launcher derives
 // from K and the bit widths) every factor fits 24 bits and every sum 32 bits, and the bracket costs
 // three full-rate multiply-adds; otherwise it is formed in 64-bit arithmetic.
-template <int ABITS, int WBITS, typename YT, int NI, int NJ>
-__device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const v4i (&acc)[NI][NJ], int n_base, int o_base,
+// An accumulator as the integer it stands for: the int8 matrix cores' own, or 64 x the FP6 path's float (exact).
+typedef float v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int32_t acc_int(const v4i &a, int r) { return a[r]; }
+__device__ __forceinline__ int32_t acc_int(const v4f &a, int r) { return (int32_t)(a[r] * 64.0f); }
+
+template <int ABITS, int WBITS, typename YT, int NI, int NJ, typename ACC>
+__device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const ACC (&acc)[NI][NJ], int n_base, int o_base,
                                                  int lane)
 {
     constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
@@ -231,6 +236,56 @@ __device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const v4i (&
             cols_small = cols_small && abs(bw[j][r]) < g.small_zero;
         }
     const int32_t k_off = 16384 * SA * SW * g.Kpad;
+
+    // The usual case, decided once for the wave: the tile lies inside Y, Y's rows are aligned for whole stores, nobody
+    // asked for the raw accumulators, and every zero-point of the tile is small.  Then the tile is straight-line
+    // code: three 24-bit multiply-adds, a conversion and two multiplications per output, one store per four.
+    {
+        const bool inside = n_base + 16 * NI <= g.N && o_base + 16 * NJ <= g.O;
+        const bool aligned = (reinterpret_cast<uintptr_t>(g.y) & (sizeof(YT) == 4 ? 15u : 7u)) == 0 && (g.ldy & 3) == 0;
+        if (inside && aligned && !g.acc_dump) { // wave-uniform so far: the loads below are in bounds
+            int32_t bxs[NI], rss[NI];
+            float axs[NI];
+            bool small = cols_small;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int n = n_base + i * 16 + (lane & 15);
+                bxs[i] = g.bx[n];
+                rss[i] = g.rs[n];
+                axs[i] = g.ax[n];
+                small = small && abs(bxs[i]) < g.small_zero;
+            }
+            if (__all(small)) {
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const int n = n_base + i * 16 + (lane & 15);
+                    const int32_t kbx = g.K * bxs[i];
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        float out[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            int32_t t = acc_int(acc[i][j], r) + 128 * SW * rss[i] + 128 * SA * cs[j][r] - k_off;
+                            t -= __mul24(bxs[i], cs[j][r]);
+                            t -= __mul24(bw[j][r], rss[i]);
+                            t += __mul24(kbx, bw[j][r]);
+                            float v = (float)t;
+                            v = v * axs[i];
+                            v = v * aw[j][r];
+                            out[r] = v;
+                        }
+                        const int64_t at = (int64_t)n * g.ldy + o_base + j * 16 + 4 * (lane >> 4);
+                        if constexpr (sizeof(YT) == 4)
+                            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(g.y) + at) = make_float4(out[0], out[1], out[2], out[3]);
+                        else
+                            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(g.y) + at) =
+                                make_uint2(f32x2_to_bf16x2_rne(out[0], out[1]), f32x2_to_bf16x2_rne(out[2], out[3]));
+                    }
+                }
+                return;
+            }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int n = n_base + i * 16 + (lane & 15);
@@ -246,7 +301,7 @@ __device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const v4i (&
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // the true accumulator fits int32 (checked by the launcher), so wrapping sums are exact
-                raw[r] = acc[i][j][r] + 128 * SW * rs + 128 * SA * cs[j][r] - k_off;
+                raw[r] = acc_int(acc[i][j], r) + 128 * SW * rs + 128 * SA * cs[j][r] - k_off;
                 float v;
                 if (small) {
                     int32_t t = raw[r] - __mul24(bx, cs[j][r]);
@@ -681,7 +736,6 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void int_gemm_w4a4_kerne
 // groups (an iteration starts with the last groups of the K-tile before, zeros the first time), and
 // unrolled by two so that the alternation of the feature-side register sets is static.
 typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int T6_BLOCK = 1536, T6_X = 1024, T6_KT = 128, T6_STAGES = 3;
 
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -824,14 +878,7 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
     if (all_kt & 1) last_groups(std::integral_constant<int, 0>{});
     else last_groups(std::integral_constant<int, 1>{});
 
-    v4i sums[MI][NJ]; // 64 acc: the integer accumulators, exactly
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sums[i][j][e] = (int)(acc[i][j][e] * 64.0f);
-    finish_wave_tile<4, 4, YT, MI, NJ>(g, sums, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane);
+    finish_wave_tile<4, 4, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane); // 64 acc: the integer accumulators, exactly
 }
 
 // 4 nibbles in bits 0..15 -> four 6-bit fields in bits 0..23
