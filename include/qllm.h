@@ -248,6 +248,19 @@ int64_t qllm_sq_error_workspace_bytes(int64_t N);
 int32_t qllm_sq_error(const void *got, int32_t got_dtype, int64_t N, int64_t O, int64_t ldg, const double *ref,
                       int64_t ldr, double *result, void *workspace, int64_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * The gated activation that feeds a down projection in the models of Sec. 5 (LLaMA): x = silu(gate) * up with
+ * silu(g) = g / (1 + e^-g); the producer of the input that the layer above then reassembles and quantizes.
+ *   gate, up  device, [N, ld_gate] / [N, ld_up] raw bfloat16 bits; x device, [N, ldx] bfloat16; ld* >= C in elements.
+ * The arithmetic is fixed (fp32, one rounding per operation, an expf by range reduction and a degree-5
+ * polynomial, a correctly rounded division; within 2 ulp of silu before the product): the same bits on every run
+ * and as the CPU statement of the same sequence.  16-byte aligned buffers with strides that are multiples of 8
+ * take the fast path (16-byte accesses); anything 2-byte aligned works.  Gates below -88 give a zero.
+ * Errors: NULL / SHAPE / ALIGN / HIP.  N == 0: no-op.
+ */
+int32_t qllm_swiglu(const void *gate, int64_t ld_gate, const void *up, int64_t ld_up, int64_t N, int64_t C, void *x,
+                    int64_t ldx, void *hip_stream);
+
 /* Sizes.  Negative return = qllm_status. */
 int64_t qllm_packed_row_bytes(int64_t K, int32_t bits);
 int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits);

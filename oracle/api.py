@@ -305,5 +305,16 @@ def nearest_member(y, W, chan_a, chan_b):
     return best_j, best_d
 
 
+def swiglu(gate, up, want_f32=False):
+    """x = silu(gate) * up for bfloat16 bit patterns gate, up [N, C] (uint16): bfloat16 bits, and on request the fp32
+    values before the last rounding."""
+    gate, up = _c(gate, np.uint16), _c(up, np.uint16)
+    N, Cc = gate.shape
+    x = np.empty((N, Cc), np.uint16)
+    f = np.empty((N, Cc), np.float32) if want_f32 else None
+    _chk(lib().oracle_swiglu(_p(gate), _i64(Cc), _p(up), _i64(Cc), _i64(N), _i64(Cc), _p(x), _i64(Cc), _p(f)), "swiglu")
+    return (x, f) if want_f32 else x
+
+
 def max_threads():
     return int(lib().oracle_max_threads())

@@ -23,6 +23,8 @@
  *                           channel for weights (Sec. 5 "Quantization settings")
  *   quantized linear layer  Eq. (1) applied to the codes; Y~ = quant(X^) quant(W^) (Sec. 4.1.3)
  *   weight reassembly       Eq. (3) (rows duplicated), Eq. (4) (rows summed), Appendix B
+ *   gated activation        the producer of a down projection's input in the models of Sec. 5
+ *                           (silu(gate) * up; its arithmetic is this build's, stated where it is defined)
  *
  * Fixed arithmetic (the paper states none; these are this build's readings, listed in the design
  * notes): row statistics in fp64, rounded once to fp32; every element-wise step in fp32 with
@@ -687,6 +689,61 @@ int oracle_nearest_member(const float *y, int64_t n, int64_t ldy, const float *W
         best_d[i] = bd;
     }
     free(xb);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- the gated activation before a down projection
+ *
+ * The models of Sec. 5 (LLaMA-1/2) feed their down projection with x = silu(gate) * up, silu(g) = g / (1 + e^-g):
+ * the producer of the activations that the headline shape reassembles.  The paper says nothing of its
+ * arithmetic; this build fixes it as the following sequence of fp32 operations, each rounded once (fma = one
+ * rounding), so that a GPU can reproduce it bit for bit:
+ *     z  = min(max(-g, -86), 88)                       (e^z stays a normal number)
+ *     n  = rint(z * log2(e));  r = fma(n, -ln2_hi, z);  r = fma(n, -ln2_lo, r)        (|r| <= ln2 / 2)
+ *     p  = the degree-5 polynomial of the Cephes expf in r, by Horner's rule with fma;  e = fma(p, r*r, r) + 1
+ *     e  = e * 2^n;   d = 1 + e;   s = g / d (correctly rounded);   s = -0 where g < -88
+ *     x  = s * up, rounded to bfloat16 (nearest even)
+ * gate and up are bfloat16.  The fp32 value before the last rounding is within 2 ulp of the real-number
+ * silu(g) * up for the inputs the tests sweep (tests/test_oracle_swiglu.py).
+ */
+static float silu_times_up(float g, float up)
+{
+    const float LOG2E = 1.44269504088896341f, LN2_HI = 0.693359375f, LN2_LO = -2.12194440e-4f;
+    float z = -g;
+    z = fminf(fmaxf(z, -86.0f), 88.0f);
+    const float n = rintf(z * LOG2E);
+    float r = fmaf(n, -LN2_HI, z);
+    r = fmaf(n, -LN2_LO, r);
+    float p = 1.9875691500e-4f;
+    p = fmaf(p, r, 1.3981999507e-3f);
+    p = fmaf(p, r, 8.3334519073e-3f);
+    p = fmaf(p, r, 4.1665795894e-2f);
+    p = fmaf(p, r, 1.6666665459e-1f);
+    p = fmaf(p, r, 5.0000001201e-1f);
+    float e = fmaf(p, r * r, r);
+    e = e + 1.0f;
+    const uint32_t scale_bits = (uint32_t)((int32_t)n + 127) << 23; /* 2^n, n in [-124, 127] */
+    float scale;
+    memcpy(&scale, &scale_bits, sizeof scale);
+    e = e * scale;
+    const float d = 1.0f + e;
+    float s = g / d;
+    if (g < -88.0f) s = -0.0f;
+    return s * up;
+}
+
+/* gate, up: [N, ld*] bfloat16 bits; x: [N, ldx] bfloat16 bits; f32 (may be NULL): [N, C] the values before the last rounding */
+int oracle_swiglu(const uint16_t *gate, int64_t ld_gate, const uint16_t *up, int64_t ld_up, int64_t N, int64_t C,
+                  uint16_t *x, int64_t ldx, float *f32)
+{
+    if (!gate || !up || !x || N < 0 || C <= 0 || ld_gate < C || ld_up < C || ldx < C) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t c = 0; c < C; ++c) {
+            const float v = silu_times_up(bf16_bits_to_f32(gate[n * ld_gate + c]), bf16_bits_to_f32(up[n * ld_up + c]));
+            if (f32) f32[n * C + c] = v;
+            x[n * ldx + c] = f32_to_bf16_bits(v);
+        }
     return 0;
 }
 

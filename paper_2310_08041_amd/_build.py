@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqllm.so")
-SOURCES = ["fused_nrq.hip", "fused_planned.hip", "int_gemm.hip", "match_pairs.hip", "probes.hip", "calib_ops.hip", "host_offline.cpp"]
+SOURCES = ["fused_nrq.hip", "fused_planned.hip", "int_gemm.hip", "match_pairs.hip", "probes.hip", "calib_ops.hip", "swiglu.hip", "host_offline.cpp"]
 
 # -ffp-contract=off: the fused kernel's fp32 arithmetic is defined with one rounding per operation.
 # packed-fp32 instructions are switched off for the device passes.

@@ -61,6 +61,7 @@ _sigs = {
     "qllm_gemm_workspace_floor_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_tiles6_bytes": (_i64, [_i64, _i64]),
     "qllm_pack_tiles6": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "qllm_swiglu": (_i32, [_vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp]),
     "qllm_status_string": (C.c_char_p, [_i32]),
     "qllm_last_hip_error": (C.c_char_p, []),
     "qllm_build_map_host": (_i32, [_vp, _i64, _f, _vp, _vp, _i64, _vp, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64),
@@ -586,6 +587,20 @@ def qllm_sq_error(got, ref, result, workspace, stream=None):
                             _dp(result), _dp(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
          "qllm_sq_error")
     return result
+
+
+def qllm_swiglu(gate, up, x, stream=None):
+    """x = silu(gate) * up; gate, up, x: [N, C] bfloat16 device tensors (rows may be strided)."""
+    torch = _torch()
+    _check_tensor(gate, "gate", (torch.bfloat16,))
+    _need(gate.dim() == 2, "gate must be [N, C]")
+    _check_tensor(up, "up", (torch.bfloat16,), shape=tuple(gate.shape))
+    _check_tensor(x, "x", (torch.bfloat16,), shape=tuple(gate.shape))
+    _check_on_device(gate=gate, up=up, x=x)
+    N, Cc = gate.shape
+    ld = lambda t: t.stride(0) if N > 1 else Cc          # the stride of a single row says nothing
+    _chk(_lib.qllm_swiglu(_dp(gate), ld(gate), _dp(up), ld(up), int(N), int(Cc), _dp(x), ld(x), _stream(stream)), "qllm_swiglu")
+    return x
 
 
 def qllm_probe_mfma(workgroups, iters, sink, stream=None):

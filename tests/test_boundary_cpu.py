@@ -152,6 +152,17 @@ def test_tiles6_entry_points_reject_bad_arguments_before_launching():
     assert lib.qllm_tiles6_bytes(-1, 128) == -2 and lib.qllm_tiles6_bytes(16, 0) == -2
 
 
+def test_swiglu_entry_point_rejects_bad_arguments_before_launching():
+    f = b.raw().qllm_swiglu
+    G, U, X = 0x1000, 0x2000, 0x3000
+    assert f(None, 64, U, 64, 4, 64, X, 64, None) == -1 and f(G, 64, None, 64, 4, 64, X, 64, None) == -1
+    assert f(G, 64, U, 64, 4, 64, None, 64, None) == -1
+    assert f(G, 63, U, 64, 4, 64, X, 64, None) == -2 and f(G, 64, U, 64, 4, 64, X, 10, None) == -2
+    assert f(G, 64, U, 64, -1, 64, X, 64, None) == -2 and f(G, 64, U, 64, 4, 0, X, 64, None) == -2
+    assert f(G + 1, 64, U, 64, 4, 64, X, 64, None) == -6
+    assert f(G, 64, U, 64, 0, 64, X, 64, None) == 0
+
+
 def test_linear_entry_point_rejects_bad_arguments_before_launching():
     lib = b.raw()
     m, q, w = _structs()

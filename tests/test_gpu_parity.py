@@ -9,6 +9,7 @@ import pytest
 
 from helpers import random_csr_map, NORM_ID, expected_qact, make_case, rel_err, to_torch_x
 from paper_2310_08041_amd import workloads as wl
+from paper_2310_08041_amd.workloads import bf16_bits_to_f32, f32_to_bf16_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -458,6 +459,57 @@ def test_gemm_full_configs_sampled(oracle, b, name):
         ref_rows = oracle.epilogue(acc[rows], w.C, ax[rows], bx[rows], rs[rows], aw, bw, cs)
         got_rows = oracle.widen_bf16(y[__import__("torch").from_numpy(rows).cuda()].view(__import__("torch").int16).cpu().numpy().view(np.uint16))
         assert rel_err(got_rows, ref_rows).max() <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------- the producer of a down projection's input
+
+def _bf16_tensor(bits):
+    import torch
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+@pytest.mark.parametrize("N,C", [(1, 1), (3, 17), (5, 64), (64, 512), (33, 1000)])
+def test_swiglu_matches_the_oracle(oracle, b, N, C):
+    """x = silu(gate) * up, bit for bit: both sides state the same sequence of fp32 operations."""
+    import torch
+    rng = np.random.default_rng(N * 31 + C)
+    gate = f32_to_bf16_bits((rng.standard_normal((N, C)) * 5).astype(np.float32))
+    up = f32_to_bf16_bits((rng.standard_normal((N, C)) * 2).astype(np.float32))
+    x = torch.full((N, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+    b.qllm_swiglu(_bf16_tensor(gate), _bf16_tensor(up), x)
+    torch.cuda.synchronize()
+    assert np.array_equal(x.view(torch.int16).cpu().numpy().view(np.uint16), oracle.swiglu(gate, up))
+    # rows inside wider buffers (strides that are no multiple of 8 elements: the element-by-element path)
+    wide_g, wide_u = _bf16_tensor(np.pad(gate, ((0, 0), (0, 3)))), _bf16_tensor(np.pad(up, ((0, 0), (0, 5))))
+    xw = torch.full((N, C + 1), float("nan"), dtype=torch.bfloat16, device="cuda")
+    b.qllm_swiglu(wide_g[:, :C], wide_u[:, :C], xw[:, :C])
+    torch.cuda.synchronize()
+    assert np.array_equal(xw[:, :C].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), oracle.swiglu(gate, up))
+    assert bool(torch.isnan(xw[:, C]).all())                                      # nothing written past a row
+
+
+def test_swiglu_every_finite_gate_and_the_headline_shape(oracle, b):
+    import torch
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    gate = bits[np.isfinite(bf16_bits_to_f32(bits))]                              # all 65280 finite bfloat16 values
+    gate = np.tile(gate, 2)[None]
+    up = f32_to_bf16_bits(np.concatenate([np.ones(65280, np.float32), np.full(65280, -0.37, np.float32)]))[None]
+    x = torch.empty((1, gate.shape[1]), dtype=torch.bfloat16, device="cuda")
+    b.qllm_swiglu(_bf16_tensor(gate), _bf16_tensor(up), x)
+    torch.cuda.synchronize()
+    assert np.array_equal(x.view(torch.int16).cpu().numpy().view(np.uint16), oracle.swiglu(gate, up))
+    # the down projection's input at the 70B shape, as launched for the whole batch; the oracle checks 192 sampled rows
+    N, C = 2048, 28672
+    rng = np.random.default_rng(7)
+    g = torch.from_numpy((rng.standard_normal((N, C), dtype=np.float32) * 3)).cuda().to(torch.bfloat16)
+    u = torch.from_numpy(rng.standard_normal((N, C), dtype=np.float32)).cuda().to(torch.bfloat16)
+    x = torch.empty((N, C), dtype=torch.bfloat16, device="cuda")
+    b.qllm_swiglu(g, u, x)
+    torch.cuda.synchronize()
+    rows = np.sort(rng.choice(N, 192, replace=False))
+    idx = torch.from_numpy(rows).cuda()
+    tobits = lambda t: t[idx].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(tobits(x), oracle.swiglu(tobits(g), tobits(u)))
 
 
 # ---------------------------------------------------------------- the whole layer (a1..a6)
