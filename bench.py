@@ -59,6 +59,65 @@ def read_traffic(workload):
     return out
 
 
+def bench_swiglu(args, w, dev):
+    """The producer of a down projection's input: x = silu(gate) * up at the workload's N x C, bfloat16.
+    A step = one qllm_swiglu call; 6 bytes per element against HBM."""
+    import numpy as np
+    import torch
+
+    from paper_2310_08041_amd import binding as b
+
+    g = torch.Generator(device=dev).manual_seed(w.seed)
+    sets = 3                                                                       # 3 x 352 MB at the 70B shape: past the last-level cache
+    gate = [(torch.randn((w.N, w.C), device=dev, generator=g) * 3).to(torch.bfloat16) for _ in range(sets)]
+    up = [torch.randn((w.N, w.C), device=dev, generator=g).to(torch.bfloat16) for _ in range(sets)]
+    x = [torch.empty((w.N, w.C), dtype=torch.bfloat16, device=dev) for _ in range(sets)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    warm_ms, warm_steps = 0.0, 0
+    while warm_steps < args.warmup or warm_ms < MIN_WARMUP_MS:
+        ev[0].record()
+        for i in range(16):
+            b.qllm_swiglu(gate[i % sets], up[i % sets], x[i % sets])
+        ev[1].record()
+        torch.cuda.synchronize()
+        warm_steps += 16
+        warm_ms += ev[0].elapsed_time(ev[1])
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(args.steps):
+        b.qllm_swiglu(gate[i % sets], up[i % sets], x[i % sets])
+    ev[1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_kernel = ev[0].elapsed_time(ev[1]) * 1e-3 / args.steps
+    nbytes = 6.0 * w.N * w.C
+    result = {
+        "metric": "silu(gate)*up producer of the reassembled linear layer's input, GB/s", "value": nbytes / (wall / args.steps) / 1e9,
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (fixed sequence of fp32 operations, bf16 in and out)", "data": "synthetic",
+        "config": {"workload": w.name + " (producer of its input)", "N": w.N, "C": w.C, "warmup_done": {"steps": warm_steps, "gpu_ms": warm_ms}},
+        "roofline": {"kernel": "swiglu_kernel", "bound": "hbm", "achieved": nbytes / t_kernel / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": nbytes / t_kernel / 1e9 / HBM_PEAK_GBS, "avg_launch_us": t_kernel * 1e6, "algorithmic_bytes": nbytes,
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import api as oracle
+        rows = np.sort(np.random.default_rng(w.seed).choice(w.N, min(256, w.N), replace=False))
+        idx = torch.from_numpy(rows).to(dev)
+        bits = lambda t: t[idx].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        gb, ub = bits(gate[(args.steps - 1) % sets]), bits(up[(args.steps - 1) % sets])
+        t1 = time.perf_counter()
+        ref = oracle.swiglu(gb, ub)
+        cpu_s = time.perf_counter() - t1
+        result["cpu_baseline"] = {"value": 6.0 * rows.size * w.C / cpu_s / 1e9, "unit": "GB/s", "cores": oracle.max_threads(), "kind": "oracle",
+                                  "sample": f"{rows.size} sampled rows of {w.N}, {cpu_s:.1f} s"}
+        result["parity_checked"] = {"rows": int(rows.size), "bit_exact": bool(np.array_equal(bits(x[(args.steps - 1) % sets]), ref))}
+        result["parity_checked"]["ok"] = result["parity_checked"]["bit_exact"]
+    print(json.dumps(result))
+    return 0 if result.get("parity_checked", {"ok": True})["ok"] else 1
+
+
 def bench_matching(args, w, norm, dev):
     """The step before the path: Appendix A steps 1-2 with the distance of Eq. (5) for the workload's
     layer, 256 calibration tokens.  A step = one qllm_match_nearest call (norms + nearest-member search)."""
@@ -157,9 +216,10 @@ def main():
                     help="expansion ratio that fixes theta (Sec. 5.2 varies it up to 0.1); default: the workload's own")
     ap.add_argument("--allow-map-walk", action="store_true",
                     help="do not stop when the fused kernel would fall back to walking the map's CSR rows")
-    ap.add_argument("--stage", default="layer", choices=["layer", "match"],
+    ap.add_argument("--stage", default="layer", choices=["layer", "match", "swiglu"],
                     help="layer: the hot path (the default, the line the contract asks for); match: the offline "
-                         "channel matching of Eq. (5) / Appendix A at the workload's channel count")
+                         "channel matching of Eq. (5) / Appendix A at the workload's channel count; swiglu: the "
+                         "producer of a down projection's input, silu(gate) * up, at the workload's N x C")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over tokens with no "
@@ -178,6 +238,8 @@ def main():
     norm = {"none": b.NORM_NONE, "layer": b.NORM_LAYER, "rms": b.NORM_RMS}[w.norm]
     if args.stage == "match":
         return bench_matching(args, w, norm, dev)
+    if args.stage == "swiglu":
+        return bench_swiglu(args, w, dev)
 
     # ---- synthetic inputs, resident in HBM before anything is timed
     t0 = time.time()
