@@ -22,9 +22,12 @@ namespace {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-constexpr int TA = 64, TB = 128, KT = 32, THREADS = 256, PAD = KT + 1; // PAD: row stride in doubles, odd against bank conflicts
-constexpr int NA_STEP = TA * KT / THREADS, NB_STEP = TB * KT / THREADS;     // values per lane and K-step: 8 and 16
-constexpr size_t TILE_LDS = (size_t)2 * (TA + TB) * PAD * sizeof(double);   // two buffers of both tiles: 101376 bytes
+constexpr int TA = 64, TB = 128, KT = 32, THREADS = 256;
+// The fp64 tiles of the register path: K-steps of KTX values, row stride KTX + 1 doubles (odd, against bank
+// conflicts), two buffers of both tiles.  KTX = 32: 101376 bytes, one workgroup per CU.  The kernel whose weight
+// pass goes straight into LDS runs its token pass with KTX = 16 (52224 bytes), so that its LDS need is the weight
+// ring's and two workgroups share a CU.
+constexpr size_t tile_lds(int ktx) { return (size_t)2 * (TA + TB) * (ktx + 1) * sizeof(double); }
 
 struct MatchArgs {
     const float *y;  // [n, ldy]: activations, token-major
@@ -122,7 +125,7 @@ __device__ __forceinline__ void fetch_tile(const MatchArgs &g, const int32_t *ch
     }
 }
 
-template <bool XPASS, int ROWS, int PER>
+template <bool XPASS, int ROWS, int PAD, int PER>
 __device__ __forceinline__ void stage_tile(double *tile, int tid, const float (&p)[PER])
 {
     if constexpr (XPASS) {
@@ -141,29 +144,33 @@ __device__ __forceinline__ void stage_tile(double *tile, int tid, const float (&
     }
 }
 
-// acc[ti][tj] += A tile rows 16 ti.. times B tile rows 32 wave + 16 tj.., over K (n tokens or O features)
-template <bool XPASS, bool VEC>
-__device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca, const int32_t *cb, double *as, double *bs,
-                                          int tid, v4d (&acc)[4][2])
+// acc[ti][tj] += A tile rows 16 ti.. times B tile rows 32 wave + 16 tj.., over K (n tokens or O features),
+// in K-steps of KTX values (the weight rows' 16-byte loads are laid out for KTX == KT)
+template <bool XPASS, bool VEC, int KTX>
+__device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca, const int32_t *cb, double *tiles, int tid,
+                                          v4d (&acc)[4][2])
 {
+    static_assert(XPASS || KTX == KT, "weight rows are fetched in K-steps of KT");
+    constexpr int PAD = KTX + 1, NA_STEP = TA * KTX / THREADS, NB_STEP = TB * KTX / THREADS;
+    double *as = tiles, *bs = tiles + 2 * TA * PAD;
     const int lane = tid & 63, wave = tid >> 6;
     const int K = XPASS ? g.n : g.O;
-    const int steps = (K + KT - 1) / KT;
+    const int steps = (K + KTX - 1) / KTX;
     float pa[NA_STEP], pb[NB_STEP];
     fetch_tile<XPASS, VEC, TA, NA_STEP>(g, ca, 0, tid, pa);
     fetch_tile<XPASS, VEC, TB, NB_STEP>(g, cb, 0, tid, pb);
     for (int s = 0; s < steps; ++s) {
         double *a_buf = as + (s & 1) * TA * PAD, *b_buf = bs + (s & 1) * TB * PAD;
-        stage_tile<XPASS, TA, NA_STEP>(a_buf, tid, pa);
-        stage_tile<XPASS, TB, NB_STEP>(b_buf, tid, pb);
+        stage_tile<XPASS, TA, PAD, NA_STEP>(a_buf, tid, pa);
+        stage_tile<XPASS, TB, PAD, NB_STEP>(b_buf, tid, pb);
         // one barrier per step: the buffer written now was last read two steps ago, before the previous barrier
         __syncthreads();
         if (s + 1 < steps) {
-            fetch_tile<XPASS, VEC, TA, NA_STEP>(g, ca, (s + 1) * KT, tid, pa);
-            fetch_tile<XPASS, VEC, TB, NB_STEP>(g, cb, (s + 1) * KT, tid, pb);
+            fetch_tile<XPASS, VEC, TA, NA_STEP>(g, ca, (s + 1) * KTX, tid, pa);
+            fetch_tile<XPASS, VEC, TB, NB_STEP>(g, cb, (s + 1) * KTX, tid, pb);
         }
 #pragma unroll
-        for (int kk = 0; kk < KT / 4; ++kk) {
+        for (int kk = 0; kk < KTX / 4; ++kk) {
             double a[4], b[2];
 #pragma unroll
             for (int ti = 0; ti < 4; ++ti) a[ti] = a_buf[(16 * ti + (lane & 15)) * PAD + 4 * kk + (lane >> 4)];
@@ -181,17 +188,20 @@ __device__ __forceinline__ void gram_pass(const MatchArgs &g, const int32_t *ca,
 
 // The weight pass when every row allows 16-byte loads and O is a multiple of the K-step: the operands
 // go from global memory straight into LDS (global_load_lds_dwordx4: lane l of a wave lands at the
-// wave's LDS base + 16 l), as fp32, three K-steps ahead in a ring of four stages, and are widened to
-// double when the matrix-core operands are read.  No staging registers, no conversion and store pass;
-// with one wave per SIMD the latency of the loads was what the register path spent half its time on.
+// wave's LDS base + 16 l), as fp32, two K-steps ahead in a ring of three stages, and are widened to
+// double when the matrix-core operands are read.  No staging registers, no conversion and store pass.
+// Three stages (72 KB) and the token pass in K-steps of 16 leave room for a second workgroup on the CU:
+// two waves per SIMD, so that one's wait for its operand reads is the other's matrix-core time.
 // A stage holds 192 rows (64 of the A tile, 128 of the B tile) of 32 floats; a wave load covers 8 rows;
 // the 16-byte chunk c of row R sits at position c ^ ((R >> 1) & 7), chosen on the global side (which
 // chunk a lane fetches), so that the 64 lanes of an operand read fall on 64 different banks.
-constexpr int MAX_SPLITS = 8;
-constexpr int STAGE_F = (TA + TB) * KT, NSTAGE = 4;                 // floats per stage (24 KB), stages
-constexpr int WAIT_VM12_LGKM0 = 12 | (7 << 4) | (0 << 8);          // s_waitcnt vmcnt(12) lgkmcnt(0)
+constexpr int MAX_SPLITS = 16;
+constexpr int STAGE_F = (TA + TB) * KT, NSTAGE = 3;                 // floats per stage (24 KB), stages
+constexpr int KTX_DMA = 16;                                         // K-step of the token pass in the same kernel
+constexpr size_t RING_LDS = (size_t)NSTAGE * STAGE_F * sizeof(float);
+constexpr int WAIT_VM6_LGKM0 = 6 | (7 << 4) | (0 << 8);            // s_waitcnt vmcnt(6) lgkmcnt(0)
 constexpr int WAIT_VM0_ONLY = 0 | (7 << 4) | (15 << 8);            // s_waitcnt vmcnt(0)
-static_assert((size_t)NSTAGE * STAGE_F * sizeof(float) <= TILE_LDS, "the fp32 ring fits where the fp64 tiles are");
+static_assert(tile_lds(KTX_DMA) <= RING_LDS, "the token pass's fp64 tiles fit where the fp32 ring is");
 
 __device__ __forceinline__ void gram_pass_w_dma(const MatchArgs &g, const int32_t *ca, const int32_t *cb, float *ring, int tid,
                                                 v4d (&acc)[4][2])
@@ -206,27 +216,28 @@ __device__ __forceinline__ void gram_pass_w_dma(const MatchArgs &g, const int32_
         const int chan = row < TA ? ca[row] : cb[row - TA];
         src[t] = g.w + (int64_t)chan * g.ldw + 4 * ((lane & 7) ^ ((row >> 1) & 7));
     }
-    auto fetch = [&](int s) { // K-step s (clamped to the last one) -> stage s & 3
+    auto fetch = [&](int s, int stage) { // K-step s (clamped to the last one) -> stage s % 3
         const int sc = min(s, steps - 1);
-        float *dst = ring + (s & (NSTAGE - 1)) * STAGE_F;
+        float *dst = ring + stage * STAGE_F;
 #pragma unroll
         for (int t = 0; t < 6; ++t)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[t] + (int64_t)sc * KT),
                                              (__attribute__((address_space(3))) void *)(dst + 8 * (wave + 4 * t) * KT), 16, 0, 0);
     };
     const int r = lane & 15, kq = lane >> 4, f = (r >> 1) & 7;
-    fetch(0);
-    fetch(1);
-    fetch(2);
+    fetch(0, 0);
+    fetch(1, 1);
+    int stage = 0; // s % 3
     for (int s = 0; s < steps; ++s) {
-        // loads complete in order: at most the two newest steps outstanding = step s has landed (this
-        // wave's share; the barrier adds the others').  The stage written next was read in step s - 1.
-        __builtin_amdgcn_s_waitcnt(WAIT_VM12_LGKM0);
+        // loads complete in order: at most the newest step outstanding = step s has landed (this wave's
+        // share; the barrier adds the others').  The stage written next was read in step s - 1.
+        __builtin_amdgcn_s_waitcnt(WAIT_VM6_LGKM0);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        fetch(s + 3);
-        const float *sb = ring + (s & (NSTAGE - 1)) * STAGE_F;
+        fetch(s + 2, stage == 0 ? 2 : stage - 1);
+        const float *sb = ring + stage * STAGE_F;
+        stage = stage == 2 ? 0 : stage + 1;
 #pragma unroll
         for (int kk = 0; kk < KT / 4; ++kk) {
             const int off = 4 * (kk ^ f) + kq;
@@ -251,10 +262,10 @@ __device__ __forceinline__ void gram_pass_w_dma(const MatchArgs &g, const int32_
 // MODE 0: 4-byte loads; 1: 16-byte loads of weight rows; 2: weight rows straight into LDS.
 // L2: no weights, the distance is |x_i - x_j|^2 alone.
 template <int MODE, bool L2 = false>
-__global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs g)
+__global__ __launch_bounds__(THREADS, MODE == 2 ? 2 : 1) void match_nearest_kernel(const MatchArgs g)
 {
     extern __shared__ __align__(16) double tiles[];
-    double *as = tiles, *bs = tiles + 2 * TA * PAD;
+    constexpr int KTX = MODE == 2 ? KTX_DMA : KT; // K-step of the token pass
     __shared__ double na_x[TA], na_w[TA], nb_x[TB], nb_w[TB];
     __shared__ int32_t ca[TA], cb[TB];
     __shared__ double fin_d[THREADS / 64][TA];
@@ -304,12 +315,12 @@ __global__ __launch_bounds__(THREADS) void match_nearest_kernel(const MatchArgs 
         for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
             for (int tj = 0; tj < 2; ++tj) gx[ti][tj] = gw[ti][tj] = v4d{0.0, 0.0, 0.0, 0.0};
-        gram_pass<true, MODE != 0>(g, ca, cb, as, bs, tid, gx);
+        gram_pass<true, MODE != 0, KTX>(g, ca, cb, tiles, tid, gx);
         if constexpr (L2) {
         } else if constexpr (MODE == 2) {
             gram_pass_w_dma(g, ca, cb, reinterpret_cast<float *>(tiles), tid, gw);
         } else {
-            gram_pass<false, MODE != 0>(g, ca, cb, as, bs, tid, gw);
+            gram_pass<false, MODE != 0, KT>(g, ca, cb, tiles, tid, gw);
         }
         // distances of this tile; element r of an accumulator: row (lane >> 4) + 4 r, column lane & 15
         // (checked against the oracle: the fp64 operation interleaves the rows of its four result registers)
@@ -432,12 +443,13 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
                      : mode == 2 ? reinterpret_cast<const void *>(&match_nearest_kernel<2>)
                      : mode == 1 ? reinterpret_cast<const void *>(&match_nearest_kernel<1>)
                                  : reinterpret_cast<const void *>(&match_nearest_kernel<0>);
+    const size_t lds = mode == 2 ? RING_LDS : tile_lds(KT);
     { // the LDS limit is raised once per kernel; later calls (also under stream capture) only launch
         static std::mutex lock;
         static bool raised[4] = {false, false, false, false};
         std::lock_guard<std::mutex> hold(lock);
         if (!raised[mode]) {
-            const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TILE_LDS);
+            const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (ea != hipSuccess) {
                 (void)hipGetLastError();
                 qllm_note_hip_error("channel matching: raising the LDS limit", hipGetErrorName(ea));
@@ -448,10 +460,10 @@ extern "C" int32_t qllm_match_nearest(const float *y, int64_t n, int64_t ldy, co
     }
     const int64_t n_a_tiles = (nA + TA - 1) / TA;
     const dim3 grid((unsigned)((n_a_tiles + 7) / 8 * 8 * g.splits));
-    if (mode == 3) hipLaunchKernelGGL((match_nearest_kernel<0, true>), grid, dim3(THREADS), TILE_LDS, stream, g);
-    else if (mode == 2) hipLaunchKernelGGL(match_nearest_kernel<2>, grid, dim3(THREADS), TILE_LDS, stream, g);
-    else if (mode == 1) hipLaunchKernelGGL(match_nearest_kernel<1>, grid, dim3(THREADS), TILE_LDS, stream, g);
-    else hipLaunchKernelGGL(match_nearest_kernel<0>, grid, dim3(THREADS), TILE_LDS, stream, g);
+    if (mode == 3) hipLaunchKernelGGL((match_nearest_kernel<0, true>), grid, dim3(THREADS), lds, stream, g);
+    else if (mode == 2) hipLaunchKernelGGL(match_nearest_kernel<2>, grid, dim3(THREADS), lds, stream, g);
+    else if (mode == 1) hipLaunchKernelGGL(match_nearest_kernel<1>, grid, dim3(THREADS), lds, stream, g);
+    else hipLaunchKernelGGL(match_nearest_kernel<0>, grid, dim3(THREADS), lds, stream, g);
     hipLaunchKernelGGL(match_combine_kernel, dim3((unsigned)((nA + THREADS - 1) / THREADS)), dim3(THREADS), 0, stream, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {

@@ -466,7 +466,7 @@ def test_matching_entry_point_rejects_bad_arguments_before_launching():
     assert call(ws=None) == -7 and call(wsb=b.qllm_match_workspace_bytes(10, 12) - 1) == -7
     assert call(ws=P + 4) == -6
     assert call(nA=0) == 0                                            # nothing to match
-    assert b.qllm_match_workspace_bytes(10, 12) == 2 * 22 * 8 + 8 * 10 * 12 and b.qllm_match_workspace_bytes(-1, 3) == -2
+    assert b.qllm_match_workspace_bytes(10, 12) == 2 * 22 * 8 + 16 * 10 * 12 and b.qllm_match_workspace_bytes(-1, 3) == -2
 
 
 def test_select_edges_host_matches_the_oracle():
