@@ -205,6 +205,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--int8", action="store_true",
                     help="4-bit codes: keep the GEMM on the int8 matrix cores (no FP6-path copy of the weight)")
+    ap.add_argument("--bits", default=None,
+                    help="A,W: activation and weight bits instead of the workload's own (6,6 / 8,8 / 8,4: the other "
+                         "settings of Sec. 5), same shapes and inputs")
+    ap.add_argument("--packed", action="store_true",
+                    help="6- and 8-bit activations: no one-byte-per-code copy of the weight, so that the GEMM expands "
+                         "the packed codes itself")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -235,6 +241,10 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
     w = wl.WORKLOADS[args.workload]
+    if args.bits:
+        import dataclasses
+        a_bits, w_bits = (int(v) for v in args.bits.split(","))
+        w = dataclasses.replace(w, a_bits=a_bits, w_bits=w_bits)
     norm = {"none": b.NORM_NONE, "layer": b.NORM_LAYER, "rms": b.NORM_RMS}[w.norm]
     if args.stage == "match":
         return bench_matching(args, w, norm, dev)
@@ -264,9 +274,10 @@ def main():
     W = wl.draw_weight(w)
     q = b.qllm_quantize_weight_host(W, cal["row_ptr"], cal["src"], w.w_bits)
     del W
-    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, w.w_bits, tiles6=not args.int8)
+    dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, w.w_bits, tiles6=not args.int8 and w.a_bits == 4,
+                        tiles8=not args.packed and (w.a_bits, w.w_bits) != (4, 4))
     # 4-bit codes, more than 32 tokens, K not split over workgroups: the GEMM runs on the FP6 matrix cores
-    fp6_path = dw.tiles6 is not None and w.N > 32 and b.qllm_gemm_workspace_floor_bytes(w.N, K, w.O, w.a_bits) == 0
+    fp6_path = dw.tiles6 is not None and w.a_bits == 4 and w.N > 32 and b.qllm_gemm_workspace_floor_bytes(w.N, K, w.O, w.a_bits) == 0
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, N_ROTATE)]   # same rows, other addresses
     ys = [torch.empty((w.N, w.O), dtype=torch.bfloat16, device=dev) for _ in range(N_ROTATE)]
     ws = torch.empty(b.qllm_workspace_bytes(w.N, K, w.O, w.a_bits), dtype=torch.uint8, device=dev)
@@ -415,8 +426,11 @@ def main():
     stream_probe_gbs = 10 * (sbytes + sbytes // 4) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
     del ssrc, sdst
 
+    bytes_path = dw.tiles8 is not None and w.N > 32
     if fp6_path:
         gemm_kernel = "gemm_w4a4_fp6_kernel<bf16>"
+    elif bytes_path:
+        gemm_kernel = "gemm_tiles8_kernel<%d,%d,bf16> after tiles8_kernel" % (w.a_bits, w.w_bits)
     elif w.N > 128:
         gemm_kernel = ("int_gemm_w4a4_kernel<bf16>" if (w.a_bits, w.w_bits) == (4, 4) else
                        "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits))
@@ -455,14 +469,16 @@ def main():
                     "probe": {"what": "loop of int8 matrix-core operations on register operands, all CUs",
                               "achieved": mfma_probe_tops, "frac_of_probe": gemm_tops / mfma_probe_tops}}
     result = {
-        "metric": "reassembled W4A4 linear TOPS at 70B shapes; fused norm+reassembly+quant GB/s",
+        "metric": "reassembled W%dA%d linear TOPS at 70B shapes; fused norm+reassembly+quant GB/s" % (w.w_bits, w.a_bits)
+                  if args.bits else "reassembled W4A4 linear TOPS at 70B shapes; fused norm+reassembly+quant GB/s",
         "value": ops / (ms_per_step * 1e-3) / 1e12,
         "unit": "TOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("fp6 E2M3 (4-bit codes as FP6 numbers on the FP6 matrix cores, fp32 sums that are exact integers / 64); "
                   "fp32 norm/quantizer" if fp6_path else
-                  "int8 (4-bit codes on the int8 matrix cores, int32 accumulate); fp32 norm/quantizer"),
+                  "int8 (%d-bit activation and %d-bit weight codes on the int8 matrix cores, int32 accumulate); "
+                  "fp32 norm/quantizer" % (w.a_bits, w.w_bits)),
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "C": w.C, "C_hat": K, "O": w.O, "a_bits": w.a_bits,
                    "w_bits": w.w_bits, "in_dtype": w.in_dtype, "out_dtype": "bf16", "norm": w.norm,

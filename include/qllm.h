@@ -100,6 +100,11 @@ typedef struct {
     const uint8_t *tiles6;  /* optional, bits == 4 only: device copy of the codes in the layout qllm_pack_tiles6
                                makes, qllm_tiles6_bytes(O, K) bytes, 16-byte aligned.  With it (and room in the
                                workspace, see qllm_int_gemm) the GEMM runs on the FP6 matrix cores.  NULL: int8. */
+    const uint8_t *tiles8;  /* optional, any bits (unused when the activations are 4-bit too): device copy of the
+                               codes, one byte each, in the layout qllm_pack_tiles8 makes, qllm_tiles8_bytes(O, K)
+                               bytes, 16-byte aligned.  With it (and room in the workspace) the GEMM of 6- and 8-bit
+                               activations feeds the int8 matrix cores without unpacking anything on the way.
+                               NULL: the packed codes are expanded inside the GEMM. */
 } qllm_weight;
 
 /* Per-token quantized activations: output of the fused kernel, input of the GEMM. */
@@ -150,6 +155,11 @@ int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, in
  * w->tiles6 is set, qllm_gemm_workspace_floor_bytes(...) is 0 for the shape (K not split) and the workspace
  * holds at least qllm_tiles6_bytes(N, w->K) bytes (the activations are re-laid into it first, a few per cent of
  * the GEMM's time); otherwise the int8 path runs.  Same results either way.
+ *
+ * Byte operands.  For the other bit pairs (6/6, 8/8, 8-bit activations on 4-bit weights; Sec. 5, "Quantization
+ * settings") and N > 32 the int8 matrix cores can be fed straight from one-byte-per-code copies of both operands:
+ * taken when w->tiles8 is set and the workspace holds at least qllm_tiles8_bytes(N, w->K) bytes (the activations
+ * are re-laid into it first); otherwise the packed codes are expanded inside the GEMM.  Same results either way.
  */
 int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
                       int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
@@ -281,6 +291,20 @@ int64_t qllm_workspace_floor_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bi
  */
 int64_t qllm_tiles6_bytes(int64_t rows, int64_t K);
 int32_t qllm_pack_tiles6(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *tiles, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Codes re-laid one byte each for the byte-operand path of qllm_int_gemm (Eq. 1 on the codes; see there).
+ *   codes   device, [rows, qllm_packed_row_bytes(K, bits)] in the packed format above, 16-byte aligned; bits 4, 6, 8.
+ *   tiles   device, qllm_tiles8_bytes(rows, K) bytes, 16-byte aligned, fully overwritten:
+ *           rows in blocks of 16, K in tiles of 64 codes (ceil(K / 64) of them); block b, K-tile t is the 1024 bytes
+ *           at (b * tiles_per_row + t) * 1024; for l = 0..63, r = l % 16, q = l / 16 the code 64 t + 16 q + e
+ *           (e = 0..15) of row 16 b + r is the byte at 16 l + e: the code itself for 4- and 6-bit codes, the code
+ *           XOR 0x80 (code - 128 as a signed byte) for 8-bit codes.  Rows past the matrix and places past K are
+ *           zero bytes.
+ * For a weight: once, offline, into qllm_weight.tiles8.  Errors: NULL / BITS / SHAPE / ALIGN / HIP.  rows == 0: no-op.
+ */
+int64_t qllm_tiles8_bytes(int64_t rows, int64_t K);
+int32_t qllm_pack_tiles8(const uint8_t *codes, int32_t bits, int64_t rows, int64_t K, uint8_t *tiles, void *hip_stream);
 
 const char *qllm_status_string(int32_t status);
 

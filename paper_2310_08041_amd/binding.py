@@ -38,7 +38,8 @@ class _Map(C.Structure):
 
 class _Weight(C.Structure):
     _fields_ = [("O", C.c_int64), ("K", C.c_int64), ("bits", C.c_int32), ("codes", C.c_void_p),
-                ("scale", C.c_void_p), ("zero", C.c_void_p), ("colsum", C.c_void_p), ("tiles6", C.c_void_p)]
+                ("scale", C.c_void_p), ("zero", C.c_void_p), ("colsum", C.c_void_p), ("tiles6", C.c_void_p),
+                ("tiles8", C.c_void_p)]
 
 
 class _QAct(C.Structure):
@@ -61,6 +62,8 @@ _sigs = {
     "qllm_gemm_workspace_floor_bytes": (_i64, [_i64, _i64, _i64, _i32]),
     "qllm_tiles6_bytes": (_i64, [_i64, _i64]),
     "qllm_pack_tiles6": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "qllm_tiles8_bytes": (_i64, [_i64, _i64]),
+    "qllm_pack_tiles8": (_i32, [_vp, _i32, _i64, _i64, _vp, _vp]),
     "qllm_swiglu": (_i32, [_vp, _i64, _vp, _i64, _i64, _i64, _vp, _i64, _vp]),
     "qllm_status_string": (C.c_char_p, [_i32]),
     "qllm_last_hip_error": (C.c_char_p, []),
@@ -156,6 +159,21 @@ def qllm_pack_tiles6(codes, rows, K, tiles, stream=None):
     _check_tensor(tiles, "tiles", (torch.uint8,), numel=qllm_tiles6_bytes(rows, K))
     _check_on_device(codes=codes, tiles=tiles)
     _chk(_lib.qllm_pack_tiles6(_dp(codes), int(rows), int(K), _dp(tiles), _stream(stream)), "qllm_pack_tiles6")
+
+
+def qllm_tiles8_bytes(rows, K):
+    v = _lib.qllm_tiles8_bytes(int(rows), int(K))
+    _chk(v if v < 0 else 0, "qllm_tiles8_bytes")
+    return int(v)
+
+
+def qllm_pack_tiles8(codes, bits, rows, K, tiles, stream=None):
+    """codes [rows, packed_row_bytes(K, bits)] uint8, tiles [tiles8_bytes(rows, K)] uint8: device tensors."""
+    torch = _torch()
+    _check_tensor(codes, "codes", (torch.uint8,), numel=int(rows) * qllm_packed_row_bytes(K, bits))
+    _check_tensor(tiles, "tiles", (torch.uint8,), numel=qllm_tiles8_bytes(rows, K))
+    _check_on_device(codes=codes, tiles=tiles)
+    _chk(_lib.qllm_pack_tiles8(_dp(codes), int(bits), int(rows), int(K), _dp(tiles), _stream(stream)), "qllm_pack_tiles8")
 
 
 def qllm_gemm_workspace_bytes(N, K, O, a_bits):
@@ -325,8 +343,10 @@ class DeviceMap:
 class DeviceWeight:
     """Device copy of packed per-output-channel quantized weights."""
 
-    def __init__(self, codes, scale, zero, colsum, K, bits, device="cuda", tiles6=True):
-        """tiles6: for 4-bit codes also keep the copy laid out for the FP6 matrix-core path (1.5 x the packed size)."""
+    def __init__(self, codes, scale, zero, colsum, K, bits, device="cuda", tiles6=True, tiles8=None):
+        """tiles6: for 4-bit codes also keep the copy laid out for the FP6 matrix-core path (1.5 x the packed size).
+        tiles8: also keep the one-byte-per-code copy that the GEMM of 6- and 8-bit activations reads without
+        unpacking (None: for 6- and 8-bit codes; 4-bit weights need it only under 8-bit activations, so say True)."""
         torch = _torch()
         self.codes = torch.as_tensor(np.ascontiguousarray(codes, np.uint8)).to(device)
         self.scale = torch.as_tensor(np.ascontiguousarray(scale, np.float32)).to(device)
@@ -338,8 +358,12 @@ class DeviceWeight:
         if tiles6 and self.bits == 4:
             self.tiles6 = torch.empty(qllm_tiles6_bytes(self.O, self.K), dtype=torch.uint8, device=device)
             qllm_pack_tiles6(self.codes, self.O, self.K, self.tiles6)
+        self.tiles8 = None
+        if tiles8 or (tiles8 is None and self.bits != 4):
+            self.tiles8 = torch.empty(qllm_tiles8_bytes(self.O, self.K), dtype=torch.uint8, device=device)
+            qllm_pack_tiles8(self.codes, self.bits, self.O, self.K, self.tiles8)
         self.c = _Weight(self.O, self.K, self.bits, _dp(self.codes), _dp(self.scale), _dp(self.zero),
-                         _dp(self.colsum), _dp(self.tiles6))
+                         _dp(self.colsum), _dp(self.tiles6), _dp(self.tiles8))
 
 
 class DeviceQAct:

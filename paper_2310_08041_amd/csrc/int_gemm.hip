@@ -46,6 +46,7 @@ struct GemmArgs {
     int32_t *partial; // [splits][N][O] raw accumulators when K is split over workgroups, else unused
     int32_t splits;
     const uint8_t *a_tiles, *w_tiles; // both operands as 6-bit fields in matrix-core order (see TILES6 below), or null
+    const uint8_t *a_tiles8, *w_tiles8; // both operands as bytes in matrix-core order (see TILES8 below), or null
 };
 
 template <int BITS>
@@ -219,7 +220,7 @@ __device__ __forceinline__ int32_t acc_int(const v4f &a, int r) { return (int32_
 
 template <int ABITS, int WBITS, typename YT, int NI, int NJ, typename ACC>
 __device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const ACC (&acc)[NI][NJ], int n_base, int o_base,
-                                                 int lane)
+                                                 int lane, int32_t k_biased = -1)
 {
     constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
     int32_t cs[NJ][4], bw[NJ][4];
@@ -235,7 +236,9 @@ __device__ __forceinline__ void finish_wave_tile(const GemmArgs &g, const ACC (&
             aw[j][r] = g.aw[o];
             cols_small = cols_small && abs(bw[j][r]) < g.small_zero;
         }
-    const int32_t k_off = 16384 * SA * SW * g.Kpad;
+    // 8-bit codes went into the matrix cores as code - 128; where both sides did, every place of K that held such a
+    // pair adds 128 * 128: the padded row length, unless the kernel says how many places it summed that way
+    const int32_t k_off = 16384 * SA * SW * (k_biased >= 0 ? k_biased : g.Kpad);
 
     // The usual case, decided once for the wave: the tile lies inside Y, Y's rows are aligned for whole stores, nobody
     // asked for the raw accumulators, and every zero-point of the tile is small.  Then the tile is straight-line
@@ -913,6 +916,172 @@ __global__ __launch_bounds__(256) void tiles6_kernel(const uint8_t *codes, int64
     *reinterpret_cast<uint2 *>(blk + T6_X + 8 * l) = make_uint2((s[5] >> 8) | (s[6] << 16), (s[6] >> 16) | (s[7] << 8));
 }
 
+// ---- 6- and 8-bit codes (and 8-bit activations on 4-bit weights) straight from LDS into the int8 matrix cores.
+// TILES8, the operand format (made once per weight by qllm_pack_tiles8, per call for the activations): one byte
+// per code, rows in blocks of 16, K in tiles of 64 codes; block b, K-tile t is the 1024 bytes at
+// (b * tiles + t) * 1024 and holds what the 64 lanes of one operand read need: lane l = 16 q + r has row
+// 16 b + r and codes 64 t + 16 q + e, e = 0..15, at byte 16 l + e.  A 4- or 6-bit code is its own value; an 8-bit
+// code c is stored as c ^ 0x80, the signed byte c - 128 (the epilogue adds the difference back).  Rows past the
+// matrix and places past K are zero bytes: they add nothing.  As with TILES6 a stage of LDS is such blocks as
+// they lie in memory, the refill a plain copy by 16-byte loads that write LDS directly, an operand read one
+// contiguous ds_read_b128 per wave, and there is no vector instruction between LDS and the matrix cores (the
+// kernels that expand packed codes at refill time spend most of their issue slots on that).
+// Tiling, ring, group plan and loop rotation are those of gemm_w4a4_fp6_kernel; one K-tile here is 64 codes,
+// which takes the int8 matrix cores as long as 128 codes take the FP6 ones.
+constexpr int T8_BLOCK = 1024, T8_KT = 64, T8_STAGES = 3;
+
+template <int ABITS, int WBITS, typename YT, int MI, int NJ>
+__global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_tiles8_kernel(const GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int TM = 2 * MI * 16, TN = 4 * NJ * 16;
+    constexpr int BLOCKS = (TM + TN) / 16, STAGE = BLOCKS * T8_BLOCK, NLOAD = STAGE / (8 * 1024);
+    static_assert(STAGE % (8 * 1024) == 0 && NLOAD <= MI, "a stage is a whole number of 1 KB loads per wave, one per group");
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int n0 = blockIdx.y * TM, o0 = blockIdx.x * TN;
+    const int all_kt = (g.K + T8_KT - 1) / T8_KT;
+    const int a_blocks = (g.N + 15) / 16, w_blocks = (g.O + 15) / 16;
+
+    // fetch assignment: load t of wave w fills block NLOAD w + t of the stage, lane l its l-th 16 bytes; a load is
+    // all token side or all feature side: one base for the wave, a 32-bit offset per lane that never changes
+    uint32_t src_off[NLOAD];
+#pragma unroll
+    for (int t = 0; t < NLOAD; ++t) {
+        const int blk = wave * NLOAD + t;
+        const bool token = blk < TM / 16; // past the edge: the last block again (its results are not stored)
+        const int rb = token ? min(n0 / 16 + blk, a_blocks - 1) : min(o0 / 16 + blk - TM / 16, w_blocks - 1);
+        src_off[t] = (uint32_t)rb * (uint32_t)all_kt * T8_BLOCK + lane * 16;
+    }
+    auto fetch_one = [&](int kt, int stage, int t) { // load t of K-tile kt (clamped to the last one) -> that stage
+        const int ktc = min(kt, all_kt - 1);
+        const bool token = wave * NLOAD + t < TM / 16;
+        const uint8_t *base = (token ? g.a_tiles8 : g.w_tiles8) + (int64_t)ktc * T8_BLOCK;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + src_off[t]),
+                                         (__attribute__((address_space(3))) void *)(lds + stage * STAGE + (wave * NLOAD + t) * 1024), 16, 0,
+                                         0);
+    };
+    auto fetch = [&](int kt, int stage) {
+#pragma unroll
+        for (int t = 0; t < NLOAD; ++t) fetch_one(kt, stage, t);
+    };
+    constexpr int WAIT_LANDED = NLOAD | (7 << 4) | (15 << 8);       // s_waitcnt vmcnt(NLOAD): all but the newest fetch
+    constexpr int WAIT_LANDED_LGKM0 = NLOAD | (7 << 4) | (0 << 8);  // ... and lgkmcnt(0)
+
+    v4i acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+    fetch(0, 0);
+    fetch(1, 1);
+    __builtin_amdgcn_s_waitcnt(WAIT_LANDED);
+    __syncthreads();
+
+    constexpr int RING = MI, AHEAD = 2, PER_STEP = MI == 8 ? 2 : 1;
+    static_assert(MI % PER_STEP == 0 && (MI - 1) / PER_STEP > AHEAD - 1 && (MI - AHEAD) / PER_STEP > 0, "group plan");
+    v4i ar[RING], wr[2][NJ];
+#pragma unroll
+    for (int k = 0; k < RING; ++k) ar[k] = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) wr[0][j] = wr[1][j] = v4i{0, 0, 0, 0};
+
+    const int a_blk0 = wm * MI, w_blk0 = TM / 16 + wn * NJ; // the wave's first token-side and feature-side block of a stage
+    int stage = 0, fetch_stage = 2;
+    auto k_tile = [&](auto parity, int kt) {
+        constexpr int P = decltype(parity)::value;
+        const uint8_t *cur = lds + stage * STAGE;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) wr[P][j] = *reinterpret_cast<const v4i *>(cur + (w_blk0 + j) * T8_BLOCK + 16 * lane);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < MI; ++u) {
+            const bool old = u < AHEAD;
+            const int i = old ? MI - AHEAD + u : u - AHEAD;
+            if (u < NLOAD) fetch_one(kt + 2, fetch_stage, u); // one load per group, not all at once
+            if (PER_STEP * u < MI) {
+#pragma unroll
+                for (int h = 0; h < PER_STEP; ++h)
+                    ar[PER_STEP * u + h] = *reinterpret_cast<const v4i *>(cur + (a_blk0 + PER_STEP * u + h) * T8_BLOCK + 16 * lane);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wr[old ? 1 - P : P][j], ar[i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the next K-tile has landed (this wave's share; the barrier adds the others'), own reads done
+        __builtin_amdgcn_s_waitcnt(WAIT_LANDED_LGKM0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        fetch_stage = stage;
+        stage = stage == T8_STAGES - 1 ? 0 : stage + 1;
+    };
+    int kt = 0;
+    for (; kt + 1 < all_kt; kt += 2) {
+        k_tile(std::integral_constant<int, 0>{}, kt);
+        k_tile(std::integral_constant<int, 1>{}, kt + 1);
+    }
+    if (kt < all_kt) k_tile(std::integral_constant<int, 0>{}, kt);
+    // the loads past the last K-tile went to stages nobody reads; they must not outlive the workgroup
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    auto last_groups = [&](auto parity) { // the last groups of the last K-tile
+        constexpr int P = decltype(parity)::value;
+#pragma unroll
+        for (int i = MI - AHEAD; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wr[P][j], ar[i], acc[i][j], 0, 0, 0);
+    };
+    if (all_kt & 1) last_groups(std::integral_constant<int, 0>{});
+    else last_groups(std::integral_constant<int, 1>{});
+
+    // places past K are zero bytes on both sides, so only the K real places carry the two offsets of 128
+    finish_wave_tile<ABITS, WBITS, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane, g.K);
+}
+
+// Packed rows -> TILES8; one lane per (block, K-tile, lane of the operand read): 16 codes of one row.
+template <int BITS>
+__global__ __launch_bounds__(256) void tiles8_kernel(const uint8_t *codes, int64_t row_bytes, int32_t rows, int32_t K, int32_t n_kt,
+                                                    uint8_t *tiles, int64_t n_items)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_items) return;
+    const int l = (int)(idx & 63), r = l & 15, q = l >> 4;
+    const int64_t bk = idx >> 6, b = bk / n_kt;
+    const int kt = (int)(bk - b * n_kt);
+    const int64_t row = b * 16 + r;
+    const int k0 = kt * T8_KT + 16 * q; // the lane's first code
+    uint32_t d[4] = {0u, 0u, 0u, 0u};
+    if (row < rows && k0 < K) {
+        // the lane's 2 * BITS bytes of the packed row, dword by dword; what lies past the row's end reads as zero codes
+        const int64_t at = (int64_t)k0 * BITS / 8; // a multiple of 4
+        const uint8_t *src = codes + row * row_bytes + at;
+        uint32_t w[BITS / 2];
+#pragma unroll
+        for (int i = 0; i < BITS / 2; ++i) w[i] = at + 4 * i < row_bytes ? reinterpret_cast<const uint32_t *>(src)[i] : 0u;
+        if constexpr (BITS == 4) {
+            expand4(w[0], d[0], d[1]);
+            expand4(w[1], d[2], d[3]);
+        } else if constexpr (BITS == 6) {
+            d[0] = spread6(w[0]);
+            d[1] = spread6(__builtin_amdgcn_alignbit(w[1], w[0], 24));
+            d[2] = spread6(__builtin_amdgcn_alignbit(w[2], w[1], 16));
+            d[3] = spread6(w[2] >> 8);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // code - 128 as a signed byte, in the places that hold a code
+                const int left = K - (k0 + 4 * i);
+                const uint32_t live = left >= 4 ? 0xffffffffu : left <= 0 ? 0u : (1u << (8 * left)) - 1u;
+                d[i] = (w[i] ^ 0x80808080u) & live;
+            }
+        }
+    }
+    *reinterpret_cast<uint4 *>(tiles + bk * T8_BLOCK + 16 * l) = make_uint4(d[0], d[1], d[2], d[3]);
+}
+
 // Sum of the parts of a split K and the dequantising epilogue (4-bit codes on both sides: no offsets),
 // one output per lane; the bracket in 64-bit arithmetic, which gives the same float as the narrow form.
 template <typename YT>
@@ -1142,6 +1311,47 @@ int32_t launch_fp6(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
     return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
 }
 
+// Packed rows (device) -> TILES8 (device).
+int32_t launch_tiles8(const uint8_t *codes, int32_t bits, int64_t rows, int64_t K, uint8_t *tiles, hipStream_t stream)
+{
+    const int64_t n_kt = (K + T8_KT - 1) / T8_KT, n_items = (rows + 15) / 16 * n_kt * 64;
+    const dim3 grid((unsigned)((n_items + 255) / 256));
+    const int64_t row_bytes = qllm_packed_row_bytes(K, bits);
+    (void)hipGetLastError();
+    if (bits == 4) hipLaunchKernelGGL(tiles8_kernel<4>, grid, dim3(256), 0, stream, codes, row_bytes, (int32_t)rows, (int32_t)K, (int32_t)n_kt, tiles, n_items);
+    else if (bits == 6) hipLaunchKernelGGL(tiles8_kernel<6>, grid, dim3(256), 0, stream, codes, row_bytes, (int32_t)rows, (int32_t)K, (int32_t)n_kt, tiles, n_items);
+    else hipLaunchKernelGGL(tiles8_kernel<8>, grid, dim3(256), 0, stream, codes, row_bytes, (int32_t)rows, (int32_t)K, (int32_t)n_kt, tiles, n_items);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        qllm_note_hip_error("tiles8: launch", hipGetErrorName(e));
+        return QLLM_ERR_HIP;
+    }
+    return QLLM_OK;
+}
+
+// 6- or 8-bit activations, more than 32 tokens, byte operands straight into the int8 matrix cores: the
+// activations are re-laid into the workspace, then the product.  Tile choice as on the FP6 path.
+template <int ABITS, int WBITS>
+int32_t launch_t8(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
+{
+    const int32_t st = launch_tiles8(g.a_codes, ABITS, g.N, g.K, const_cast<uint8_t *>(g.a_tiles8), stream);
+    if (st != QLLM_OK) return st;
+    const int64_t big_tiles = (int64_t)((g.O + LBN - 1) / LBN) * ((g.N + LBM - 1) / LBM);
+    const int64_t small_tiles = (int64_t)((g.O + 127) / 128) * ((g.N + 127) / 128);
+    const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
+    const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
+    if (g.N <= 128 || big_fill < 0.78 * small_fill) {
+        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
+        constexpr size_t lds = (size_t)T8_STAGES * 16 * T8_BLOCK;
+        if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+        return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+    }
+    const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
+    constexpr size_t lds = (size_t)T8_STAGES * 32 * T8_BLOCK;
+    if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
+    return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
+}
+
 template <int ABITS, int WBITS>
 int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
@@ -1169,6 +1379,8 @@ int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
                 return launch_kernel(int_gemm_w4a4_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
             return launch_kernel(int_gemm_w4a4_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
         }
+    } else {
+        if (g.a_tiles8 && g.w_tiles8) return launch_t8<ABITS, WBITS>(g, y_dtype, stream);
     }
     if (g.N > 128) { // enough tokens to fill 256-row tiles
         const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
@@ -1246,7 +1458,9 @@ extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, in
 {
     const int64_t floor_bytes = qllm_gemm_workspace_floor_bytes(N, K, O, a_bits);
     if (floor_bytes != 0) return floor_bytes; // an error, or K is split (then the FP6 path is not taken)
-    return a_bits == 4 && N > 32 && 225 * K < (1 << 24) ? qllm_tiles6_bytes(N, K) : 0;
+    if (N <= 32) return 0;
+    if (a_bits == 4) return 225 * K < (1 << 24) ? qllm_tiles6_bytes(N, K) : 0;
+    return qllm_tiles8_bytes(N, K);
 }
 
 extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
@@ -1292,6 +1506,14 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
         g.a_tiles = static_cast<const uint8_t *>(workspace);
         g.w_tiles = w->tiles6;
     }
+    // the byte-operand path of the other bit pairs: more than 32 tokens, the weight's tiles at hand and room for the
+    // activations' in the workspace
+    if (!(a_bits == 4 && wb == 4) && w->tiles8 && N > 32 && workspace && workspace_bytes >= qllm_tiles8_bytes(N, w->K) &&
+        qllm_tiles8_bytes(N, w->K) < (1ll << 32) && qllm_tiles8_bytes(w->O, w->K) < (1ll << 32)) {
+        if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (reinterpret_cast<uintptr_t>(w->tiles8) & 15u)) return QLLM_ERR_ALIGN;
+        g.a_tiles8 = static_cast<const uint8_t *>(workspace);
+        g.w_tiles8 = w->tiles8;
+    }
     g.small_zero = small_zero_bound(w->K, a_bits, wb);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (a_bits == 4) return launch<4, 4>(g, y_dtype, stream);
@@ -1315,6 +1537,22 @@ extern "C" int32_t qllm_pack_tiles6(const uint8_t *codes, int64_t rows, int64_t 
     if (rows == 0) return QLLM_OK;
     const int64_t Kpad = (K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD;
     return launch_tiles6(codes, qllm_packed_row_bytes(K, 4), rows, Kpad, tiles, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int64_t qllm_tiles8_bytes(int64_t rows, int64_t K)
+{
+    if (rows < 0 || K <= 0) return QLLM_ERR_SHAPE;
+    return (rows + 15) / 16 * ((K + T8_KT - 1) / T8_KT) * T8_BLOCK;
+}
+
+extern "C" int32_t qllm_pack_tiles8(const uint8_t *codes, int32_t bits, int64_t rows, int64_t K, uint8_t *tiles, void *hip_stream)
+{
+    if (!codes || !tiles) return QLLM_ERR_NULL;
+    if (bits != 4 && bits != 6 && bits != 8) return QLLM_ERR_BITS;
+    if (rows < 0 || rows > INT32_MAX || K <= 0 || K > (1 << 24)) return QLLM_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(codes) & 15u) || (reinterpret_cast<uintptr_t>(tiles) & 15u)) return QLLM_ERR_ALIGN;
+    if (rows == 0) return QLLM_OK;
+    return launch_tiles8(codes, bits, rows, K, tiles, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
 namespace {

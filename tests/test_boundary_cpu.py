@@ -63,7 +63,12 @@ def test_packed_row_bytes_and_workspace():
     assert b.qllm_tiles6_bytes(2048, 28672) == 2048 // 16 * (28672 // 128) * 1536
     assert b.qllm_tiles6_bytes(17, 100) == 2 * 2 * 1536                     # rows up to 32, K up to 256
     assert b.qllm_gemm_workspace_bytes(2048, 28672, 8192, 4) == b.qllm_tiles6_bytes(2048, 28672)
-    assert b.qllm_gemm_workspace_bytes(16, 8192, 8192, 4) == 0 and b.qllm_gemm_workspace_bytes(2048, 8192, 8192, 6) == 0
+    assert b.qllm_gemm_workspace_bytes(16, 8192, 8192, 4) == 0 and b.qllm_gemm_workspace_bytes(16, 8192, 8192, 6) == 0
+    # the byte-operand path of 6- and 8-bit activations: one byte per code, rows in blocks of 16, K in tiles of 64
+    assert b.qllm_tiles8_bytes(2048, 28672) == 2048 * 28672 and b.qllm_tiles8_bytes(17, 100) == 2 * 2 * 1024
+    assert b.qllm_gemm_workspace_bytes(2048, 8192, 8192, 6) == b.qllm_tiles8_bytes(2048, 8192)
+    assert b.qllm_gemm_workspace_bytes(40, 100, 8192, 8) == b.qllm_tiles8_bytes(40, 100)
+    assert b.qllm_workspace_bytes(2048, 8192, 8192, 6) == b.qllm_workspace_floor_bytes(2048, 8192, 8192, 6) + b.qllm_tiles8_bytes(2048, 8192)
     assert b.qllm_workspace_bytes(2048, 28672, 8192, 4) == b.qllm_workspace_floor_bytes(2048, 28672, 8192, 4) + b.qllm_tiles6_bytes(2048, 28672)
     assert b.qllm_workspace_floor_bytes(2048, 28672, 8192, 4) == 2048 * 14336 + 3 * 2048 * 4
 
@@ -150,6 +155,24 @@ def test_tiles6_entry_points_reject_bad_arguments_before_launching():
     assert f(0x1008, 16, 128, 0x2000, None) == -6 and f(0x1000, 16, 128, 0x2004, None) == -6
     assert f(0x1000, 0, 128, 0x2000, None) == 0
     assert lib.qllm_tiles6_bytes(-1, 128) == -2 and lib.qllm_tiles6_bytes(16, 0) == -2
+
+
+def test_tiles8_entry_points_reject_bad_arguments_before_launching():
+    lib = b.raw()
+    f = lib.qllm_pack_tiles8
+    assert f(None, 6, 16, 128, 0x2000, None) == -1 and f(0x1000, 6, 16, 128, None, None) == -1
+    assert f(0x1000, 5, 16, 128, 0x2000, None) == -3 and f(0x1000, 0, 16, 128, 0x2000, None) == -3
+    assert f(0x1000, 8, -1, 128, 0x2000, None) == -2 and f(0x1000, 8, 16, 0, 0x2000, None) == -2
+    assert f(0x1008, 4, 16, 128, 0x2000, None) == -6 and f(0x1000, 4, 16, 128, 0x2004, None) == -6
+    assert f(0x1000, 6, 0, 128, 0x2000, None) == 0
+    assert lib.qllm_tiles8_bytes(-1, 128) == -2 and lib.qllm_tiles8_bytes(16, 0) == -2
+    # a weight's byte copy must be 16-byte aligned, and so must the workspace that receives the activations'
+    q = b._QAct(0x1000, 0x1000, 0x1000, 0x1000)
+    g = lib.qllm_int_gemm
+    bad = b._Weight(32, 64, 6, 0x1000, 0x1000, 0x1000, 0x1000, None, 0x5008)
+    assert g(C.byref(q), 6, 64, C.byref(bad), 0x9000, b.F32, 32, None, 0x4000, 1 << 20, None) == -6
+    good = b._Weight(32, 64, 6, 0x1000, 0x1000, 0x1000, 0x1000, None, 0x5000)
+    assert g(C.byref(q), 6, 64, C.byref(good), 0x9000, b.F32, 32, None, 0x4008, 1 << 20, None) == -6
 
 
 def test_swiglu_entry_point_rejects_bad_arguments_before_launching():

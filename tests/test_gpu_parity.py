@@ -278,9 +278,10 @@ def random_gemm_case(rng, N, K, O, a_bits, w_bits):
     return a, w, ax, aw, bx, bw
 
 
-def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True, tiles6=True):
-    """tiles6 (4-bit weights only): give the weight its FP6-path copy; the workspace has room for that path either way,
-    so False is what sends a 4-bit shape down the int8 path."""
+def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True, tiles6=True, tiles8=True):
+    """tiles6 (4-bit codes on both sides): give the weight its FP6-path copy; the workspace has room for that path either
+    way, so False is what sends a 4-bit shape down the int8 path.  tiles8 (the other bit pairs): give the weight its
+    one-byte-per-code copy; False sends the shape to the kernels that expand packed codes themselves."""
     import torch
     N, K = a.shape
     O = w.shape[0]
@@ -290,7 +291,7 @@ def run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, dump=True, tiles6
     qa.zero.copy_(torch.from_numpy(bx))
     qa.rowsum.copy_(torch.from_numpy(a.astype(np.int64).sum(1).astype(np.int32)))
     dw = b.DeviceWeight(b.qllm_pack_codes_host(w, w_bits), aw, bw, w.astype(np.int64).sum(1).astype(np.int32), K, w_bits,
-                        tiles6=tiles6)
+                        tiles6=tiles6, tiles8=tiles8 and not (a_bits == 4 and w_bits == 4))
     y = torch.full((N, O), float("nan"), dtype=torch.float32 if y_dtype == "f32" else torch.bfloat16, device="cuda")
     acc = torch.full((N, O), -1, dtype=torch.int32, device="cuda") if dump else None
     ws_bytes = b.qllm_gemm_workspace_bytes(N, K, O, a_bits)     # partial sums where K is split, else room for the FP6 path
@@ -325,9 +326,9 @@ def test_gemm_small_shapes(oracle, b, a_bits, w_bits, N, K, O, y_dtype):
     a, w, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, a_bits, w_bits)
     ref_acc = oracle.int_gemm(a, w)
     ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
-    for tiles6 in ((True, False) if a_bits == 4 and w_bits == 4 and N > 32 else (True,)):   # both matrix-core paths
-        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, tiles6=tiles6)
-        assert np.array_equal(acc.cpu().numpy(), ref_acc), tiles6
+    for tiles in ((True, False) if N > 32 else (True,)):   # FP6 / byte-operand path, and the kernels that unpack
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, y_dtype, tiles6=tiles, tiles8=tiles)
+        assert np.array_equal(acc.cpu().numpy(), ref_acc), tiles
         check_y(oracle, y, ref_y, y_dtype)
 
 
@@ -368,6 +369,52 @@ def test_tiles6_layout(b, rows, K):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("bits", [4, 6, 8])
+@pytest.mark.parametrize("rows,K", [(1, 1), (16, 64), (37, 700), (300, 5000)])
+def test_tiles8_layout(b, bits, rows, K):
+    """qllm_pack_tiles8 against its documented layout: byte 16 l + e of block b, K-tile t is code 64 t + 16 (l / 16) + e
+    of row 16 b + l % 16 (XOR 0x80 for 8-bit codes), zero bytes in rows past the matrix and places past K."""
+    import torch
+    rng = np.random.default_rng(rows * 7 + K + bits)
+    codes = rng.integers(0, 2 ** bits, (rows, K), dtype=np.uint8)
+    packed = torch.from_numpy(b.qllm_pack_codes_host(codes, bits)).cuda()
+    tiles = torch.full((b.qllm_tiles8_bytes(rows, K),), 0xEE, dtype=torch.uint8, device="cuda")
+    b.qllm_pack_tiles8(packed, bits, rows, K, tiles)
+    torch.cuda.synchronize()
+    nb, n_kt = -(-rows // 16), -(-K // 64)
+    assert tiles.numel() == nb * n_kt * 1024
+    t = tiles.cpu().numpy().reshape(nb, n_kt, 4, 16, 16)            # block, K-tile, q, r, e
+    got = t.transpose(0, 3, 1, 2, 4).reshape(nb * 16, n_kt * 64)     # row 16 b + r, code 64 t + 16 q + e
+    want = np.zeros_like(got)
+    want[:rows, :K] = codes ^ 0x80 if bits == 8 else codes
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("a_bits,w_bits", [(6, 6), (8, 8), (8, 4)])
+def test_gemm_byte_operands_at_the_70b_shape(oracle, b, a_bits, w_bits):
+    """The other bit pairs of Sec. 5 at the headline shape, on the byte-operand path and on the kernels that unpack:
+    all tokens x 48 sampled output features and 24 sampled tokens x all output features against the oracle, the sums
+    over the output axis against numpy."""
+    import torch
+    N, K, O = 2048, 28672, 8192
+    rng = np.random.default_rng(a_bits * 10 + w_bits)
+    a, wc, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, a_bits, w_bits)
+    cols = np.sort(rng.choice(O, 48, replace=False))
+    rows = np.sort(rng.choice(N, 24, replace=False))
+    ref_cols, ref_rows_acc = oracle.int_gemm(a, wc[cols]), oracle.int_gemm(a[rows], wc)
+    row_sums = a.astype(np.int64) @ wc.astype(np.int64).sum(0)
+    rs, cs = a.astype(np.int64).sum(1), wc.astype(np.int64).sum(1)
+    for tiles8 in (True, False):
+        y, acc = run_gemm(b, a, wc, ax, aw, bx, bw, a_bits, w_bits, "bf16", tiles8=tiles8)
+        acc = acc.cpu().numpy()
+        assert np.array_equal(acc[:, cols], ref_cols), tiles8
+        assert np.array_equal(acc[rows], ref_rows_acc), tiles8
+        assert np.array_equal(acc.astype(np.int64).sum(1), row_sums), tiles8
+        ref_rows = oracle.epilogue(acc[rows], K, ax[rows], bx[rows], rs[rows], aw, bw, cs)
+        got_rows = oracle.widen_bf16(y[torch.from_numpy(rows).cuda()].view(torch.int16).cpu().numpy().view(np.uint16))
+        assert rel_err(got_rows, ref_rows).max() <= TOL["bf16"], tiles8
+
+
 @pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
 def test_gemm_large_tiles_ragged(oracle, b, y_dtype):
     """W4A4 with enough 256 x 256 tiles (9 x 22) for the large-tile kernel to be chosen, ragged in both
@@ -390,6 +437,13 @@ def test_gemm_extreme_codes(oracle, b):
         w = np.full((33, K), 2 ** bits - 1, np.uint8)
         ax, aw = np.ones(17, np.float32), np.ones(33, np.float32)
         bx, bw = np.zeros(17, np.int32), np.zeros(33, np.int32)
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, bits, bits, "f32")
+        assert np.all(acc.cpu().numpy() == (2 ** bits - 1) ** 2 * K)
+    for bits, K in [(6, 8192), (8, 28672)]:                         # enough tokens for the byte-operand path
+        a = np.full((130, K), 2 ** bits - 1, np.uint8)
+        w = np.full((33, K), 2 ** bits - 1, np.uint8)
+        ax, aw = np.ones(130, np.float32), np.ones(33, np.float32)
+        bx, bw = np.zeros(130, np.int32), np.zeros(33, np.int32)
         y, acc = run_gemm(b, a, w, ax, aw, bx, bw, bits, bits, "f32")
         assert np.all(acc.cpu().numpy() == (2 ** bits - 1) ** 2 * K)
 
@@ -428,13 +482,14 @@ def test_gemm_extreme_codes_with_negative_zero_points(oracle, b, N, zx, zw):
     w[1::2, ::3] = 7                                                # not every column the same
     ax, aw = np.full(N, 2.0 ** -20, np.float32), np.full(O, 0.5, np.float32)
     bx, bw = np.full(N, zx, np.int32), np.full(O, zw, np.int32)
-    y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 8, 8, "f32")
     ref_acc = oracle.int_gemm(a, w)
-    assert np.array_equal(acc.cpu().numpy(), ref_acc)
     ref_y = oracle.epilogue(ref_acc, K, ax, bx, a.astype(np.int64).sum(1), aw, bw, w.astype(np.int64).sum(1))
     exact = (a.astype(np.int64) - zx) @ (w.astype(np.int64) - zw).T   # the bracket itself, in 64 bits
     assert np.allclose(ref_y, exact.astype(np.float64) * 2.0 ** -21, rtol=1e-6)
-    check_y(oracle, y, ref_y, "f32")
+    for tiles8 in ((True, False) if N > 32 else (True,)):
+        y, acc = run_gemm(b, a, w, ax, aw, bx, bw, 8, 8, "f32", tiles8=tiles8)
+        assert np.array_equal(acc.cpu().numpy(), ref_acc), tiles8
+        check_y(oracle, y, ref_y, "f32")
 
 
 @pytest.mark.parametrize("name", FULL)
