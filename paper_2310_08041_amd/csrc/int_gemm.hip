@@ -930,7 +930,9 @@ __global__ __launch_bounds__(256) void tiles6_kernel(const uint8_t *codes, int64
 // which takes the int8 matrix cores as long as 128 codes take the FP6 ones.
 constexpr int T8_BLOCK = 1024, T8_KT = 64, T8_STAGES = 3;
 
-template <int ABITS, int WBITS, typename YT, int MI, int NJ>
+// SPLIT: K is dealt out to gridDim.z workgroups per tile of Y (so few tiles that most CUs would idle); each writes
+// its raw accumulators to g.partial and splitk_finish_kernel adds them up and does the epilogue.
+template <int ABITS, int WBITS, typename YT, int MI, int NJ, bool SPLIT = false>
 __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_tiles8_kernel(const GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -974,8 +976,11 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_tiles8_kernel(
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
-    fetch(0, 0);
-    fetch(1, 1);
+    // this workgroup's K-tiles (fetches past them, up to the last K-tile of the row, go to stages nobody reads)
+    const int kt_first = SPLIT ? (int)((int64_t)all_kt * blockIdx.z / gridDim.z) : 0;
+    const int kt_end = SPLIT ? (int)((int64_t)all_kt * (blockIdx.z + 1) / gridDim.z) : all_kt;
+    fetch(kt_first, 0);
+    fetch(kt_first + 1, 1);
     __builtin_amdgcn_s_waitcnt(WAIT_LANDED);
     __syncthreads();
 
@@ -1019,12 +1024,12 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_tiles8_kernel(
         fetch_stage = stage;
         stage = stage == T8_STAGES - 1 ? 0 : stage + 1;
     };
-    int kt = 0;
-    for (; kt + 1 < all_kt; kt += 2) {
+    int kt = kt_first;
+    for (; kt + 1 < kt_end; kt += 2) {
         k_tile(std::integral_constant<int, 0>{}, kt);
         k_tile(std::integral_constant<int, 1>{}, kt + 1);
     }
-    if (kt < all_kt) k_tile(std::integral_constant<int, 0>{}, kt);
+    if (kt < kt_end) k_tile(std::integral_constant<int, 0>{}, kt);
     // the loads past the last K-tile went to stages nobody reads; they must not outlive the workgroup
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
     auto last_groups = [&](auto parity) { // the last groups of the last K-tile
@@ -1034,11 +1039,33 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_tiles8_kernel(
 #pragma unroll
             for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wr[P][j], ar[i], acc[i][j], 0, 0, 0);
     };
-    if (all_kt & 1) last_groups(std::integral_constant<int, 0>{});
+    if ((kt_end - kt_first) & 1) last_groups(std::integral_constant<int, 0>{});
     else last_groups(std::integral_constant<int, 1>{});
 
-    // places past K are zero bytes on both sides, so only the K real places carry the two offsets of 128
-    finish_wave_tile<ABITS, WBITS, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane, g.K);
+    if constexpr (SPLIT) {
+        // raw accumulators of this part of K: token n, four consecutive features per lane and tile
+        int32_t *part = g.partial + (int64_t)blockIdx.z * g.N * g.O;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int n = n0 + wm * 16 * MI + i * 16 + (lane & 15);
+            if (n >= g.N) continue;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int o = o0 + wn * 16 * NJ + j * 16 + 4 * (lane >> 4);
+                int32_t *p = part + (int64_t)n * g.O + o;
+                if (o + 3 < g.O && (g.O & 3) == 0) {
+                    *reinterpret_cast<v4i *>(p) = acc[i][j];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (o + e < g.O) p[e] = acc[i][j][e];
+                }
+            }
+        }
+    } else {
+        // places past K are zero bytes on both sides, so only the K real places carry the two offsets of 128
+        finish_wave_tile<ABITS, WBITS, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane, g.K);
+    }
 }
 
 // Packed rows -> TILES8; one lane per (block, K-tile, lane of the operand read): 16 codes of one row.
@@ -1082,9 +1109,10 @@ __global__ __launch_bounds__(256) void tiles8_kernel(const uint8_t *codes, int64
     *reinterpret_cast<uint4 *>(tiles + bk * T8_BLOCK + 16 * l) = make_uint4(d[0], d[1], d[2], d[3]);
 }
 
-// Sum of the parts of a split K and the dequantising epilogue (4-bit codes on both sides: no offsets),
-// one output per lane; the bracket in 64-bit arithmetic, which gives the same float as the narrow form.
-template <typename YT>
+// Sum of the parts of a split K and the dequantising epilogue, one output per lane; the bracket in 64-bit
+// arithmetic, which gives the same float as the narrow form.  SA / SW: that side's codes are 8-bit and went into
+// the matrix cores as code - 128 in every one of the K places (the byte-operand path), which is added back here.
+template <typename YT, int SA = 0, int SW = 0>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const GemmArgs g)
 {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1092,6 +1120,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const GemmArgs g)
     const int n = (int)(idx / g.O), o = (int)(idx % g.O);
     int32_t raw = 0; // the true accumulator fits int32 (checked by the launcher), so wrapping sums are exact
     for (int z = 0; z < g.splits; ++z) raw += g.partial[(int64_t)z * g.N * g.O + idx];
+    raw += 128 * SW * g.rs[n] + 128 * SA * g.cs[o] - 16384 * SA * SW * g.K;
     const int64_t bx = g.bx[n], bw = g.bw[o];
     const int64_t t = (int64_t)raw - bx * g.cs[o] - bw * g.rs[n] + (int64_t)g.K * bx * bw;
     float v = (float)t;
@@ -1329,20 +1358,48 @@ int32_t launch_tiles8(const uint8_t *codes, int32_t bits, int64_t rows, int64_t 
     return QLLM_OK;
 }
 
+// The byte-operand path's tile: 128 x 128 (two workgroups per CU) where that fills the chip's rounds better than
+// 256 x 256, as on the FP6 path, and for up to 128 tokens.
+bool t8_small_tile(int64_t N, int64_t O)
+{
+    const int64_t big_tiles = ((O + LBN - 1) / LBN) * ((N + LBM - 1) / LBM);
+    const int64_t small_tiles = ((O + 127) / 128) * ((N + 127) / 128);
+    const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
+    const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
+    return N <= 128 || big_fill < 0.78 * small_fill;
+}
+
+// Into how many parts the byte-operand path splits K when it has room for the parts' accumulators: as on the
+// 4-bit path, only where 128 x 128 tiles leave most CUs without a workgroup, every part at least eight K-tiles.
+int32_t t8_splits(int64_t N, int64_t K, int64_t O)
+{
+    if (N <= 32 || !t8_small_tile(N, O)) return 1;
+    const int64_t tiles = ((O + 127) / 128) * ((N + 127) / 128), n_kt = (K + T8_KT - 1) / T8_KT;
+    if (tiles > 128) return 1;
+    int64_t s = 256 / tiles;
+    if (s > 4) s = 4;
+    if (s > n_kt / 8) s = n_kt / 8;
+    return s < 2 ? 1 : (int32_t)s;
+}
+
 // 6- or 8-bit activations, more than 32 tokens, byte operands straight into the int8 matrix cores: the
-// activations are re-laid into the workspace, then the product.  Tile choice as on the FP6 path.
+// activations are re-laid into the workspace, then the product.
 template <int ABITS, int WBITS>
 int32_t launch_t8(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     const int32_t st = launch_tiles8(g.a_codes, ABITS, g.N, g.K, const_cast<uint8_t *>(g.a_tiles8), stream);
     if (st != QLLM_OK) return st;
-    const int64_t big_tiles = (int64_t)((g.O + LBN - 1) / LBN) * ((g.N + LBM - 1) / LBM);
-    const int64_t small_tiles = (int64_t)((g.O + 127) / 128) * ((g.N + 127) / 128);
-    const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
-    const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
-    if (g.N <= 128 || big_fill < 0.78 * small_fill) {
-        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
+    if (t8_small_tile(g.N, g.O)) {
+        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128), (unsigned)(g.splits > 1 ? g.splits : 1));
         constexpr size_t lds = (size_t)T8_STAGES * 16 * T8_BLOCK;
+        if (g.splits > 1) {
+            const int32_t sp = launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2, true>, grid, dim3(LTHREADS), lds, g, stream);
+            if (sp != QLLM_OK) return sp;
+            constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
+            const dim3 fgrid((unsigned)(((int64_t)g.N * g.O + 255) / 256));
+            if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float, SA, SW>, fgrid, dim3(256), 0, g, stream);
+            return launch_kernel(splitk_finish_kernel<uint16_t, SA, SW>, fgrid, dim3(256), 0, g, stream);
+        }
         if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
         return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
     }
@@ -1460,7 +1517,9 @@ extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, in
     if (floor_bytes != 0) return floor_bytes; // an error, or K is split (then the FP6 path is not taken)
     if (N <= 32) return 0;
     if (a_bits == 4) return 225 * K < (1 << 24) ? qllm_tiles6_bytes(N, K) : 0;
-    return qllm_tiles8_bytes(N, K);
+    // the byte-operand path: the activations' bytes, then the parts' accumulators where it splits K
+    const int32_t s8 = t8_splits(N, K, O);
+    return (qllm_tiles8_bytes(N, K) + 255) / 256 * 256 + (s8 > 1 ? (int64_t)s8 * N * O * (int64_t)sizeof(int32_t) : 0);
 }
 
 extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
@@ -1513,6 +1572,13 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
         if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (reinterpret_cast<uintptr_t>(w->tiles8) & 15u)) return QLLM_ERR_ALIGN;
         g.a_tiles8 = static_cast<const uint8_t *>(workspace);
         g.w_tiles8 = w->tiles8;
+        // K split over workgroups where few tiles would leave most CUs idle, if the workspace also holds the parts
+        const int32_t s8 = t8_splits(N, w->K, w->O);
+        const int64_t at = (qllm_tiles8_bytes(N, w->K) + 255) / 256 * 256;
+        if (s8 > 1 && workspace_bytes >= at + (int64_t)s8 * N * w->O * (int64_t)sizeof(int32_t)) {
+            g.splits = s8;
+            g.partial = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(workspace) + at);
+        }
     }
     g.small_zero = small_zero_bound(w->K, a_bits, wb);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
