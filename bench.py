@@ -208,6 +208,9 @@ def main():
     ap.add_argument("--bits", default=None,
                     help="A,W: activation and weight bits instead of the workload's own (6,6 / 8,8 / 8,4: the other "
                          "settings of Sec. 5), same shapes and inputs")
+    ap.add_argument("--norm", default=None, choices=["none", "rms", "layer"],
+                    help="the norm in front of the layer instead of the workload's own (none: a layer whose producer is not "
+                         "a norm, e.g. a down projection after the gated activation)")
     ap.add_argument("--packed", action="store_true",
                     help="6- and 8-bit activations: no one-byte-per-code copy of the weight, so that the GEMM expands "
                          "the packed codes itself")
@@ -245,6 +248,9 @@ def main():
         import dataclasses
         a_bits, w_bits = (int(v) for v in args.bits.split(","))
         w = dataclasses.replace(w, a_bits=a_bits, w_bits=w_bits)
+    if args.norm:
+        import dataclasses
+        w = dataclasses.replace(w, norm=args.norm)
     norm = {"none": b.NORM_NONE, "layer": b.NORM_LAYER, "rms": b.NORM_RMS}[w.norm]
     if args.stage == "match":
         return bench_matching(args, w, norm, dev)
