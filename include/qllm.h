@@ -160,6 +160,8 @@ int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, in
  * settings") and N > 32 the int8 matrix cores can be fed straight from one-byte-per-code copies of both operands:
  * taken when w->tiles8 is set and the workspace holds at least qllm_tiles8_bytes(N, w->K) bytes (the activations
  * are re-laid into it first); otherwise the packed codes are expanded inside the GEMM.  Same results either way.
+ * With qllm_gemm_workspace_bytes(...) bytes this path also splits the sum over K over workgroups where a small
+ * batch would leave most of the chip idle (the parts' accumulators follow the activations' bytes in the workspace).
  */
 int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, const qllm_weight *w, void *y,
                       int32_t y_dtype, int64_t ldy, int32_t *acc_dump, void *workspace,
