@@ -461,7 +461,7 @@ def main():
                        "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits))
     else:
         gemm_kernel = "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
-    traffic = read_traffic(w.name)
+    traffic = read_traffic(w.name + ("_w%da%d" % (w.w_bits, w.a_bits) if args.bits else ""))
     if w.N <= 32:
         # decode-sized batch: the GEMM streams the packed weights once and does little arithmetic per byte
         gemm_bytes = (w.O * b.qllm_packed_row_bytes(K, w.w_bits) + w.N * b.qllm_packed_row_bytes(K, w.a_bits)
@@ -490,7 +490,9 @@ def main():
     else:
         roofline = {"kernel": gemm_kernel, "bound": "mfma", "achieved": gemm_tops,
                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_PEAK_TOPS,
-                    "avg_launch_us": t_gemm * 1e6, "single_launch_event_us": spread(gemm_us), "traffic": traffic.get("int_gemm"),
+                    "avg_launch_us": t_gemm * 1e6, "single_launch_event_us": spread(gemm_us),
+                    "traffic": ((traffic.get("gemm_tiles8", 0) + traffic.get("tiles8", 0)) or None) if bytes_path
+                    else traffic.get("int_gemm"),
                     "probe": {"what": "loop of int8 matrix-core operations on register operands, all CUs",
                               "achieved": mfma_probe_tops, "frac_of_probe": gemm_tops / mfma_probe_tops}}
     result = {
