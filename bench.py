@@ -280,6 +280,15 @@ def main():
     W = wl.draw_weight(w)
     q = b.qllm_quantize_weight_host(W, cal["row_ptr"], cal["src"], w.w_bits)
     del W
+    # what was measured on: digests of the seeded inputs as the kernels get them, and the machine
+    import hashlib
+    digest = lambda *arrays: hashlib.sha256(b"".join(np.ascontiguousarray(v).tobytes() for v in arrays)).hexdigest()
+    inputs_sha256 = {"x": digest(x_host), "map": digest(cal["row_ptr"], cal["src"], cal["scale"]),
+                     "packed_weights": digest(q["codes"], q["scale"], q["zero"], q["colsum"])}
+    prop = torch.cuda.get_device_properties(0)
+    cpu_model = next((line.split(":", 1)[1].strip() for line in open("/proc/cpuinfo") if line.startswith("model name")), "unknown")
+    machine = {"gpu": prop.name, "compute_units": prop.multi_processor_count, "gpu_memory_GiB": round(prop.total_memory / 2 ** 30, 1),
+               "arch": getattr(prop, "gcnArchName", ""), "cpu": cpu_model, "host_cpus": os.cpu_count()}
     dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, w.w_bits, tiles6=not args.int8 and w.a_bits == 4,
                         tiles8=not args.packed and (w.a_bits, w.w_bits) != (4, 4))
     # 4-bit codes, more than 32 tokens, K not split over workgroups: the GEMM runs on the FP6 matrix cores
@@ -525,6 +534,8 @@ def main():
                            "probe": {"what": "plain stream, 16 bytes read : 4 written, 1.25 GB per pass",
                                      "achieved": stream_probe_gbs, "frac_of_probe": fused_gbs / stream_probe_gbs}},
         "setup_s": setup_s,
+        "inputs_sha256": inputs_sha256,
+        "machine": machine,
     }
 
     if not args.no_cpu_baseline:
