@@ -152,9 +152,9 @@ int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, in
  * matrix cores at close to twice the int8 rate: a code c, zero-extended to 6 bits, is the E2M3 number c/8, the
  * products a*w/64 and all their partial sums (multiples of 1/64 below 2^18, K <= 74564) are exact in fp32, and
  * 64 times the fp32 accumulator is the integer accumulator of Eq. (1), bit for bit.  It is taken when
- * w->tiles6 is set, qllm_gemm_workspace_floor_bytes(...) is 0 for the shape (K not split) and the workspace
- * holds at least qllm_tiles6_bytes(N, w->K) bytes (the activations are re-laid into it first, a few per cent of
- * the GEMM's time); otherwise the int8 path runs.  Same results either way.
+ * w->tiles6 is set and the workspace holds, behind the qllm_gemm_workspace_floor_bytes(...) bytes rounded up to a
+ * multiple of 256, at least qllm_tiles6_bytes(N, w->K) bytes (the activations are re-laid into them first, a few
+ * per cent of the GEMM's time); otherwise the int8 path runs.  Same results either way.
  *
  * Byte operands.  For the other bit pairs (6/6, 8/8, 8-bit activations on 4-bit weights; Sec. 5, "Quantization
  * settings") and N > 32 the int8 matrix cores can be fed straight from one-byte-per-code copies of both operands:

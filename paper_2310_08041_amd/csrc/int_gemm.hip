@@ -755,7 +755,9 @@ __device__ __forceinline__ Frag6 read6(const uint8_t *block, int lane)
     return f;
 }
 
-template <typename YT, int MI, int NJ>
+// SPLIT: K is dealt out to gridDim.z workgroups per tile of Y, as in int_gemm_w4a4_kernel; the parts' sums leave as
+// the integers they stand for.
+template <typename YT, int MI, int NJ, bool SPLIT = false>
 __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kernel(const GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -802,8 +804,11 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    fetch(0, 0);
-    fetch(1, 1);
+    // this workgroup's K-tiles (fetches past them, up to the last K-tile of the row, go to stages nobody reads)
+    const int kt_first = SPLIT ? (int)((int64_t)all_kt * blockIdx.z / gridDim.z) : 0;
+    const int kt_end = SPLIT ? (int)((int64_t)all_kt * (blockIdx.z + 1) / gridDim.z) : all_kt;
+    fetch(kt_first, 0);
+    fetch(kt_first + 1, 1);
     __builtin_amdgcn_s_waitcnt(WAIT_LANDED);
     __syncthreads();
 
@@ -860,12 +865,12 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
         fetch_stage = stage;
         stage = stage == T6_STAGES - 1 ? 0 : stage + 1;
     };
-    int kt = 0;
-    for (; kt + 1 < all_kt; kt += 2) {
+    int kt = kt_first;
+    for (; kt + 1 < kt_end; kt += 2) {
         k_tile(std::integral_constant<int, 0>{}, kt);
         k_tile(std::integral_constant<int, 1>{}, kt + 1);
     }
-    if (kt < all_kt) k_tile(std::integral_constant<int, 0>{}, kt);
+    if (kt < kt_end) k_tile(std::integral_constant<int, 0>{}, kt);
     // the loads past the last K-tile went to stages nobody reads; they must not outlive the workgroup
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
     // the last groups of the last K-tile
@@ -878,10 +883,33 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(operand6(wr[P][j]), operand6(ar[i]), acc[i][j], 2, 2,
                                                                              0, 0, 0, 0);
     };
-    if (all_kt & 1) last_groups(std::integral_constant<int, 0>{});
+    if ((kt_end - kt_first) & 1) last_groups(std::integral_constant<int, 0>{});
     else last_groups(std::integral_constant<int, 1>{});
 
-    finish_wave_tile<4, 4, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane); // 64 acc: the integer accumulators, exactly
+    if constexpr (SPLIT) {
+        // this part's sums as integers (64 acc, exactly): token n, four consecutive features per lane and tile
+        int32_t *part = g.partial + (int64_t)blockIdx.z * g.N * g.O;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int n = n0 + wm * 16 * MI + i * 16 + (lane & 15);
+            if (n >= g.N) continue;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int o = o0 + wn * 16 * NJ + j * 16 + 4 * (lane >> 4);
+                int32_t *p = part + (int64_t)n * g.O + o;
+                const v4i v{acc_int(acc[i][j], 0), acc_int(acc[i][j], 1), acc_int(acc[i][j], 2), acc_int(acc[i][j], 3)};
+                if (o + 3 < g.O && (g.O & 3) == 0) {
+                    *reinterpret_cast<v4i *>(p) = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (o + e < g.O) p[e] = v[e];
+                }
+            }
+        }
+    } else {
+        finish_wave_tile<4, 4, YT, MI, NJ>(g, acc, n0 + wm * 16 * MI, o0 + wn * 16 * NJ, lane); // 64 acc: the integer accumulators, exactly
+    }
 }
 
 // 4 nibbles in bits 0..15 -> four 6-bit fields in bits 0..23
@@ -1328,9 +1356,16 @@ int32_t launch_fp6(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
     const int64_t small_tiles = (int64_t)((g.O + 127) / 128) * ((g.N + 127) / 128);
     const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
     const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
-    if (g.N <= 128 || big_fill < 0.78 * small_fill) {
-        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128));
+    if (g.splits > 1 || g.N <= 128 || big_fill < 0.78 * small_fill) { // K is only split where the small tile is the choice
+        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128), (unsigned)(g.splits > 1 ? g.splits : 1));
         constexpr size_t lds = (size_t)T6_STAGES * 16 * T6_BLOCK;
+        if (g.splits > 1) {
+            const int32_t sp = launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2, true>, grid, dim3(LTHREADS), lds, g, stream);
+            if (sp != QLLM_OK) return sp;
+            const dim3 fgrid((unsigned)(((int64_t)g.N * g.O + 255) / 256));
+            if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float>, fgrid, dim3(256), 0, g, stream);
+            return launch_kernel(splitk_finish_kernel<uint16_t>, fgrid, dim3(256), 0, g, stream);
+        }
         if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
         return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
     }
@@ -1514,9 +1549,10 @@ extern "C" int64_t qllm_gemm_workspace_floor_bytes(int64_t N, int64_t K, int64_t
 extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, int32_t a_bits)
 {
     const int64_t floor_bytes = qllm_gemm_workspace_floor_bytes(N, K, O, a_bits);
-    if (floor_bytes != 0) return floor_bytes; // an error, or K is split (then the FP6 path is not taken)
-    if (N <= 32) return 0;
-    if (a_bits == 4) return 225 * K < (1 << 24) ? qllm_tiles6_bytes(N, K) : 0;
+    if (floor_bytes < 0) return floor_bytes;
+    if (N <= 32) return floor_bytes;
+    // 4-bit codes: the parts' accumulators where K is split (the floor), then the activations' tiles for the FP6 path
+    if (a_bits == 4) return 225 * K < (1 << 24) ? (floor_bytes + 255) / 256 * 256 + qllm_tiles6_bytes(N, K) : floor_bytes;
     // the byte-operand path: the activations' bytes, then the parts' accumulators where it splits K
     const int32_t s8 = t8_splits(N, K, O);
     return (qllm_tiles8_bytes(N, K) + 255) / 256 * 256 + (s8 > 1 ? (int64_t)s8 * N * O * (int64_t)sizeof(int32_t) : 0);
@@ -1558,11 +1594,13 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     if (g.splits > 1 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u))) return workspace ? QLLM_ERR_ALIGN : QLLM_ERR_WORKSPACE;
     // the FP6 matrix-core path: 4-bit codes, more than 32 tokens, K not split, the weight's tiles at hand and room
     // for the activations' in the workspace
-    if (a_bits == 4 && wb == 4 && w->tiles6 && N > 32 && g.splits == 1 && workspace && 225 * w->K < (1 << 24) &&
-        workspace_bytes >= qllm_tiles6_bytes(N, w->K) && qllm_tiles6_bytes(N, w->K) < (1ll << 32) &&
+    // (where K is split, the parts' accumulators come first in the workspace and the tiles behind them)
+    const int64_t tiles_at = g.splits > 1 ? ((int64_t)g.splits * N * w->O * (int64_t)sizeof(int32_t) + 255) / 256 * 256 : 0;
+    if (a_bits == 4 && wb == 4 && w->tiles6 && N > 32 && workspace && 225 * w->K < (1 << 24) &&
+        workspace_bytes >= tiles_at + qllm_tiles6_bytes(N, w->K) && qllm_tiles6_bytes(N, w->K) < (1ll << 32) &&
         qllm_tiles6_bytes(w->O, w->K) < (1ll << 32)) { // the kernel addresses either operand with 32-bit offsets
         if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (reinterpret_cast<uintptr_t>(w->tiles6) & 15u)) return QLLM_ERR_ALIGN;
-        g.a_tiles = static_cast<const uint8_t *>(workspace);
+        g.a_tiles = static_cast<const uint8_t *>(workspace) + tiles_at;
         g.w_tiles = w->tiles6;
     }
     // the byte-operand path of the other bit pairs: more than 32 tokens, the weight's tiles at hand and room for the

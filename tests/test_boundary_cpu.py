@@ -57,9 +57,9 @@ def test_packed_row_bytes_and_workspace():
     assert floor(128, 8192, 8192, 4) == 4 * 128 * 8192 * 4
     assert floor(128, 8192, 8192, 6) == 0 and floor(128, 512, 8192, 4) == 0
     assert b.qllm_workspace_bytes(128, 8192, 8192, 4) >= 128 * 4096 + 4 * 128 * 8192 * 4
-    # what serves every path: the same where K is split; else, for 4-bit codes and more than 32 tokens, room for the
-    # activations in the FP6 path's layout (1536 bytes per 16 rows and 128 codes of the padded row)
-    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 4) == floor(128, 8192, 8192, 4)
+    # what serves every path: for 4-bit codes and more than 32 tokens the parts' accumulators where K is split, then
+    # room for the activations in the FP6 path's layout (1536 bytes per 16 rows and 128 codes of the padded row)
+    assert b.qllm_gemm_workspace_bytes(128, 8192, 8192, 4) == floor(128, 8192, 8192, 4) + b.qllm_tiles6_bytes(128, 8192)
     assert b.qllm_tiles6_bytes(2048, 28672) == 2048 // 16 * (28672 // 128) * 1536
     assert b.qllm_tiles6_bytes(17, 100) == 2 * 2 * 1536                     # rows up to 32, K up to 256
     assert b.qllm_gemm_workspace_bytes(2048, 28672, 8192, 4) == b.qllm_tiles6_bytes(2048, 28672)
