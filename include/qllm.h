@@ -148,7 +148,7 @@ int32_t qllm_norm_reassemble_quant(const void *x, int32_t x_dtype, int64_t N, in
  *               are required (may be NULL when that is 0: it is non-zero only where the sum over K is
  *               split over workgroups), else QLLM_ERR_WORKSPACE.
  *
- * The FP6 path.  For 4-bit codes on both sides and N > 32 the same acc[n,o] is also available from the FP6
+ * The FP6 path.  For 4-bit codes on both sides and N > 64 the same acc[n,o] is also available from the FP6
  * matrix cores at close to twice the int8 rate: a code c, zero-extended to 6 bits, is the E2M3 number c/8, the
  * products a*w/64 and all their partial sums (multiples of 1/64 below 2^18, K <= 74564) are exact in fp32, and
  * 64 times the fp32 accumulator is the integer accumulator of Eq. (1), bit for bit.  It is taken when

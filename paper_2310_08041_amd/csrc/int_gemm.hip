@@ -1293,7 +1293,7 @@ __global__ __launch_bounds__(SK_THREADS) void int_gemm_skinny_kernel(const GemmA
 template <int ABITS, int WBITS>
 constexpr size_t skinny_lds(int nt)
 {
-    const size_t strips = (size_t)SK_WAVES * (nt == 1 ? SK_STRIP<ABITS, WBITS, 1> : SK_STRIP<ABITS, WBITS, 2>);
+    const size_t strips = (size_t)SK_WAVES * (nt == 1 ? SK_STRIP<ABITS, WBITS, 1> : nt == 2 ? SK_STRIP<ABITS, WBITS, 2> : SK_STRIP<ABITS, WBITS, 4>);
     const size_t red = (size_t)SK_WAVES * nt * SK_RT * 64 * sizeof(v4i);
     return strips > red ? strips : red;
 }
@@ -1444,10 +1444,20 @@ int32_t launch_t8(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
     return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
 }
 
+// Up to this many tokens the weight-streaming kernel takes 4-bit codes on both sides (four token tiles per
+// workgroup: its LDS strips hold no more, and none of the wider codes at that count).
+constexpr int SK4_TOKENS = 64;
+
 template <int ABITS, int WBITS>
 int32_t launch(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     if constexpr (ABITS == 4 && WBITS == 4) {
+        if (g.N > 32 && g.N <= SK4_TOKENS) {
+            const dim3 grid((unsigned)((g.O + 16 * SK_RT - 1) / (16 * SK_RT)));
+            const size_t lds = skinny_lds<4, 4>(4);
+            if (y_dtype == QLLM_F32) return launch_kernel(int_gemm_skinny_kernel<4, 4, float, 4>, grid, dim3(SK_THREADS), lds, g, stream);
+            return launch_kernel(int_gemm_skinny_kernel<4, 4, uint16_t, 4>, grid, dim3(SK_THREADS), lds, g, stream);
+        }
         if (g.a_tiles && g.w_tiles) return launch_fp6(g, y_dtype, stream);
         // 4-bit codes on both sides, more than 32 tokens.  256 x 256 tiles run one workgroup per CU, 128 x 128
         // tiles two, at about three quarters of the large tile's rate per matrix-core operation: the
@@ -1526,7 +1536,7 @@ int32_t small_zero_bound(int64_t K, int32_t a_bits, int32_t w_bits)
 // eight K-tiles.
 int32_t k_splits(int64_t N, int64_t K, int64_t O, int32_t a_bits)
 {
-    if (a_bits != 4 || N <= 32) return 1;
+    if (a_bits != 4 || N <= 64) return 1; // up to 64 tokens the weight-streaming kernel runs (SK4_TOKENS)
     const int64_t tiles = ((O + 127) / 128) * ((N + 127) / 128);
     const int64_t n_kt = (K + QLLM_K_PAD - 1) / QLLM_K_PAD * QLLM_K_PAD / PKT;
     if (tiles > 128) return 1;
@@ -1550,7 +1560,7 @@ extern "C" int64_t qllm_gemm_workspace_bytes(int64_t N, int64_t K, int64_t O, in
 {
     const int64_t floor_bytes = qllm_gemm_workspace_floor_bytes(N, K, O, a_bits);
     if (floor_bytes < 0) return floor_bytes;
-    if (N <= 32) return floor_bytes;
+    if (N <= 32 || (a_bits == 4 && N <= 64)) return floor_bytes; // the weight-streaming kernel needs none
     // 4-bit codes: the parts' accumulators where K is split (the floor), then the activations' tiles for the FP6 path
     if (a_bits == 4) return 225 * K < (1 << 24) ? (floor_bytes + 255) / 256 * 256 + qllm_tiles6_bytes(N, K) : floor_bytes;
     // the byte-operand path: the activations' bytes, then the parts' accumulators where it splits K
@@ -1596,7 +1606,7 @@ extern "C" int32_t qllm_int_gemm(const qllm_qact *a, int32_t a_bits, int64_t N, 
     // for the activations' in the workspace
     // (where K is split, the parts' accumulators come first in the workspace and the tiles behind them)
     const int64_t tiles_at = g.splits > 1 ? ((int64_t)g.splits * N * w->O * (int64_t)sizeof(int32_t) + 255) / 256 * 256 : 0;
-    if (a_bits == 4 && wb == 4 && w->tiles6 && N > 32 && workspace && 225 * w->K < (1 << 24) &&
+    if (a_bits == 4 && wb == 4 && w->tiles6 && N > 64 && workspace && 225 * w->K < (1 << 24) &&
         workspace_bytes >= tiles_at + qllm_tiles6_bytes(N, w->K) && qllm_tiles6_bytes(N, w->K) < (1ll << 32) &&
         qllm_tiles6_bytes(w->O, w->K) < (1ll << 32)) { // the kernel addresses either operand with 32-bit offsets
         if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (reinterpret_cast<uintptr_t>(w->tiles6) & 15u)) return QLLM_ERR_ALIGN;

@@ -139,12 +139,12 @@ def test_gemm_entry_point_rejects_bad_arguments_before_launching():
     assert call(wt=b._Weight(32, 64, 4, 0x1004, 0x1000, 0x1000, 0x1000)) == -6
     assert call(qa=b._QAct(0x1000, 0x1000, None, 0x1000)) == -1
     assert call(N=0) == 0
-    # a weight that comes with tiles for the FP6 path, more than 32 tokens, room in the workspace: the tiles' and the
+    # a weight that comes with tiles for the FP6 path, more than 64 tokens, room in the workspace: the tiles' and the
     # workspace's alignment are checked before anything is launched
     big = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000, 0x5008)
-    assert f(C.byref(q), 4, 64, C.byref(big), Y, b.F32, 32, None, 0x4000, 1 << 20, None) == -6
+    assert f(C.byref(q), 4, 128, C.byref(big), Y, b.F32, 32, None, 0x4000, 1 << 20, None) == -6
     good = b._Weight(32, 64, 4, 0x1000, 0x1000, 0x1000, 0x1000, 0x5000)
-    assert f(C.byref(q), 4, 64, C.byref(good), Y, b.F32, 32, None, 0x4008, 1 << 20, None) == -6
+    assert f(C.byref(q), 4, 128, C.byref(good), Y, b.F32, 32, None, 0x4008, 1 << 20, None) == -6
 
 
 def test_tiles6_entry_points_reject_bad_arguments_before_launching():
