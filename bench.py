@@ -291,8 +291,9 @@ def main():
                "arch": getattr(prop, "gcnArchName", ""), "cpu": cpu_model, "host_cpus": os.cpu_count()}
     dw = b.DeviceWeight(q["codes"], q["scale"], q["zero"], q["colsum"], K, w.w_bits, tiles6=not args.int8 and w.a_bits == 4,
                         tiles8=not args.packed and (w.a_bits, w.w_bits) != (4, 4))
-    # 4-bit codes, more than 32 tokens, K not split over workgroups: the GEMM runs on the FP6 matrix cores
-    fp6_path = dw.tiles6 is not None and w.a_bits == 4 and w.N > 32 and b.qllm_gemm_workspace_floor_bytes(w.N, K, w.O, w.a_bits) == 0
+    # 4-bit codes, more than 64 tokens: the GEMM runs on the FP6 matrix cores
+    streams_weights = w.N <= 32 or ((w.a_bits, w.w_bits) == (4, 4) and w.N <= 64)   # the decode kernel: weights read once
+    fp6_path = dw.tiles6 is not None and w.a_bits == 4 and not streams_weights
     xs = [x0] + [x0.roll(i, dims=0).contiguous() for i in range(1, N_ROTATE)]   # same rows, other addresses
     ys = [torch.empty((w.N, w.O), dtype=torch.bfloat16, device=dev) for _ in range(N_ROTATE)]
     ws = torch.empty(b.qllm_workspace_bytes(w.N, K, w.O, w.a_bits), dtype=torch.uint8, device=dev)
@@ -460,7 +461,7 @@ def main():
     stream_probe_gbs = 10 * (sbytes + sbytes // 4) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
     del ssrc, sdst
 
-    bytes_path = dw.tiles8 is not None and w.N > 32
+    bytes_path = dw.tiles8 is not None and not streams_weights
     if fp6_path:
         gemm_kernel = "gemm_w4a4_fp6_kernel<bf16>"
     elif bytes_path:
@@ -469,9 +470,9 @@ def main():
         gemm_kernel = ("int_gemm_w4a4_kernel<bf16>" if (w.a_bits, w.w_bits) == (4, 4) else
                        "int_gemm_big_kernel<%d,%d,bf16>" % (w.a_bits, w.w_bits))
     else:
-        gemm_kernel = "int_gemm_skinny_kernel" if w.N <= 32 else "int_gemm_kernel"
+        gemm_kernel = "int_gemm_skinny_kernel" if streams_weights else "int_gemm_kernel"
     traffic = read_traffic(w.name + ("_w%da%d" % (w.w_bits, w.a_bits) if args.bits else ""))
-    if w.N <= 32:
+    if streams_weights:
         # decode-sized batch: the GEMM streams the packed weights once and does little arithmetic per byte
         gemm_bytes = (w.O * b.qllm_packed_row_bytes(K, w.w_bits) + w.N * b.qllm_packed_row_bytes(K, w.a_bits)
                       + w.N * w.O * 2 + 12 * (w.N + w.O))
