@@ -47,6 +47,9 @@ struct GemmArgs {
     int32_t splits;
     const uint8_t *a_tiles, *w_tiles; // both operands as 6-bit fields in matrix-core order (see TILES6 below), or null
     const uint8_t *a_tiles8, *w_tiles8; // both operands as bytes in matrix-core order (see TILES8 below), or null
+    // A launch of the FP6 or the byte-operand kernel may cover the output features o_first .. O - 1 only (the call is
+    // then two launches with different tiles, each with its own O); never together with acc_dump, whose rows are O long.
+    int32_t o_first;
 };
 
 template <int BITS>
@@ -766,7 +769,7 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_w4a4_fp6_kerne
     static_assert(STAGE % (8 * 1024) == 0, "a stage is a whole number of 1 KB loads per wave");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
-    const int n0 = blockIdx.y * TM, o0 = blockIdx.x * TN;
+    const int n0 = blockIdx.y * TM, o0 = g.o_first + blockIdx.x * TN;
     const int all_kt = g.Kpad / T6_KT;
     const int a_blocks = (g.N + 15) / 16, w_blocks = (g.O + 15) / 16;
 
@@ -969,7 +972,7 @@ __global__ __launch_bounds__(LTHREADS, MI == 8 ? 1 : 2) void gemm_tiles8_kernel(
     static_assert(STAGE % (8 * 1024) == 0 && NLOAD <= MI, "a stage is a whole number of 1 KB loads per wave, one per group");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
-    const int n0 = blockIdx.y * TM, o0 = blockIdx.x * TN;
+    const int n0 = blockIdx.y * TM, o0 = g.o_first + blockIdx.x * TN;
     const int all_kt = (g.K + T8_KT - 1) / T8_KT;
     const int a_blocks = (g.N + 15) / 16, w_blocks = (g.O + 15) / 16;
 
@@ -1331,6 +1334,32 @@ int32_t launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const GemmArg
     return QLLM_OK;
 }
 
+// How a product with 256 x 256 or 128 x 128 tiles is laid over the chip.  A round of 256 large tiles (one per CU)
+// takes one unit of time, a round of 512 small ones (two per CU; half the outputs at about three quarters of the
+// rate) 0.65.  Large tiles throughout, small tiles throughout, or -- when the large tiles fill whole rounds and
+// leave a rest -- large tiles for the output features of the whole rounds and small tiles for the others, as two
+// launches (7B q/k/v: 384 large tiles are two rounds, 1536 small ones three; 256 large + 512 small are 1.65).
+struct TilePlan {
+    bool small;      // 128 x 128 tiles for everything (or for everything from o_split on)
+    int32_t o_split; // > 0: large tiles for features below o_split, small tiles from there on
+};
+TilePlan plan_tiles(int64_t N, int64_t O, bool may_split_launch)
+{
+    const int64_t nb = (N + LBM - 1) / LBM, ob = (O + LBN - 1) / LBN, big_tiles = nb * ob;
+    const int64_t small_tiles = ((O + 127) / 128) * ((N + 127) / 128);
+    const double cost_big = (double)((big_tiles + 255) / 256), cost_small = 0.65 * (double)((small_tiles + 511) / 512);
+    if (N <= 128) return TilePlan{true, 0};
+    TilePlan best{cost_small < cost_big, 0};
+    double best_cost = cost_small < cost_big ? cost_small : cost_big;
+    const int64_t whole = big_tiles / 256, ca = whole * 256 / nb; // feature blocks that whole rounds of large tiles cover
+    if (may_split_launch && whole >= 1 && ca > 0 && ca < ob) {
+        const int64_t rest_small = ((O - ca * LBN + 127) / 128) * ((N + 127) / 128);
+        const double cost = (double)((ca * nb + 255) / 256) + 0.65 * (double)((rest_small + 511) / 512);
+        if (cost < best_cost - 0.05) best = TilePlan{false, (int32_t)(ca * LBN)};
+    }
+    return best;
+}
+
 // Packed 4-bit rows (device) -> TILES6 (device).
 int32_t launch_tiles6(const uint8_t *codes, int64_t row_bytes, int64_t rows, int64_t Kpad, uint8_t *tiles, hipStream_t stream)
 {
@@ -1352,27 +1381,35 @@ int32_t launch_fp6(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     const int32_t st = launch_tiles6(g.a_codes, g.a_row_bytes, g.N, g.Kpad, const_cast<uint8_t *>(g.a_tiles), stream);
     if (st != QLLM_OK) return st;
-    const int64_t big_tiles = (int64_t)((g.O + LBN - 1) / LBN) * ((g.N + LBM - 1) / LBM);
-    const int64_t small_tiles = (int64_t)((g.O + 127) / 128) * ((g.N + 127) / 128);
-    const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
-    const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
-    if (g.splits > 1 || g.N <= 128 || big_fill < 0.78 * small_fill) { // K is only split where the small tile is the choice
-        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128), (unsigned)(g.splits > 1 ? g.splits : 1));
+    const TilePlan plan = plan_tiles(g.N, g.O, g.splits == 1 && !g.acc_dump);
+    auto launch_small = [&](const GemmArgs &ga) -> int32_t {
+        const dim3 grid((unsigned)((ga.O - ga.o_first + 127) / 128), (unsigned)((ga.N + 127) / 128), (unsigned)(ga.splits > 1 ? ga.splits : 1));
         constexpr size_t lds = (size_t)T6_STAGES * 16 * T6_BLOCK;
-        if (g.splits > 1) {
-            const int32_t sp = launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2, true>, grid, dim3(LTHREADS), lds, g, stream);
+        if (ga.splits > 1) {
+            const int32_t sp = launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2, true>, grid, dim3(LTHREADS), lds, ga, stream);
             if (sp != QLLM_OK) return sp;
-            const dim3 fgrid((unsigned)(((int64_t)g.N * g.O + 255) / 256));
-            if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float>, fgrid, dim3(256), 0, g, stream);
-            return launch_kernel(splitk_finish_kernel<uint16_t>, fgrid, dim3(256), 0, g, stream);
+            const dim3 fgrid((unsigned)(((int64_t)ga.N * ga.O + 255) / 256));
+            if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float>, fgrid, dim3(256), 0, ga, stream);
+            return launch_kernel(splitk_finish_kernel<uint16_t>, fgrid, dim3(256), 0, ga, stream);
         }
-        if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
-        return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+        if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 4, 2>, grid, dim3(LTHREADS), lds, ga, stream);
+        return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, ga, stream);
+    };
+    auto launch_big = [&](const GemmArgs &ga) -> int32_t {
+        const dim3 grid((unsigned)((ga.O - ga.o_first + LBN - 1) / LBN), (unsigned)((ga.N + LBM - 1) / LBM));
+        constexpr size_t lds = (size_t)T6_STAGES * 32 * T6_BLOCK;
+        if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 8, 4>, grid, dim3(LTHREADS), lds, ga, stream);
+        return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, ga, stream);
+    };
+    if (g.splits > 1) return launch_small(g); // K is only split where the small tile is the choice
+    if (plan.o_split > 0) { // whole rounds of large tiles, then the other output features with small ones
+        GemmArgs first = g, rest = g;
+        first.O = plan.o_split;
+        rest.o_first = plan.o_split;
+        const int32_t rc = launch_big(first);
+        return rc != QLLM_OK ? rc : launch_small(rest);
     }
-    const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
-    constexpr size_t lds = (size_t)T6_STAGES * 32 * T6_BLOCK;
-    if (y_dtype == QLLM_F32) return launch_kernel(gemm_w4a4_fp6_kernel<float, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
-    return launch_kernel(gemm_w4a4_fp6_kernel<uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
+    return plan.small ? launch_small(g) : launch_big(g);
 }
 
 // Packed rows (device) -> TILES8 (device).
@@ -1393,16 +1430,9 @@ int32_t launch_tiles8(const uint8_t *codes, int32_t bits, int64_t rows, int64_t 
     return QLLM_OK;
 }
 
-// The byte-operand path's tile: 128 x 128 (two workgroups per CU) where that fills the chip's rounds better than
-// 256 x 256, as on the FP6 path, and for up to 128 tokens.
-bool t8_small_tile(int64_t N, int64_t O)
-{
-    const int64_t big_tiles = ((O + LBN - 1) / LBN) * ((N + LBM - 1) / LBM);
-    const int64_t small_tiles = ((O + 127) / 128) * ((N + 127) / 128);
-    const double big_fill = (double)big_tiles / (double)(256 * ((big_tiles + 255) / 256));
-    const double small_fill = (double)small_tiles / (double)(512 * ((small_tiles + 511) / 512));
-    return N <= 128 || big_fill < 0.78 * small_fill;
-}
+// The byte-operand path's tile where K may be split: 128 x 128 (two workgroups per CU) where that is the plan
+// for the whole product, as on the FP6 path, and for up to 128 tokens.
+bool t8_small_tile(int64_t N, int64_t O) { return plan_tiles(N, O, false).small; }
 
 // Into how many parts the byte-operand path splits K when it has room for the parts' accumulators: as on the
 // 4-bit path, only where 128 x 128 tiles leave most CUs without a workgroup, every part at least eight K-tiles.
@@ -1418,30 +1448,42 @@ int32_t t8_splits(int64_t N, int64_t K, int64_t O)
 }
 
 // 6- or 8-bit activations, more than 32 tokens, byte operands straight into the int8 matrix cores: the
-// activations are re-laid into the workspace, then the product.
+// activations are re-laid into the workspace, then the product, laid over the chip as on the FP6 path.
 template <int ABITS, int WBITS>
 int32_t launch_t8(const GemmArgs &g, int32_t y_dtype, hipStream_t stream)
 {
     const int32_t st = launch_tiles8(g.a_codes, ABITS, g.N, g.K, const_cast<uint8_t *>(g.a_tiles8), stream);
     if (st != QLLM_OK) return st;
-    if (t8_small_tile(g.N, g.O)) {
-        const dim3 grid((unsigned)((g.O + 127) / 128), (unsigned)((g.N + 127) / 128), (unsigned)(g.splits > 1 ? g.splits : 1));
+    const TilePlan plan = plan_tiles(g.N, g.O, g.splits == 1 && !g.acc_dump);
+    auto launch_small = [&](const GemmArgs &ga) -> int32_t {
+        const dim3 grid((unsigned)((ga.O - ga.o_first + 127) / 128), (unsigned)((ga.N + 127) / 128), (unsigned)(ga.splits > 1 ? ga.splits : 1));
         constexpr size_t lds = (size_t)T8_STAGES * 16 * T8_BLOCK;
-        if (g.splits > 1) {
-            const int32_t sp = launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2, true>, grid, dim3(LTHREADS), lds, g, stream);
+        if (ga.splits > 1) {
+            const int32_t sp = launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2, true>, grid, dim3(LTHREADS), lds, ga, stream);
             if (sp != QLLM_OK) return sp;
             constexpr int SA = ABITS == 8 ? 1 : 0, SW = WBITS == 8 ? 1 : 0;
-            const dim3 fgrid((unsigned)(((int64_t)g.N * g.O + 255) / 256));
-            if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float, SA, SW>, fgrid, dim3(256), 0, g, stream);
-            return launch_kernel(splitk_finish_kernel<uint16_t, SA, SW>, fgrid, dim3(256), 0, g, stream);
+            const dim3 fgrid((unsigned)(((int64_t)ga.N * ga.O + 255) / 256));
+            if (y_dtype == QLLM_F32) return launch_kernel(splitk_finish_kernel<float, SA, SW>, fgrid, dim3(256), 0, ga, stream);
+            return launch_kernel(splitk_finish_kernel<uint16_t, SA, SW>, fgrid, dim3(256), 0, ga, stream);
         }
-        if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
-        return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, g, stream);
+        if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 4, 2>, grid, dim3(LTHREADS), lds, ga, stream);
+        return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 4, 2>, grid, dim3(LTHREADS), lds, ga, stream);
+    };
+    auto launch_big = [&](const GemmArgs &ga) -> int32_t {
+        const dim3 grid((unsigned)((ga.O - ga.o_first + LBN - 1) / LBN), (unsigned)((ga.N + LBM - 1) / LBM));
+        constexpr size_t lds = (size_t)T8_STAGES * 32 * T8_BLOCK;
+        if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 8, 4>, grid, dim3(LTHREADS), lds, ga, stream);
+        return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, ga, stream);
+    };
+    if (g.splits > 1) return launch_small(g); // K is only split where the small tile is the choice
+    if (plan.o_split > 0) { // whole rounds of large tiles, then the other output features with small ones
+        GemmArgs first = g, rest = g;
+        first.O = plan.o_split;
+        rest.o_first = plan.o_split;
+        const int32_t rc = launch_big(first);
+        return rc != QLLM_OK ? rc : launch_small(rest);
     }
-    const dim3 grid((unsigned)((g.O + LBN - 1) / LBN), (unsigned)((g.N + LBM - 1) / LBM));
-    constexpr size_t lds = (size_t)T8_STAGES * 32 * T8_BLOCK;
-    if (y_dtype == QLLM_F32) return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, float, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
-    return launch_kernel(gemm_tiles8_kernel<ABITS, WBITS, uint16_t, 8, 4>, grid, dim3(LTHREADS), lds, g, stream);
+    return plan.small ? launch_small(g) : launch_big(g);
 }
 
 // Up to this many tokens the weight-streaming kernel takes 4-bit codes on both sides (four token tiles per
