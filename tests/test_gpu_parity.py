@@ -430,6 +430,37 @@ def test_gemm_large_tiles_ragged(oracle, b, y_dtype):
         check_y(oracle, y, ref_y, y_dtype)
 
 
+@pytest.mark.parametrize("a_bits,w_bits", [(4, 4), (6, 6), (8, 4)])
+def test_gemm_two_launch_tile_plan(oracle, b, a_bits, w_bits):
+    """A shape whose 256 x 256 tiles fill one whole round of the chip and leave a rest that 128 x 128 tiles finish in one
+    round of theirs: the call is then two launches, large tiles for the first 8192 output features and small ones for
+    the others (taken only without acc_dump).  Ragged in both directions (the last token tile and the last feature tile
+    of either size are partial).  Y against the oracle on sampled rows and columns and, with unit scales and zero
+    zero-points, exactly equal to the integer product from numpy on every element; and equal, bit for bit, to the
+    call with acc_dump, which is one launch."""
+    N, K, O = 2040, 256, 12200
+    rng = np.random.default_rng(a_bits * 100 + w_bits)
+    a, w, ax, aw, bx, bw = random_gemm_case(rng, N, K, O, a_bits, w_bits)
+    cols = np.sort(rng.choice(O, 64, replace=False))
+    cols[-3:] = [O - 3, O - 2, O - 1]
+    rows = np.sort(rng.choice(N, 32, replace=False))
+    rows[-2:] = [N - 2, N - 1]
+    rs, cs = a.astype(np.int64).sum(1), w.astype(np.int64).sum(1)
+    y, _ = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, "f32", dump=False)
+    y = y.cpu().numpy()
+    ref_cols = oracle.epilogue(oracle.int_gemm(a, w[cols]), K, ax, bx, rs, aw[cols], bw[cols], cs[cols])
+    ref_rows = oracle.epilogue(oracle.int_gemm(a[rows], w), K, ax[rows], bx[rows], rs[rows], aw, bw, cs)
+    assert rel_err(y[:, cols], ref_cols).max() <= TOL["f32"] and rel_err(y[rows], ref_rows).max() <= TOL["f32"]
+    y1, acc = run_gemm(b, a, w, ax, aw, bx, bw, a_bits, w_bits, "f32", dump=True)
+    assert np.array_equal(y1.cpu().numpy(), y)
+    one, zero = np.ones(N, np.float32), np.zeros(N, np.int32)
+    yb, _ = run_gemm(b, a, w, one, np.ones(O, np.float32), zero, np.zeros(O, np.int32), a_bits, w_bits, "bf16", dump=False)
+    exact = (a.astype(np.float64) @ w.astype(np.float64).T)                 # integers below 2^53: exact
+    assert np.array_equal(acc.cpu().numpy(), exact.astype(np.int64))
+    got = oracle.widen_bf16(yb.view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+    assert np.array_equal(got, oracle.widen_bf16(oracle.round_to_bf16(exact.astype(np.float32))))
+
+
 def test_gemm_extreme_codes(oracle, b):
     """All codes at their maximum: the largest accumulators the shapes allow."""
     for bits, K in [(4, 28672), (6, 8192), (8, 28672)]:
